@@ -1,0 +1,402 @@
+"""Pins of the CPU oracle against things other than itself (no GPU needed).
+
+Each test names what fixes the expected value: IEEE/numpy float semantics, a
+library routine, a closed form, a hand-worked value in tests/golden/, brute
+force on tiny inputs, or the independent pure-Python statement of the format.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy import stats
+
+from oracle import oracle as O
+from oracle import py_rans as P
+from paper_2410_20650_amd import inputs
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+ALL = np.arange(65536, dtype=np.uint16)
+
+
+def as_float(words):
+    """bf16 words -> the real numbers they denote, via numpy's fp32 (bf16 is its upper half)."""
+    with np.errstate(invalid="ignore"):                         # signalling NaNs are fine here
+        return (words.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+# ---------------------------------------------------------------- split / merge (Alg. 1, App. D)
+
+def test_split_agrees_with_ieee_meaning_of_every_pattern():
+    s, e, m = O.split(ALL)
+    v = as_float(ALL)
+    finite = np.isfinite(v)
+    normal = finite & (np.abs(v) >= 2.0 ** -126)
+    # sign: numpy's signbit of the value
+    assert np.array_equal(s.astype(bool), np.signbit(v))
+    # normal numbers: |v| = 2^(E-127) * (1 + mant/128)
+    frac, ex = np.frexp(np.abs(v[normal]))            # |v| = frac * 2^ex, frac in [0.5, 1)
+    assert np.array_equal(e[normal], (ex - 1 + 127).astype(np.uint8))
+    assert np.array_equal(m[normal], ((frac * 2 - 1) * 128).astype(np.uint8))
+    # zeros and subnormals: exponent field 0, |v| = 2^-126 * mant/128
+    sub = finite & ~normal
+    assert np.all(e[sub] == 0)
+    assert np.array_equal(m[sub], (np.abs(v[sub]) * 2.0 ** 126 * 128).astype(np.uint8))
+    # Inf / NaN: exponent field all ones; Inf has mantissa 0
+    assert np.all(e[~finite] == 255)
+    assert np.array_equal(m[~finite] == 0, np.isinf(v[~finite]))
+
+
+def test_merge_inverts_split_on_every_pattern():
+    assert np.array_equal(O.merge(*O.split(ALL)), ALL)
+
+
+# ---------------------------------------------------------------- truncation (Sec. 2.3)
+
+@pytest.mark.parametrize("k", [7, 3, 1, 0])
+def test_truncate_is_round_toward_zero_to_k_mantissa_bits(k):
+    t = O.truncate(ALL, k)
+    v, vt = as_float(ALL), as_float(t)
+    normal = np.isfinite(v) & (np.abs(v) >= 2.0 ** -126)
+    # independent definition on the reals: largest multiple of 2^(E-127-k) not above |v|
+    _, ex = np.frexp(np.abs(v[normal]))
+    ulp = np.ldexp(1.0, ex - 1 - k)
+    expect = np.copysign(np.floor(np.abs(v[normal]) / ulp) * ulp, v[normal])
+    assert np.array_equal(vt[normal], expect)
+    # the paper's bound: relative change below 2^-k, sign and binade kept
+    rel = np.abs(v[normal] - vt[normal]) / np.abs(v[normal])
+    assert rel.max() < 2.0 ** -k
+    assert np.array_equal(np.signbit(vt), np.signbit(v))
+    assert np.array_equal(np.frexp(np.abs(vt[normal]))[1], ex)
+    assert np.array_equal(O.truncate(t, k), t)                 # idempotent
+    if k == 7:
+        assert np.array_equal(t, ALL)
+
+
+# ---------------------------------------------------------------- signed-mantissa packing (Sec. 2.3, App. D)
+
+@pytest.mark.parametrize("k", [7, 3, 1, 0])
+@pytest.mark.parametrize("n", [0, 1, 5, 8, 13, 65536])
+def test_pack_signmant_layout(k, n):
+    w = ALL[:n] if n <= 65536 else ALL
+    if n and n < 65536:
+        w = np.random.default_rng(n + k).integers(0, 65536, n).astype(np.uint16)
+    packed = O.pack_signmant(w, k)
+    assert packed.size == math.ceil(n * (k + 1) / 8)
+    # unpack with numpy's bit unpacker: field i occupies bits [i*(k+1), (i+1)*(k+1)) LSB first
+    bits = np.unpackbits(packed, bitorder="little")
+    assert np.all(bits[n * (k + 1):] == 0)                      # padding is zero
+    fields = bits[: n * (k + 1)].reshape(n, k + 1)
+    v = as_float(w)
+    assert np.array_equal(fields[:, k].astype(bool), np.signbit(v))   # sign is the top bit
+    kept = (fields[:, :k] << np.arange(k)).sum(axis=1) if k else np.zeros(n, int)
+    _, _, mant = O.split(w)
+    assert np.array_equal(kept, mant >> (7 - k))
+    assert packed.tobytes() == P.pack_signmant([int(u) for u in w], k)
+
+
+# ---------------------------------------------------------------- statistics (Sec. 2.2, Eq. 1)
+
+def test_histogram_matches_bincount_of_float_exponents():
+    w = inputs.bits(inputs.gaussian_bf16(200_000, seed=11))
+    v = as_float(w)
+    _, ex = np.frexp(np.abs(v))                                 # all values are normal here
+    assert np.all(np.abs(v[v != 0]) >= 2.0 ** -126)
+    field = np.where(v == 0, 0, ex - 1 + 127)
+    assert np.array_equal(O.histogram(w), np.bincount(field, minlength=256).astype(np.uint64))
+    assert int(O.histogram(w).sum()) == w.size
+    assert O.histogram(np.zeros(0, np.uint16)).sum() == 0
+
+
+def test_entropy_closed_cases():
+    c = np.zeros(256, np.uint64)
+    assert O.entropy(c) == 0.0
+    c[17] = 5
+    assert O.entropy(c) == 0.0
+    c[200] = 5
+    assert O.entropy(c) == pytest.approx(1.0, abs=1e-12)
+    assert O.entropy(np.full(256, 3, np.uint64)) == pytest.approx(8.0, abs=1e-12)
+    c = np.zeros(256, np.uint64)
+    c[:4] = [4, 2, 1, 1]                                        # 1/2, 1/4, 1/8, 1/8 -> 1.75 bits
+    assert O.entropy(c) == pytest.approx(1.75, abs=1e-12)
+    f = np.zeros(256, np.uint16)
+    f[:4] = [2048, 1024, 512, 512]
+    assert O.cross_entropy(c, f) == pytest.approx(1.75, abs=1e-12)
+    f[:4] = [1024, 1024, 1024, 1024]
+    assert O.cross_entropy(c, f) == pytest.approx(2.0, abs=1e-12)
+
+
+def gaussian_exponent_pmf(std):
+    """P(exponent field = E) for bf16(round-to-nearest-even(N(0, std^2))), from the normal CDF.
+
+    A value rounds into binade E when 2^(E-127) * (1 - 2^-9) <= |x| < 2^(E-126) * (1 - 2^-9)
+    (half of the last bf16 step below a power of two already rounds up to it).
+    """
+    p = np.zeros(256)
+    shift = 1.0 - 2.0 ** -9
+    for E in range(1, 255):
+        lo, hi = 2.0 ** (E - 127) * shift, 2.0 ** (E - 126) * shift
+        p[E] = 2 * (stats.norm.cdf(hi / std) - stats.norm.cdf(lo / std))
+    p[0] = 1 - p.sum()
+    return p
+
+
+def test_exponent_entropy_of_gaussian_weights_matches_closed_form():
+    p = gaussian_exponent_pmf(0.02)
+    h_closed = -(p[p > 0] * np.log2(p[p > 0])).sum()
+    assert h_closed == pytest.approx(2.545, abs=2e-3)           # "less than 3 bits" (Sec. 2.1)
+    w = inputs.bits(inputs.gaussian_bf16(4_000_000, seed=12))
+    cnt = O.histogram(w)
+    assert O.entropy(cnt) == pytest.approx(h_closed, abs=5e-3)
+    emp = cnt / cnt.sum()
+    assert np.abs(emp - p).max() < 2e-3
+    # mantissa and sign carry (almost) their full width, as Fig. 1 reports
+    s, _, m = O.split(w)
+    pm = np.bincount(m, minlength=128) / m.size
+    assert -(pm[pm > 0] * np.log2(pm[pm > 0])).sum() > 6.95
+    assert abs(s.mean() - 0.5) < 2e-3
+
+
+# ---------------------------------------------------------------- frequency table
+
+def test_quantise_closed_cases():
+    c = np.zeros(256, np.uint64)
+    assert O.quantise(c).sum() == 0
+    c[42] = 9
+    f = O.quantise(c)
+    assert f[42] == 4096 and f.sum() == 4096
+    c[7] = 9
+    f = O.quantise(c)
+    assert f[7] == 2048 and f[42] == 2048
+    f = O.quantise(np.full(256, 123, np.uint64))
+    assert np.all(f == 16)
+    # 255 singletons and one huge count: every singleton keeps f = 1, the rest goes to the big one
+    c = np.ones(256, np.uint64)
+    c[100] = 10 ** 9
+    f = O.quantise(c)
+    assert f[100] == 4096 - 255 and np.all(np.delete(f, 100) == 1)
+    # three equal counts: floor gives 1365 each, the shortfall of 1 goes to the lowest symbol
+    c = np.zeros(256, np.uint64)
+    c[[9, 3, 200]] = 50
+    f = O.quantise(c)
+    assert (f[3], f[9], f[200]) == (1366, 1365, 1365)
+
+
+def test_quantise_excess_is_taken_from_the_largest():
+    # 200 symbols with count 1 and 56 with count 100: floors are 0 -> 1 for the rare ones,
+    # floor(100*4096/5800) = 70 for the common ones; 200 + 56*70 = 4120 > 4096, so 24 units
+    # come off the largest entries, lowest symbol first.
+    c = np.ones(256, np.uint64)
+    c[:56] = 100
+    f = O.quantise(c)
+    assert f.sum() == 4096
+    assert np.all(f[56:] == 1)
+    assert np.all(f[:24] == 69) and np.all(f[24:56] == 70)
+
+
+def test_quantise_properties_and_second_implementation():
+    rng = np.random.default_rng(5)
+    for trial in range(200):
+        k = int(rng.integers(1, 257))
+        c = np.zeros(256, np.uint64)
+        idx = rng.choice(256, k, replace=False)
+        c[idx] = (rng.pareto(0.7, k) * 10 + 1).astype(np.uint64)
+        f = O.quantise(c)
+        assert f.sum() == 4096
+        assert np.array_equal(f > 0, c > 0)
+        assert list(f) == P.quantise([int(x) for x in c])
+        # never costs much more than the empirical entropy
+        assert O.cross_entropy(c, f) >= O.entropy(c) - 1e-9
+
+
+# ---------------------------------------------------------------- rANS step arithmetic (Sec. 2.2)
+
+def golden_steps():
+    rows = []
+    with open(os.path.join(GOLDEN, "rans_steps.txt")) as fh:
+        for line in fh:
+            line = line.split("#")[0].split()
+            if line:
+                f, c, x0, x1 = (int(t) for t in line[:4])
+                rows.append((f, c, x0, x1, None if line[4] == "-" else int(line[4])))
+    return rows
+
+
+def test_rans_steps_match_hand_worked_values():
+    rows = golden_steps()
+    assert len(rows) == 8
+    for f, c, x0, x1, word in rows:
+        assert O.rans_encode_step(x0, f, c) == (x1, word)
+        # and the decoder undoes exactly that step
+        back, consumed = O.rans_decode_step(x1, f, c, 0 if word is None else word)
+        assert back == x0 and consumed == (word is not None)
+
+
+def test_rans_step_is_a_bijection_that_keeps_the_state_interval():
+    rng = np.random.default_rng(9)
+    for _ in range(20000):
+        f = int(rng.integers(1, 4096))
+        c = int(rng.integers(0, 4096 - f + 1))
+        x = int(rng.integers(1 << 16, 1 << 32))
+        xn, word = O.rans_encode_step(x, f, c)
+        assert (1 << 16) <= xn < (1 << 32)
+        assert c <= xn % 4096 < c + f                           # the slot names the symbol
+        back, consumed = O.rans_decode_step(xn, f, c, word or 0)
+        assert back == x and consumed == (word is not None)
+
+
+def test_equal_halves_turn_the_state_into_the_binary_number():
+    # With two symbols of frequency M/2 every step appends one bit: starting from 2^16 the
+    # state after n <= 15 steps is 2^(16+n) + 2048 * (the bits read as a binary number).
+    freq = np.zeros(256, np.uint16)
+    freq[[10, 20]] = 2048
+    for bits in itertools.product([0, 1], repeat=6):
+        sym = [10 if b == 0 else 20 for b in bits]
+        states, lens, runs = O.encode_chunk(sym, freq, k_states=1, g=1)
+        value = 0
+        for b in reversed(bits):                                # the coder runs back to front
+            value = 2 * value + b
+        assert int(states[0]) == (1 << (16 + len(bits))) + 2048 * value
+        assert lens[0] == 0
+
+
+def test_single_symbol_chunk_never_emits():
+    freq = np.zeros(256, np.uint16)
+    freq[121] = 4096
+    states, lens, runs = O.encode_chunk(np.full(4096, 121, np.uint8), freq)
+    assert np.all(states == 65536) and np.all(lens == 0)
+    assert np.all(O.decode_chunk(4096, freq, states, runs) == 121)
+
+
+def test_chunk_codec_brute_force_small_alphabets():
+    tables = [{0: 4096}, {0: 2048, 1: 2048}, {0: 4095, 1: 1}, {0: 1, 1: 4095},
+              {3: 1, 7: 2, 9: 4093}, {3: 1365, 7: 1365, 9: 1366}, {0: 1, 128: 1, 255: 4094}]
+    for table in tables:
+        freq = np.zeros(256, np.uint16)
+        for s, f in table.items():
+            freq[s] = f
+        alphabet = sorted(table)
+        for n in range(0, 9):
+            for seq in itertools.product(alphabet, repeat=n):
+                for K, G in ((1, 1), (2, 2), (3, 1)):
+                    states, lens, runs = O.encode_chunk(seq, freq, k_states=K, g=G, words_cap=16)
+                    back = O.decode_chunk(n, freq, states, runs, k_states=K, g=G)
+                    assert tuple(back) == seq
+                    # the independent per-state coder gives the same states and words
+                    for j in range(K):
+                        mine = [seq[i] for i in P.state_symbols(n, j, K, G)]
+                        x, words = P.encode_state(mine, [int(f) for f in freq])
+                        assert x == int(states[j]) and words == list(runs[j])
+
+
+def test_long_rare_symbol_run_hits_the_word_capacity_bound():
+    # 4096 symbols of frequency 1 cost 12 bits each: 256 per state -> exactly 192 words per state
+    freq = np.zeros(256, np.uint16)
+    freq[0] = 4095
+    freq[255] = 1
+    states, lens, runs = O.encode_chunk(np.full(4096, 255, np.uint8), freq, words_cap=192)
+    assert np.all(lens == 192)
+    assert np.all(O.decode_chunk(4096, freq, states, runs) == 255)
+
+
+# ---------------------------------------------------------------- container: both statements of the format agree
+
+@pytest.mark.parametrize("k", [7, 3, 1, 0])
+@pytest.mark.parametrize("n", [0, 1, 7, 130, 4096, 4097, 9001])
+def test_c_oracle_and_python_codec_write_identical_bytes(n, k):
+    w = inputs.bits(inputs.gaussian_bf16(n, seed=100 + n)) if n else np.zeros(0, np.uint16)
+    blob = O.compress(w, k, threads=2)
+    mine = P.compress([int(u) for u in w], k)
+    assert blob.tobytes() == mine
+    assert P.decompress(mine) == [int(u) for u in O.truncate(w, k)]
+    assert np.array_equal(O.decompress(np.frombuffer(mine, np.uint8), n), O.truncate(w, k))
+
+
+def test_python_codec_decodes_heavy_tailed_blob_from_c_oracle():
+    w = inputs.bits(inputs.student_t4_bf16(6000, seed=3))
+    blob = O.compress(w, 3)
+    assert P.decompress(blob.tobytes()) == [int(u) for u in O.truncate(w, 3)]
+
+
+# ---------------------------------------------------------------- invariants of the whole path
+
+@pytest.mark.parametrize("k", [7, 3, 1, 0])
+def test_round_trip_of_every_bf16_pattern(k):
+    blob = O.compress(ALL, k, threads=4)
+    assert np.array_equal(O.decompress(blob, 65536, threads=3), O.truncate(ALL, k))
+    perm = np.random.default_rng(k).permutation(ALL)
+    assert np.array_equal(O.decompress(O.compress(perm, k), 65536), O.truncate(perm, k))
+
+
+@pytest.mark.parametrize("n", [1, 2, 127, 128, 129, 4095, 4096 * 3 + 1, 100_003])
+def test_lossless_round_trip_ragged_sizes(n):
+    for gen in (inputs.gaussian_bf16, inputs.student_t4_bf16, inputs.random_bits_bf16):
+        w = inputs.bits(gen(n, seed=n))
+        for threads in (1, 5):
+            assert np.array_equal(O.decompress(O.compress(w, 7, threads), n, threads), w)
+
+
+def test_threads_do_not_change_the_bytes():
+    w = inputs.bits(inputs.gaussian_bf16(300_000, seed=77))
+    assert np.array_equal(O.compress(w, 7, threads=1), O.compress(w, 7, threads=8))
+
+
+def test_size_against_entropy_bound_config1():
+    # Config 1: 1024 x 1024, N(0, 0.02^2), lossless.
+    w = inputs.bits(inputs.gaussian_bf16((1024, 1024), seed=inputs.seed_for(1)))
+    n = w.size
+    blob = O.compress(w, 7, threads=8)
+    cnt = O.histogram(w)
+    info = O.blob_info(blob)
+    H, CE = O.entropy(cnt), O.cross_entropy(cnt, info["freq"])
+    assert 0 <= CE - H < 0.01                                   # cost of the 12-bit table
+    n_states = (n // 4096) * 16
+    coded_bits = 16 * info["total_words"] + 32 * n_states
+    # information content under the table, plus between 16 and 32 bits of flush per state
+    assert n * CE + 16 * n_states - 0.002 * n <= coded_bits <= n * CE + 32 * n_states + 0.002 * n
+    bits_per_weight = 8 * blob.size / n
+    assert bits_per_weight <= 1.02 * (H + 8)                    # the stated target
+    assert bits_per_weight - (H + 8) == pytest.approx(0.14, abs=0.03)
+
+
+def test_lossy_size_and_bound():
+    w = inputs.bits(inputs.student_t4_bf16(500_000, seed=inputs.seed_for(4)))
+    H = O.entropy(O.histogram(w))
+    assert H == pytest.approx(2.708, abs=0.02)
+    for k in (3, 1, 0):
+        blob = O.compress(w, k, threads=4)
+        bpw = 8 * blob.size / w.size
+        assert H + (k + 1) < bpw < H + (k + 1) + 0.2
+        # same exponents, hence the same table and words, for every k
+        sec, sec7 = O.sections(blob), O.sections(O.compress(w, 7, threads=4))
+        b7 = O.compress(w, 7, threads=4)
+        for name in ("freq", "offsets", "states", "lens", "words"):
+            assert np.array_equal(blob[slice(*sec[name])], b7[slice(*sec7[name])])
+
+
+def test_corruption_is_detected():
+    w = inputs.bits(inputs.gaussian_bf16(50_000, seed=5))
+    blob = O.compress(w, 7)
+    sec = O.sections(blob)
+    rng = np.random.default_rng(1)
+    detected = 0
+    for trial in range(40):
+        bad = blob.copy()
+        name = ("states", "words", "lens")[trial % 3]
+        lo, hi = sec[name]
+        pos = int(rng.integers(lo, hi - 16))
+        bad[pos] ^= 1 << int(rng.integers(0, 8))
+        try:
+            out = O.decompress(bad, w.size)
+            assert not np.array_equal(out, w) or name == "lens"
+        except O.OracleError as err:
+            assert err.code == O.ECORRUPT
+            detected += 1
+    assert detected >= 30                                       # final-state check catches nearly all
+    with pytest.raises(O.OracleError):
+        O.decompress(blob[:-16], w.size)
+    with pytest.raises(O.OracleError):
+        O.decompress(blob, w.size + 1)
+    with pytest.raises(O.OracleError):
+        O.compress(w, 5)
