@@ -1,0 +1,162 @@
+/*
+ * neuzip.h -- C ABI of the MI355X (gfx950) NeuZip codec library.
+ *
+ * What the library does (NeuZip, arXiv 2410.20650): a bf16 weight tensor is
+ * split into its exponent bytes and a packed sign|mantissa stream (Alg. 1
+ * "split"; App. D), the low-entropy exponents are entropy-coded with an
+ * asymmetric numeral system (Sec. 2.2 "Compression algorithm"), and the
+ * tensor is rebuilt bit-exactly into caller-provided temporary space right
+ * before a layer uses it (Sec. 2.2 Eq. (3); Alg. 1 "decompression"/"merge").
+ * The lossy inference variant keeps only the k leading mantissa bits
+ * (Sec. 2.3), k in {3, 1, 0}.
+ *
+ * Conventions for every entry point
+ *   - d_* arguments are DEVICE pointers owned by the caller, h_* arguments are
+ *     HOST pointers owned by the caller.  Nothing is retained after the call's
+ *     stream work has completed.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     All kernels and copies of a call are enqueued on it.
+ *   - Tensors are flat, contiguous arrays of n_elems 16-bit words; the shape
+ *     of the matrix is irrelevant to the codec.  d_src / d_dst must be aligned
+ *     to 16 bytes.  n_elems must be below 2^32.
+ *   - Errors are reported through the return code only (no exceptions, no
+ *     aborts, nothing is printed).  On error no output argument is modified
+ *     unless stated otherwise.
+ *   - Calls that touch different blobs may run concurrently from different
+ *     host threads; compress calls are serialised inside the library because
+ *     they share one per-device workspace.
+ */
+#ifndef NEUZIP_H
+#define NEUZIP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Opaque handle of one compressed tensor.  The library owns the device memory
+ * behind it until neuzip_free. */
+typedef struct neuzip_blob neuzip_blob;
+
+/* Element types.  The paper works on BFloat16 only (Sec. 2.1, footnote). */
+enum { NEUZIP_BF16 = 0 };
+
+enum {
+    NEUZIP_OK = 0,
+    NEUZIP_EINVAL = -1,       /* bad argument (null pointer, misaligned, wrong n/dtype/mantissa_bits) */
+    NEUZIP_ENOMEM = -2,       /* device or host allocation failed, or h_buf too small */
+    NEUZIP_EHIP = -3,         /* a HIP runtime call failed; see neuzip_last_hip_error() */
+    NEUZIP_ECORRUPT = -4,     /* a container or a decoded stream is not well formed */
+    NEUZIP_EUNSUPPORTED = -5  /* size outside the supported range */
+};
+
+/* Format constants of the stream (mirrored in every container header). */
+enum {
+    NEUZIP_PROB_BITS = 12,        /* frequencies sum to 2^12 */
+    NEUZIP_CHUNK = 4096,          /* exponent symbols per independently decodable chunk */
+    NEUZIP_STATES_PER_CHUNK = 16, /* rANS states per chunk, each with a private word run */
+    NEUZIP_RUN = 8                /* consecutive symbols one state codes per turn */
+};
+
+/*
+ * neuzip_compress -- Alg. 1 initialisation loop and the re-compression after a
+ * weight update ("split", "compression", "store"); Sec. 2.3 for k < 7.
+ *
+ *   d_src          n_elems bf16 words on the device (read only).
+ *   dtype          NEUZIP_BF16.
+ *   mantissa_bits  7 = lossless; 3, 1 or 0 = keep that many leading mantissa
+ *                  bits, truncating toward zero.
+ *   blob           in/out.  *blob == NULL: a new blob is created.  Otherwise
+ *                  *blob must be a blob of this library with the same n_elems
+ *                  and mantissa_bits; its device memory is reused (and grown
+ *                  if the new stream is longer) and its old content is lost.
+ *
+ * Builds the exponent histogram, the 12-bit frequency table, encodes every
+ * 4096-symbol chunk with 16 rANS states, and stores exponent stream and
+ * sign|mantissa stream in device memory sized exactly for this tensor.
+ * Synchronises hip_stream once (the stream length is data dependent).
+ * n_elems == 0 yields a valid empty blob.
+ */
+int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa_bits,
+                    void *hip_stream, neuzip_blob **blob);
+
+/*
+ * neuzip_decompress -- Sec. 2.2 Eq. (3), Alg. 1 "decompression" + "merge":
+ * decodes the exponents and reassembles bf16 words into the caller's
+ * temporary space in one fused kernel.
+ *
+ *   d_dst    room for n_elems bf16 words on the device, 16-byte aligned.
+ *   n_elems, dtype must equal what the blob was made from (else EINVAL).
+ *
+ * Never allocates, never synchronises.  For mantissa_bits < 7 the dropped
+ * mantissa bits come back as zeros.  A malformed stream is detected on the
+ * device and reported by the next neuzip_check on this blob.
+ */
+int neuzip_decompress(const neuzip_blob *blob, void *d_dst, uint64_t n_elems, int dtype,
+                      void *hip_stream);
+
+/*
+ * neuzip_decompress_sequence -- the per-layer schedule of Sec. 2.2 / Alg. 1
+ * forward loop: every blob, in the given order, is decompressed into the same
+ * temporary space, one after the other on hip_stream, so that the whole model
+ * is never held uncompressed.
+ *
+ *   blobs          host array of count blob handles.
+ *   d_scratch      device buffer of scratch_elems bf16 words, 16-byte aligned;
+ *                  must hold the largest tensor (else EINVAL, nothing is run).
+ * Never allocates, never synchronises.
+ */
+int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, void *d_scratch,
+                               uint64_t scratch_elems, void *hip_stream);
+
+/* Releases the blob and its device memory.  NULL is a no-op. */
+void neuzip_free(neuzip_blob *blob);
+
+/* Size in bytes of the blob's container (header, table, offsets, states, run
+ * lengths, words, sign|mantissa stream, padding): what neuzip_export writes.
+ * This is the figure bits/weight is computed from (Sec. 2.1: compression
+ * ratio).  0 for NULL. */
+uint64_t neuzip_compressed_bytes(const neuzip_blob *blob);
+
+/* Bytes of device memory the blob actually holds (container sections plus
+ * alignment padding and the derived cumulative table). */
+uint64_t neuzip_device_bytes(const neuzip_blob *blob);
+
+/* Element count and mantissa bits the blob was made with. */
+uint64_t neuzip_elems(const neuzip_blob *blob);
+int neuzip_mantissa_bits(const neuzip_blob *blob);
+
+/*
+ * neuzip_export / neuzip_import -- the container as one flat host byte buffer
+ * (App. D storage layout: compressed exponents next to the signed mantissas).
+ * Export synchronises hip_stream.  With h_buf == NULL only *written is set.
+ * Import validates every section on the host before anything is uploaded
+ * (ECORRUPT otherwise) and creates a new blob.
+ */
+int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *written,
+                  void *hip_stream);
+int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob **blob);
+
+/* Exponent statistics of the tensor the blob was compressed from (Sec. 2.2):
+ * h_counts receives the 256-bin histogram (EINVAL for imported blobs, which
+ * carry no counts), h_freq the quantised frequencies that sum to 4096. */
+int neuzip_histogram(const neuzip_blob *blob, uint32_t h_counts[256]);
+int neuzip_frequencies(const neuzip_blob *blob, uint16_t h_freq[256]);
+
+/* Synchronises hip_stream and returns ECORRUPT if any decompression of this
+ * blob so far found a state that did not return to its initial value or a
+ * word run that was not consumed exactly; clears the flag. */
+int neuzip_check(const neuzip_blob *blob, void *hip_stream);
+
+/* Frees the per-device workspace compress keeps between calls. */
+int neuzip_release_workspace(void);
+
+const char *neuzip_strerror(int code);
+/* hipError_t of the last failing HIP call on this host thread (0 if none). */
+int neuzip_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -331,7 +331,9 @@ static void put16(uint8_t *p, uint16_t v)
 }
 static uint16_t get16(const uint8_t *p) { return (uint16_t)(p[0] | (p[1] << 8)); }
 
-#define NZO_RUN_CAP 192u /* 256 symbols * at most 12 bits / 16 */
+/* Room for one state's words.  A step grows log2(x + 1) by at most 12 bits, an emitted word
+ * shrinks it by at least 16 - log2(17/16) bits, so 256 symbols give at most 193 words. */
+#define NZO_RUN_CAP 200u
 
 static uint64_t chunks_of(uint64_t n) { return (n + NZO_CHUNK - 1) / NZO_CHUNK; }
 

@@ -41,7 +41,7 @@
  *   every section is zero-padded to a multiple of 16 bytes.
  *   offsets[c] = number of words that belong to chunks before c.
  *   Inside chunk c the K private runs follow each other, state 0 first;
- *   lens[c*K+j] is the run length of state j in words (at most 192).
+ *   lens[c*K+j] is the run length of state j in words (at most 193).
  */
 #ifndef NEUZIP_ORACLE_H
 #define NEUZIP_ORACLE_H

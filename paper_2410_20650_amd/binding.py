@@ -1,0 +1,214 @@
+"""Thin ctypes binding of libneuzip.so: argument marshalling only.
+
+Every step of the method runs inside the HIP library; PyTorch is used for
+device memory and streams.  The functions mirror include/neuzip.h name for
+name.  If the library has not been built it is built once with hipcc; if that
+is impossible the import fails loudly -- there is no CPU fallback.
+"""
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+BF16 = 0
+OK, EINVAL, ENOMEM, EHIP, ECORRUPT, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+
+
+class NeuzipError(RuntimeError):
+    def __init__(self, code, what):
+        msg = _lib.neuzip_strerror(code).decode() if _lib is not None else "?"
+        hip = _lib.neuzip_last_hip_error() if _lib is not None else 0
+        super().__init__(f"{what}: {msg} (code {code}, hip error {hip})")
+        self.code = code
+
+
+def _load():
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    lib = ctypes.CDLL(_build.LIB)
+    vp, u64, i32, u32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_uint32
+    vpp = ctypes.POINTER(vp)
+    lib.neuzip_compress.argtypes = [vp, u64, i32, i32, vp, vpp]
+    lib.neuzip_compress.restype = i32
+    lib.neuzip_decompress.argtypes = [vp, vp, u64, i32, vp]
+    lib.neuzip_decompress.restype = i32
+    lib.neuzip_decompress_sequence.argtypes = [vpp, u32, vp, u64, vp]
+    lib.neuzip_decompress_sequence.restype = i32
+    lib.neuzip_free.argtypes = [vp]
+    lib.neuzip_free.restype = None
+    lib.neuzip_compressed_bytes.argtypes = [vp]
+    lib.neuzip_compressed_bytes.restype = u64
+    lib.neuzip_device_bytes.argtypes = [vp]
+    lib.neuzip_device_bytes.restype = u64
+    lib.neuzip_elems.argtypes = [vp]
+    lib.neuzip_elems.restype = u64
+    lib.neuzip_mantissa_bits.argtypes = [vp]
+    lib.neuzip_mantissa_bits.restype = i32
+    lib.neuzip_export.argtypes = [vp, vp, u64, ctypes.POINTER(u64), vp]
+    lib.neuzip_export.restype = i32
+    lib.neuzip_import.argtypes = [vp, u64, vp, vpp]
+    lib.neuzip_import.restype = i32
+    lib.neuzip_histogram.argtypes = [vp, ctypes.POINTER(u32)]
+    lib.neuzip_histogram.restype = i32
+    lib.neuzip_frequencies.argtypes = [vp, ctypes.POINTER(ctypes.c_uint16)]
+    lib.neuzip_frequencies.restype = i32
+    lib.neuzip_check.argtypes = [vp, vp]
+    lib.neuzip_check.restype = i32
+    lib.neuzip_release_workspace.argtypes = []
+    lib.neuzip_release_workspace.restype = i32
+    lib.neuzip_strerror.argtypes = [i32]
+    lib.neuzip_strerror.restype = ctypes.c_char_p
+    lib.neuzip_last_hip_error.argtypes = []
+    lib.neuzip_last_hip_error.restype = i32
+    return lib
+
+
+_lib = None
+_lib = _load()
+
+EXPORTED = ["neuzip_compress", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_free",
+            "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits",
+            "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check",
+            "neuzip_release_workspace", "neuzip_strerror", "neuzip_last_hip_error"]
+
+
+def library():
+    return _lib
+
+
+def _stream_handle(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check_tensor(t):
+    if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
+        raise TypeError("expected a contiguous bf16 CUDA tensor")
+
+
+class Blob:
+    """Owns one neuzip_blob handle."""
+
+    def __init__(self, handle):
+        self.handle = ctypes.c_void_p(handle)
+
+    def free(self):
+        if self.handle:
+            _lib.neuzip_free(self.handle)
+            self.handle = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+    @property
+    def compressed_bytes(self):
+        return int(_lib.neuzip_compressed_bytes(self.handle))
+
+    @property
+    def device_bytes(self):
+        return int(_lib.neuzip_device_bytes(self.handle))
+
+    @property
+    def elems(self):
+        return int(_lib.neuzip_elems(self.handle))
+
+    @property
+    def mantissa_bits(self):
+        return int(_lib.neuzip_mantissa_bits(self.handle))
+
+
+def neuzip_compress(src: torch.Tensor, mantissa_bits: int = 7, stream=None, blob: Blob = None) -> Blob:
+    _check_tensor(src)
+    handle = ctypes.c_void_p(blob.handle.value if blob is not None else None)
+    rc = _lib.neuzip_compress(ctypes.c_void_p(src.data_ptr()), src.numel(), BF16, mantissa_bits,
+                              _stream_handle(stream), ctypes.byref(handle))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_compress")
+    if blob is not None:
+        blob.handle = handle
+        return blob
+    return Blob(handle.value)
+
+
+def neuzip_decompress(blob: Blob, dst: torch.Tensor, stream=None) -> torch.Tensor:
+    _check_tensor(dst)
+    rc = _lib.neuzip_decompress(blob.handle, ctypes.c_void_p(dst.data_ptr()), dst.numel(), BF16,
+                                _stream_handle(stream))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_decompress")
+    return dst
+
+
+def neuzip_decompress_sequence(blobs, scratch: torch.Tensor, stream=None) -> None:
+    _check_tensor(scratch)
+    arr = (ctypes.c_void_p * len(blobs))(*[b.handle.value for b in blobs])
+    rc = _lib.neuzip_decompress_sequence(arr, len(blobs), ctypes.c_void_p(scratch.data_ptr()),
+                                         scratch.numel(), _stream_handle(stream))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_decompress_sequence")
+
+
+def neuzip_free(blob: Blob) -> None:
+    blob.free()
+
+
+def neuzip_compressed_bytes(blob: Blob) -> int:
+    return blob.compressed_bytes
+
+
+def neuzip_export(blob: Blob, stream=None) -> np.ndarray:
+    size = ctypes.c_uint64(0)
+    rc = _lib.neuzip_export(blob.handle, None, 0, ctypes.byref(size), _stream_handle(stream))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_export(size)")
+    buf = np.empty(size.value, np.uint8)
+    rc = _lib.neuzip_export(blob.handle, buf.ctypes.data_as(ctypes.c_void_p), buf.size, ctypes.byref(size),
+                            _stream_handle(stream))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_export")
+    return buf
+
+
+def neuzip_import(container: np.ndarray, stream=None) -> Blob:
+    container = np.ascontiguousarray(container, dtype=np.uint8)
+    handle = ctypes.c_void_p(None)
+    rc = _lib.neuzip_import(container.ctypes.data_as(ctypes.c_void_p), container.size, _stream_handle(stream),
+                            ctypes.byref(handle))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_import")
+    return Blob(handle.value)
+
+
+def neuzip_histogram(blob: Blob) -> np.ndarray:
+    out = np.zeros(256, np.uint32)
+    rc = _lib.neuzip_histogram(blob.handle, out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_histogram")
+    return out
+
+
+def neuzip_frequencies(blob: Blob) -> np.ndarray:
+    out = np.zeros(256, np.uint16)
+    rc = _lib.neuzip_frequencies(blob.handle, out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_frequencies")
+    return out
+
+
+def neuzip_check(blob: Blob, stream=None) -> None:
+    rc = _lib.neuzip_check(blob.handle, _stream_handle(stream))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_check")
+
+
+def neuzip_release_workspace() -> None:
+    rc = _lib.neuzip_release_workspace()
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_release_workspace")

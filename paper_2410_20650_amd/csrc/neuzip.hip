@@ -1,0 +1,1200 @@
+// NeuZip codec for MI355X (gfx950): HIP kernels and the C ABI declared in
+// include/neuzip.h.
+//
+// Stream format (little-endian):
+//   container := header(64 B) | freq[256] u16 | offsets[nc+1] u32 | states[nc*16] u32
+//              | lens[nc*16] u8 | words[total] u16 | signmant[ceil(n*(k+1)/8)] u8
+//   every section zero-padded to 16 bytes.  A chunk is 4096 exponent symbols; local symbol i
+//   belongs to rANS state j = (i mod 128) / 8, so a state codes runs of 8 neighbouring symbols.
+//   Each state owns a private run of 16-bit words (lens[] words long, at most 193) stored in
+//   the order the decoder consumes them; the 16 runs of a chunk follow each other and
+//   offsets[c] counts the words before chunk c.
+//
+// Why this shape on CDNA4: one lane walks one state.  Because every state has its own word
+// run, a refill is a lane-private pointer bump and a 16-bit LDS read, with no cross-lane
+// ballot/prefix on the per-symbol dependency chain.  Runs of 8 symbols make each lane own 8
+// neighbouring bf16 words, so the merged output leaves as one 128-bit store and the
+// sign|mantissa bytes arrive as one 64-bit load; 16 lanes cover 256 contiguous output bytes.
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <new>
+
+#include "neuzip.h"
+
+namespace {
+
+constexpr uint32_t kProbBits = NEUZIP_PROB_BITS;
+constexpr uint32_t kM = 1u << kProbBits;
+constexpr uint32_t kChunk = NEUZIP_CHUNK;
+constexpr uint32_t kStates = NEUZIP_STATES_PER_CHUNK;
+constexpr uint32_t kRun = NEUZIP_RUN;
+constexpr uint32_t kTurn = kStates * kRun;          // symbols per turn of all states (128)
+constexpr uint32_t kTurns = kChunk / kTurn;         // turns per full chunk (32)
+constexpr uint32_t kRansL = 1u << 16;
+// Words one state can emit for its 256 symbols.  Every step grows log2(x + 1) by at most 12 bits and
+// every emitted word shrinks it by at least 16 - log2(17/16) bits, which bounds a run by 193 words.
+constexpr uint32_t kRunCap = 200;
+constexpr uint32_t kMagic = 0x315A554Eu;            // "NUZ1"
+constexpr uint32_t kHeaderBytes = 64;
+
+// Decoder launch shape: 512 threads = 8 waves, each wave walks 4 chunks (4 x 16 states).
+constexpr uint32_t kDecThreads = 512;
+constexpr uint32_t kDecChunksPerWg = kDecThreads / kStates;   // 32
+// LDS: 16 KB slot table + staged word runs.  Two workgroups share a CU's 160 KB.
+constexpr uint32_t kStageBytes = 62 * 1024;
+
+thread_local int g_last_hip_error = 0;
+
+inline bool hip_ok(hipError_t e)
+{
+    if (e != hipSuccess) {
+        g_last_hip_error = static_cast<int>(e);
+        return false;
+    }
+    return true;
+}
+#define NZ_HIP(call)                 \
+    do {                             \
+        if (!hip_ok(call))           \
+            return NEUZIP_EHIP;      \
+    } while (0)
+
+inline uint64_t pad_to(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+inline bool valid_k(int k) { return k == 7 || k == 3 || k == 1 || k == 0; }
+inline uint64_t signmant_bytes(uint64_t n, int k) { return (n * static_cast<uint64_t>(k + 1) + 7) / 8; }
+inline uint32_t chunks_of(uint64_t n) { return static_cast<uint32_t>((n + kChunk - 1) / kChunk); }
+
+// ------------------------------------------------------------------------------------------
+// Device-side table block that sits at the start of every blob's fixed allocation.
+// ------------------------------------------------------------------------------------------
+struct TableBlock {
+    uint16_t freq[256];    // quantised frequencies (stored in the container)
+    uint16_t cum[264];     // exclusive cumulative frequencies, cum[256] = 4096 (derived)
+    uint32_t counts[256];  // exponent histogram of the source tensor
+    uint32_t status[4];    // [0] != 0: a decode found a malformed stream
+    uint32_t pad[56];
+};
+static_assert(sizeof(TableBlock) % 256 == 0, "table block keeps later sections aligned");
+
+// Per-symbol encoder constants (16 bytes, one ds_read_b128).
+//   magic/sh1/sh2: division by the frequency f by multiplication (Granlund & Montgomery's
+//   round-up method for 32-bit dividends): t = mulhi(magic, x); q = (t + ((x - t) >> sh1)) >> sh2.
+//   limit: the state is renormalised before the step when x >= limit = f << 20.
+//   The step itself is x <- (x / f) * M + (x mod f) + cum = q * (M - f) + x + cum.
+struct EncSym {
+    uint32_t magic;
+    uint32_t limit;
+    uint32_t cmpl_cum;  // (M - f) | cum << 16
+    uint32_t shifts;    // sh1 | sh2 << 8
+};
+
+// ------------------------------------------------------------------------------------------
+// Small helpers
+// ------------------------------------------------------------------------------------------
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t value, uint32_t count)
+{
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count)
+        p[i] = value;
+}
+
+__device__ inline uint32_t exponent_of(uint32_t u) { return (u >> 7) & 0xFFu; }
+
+template <int KB>
+__device__ inline uint32_t signmant_field(uint32_t u)
+{
+    // sign on top of the KB leading mantissa bits (Sec. 2.3 / App. D: one signed field)
+    return ((u >> 15) << KB) | ((u & 0x7Fu) >> (7 - KB));
+}
+
+template <int KB>
+__device__ inline void store_fields(uint8_t *sm, uint64_t vec, uint64_t packed)
+{
+    if constexpr (KB == 7)
+        reinterpret_cast<uint2 *>(sm)[vec] = make_uint2(static_cast<uint32_t>(packed), static_cast<uint32_t>(packed >> 32));
+    else if constexpr (KB == 3)
+        reinterpret_cast<uint32_t *>(sm)[vec] = static_cast<uint32_t>(packed);
+    else if constexpr (KB == 1)
+        reinterpret_cast<uint16_t *>(sm)[vec] = static_cast<uint16_t>(packed);
+    else
+        sm[vec] = static_cast<uint8_t>(packed);
+}
+
+// ------------------------------------------------------------------------------------------
+// Kernel 1: exponent histogram fused with the sign|mantissa split (Alg. 1 "split").
+// One pass over the bf16 words: 2 B/elem read, (k+1)/8 B/elem written.  Counts go to 32
+// bank-private copies of the 256 bins in LDS (copy = lane mod 32, so the 64 lanes of a wave
+// hit 32 different banks whatever the symbol skew is), then one global atomic per bin.
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kHistThreads = 256;
+constexpr uint32_t kHistCopies = 32;
+
+template <int KB>
+__global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const uint16_t *__restrict__ src, uint64_t n,
+                                                                 uint8_t *__restrict__ sm,
+                                                                 uint32_t *__restrict__ counts)
+{
+    __shared__ uint32_t bins[256 * kHistCopies];
+    for (uint32_t i = threadIdx.x; i < 256 * kHistCopies; i += kHistThreads)
+        bins[i] = 0;
+    __syncthreads();
+
+    const uint32_t copy = threadIdx.x & (kHistCopies - 1);
+    const uint64_t n_vec = n / 8;
+    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kHistThreads;
+    const uint4 *src4 = reinterpret_cast<const uint4 *>(src);
+    for (uint64_t v = static_cast<uint64_t>(blockIdx.x) * kHistThreads + threadIdx.x; v < n_vec; v += stride) {
+        const uint4 d = src4[v];
+        const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+        uint64_t packed = 0;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint32_t lo = w[p] & 0xFFFFu, hi = w[p] >> 16;
+            atomicAdd(&bins[exponent_of(lo) * kHistCopies + copy], 1u);
+            atomicAdd(&bins[exponent_of(hi) * kHistCopies + copy], 1u);
+            packed |= static_cast<uint64_t>(signmant_field<KB>(lo)) << ((2 * p) * (KB + 1));
+            packed |= static_cast<uint64_t>(signmant_field<KB>(hi)) << ((2 * p + 1) * (KB + 1));
+        }
+        store_fields<KB>(sm, v, packed);
+    }
+    // ragged tail (n mod 8 elements): one thread, element by element
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        constexpr uint32_t per_byte = 8 / (KB + 1);
+        uint32_t acc = 0, filled = 0;
+        for (uint64_t i = n_vec * 8; i < n; ++i) {
+            const uint32_t u = src[i];
+            atomicAdd(&bins[exponent_of(u) * kHistCopies + copy], 1u);
+            acc |= signmant_field<KB>(u) << (filled * (KB + 1));
+            if (++filled == per_byte) {
+                sm[i / per_byte] = static_cast<uint8_t>(acc);
+                acc = 0;
+                filled = 0;
+            }
+        }
+        if (filled)
+            sm[(n - 1) / per_byte] = static_cast<uint8_t>(acc);
+    }
+    __syncthreads();
+    // thread b sums the 32 copies of bin b, starting at a rotated copy to spread the banks
+    {
+        const uint32_t b = threadIdx.x;
+        uint32_t sum = 0;
+#pragma unroll 8
+        for (uint32_t i = 0; i < kHistCopies; ++i)
+            sum += bins[b * kHistCopies + ((i + b) & (kHistCopies - 1))];
+        if (sum)
+            atomicAdd(&counts[b], sum);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Kernel 2: counts -> frequencies that sum to 4096, cumulative table, encoder constants.
+// One workgroup of 256 threads, thread s owns symbol s.  Integer only:
+//   f = max(1, floor(cnt * 4096 / N)) for symbols that occur, else 0; a shortfall goes to the
+//   most frequent symbol (lowest value on a tie); an excess is taken one unit at a time from
+//   the symbol whose f is largest at that moment (lowest value on a tie).
+// ------------------------------------------------------------------------------------------
+__device__ inline uint64_t block_max_u64(uint64_t v, uint64_t *scratch)
+{
+    // 256 threads = 4 waves
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint64_t o = __shfl_xor(v, off, 64);
+        v = o > v ? o : v;
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0)
+        scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint64_t r = scratch[0];
+    for (int i = 1; i < 4; ++i)
+        r = scratch[i] > r ? scratch[i] : r;
+    return r;
+}
+
+__device__ inline uint64_t block_sum_u64(uint64_t v, uint64_t *scratch)
+{
+    for (int off = 32; off > 0; off >>= 1)
+        v += __shfl_xor(v, off, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0)
+        scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return scratch[0] + scratch[1] + scratch[2] + scratch[3];
+}
+
+__global__ __launch_bounds__(256) void table_kernel(TableBlock *__restrict__ tb, EncSym *__restrict__ enc)
+{
+    __shared__ uint64_t scratch[4];
+    __shared__ uint32_t scan[256];
+    const uint32_t s = threadIdx.x;
+    const uint64_t cnt = tb->counts[s];
+    const uint64_t total = block_sum_u64(cnt, scratch);
+    uint32_t f = 0;
+    if (total > 0) {
+        if (cnt > 0) {
+            const uint64_t scaled = cnt * kM / total;
+            f = scaled < 1 ? 1u : static_cast<uint32_t>(scaled);
+        }
+        const int32_t sum = static_cast<int32_t>(block_sum_u64(f, scratch));
+        int32_t rest = static_cast<int32_t>(kM) - sum;
+        if (rest > 0) {
+            const uint64_t key = (cnt << 8) | (255u - s);
+            const uint64_t best = block_max_u64(key, scratch);
+            if (key == best)
+                f += static_cast<uint32_t>(rest);
+        }
+        while (rest < 0) {  // uniform across the workgroup
+            const uint64_t key = (static_cast<uint64_t>(f) << 8) | (255u - s);
+            const uint64_t best = block_max_u64(key, scratch);
+            if (key == best)
+                --f;
+            ++rest;
+        }
+    }
+    // exclusive cumulative sum over the 256 symbols
+    scan[s] = f;
+    __syncthreads();
+    for (uint32_t off = 1; off < 256; off <<= 1) {
+        const uint32_t add = s >= off ? scan[s - off] : 0;
+        __syncthreads();
+        scan[s] += add;
+        __syncthreads();
+    }
+    const uint32_t cum = scan[s] - f;
+    tb->freq[s] = static_cast<uint16_t>(f);
+    tb->cum[s] = static_cast<uint16_t>(cum);
+    if (s == 255)
+        tb->cum[256] = static_cast<uint16_t>(scan[255]);
+
+    EncSym e = {1u, 0xFFFFFFFFu, 0u, 0u};
+    if (f > 0) {
+        uint32_t l = 0;
+        while ((1u << l) < f)
+            ++l;                                   // l = ceil(log2 f)
+        e.magic = static_cast<uint32_t>(((static_cast<uint64_t>((1u << l) - f)) << 32) / f) + 1u;
+        e.limit = f >= kM ? 0xFFFFFFFFu : (f << 20);  // f = 4096 only for a one-symbol tensor: never renormalises
+        e.cmpl_cum = (kM - f) | (cum << 16);
+        e.shifts = (l < 1 ? l : 1u) | ((l > 0 ? l - 1 : 0u) << 8);
+    }
+    enc[s] = e;
+}
+
+// ------------------------------------------------------------------------------------------
+// Kernel 3: chunked rANS encoder (Sec. 2.2 "Compression algorithm").  One lane per state.
+// A state visits its symbols back to front; words it pushes out go, back to front, into its
+// own 200-word slot of the workspace, so that reading the slot's tail forwards gives the
+// decoder's order.  Final states and run lengths go straight to their place in the blob.
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kEncThreads = 256;
+
+__device__ inline uint32_t rans_put(uint32_t x, const EncSym e, uint16_t *slot, uint32_t &wp)
+{
+    if (x >= e.limit) {
+        slot[--wp] = static_cast<uint16_t>(x);
+        x >>= 16;
+    }
+    const uint32_t t = __umulhi(e.magic, x);
+    const uint32_t q = (t + ((x - t) >> (e.shifts & 0xFFu))) >> (e.shifts >> 8);
+    return __umul24(q, e.cmpl_cum & 0xFFFFu) + x + (e.cmpl_cum >> 16);
+}
+
+__global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__restrict__ src, uint64_t n,
+                                                            uint32_t n_chunks, const EncSym *__restrict__ enc_g,
+                                                            uint32_t *__restrict__ states,
+                                                            uint8_t *__restrict__ lens,
+                                                            uint16_t *__restrict__ slots)
+{
+    __shared__ uint4 enc_raw[256];
+    enc_raw[threadIdx.x] = reinterpret_cast<const uint4 *>(enc_g)[threadIdx.x];
+    __syncthreads();
+    const EncSym *enc = reinterpret_cast<const EncSym *>(enc_raw);
+
+    const uint32_t lane_id = blockIdx.x * kEncThreads + threadIdx.x;  // = chunk * 16 + state
+    const uint32_t c = lane_id / kStates, j = lane_id % kStates;
+    if (c >= n_chunks)
+        return;
+    const uint64_t base = static_cast<uint64_t>(c) * kChunk;
+    const uint32_t m = (n - base) < kChunk ? static_cast<uint32_t>(n - base) : kChunk;
+    uint16_t *slot = slots + static_cast<uint64_t>(lane_id) * kRunCap;
+    uint32_t wp = kRunCap;
+    uint32_t x = kRansL;
+
+    if (m == kChunk) {
+        const uint4 *src4 = reinterpret_cast<const uint4 *>(src + base) + j;
+        for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
+            const uint4 d = src4[q * kStates];
+            const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+            for (int p = 3; p >= 0; --p) {
+                x = rans_put(x, enc[exponent_of(w[p] >> 16)], slot, wp);
+                x = rans_put(x, enc[exponent_of(w[p] & 0xFFFFu)], slot, wp);
+            }
+        }
+    } else {
+        for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
+            for (int t = static_cast<int>(kRun) - 1; t >= 0; --t) {
+                const uint32_t i = static_cast<uint32_t>(q) * kTurn + j * kRun + static_cast<uint32_t>(t);
+                if (i < m)
+                    x = rans_put(x, enc[exponent_of(src[base + i])], slot, wp);
+            }
+        }
+    }
+    states[lane_id] = x;
+    lens[lane_id] = static_cast<uint8_t>(kRunCap - wp);
+}
+
+// ------------------------------------------------------------------------------------------
+// Kernel 4: offsets[c] = words before chunk c (exclusive prefix sum of the per-chunk totals).
+// One workgroup; each thread owns a contiguous range of chunks.
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kScanThreads = 1024;
+
+__device__ inline uint32_t chunk_words(const uint8_t *lens, uint32_t c)
+{
+    const uint4 v = reinterpret_cast<const uint4 *>(lens)[c];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t sum = 0;
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+        sum += (w[p] & 0xFFu) + ((w[p] >> 8) & 0xFFu) + ((w[p] >> 16) & 0xFFu) + (w[p] >> 24);
+    return sum;
+}
+
+__global__ __launch_bounds__(kScanThreads) void offsets_kernel(const uint8_t *__restrict__ lens, uint32_t n_chunks,
+                                                              uint32_t *__restrict__ offsets)
+{
+    __shared__ uint64_t part[kScanThreads];
+    const uint32_t per = (n_chunks + kScanThreads - 1) / kScanThreads;
+    const uint32_t begin = threadIdx.x * per;
+    const uint32_t end = begin + per < n_chunks ? begin + per : n_chunks;
+    uint64_t mine = 0;
+    for (uint32_t c = begin; c < end; ++c)
+        mine += chunk_words(lens, c);
+    part[threadIdx.x] = mine;
+    __syncthreads();
+    for (uint32_t off = 1; off < kScanThreads; off <<= 1) {
+        const uint64_t add = threadIdx.x >= off ? part[threadIdx.x - off] : 0;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    uint64_t running = part[threadIdx.x] - mine;
+    for (uint32_t c = begin; c < end; ++c) {
+        offsets[c] = static_cast<uint32_t>(running);
+        running += chunk_words(lens, c);
+    }
+    if (threadIdx.x == kScanThreads - 1) {
+        offsets[n_chunks] = static_cast<uint32_t>(part[kScanThreads - 1]);
+        offsets[n_chunks + 1] = static_cast<uint32_t>(part[kScanThreads - 1] >> 32);  // overflow guard for the host
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Kernel 5: gather the runs from the workspace slots into the blob's word section.
+// One wave per chunk: lanes copy run after run.
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kCompactThreads = 256;
+
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(const uint16_t *__restrict__ slots,
+                                                                 const uint8_t *__restrict__ lens,
+                                                                 const uint32_t *__restrict__ offsets,
+                                                                 uint32_t n_chunks, uint16_t *__restrict__ words)
+{
+    const uint32_t c = blockIdx.x * (kCompactThreads / 64) + threadIdx.x / 64;
+    const uint32_t lane = threadIdx.x & 63;
+    if (c >= n_chunks)
+        return;
+    uint64_t at = offsets[c];
+    for (uint32_t j = 0; j < kStates; ++j) {
+        const uint32_t id = c * kStates + j;
+        const uint32_t len = lens[id];
+        const uint16_t *from = slots + static_cast<uint64_t>(id) * kRunCap + (kRunCap - len);
+        for (uint32_t i = lane; i < len; i += 64)
+            words[at + i] = from[i];
+        at += len;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Kernel 6: fused decoder (Alg. 1 "decompression" + "merge"; Sec. 2.2 Eq. (3)).
+//
+// A workgroup owns 32 neighbouring chunks.  It builds the 4096-entry slot table
+// (symbol | f << 8 | (slot - cum) << 20) in LDS, copies the chunks' word runs -- one
+// contiguous piece of the blob -- into LDS with 128-bit loads, and then every lane walks one
+// state: 32 turns of 8 symbols; per symbol one table read, one multiply-add, one compare,
+// and a lane-private refill.  The 8 decoded exponents are merged with the 8 sign|mantissa
+// fields and leave as one 128-bit store.
+// ------------------------------------------------------------------------------------------
+template <int KB>
+__device__ inline uint64_t load_fields(const uint8_t *__restrict__ sm, uint64_t first_elem)
+{
+    // the (KB+1)*8 field bits of 8 neighbouring elements
+    if constexpr (KB == 7) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(sm + first_elem);
+        return static_cast<uint64_t>(v.x) | (static_cast<uint64_t>(v.y) << 32);
+    } else if constexpr (KB == 3) {
+        return *reinterpret_cast<const uint32_t *>(sm + first_elem / 2);
+    } else if constexpr (KB == 1) {
+        return *reinterpret_cast<const uint16_t *>(sm + first_elem / 4);
+    } else {
+        return sm[first_elem / 8];
+    }
+}
+
+template <int KB>
+__device__ inline uint32_t merge_pair(uint64_t fields, int pair, uint32_t e_lo, uint32_t e_hi)
+{
+    // two bf16 words: sign << 15 | exponent << 7 | kept mantissa bits << (7 - KB)
+    constexpr uint32_t width = KB + 1;
+    constexpr uint32_t fmask = (1u << width) - 1u;
+    const uint32_t f_lo = static_cast<uint32_t>(fields >> ((2 * pair) * width)) & fmask;
+    const uint32_t f_hi = static_cast<uint32_t>(fields >> ((2 * pair + 1) * width)) & fmask;
+    const uint32_t lo = ((f_lo >> KB) << 15) | (e_lo << 7) | ((f_lo & ((1u << KB) - 1u)) << (7 - KB));
+    const uint32_t hi = ((f_hi >> KB) << 15) | (e_hi << 7) | ((f_hi & ((1u << KB) - 1u)) << (7 - KB));
+    return lo | (hi << 16);
+}
+
+// One rANS decoding step of a lane's state.  WordSrc::peek(at) returns the 16-bit word at byte
+// position `at` of the lane's word source.
+template <class WordSrc>
+__device__ __forceinline__ uint32_t rans_get(const uint32_t *__restrict__ lut, uint32_t &x, uint32_t &wp,
+                                             uint32_t &next, const WordSrc &src)
+{
+    const uint32_t e = lut[x & (kM - 1)];
+    x = __umul24((e >> 8) & 0xFFFu, x >> kProbBits) + (e >> 20);
+    if (x < kRansL) {
+        x = (x << 16) | next;
+        wp += 2;
+    }
+    next = src.peek(wp);
+    return e & 0xFFu;
+}
+
+struct LdsWords {
+    const uint8_t *base;  // LDS copy of the workgroup's runs
+    __device__ __forceinline__ uint32_t peek(uint32_t at) const { return *reinterpret_cast<const uint16_t *>(base + at); }
+};
+struct GlobalWords {
+    const uint8_t *base;  // the lane's run inside the blob
+    __device__ __forceinline__ uint32_t peek(uint32_t at) const { return *reinterpret_cast<const uint16_t *>(base + at); }
+};
+struct NoWords {
+    __device__ __forceinline__ uint32_t peek(uint32_t) const { return 0; }
+};
+
+// Walks one state over its part of chunk [base, base + m) and writes the merged bf16 words.
+// LONE: the tensor has a single exponent value (f = 4096): the state never moves and there are
+// no words.  Returns through x / wp what the well-formedness check needs.
+template <int KB, bool LONE, class WordSrc>
+__device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
+                                           uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
+                                           uint16_t *__restrict__ out, uint64_t base, uint32_t m, uint32_t j)
+{
+    uint32_t next = LONE ? 0u : src.peek(wp);
+    if (m == kChunk) {
+        uint4 *out4 = reinterpret_cast<uint4 *>(out + base) + j;
+        for (uint32_t q = 0; q < kTurns; ++q) {
+            const uint64_t fields = load_fields<KB>(sm, base + q * kTurn + j * kRun);
+            uint32_t e[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                e[t] = LONE ? lone : rans_get(lut, x, wp, next, src);
+            uint4 o;
+            o.x = merge_pair<KB>(fields, 0, e[0], e[1]);
+            o.y = merge_pair<KB>(fields, 1, e[2], e[3]);
+            o.z = merge_pair<KB>(fields, 2, e[4], e[5]);
+            o.w = merge_pair<KB>(fields, 3, e[6], e[7]);
+            out4[q * kStates] = o;
+        }
+    } else {
+        // ragged last chunk: element by element
+        constexpr uint32_t width = KB + 1, per_byte = 8 / width;
+        for (uint32_t q = 0; q < kTurns; ++q) {
+            for (uint32_t t = 0; t < kRun; ++t) {
+                const uint32_t i = q * kTurn + j * kRun + t;
+                if (i >= m)
+                    continue;
+                const uint32_t sym = LONE ? lone : rans_get(lut, x, wp, next, src);
+                const uint64_t g = base + i;
+                const uint32_t field = (sm[g / per_byte] >> ((g % per_byte) * width)) & ((1u << width) - 1u);
+                out[g] = static_cast<uint16_t>(((field >> KB) << 15) | (sym << 7) |
+                                               ((field & ((1u << KB) - 1u)) << (7 - KB)));
+            }
+        }
+    }
+}
+
+template <int KB>
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(const TableBlock *__restrict__ tb,
+                                                            const uint32_t *__restrict__ offsets,
+                                                            const uint32_t *__restrict__ states,
+                                                            const uint8_t *__restrict__ lens,
+                                                            const uint16_t *__restrict__ words,
+                                                            const uint8_t *__restrict__ sm,
+                                                            uint16_t *__restrict__ out, uint64_t n,
+                                                            uint32_t n_chunks, uint32_t *__restrict__ status)
+{
+    __shared__ uint32_t lut[kM];
+    __shared__ __align__(16) uint8_t stage[kStageBytes];
+    __shared__ uint16_t cum[260];
+    __shared__ uint32_t lone_symbol;  // 256 = none; else the only symbol of the tensor (f = 4096)
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t c0 = blockIdx.x * kDecChunksPerWg;
+    const uint32_t c1 = c0 + kDecChunksPerWg < n_chunks ? c0 + kDecChunksPerWg : n_chunks;
+
+    // ---- stage the word runs of chunks [c0, c1): one contiguous piece of the blob
+    const uint64_t byte0 = static_cast<uint64_t>(offsets[c0]) * 2;
+    const uint64_t byte1 = static_cast<uint64_t>(offsets[c1]) * 2;
+    const uint64_t aligned0 = byte0 & ~static_cast<uint64_t>(15);
+    const uint64_t stage_len = byte1 - aligned0;
+    const bool staged = stage_len + 16 <= kStageBytes;  // room for the one-word look-ahead
+    if (staged) {
+        const uint4 *from = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(words) + aligned0);
+        uint4 *to = reinterpret_cast<uint4 *>(stage);
+        for (uint32_t i = tid; i * 16 < stage_len; i += kDecThreads)
+            to[i] = from[i];
+    }
+
+    // ---- slot table: entry = symbol | f << 8 | (slot - cum[symbol]) << 20
+    if (tid < 257)
+        cum[tid] = tb->cum[tid];
+    if (tid == 0)
+        lone_symbol = 256;
+    __syncthreads();
+    {
+        constexpr uint32_t per_thread = kM / kDecThreads;
+        const uint32_t first = tid * per_thread;
+        uint32_t lo = 0, hi = 255;  // smallest s with cum[s + 1] > first
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (cum[mid + 1] > first)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        uint32_t s = lo;
+        for (uint32_t t = 0; t < per_thread; ++t) {
+            const uint32_t slot = first + t;
+            while (s < 255 && cum[s + 1] <= slot)
+                ++s;
+            const uint32_t f = static_cast<uint32_t>(cum[s + 1]) - cum[s];
+            lut[slot] = s | ((f & 0xFFFu) << 8) | ((slot - cum[s]) << 20);
+            if (f == kM && slot == 0)
+                lone_symbol = s;
+        }
+    }
+    __syncthreads();
+
+    // ---- one lane, one state
+    const uint32_t c = c0 + tid / kStates;
+    const uint32_t j = tid % kStates;
+    if (c >= n_chunks)
+        return;
+    const uint32_t id = c * kStates + j;
+    uint32_t x = states[id];
+    const uint32_t len = lens[id];
+    // start of this state's run: chunk offset + lengths of the states before it (16-lane prefix)
+    uint32_t before = len;
+#pragma unroll
+    for (uint32_t d = 1; d < kStates; d <<= 1) {
+        const uint32_t o = __shfl_up(before, d, kStates);
+        if (j >= d)
+            before += o;
+    }
+    before -= len;
+    const uint64_t run_byte = (static_cast<uint64_t>(offsets[c]) + before) * 2;
+    const uint64_t base = static_cast<uint64_t>(c) * kChunk;
+    const uint32_t m = (n - base) < kChunk ? static_cast<uint32_t>(n - base) : kChunk;
+    const uint32_t lone = lone_symbol;
+
+    uint32_t wp = 0, wp_begin = 0;
+    if (lone < 256) {
+        walk_state<KB, true>(lut, NoWords{}, lone, x, wp, sm, out, base, m, j);
+    } else if (staged) {
+        wp = wp_begin = static_cast<uint32_t>(run_byte - aligned0);
+        walk_state<KB, false>(lut, LdsWords{stage}, 0u, x, wp, sm, out, base, m, j);
+    } else {
+        // the runs of these 32 chunks did not fit the LDS window (more than ~4 bits per symbol):
+        // read the words straight from the blob
+        walk_state<KB, false>(lut, GlobalWords{reinterpret_cast<const uint8_t *>(words) + run_byte}, 0u, x, wp, sm,
+                              out, base, m, j);
+    }
+    // a well-formed run is consumed exactly and leaves the state where the encoder started
+    if (x != kRansL || wp - wp_begin != 2 * len)
+        atomicOr(status, 1u);
+}
+
+// ------------------------------------------------------------------------------------------
+// Host side
+// ------------------------------------------------------------------------------------------
+struct Layout {
+    uint64_t offsets, states, lens, sm, total;  // byte positions inside the fixed allocation
+};
+
+Layout fixed_layout(uint64_t n, int k)
+{
+    const uint64_t nc = chunks_of(n);
+    Layout l;
+    l.offsets = sizeof(TableBlock);
+    l.states = l.offsets + pad_to((nc + 2) * 4, 256);
+    l.lens = l.states + pad_to(nc * kStates * 4, 256);
+    l.sm = l.lens + pad_to(nc * kStates, 256);
+    l.total = l.sm + pad_to(signmant_bytes(n, k), 256) + 256;
+    return l;
+}
+
+struct Container {
+    uint64_t freq, offsets, states, lens, words, sm, total;  // byte positions in the flat container
+};
+
+Container container_layout(uint64_t n, int k, uint64_t total_words)
+{
+    const uint64_t nc = chunks_of(n);
+    Container c;
+    c.freq = kHeaderBytes;
+    c.offsets = c.freq + 512;
+    c.states = c.offsets + pad_to((nc + 1) * 4, 16);
+    c.lens = c.states + nc * kStates * 4;
+    c.words = c.lens + nc * kStates;
+    c.sm = c.words + pad_to(total_words * 2, 16);
+    c.total = c.sm + pad_to(signmant_bytes(n, k), 16);
+    return c;
+}
+
+}  // namespace
+
+struct neuzip_blob {
+    uint32_t magic;
+    int device;
+    uint64_t n;
+    int k;
+    uint32_t n_chunks;
+    uint64_t total_words;
+    uint8_t *fixed;
+    uint64_t fixed_bytes;
+    uint8_t *words;
+    uint64_t words_bytes;  // capacity of the word allocation
+    Layout at;
+    bool have_counts;
+    uint32_t h_counts[256];
+    uint16_t h_freq[256];
+};
+
+namespace {
+
+constexpr uint32_t kBlobMagic = 0x424C5A4Eu;
+
+inline TableBlock *table_of(const neuzip_blob *b) { return reinterpret_cast<TableBlock *>(b->fixed); }
+inline uint32_t *offsets_of(const neuzip_blob *b) { return reinterpret_cast<uint32_t *>(b->fixed + b->at.offsets); }
+inline uint32_t *states_of(const neuzip_blob *b) { return reinterpret_cast<uint32_t *>(b->fixed + b->at.states); }
+inline uint8_t *lens_of(const neuzip_blob *b) { return b->fixed + b->at.lens; }
+inline uint8_t *sm_of(const neuzip_blob *b) { return b->fixed + b->at.sm; }
+inline bool is_blob(const neuzip_blob *b) { return b && b->magic == kBlobMagic; }
+
+// Per-process compress workspace (encoder constants, run slots, pinned staging for the size read).
+struct Workspace {
+    int device = -1;
+    EncSym *enc = nullptr;
+    uint16_t *slots = nullptr;
+    uint64_t slots_bytes = 0;
+    uint32_t *pinned = nullptr;  // [0..1] total words, [2..257] counts, [258..385] freq
+    hipEvent_t idle = nullptr;   // recorded after the last kernel that reads the slots
+};
+std::mutex g_ws_mutex;
+Workspace g_ws;
+
+int release_workspace_locked()
+{
+    int rc = NEUZIP_OK;
+    if (g_ws.device >= 0) {
+        int cur = 0;
+        if (!hip_ok(hipGetDevice(&cur)))
+            return NEUZIP_EHIP;
+        if (!hip_ok(hipSetDevice(g_ws.device)))
+            return NEUZIP_EHIP;
+        if (g_ws.idle) {
+            if (!hip_ok(hipEventSynchronize(g_ws.idle)))
+                rc = NEUZIP_EHIP;
+            hipEventDestroy(g_ws.idle);
+        }
+        if (g_ws.enc)
+            hipFree(g_ws.enc);
+        if (g_ws.slots)
+            hipFree(g_ws.slots);
+        if (g_ws.pinned)
+            hipHostFree(g_ws.pinned);
+        hipSetDevice(cur);
+    }
+    g_ws = Workspace();
+    return rc;
+}
+
+int ensure_workspace(int device, uint64_t slots_bytes, hipStream_t stream)
+{
+    if (g_ws.device != device) {
+        const int rc = release_workspace_locked();
+        if (rc != NEUZIP_OK)
+            return rc;
+        g_ws.device = device;
+        NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.enc), 256 * sizeof(EncSym)));
+        NZ_HIP(hipHostMalloc(reinterpret_cast<void **>(&g_ws.pinned), 512 * sizeof(uint32_t), hipHostMallocDefault));
+        NZ_HIP(hipEventCreateWithFlags(&g_ws.idle, hipEventDisableTiming));
+        NZ_HIP(hipEventRecord(g_ws.idle, stream));
+    }
+    // the previous user of the slots may still be running on another stream
+    NZ_HIP(hipStreamWaitEvent(stream, g_ws.idle, 0));
+    if (g_ws.slots_bytes < slots_bytes) {
+        NZ_HIP(hipEventSynchronize(g_ws.idle));
+        if (g_ws.slots) {
+            NZ_HIP(hipFree(g_ws.slots));
+            g_ws.slots = nullptr;
+            g_ws.slots_bytes = 0;
+        }
+        if (hipMalloc(reinterpret_cast<void **>(&g_ws.slots), slots_bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return NEUZIP_ENOMEM;
+        }
+        g_ws.slots_bytes = slots_bytes;
+    }
+    return NEUZIP_OK;
+}
+
+int alloc_blob(uint64_t n, int k, neuzip_blob **out)
+{
+    neuzip_blob *b = new (std::nothrow) neuzip_blob();
+    if (!b)
+        return NEUZIP_ENOMEM;
+    std::memset(b, 0, sizeof(*b));
+    b->magic = kBlobMagic;
+    b->n = n;
+    b->k = k;
+    b->n_chunks = chunks_of(n);
+    b->at = fixed_layout(n, k);
+    if (!hip_ok(hipGetDevice(&b->device))) {
+        delete b;
+        return NEUZIP_EHIP;
+    }
+    if (hipMalloc(reinterpret_cast<void **>(&b->fixed), b->at.total) != hipSuccess) {
+        (void)hipGetLastError();
+        delete b;
+        return NEUZIP_ENOMEM;
+    }
+    b->fixed_bytes = b->at.total;
+    *out = b;
+    return NEUZIP_OK;
+}
+
+int reserve_words(neuzip_blob *b, uint64_t total_words)
+{
+    // slack behind the last word: the decoder copies whole 16-byte pieces, looks one word ahead,
+    // and a state fed a damaged stream may walk up to 256 words past the start of its run
+    const uint64_t need = pad_to(total_words * 2, 256) + 1024;
+    if (b->words_bytes < need) {
+        if (b->words) {
+            NZ_HIP(hipFree(b->words));
+            b->words = nullptr;
+            b->words_bytes = 0;
+        }
+        if (hipMalloc(reinterpret_cast<void **>(&b->words), need) != hipSuccess) {
+            (void)hipGetLastError();
+            return NEUZIP_ENOMEM;
+        }
+        b->words_bytes = need;
+    }
+    return NEUZIP_OK;
+}
+
+template <int KB>
+int launch_hist(const void *d_src, uint64_t n, neuzip_blob *b, hipStream_t stream)
+{
+    const uint64_t n_vec = n / 8;
+    uint64_t groups = (n_vec + kHistThreads - 1) / kHistThreads;
+    if (groups < 1)
+        groups = 1;
+    if (groups > 2048)
+        groups = 2048;
+    hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(static_cast<uint32_t>(groups)), dim3(kHistThreads), 0, stream,
+                       static_cast<const uint16_t *>(d_src), n, sm_of(b), table_of(b)->counts);
+    return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
+}
+
+template <int KB>
+int launch_decode(const neuzip_blob *b, void *d_dst, hipStream_t stream)
+{
+    const uint32_t groups = (b->n_chunks + kDecChunksPerWg - 1) / kDecChunksPerWg;
+    hipLaunchKernelGGL(decode_kernel<KB>, dim3(groups), dim3(kDecThreads), 0, stream, table_of(b), offsets_of(b),
+                       states_of(b), lens_of(b), reinterpret_cast<const uint16_t *>(b->words), sm_of(b),
+                       static_cast<uint16_t *>(d_dst), b->n, b->n_chunks, table_of(b)->status);
+    return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
+}
+
+int decode_dispatch(const neuzip_blob *b, void *d_dst, hipStream_t stream)
+{
+    if (b->n == 0)
+        return NEUZIP_OK;
+    switch (b->k) {
+    case 7: return launch_decode<7>(b, d_dst, stream);
+    case 3: return launch_decode<3>(b, d_dst, stream);
+    case 1: return launch_decode<1>(b, d_dst, stream);
+    default: return launch_decode<0>(b, d_dst, stream);
+    }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------
+extern "C" {
+
+int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa_bits, void *hip_stream,
+                    neuzip_blob **blob)
+{
+    if (!blob || dtype != NEUZIP_BF16 || !valid_k(mantissa_bits))
+        return NEUZIP_EINVAL;
+    if (n_elems > 0 && (!d_src || (reinterpret_cast<uintptr_t>(d_src) & 15u)))
+        return NEUZIP_EINVAL;
+    if (n_elems >= (1ull << 32))
+        return NEUZIP_EUNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    neuzip_blob *b = *blob;
+    const bool fresh = (b == nullptr);
+    if (!fresh && (!is_blob(b) || b->n != n_elems || b->k != mantissa_bits))
+        return NEUZIP_EINVAL;
+    if (fresh) {
+        const int rc = alloc_blob(n_elems, mantissa_bits, &b);
+        if (rc != NEUZIP_OK)
+            return rc;
+    }
+    auto fail = [&](int rc) {
+        if (fresh)
+            neuzip_free(b);
+        return rc;
+    };
+
+    const uint32_t nc = b->n_chunks;
+    // table block starts from zero (counts, status); a fill kernel, not a memset node, so the
+    // call stays safe to record into a graph
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((sizeof(TableBlock) / 4 + 255) / 256), dim3(256), 0, stream,
+                       reinterpret_cast<uint32_t *>(b->fixed), 0u, static_cast<uint32_t>(sizeof(TableBlock) / 4));
+    if (!hip_ok(hipGetLastError()))
+        return fail(NEUZIP_EHIP);
+    b->have_counts = false;
+    b->total_words = 0;
+
+    if (n_elems == 0) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, stream, offsets_of(b), 0u, 2u);
+        if (!hip_ok(hipGetLastError()) || !hip_ok(hipStreamSynchronize(stream)))
+            return fail(NEUZIP_EHIP);
+        std::memset(b->h_counts, 0, sizeof(b->h_counts));
+        std::memset(b->h_freq, 0, sizeof(b->h_freq));
+        b->have_counts = true;
+        *blob = b;
+        return NEUZIP_OK;
+    }
+
+    std::lock_guard<std::mutex> guard(g_ws_mutex);
+    int rc = ensure_workspace(b->device, static_cast<uint64_t>(nc) * kStates * kRunCap * 2, stream);
+    if (rc != NEUZIP_OK)
+        return fail(rc);
+
+    switch (mantissa_bits) {
+    case 7: rc = launch_hist<7>(d_src, n_elems, b, stream); break;
+    case 3: rc = launch_hist<3>(d_src, n_elems, b, stream); break;
+    case 1: rc = launch_hist<1>(d_src, n_elems, b, stream); break;
+    default: rc = launch_hist<0>(d_src, n_elems, b, stream); break;
+    }
+    if (rc != NEUZIP_OK)
+        return fail(rc);
+
+    hipLaunchKernelGGL(table_kernel, dim3(1), dim3(256), 0, stream, table_of(b), g_ws.enc);
+    hipLaunchKernelGGL(encode_kernel, dim3((nc * kStates + kEncThreads - 1) / kEncThreads), dim3(kEncThreads), 0,
+                       stream, static_cast<const uint16_t *>(d_src), n_elems, nc, g_ws.enc, states_of(b), lens_of(b),
+                       g_ws.slots);
+    hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kScanThreads), 0, stream, lens_of(b), nc, offsets_of(b));
+    if (!hip_ok(hipGetLastError()))
+        return fail(NEUZIP_EHIP);
+
+    // the stream length is data dependent: read it (and the statistics) back once
+    if (!hip_ok(hipMemcpyAsync(g_ws.pinned, offsets_of(b) + nc, 8, hipMemcpyDeviceToHost, stream)) ||
+        !hip_ok(hipMemcpyAsync(g_ws.pinned + 2, table_of(b)->counts, 1024, hipMemcpyDeviceToHost, stream)) ||
+        !hip_ok(hipMemcpyAsync(g_ws.pinned + 258, table_of(b)->freq, 512, hipMemcpyDeviceToHost, stream)) ||
+        !hip_ok(hipStreamSynchronize(stream)))
+        return fail(NEUZIP_EHIP);
+    if (g_ws.pinned[1] != 0)
+        return fail(NEUZIP_EUNSUPPORTED);  // more than 2^32 words
+    const uint64_t total_words = g_ws.pinned[0];
+    std::memcpy(b->h_counts, g_ws.pinned + 2, 1024);
+    std::memcpy(b->h_freq, g_ws.pinned + 258, 512);
+    b->have_counts = true;
+
+    rc = reserve_words(b, total_words);
+    if (rc != NEUZIP_OK)
+        return fail(rc);
+    b->total_words = total_words;
+    hipLaunchKernelGGL(compact_kernel, dim3((nc + kCompactThreads / 64 - 1) / (kCompactThreads / 64)),
+                       dim3(kCompactThreads), 0, stream, g_ws.slots, lens_of(b), offsets_of(b), nc,
+                       reinterpret_cast<uint16_t *>(b->words));
+    if (!hip_ok(hipGetLastError()) || !hip_ok(hipEventRecord(g_ws.idle, stream)))
+        return fail(NEUZIP_EHIP);
+    *blob = b;
+    return NEUZIP_OK;
+}
+
+int neuzip_decompress(const neuzip_blob *blob, void *d_dst, uint64_t n_elems, int dtype, void *hip_stream)
+{
+    if (!is_blob(blob) || dtype != NEUZIP_BF16 || blob->n != n_elems)
+        return NEUZIP_EINVAL;
+    if (n_elems > 0 && (!d_dst || (reinterpret_cast<uintptr_t>(d_dst) & 15u)))
+        return NEUZIP_EINVAL;
+    return decode_dispatch(blob, d_dst, static_cast<hipStream_t>(hip_stream));
+}
+
+int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, void *d_scratch,
+                               uint64_t scratch_elems, void *hip_stream)
+{
+    if (count > 0 && !blobs)
+        return NEUZIP_EINVAL;
+    if (reinterpret_cast<uintptr_t>(d_scratch) & 15u)
+        return NEUZIP_EINVAL;
+    for (uint32_t i = 0; i < count; ++i) {
+        if (!is_blob(blobs[i]) || blobs[i]->n > scratch_elems || (blobs[i]->n > 0 && !d_scratch))
+            return NEUZIP_EINVAL;
+    }
+    for (uint32_t i = 0; i < count; ++i) {
+        const int rc = decode_dispatch(blobs[i], d_scratch, static_cast<hipStream_t>(hip_stream));
+        if (rc != NEUZIP_OK)
+            return rc;
+    }
+    return NEUZIP_OK;
+}
+
+void neuzip_free(neuzip_blob *blob)
+{
+    if (!is_blob(blob))
+        return;
+    int cur = 0;
+    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+    if (have_cur && cur != blob->device)
+        hipSetDevice(blob->device);
+    if (blob->fixed)
+        hipFree(blob->fixed);
+    if (blob->words)
+        hipFree(blob->words);
+    if (have_cur && cur != blob->device)
+        hipSetDevice(cur);
+    blob->magic = 0;
+    delete blob;
+}
+
+uint64_t neuzip_compressed_bytes(const neuzip_blob *blob)
+{
+    if (!is_blob(blob))
+        return 0;
+    return container_layout(blob->n, blob->k, blob->total_words).total;
+}
+
+uint64_t neuzip_device_bytes(const neuzip_blob *blob)
+{
+    if (!is_blob(blob))
+        return 0;
+    return blob->fixed_bytes + blob->words_bytes;
+}
+
+uint64_t neuzip_elems(const neuzip_blob *blob) { return is_blob(blob) ? blob->n : 0; }
+int neuzip_mantissa_bits(const neuzip_blob *blob) { return is_blob(blob) ? blob->k : -1; }
+
+int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *written, void *hip_stream)
+{
+    if (!is_blob(blob))
+        return NEUZIP_EINVAL;
+    const Container lay = container_layout(blob->n, blob->k, blob->total_words);
+    if (written)
+        *written = lay.total;
+    if (!h_buf)
+        return written ? NEUZIP_OK : NEUZIP_EINVAL;
+    if (cap < lay.total)
+        return NEUZIP_ENOMEM;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    uint8_t *p = static_cast<uint8_t *>(h_buf);
+    std::memset(p, 0, lay.total);
+    auto put32 = [&](uint64_t at, uint32_t v) { std::memcpy(p + at, &v, 4); };
+    auto put64 = [&](uint64_t at, uint64_t v) { std::memcpy(p + at, &v, 8); };
+    put32(0, kMagic);
+    put32(4, 1);
+    put64(8, blob->n);
+    put32(16, static_cast<uint32_t>(blob->k));
+    put32(20, kProbBits);
+    put32(24, kChunk);
+    put32(28, kStates);
+    put32(32, kRun);
+    put32(36, blob->n_chunks);
+    put64(40, blob->total_words);
+    const uint64_t nc = blob->n_chunks;
+    NZ_HIP(hipMemcpyAsync(p + lay.freq, table_of(blob)->freq, 512, hipMemcpyDeviceToHost, stream));
+    NZ_HIP(hipMemcpyAsync(p + lay.offsets, offsets_of(blob), (nc + 1) * 4, hipMemcpyDeviceToHost, stream));
+    if (nc) {
+        NZ_HIP(hipMemcpyAsync(p + lay.states, states_of(blob), nc * kStates * 4, hipMemcpyDeviceToHost, stream));
+        NZ_HIP(hipMemcpyAsync(p + lay.lens, lens_of(blob), nc * kStates, hipMemcpyDeviceToHost, stream));
+    }
+    if (blob->total_words)
+        NZ_HIP(hipMemcpyAsync(p + lay.words, blob->words, blob->total_words * 2, hipMemcpyDeviceToHost, stream));
+    if (blob->n)
+        NZ_HIP(hipMemcpyAsync(p + lay.sm, sm_of(blob), signmant_bytes(blob->n, blob->k), hipMemcpyDeviceToHost,
+                              stream));
+    NZ_HIP(hipStreamSynchronize(stream));
+    return NEUZIP_OK;
+}
+
+int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob **blob)
+{
+    if (!h_buf || !blob)
+        return NEUZIP_EINVAL;
+    if (len < kHeaderBytes + 512)
+        return NEUZIP_ECORRUPT;
+    const uint8_t *p = static_cast<const uint8_t *>(h_buf);
+    auto get32 = [&](uint64_t at) { uint32_t v; std::memcpy(&v, p + at, 4); return v; };
+    auto get64 = [&](uint64_t at) { uint64_t v; std::memcpy(&v, p + at, 8); return v; };
+    if (get32(0) != kMagic || get32(4) != 1 || get32(20) != kProbBits || get32(24) != kChunk ||
+        get32(28) != kStates || get32(32) != kRun)
+        return NEUZIP_ECORRUPT;
+    const uint64_t n = get64(8);
+    const int k = static_cast<int>(get32(16));
+    const uint64_t total_words = get64(40);
+    if (!valid_k(k) || n >= (1ull << 32) || total_words >= (1ull << 32))
+        return NEUZIP_ECORRUPT;
+    const uint32_t nc = chunks_of(n);
+    if (get32(36) != nc)
+        return NEUZIP_ECORRUPT;
+    const Container lay = container_layout(n, k, total_words);
+    if (lay.total != len)
+        return NEUZIP_ECORRUPT;
+
+    // every section is checked here, on the host, so that the decoder's indexing holds
+    uint16_t freq[256];
+    uint16_t cum[264] = {0};
+    std::memcpy(freq, p + lay.freq, 512);
+    uint32_t sum = 0;
+    for (int s = 0; s < 256; ++s) {
+        cum[s] = static_cast<uint16_t>(sum);
+        sum += freq[s];
+        if (sum > kM)
+            return NEUZIP_ECORRUPT;
+    }
+    cum[256] = static_cast<uint16_t>(sum);
+    if (sum != (n ? kM : 0u))
+        return NEUZIP_ECORRUPT;
+    uint64_t run = 0;
+    for (uint32_t c = 0; c < nc; ++c) {
+        if (get32(lay.offsets + 4ull * c) != run)
+            return NEUZIP_ECORRUPT;
+        for (uint32_t j = 0; j < kStates; ++j) {
+            const uint32_t l = p[lay.lens + static_cast<uint64_t>(c) * kStates + j];
+            if (l > kRunCap)
+                return NEUZIP_ECORRUPT;
+            run += l;
+        }
+    }
+    if (get32(lay.offsets + 4ull * nc) != run || run != total_words)
+        return NEUZIP_ECORRUPT;
+
+    neuzip_blob *b = nullptr;
+    int rc = alloc_blob(n, k, &b);
+    if (rc != NEUZIP_OK)
+        return rc;
+    auto fail = [&](int code) {
+        neuzip_free(b);
+        return code;
+    };
+    rc = reserve_words(b, total_words);
+    if (rc != NEUZIP_OK)
+        return fail(rc);
+    b->total_words = total_words;
+    std::memcpy(b->h_freq, freq, 512);
+    b->have_counts = false;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    TableBlock tb;
+    std::memset(&tb, 0, sizeof(tb));
+    std::memcpy(tb.freq, freq, 512);
+    std::memcpy(tb.cum, cum, sizeof(tb.cum));
+    const uint32_t zeros[2] = {0, 0};
+    if (!hip_ok(hipMemcpyAsync(b->fixed, &tb, sizeof(tb), hipMemcpyHostToDevice, stream)) ||
+        !hip_ok(hipMemcpyAsync(offsets_of(b), p + lay.offsets, (nc + 1ull) * 4, hipMemcpyHostToDevice, stream)) ||
+        !hip_ok(hipMemcpyAsync(offsets_of(b) + nc + 1, zeros, 4, hipMemcpyHostToDevice, stream)))
+        return fail(NEUZIP_EHIP);
+    if (nc && (!hip_ok(hipMemcpyAsync(states_of(b), p + lay.states, nc * kStates * 4ull, hipMemcpyHostToDevice, stream)) ||
+               !hip_ok(hipMemcpyAsync(lens_of(b), p + lay.lens, nc * static_cast<uint64_t>(kStates), hipMemcpyHostToDevice, stream))))
+        return fail(NEUZIP_EHIP);
+    if (total_words && !hip_ok(hipMemcpyAsync(b->words, p + lay.words, total_words * 2, hipMemcpyHostToDevice, stream)))
+        return fail(NEUZIP_EHIP);
+    if (n && !hip_ok(hipMemcpyAsync(sm_of(b), p + lay.sm, signmant_bytes(n, k), hipMemcpyHostToDevice, stream)))
+        return fail(NEUZIP_EHIP);
+    if (!hip_ok(hipStreamSynchronize(stream)))  // tb and zeros live on this stack frame
+        return fail(NEUZIP_EHIP);
+    *blob = b;
+    return NEUZIP_OK;
+}
+
+int neuzip_histogram(const neuzip_blob *blob, uint32_t h_counts[256])
+{
+    if (!is_blob(blob) || !h_counts || !blob->have_counts)
+        return NEUZIP_EINVAL;
+    std::memcpy(h_counts, blob->h_counts, sizeof(blob->h_counts));
+    return NEUZIP_OK;
+}
+
+int neuzip_frequencies(const neuzip_blob *blob, uint16_t h_freq[256])
+{
+    if (!is_blob(blob) || !h_freq)
+        return NEUZIP_EINVAL;
+    std::memcpy(h_freq, blob->h_freq, sizeof(blob->h_freq));
+    return NEUZIP_OK;
+}
+
+int neuzip_check(const neuzip_blob *blob, void *hip_stream)
+{
+    if (!is_blob(blob))
+        return NEUZIP_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    uint32_t flag = 0;
+    NZ_HIP(hipMemcpyAsync(&flag, table_of(blob)->status, 4, hipMemcpyDeviceToHost, stream));
+    NZ_HIP(hipStreamSynchronize(stream));
+    if (flag) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, stream, table_of(blob)->status, 0u, 1u);
+        NZ_HIP(hipGetLastError());
+        NZ_HIP(hipStreamSynchronize(stream));
+        return NEUZIP_ECORRUPT;
+    }
+    return NEUZIP_OK;
+}
+
+int neuzip_release_workspace(void)
+{
+    std::lock_guard<std::mutex> guard(g_ws_mutex);
+    return release_workspace_locked();
+}
+
+const char *neuzip_strerror(int code)
+{
+    switch (code) {
+    case NEUZIP_OK: return "ok";
+    case NEUZIP_EINVAL: return "invalid argument";
+    case NEUZIP_ENOMEM: return "out of memory or buffer too small";
+    case NEUZIP_EHIP: return "HIP runtime error";
+    case NEUZIP_ECORRUPT: return "malformed container or stream";
+    case NEUZIP_EUNSUPPORTED: return "size not supported";
+    default: return "unknown error";
+    }
+}
+
+int neuzip_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

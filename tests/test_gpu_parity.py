@@ -1,0 +1,221 @@
+"""GPU parity: the HIP path against the CPU oracle, through the C ABI (-m gpu).
+
+Integer/byte work throughout, so the bar is bit-exact: decoded bf16 words equal the oracle's
+(0 ULP, lossy truncation included) and the exported container equals the oracle's byte for byte.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2410_20650_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+KS = [7, 3, 1, 0]
+
+
+@pytest.fixture(scope="module")
+def nz():
+    from paper_2410_20650_amd import binding
+    return binding
+
+
+def roundtrip_and_compare(nz, w: torch.Tensor, k: int, threads: int = 16):
+    """Compress on the GPU, compare container and decoded words with the oracle's."""
+    words = inputs.bits(w)
+    n = words.size
+    blob = nz.neuzip_compress(w, k)
+    got = nz.neuzip_export(blob)
+    want = O.compress(words, k, threads=threads)
+    assert got.size == want.size == blob.compressed_bytes
+    if not np.array_equal(got, want):
+        sec = O.sections(want)
+        bad = [name for name, (lo, hi) in sec.items() if not np.array_equal(got[lo:hi], want[lo:hi])]
+        raise AssertionError(f"container differs from the oracle's in sections {bad} (n={n}, k={k})")
+    out = torch.full_like(w, float("nan"))
+    nz.neuzip_decompress(blob, out)
+    nz.neuzip_check(blob)
+    expect = O.truncate(words, k)
+    assert np.array_equal(inputs.bits(out), expect), f"decoded words differ (n={n}, k={k})"
+    # the oracle reads the GPU's container, the GPU reads the oracle's
+    assert np.array_equal(O.decompress(got, n, threads=threads), expect)
+    theirs = nz.neuzip_import(want)
+    out2 = torch.zeros_like(w)
+    nz.neuzip_decompress(theirs, out2)
+    nz.neuzip_check(theirs)
+    assert np.array_equal(inputs.bits(out2), expect)
+    return blob
+
+
+def test_config1_gaussian_1024x1024(nz):
+    w = inputs.gaussian_bf16((1024, 1024), inputs.seed_for(1), device=DEV)
+    blob = roundtrip_and_compare(nz, w, 7)
+    words = inputs.bits(w)
+    cnt = O.histogram(words)
+    assert np.array_equal(nz.neuzip_histogram(blob).astype(np.uint64), cnt)
+    assert np.array_equal(nz.neuzip_frequencies(blob), O.quantise(cnt))
+    bits_per_weight = 8 * blob.compressed_bytes / words.size
+    assert bits_per_weight <= 1.02 * (O.entropy(cnt) + 8)
+    assert blob.device_bytes < 1.01 * blob.compressed_bytes + 8192
+
+
+@pytest.mark.parametrize("k", KS)
+@pytest.mark.parametrize("n", [1, 7, 8, 9, 127, 128, 129, 4095, 4096, 4097, 3 * 4096 + 1001,
+                               32 * 4096, 33 * 4096 + 5, 1_000_003])
+def test_ragged_sizes(nz, n, k):
+    w = inputs.gaussian_bf16(n, 7000 + n, device=DEV)
+    roundtrip_and_compare(nz, w, k)
+
+
+@pytest.mark.parametrize("k", KS)
+def test_every_bf16_pattern(nz, k):
+    w = inputs.all_patterns_bf16(device=DEV)
+    roundtrip_and_compare(nz, w, k)
+    perm = torch.randperm(65536, generator=torch.Generator().manual_seed(k)).to(DEV)
+    roundtrip_and_compare(nz, w[perm].contiguous(), k)
+
+
+@pytest.mark.parametrize("k", KS)
+def test_heavy_tailed(nz, k):
+    w = inputs.student_t4_bf16(700_001, inputs.seed_for(4), device=DEV)
+    roundtrip_and_compare(nz, w, k)
+
+
+@pytest.mark.parametrize("n", [5, 4096, 40_000, 300_000])
+def test_uniform_exponents_take_the_unstaged_path(nz, n):
+    # 8 bits per symbol: the word runs of 32 chunks exceed the LDS window
+    w = inputs.random_bits_bf16(n, 99 + n, device=DEV)
+    roundtrip_and_compare(nz, w, 7)
+    roundtrip_and_compare(nz, w, 0)
+
+
+@pytest.mark.parametrize("n", [1, 100, 4096, 200_000 + 3])
+def test_single_exponent_tensor(nz, n):
+    w = inputs.constant_bf16(n, 0.75, device=DEV)
+    blob = roundtrip_and_compare(nz, w, 7)
+    assert nz.neuzip_frequencies(blob).max() == 4096
+    # same exponent, varying sign and mantissa
+    g = torch.Generator(device=DEV).manual_seed(n)
+    v = (torch.rand(n, generator=g, device=DEV) + 1.0) * (torch.randint(0, 2, (n,), generator=g, device=DEV) * 2 - 1)
+    roundtrip_and_compare(nz, v.to(torch.bfloat16), 3)
+
+
+def test_rare_symbols_and_long_runs(nz):
+    # one dominant exponent and 200 rare ones: frequencies of 1, 12-bit codes, runs near the 192-word cap
+    n = 64 * 4096
+    g = torch.Generator(device=DEV).manual_seed(5)
+    expo = torch.full((n,), 120, dtype=torch.int32, device=DEV)
+    rare = torch.randint(0, n, (600,), generator=g, device=DEV)
+    expo[rare] = torch.randint(1, 201, (600,), generator=g, device=DEV, dtype=torch.int32)
+    expo[4096 * 3: 4096 * 4] = torch.arange(4096, device=DEV, dtype=torch.int32) % 200 + 1   # a chunk of rare symbols only
+    mant = torch.randint(0, 128, (n,), generator=g, device=DEV, dtype=torch.int32)
+    sign = torch.randint(0, 2, (n,), generator=g, device=DEV, dtype=torch.int32)
+    u = (sign << 15) | (expo << 7) | mant
+    w = (u - 65536 * (u >= 32768)).to(torch.int16).view(torch.bfloat16)
+    roundtrip_and_compare(nz, w, 7)
+    roundtrip_and_compare(nz, w, 1)
+
+
+def test_empty_tensor(nz):
+    w = torch.empty(0, dtype=torch.bfloat16, device=DEV)
+    blob = nz.neuzip_compress(w, 7)
+    got = nz.neuzip_export(blob)
+    assert np.array_equal(got, O.compress(np.zeros(0, np.uint16), 7))
+    nz.neuzip_decompress(blob, w)
+    assert nz.neuzip_import(got).elems == 0
+
+
+def test_blob_reuse_and_recompression(nz):
+    w = inputs.gaussian_bf16(500_000, 31, device=DEV)
+    blob = nz.neuzip_compress(w, 7)
+    for step in range(3):
+        w = inputs.synthetic_update(w, 40 + step)
+        same = nz.neuzip_compress(w, 7, blob=blob)
+        assert same is blob
+        assert np.array_equal(nz.neuzip_export(blob), O.compress(inputs.bits(w), 7, threads=8))
+        out = torch.empty_like(w)
+        nz.neuzip_decompress(blob, out)
+        assert torch.equal(out.view(torch.int16), w.view(torch.int16))
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_compress(w[:1000].contiguous(), 7, blob=blob)      # different size
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_compress(w, 3, blob=blob)                         # different precision
+
+
+def test_forward_schedule_into_one_scratch(nz):
+    # Alg. 1 forward loop at small scale: every layer goes through the same temporary buffer
+    shapes = [(256, 512), (64, 512), (64, 512), (256, 512), (896, 256), (896, 256), (256, 896)]
+    tensors = [inputs.gaussian_bf16(s, inputs.seed_for(3, i), device=DEV) for i, s in enumerate(shapes)]
+    blobs = [nz.neuzip_compress(t, 7) for t in tensors]
+    scratch = torch.zeros(max(t.numel() for t in tensors), dtype=torch.bfloat16, device=DEV)
+    # one call runs the whole sequence; what is left in the scratch is the last layer
+    nz.neuzip_decompress_sequence(blobs, scratch)
+    assert torch.equal(scratch[: tensors[-1].numel()].view(torch.int16), tensors[-1].reshape(-1).view(torch.int16))
+    # layer by layer with a consumer in between sees every layer intact
+    for t, b in zip(tensors, blobs):
+        nz.neuzip_decompress_sequence([b], scratch)
+        assert torch.equal(scratch[: t.numel()].view(torch.int16), t.reshape(-1).view(torch.int16))
+    small = torch.zeros(1000, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_decompress_sequence(blobs, small)
+
+
+def test_other_stream(nz):
+    s = torch.cuda.Stream()
+    w = inputs.gaussian_bf16(300_000, 3, device=DEV)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        blob = nz.neuzip_compress(w, 7, stream=s)
+        out = torch.empty_like(w)
+        nz.neuzip_decompress(blob, out, stream=s)
+    s.synchronize()
+    assert torch.equal(out.view(torch.int16), w.view(torch.int16))
+
+
+def test_argument_errors(nz):
+    w = inputs.gaussian_bf16(10_000, 1, device=DEV)
+    blob = nz.neuzip_compress(w, 7)
+    with pytest.raises(nz.NeuzipError) as e:
+        nz.neuzip_compress(w, 5)
+    assert e.value.code == nz.EINVAL
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_decompress(blob, torch.empty(9_999, dtype=torch.bfloat16, device=DEV))
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_decompress(blob, torch.empty(10_008, dtype=torch.bfloat16, device=DEV)[1:10_001])  # misaligned
+    with pytest.raises(TypeError):
+        nz.neuzip_compress(w.float(), 7)
+
+
+def test_import_rejects_malformed_containers(nz):
+    w = inputs.bits(inputs.gaussian_bf16(50_000, 5))
+    good = O.compress(w, 7)
+    sec = O.sections(good)
+    for name, delta in (("header", 0), ("freq", 2), ("offsets", 4), ("lens", 3)):
+        bad = good.copy()
+        bad[sec[name][0] + delta] ^= 0x10
+        with pytest.raises(nz.NeuzipError) as e:
+            nz.neuzip_import(bad)
+        assert e.value.code == nz.ECORRUPT
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_import(good[:-16])
+
+
+def test_damaged_words_are_reported_by_check(nz):
+    # the container is structurally valid, only coded bits are flipped: the decoder stays in bounds,
+    # and a state that does not come back to its start raises the flag
+    w = inputs.bits(inputs.gaussian_bf16(200_000, 6))
+    good = O.compress(w, 7)
+    lo, hi = O.sections(good)["words"]
+    bad = good.copy()
+    rng = np.random.default_rng(2)
+    for pos in rng.integers(lo, hi - 16, 50):
+        bad[pos] ^= 0x5A
+    blob = nz.neuzip_import(bad)
+    out = torch.empty(w.size, dtype=torch.bfloat16, device=DEV)
+    nz.neuzip_decompress(blob, out)
+    with pytest.raises(nz.NeuzipError) as e:
+        nz.neuzip_check(blob)
+    assert e.value.code == nz.ECORRUPT
+    nz.neuzip_check(blob)  # flag is cleared by the report
