@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the NeuZip hot path on one MI355X.
+
+Workload (config 2 of the baseline): one Llama-style MLP weight, bf16 4096 x 14336,
+i.i.d. N(0, 0.02^2), lossless; compressed once, then decompressed K times by the fused
+decode kernel into one bf16 scratch buffer.  A "step" is one such decompression: it is
+what Alg. 1 runs per layer in every forward and backward pass.  The reported value is
+GB/s of bf16 output (2 bytes x elements / time) with everything resident in HBM.
+
+Prints ONE JSON line.  Extra keys: the roofline of the decode kernel, the CPU oracle
+timed on this machine's host cores, bits/weight against the exponent entropy, the
+compress rate, and (with --extended) the lossy 70B-shaped case and a Llama-3-8B-shaped
+per-layer sweep.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
+
+
+def parse_args():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=200)
+    p.add_argument("--warmup", type=int, default=20)
+    p.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    p.add_argument("--extended", action="store_true", help="also time config 4 (lossy) and a config-3 sweep")
+    p.add_argument("--layers", type=int, default=2, help="layers of the Llama-3-8B-shaped sweep with --extended")
+    return p.parse_args()
+
+
+def read_traffic_note():
+    """HBM bytes per decode launch measured with rocprofv3 --pmc (see profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", "decode_config2_traffic.txt")
+    try:
+        with open(path) as fh:
+            for line in fh:
+                if line.startswith("traffic_bytes_per_launch="):
+                    return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def timed_region(torch, stream, fn, steps):
+    """Runs fn() `steps` times on `stream`; returns (wall seconds, HIP-event milliseconds)."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    start.record(stream)
+    for _ in range(steps):
+        fn()
+    stop.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, start.elapsed_time(stop)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2410_20650_amd import binding as nz, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream()
+
+    # ---------------------------------------------------------------- workload: config 2
+    shape = inputs.MLP_8B
+    w = inputs.gaussian_bf16(shape, inputs.seed_for(2), device=dev)
+    n = w.numel()
+    blob = nz.neuzip_compress(w, 7)
+    scratch = torch.empty(n, dtype=torch.bfloat16, device=dev)
+
+    def step():
+        nz.neuzip_decompress(blob, scratch)
+
+    for _ in range(args.warmup):
+        step()
+    wall, event_ms = timed_region(torch, stream, step, args.steps)
+    nz.neuzip_check(blob)
+    assert torch.equal(scratch.view(torch.int16), w.reshape(-1).view(torch.int16)), "round trip is not bit exact"
+
+    ms_per_step = wall * 1e3 / args.steps
+    out_bytes = 2.0 * n
+    value = out_bytes / (wall / args.steps) / 1e9
+
+    # statistics of the tensor and of its container
+    cnt = nz.neuzip_histogram(blob).astype(np.float64)
+    p = cnt[cnt > 0] / cnt.sum()
+    entropy = float(-(p * np.log2(p)).sum())
+    comp_bytes = blob.compressed_bytes
+    bits_per_weight = 8.0 * comp_bytes / n
+
+    # roofline of the decode kernel: algorithmic bytes = container bytes read + bf16 bytes written
+    kernel_ms = event_ms / args.steps
+    algo_bytes = comp_bytes + out_bytes
+    achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic_note(),
+                "kernel": "decode_kernel<7>", "avg_launch_us": round(kernel_ms * 1e3, 2),
+                "algorithmic_bytes_per_elem": round(algo_bytes / n, 4)}
+
+    # context: a plain device copy of the same output size
+    src = torch.empty_like(scratch)
+    for _ in range(5):
+        scratch.copy_(src)
+    _, copy_ms = timed_region(torch, stream, lambda: scratch.copy_(src), 50)
+    copy_gbps = 2 * out_bytes / (copy_ms / 50 * 1e-3) / 1e9
+
+    # compress rate (histogram + table + encode + offsets + compaction, incl. the one size read-back)
+    for _ in range(3):
+        nz.neuzip_compress(w, 7, blob=blob)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    reps = 10
+    for _ in range(reps):
+        nz.neuzip_compress(w, 7, blob=blob)
+    torch.cuda.synchronize()
+    compress_gbps = out_bytes / ((time.perf_counter() - t0) / reps) / 1e9
+
+    result = {
+        "metric": "bf16 decompress GB/s (output)", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32", "data": "synthetic",
+        "config": {"workload": "config 2: bf16 4096x14336 i.i.d. N(0,0.02), lossless, one compress then "
+                               "repeated fused decompress into one bf16 scratch", "elements": n,
+                   "mantissa_bits": 7, "chunk": 4096, "states_per_chunk": 16, "prob_bits": 12},
+        "roofline": roofline,
+        "bits_per_weight": round(bits_per_weight, 4), "exponent_entropy_bits": round(entropy, 4),
+        "bits_per_weight_over_bound": round(bits_per_weight / (entropy + 8.0), 5),
+        "compress_GBps_input": round(compress_gbps, 1),
+        "device_copy_GBps_read_plus_write": round(copy_gbps, 1),
+        "event_ms_per_step": round(kernel_ms, 5),
+    }
+
+    # ---------------------------------------------------------------- CPU oracle on the host cores
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        cores = min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "16") or 16))
+        words = inputs.bits(w)
+        container = nz.neuzip_export(blob)
+        best = float("inf")
+        for _ in range(3):
+            t0 = time.perf_counter()
+            back = O.decompress(container, n, threads=cores)
+            best = min(best, time.perf_counter() - t0)
+        assert np.array_equal(back, words), "oracle and GPU disagree"
+        t0 = time.perf_counter()
+        theirs = O.compress(words, 7, threads=cores)
+        enc_s = time.perf_counter() - t0
+        assert np.array_equal(theirs, container), "container differs from the oracle's"
+        result["cpu_baseline"] = {"value": round(out_bytes / best / 1e9, 3), "unit": "GB/s", "cores": cores,
+                                  "kind": "oracle",
+                                  "sample": "the whole config-2 tensor (58.7M elements), oracle decompress of "
+                                            "the GPU-written container, best of 3; containers compared "
+                                            "byte for byte",
+                                  "compress_GBps_input": round(out_bytes / enc_s / 1e9, 3)}
+        del words, container, back, theirs
+
+    # ---------------------------------------------------------------- optional: configs 4 and 3
+    if args.extended:
+        ext = {}
+        del w, scratch, src
+        nz.neuzip_free(blob)
+        torch.cuda.empty_cache()
+        t4 = inputs.student_t4_bf16(inputs.MLP_70B, inputs.seed_for(4), device=dev)
+        n4 = t4.numel()
+        buf = torch.empty(n4, dtype=torch.bfloat16, device=dev)
+        for k in (7, 3, 1, 0):
+            b4 = nz.neuzip_compress(t4, k)
+            for _ in range(5):
+                nz.neuzip_decompress(b4, buf)
+            _, ms = timed_region(torch, stream, lambda: nz.neuzip_decompress(b4, buf), 50)
+            ms /= 50
+            ext[f"config4_k{k}"] = {"decompress_GBps_output": round(2.0 * n4 / (ms * 1e-3) / 1e9, 1),
+                                    "hbm_frac": round((b4.compressed_bytes + 2.0 * n4) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                    "bits_per_weight": round(8.0 * b4.compressed_bytes / n4, 4)}
+            nz.neuzip_free(b4)
+        del t4, buf
+        torch.cuda.empty_cache()
+        # config-3-shaped sweep over the first layers (embedding + `layers` decoder layers)
+        names = inputs.llama3_8b_tensors()[: 1 + 7 * args.layers]
+        blobs, total = [], 0
+        for i, (name, shp) in enumerate(names):
+            t = inputs.gaussian_bf16(shp, inputs.seed_for(3, i), device=dev)
+            blobs.append(nz.neuzip_compress(t, 7))
+            total += t.numel()
+            del t
+        big = torch.empty(max(b.elems for b in blobs), dtype=torch.bfloat16, device=dev)
+        for _ in range(2):
+            nz.neuzip_decompress_sequence(blobs, big)
+        _, ms = timed_region(torch, stream, lambda: nz.neuzip_decompress_sequence(blobs, big), 5)
+        ms /= 5
+        comp = sum(b.compressed_bytes for b in blobs)
+        ext["config3_sweep"] = {"tensors": len(blobs), "elements": total, "ms": round(ms, 4),
+                                "decompress_GBps_output": round(2.0 * total / (ms * 1e-3) / 1e9, 1),
+                                "hbm_frac": round((comp + 2.0 * total) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        result["extended"] = ext
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
