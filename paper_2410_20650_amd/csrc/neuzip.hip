@@ -42,7 +42,7 @@ constexpr uint32_t kRunCap = 200;
 constexpr uint32_t kMagic = 0x315A554Eu;            // "NUZ1"
 constexpr uint32_t kHeaderBytes = 64;
 
-// Decoder launch shape: 512 threads = 8 waves, each wave walks 4 chunks (4 x 16 states).
+// Decoder launch shape: at most 512 threads = 8 waves, each wave walks 4 chunks (4 x 16 states).
 constexpr uint32_t kDecThreads = 512;
 constexpr uint32_t kDecChunksPerWg = kDecThreads / kStates;   // 32
 // LDS: 16 KB slot table + staged word runs.  Two workgroups share a CU's 160 KB.
@@ -77,7 +77,10 @@ struct TableBlock {
     uint16_t cum[264];     // exclusive cumulative frequencies, cum[256] = 4096 (derived)
     uint32_t counts[256];  // exponent histogram of the source tensor
     uint32_t status[4];    // [0] != 0: a decode found a malformed stream
-    uint32_t pad[56];
+    uint32_t lone;         // the only exponent value of the tensor (its f is 4096), else 256
+    uint32_t pad[55];
+    // decoder slot table (derived): lut[slot] = symbol | f << 8 | (slot - cum[symbol]) << 20
+    uint32_t lut[4096];
 };
 static_assert(sizeof(TableBlock) % 256 == 0, "table block keeps later sections aligned");
 
@@ -270,6 +273,30 @@ __global__ __launch_bounds__(256) void table_kernel(TableBlock *__restrict__ tb,
     tb->cum[s] = static_cast<uint16_t>(cum);
     if (s == 255)
         tb->cum[256] = static_cast<uint16_t>(scan[255]);
+    if (s == 0)
+        tb->lone = 256;
+    __syncthreads();
+    if (f == kM)
+        tb->lone = s;
+    // decoder slot table: thread s fills slots [16 s, 16 s + 16); scan[t] = cum[t + 1]
+    if (total > 0) {
+        const uint32_t first = s * (kM / 256);
+        uint32_t lo = 0, hi = 255;  // smallest t with cum[t + 1] > first
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (scan[mid] > first)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        uint32_t t = lo;
+        for (uint32_t slot = first; slot < first + kM / 256; ++slot) {
+            while (t < 255 && scan[t] <= slot)
+                ++t;
+            const uint32_t start = t ? scan[t - 1] : 0u;
+            tb->lut[slot] = t | (((scan[t] - start) & 0xFFFu) << 8) | ((slot - start) << 20);
+        }
+    }
 
     EncSym e = {1u, 0xFFFFFFFFu, 0u, 0u};
     if (f > 0) {
@@ -423,15 +450,17 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const uint16_t
 // ------------------------------------------------------------------------------------------
 // Kernel 6: fused decoder (Alg. 1 "decompression" + "merge"; Sec. 2.2 Eq. (3)).
 //
-// A workgroup owns 32 neighbouring chunks.  It builds the 4096-entry slot table
-// (symbol | f << 8 | (slot - cum) << 20) in LDS, copies the chunks' word runs -- one
-// contiguous piece of the blob -- into LDS with 128-bit loads, and then every lane walks one
-// state: 32 turns of 8 symbols; per symbol one table read, one multiply-add, one compare,
-// and a lane-private refill.  The 8 decoded exponents are merged with the 8 sign|mantissa
-// fields and leave as one 128-bit store.
+// A workgroup owns blockDim.x / 16 neighbouring chunks (at most 32).  It copies the 4096-entry
+// slot table (symbol | f << 8 | (slot - cum) << 20, prepared once per tensor) and the chunks'
+// word runs -- one contiguous piece of the blob -- into LDS with 128-bit loads behind a single
+// barrier, and then every lane walks one
+// state: 32 turns of 8 symbols; per symbol one table read, one multiply-add, one compare, and
+// a lane-private refill that touches LDS only when a word is consumed.  The 8 decoded
+// exponents are merged with the 8 sign|mantissa fields and leave as one 128-bit store; the
+// fields of the next turn are requested before the current turn is decoded.
 // ------------------------------------------------------------------------------------------
 template <int KB>
-__device__ inline uint64_t load_fields(const uint8_t *__restrict__ sm, uint64_t first_elem)
+__device__ __forceinline__ uint64_t load_fields(const uint8_t *__restrict__ sm, uint64_t first_elem)
 {
     // the (KB+1)*8 field bits of 8 neighbouring elements
     if constexpr (KB == 7) {
@@ -446,33 +475,29 @@ __device__ inline uint64_t load_fields(const uint8_t *__restrict__ sm, uint64_t 
     }
 }
 
+// Two bf16 words (sign << 15 | exponent << 7 | kept mantissa bits << (7 - KB)) from the field
+// bits of a pair of neighbouring elements and the two slot-table entries that decoded them
+// (exponent in the low byte of an entry).
 template <int KB>
-__device__ inline uint32_t merge_pair(uint64_t fields, int pair, uint32_t e_lo, uint32_t e_hi)
+__device__ __forceinline__ uint32_t merge_pair(uint64_t fields, int pair, uint32_t entry_lo, uint32_t entry_hi)
 {
-    // two bf16 words: sign << 15 | exponent << 7 | kept mantissa bits << (7 - KB)
-    constexpr uint32_t width = KB + 1;
-    constexpr uint32_t fmask = (1u << width) - 1u;
-    const uint32_t f_lo = static_cast<uint32_t>(fields >> ((2 * pair) * width)) & fmask;
-    const uint32_t f_hi = static_cast<uint32_t>(fields >> ((2 * pair + 1) * width)) & fmask;
-    const uint32_t lo = ((f_lo >> KB) << 15) | (e_lo << 7) | ((f_lo & ((1u << KB) - 1u)) << (7 - KB));
-    const uint32_t hi = ((f_hi >> KB) << 15) | (e_hi << 7) | ((f_hi & ((1u << KB) - 1u)) << (7 - KB));
-    return lo | (hi << 16);
-}
-
-// One rANS decoding step of a lane's state.  WordSrc::peek(at) returns the 16-bit word at byte
-// position `at` of the lane's word source.
-template <class WordSrc>
-__device__ __forceinline__ uint32_t rans_get(const uint32_t *__restrict__ lut, uint32_t &x, uint32_t &wp,
-                                             uint32_t &next, const WordSrc &src)
-{
-    const uint32_t e = lut[x & (kM - 1)];
-    x = __umul24((e >> 8) & 0xFFFu, x >> kProbBits) + (e >> 20);
-    if (x < kRansL) {
-        x = (x << 16) | next;
-        wp += 2;
+    // [0, exponent_hi, 0, exponent_lo]
+    const uint32_t expo = __builtin_amdgcn_perm(entry_hi, entry_lo, 0x0c040c00u);
+    if constexpr (KB == 7) {
+        // lossless: a field is the byte sign << 7 | mantissa.  Spread the two bytes over the two
+        // halfwords ([b1, b1, b0, b0]) and keep bit 15 and bits 6..0 of each.
+        const uint32_t half = static_cast<uint32_t>(fields >> (32 * (pair >> 1)));
+        const uint32_t twice = __builtin_amdgcn_perm(half, half, (pair & 1) ? 0x03030202u : 0x01010000u);
+        return (expo << 7) | (twice & 0x807F807Fu);
+    } else {
+        constexpr uint32_t width = KB + 1;
+        constexpr uint32_t fmask = (1u << width) - 1u;
+        const uint32_t f_lo = static_cast<uint32_t>(fields >> ((2 * pair) * width)) & fmask;
+        const uint32_t f_hi = static_cast<uint32_t>(fields >> ((2 * pair + 1) * width)) & fmask;
+        const uint32_t lo = ((f_lo >> KB) << 15) | ((f_lo & ((1u << KB) - 1u)) << (7 - KB));
+        const uint32_t hi = ((f_hi >> KB) << 15) | ((f_hi & ((1u << KB) - 1u)) << (7 - KB));
+        return (expo << 7) | lo | (hi << 16);
     }
-    next = src.peek(wp);
-    return e & 0xFFu;
 }
 
 struct LdsWords {
@@ -487,19 +512,41 @@ struct NoWords {
     __device__ __forceinline__ uint32_t peek(uint32_t) const { return 0; }
 };
 
+// One rANS decoding step of a lane's state; returns the slot-table entry (symbol in its low
+// byte).  `next` always holds the word at byte position wp of the lane's word source, so a
+// refill is a shift-or; the following word is fetched only then.
+template <class WordSrc>
+__device__ __forceinline__ uint32_t rans_get(const uint32_t *__restrict__ lut, uint32_t &x, uint32_t &wp,
+                                             uint32_t &next, const WordSrc &src)
+{
+    const uint32_t e = lut[x & (kM - 1)];
+    x = __umul24((e >> 8) & 0xFFFu, x >> kProbBits) + (e >> 20);
+    if (x < kRansL) {
+        x = (x << 16) | next;
+        wp += 2;
+        next = src.peek(wp);
+    }
+    return e;
+}
+
 // Walks one state over its part of chunk [base, base + m) and writes the merged bf16 words.
 // LONE: the tensor has a single exponent value (f = 4096): the state never moves and there are
 // no words.  Returns through x / wp what the well-formedness check needs.
 template <int KB, bool LONE, class WordSrc>
 __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
                                            uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
-                                           uint16_t *__restrict__ out, uint64_t base, uint32_t m, uint32_t j)
+                                           uint64_t fields, uint16_t *__restrict__ out, uint64_t base, uint32_t m,
+                                           uint32_t j)
 {
+    // `fields` arrives holding the field bits of the state's first 8 elements (full chunks only)
     uint32_t next = LONE ? 0u : src.peek(wp);
     if (m == kChunk) {
         uint4 *out4 = reinterpret_cast<uint4 *>(out + base) + j;
+        const uint64_t first = base + j * kRun;
         for (uint32_t q = 0; q < kTurns; ++q) {
-            const uint64_t fields = load_fields<KB>(sm, base + q * kTurn + j * kRun);
+            // ask for the next turn's fields now; the last turn re-reads its own (stays in bounds)
+            const uint32_t qn = q + 1 < kTurns ? q + 1 : q;
+            const uint64_t fields_next = load_fields<KB>(sm, first + qn * kTurn);
             uint32_t e[8];
 #pragma unroll
             for (int t = 0; t < 8; ++t)
@@ -510,6 +557,7 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
             o.z = merge_pair<KB>(fields, 2, e[4], e[5]);
             o.w = merge_pair<KB>(fields, 3, e[6], e[7]);
             out4[q * kStates] = o;
+            fields = fields_next;
         }
     } else {
         // ragged last chunk: element by element
@@ -519,7 +567,7 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
                 const uint32_t i = q * kTurn + j * kRun + t;
                 if (i >= m)
                     continue;
-                const uint32_t sym = LONE ? lone : rans_get(lut, x, wp, next, src);
+                const uint32_t sym = (LONE ? lone : rans_get(lut, x, wp, next, src)) & 0xFFu;
                 const uint64_t g = base + i;
                 const uint32_t field = (sm[g / per_byte] >> ((g % per_byte) * width)) & ((1u << width) - 1u);
                 out[g] = static_cast<uint16_t>(((field >> KB) << 15) | (sym << 7) |
@@ -539,66 +587,63 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(const TableBlock *_
                                                             uint16_t *__restrict__ out, uint64_t n,
                                                             uint32_t n_chunks, uint32_t *__restrict__ status)
 {
-    __shared__ uint32_t lut[kM];
+    __shared__ __align__(16) uint32_t lut[kM];
     __shared__ __align__(16) uint8_t stage[kStageBytes];
-    __shared__ uint16_t cum[260];
-    __shared__ uint32_t lone_symbol;  // 256 = none; else the only symbol of the tensor (f = 4096)
 
     const uint32_t tid = threadIdx.x;
-    const uint32_t c0 = blockIdx.x * kDecChunksPerWg;
-    const uint32_t c1 = c0 + kDecChunksPerWg < n_chunks ? c0 + kDecChunksPerWg : n_chunks;
+    const uint32_t threads = blockDim.x;            // a multiple of 64, at most kDecThreads
+    const uint32_t chunks_per_wg = threads / kStates;
+    const uint32_t c0 = blockIdx.x * chunks_per_wg;
+    const uint32_t c1 = c0 + chunks_per_wg < n_chunks ? c0 + chunks_per_wg : n_chunks;
+    const uint32_t c = c0 + tid / kStates;
+    const uint32_t j = tid % kStates;
+    const bool live = c < n_chunks;
+    const uint32_t id = c * kStates + j;
+    const uint64_t base = static_cast<uint64_t>(c) * kChunk;
+    const uint32_t m = !live ? 0u : ((n - base) < kChunk ? static_cast<uint32_t>(n - base) : kChunk);
+
+    // ---- every load that depends on nothing is issued first, so their latencies overlap
+    const uint32_t off0 = offsets[c0];
+    const uint32_t off1 = offsets[c1];
+    const uint32_t off_c = live ? offsets[c] : 0u;
+    uint32_t x = live ? states[id] : kRansL;
+    const uint32_t len = live ? lens[id] : 0u;
+    const uint32_t lone = tb->lone;
+    const uint64_t fields0 = m == kChunk ? load_fields<KB>(sm, base + j * kRun) : 0;
+    const uint4 *lut_g = reinterpret_cast<const uint4 *>(tb->lut);
+    uint4 lut_piece[2];  // 16 KB table / 16 B = 1024 pieces; 2 per thread at 512 threads
+#pragma unroll
+    for (uint32_t r = 0; r < 2; ++r) {
+        const uint32_t i = tid + r * threads;
+        lut_piece[r] = i < kM / 4 ? lut_g[i] : make_uint4(0, 0, 0, 0);
+    }
 
     // ---- stage the word runs of chunks [c0, c1): one contiguous piece of the blob
-    const uint64_t byte0 = static_cast<uint64_t>(offsets[c0]) * 2;
-    const uint64_t byte1 = static_cast<uint64_t>(offsets[c1]) * 2;
+    const uint64_t byte0 = static_cast<uint64_t>(off0) * 2;
+    const uint64_t byte1 = static_cast<uint64_t>(off1) * 2;
     const uint64_t aligned0 = byte0 & ~static_cast<uint64_t>(15);
     const uint64_t stage_len = byte1 - aligned0;
     const bool staged = stage_len + 16 <= kStageBytes;  // room for the one-word look-ahead
     if (staged) {
         const uint4 *from = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(words) + aligned0);
         uint4 *to = reinterpret_cast<uint4 *>(stage);
-        for (uint32_t i = tid; i * 16 < stage_len; i += kDecThreads)
+        for (uint32_t i = tid; i * 16 < stage_len; i += threads)
             to[i] = from[i];
     }
-
-    // ---- slot table: entry = symbol | f << 8 | (slot - cum[symbol]) << 20
-    if (tid < 257)
-        cum[tid] = tb->cum[tid];
-    if (tid == 0)
-        lone_symbol = 256;
-    __syncthreads();
-    {
-        constexpr uint32_t per_thread = kM / kDecThreads;
-        const uint32_t first = tid * per_thread;
-        uint32_t lo = 0, hi = 255;  // smallest s with cum[s + 1] > first
-        while (lo < hi) {
-            const uint32_t mid = (lo + hi) >> 1;
-            if (cum[mid + 1] > first)
-                hi = mid;
-            else
-                lo = mid + 1;
-        }
-        uint32_t s = lo;
-        for (uint32_t t = 0; t < per_thread; ++t) {
-            const uint32_t slot = first + t;
-            while (s < 255 && cum[s + 1] <= slot)
-                ++s;
-            const uint32_t f = static_cast<uint32_t>(cum[s + 1]) - cum[s];
-            lut[slot] = s | ((f & 0xFFFu) << 8) | ((slot - cum[s]) << 20);
-            if (f == kM && slot == 0)
-                lone_symbol = s;
-        }
+    // ---- slot table into LDS (small workgroups loop over the remaining pieces)
+#pragma unroll
+    for (uint32_t r = 0; r < 2; ++r) {
+        const uint32_t i = tid + r * threads;
+        if (i < kM / 4)
+            reinterpret_cast<uint4 *>(lut)[i] = lut_piece[r];
     }
+    for (uint32_t i = tid + 2 * threads; i < kM / 4; i += threads)
+        reinterpret_cast<uint4 *>(lut)[i] = lut_g[i];
     __syncthreads();
 
     // ---- one lane, one state
-    const uint32_t c = c0 + tid / kStates;
-    const uint32_t j = tid % kStates;
-    if (c >= n_chunks)
+    if (!live)
         return;
-    const uint32_t id = c * kStates + j;
-    uint32_t x = states[id];
-    const uint32_t len = lens[id];
     // start of this state's run: chunk offset + lengths of the states before it (16-lane prefix)
     uint32_t before = len;
 #pragma unroll
@@ -608,22 +653,19 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(const TableBlock *_
             before += o;
     }
     before -= len;
-    const uint64_t run_byte = (static_cast<uint64_t>(offsets[c]) + before) * 2;
-    const uint64_t base = static_cast<uint64_t>(c) * kChunk;
-    const uint32_t m = (n - base) < kChunk ? static_cast<uint32_t>(n - base) : kChunk;
-    const uint32_t lone = lone_symbol;
+    const uint64_t run_byte = (static_cast<uint64_t>(off_c) + before) * 2;
 
     uint32_t wp = 0, wp_begin = 0;
     if (lone < 256) {
-        walk_state<KB, true>(lut, NoWords{}, lone, x, wp, sm, out, base, m, j);
+        walk_state<KB, true>(lut, NoWords{}, lone, x, wp, sm, fields0, out, base, m, j);
     } else if (staged) {
         wp = wp_begin = static_cast<uint32_t>(run_byte - aligned0);
-        walk_state<KB, false>(lut, LdsWords{stage}, 0u, x, wp, sm, out, base, m, j);
+        walk_state<KB, false>(lut, LdsWords{stage}, 0u, x, wp, sm, fields0, out, base, m, j);
     } else {
-        // the runs of these 32 chunks did not fit the LDS window (more than ~4 bits per symbol):
-        // read the words straight from the blob
+        // the runs of this workgroup's chunks did not fit the LDS window (more than ~4 bits per
+        // symbol): read the words straight from the blob
         walk_state<KB, false>(lut, GlobalWords{reinterpret_cast<const uint8_t *>(words) + run_byte}, 0u, x, wp, sm,
-                              out, base, m, j);
+                              fields0, out, base, m, j);
     }
     // a well-formed run is consumed exactly and leaves the state where the encoder started
     if (x != kRansL || wp - wp_begin != 2 * len)
@@ -824,11 +866,26 @@ int launch_hist(const void *d_src, uint64_t n, neuzip_blob *b, hipStream_t strea
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
 
+// Chunks per decoder workgroup.  32 (8 waves) measured best at every size: two such workgroups
+// fill a CU's LDS with 16 waves, and smaller workgroups lower that occupancy.
+// NEUZIP_DECODE_CHUNKS_PER_WG (4..32, multiple of 4) overrides the choice for tuning runs.
+uint32_t decode_chunks_per_wg()
+{
+    static int forced = -1;
+    if (forced < 0) {
+        const char *env = std::getenv("NEUZIP_DECODE_CHUNKS_PER_WG");
+        const int v = env ? std::atoi(env) : 0;
+        forced = (v >= 4 && v <= static_cast<int>(kDecChunksPerWg) && v % 4 == 0) ? v : 0;
+    }
+    return forced > 0 ? static_cast<uint32_t>(forced) : kDecChunksPerWg;
+}
+
 template <int KB>
 int launch_decode(const neuzip_blob *b, void *d_dst, hipStream_t stream)
 {
-    const uint32_t groups = (b->n_chunks + kDecChunksPerWg - 1) / kDecChunksPerWg;
-    hipLaunchKernelGGL(decode_kernel<KB>, dim3(groups), dim3(kDecThreads), 0, stream, table_of(b), offsets_of(b),
+    const uint32_t per = decode_chunks_per_wg();
+    const uint32_t groups = (b->n_chunks + per - 1) / per;
+    hipLaunchKernelGGL(decode_kernel<KB>, dim3(groups), dim3(per * kStates), 0, stream, table_of(b), offsets_of(b),
                        states_of(b), lens_of(b), reinterpret_cast<const uint16_t *>(b->words), sm_of(b),
                        static_cast<uint16_t *>(d_dst), b->n, b->n_chunks, table_of(b)->status);
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
@@ -1121,10 +1178,17 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
     b->have_counts = false;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    TableBlock tb;
+    static thread_local TableBlock tb;  // 18 KB: off the stack
     std::memset(&tb, 0, sizeof(tb));
     std::memcpy(tb.freq, freq, 512);
     std::memcpy(tb.cum, cum, sizeof(tb.cum));
+    tb.lone = 256;
+    for (uint32_t sym = 0; sym < 256; ++sym) {
+        if (freq[sym] == kM)
+            tb.lone = sym;
+        for (uint32_t slot = cum[sym]; slot < static_cast<uint32_t>(cum[sym]) + freq[sym]; ++slot)
+            tb.lut[slot] = sym | ((freq[sym] & 0xFFFu) << 8) | ((slot - cum[sym]) << 20);
+    }
     const uint32_t zeros[2] = {0, 0};
     if (!hip_ok(hipMemcpyAsync(b->fixed, &tb, sizeof(tb), hipMemcpyHostToDevice, stream)) ||
         !hip_ok(hipMemcpyAsync(offsets_of(b), p + lay.offsets, (nc + 1ull) * 4, hipMemcpyHostToDevice, stream)) ||
@@ -1137,7 +1201,7 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
         return fail(NEUZIP_EHIP);
     if (n && !hip_ok(hipMemcpyAsync(sm_of(b), p + lay.sm, signmant_bytes(n, k), hipMemcpyHostToDevice, stream)))
         return fail(NEUZIP_EHIP);
-    if (!hip_ok(hipStreamSynchronize(stream)))  // tb and zeros live on this stack frame
+    if (!hip_ok(hipStreamSynchronize(stream)))  // tb and zeros must outlive the copies
         return fail(NEUZIP_EHIP);
     *blob = b;
     return NEUZIP_OK;
