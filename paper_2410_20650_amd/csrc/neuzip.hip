@@ -47,6 +47,12 @@ constexpr uint32_t kDecThreads = 512;
 constexpr uint32_t kDecChunksPerWg = kDecThreads / kStates;   // 32
 // LDS: 16 KB slot table + staged word runs.  Two workgroups share a CU's 160 KB.
 constexpr uint32_t kStageBytes = 62 * 1024;
+// Turns (of 8 symbols per state) whose loads and stores are issued together.
+#ifndef NEUZIP_TURN_GROUP
+#define NEUZIP_TURN_GROUP 2
+#endif
+constexpr uint32_t kTurnGroup = NEUZIP_TURN_GROUP;
+static_assert(kTurns % kTurnGroup == 0, "a chunk is a whole number of turn groups");
 
 thread_local int g_last_hip_error = 0;
 
@@ -535,29 +541,42 @@ __device__ __forceinline__ uint32_t rans_get(const uint32_t *__restrict__ lut, u
 template <int KB, bool LONE, class WordSrc>
 __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
                                            uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
-                                           uint64_t fields, uint16_t *__restrict__ out, uint64_t base, uint32_t m,
-                                           uint32_t j)
+                                           uint64_t (&fields)[kTurnGroup], uint16_t *__restrict__ out,
+                                           uint64_t base, uint32_t m, uint32_t j)
 {
-    // `fields` arrives holding the field bits of the state's first 8 elements (full chunks only)
+    // `fields` arrives holding the field bits of the state's first kTurnGroup turns (full chunks only)
     uint32_t next = LONE ? 0u : src.peek(wp);
     if (m == kChunk) {
         uint4 *out4 = reinterpret_cast<uint4 *>(out + base) + j;
         const uint64_t first = base + j * kRun;
-        for (uint32_t q = 0; q < kTurns; ++q) {
-            // ask for the next turn's fields now; the last turn re-reads its own (stays in bounds)
-            const uint32_t qn = q + 1 < kTurns ? q + 1 : q;
-            const uint64_t fields_next = load_fields<KB>(sm, first + qn * kTurn);
-            uint32_t e[8];
+        // Turns are taken in groups: the field loads of the next group are issued together before
+        // the current group is decoded, and the group's 128-bit stores leave back to back, so
+        // each state keeps several memory requests in flight and a chunk is written in bursts of
+        // kTurnGroup * 256 contiguous bytes.
+        for (uint32_t q0 = 0; q0 < kTurns; q0 += kTurnGroup) {
+            uint64_t fields_next[kTurnGroup];
+            // the last group re-reads its own fields (stays in bounds)
+            const uint32_t qn = q0 + kTurnGroup < kTurns ? q0 + kTurnGroup : q0;
 #pragma unroll
-            for (int t = 0; t < 8; ++t)
-                e[t] = LONE ? lone : rans_get(lut, x, wp, next, src);
-            uint4 o;
-            o.x = merge_pair<KB>(fields, 0, e[0], e[1]);
-            o.y = merge_pair<KB>(fields, 1, e[2], e[3]);
-            o.z = merge_pair<KB>(fields, 2, e[4], e[5]);
-            o.w = merge_pair<KB>(fields, 3, e[6], e[7]);
-            out4[q * kStates] = o;
-            fields = fields_next;
+            for (uint32_t r = 0; r < kTurnGroup; ++r)
+                fields_next[r] = load_fields<KB>(sm, first + (qn + r) * kTurn);
+            uint4 o[kTurnGroup];
+#pragma unroll
+            for (uint32_t r = 0; r < kTurnGroup; ++r) {
+                uint32_t e[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    e[t] = LONE ? lone : rans_get(lut, x, wp, next, src);
+                o[r].x = merge_pair<KB>(fields[r], 0, e[0], e[1]);
+                o[r].y = merge_pair<KB>(fields[r], 1, e[2], e[3]);
+                o[r].z = merge_pair<KB>(fields[r], 2, e[4], e[5]);
+                o[r].w = merge_pair<KB>(fields[r], 3, e[6], e[7]);
+            }
+#pragma unroll
+            for (uint32_t r = 0; r < kTurnGroup; ++r) {
+                out4[(q0 + r) * kStates] = o[r];
+                fields[r] = fields_next[r];
+            }
         }
     } else {
         // ragged last chunk: element by element
@@ -609,7 +628,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(const TableBlock *_
     uint32_t x = live ? states[id] : kRansL;
     const uint32_t len = live ? lens[id] : 0u;
     const uint32_t lone = tb->lone;
-    const uint64_t fields0 = m == kChunk ? load_fields<KB>(sm, base + j * kRun) : 0;
+    uint64_t fields0[kTurnGroup];
+#pragma unroll
+    for (uint32_t r = 0; r < kTurnGroup; ++r)
+        fields0[r] = m == kChunk ? load_fields<KB>(sm, base + r * kTurn + j * kRun) : 0;
     const uint4 *lut_g = reinterpret_cast<const uint4 *>(tb->lut);
     uint4 lut_piece[2];  // 16 KB table / 16 B = 1024 pieces; 2 per thread at 512 threads
 #pragma unroll
