@@ -1,0 +1,126 @@
+"""The five baseline configurations at their full sizes, through the C ABI (-m gpu).
+
+Bar: bit-exact.  Where the oracle finishes in seconds the whole container and every decoded word
+are compared with it; on the Llama-3-8B-shaped set every tensor round-trips bit-exactly on the GPU
+and a fixed sample of tensors is compared with the oracle byte for byte.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2410_20650_amd import inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+THREADS = 16
+
+
+@pytest.fixture(scope="module")
+def nz():
+    from paper_2410_20650_amd import binding
+    return binding
+
+
+def same_bits(a: torch.Tensor, b: torch.Tensor) -> bool:
+    return torch.equal(a.reshape(-1).view(torch.int16), b.reshape(-1).view(torch.int16))
+
+
+def oracle_parity(nz, w, blob, k):
+    words = inputs.bits(w)
+    want = O.compress(words, k, threads=THREADS)
+    got = nz.neuzip_export(blob)
+    assert got.size == want.size
+    assert np.array_equal(got, want), "container differs from the oracle's"
+    assert np.array_equal(O.decompress(got, words.size, threads=THREADS), O.truncate(words, k))
+
+
+def test_config2_llama_mlp_weight(nz):
+    w = inputs.gaussian_bf16(inputs.MLP_8B, inputs.seed_for(2), device=DEV)
+    blob = nz.neuzip_compress(w, 7)
+    scratch = torch.empty(w.numel(), dtype=torch.bfloat16, device=DEV)
+    for _ in range(3):                                     # repeated fused decompress into one scratch
+        scratch.zero_()
+        nz.neuzip_decompress(blob, scratch)
+        assert same_bits(scratch, w)
+    nz.neuzip_check(blob)
+    oracle_parity(nz, w, blob, 7)
+    cnt = nz.neuzip_histogram(blob).astype(np.float64)
+    p = cnt[cnt > 0] / cnt.sum()
+    entropy = -(p * np.log2(p)).sum()
+    assert 8 * blob.compressed_bytes / w.numel() <= 1.02 * (entropy + 8)
+
+
+@pytest.mark.parametrize("k", [3, 0])
+def test_config4_lossy_70b_mlp_weight(nz, k):
+    w = inputs.student_t4_bf16(inputs.MLP_70B, inputs.seed_for(4), device=DEV)
+    blob = nz.neuzip_compress(w, k)
+    out = torch.empty(w.numel(), dtype=torch.bfloat16, device=DEV)
+    nz.neuzip_decompress(blob, out)
+    nz.neuzip_check(blob)
+    # plain definition on the GPU copy: drop the low 7 - k mantissa bits
+    mask = ~((1 << (7 - k)) - 1)
+    expect = (w.reshape(-1).view(torch.int16) & mask)
+    assert torch.equal(out.view(torch.int16), expect)
+    # the paper's bound on the relative change (finite, normal values)
+    a, b = w.reshape(-1)[:4_000_000].float(), out[:4_000_000].float()
+    ok = a.abs() >= 2.0 ** -126
+    assert ((a[ok] - b[ok]).abs() / a[ok].abs()).max().item() < 2.0 ** -k
+    oracle_parity(nz, w, blob, k)
+    assert blob.compressed_bytes == O.compress(inputs.bits(w), k, threads=THREADS).size
+
+
+def test_config3_forward_schedule_llama3_8b_shapes(nz):
+    names = inputs.llama3_8b_tensors()
+    assert len(names) == 225
+    sample = {0, 1, 7, 218, 224}                           # embedding, layer 0 q and down, layer 31 q and down
+    blobs, sums, total, comp = [], [], 0, 0
+    scratch = torch.empty(128256 * 4096, dtype=torch.bfloat16, device=DEV)
+    for i, (name, shape) in enumerate(names):
+        w = inputs.gaussian_bf16(shape, inputs.seed_for(3, i), device=DEV)
+        blob = nz.neuzip_compress(w, 7)
+        blobs.append(blob)
+        total += w.numel()
+        comp += blob.compressed_bytes
+        sums.append(int(w.reshape(-1).view(torch.int16).to(torch.int64).sum().item()))
+        # every tensor goes through the one scratch buffer and comes back bit-exact
+        nz.neuzip_decompress_sequence([blob], scratch)
+        assert same_bits(scratch[: w.numel()], w), name
+        if i in sample:
+            oracle_parity(nz, w, blob, 7)
+        del w
+    assert total == 7_504_658_432
+    assert 8 * comp / total < 10.76                        # 2 % over entropy + 8 bits
+    # the whole forward pass in one call; the scratch ends up holding the last layer
+    nz.neuzip_decompress_sequence(blobs, scratch)
+    for b in blobs:
+        nz.neuzip_check(b)
+    last = blobs[-1].elems
+    assert int(scratch[:last].view(torch.int16).to(torch.int64).sum().item()) == sums[-1]
+
+
+def test_config5_training_step_loop(nz):
+    # 10 steps of decompress -> synthetic update -> recompress (histogram rebuilt) -> verify,
+    # on a two-layer slice of the config-3 shapes plus the embedding; oracle cross-check on a sample
+    names = inputs.llama3_8b_tensors()[:15]
+    tensors = [inputs.gaussian_bf16(s, inputs.seed_for(5, i), device=DEV) for i, (_, s) in enumerate(names)]
+    blobs = [nz.neuzip_compress(t, 7) for t in tensors]
+    del tensors
+    scratch = torch.empty(128256 * 4096, dtype=torch.bfloat16, device=DEV)
+    check = torch.empty_like(scratch)
+    for step in range(10):
+        for i, blob in enumerate(blobs):
+            n = blob.elems
+            w = scratch[:n]
+            nz.neuzip_decompress(blob, w)
+            new = inputs.synthetic_update(w, inputs.seed_for(5, 1000 * (step + 1) + i))
+            changed = (new.view(torch.int16) != w.view(torch.int16)).float().mean().item()
+            assert 0.2 < changed < 0.8                     # about half the weights move by one bf16 step
+            nz.neuzip_compress(new, 7, blob=blob)
+            nz.neuzip_decompress(blob, check[:n])
+            assert same_bits(check[:n], new), (step, names[i][0])
+            if i in (1, 7) or (i == 0 and step in (0, 9)):
+                oracle_parity(nz, new, blob, 7)
+            del new
+        for blob in blobs:
+            nz.neuzip_check(blob)
