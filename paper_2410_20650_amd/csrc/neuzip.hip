@@ -236,12 +236,19 @@ __device__ inline uint64_t block_sum_u64(uint64_t v, uint64_t *scratch)
     return scratch[0] + scratch[1] + scratch[2] + scratch[3];
 }
 
-__global__ __launch_bounds__(256) void table_kernel(TableBlock *__restrict__ tb, EncSym *__restrict__ enc)
+__global__ __launch_bounds__(256) void table_kernel(uint32_t *__restrict__ counts_ws, TableBlock *__restrict__ tb,
+                                                    EncSym *__restrict__ enc)
 {
     __shared__ uint64_t scratch[4];
     __shared__ uint32_t scan[256];
     const uint32_t s = threadIdx.x;
-    const uint64_t cnt = tb->counts[s];
+    // the histogram was accumulated in the workspace; keep a copy in the blob and leave the
+    // workspace bins at zero for the next tensor
+    const uint64_t cnt = counts_ws[s];
+    counts_ws[s] = 0;
+    tb->counts[s] = static_cast<uint32_t>(cnt);
+    if (s < 4)
+        tb->status[s] = 0;
     const uint64_t total = block_sum_u64(cnt, scratch);
     uint32_t f = 0;
     if (total > 0) {
@@ -284,6 +291,20 @@ __global__ __launch_bounds__(256) void table_kernel(TableBlock *__restrict__ tb,
     __syncthreads();
     if (f == kM)
         tb->lone = s;
+
+    // encoder constants first: the encode kernel waits for them, the decoder table is not urgent
+    EncSym e = {1u, 0xFFFFFFFFu, 0u, 0u};
+    if (f > 0) {
+        uint32_t l = 0;
+        while ((1u << l) < f)
+            ++l;                                   // l = ceil(log2 f)
+        e.magic = static_cast<uint32_t>(((static_cast<uint64_t>((1u << l) - f)) << 32) / f) + 1u;
+        e.limit = f >= kM ? 0xFFFFFFFFu : (f << 20);  // f = 4096 only for a one-symbol tensor: never renormalises
+        e.cmpl_cum = (kM - f) | (cum << 16);
+        e.shifts = (l < 1 ? l : 1u) | ((l > 0 ? l - 1 : 0u) << 8);
+    }
+    enc[s] = e;
+
     // decoder slot table: thread s fills slots [16 s, 16 s + 16); scan[t] = cum[t + 1]
     if (total > 0) {
         const uint32_t first = s * (kM / 256);
@@ -296,53 +317,73 @@ __global__ __launch_bounds__(256) void table_kernel(TableBlock *__restrict__ tb,
                 lo = mid + 1;
         }
         uint32_t t = lo;
-        for (uint32_t slot = first; slot < first + kM / 256; ++slot) {
+        uint32_t entry[kM / 256];
+#pragma unroll
+        for (uint32_t r = 0; r < kM / 256; ++r) {
+            const uint32_t slot = first + r;
             while (t < 255 && scan[t] <= slot)
                 ++t;
-            const uint32_t start = t ? scan[t - 1] : 0u;
-            tb->lut[slot] = t | (((scan[t] - start) & 0xFFFu) << 8) | ((slot - start) << 20);
+            const uint32_t begin = t ? scan[t - 1] : 0u;
+            entry[r] = t | (((scan[t] - begin) & 0xFFFu) << 8) | ((slot - begin) << 20);
         }
+        uint4 *dst = reinterpret_cast<uint4 *>(tb->lut + first);
+#pragma unroll
+        for (uint32_t r = 0; r < kM / 256; r += 4)
+            dst[r / 4] = make_uint4(entry[r], entry[r + 1], entry[r + 2], entry[r + 3]);
     }
-
-    EncSym e = {1u, 0xFFFFFFFFu, 0u, 0u};
-    if (f > 0) {
-        uint32_t l = 0;
-        while ((1u << l) < f)
-            ++l;                                   // l = ceil(log2 f)
-        e.magic = static_cast<uint32_t>(((static_cast<uint64_t>((1u << l) - f)) << 32) / f) + 1u;
-        e.limit = f >= kM ? 0xFFFFFFFFu : (f << 20);  // f = 4096 only for a one-symbol tensor: never renormalises
-        e.cmpl_cum = (kM - f) | (cum << 16);
-        e.shifts = (l < 1 ? l : 1u) | ((l > 0 ? l - 1 : 0u) << 8);
-    }
-    enc[s] = e;
 }
 
 // ------------------------------------------------------------------------------------------
 // Kernel 3: chunked rANS encoder (Sec. 2.2 "Compression algorithm").  One lane per state.
-// A state visits its symbols back to front; words it pushes out go, back to front, into its
-// own 200-word slot of the workspace, so that reading the slot's tail forwards gives the
-// decoder's order.  Final states and run lengths go straight to their place in the blob.
+// A state visits its symbols back to front; the words it pushes out are collected, back to
+// front, in a 16-word LDS ring and leave for the state's own 200-word slot of the workspace in
+// 16-byte pieces, so that the tail of the slot read forwards is the decoder's order.  Final
+// states and run lengths go straight to their place in the blob; the chunk's word count goes to
+// the workspace for the offsets scan.  The next turn's 8 bf16 words are requested before the
+// current turn is coded.
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kEncThreads = 256;
+constexpr uint32_t kRingWords = 16;  // per state; two halves of 8 words = 16 bytes
 
-__device__ inline uint32_t rans_put(uint32_t x, const EncSym e, uint16_t *slot, uint32_t &wp)
+struct EncState {
+    uint32_t x;
+    uint32_t wp;          // next free position in the slot is wp - 1 (words, counts down from kRunCap)
+};
+
+__device__ __forceinline__ void rans_put(EncState &st, const EncSym e, uint16_t *__restrict__ ring)
 {
-    if (x >= e.limit) {
-        slot[--wp] = static_cast<uint16_t>(x);
-        x >>= 16;
+    if (st.x >= e.limit) {
+        --st.wp;
+        ring[st.wp & (kRingWords - 1)] = static_cast<uint16_t>(st.x);
+        st.x >>= 16;
     }
-    const uint32_t t = __umulhi(e.magic, x);
-    const uint32_t q = (t + ((x - t) >> (e.shifts & 0xFFu))) >> (e.shifts >> 8);
-    return __umul24(q, e.cmpl_cum & 0xFFFFu) + x + (e.cmpl_cum >> 16);
+    const uint32_t t = __umulhi(e.magic, st.x);
+    const uint32_t q = (t + ((st.x - t) >> (e.shifts & 0xFFu))) >> (e.shifts >> 8);
+    st.x = __umul24(q, e.cmpl_cum & 0xFFFFu) + st.x + (e.cmpl_cum >> 16);
+}
+
+// Moves the 8-word group completed during the last turn (at most one: a turn pushes at most 8
+// words) from the ring to the slot.  Positions run down from wp_before to wp_after; group g
+// (positions 8g .. 8g+7) is complete once position 8g has been written.
+__device__ __forceinline__ void ring_flush(uint32_t wp_before, uint32_t wp_after, const uint16_t *__restrict__ ring,
+                                           uint16_t *__restrict__ slot)
+{
+    const uint32_t g = (wp_after + 7) >> 3;  // lowest group whose first position is >= wp_after
+    if (g * 8 < wp_before) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(ring + ((g * 8) & (kRingWords - 1)));
+        *reinterpret_cast<uint4 *>(slot + g * 8) = v;
+    }
 }
 
 __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__restrict__ src, uint64_t n,
                                                             uint32_t n_chunks, const EncSym *__restrict__ enc_g,
                                                             uint32_t *__restrict__ states,
                                                             uint8_t *__restrict__ lens,
+                                                            uint32_t *__restrict__ chunk_words,
                                                             uint16_t *__restrict__ slots)
 {
     __shared__ uint4 enc_raw[256];
+    __shared__ __align__(16) uint16_t rings[kEncThreads * kRingWords];
     enc_raw[threadIdx.x] = reinterpret_cast<const uint4 *>(enc_g)[threadIdx.x];
     __syncthreads();
     const EncSym *enc = reinterpret_cast<const EncSym *>(enc_raw);
@@ -354,82 +395,105 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__r
     const uint64_t base = static_cast<uint64_t>(c) * kChunk;
     const uint32_t m = (n - base) < kChunk ? static_cast<uint32_t>(n - base) : kChunk;
     uint16_t *slot = slots + static_cast<uint64_t>(lane_id) * kRunCap;
-    uint32_t wp = kRunCap;
-    uint32_t x = kRansL;
+    uint16_t *ring = rings + threadIdx.x * kRingWords;
+    EncState st = {kRansL, kRunCap};
 
     if (m == kChunk) {
         const uint4 *src4 = reinterpret_cast<const uint4 *>(src + base) + j;
+        uint4 d = src4[(kTurns - 1) * kStates];
         for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
-            const uint4 d = src4[q * kStates];
+            const uint4 d_next = src4[(q > 0 ? q - 1 : 0) * kStates];
             const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+            const uint32_t wp_before = st.wp;
 #pragma unroll
             for (int p = 3; p >= 0; --p) {
-                x = rans_put(x, enc[exponent_of(w[p] >> 16)], slot, wp);
-                x = rans_put(x, enc[exponent_of(w[p] & 0xFFFFu)], slot, wp);
+                rans_put(st, enc[exponent_of(w[p] >> 16)], ring);
+                rans_put(st, enc[exponent_of(w[p] & 0xFFFFu)], ring);
             }
+            ring_flush(wp_before, st.wp, ring, slot);
+            d = d_next;
         }
     } else {
         for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
+            const uint32_t wp_before = st.wp;
             for (int t = static_cast<int>(kRun) - 1; t >= 0; --t) {
                 const uint32_t i = static_cast<uint32_t>(q) * kTurn + j * kRun + static_cast<uint32_t>(t);
                 if (i < m)
-                    x = rans_put(x, enc[exponent_of(src[base + i])], slot, wp);
+                    rans_put(st, enc[exponent_of(src[base + i])], ring);
             }
+            ring_flush(wp_before, st.wp, ring, slot);
         }
     }
-    states[lane_id] = x;
-    lens[lane_id] = static_cast<uint8_t>(kRunCap - wp);
+    // the incomplete group at the low end: word by word
+    for (uint32_t p = st.wp; p < ((st.wp + 7) & ~7u) && p < kRunCap; ++p)
+        slot[p] = ring[p & (kRingWords - 1)];
+
+    const uint32_t len = kRunCap - st.wp;
+    states[lane_id] = st.x;
+    lens[lane_id] = static_cast<uint8_t>(len);
+    // words of the whole chunk (16 neighbouring lanes)
+    uint32_t sum = len;
+#pragma unroll
+    for (uint32_t dlt = 1; dlt < kStates; dlt <<= 1)
+        sum += __shfl_xor(sum, dlt, kStates);
+    if (j == 0)
+        chunk_words[c] = sum;
 }
 
 // ------------------------------------------------------------------------------------------
 // Kernel 4: offsets[c] = words before chunk c (exclusive prefix sum of the per-chunk totals).
-// One workgroup; each thread owns a contiguous range of chunks.
+// One workgroup walks the chunks in tiles of 4096 with coalesced 128-bit accesses.
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kScanThreads = 1024;
 
-__device__ inline uint32_t chunk_words(const uint8_t *lens, uint32_t c)
+__global__ __launch_bounds__(kScanThreads) void offsets_kernel(const uint32_t *__restrict__ chunk_words,
+                                                              uint32_t n_chunks, uint32_t *__restrict__ offsets)
 {
-    const uint4 v = reinterpret_cast<const uint4 *>(lens)[c];
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    uint32_t sum = 0;
+    __shared__ uint64_t wave_sum[kScanThreads / 64];
+    __shared__ uint64_t carry_s;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint64_t carry = 0;
+    for (uint32_t tile = 0; tile < n_chunks; tile += kScanThreads * 4) {
+        const uint32_t i0 = tile + tid * 4;
+        uint32_t v[4];
 #pragma unroll
-    for (int p = 0; p < 4; ++p)
-        sum += (w[p] & 0xFFu) + ((w[p] >> 8) & 0xFFu) + ((w[p] >> 16) & 0xFFu) + (w[p] >> 24);
-    return sum;
-}
-
-__global__ __launch_bounds__(kScanThreads) void offsets_kernel(const uint8_t *__restrict__ lens, uint32_t n_chunks,
-                                                              uint32_t *__restrict__ offsets)
-{
-    __shared__ uint64_t part[kScanThreads];
-    const uint32_t per = (n_chunks + kScanThreads - 1) / kScanThreads;
-    const uint32_t begin = threadIdx.x * per;
-    const uint32_t end = begin + per < n_chunks ? begin + per : n_chunks;
-    uint64_t mine = 0;
-    for (uint32_t c = begin; c < end; ++c)
-        mine += chunk_words(lens, c);
-    part[threadIdx.x] = mine;
-    __syncthreads();
-    for (uint32_t off = 1; off < kScanThreads; off <<= 1) {
-        const uint64_t add = threadIdx.x >= off ? part[threadIdx.x - off] : 0;
+        for (uint32_t r = 0; r < 4; ++r)
+            v[r] = i0 + r < n_chunks ? chunk_words[i0 + r] : 0u;
+        const uint64_t mine = static_cast<uint64_t>(v[0]) + v[1] + v[2] + v[3];
+        uint64_t incl = mine;  // inclusive scan over the wave
+#pragma unroll
+        for (uint32_t d = 1; d < 64; d <<= 1) {
+            const uint64_t o = __shfl_up(incl, d, 64);
+            if (lane >= d)
+                incl += o;
+        }
+        if (lane == 63)
+            wave_sum[wave] = incl;
         __syncthreads();
-        part[threadIdx.x] += add;
+        uint64_t before = carry;
+        for (uint32_t wv = 0; wv < wave; ++wv)
+            before += wave_sum[wv];
+        uint64_t run = before + incl - mine;
+#pragma unroll
+        for (uint32_t r = 0; r < 4; ++r) {
+            if (i0 + r < n_chunks)
+                offsets[i0 + r] = static_cast<uint32_t>(run);
+            run += v[r];
+        }
+        if (tid == kScanThreads - 1)
+            carry_s = run;
         __syncthreads();
+        carry = carry_s;
     }
-    uint64_t running = part[threadIdx.x] - mine;
-    for (uint32_t c = begin; c < end; ++c) {
-        offsets[c] = static_cast<uint32_t>(running);
-        running += chunk_words(lens, c);
-    }
-    if (threadIdx.x == kScanThreads - 1) {
-        offsets[n_chunks] = static_cast<uint32_t>(part[kScanThreads - 1]);
-        offsets[n_chunks + 1] = static_cast<uint32_t>(part[kScanThreads - 1] >> 32);  // overflow guard for the host
+    if (tid == 0) {
+        offsets[n_chunks] = static_cast<uint32_t>(carry);
+        offsets[n_chunks + 1] = static_cast<uint32_t>(carry >> 32);  // overflow guard for the host
     }
 }
 
 // ------------------------------------------------------------------------------------------
 // Kernel 5: gather the runs from the workspace slots into the blob's word section.
-// One wave per chunk: lanes copy run after run.
+// One wave per chunk; the 16 runs are read with all loads in flight, then written.
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kCompactThreads = 256;
 
@@ -442,14 +506,35 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const uint16_t
     const uint32_t lane = threadIdx.x & 63;
     if (c >= n_chunks)
         return;
-    uint64_t at = offsets[c];
+    const uint64_t at0 = offsets[c];
+    // run length of state (lane mod 16) and its start inside the chunk (16-lane exclusive prefix)
+    const uint32_t my_len = lens[c * kStates + (lane & 15)];
+    uint32_t start = my_len;
+#pragma unroll
+    for (uint32_t d = 1; d < kStates; d <<= 1) {
+        const uint32_t o = __shfl_up(start, d, kStates);
+        if ((lane & 15) >= d)
+            start += o;
+    }
+    start -= my_len;
+    uint16_t v[kStates];
+    uint32_t len_j[kStates], start_j[kStates];
+#pragma unroll
     for (uint32_t j = 0; j < kStates; ++j) {
-        const uint32_t id = c * kStates + j;
-        const uint32_t len = lens[id];
-        const uint16_t *from = slots + static_cast<uint64_t>(id) * kRunCap + (kRunCap - len);
-        for (uint32_t i = lane; i < len; i += 64)
-            words[at + i] = from[i];
-        at += len;
+        len_j[j] = __shfl(my_len, j, 64);
+        start_j[j] = __shfl(start, j, 64);
+        const uint16_t *from = slots + static_cast<uint64_t>(c * kStates + j) * kRunCap + (kRunCap - len_j[j]);
+        v[j] = lane < len_j[j] ? from[lane] : static_cast<uint16_t>(0);
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < kStates; ++j)
+        if (lane < len_j[j])
+            words[at0 + start_j[j] + lane] = v[j];
+    // runs longer than a wave (more than 4 bits per symbol): the rest, run by run
+    for (uint32_t j = 0; j < kStates; ++j) {
+        const uint16_t *from = slots + static_cast<uint64_t>(c * kStates + j) * kRunCap + (kRunCap - len_j[j]);
+        for (uint32_t i = lane + 64; i < len_j[j]; i += 64)
+            words[at0 + start_j[j] + i] = from[i];
     }
 }
 
@@ -765,10 +850,13 @@ inline bool is_blob(const neuzip_blob *b) { return b && b->magic == kBlobMagic; 
 struct Workspace {
     int device = -1;
     EncSym *enc = nullptr;
+    uint32_t *counts = nullptr;       // 256 histogram bins, zero between compress calls
+    uint32_t *chunk_words = nullptr;  // words per chunk, input of the offsets scan
+    uint64_t chunk_cap = 0;
     uint16_t *slots = nullptr;
     uint64_t slots_bytes = 0;
     uint32_t *pinned = nullptr;  // [0..1] total words, [2..257] counts, [258..385] freq
-    hipEvent_t idle = nullptr;   // recorded after the last kernel that reads the slots
+    hipEvent_t idle = nullptr;   // recorded after the last kernel that uses the workspace
 };
 std::mutex g_ws_mutex;
 Workspace g_ws;
@@ -789,6 +877,10 @@ int release_workspace_locked()
         }
         if (g_ws.enc)
             hipFree(g_ws.enc);
+        if (g_ws.counts)
+            hipFree(g_ws.counts);
+        if (g_ws.chunk_words)
+            hipFree(g_ws.chunk_words);
         if (g_ws.slots)
             hipFree(g_ws.slots);
         if (g_ws.pinned)
@@ -799,32 +891,50 @@ int release_workspace_locked()
     return rc;
 }
 
-int ensure_workspace(int device, uint64_t slots_bytes, hipStream_t stream)
+int ensure_workspace(int device, uint32_t n_chunks, hipStream_t stream)
 {
+    const uint64_t slots_bytes = static_cast<uint64_t>(n_chunks) * kStates * kRunCap * 2;
     if (g_ws.device != device) {
         const int rc = release_workspace_locked();
         if (rc != NEUZIP_OK)
             return rc;
         g_ws.device = device;
         NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.enc), 256 * sizeof(EncSym)));
+        NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.counts), 256 * sizeof(uint32_t)));
         NZ_HIP(hipHostMalloc(reinterpret_cast<void **>(&g_ws.pinned), 512 * sizeof(uint32_t), hipHostMallocDefault));
         NZ_HIP(hipEventCreateWithFlags(&g_ws.idle, hipEventDisableTiming));
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, stream, g_ws.counts, 0u, 256u);
+        NZ_HIP(hipGetLastError());
         NZ_HIP(hipEventRecord(g_ws.idle, stream));
     }
-    // the previous user of the slots may still be running on another stream
+    // the previous user of the workspace may still be running on another stream
     NZ_HIP(hipStreamWaitEvent(stream, g_ws.idle, 0));
-    if (g_ws.slots_bytes < slots_bytes) {
+    if (g_ws.slots_bytes < slots_bytes || g_ws.chunk_cap < n_chunks) {
         NZ_HIP(hipEventSynchronize(g_ws.idle));
-        if (g_ws.slots) {
-            NZ_HIP(hipFree(g_ws.slots));
-            g_ws.slots = nullptr;
-            g_ws.slots_bytes = 0;
+        if (g_ws.slots_bytes < slots_bytes) {
+            if (g_ws.slots) {
+                NZ_HIP(hipFree(g_ws.slots));
+                g_ws.slots = nullptr;
+                g_ws.slots_bytes = 0;
+            }
+            if (hipMalloc(reinterpret_cast<void **>(&g_ws.slots), slots_bytes) != hipSuccess) {
+                (void)hipGetLastError();
+                return NEUZIP_ENOMEM;
+            }
+            g_ws.slots_bytes = slots_bytes;
         }
-        if (hipMalloc(reinterpret_cast<void **>(&g_ws.slots), slots_bytes) != hipSuccess) {
-            (void)hipGetLastError();
-            return NEUZIP_ENOMEM;
+        if (g_ws.chunk_cap < n_chunks) {
+            if (g_ws.chunk_words) {
+                NZ_HIP(hipFree(g_ws.chunk_words));
+                g_ws.chunk_words = nullptr;
+                g_ws.chunk_cap = 0;
+            }
+            if (hipMalloc(reinterpret_cast<void **>(&g_ws.chunk_words), (static_cast<uint64_t>(n_chunks) + 4) * 4) != hipSuccess) {
+                (void)hipGetLastError();
+                return NEUZIP_ENOMEM;
+            }
+            g_ws.chunk_cap = n_chunks;
         }
-        g_ws.slots_bytes = slots_bytes;
     }
     return NEUZIP_OK;
 }
@@ -884,7 +994,7 @@ int launch_hist(const void *d_src, uint64_t n, neuzip_blob *b, hipStream_t strea
     if (groups > 2048)
         groups = 2048;
     hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(static_cast<uint32_t>(groups)), dim3(kHistThreads), 0, stream,
-                       static_cast<const uint16_t *>(d_src), n, sm_of(b), table_of(b)->counts);
+                       static_cast<const uint16_t *>(d_src), n, sm_of(b), g_ws.counts);
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
 
@@ -952,23 +1062,24 @@ int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa
         if (rc != NEUZIP_OK)
             return rc;
     }
+    bool bins_dirty = false;  // the histogram kernel ran but the table kernel did not clear the bins
     auto fail = [&](int rc) {
+        if (bins_dirty && g_ws.counts)
+            hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, stream, g_ws.counts, 0u, 256u);
         if (fresh)
             neuzip_free(b);
         return rc;
     };
 
     const uint32_t nc = b->n_chunks;
-    // table block starts from zero (counts, status); a fill kernel, not a memset node, so the
-    // call stays safe to record into a graph
-    hipLaunchKernelGGL(fill_u32_kernel, dim3((sizeof(TableBlock) / 4 + 255) / 256), dim3(256), 0, stream,
-                       reinterpret_cast<uint32_t *>(b->fixed), 0u, static_cast<uint32_t>(sizeof(TableBlock) / 4));
-    if (!hip_ok(hipGetLastError()))
-        return fail(NEUZIP_EHIP);
     b->have_counts = false;
     b->total_words = 0;
 
     if (n_elems == 0) {
+        // empty tensor: zeroed table block (a fill kernel, not a memset node, so the call stays
+        // safe to record into a graph) and a single zero offset
+        hipLaunchKernelGGL(fill_u32_kernel, dim3((sizeof(TableBlock) / 4 + 255) / 256), dim3(256), 0, stream,
+                           reinterpret_cast<uint32_t *>(b->fixed), 0u, static_cast<uint32_t>(sizeof(TableBlock) / 4));
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, stream, offsets_of(b), 0u, 2u);
         if (!hip_ok(hipGetLastError()) || !hip_ok(hipStreamSynchronize(stream)))
             return fail(NEUZIP_EHIP);
@@ -980,7 +1091,7 @@ int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa
     }
 
     std::lock_guard<std::mutex> guard(g_ws_mutex);
-    int rc = ensure_workspace(b->device, static_cast<uint64_t>(nc) * kStates * kRunCap * 2, stream);
+    int rc = ensure_workspace(b->device, nc, stream);
     if (rc != NEUZIP_OK)
         return fail(rc);
 
@@ -992,12 +1103,16 @@ int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa
     }
     if (rc != NEUZIP_OK)
         return fail(rc);
+    bins_dirty = true;
 
-    hipLaunchKernelGGL(table_kernel, dim3(1), dim3(256), 0, stream, table_of(b), g_ws.enc);
+    // the table kernel also returns the workspace histogram bins to zero
+    hipLaunchKernelGGL(table_kernel, dim3(1), dim3(256), 0, stream, g_ws.counts, table_of(b), g_ws.enc);
+    if (hip_ok(hipGetLastError()))
+        bins_dirty = false;
     hipLaunchKernelGGL(encode_kernel, dim3((nc * kStates + kEncThreads - 1) / kEncThreads), dim3(kEncThreads), 0,
                        stream, static_cast<const uint16_t *>(d_src), n_elems, nc, g_ws.enc, states_of(b), lens_of(b),
-                       g_ws.slots);
-    hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kScanThreads), 0, stream, lens_of(b), nc, offsets_of(b));
+                       g_ws.chunk_words, g_ws.slots);
+    hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kScanThreads), 0, stream, g_ws.chunk_words, nc, offsets_of(b));
     if (!hip_ok(hipGetLastError()))
         return fail(NEUZIP_EHIP);
 
