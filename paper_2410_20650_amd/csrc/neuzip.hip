@@ -580,14 +580,22 @@ __device__ __forceinline__ uint32_t merge_pair(uint64_t fields, int pair, uint32
         const uint32_t half = static_cast<uint32_t>(fields >> (32 * (pair >> 1)));
         const uint32_t twice = __builtin_amdgcn_perm(half, half, (pair & 1) ? 0x03030202u : 0x01010000u);
         return (expo << 7) | (twice & 0x807F807Fu);
+    } else if constexpr (KB == 3) {
+        // byte `pair` of the 32 field bits holds two nibbles s m2 m1 m0 (low nibble = first element).
+        // Nibbles into halfwords, then one multiply by 2^4 + 2^12 puts m at bits 6..4 and s at bit 15.
+        const uint32_t v = static_cast<uint32_t>(fields);
+        const uint32_t even = v & 0x0F0F0F0Fu, odd = (v >> 4) & 0x0F0F0F0Fu;
+        const uint32_t nib = __builtin_amdgcn_perm(odd, even, 0x0c000c00u | ((4u + pair) << 16) | pair);
+        return (expo << 7) | (__umul24(nib, 0x1010u) & 0x80708070u);
+    } else if constexpr (KB == 1) {
+        // nibble `pair` of the 16 field bits is s1 m1 s0 m0: m0 -> bit 6, s0 -> 15, m1 -> 22, s1 -> 31
+        const uint32_t f2 = (static_cast<uint32_t>(fields) >> (4 * pair)) & 0xFu;
+        const uint32_t spread = __umul24(f2 << 16, 0x1010u) + __umul24(f2, 0x4040u);
+        return (expo << 7) | (spread & 0x80408040u);
     } else {
-        constexpr uint32_t width = KB + 1;
-        constexpr uint32_t fmask = (1u << width) - 1u;
-        const uint32_t f_lo = static_cast<uint32_t>(fields >> ((2 * pair) * width)) & fmask;
-        const uint32_t f_hi = static_cast<uint32_t>(fields >> ((2 * pair + 1) * width)) & fmask;
-        const uint32_t lo = ((f_lo >> KB) << 15) | ((f_lo & ((1u << KB) - 1u)) << (7 - KB));
-        const uint32_t hi = ((f_hi >> KB) << 15) | ((f_hi & ((1u << KB) - 1u)) << (7 - KB));
-        return (expo << 7) | lo | (hi << 16);
+        // bits 2*pair and 2*pair + 1 of the 8 field bits are the two signs
+        const uint32_t v = static_cast<uint32_t>(fields);
+        return (expo << 7) | ((v << (15 - 2 * pair)) & 0x8000u) | ((v << (30 - 2 * pair)) & 0x80000000u);
     }
 }
 
