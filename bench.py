@@ -32,7 +32,7 @@ def parse_args():
     p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     p.add_argument("--extended", action="store_true", help="also time config 4 (lossy) and a config-3 sweep")
-    p.add_argument("--layers", type=int, default=2, help="layers of the Llama-3-8B-shaped sweep with --extended")
+    p.add_argument("--layers", type=int, default=32, help="decoder layers of the Llama-3-8B-shaped set used with --extended")
     return p.parse_args()
 
 
@@ -174,12 +174,14 @@ def main():
                                   "compress_GBps_input": round(out_bytes / enc_s / 1e9, 3)}
         del words, container, back, theirs
 
-    # ---------------------------------------------------------------- optional: configs 4 and 3
+    # ---------------------------------------------------------------- optional: configs 4, 3 and 5
     if args.extended:
         ext = {}
         del w, scratch, src
         nz.neuzip_free(blob)
         torch.cuda.empty_cache()
+
+        # config 4: lossy inference variant on a 70B-shaped MLP weight, heavy-tailed values
         t4 = inputs.student_t4_bf16(inputs.MLP_70B, inputs.seed_for(4), device=dev)
         n4 = t4.numel()
         buf = torch.empty(n4, dtype=torch.bfloat16, device=dev)
@@ -189,29 +191,82 @@ def main():
                 nz.neuzip_decompress(b4, buf)
             _, ms = timed_region(torch, stream, lambda: nz.neuzip_decompress(b4, buf), 50)
             ms /= 50
+            if k == 7:
+                c4 = nz.neuzip_histogram(b4).astype(np.float64)
+                p4 = c4[c4 > 0] / c4.sum()
+                ext["config4_exponent_entropy_bits"] = round(float(-(p4 * np.log2(p4)).sum()), 4)
             ext[f"config4_k{k}"] = {"decompress_GBps_output": round(2.0 * n4 / (ms * 1e-3) / 1e9, 1),
                                     "hbm_frac": round((b4.compressed_bytes + 2.0 * n4) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                                     "bits_per_weight": round(8.0 * b4.compressed_bytes / n4, 4)}
             nz.neuzip_free(b4)
         del t4, buf
         torch.cuda.empty_cache()
-        # config-3-shaped sweep over the first layers (embedding + `layers` decoder layers)
-        names = inputs.llama3_8b_tensors()[: 1 + 7 * args.layers]
+
+        # config 3: every weight of a Llama-3-8B-shaped model, forward order, one reusable scratch
+        names = inputs.llama3_8b_tensors()
+        if args.layers < 32:
+            names = names[: 1 + 7 * args.layers]
         blobs, total = [], 0
         for i, (name, shp) in enumerate(names):
             t = inputs.gaussian_bf16(shp, inputs.seed_for(3, i), device=dev)
             blobs.append(nz.neuzip_compress(t, 7))
             total += t.numel()
             del t
-        big = torch.empty(max(b.elems for b in blobs), dtype=torch.bfloat16, device=dev)
-        for _ in range(2):
-            nz.neuzip_decompress_sequence(blobs, big)
-        _, ms = timed_region(torch, stream, lambda: nz.neuzip_decompress_sequence(blobs, big), 5)
-        ms /= 5
         comp = sum(b.compressed_bytes for b in blobs)
-        ext["config3_sweep"] = {"tensors": len(blobs), "elements": total, "ms": round(ms, 4),
-                                "decompress_GBps_output": round(2.0 * total / (ms * 1e-3) / 1e9, 1),
-                                "hbm_frac": round((comp + 2.0 * total) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        big = torch.empty(max(b.elems for b in blobs), dtype=torch.bfloat16, device=dev)
+
+        def sweep_tensor_by_tensor():
+            nz.neuzip_decompress_sequence(blobs, big)
+
+        # layer schedule: the embedding, then the 7 weights of a layer in one launch into the scratch
+        groups = [[0]] + [list(range(1 + 7 * l, 8 + 7 * l)) for l in range((len(blobs) - 1) // 7)]
+        plans = []
+        for g in groups:
+            at, dsts = 0, []
+            for i in g:
+                dsts.append(big[at: at + blobs[i].elems])
+                at += (blobs[i].elems + 127) // 128 * 128
+            plans.append(([blobs[i] for i in g], dsts))
+
+        def sweep_layer_by_layer():
+            for bl, dsts in plans:
+                nz.neuzip_decompress_batch(bl, dsts)
+
+        for label, fn in (("tensor_by_tensor", sweep_tensor_by_tensor), ("layer_by_layer", sweep_layer_by_layer)):
+            for _ in range(2):
+                fn()
+            _, ms = timed_region(torch, stream, fn, 5)
+            ms /= 5
+            ext[f"config3_{label}"] = {"tensors": len(blobs), "elements": total, "ms": round(ms, 4),
+                                       "decompress_GBps_output": round(2.0 * total / (ms * 1e-3) / 1e9, 1),
+                                       "hbm_frac": round((comp + 2.0 * total) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                       "bits_per_weight": round(8.0 * comp / total, 4)}
+
+        # config 5: training-step loop on the same blobs: decompress all, synthetic update,
+        # recompress with a rebuilt histogram, bitwise check, 10 steps
+        steps5 = 10 if args.layers >= 32 else 3
+        dec_ms, enc_s = 0.0, 0.0
+        upd = torch.empty_like(big)
+        for step in range(steps5):
+            _, ms = timed_region(torch, stream, sweep_layer_by_layer, 1)
+            dec_ms += ms
+            for i, b in enumerate(blobs):
+                nelem = b.elems
+                nz.neuzip_decompress(b, big[:nelem])
+                new = inputs.synthetic_update(big[:nelem], inputs.seed_for(5, 1000 * (step + 1) + i))
+                upd[:nelem].copy_(new)
+                del new
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                nz.neuzip_compress(upd[:nelem], 7, blob=b)
+                torch.cuda.synchronize()
+                enc_s += time.perf_counter() - t0
+                nz.neuzip_decompress(b, big[:nelem])
+                assert torch.equal(big[:nelem].view(torch.int16), upd[:nelem].view(torch.int16)), "step %d" % step
+        ext["config5_loop"] = {"steps": steps5, "tensors": len(blobs),
+                               "decompress_GBps_output": round(2.0 * total * steps5 / (dec_ms * 1e-3) / 1e9, 1),
+                               "compress_GBps_input": round(2.0 * total * steps5 / enc_s / 1e9, 1),
+                               "bitwise_round_trip": "verified for every tensor at every step"}
         result["extended"] = ext
 
     print(json.dumps(result), flush=True)

@@ -110,6 +110,21 @@ int neuzip_decompress(const neuzip_blob *blob, void *d_dst, uint64_t n_elems, in
 int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, void *d_scratch,
                                uint64_t scratch_elems, void *hip_stream);
 
+/*
+ * neuzip_decompress_batch -- Sec. 2.2 Eq. (3) / Alg. 1 "decompression" + "merge" for the
+ * weights that a layer uses together (e.g. q, k, v, o, gate, up, down): blob i is
+ * decompressed to d_dsts[i], all in as few launches as possible, so that tensors too small
+ * to fill the GPU on their own overlap with the others.
+ *
+ *   blobs, d_dsts  host arrays of count entries; d_dsts[i] is a device buffer of
+ *                  neuzip_elems(blobs[i]) bf16 words, 16-byte aligned, not overlapping any
+ *                  other destination.
+ * Tensors are grouped by mantissa_bits (one launch per group of up to 8).  Never allocates,
+ * never synchronises.  On EINVAL nothing has been launched.
+ */
+int neuzip_decompress_batch(const neuzip_blob *const *blobs, void *const *d_dsts, uint32_t count,
+                            void *hip_stream);
+
 /* Releases the blob and its device memory.  NULL is a no-op. */
 void neuzip_free(neuzip_blob *blob);
 
@@ -120,7 +135,7 @@ void neuzip_free(neuzip_blob *blob);
 uint64_t neuzip_compressed_bytes(const neuzip_blob *blob);
 
 /* Bytes of device memory the blob actually holds (container sections plus
- * alignment padding and the derived cumulative table). */
+ * alignment padding and the derived cumulative and slot tables). */
 uint64_t neuzip_device_bytes(const neuzip_blob *blob);
 
 /* Element count and mantissa bits the blob was made with. */

@@ -37,6 +37,8 @@ def _load():
     lib.neuzip_decompress.restype = i32
     lib.neuzip_decompress_sequence.argtypes = [vpp, u32, vp, u64, vp]
     lib.neuzip_decompress_sequence.restype = i32
+    lib.neuzip_decompress_batch.argtypes = [vpp, vpp, u32, vp]
+    lib.neuzip_decompress_batch.restype = i32
     lib.neuzip_free.argtypes = [vp]
     lib.neuzip_free.restype = None
     lib.neuzip_compressed_bytes.argtypes = [vp]
@@ -69,7 +71,8 @@ def _load():
 _lib = None
 _lib = _load()
 
-EXPORTED = ["neuzip_compress", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_free",
+EXPORTED = ["neuzip_compress", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
+            "neuzip_free",
             "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits",
             "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check",
             "neuzip_release_workspace", "neuzip_strerror", "neuzip_last_hip_error"]
@@ -153,6 +156,18 @@ def neuzip_decompress_sequence(blobs, scratch: torch.Tensor, stream=None) -> Non
                                          scratch.numel(), _stream_handle(stream))
     if rc != OK:
         raise NeuzipError(rc, "neuzip_decompress_sequence")
+
+
+def neuzip_decompress_batch(blobs, dsts, stream=None) -> None:
+    for d in dsts:
+        _check_tensor(d)
+    if len(blobs) != len(dsts) or any(b.elems != d.numel() for b, d in zip(blobs, dsts)):
+        raise ValueError("one destination of matching size per blob")
+    arr = (ctypes.c_void_p * len(blobs))(*[b.handle.value for b in blobs])
+    ptrs = (ctypes.c_void_p * len(dsts))(*[d.data_ptr() for d in dsts])
+    rc = _lib.neuzip_decompress_batch(arr, ptrs, len(blobs), _stream_handle(stream))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_decompress_batch")
 
 
 def neuzip_free(blob: Blob) -> None:

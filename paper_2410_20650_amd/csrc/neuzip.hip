@@ -689,23 +689,36 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
     }
 }
 
-template <int KB>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(const TableBlock *__restrict__ tb,
-                                                            const uint32_t *__restrict__ offsets,
-                                                            const uint32_t *__restrict__ states,
-                                                            const uint8_t *__restrict__ lens,
-                                                            const uint16_t *__restrict__ words,
-                                                            const uint8_t *__restrict__ sm,
-                                                            uint16_t *__restrict__ out, uint64_t n,
-                                                            uint32_t n_chunks, uint32_t *__restrict__ status)
-{
-    __shared__ __align__(16) uint32_t lut[kM];
-    __shared__ __align__(16) uint8_t stage[kStageBytes];
+// What the decoder needs to know about one tensor (all device pointers).
+struct DecodeArgs {
+    const TableBlock *tb;
+    const uint32_t *offsets;
+    const uint32_t *states;
+    const uint8_t *lens;
+    const uint16_t *words;
+    const uint8_t *sm;
+    uint16_t *out;
+    uint32_t *status;
+    uint64_t n;
+    uint32_t n_chunks;
+    uint32_t wg_end;  // batches: first workgroup index after this tensor's
+};
 
+// Decodes the chunks of workgroup `wg` of one tensor.
+template <int KB>
+__device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ tb,
+                                                 const uint32_t *__restrict__ offsets,
+                                                 const uint32_t *__restrict__ states,
+                                                 const uint8_t *__restrict__ lens,
+                                                 const uint16_t *__restrict__ words,
+                                                 const uint8_t *__restrict__ sm, uint16_t *__restrict__ out,
+                                                 uint64_t n, uint32_t n_chunks, uint32_t *__restrict__ status,
+                                                 uint32_t wg, uint32_t *__restrict__ lut, uint8_t *__restrict__ stage)
+{
     const uint32_t tid = threadIdx.x;
     const uint32_t threads = blockDim.x;            // a multiple of 64, at most kDecThreads
     const uint32_t chunks_per_wg = threads / kStates;
-    const uint32_t c0 = blockIdx.x * chunks_per_wg;
+    const uint32_t c0 = wg * chunks_per_wg;
     const uint32_t c1 = c0 + chunks_per_wg < n_chunks ? c0 + chunks_per_wg : n_chunks;
     const uint32_t c = c0 + tid / kStates;
     const uint32_t j = tid % kStates;
@@ -785,6 +798,38 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(const TableBlock *_
     // a well-formed run is consumed exactly and leaves the state where the encoder started
     if (x != kRansL || wp - wp_begin != 2 * len)
         atomicOr(status, 1u);
+}
+
+template <int KB>
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(const DecodeArgs a)
+{
+    __shared__ __align__(16) uint32_t lut[kM];
+    __shared__ __align__(16) uint8_t stage[kStageBytes];
+    decode_workgroup<KB>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.out, a.n, a.n_chunks, a.status,
+                         blockIdx.x, lut, stage);
+}
+
+// Several tensors in one launch (a layer's weights): workgroups [t[i-1].wg_end, t[i].wg_end)
+// belong to tensor i.  Small tensors, which alone cannot fill the chip, overlap with the others.
+constexpr uint32_t kBatchMax = 8;
+struct BatchArgs {
+    DecodeArgs t[kBatchMax];
+    uint32_t count;
+};
+
+template <int KB>
+__global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchArgs b)
+{
+    __shared__ __align__(16) uint32_t lut[kM];
+    __shared__ __align__(16) uint8_t stage[kStageBytes];
+    uint32_t i = 0, first = 0;
+    while (i + 1 < b.count && blockIdx.x >= b.t[i].wg_end) {
+        first = b.t[i].wg_end;
+        ++i;
+    }
+    const DecodeArgs &a = b.t[i];
+    decode_workgroup<KB>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.out, a.n, a.n_chunks, a.status,
+                         blockIdx.x - first, lut, stage);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1020,14 +1065,29 @@ uint32_t decode_chunks_per_wg()
     return forced > 0 ? static_cast<uint32_t>(forced) : kDecChunksPerWg;
 }
 
+DecodeArgs decode_args(const neuzip_blob *b, void *d_dst)
+{
+    DecodeArgs a;
+    a.tb = table_of(b);
+    a.offsets = offsets_of(b);
+    a.states = states_of(b);
+    a.lens = lens_of(b);
+    a.words = reinterpret_cast<const uint16_t *>(b->words);
+    a.sm = sm_of(b);
+    a.out = static_cast<uint16_t *>(d_dst);
+    a.status = table_of(b)->status;
+    a.n = b->n;
+    a.n_chunks = b->n_chunks;
+    a.wg_end = 0;
+    return a;
+}
+
 template <int KB>
 int launch_decode(const neuzip_blob *b, void *d_dst, hipStream_t stream)
 {
     const uint32_t per = decode_chunks_per_wg();
     const uint32_t groups = (b->n_chunks + per - 1) / per;
-    hipLaunchKernelGGL(decode_kernel<KB>, dim3(groups), dim3(per * kStates), 0, stream, table_of(b), offsets_of(b),
-                       states_of(b), lens_of(b), reinterpret_cast<const uint16_t *>(b->words), sm_of(b),
-                       static_cast<uint16_t *>(d_dst), b->n, b->n_chunks, table_of(b)->status);
+    hipLaunchKernelGGL(decode_kernel<KB>, dim3(groups), dim3(per * kStates), 0, stream, decode_args(b, d_dst));
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
 
@@ -1041,6 +1101,18 @@ int decode_dispatch(const neuzip_blob *b, void *d_dst, hipStream_t stream)
     case 1: return launch_decode<1>(b, d_dst, stream);
     default: return launch_decode<0>(b, d_dst, stream);
     }
+}
+
+int launch_batch(const BatchArgs &args, int k, uint32_t groups, hipStream_t stream)
+{
+    const dim3 grid(groups), block(kDecThreads);
+    switch (k) {
+    case 7: hipLaunchKernelGGL(decode_batch_kernel<7>, grid, block, 0, stream, args); break;
+    case 3: hipLaunchKernelGGL(decode_batch_kernel<3>, grid, block, 0, stream, args); break;
+    case 1: hipLaunchKernelGGL(decode_batch_kernel<1>, grid, block, 0, stream, args); break;
+    default: hipLaunchKernelGGL(decode_batch_kernel<0>, grid, block, 0, stream, args); break;
+    }
+    return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
 
 }  // namespace
@@ -1174,6 +1246,46 @@ int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, 
         const int rc = decode_dispatch(blobs[i], d_scratch, static_cast<hipStream_t>(hip_stream));
         if (rc != NEUZIP_OK)
             return rc;
+    }
+    return NEUZIP_OK;
+}
+
+int neuzip_decompress_batch(const neuzip_blob *const *blobs, void *const *d_dsts, uint32_t count, void *hip_stream)
+{
+    if (count > 0 && (!blobs || !d_dsts))
+        return NEUZIP_EINVAL;
+    for (uint32_t i = 0; i < count; ++i) {
+        if (!is_blob(blobs[i]))
+            return NEUZIP_EINVAL;
+        if (blobs[i]->n > 0 && (!d_dsts[i] || (reinterpret_cast<uintptr_t>(d_dsts[i]) & 15u)))
+            return NEUZIP_EINVAL;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // tensors of equal mantissa_bits share launches of up to kBatchMax tensors, in the given order
+    static const int ks[4] = {7, 3, 1, 0};
+    for (int k : ks) {
+        BatchArgs args;
+        args.count = 0;
+        uint32_t groups = 0;
+        for (uint32_t i = 0; i <= count; ++i) {
+            const bool flush = (i == count) || (args.count == kBatchMax);
+            if (flush && args.count > 0) {
+                const int rc = launch_batch(args, k, groups, stream);
+                if (rc != NEUZIP_OK)
+                    return rc;
+                args.count = 0;
+                groups = 0;
+            }
+            if (i == count)
+                break;
+            const neuzip_blob *b = blobs[i];
+            if (b->k != k || b->n == 0)
+                continue;
+            DecodeArgs a = decode_args(b, d_dsts[i]);
+            groups += (b->n_chunks + kDecChunksPerWg - 1) / kDecChunksPerWg;
+            a.wg_end = groups;
+            args.t[args.count++] = a;
+        }
     }
     return NEUZIP_OK;
 }

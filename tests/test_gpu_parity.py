@@ -162,6 +162,35 @@ def test_forward_schedule_into_one_scratch(nz):
         nz.neuzip_decompress_sequence(blobs, small)
 
 
+def test_batch_of_a_layer_in_one_launch(nz):
+    # the weights a layer uses together, mixed sizes and precisions, ragged tails, an empty tensor
+    shapes = [(256, 512), (64, 512), (64, 515), (256, 512), (896, 256), (896, 256), (256, 896), (3, 7), (0,),
+              (1024, 1024), (33, 4096)]
+    ks = [7, 7, 3, 7, 7, 0, 7, 1, 7, 7, 3]
+    tensors = [inputs.gaussian_bf16(s, inputs.seed_for(3, 50 + i), device=DEV) for i, s in enumerate(shapes)]
+    blobs = [nz.neuzip_compress(t, k) for t, k in zip(tensors, ks)]
+    # one scratch buffer holds the whole layer: destinations are consecutive 256-byte aligned pieces
+    sizes = [(t.numel() + 127) // 128 * 128 for t in tensors]
+    scratch = torch.full((sum(sizes),), float("nan"), dtype=torch.bfloat16, device=DEV)
+    dsts, at = [], 0
+    for t, size in zip(tensors, sizes):
+        dsts.append(scratch[at: at + t.numel()])
+        at += size
+    nz.neuzip_decompress_batch(blobs, dsts)
+    for t, k, d, b in zip(tensors, ks, dsts, blobs):
+        assert np.array_equal(inputs.bits(d), O.truncate(inputs.bits(t), k))
+        nz.neuzip_check(b)
+    # nothing outside the destinations was touched
+    at = 0
+    for t, size in zip(tensors, sizes):
+        assert torch.isnan(scratch[at + t.numel(): at + size].float()).all()
+        at += size
+    with pytest.raises(ValueError):
+        nz.neuzip_decompress_batch(blobs[:2], dsts[:1])
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_decompress_batch(blobs[:1], [scratch[1:1 + tensors[0].numel()]])   # misaligned
+
+
 def test_other_stream(nz):
     s = torch.cuda.Stream()
     w = inputs.gaussian_bf16(300_000, 3, device=DEV)
