@@ -236,8 +236,15 @@ __device__ inline uint64_t block_sum_u64(uint64_t v, uint64_t *scratch)
     return scratch[0] + scratch[1] + scratch[2] + scratch[3];
 }
 
+// Host-visible record of one compress call (pinned host memory the kernels write directly).
+struct HostRecord {
+    uint32_t total_words[2];
+    uint32_t counts[256];
+    uint16_t freq[256];
+};
+
 __global__ __launch_bounds__(256) void table_kernel(uint32_t *__restrict__ counts_ws, TableBlock *__restrict__ tb,
-                                                    EncSym *__restrict__ enc)
+                                                    EncSym *__restrict__ enc, HostRecord *__restrict__ record)
 {
     __shared__ uint64_t scratch[4];
     __shared__ uint32_t scan[256];
@@ -247,6 +254,7 @@ __global__ __launch_bounds__(256) void table_kernel(uint32_t *__restrict__ count
     const uint64_t cnt = counts_ws[s];
     counts_ws[s] = 0;
     tb->counts[s] = static_cast<uint32_t>(cnt);
+    record->counts[s] = static_cast<uint32_t>(cnt);
     if (s < 4)
         tb->status[s] = 0;
     const uint64_t total = block_sum_u64(cnt, scratch);
@@ -283,6 +291,7 @@ __global__ __launch_bounds__(256) void table_kernel(uint32_t *__restrict__ count
     }
     const uint32_t cum = scan[s] - f;
     tb->freq[s] = static_cast<uint16_t>(f);
+    record->freq[s] = static_cast<uint16_t>(f);
     tb->cum[s] = static_cast<uint16_t>(cum);
     if (s == 255)
         tb->cum[256] = static_cast<uint16_t>(scan[255]);
@@ -447,7 +456,8 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__r
 constexpr uint32_t kScanThreads = 1024;
 
 __global__ __launch_bounds__(kScanThreads) void offsets_kernel(const uint32_t *__restrict__ chunk_words,
-                                                              uint32_t n_chunks, uint32_t *__restrict__ offsets)
+                                                              uint32_t n_chunks, uint32_t *__restrict__ offsets,
+                                                              HostRecord *__restrict__ record)
 {
     __shared__ uint64_t wave_sum[kScanThreads / 64];
     __shared__ uint64_t carry_s;
@@ -487,7 +497,9 @@ __global__ __launch_bounds__(kScanThreads) void offsets_kernel(const uint32_t *_
     }
     if (tid == 0) {
         offsets[n_chunks] = static_cast<uint32_t>(carry);
-        offsets[n_chunks + 1] = static_cast<uint32_t>(carry >> 32);  // overflow guard for the host
+        offsets[n_chunks + 1] = 0;
+        record->total_words[0] = static_cast<uint32_t>(carry);
+        record->total_words[1] = static_cast<uint32_t>(carry >> 32);  // non-zero: too long for 32-bit offsets
     }
 }
 
@@ -908,7 +920,7 @@ struct Workspace {
     uint64_t chunk_cap = 0;
     uint16_t *slots = nullptr;
     uint64_t slots_bytes = 0;
-    uint32_t *pinned = nullptr;  // [0..1] total words, [2..257] counts, [258..385] freq
+    HostRecord *pinned = nullptr;  // pinned host memory, written by the table and offsets kernels
     hipEvent_t idle = nullptr;   // recorded after the last kernel that uses the workspace
 };
 std::mutex g_ws_mutex;
@@ -954,7 +966,7 @@ int ensure_workspace(int device, uint32_t n_chunks, hipStream_t stream)
         g_ws.device = device;
         NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.enc), 256 * sizeof(EncSym)));
         NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.counts), 256 * sizeof(uint32_t)));
-        NZ_HIP(hipHostMalloc(reinterpret_cast<void **>(&g_ws.pinned), 512 * sizeof(uint32_t), hipHostMallocDefault));
+        NZ_HIP(hipHostMalloc(reinterpret_cast<void **>(&g_ws.pinned), sizeof(HostRecord), hipHostMallocDefault));
         NZ_HIP(hipEventCreateWithFlags(&g_ws.idle, hipEventDisableTiming));
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, stream, g_ws.counts, 0u, 256u);
         NZ_HIP(hipGetLastError());
@@ -1041,11 +1053,13 @@ template <int KB>
 int launch_hist(const void *d_src, uint64_t n, neuzip_blob *b, hipStream_t stream)
 {
     const uint64_t n_vec = n / 8;
-    uint64_t groups = (n_vec + kHistThreads - 1) / kHistThreads;
+    // every workgroup pays for clearing and merging its 32 KB of bins: give it at least 8 vectors
+    // (64 elements) per thread, and launch no more workgroups than fit the chip at once
+    uint64_t groups = (n_vec + kHistThreads * 8 - 1) / (kHistThreads * 8);
     if (groups < 1)
         groups = 1;
-    if (groups > 2048)
-        groups = 2048;
+    if (groups > 1280)
+        groups = 1280;
     hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(static_cast<uint32_t>(groups)), dim3(kHistThreads), 0, stream,
                        static_cast<const uint16_t *>(d_src), n, sm_of(b), g_ws.counts);
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
@@ -1186,27 +1200,26 @@ int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa
     bins_dirty = true;
 
     // the table kernel also returns the workspace histogram bins to zero
-    hipLaunchKernelGGL(table_kernel, dim3(1), dim3(256), 0, stream, g_ws.counts, table_of(b), g_ws.enc);
+    hipLaunchKernelGGL(table_kernel, dim3(1), dim3(256), 0, stream, g_ws.counts, table_of(b), g_ws.enc, g_ws.pinned);
     if (hip_ok(hipGetLastError()))
         bins_dirty = false;
     hipLaunchKernelGGL(encode_kernel, dim3((nc * kStates + kEncThreads - 1) / kEncThreads), dim3(kEncThreads), 0,
                        stream, static_cast<const uint16_t *>(d_src), n_elems, nc, g_ws.enc, states_of(b), lens_of(b),
                        g_ws.chunk_words, g_ws.slots);
-    hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kScanThreads), 0, stream, g_ws.chunk_words, nc, offsets_of(b));
+    hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kScanThreads), 0, stream, g_ws.chunk_words, nc, offsets_of(b),
+                       g_ws.pinned);
     if (!hip_ok(hipGetLastError()))
         return fail(NEUZIP_EHIP);
 
-    // the stream length is data dependent: read it (and the statistics) back once
-    if (!hip_ok(hipMemcpyAsync(g_ws.pinned, offsets_of(b) + nc, 8, hipMemcpyDeviceToHost, stream)) ||
-        !hip_ok(hipMemcpyAsync(g_ws.pinned + 2, table_of(b)->counts, 1024, hipMemcpyDeviceToHost, stream)) ||
-        !hip_ok(hipMemcpyAsync(g_ws.pinned + 258, table_of(b)->freq, 512, hipMemcpyDeviceToHost, stream)) ||
-        !hip_ok(hipStreamSynchronize(stream)))
+    // the stream length is data dependent: wait for it (and the statistics), which the kernels
+    // have written straight into pinned host memory
+    if (!hip_ok(hipStreamSynchronize(stream)))
         return fail(NEUZIP_EHIP);
-    if (g_ws.pinned[1] != 0)
+    if (g_ws.pinned->total_words[1] != 0)
         return fail(NEUZIP_EUNSUPPORTED);  // more than 2^32 words
-    const uint64_t total_words = g_ws.pinned[0];
-    std::memcpy(b->h_counts, g_ws.pinned + 2, 1024);
-    std::memcpy(b->h_freq, g_ws.pinned + 258, 512);
+    const uint64_t total_words = g_ws.pinned->total_words[0];
+    std::memcpy(b->h_counts, g_ws.pinned->counts, 1024);
+    std::memcpy(b->h_freq, g_ws.pinned->freq, 512);
     b->have_counts = true;
 
     rc = reserve_words(b, total_words);
