@@ -14,6 +14,7 @@ per-layer sweep.
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -32,6 +33,8 @@ def parse_args():
     p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     p.add_argument("--extended", action="store_true", help="also time config 4 (lossy) and a config-3 sweep")
+    p.add_argument("--sweep", action="store_true",
+                   help="also time compress/decompress against matrix size, 1e5..1e8 bytes (the axis of the paper's Fig. 4)")
     p.add_argument("--layers", type=int, default=32, help="decoder layers of the Llama-3-8B-shaped set used with --extended")
     return p.parse_args()
 
@@ -268,6 +271,45 @@ def main():
                                "compress_GBps_input": round(2.0 * total * steps5 / enc_s / 1e9, 1),
                                "bitwise_round_trip": "verified for every tensor at every step"}
         result["extended"] = ext
+
+    # ---------------------------------------------------------------- optional: size sweep (Fig. 4's axis)
+    if args.sweep:
+        rows = []
+        for nbytes in (1e5, 3e5, 1e6, 3e6, 1e7, 3e7, 1e8):
+            ne = int(nbytes) // 2 // 8 * 8
+            t = inputs.gaussian_bf16(ne, inputs.seed_for(6, int(math.log10(nbytes) * 10)), device=dev)
+            o = torch.empty_like(t)
+            row = {"bytes": 2 * ne}
+            gib = 2.0 * ne / 2 ** 30
+            for k in (7, 3):
+                bk = nz.neuzip_compress(t, k)
+                for _ in range(3):
+                    nz.neuzip_decompress(bk, o)
+                _, ms = timed_region(torch, stream, lambda: nz.neuzip_decompress(bk, o), 50)
+                row[f"decompress_k{k}_GiBps"] = round(gib / (ms / 50 * 1e-3), 1)
+                for _ in range(2):
+                    nz.neuzip_compress(t, k, blob=bk)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(10):
+                    nz.neuzip_compress(t, k, blob=bk)
+                torch.cuda.synchronize()
+                row[f"compress_k{k}_GiBps"] = round(gib / ((time.perf_counter() - t0) / 10), 1)
+                nz.neuzip_free(bk)
+            _, ms = timed_region(torch, stream, lambda: o.copy_(t), 50)
+            row["device_copy_GiBps"] = round(gib / (ms / 50 * 1e-3), 1)
+            # the paper's CPU-offloading baseline: the matrix leaves for pinned host memory and comes back
+            host = torch.empty(ne, dtype=torch.bfloat16, pin_memory=True)
+            for _ in range(2):
+                host.copy_(t, non_blocking=True)
+                o.copy_(host, non_blocking=True)
+            _, ms_out = timed_region(torch, stream, lambda: host.copy_(t, non_blocking=True), 10)
+            _, ms_in = timed_region(torch, stream, lambda: o.copy_(host, non_blocking=True), 10)
+            row["offload_to_host_GiBps"] = round(gib / (ms_out / 10 * 1e-3), 1)
+            row["reload_from_host_GiBps"] = round(gib / (ms_in / 10 * 1e-3), 1)
+            rows.append(row)
+            del t, o, host
+        result["size_sweep"] = rows
 
     print(json.dumps(result), flush=True)
 
