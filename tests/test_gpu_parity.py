@@ -191,6 +191,39 @@ def test_batch_of_a_layer_in_one_launch(nz):
         nz.neuzip_decompress_batch(blobs[:1], [scratch[1:1 + tensors[0].numel()]])   # misaligned
 
 
+def test_decompression_can_be_captured_in_a_hip_graph(nz):
+    # decompress allocates nothing and records no memset node, so a per-layer schedule can be
+    # captured once and replayed; every replay is checked against the eager result, with eager
+    # work and synchronisation in between
+    shapes = [(300, 512), (64, 512), (1000, 1000)]
+    tensors = [inputs.gaussian_bf16(s, inputs.seed_for(3, 80 + i), device=DEV) for i, s in enumerate(shapes)]
+    blobs = [nz.neuzip_compress(t, 7) for t in tensors]
+    outs = [torch.zeros(t.numel(), dtype=torch.bfloat16, device=DEV) for t in tensors]
+    scratch = torch.zeros(max(t.numel() for t in tensors), dtype=torch.bfloat16, device=DEV)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        nz.neuzip_decompress_batch(blobs, outs, stream=side)          # warm up outside the capture
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            nz.neuzip_decompress_batch(blobs, outs, stream=side)
+            nz.neuzip_decompress_sequence(blobs, scratch, stream=side)
+    for replay in range(4):
+        for o in outs:
+            o.fill_(float(replay))                                    # eager work between replays
+        scratch.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, o in zip(tensors, outs):
+            assert torch.equal(o.view(torch.int16), t.reshape(-1).view(torch.int16)), replay
+        last = tensors[-1]
+        assert torch.equal(scratch[: last.numel()].view(torch.int16), last.reshape(-1).view(torch.int16))
+    for b in blobs:
+        nz.neuzip_check(b)
+
+
 def test_other_stream(nz):
     s = torch.cuda.Stream()
     w = inputs.gaussian_bf16(300_000, 3, device=DEV)
