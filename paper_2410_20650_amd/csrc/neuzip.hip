@@ -20,6 +20,7 @@
 
 #include <cstdint>
 #include <cstdlib>
+#include <chrono>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -91,15 +92,17 @@ struct TableBlock {
 static_assert(sizeof(TableBlock) % 256 == 0, "table block keeps later sections aligned");
 
 // Per-symbol encoder constants (16 bytes, one ds_read_b128).
-//   magic/sh1/sh2: division by the frequency f by multiplication (Granlund & Montgomery's
-//   round-up method for 32-bit dividends): t = mulhi(magic, x); q = (t + ((x - t) >> sh1)) >> sh2.
-//   limit: the state is renormalised before the step when x >= limit = f << 20.
-//   The step itself is x <- (x / f) * M + (x mod f) + cum = q * (M - f) + x + cum.
+//   The step is x <- (x / f) * M + (x mod f) + cum = q * (M - f) + x + cum with q = floor(x / f).
+//   limit: the state is renormalised before the step when x >= limit = f << 20, so q < 2^20.
+//   rcp: a float slightly below 1/f, (1/f)(1 - 2^-21).  float(x) * rcp, truncated, is q or q - 1
+//   (three roundings of 2^-24 cannot overcome the 2^-21 bias, and q * 1.5 * 2^-21 < 1); one
+//   compare of the remainder against f settles it.  All of this runs at full VALU rate, unlike a
+//   32-bit multiply-high.
 struct EncSym {
-    uint32_t magic;
+    float rcp;
     uint32_t limit;
     uint32_t cmpl_cum;  // (M - f) | cum << 16
-    uint32_t shifts;    // sh1 | sh2 << 8
+    uint32_t f;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -157,19 +160,33 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const uint16_t
     const uint64_t n_vec = n / 8;
     const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kHistThreads;
     const uint4 *src4 = reinterpret_cast<const uint4 *>(src);
-    for (uint64_t v = static_cast<uint64_t>(blockIdx.x) * kHistThreads + threadIdx.x; v < n_vec; v += stride) {
-        const uint4 d = src4[v];
-        const uint32_t w[4] = {d.x, d.y, d.z, d.w};
-        uint64_t packed = 0;
+    // four 128-bit loads are in flight per lane before any of them is used
+    constexpr uint32_t kDepth = 4;
+    for (uint64_t v0 = static_cast<uint64_t>(blockIdx.x) * kHistThreads + threadIdx.x; v0 < n_vec;
+         v0 += stride * kDepth) {
+        uint4 d[kDepth];
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const uint32_t lo = w[p] & 0xFFFFu, hi = w[p] >> 16;
-            atomicAdd(&bins[exponent_of(lo) * kHistCopies + copy], 1u);
-            atomicAdd(&bins[exponent_of(hi) * kHistCopies + copy], 1u);
-            packed |= static_cast<uint64_t>(signmant_field<KB>(lo)) << ((2 * p) * (KB + 1));
-            packed |= static_cast<uint64_t>(signmant_field<KB>(hi)) << ((2 * p + 1) * (KB + 1));
+        for (uint32_t r = 0; r < kDepth; ++r) {
+            const uint64_t v = v0 + r * stride;
+            d[r] = v < n_vec ? src4[v] : make_uint4(0, 0, 0, 0);
         }
-        store_fields<KB>(sm, v, packed);
+#pragma unroll
+        for (uint32_t r = 0; r < kDepth; ++r) {
+            const uint64_t v = v0 + r * stride;
+            if (v >= n_vec)
+                break;
+            const uint32_t w[4] = {d[r].x, d[r].y, d[r].z, d[r].w};
+            uint64_t packed = 0;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t lo = w[p] & 0xFFFFu, hi = w[p] >> 16;
+                atomicAdd(&bins[exponent_of(lo) * kHistCopies + copy], 1u);
+                atomicAdd(&bins[exponent_of(hi) * kHistCopies + copy], 1u);
+                packed |= static_cast<uint64_t>(signmant_field<KB>(lo)) << ((2 * p) * (KB + 1));
+                packed |= static_cast<uint64_t>(signmant_field<KB>(hi)) << ((2 * p + 1) * (KB + 1));
+            }
+            store_fields<KB>(sm, v, packed);
+        }
     }
     // ragged tail (n mod 8 elements): one thread, element by element
     if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -238,13 +255,15 @@ __device__ inline uint64_t block_sum_u64(uint64_t v, uint64_t *scratch)
 
 // Host-visible record of one compress call (pinned host memory the kernels write directly).
 struct HostRecord {
+    uint32_t seq;  // stamp of the compress call whose results are complete (written last)
+    uint32_t pad;
     uint32_t total_words[2];
     uint32_t counts[256];
     uint16_t freq[256];
 };
 
 __global__ __launch_bounds__(256) void table_kernel(uint32_t *__restrict__ counts_ws, TableBlock *__restrict__ tb,
-                                                    EncSym *__restrict__ enc, HostRecord *__restrict__ record)
+                                                    EncSym *__restrict__ enc)
 {
     __shared__ uint64_t scratch[4];
     __shared__ uint32_t scan[256];
@@ -254,7 +273,6 @@ __global__ __launch_bounds__(256) void table_kernel(uint32_t *__restrict__ count
     const uint64_t cnt = counts_ws[s];
     counts_ws[s] = 0;
     tb->counts[s] = static_cast<uint32_t>(cnt);
-    record->counts[s] = static_cast<uint32_t>(cnt);
     if (s < 4)
         tb->status[s] = 0;
     const uint64_t total = block_sum_u64(cnt, scratch);
@@ -272,7 +290,20 @@ __global__ __launch_bounds__(256) void table_kernel(uint32_t *__restrict__ count
             if (key == best)
                 f += static_cast<uint32_t>(rest);
         }
-        while (rest < 0) {  // uniform across the workgroup
+        if (rest < 0) {
+            // Usual case: the most frequent symbol stays the largest through all -rest decrements
+            // (its key after -rest - 1 of them still beats the runner-up's), so it takes them all.
+            const uint64_t key = (static_cast<uint64_t>(f) << 8) | (255u - s);
+            const uint64_t best = block_max_u64(key, scratch);
+            const uint64_t second = block_max_u64(key == best ? 0 : key, scratch);
+            const uint64_t best_late = best - (static_cast<uint64_t>(-rest - 1) << 8);
+            if ((best >> 8) >= static_cast<uint64_t>(-rest) && best_late > second) {
+                if (key == best)
+                    f -= static_cast<uint32_t>(-rest);
+                rest = 0;
+            }
+        }
+        while (rest < 0) {  // general case, one unit at a time; uniform across the workgroup
             const uint64_t key = (static_cast<uint64_t>(f) << 8) | (255u - s);
             const uint64_t best = block_max_u64(key, scratch);
             if (key == best)
@@ -280,18 +311,26 @@ __global__ __launch_bounds__(256) void table_kernel(uint32_t *__restrict__ count
             ++rest;
         }
     }
-    // exclusive cumulative sum over the 256 symbols
-    scan[s] = f;
-    __syncthreads();
-    for (uint32_t off = 1; off < 256; off <<= 1) {
-        const uint32_t add = s >= off ? scan[s - off] : 0;
+    // inclusive cumulative sum over the 256 symbols: wave scan, then the sums of the waves before
+    {
+        uint32_t incl = f;
+#pragma unroll
+        for (uint32_t d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(incl, d, 64);
+            if ((s & 63u) >= d)
+                incl += o;
+        }
         __syncthreads();
-        scan[s] += add;
+        if ((s & 63u) == 63u)
+            scratch[s >> 6] = incl;
         __syncthreads();
+        for (uint32_t wv = 0; wv < (s >> 6); ++wv)
+            incl += static_cast<uint32_t>(scratch[wv]);
+        scan[s] = incl;
     }
+    __syncthreads();
     const uint32_t cum = scan[s] - f;
     tb->freq[s] = static_cast<uint16_t>(f);
-    record->freq[s] = static_cast<uint16_t>(f);
     tb->cum[s] = static_cast<uint16_t>(cum);
     if (s == 255)
         tb->cum[256] = static_cast<uint16_t>(scan[255]);
@@ -302,43 +341,41 @@ __global__ __launch_bounds__(256) void table_kernel(uint32_t *__restrict__ count
         tb->lone = s;
 
     // encoder constants first: the encode kernel waits for them, the decoder table is not urgent
-    EncSym e = {1u, 0xFFFFFFFFu, 0u, 0u};
+    EncSym e = {0.0f, 0xFFFFFFFFu, 0u, 1u};
     if (f > 0) {
-        uint32_t l = 0;
-        while ((1u << l) < f)
-            ++l;                                   // l = ceil(log2 f)
-        e.magic = static_cast<uint32_t>(((static_cast<uint64_t>((1u << l) - f)) << 32) / f) + 1u;
+        e.rcp = __fmul_rn(__fdiv_rn(1.0f, static_cast<float>(f)), 1.0f - 0x1p-21f);
         e.limit = f >= kM ? 0xFFFFFFFFu : (f << 20);  // f = 4096 only for a one-symbol tensor: never renormalises
         e.cmpl_cum = (kM - f) | (cum << 16);
-        e.shifts = (l < 1 ? l : 1u) | ((l > 0 ? l - 1 : 0u) << 8);
+        e.f = f;
     }
     enc[s] = e;
 
-    // decoder slot table: thread s fills slots [16 s, 16 s + 16); scan[t] = cum[t + 1]
+    // decoder slot table: thread s fills slots s, s + 256, ...; scan[t] = cum[t + 1].  The 16
+    // binary searches of a thread are independent, so their LDS reads overlap.
     if (total > 0) {
-        const uint32_t first = s * (kM / 256);
-        uint32_t lo = 0, hi = 255;  // smallest t with cum[t + 1] > first
-        while (lo < hi) {
-            const uint32_t mid = (lo + hi) >> 1;
-            if (scan[mid] > first)
-                hi = mid;
-            else
-                lo = mid + 1;
-        }
-        uint32_t t = lo;
-        uint32_t entry[kM / 256];
+        constexpr uint32_t kPer = kM / 256;
+        uint32_t lo[kPer], hi[kPer];
 #pragma unroll
-        for (uint32_t r = 0; r < kM / 256; ++r) {
-            const uint32_t slot = first + r;
-            while (t < 255 && scan[t] <= slot)
-                ++t;
+        for (uint32_t r = 0; r < kPer; ++r) {
+            lo[r] = 0;
+            hi[r] = 255;
+        }
+#pragma unroll
+        for (uint32_t step = 0; step < 8; ++step) {
+#pragma unroll
+            for (uint32_t r = 0; r < kPer; ++r) {  // smallest t with cum[t + 1] > slot
+                const uint32_t mid = (lo[r] + hi[r]) >> 1;
+                const bool above = scan[mid] > s + 256 * r;
+                hi[r] = above ? mid : hi[r];
+                lo[r] = above ? lo[r] : (mid < hi[r] ? mid + 1 : hi[r]);
+            }
+        }
+#pragma unroll
+        for (uint32_t r = 0; r < kPer; ++r) {
+            const uint32_t slot = s + 256 * r, t = lo[r];
             const uint32_t begin = t ? scan[t - 1] : 0u;
-            entry[r] = t | (((scan[t] - begin) & 0xFFFu) << 8) | ((slot - begin) << 20);
+            tb->lut[slot] = t | (((scan[t] - begin) & 0xFFFu) << 8) | ((slot - begin) << 20);
         }
-        uint4 *dst = reinterpret_cast<uint4 *>(tb->lut + first);
-#pragma unroll
-        for (uint32_t r = 0; r < kM / 256; r += 4)
-            dst[r / 4] = make_uint4(entry[r], entry[r + 1], entry[r + 2], entry[r + 3]);
     }
 }
 
@@ -366,8 +403,9 @@ __device__ __forceinline__ void rans_put(EncState &st, const EncSym e, uint16_t 
         ring[st.wp & (kRingWords - 1)] = static_cast<uint16_t>(st.x);
         st.x >>= 16;
     }
-    const uint32_t t = __umulhi(e.magic, st.x);
-    const uint32_t q = (t + ((st.x - t) >> (e.shifts & 0xFFu))) >> (e.shifts >> 8);
+    uint32_t q = static_cast<uint32_t>(__fmul_rn(__uint2float_rn(st.x), e.rcp));  // q or q - 1
+    const uint32_t r = st.x - __umul24(q, e.f);
+    q += r >= e.f ? 1u : 0u;
     st.x = __umul24(q, e.cmpl_cum & 0xFFFFu) + st.x + (e.cmpl_cum >> 16);
 }
 
@@ -386,23 +424,31 @@ __device__ __forceinline__ void ring_flush(uint32_t wp_before, uint32_t wp_after
 
 __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__restrict__ src, uint64_t n,
                                                             uint32_t n_chunks, const EncSym *__restrict__ enc_g,
+                                                            const TableBlock *__restrict__ tb,
                                                             uint32_t *__restrict__ states,
                                                             uint8_t *__restrict__ lens,
                                                             uint32_t *__restrict__ chunk_words,
-                                                            uint16_t *__restrict__ slots)
+                                                            uint32_t *__restrict__ group_words,
+                                                            uint16_t *__restrict__ slots,
+                                                            HostRecord *__restrict__ record)
 {
     __shared__ uint4 enc_raw[256];
     __shared__ __align__(16) uint16_t rings[kEncThreads * kRingWords];
+    __shared__ uint32_t group_chunk[kEncThreads / kStates];
     enc_raw[threadIdx.x] = reinterpret_cast<const uint4 *>(enc_g)[threadIdx.x];
+    if (blockIdx.x == 0) {
+        // statistics for the host: posted early, they land long before this kernel ends
+        record->counts[threadIdx.x] = tb->counts[threadIdx.x];
+        record->freq[threadIdx.x] = tb->freq[threadIdx.x];
+    }
     __syncthreads();
     const EncSym *enc = reinterpret_cast<const EncSym *>(enc_raw);
 
     const uint32_t lane_id = blockIdx.x * kEncThreads + threadIdx.x;  // = chunk * 16 + state
     const uint32_t c = lane_id / kStates, j = lane_id % kStates;
-    if (c >= n_chunks)
-        return;
+    const bool live = c < n_chunks;
     const uint64_t base = static_cast<uint64_t>(c) * kChunk;
-    const uint32_t m = (n - base) < kChunk ? static_cast<uint32_t>(n - base) : kChunk;
+    const uint32_t m = !live ? 0u : ((n - base) < kChunk ? static_cast<uint32_t>(n - base) : kChunk);
     uint16_t *slot = slots + static_cast<uint64_t>(lane_id) * kRunCap;
     uint16_t *ring = rings + threadIdx.x * kRingWords;
     EncState st = {kRansL, kRunCap};
@@ -422,7 +468,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__r
             ring_flush(wp_before, st.wp, ring, slot);
             d = d_next;
         }
-    } else {
+    } else if (m > 0) {
         for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
             const uint32_t wp_before = st.wp;
             for (int t = static_cast<int>(kRun) - 1; t >= 0; --t) {
@@ -433,42 +479,56 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__r
             ring_flush(wp_before, st.wp, ring, slot);
         }
     }
-    // the incomplete group at the low end: word by word
-    for (uint32_t p = st.wp; p < ((st.wp + 7) & ~7u) && p < kRunCap; ++p)
-        slot[p] = ring[p & (kRingWords - 1)];
-
     const uint32_t len = kRunCap - st.wp;
-    states[lane_id] = st.x;
-    lens[lane_id] = static_cast<uint8_t>(len);
-    // words of the whole chunk (16 neighbouring lanes)
+    if (live) {
+        // the incomplete group at the low end: word by word
+        for (uint32_t p = st.wp; p < ((st.wp + 7) & ~7u) && p < kRunCap; ++p)
+            slot[p] = ring[p & (kRingWords - 1)];
+        states[lane_id] = st.x;
+        lens[lane_id] = static_cast<uint8_t>(len);
+    }
+    // words of the whole chunk (16 neighbouring lanes), then of the workgroup's 16 chunks
     uint32_t sum = len;
 #pragma unroll
     for (uint32_t dlt = 1; dlt < kStates; dlt <<= 1)
         sum += __shfl_xor(sum, dlt, kStates);
-    if (j == 0)
-        chunk_words[c] = sum;
+    if (j == 0) {
+        group_chunk[threadIdx.x / kStates] = sum;
+        if (live)
+            chunk_words[c] = sum;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t total = 0;
+        for (uint32_t i = 0; i < kEncThreads / kStates; ++i)
+            total += group_chunk[i];
+        group_words[blockIdx.x] = total;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
-// Kernel 4: offsets[c] = words before chunk c (exclusive prefix sum of the per-chunk totals).
-// One workgroup walks the chunks in tiles of 4096 with coalesced 128-bit accesses.
+// Kernel 4: exclusive prefix sum of the words per encoder workgroup (16 chunks each).  One
+// workgroup walks the groups in tiles of 4096; the per-chunk offsets follow from these in the
+// compaction kernel.  The total goes to the blob's last offset and to the host.
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kScanThreads = 1024;
+constexpr uint32_t kChunksPerGroup = kEncThreads / kStates;  // 16
 
-__global__ __launch_bounds__(kScanThreads) void offsets_kernel(const uint32_t *__restrict__ chunk_words,
-                                                              uint32_t n_chunks, uint32_t *__restrict__ offsets,
-                                                              HostRecord *__restrict__ record)
+__global__ __launch_bounds__(kScanThreads) void offsets_kernel(const uint32_t *__restrict__ group_words,
+                                                              uint32_t n_groups, uint64_t *__restrict__ group_prefix,
+                                                              uint32_t *__restrict__ last_offset,
+                                                              HostRecord *__restrict__ record, uint32_t seq)
 {
     __shared__ uint64_t wave_sum[kScanThreads / 64];
     __shared__ uint64_t carry_s;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint64_t carry = 0;
-    for (uint32_t tile = 0; tile < n_chunks; tile += kScanThreads * 4) {
+    for (uint32_t tile = 0; tile < n_groups; tile += kScanThreads * 4) {
         const uint32_t i0 = tile + tid * 4;
         uint32_t v[4];
 #pragma unroll
         for (uint32_t r = 0; r < 4; ++r)
-            v[r] = i0 + r < n_chunks ? chunk_words[i0 + r] : 0u;
+            v[r] = i0 + r < n_groups ? group_words[i0 + r] : 0u;
         const uint64_t mine = static_cast<uint64_t>(v[0]) + v[1] + v[2] + v[3];
         uint64_t incl = mine;  // inclusive scan over the wave
 #pragma unroll
@@ -486,8 +546,8 @@ __global__ __launch_bounds__(kScanThreads) void offsets_kernel(const uint32_t *_
         uint64_t run = before + incl - mine;
 #pragma unroll
         for (uint32_t r = 0; r < 4; ++r) {
-            if (i0 + r < n_chunks)
-                offsets[i0 + r] = static_cast<uint32_t>(run);
+            if (i0 + r < n_groups)
+                group_prefix[i0 + r] = run;
             run += v[r];
         }
         if (tid == kScanThreads - 1)
@@ -496,29 +556,32 @@ __global__ __launch_bounds__(kScanThreads) void offsets_kernel(const uint32_t *_
         carry = carry_s;
     }
     if (tid == 0) {
-        offsets[n_chunks] = static_cast<uint32_t>(carry);
-        offsets[n_chunks + 1] = 0;
+        last_offset[0] = static_cast<uint32_t>(carry);
+        last_offset[1] = 0;
         record->total_words[0] = static_cast<uint32_t>(carry);
         record->total_words[1] = static_cast<uint32_t>(carry >> 32);  // non-zero: too long for 32-bit offsets
+        __threadfence_system();
+        __hip_atomic_store(&record->seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// Kernel 5: gather the runs from the workspace slots into the blob's word section.
-// One wave per chunk; the 16 runs are read with all loads in flight, then written.
+// Kernel 5: gather the runs from the workspace slots into the blob's word section and write the
+// chunk offsets.  One wave per chunk; the 16 runs are read with all loads in flight, then written.
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kCompactThreads = 256;
 
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const uint16_t *__restrict__ slots,
                                                                  const uint8_t *__restrict__ lens,
-                                                                 const uint32_t *__restrict__ offsets,
+                                                                 const uint32_t *__restrict__ chunk_words,
+                                                                 const uint64_t *__restrict__ group_prefix,
+                                                                 uint32_t *__restrict__ offsets,
                                                                  uint32_t n_chunks, uint16_t *__restrict__ words)
 {
     const uint32_t c = blockIdx.x * (kCompactThreads / 64) + threadIdx.x / 64;
     const uint32_t lane = threadIdx.x & 63;
     if (c >= n_chunks)
         return;
-    const uint64_t at0 = offsets[c];
     // run length of state (lane mod 16) and its start inside the chunk (16-lane exclusive prefix)
     const uint32_t my_len = lens[c * kStates + (lane & 15)];
     uint32_t start = my_len;
@@ -538,6 +601,15 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const uint16_t
         const uint16_t *from = slots + static_cast<uint64_t>(c * kStates + j) * kRunCap + (kRunCap - len_j[j]);
         v[j] = lane < len_j[j] ? from[lane] : static_cast<uint16_t>(0);
     }
+    // words before this chunk: those before its encoder group plus the earlier chunks of the group
+    const uint32_t g = c / kChunksPerGroup, in_group = c % kChunksPerGroup;
+    uint32_t earlier = lane < in_group ? chunk_words[g * kChunksPerGroup + lane] : 0u;
+#pragma unroll
+    for (uint32_t d = 1; d < kChunksPerGroup; d <<= 1)
+        earlier += __shfl_xor(earlier, d, kChunksPerGroup);
+    const uint64_t at0 = group_prefix[g] + __shfl(earlier, 0, 64);
+    if (lane == 0)
+        offsets[c] = static_cast<uint32_t>(at0);
 #pragma unroll
     for (uint32_t j = 0; j < kStates; ++j)
         if (lane < len_j[j])
@@ -916,11 +988,14 @@ struct Workspace {
     int device = -1;
     EncSym *enc = nullptr;
     uint32_t *counts = nullptr;       // 256 histogram bins, zero between compress calls
-    uint32_t *chunk_words = nullptr;  // words per chunk, input of the offsets scan
+    uint32_t *chunk_words = nullptr;  // words per chunk
+    uint32_t *group_words = nullptr;  // words per encoder workgroup (16 chunks), input of the scan
+    uint64_t *group_prefix = nullptr; // its exclusive prefix sum
     uint64_t chunk_cap = 0;
     uint16_t *slots = nullptr;
     uint64_t slots_bytes = 0;
-    HostRecord *pinned = nullptr;  // pinned host memory, written by the table and offsets kernels
+    HostRecord *pinned = nullptr;  // pinned host memory, written by the encode and offsets kernels
+    uint32_t seq = 0;              // stamp of the last compress call
     hipEvent_t idle = nullptr;   // recorded after the last kernel that uses the workspace
 };
 std::mutex g_ws_mutex;
@@ -946,6 +1021,10 @@ int release_workspace_locked()
             hipFree(g_ws.counts);
         if (g_ws.chunk_words)
             hipFree(g_ws.chunk_words);
+        if (g_ws.group_words)
+            hipFree(g_ws.group_words);
+        if (g_ws.group_prefix)
+            hipFree(g_ws.group_prefix);
         if (g_ws.slots)
             hipFree(g_ws.slots);
         if (g_ws.pinned)
@@ -954,6 +1033,25 @@ int release_workspace_locked()
     }
     g_ws = Workspace();
     return rc;
+}
+
+// Waits until the offsets kernel of call `seq` has published its record.  The stamp arrives a
+// few microseconds after the kernel's last store, well before a blocking stream synchronise would
+// wake up; after a bounded spin the stream is synchronised anyway, which also surfaces errors.
+bool wait_for_record(uint32_t seq, hipStream_t stream)
+{
+    const volatile uint32_t *stamp = &g_ws.pinned->seq;
+    const auto start = std::chrono::steady_clock::now();
+    for (uint32_t spins = 0;; ++spins) {
+        if (__atomic_load_n(stamp, __ATOMIC_ACQUIRE) == seq)
+            return true;
+        if ((spins & 1023u) == 1023u &&
+            std::chrono::steady_clock::now() - start > std::chrono::milliseconds(20))
+            break;
+    }
+    if (!hip_ok(hipStreamSynchronize(stream)))
+        return false;
+    return __atomic_load_n(stamp, __ATOMIC_ACQUIRE) == seq;
 }
 
 int ensure_workspace(int device, uint32_t n_chunks, hipStream_t stream)
@@ -967,6 +1065,8 @@ int ensure_workspace(int device, uint32_t n_chunks, hipStream_t stream)
         NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.enc), 256 * sizeof(EncSym)));
         NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.counts), 256 * sizeof(uint32_t)));
         NZ_HIP(hipHostMalloc(reinterpret_cast<void **>(&g_ws.pinned), sizeof(HostRecord), hipHostMallocDefault));
+        std::memset(g_ws.pinned, 0, sizeof(HostRecord));
+        g_ws.seq = 0;
         NZ_HIP(hipEventCreateWithFlags(&g_ws.idle, hipEventDisableTiming));
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, stream, g_ws.counts, 0u, 256u);
         NZ_HIP(hipGetLastError());
@@ -989,12 +1089,19 @@ int ensure_workspace(int device, uint32_t n_chunks, hipStream_t stream)
             g_ws.slots_bytes = slots_bytes;
         }
         if (g_ws.chunk_cap < n_chunks) {
-            if (g_ws.chunk_words) {
+            if (g_ws.chunk_words)
                 NZ_HIP(hipFree(g_ws.chunk_words));
-                g_ws.chunk_words = nullptr;
-                g_ws.chunk_cap = 0;
-            }
-            if (hipMalloc(reinterpret_cast<void **>(&g_ws.chunk_words), (static_cast<uint64_t>(n_chunks) + 4) * 4) != hipSuccess) {
+            if (g_ws.group_words)
+                NZ_HIP(hipFree(g_ws.group_words));
+            if (g_ws.group_prefix)
+                NZ_HIP(hipFree(g_ws.group_prefix));
+            g_ws.chunk_words = g_ws.group_words = nullptr;
+            g_ws.group_prefix = nullptr;
+            g_ws.chunk_cap = 0;
+            const uint64_t groups = (static_cast<uint64_t>(n_chunks) + kChunksPerGroup - 1) / kChunksPerGroup;
+            if (hipMalloc(reinterpret_cast<void **>(&g_ws.chunk_words), (groups * kChunksPerGroup + 4) * 4) != hipSuccess ||
+                hipMalloc(reinterpret_cast<void **>(&g_ws.group_words), (groups + 4) * 4) != hipSuccess ||
+                hipMalloc(reinterpret_cast<void **>(&g_ws.group_prefix), (groups + 4) * 8) != hipSuccess) {
                 (void)hipGetLastError();
                 return NEUZIP_ENOMEM;
             }
@@ -1200,20 +1307,22 @@ int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa
     bins_dirty = true;
 
     // the table kernel also returns the workspace histogram bins to zero
-    hipLaunchKernelGGL(table_kernel, dim3(1), dim3(256), 0, stream, g_ws.counts, table_of(b), g_ws.enc, g_ws.pinned);
+    hipLaunchKernelGGL(table_kernel, dim3(1), dim3(256), 0, stream, g_ws.counts, table_of(b), g_ws.enc);
     if (hip_ok(hipGetLastError()))
         bins_dirty = false;
-    hipLaunchKernelGGL(encode_kernel, dim3((nc * kStates + kEncThreads - 1) / kEncThreads), dim3(kEncThreads), 0,
-                       stream, static_cast<const uint16_t *>(d_src), n_elems, nc, g_ws.enc, states_of(b), lens_of(b),
-                       g_ws.chunk_words, g_ws.slots);
-    hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kScanThreads), 0, stream, g_ws.chunk_words, nc, offsets_of(b),
-                       g_ws.pinned);
+    const uint32_t n_groups = (nc + kChunksPerGroup - 1) / kChunksPerGroup;
+    hipLaunchKernelGGL(encode_kernel, dim3(n_groups), dim3(kEncThreads), 0, stream,
+                       static_cast<const uint16_t *>(d_src), n_elems, nc, g_ws.enc, table_of(b), states_of(b),
+                       lens_of(b), g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned);
+    const uint32_t seq = ++g_ws.seq;
+    hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kScanThreads), 0, stream, g_ws.group_words, n_groups,
+                       g_ws.group_prefix, offsets_of(b) + nc, g_ws.pinned, seq);
     if (!hip_ok(hipGetLastError()))
         return fail(NEUZIP_EHIP);
 
     // the stream length is data dependent: wait for it (and the statistics), which the kernels
-    // have written straight into pinned host memory
-    if (!hip_ok(hipStreamSynchronize(stream)))
+    // write straight into pinned host memory, the stamp last
+    if (!wait_for_record(seq, stream))
         return fail(NEUZIP_EHIP);
     if (g_ws.pinned->total_words[1] != 0)
         return fail(NEUZIP_EUNSUPPORTED);  // more than 2^32 words
@@ -1227,8 +1336,8 @@ int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa
         return fail(rc);
     b->total_words = total_words;
     hipLaunchKernelGGL(compact_kernel, dim3((nc + kCompactThreads / 64 - 1) / (kCompactThreads / 64)),
-                       dim3(kCompactThreads), 0, stream, g_ws.slots, lens_of(b), offsets_of(b), nc,
-                       reinterpret_cast<uint16_t *>(b->words));
+                       dim3(kCompactThreads), 0, stream, g_ws.slots, lens_of(b), g_ws.chunk_words, g_ws.group_prefix,
+                       offsets_of(b), nc, reinterpret_cast<uint16_t *>(b->words));
     if (!hip_ok(hipGetLastError()) || !hip_ok(hipEventRecord(g_ws.idle, stream)))
         return fail(NEUZIP_EHIP);
     *blob = b;

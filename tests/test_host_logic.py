@@ -102,3 +102,24 @@ def test_import_validates_containers_on_the_host(nz):
     assert try_import(bad) == nz.ECORRUPT
     assert handle.value is None
     assert lib.neuzip_import(None, 100, None, ctypes.byref(handle)) == nz.EINVAL
+
+
+def test_float_reciprocal_division_scheme_of_the_encoder():
+    """The HIP encoder divides the state by a frequency with fp32: q' = trunc(float(x) * rcp) with
+    rcp = fl(fl(1/f) * (1 - 2^-21)), then q = q' + (x - q' f >= f).  Emulated here with numpy's IEEE
+    fp32 on every frequency and on the dividends that matter (multiples of f and their neighbours,
+    the renormalisation limit, random draws): it must equal integer division whenever x < f * 2^20."""
+    rng = np.random.default_rng(0)
+    one_minus = np.float32(1.0) - np.float32(2.0 ** -21)
+    for f in range(1, 4097):
+        rcp = np.float32(np.float32(1.0) / np.float32(f)) * one_minus
+        limit = min(f << 20, 1 << 32)
+        q_edge = np.concatenate([rng.integers(16, 1 << 20, 40), [16, (1 << 20) - 1, (1 << 20) - 2]])
+        xs = np.concatenate([q_edge * f, q_edge * f + f - 1, q_edge * f - 1, q_edge * f + 1,
+                             rng.integers(1 << 16, limit, 60), [limit - 1, 1 << 16]]).astype(np.int64)
+        xs = xs[(xs >= 0) & (xs < limit)]
+        est = (xs.astype(np.uint32).astype(np.float32) * rcp).astype(np.int64)     # astype truncates
+        rem = xs - est * f
+        assert np.all((rem >= 0) & (rem < 2 * f)), f
+        q = est + (rem >= f)
+        assert np.array_equal(q, xs // f), f
