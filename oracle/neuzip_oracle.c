@@ -67,6 +67,74 @@ int nzo_pack_signmant(const uint16_t *w, uint64_t n, int k, uint8_t *out)
 }
 
 /* ------------------------------------------------------------------ */
+/* Block-wise normalisation of the lossy variant (Sec. 2.3, last        */
+/* paragraph; block sizes 32..512 in the block-size study of Sec. 3).   */
+/*                                                                      */
+/* Reading taken here: a block is `block` consecutive weights.  Its     */
+/* coefficient is the mantissa of the weight of largest magnitude (the  */
+/* exponent is ignored; first such weight on ties), one byte per block. */
+/* With c = 1 + coef/128 every weight is stored as bf16(w / c), so the  */
+/* largest weight becomes a power of two and passes through mantissa    */
+/* truncation unchanged; decoding returns bf16(stored * c).  Both       */
+/* roundings are to nearest even; the arithmetic is IEEE binary32.      */
+/* ------------------------------------------------------------------ */
+static float bf16_value(uint16_t u)
+{
+    uint32_t bits = (uint32_t)u << 16;
+    float v;
+    memcpy(&v, &bits, 4);
+    return v;
+}
+
+static uint16_t bf16_round(float v)
+{
+    uint32_t bits;
+    memcpy(&bits, &v, 4);
+    if ((bits & 0x7FFFFFFFu) > 0x7F800000u) /* NaN stays NaN */
+        return (uint16_t)((bits >> 16) | 0x40u);
+    /* round to nearest, ties to the even bf16 */
+    return (uint16_t)((bits + 0x7FFFu + ((bits >> 16) & 1u)) >> 16);
+}
+
+static int valid_block(uint32_t block)
+{
+    return block == 32 || block == 64 || block == 128 || block == 256 || block == 512;
+}
+
+uint64_t nzo_block_count(uint64_t n, uint32_t block) { return block ? (n + block - 1) / block : 0; }
+
+int nzo_block_coefficients(const uint16_t *w, uint64_t n, uint32_t block, uint8_t *coef)
+{
+    if (!valid_block(block))
+        return NZO_EINVAL;
+    for (uint64_t b = 0; b * block < n; b++) {
+        uint64_t end = (b + 1) * block < n ? (b + 1) * block : n;
+        uint64_t best = b * block;
+        for (uint64_t i = b * block + 1; i < end; i++)
+            if ((w[i] & 0x7FFFu) > (w[best] & 0x7FFFu)) /* magnitude order of bf16 words */
+                best = i;
+        coef[b] = (uint8_t)(w[best] & 0x7Fu);
+    }
+    return NZO_OK;
+}
+
+void nzo_normalise(const uint16_t *w, uint64_t n, uint32_t block, const uint8_t *coef, uint16_t *out)
+{
+    for (uint64_t i = 0; i < n; i++) {
+        float c = 1.0f + (float)coef[i / block] / 128.0f;
+        out[i] = bf16_round(bf16_value(w[i]) / c);
+    }
+}
+
+void nzo_denormalise(const uint16_t *w, uint64_t n, uint32_t block, const uint8_t *coef, uint16_t *out)
+{
+    for (uint64_t i = 0; i < n; i++) {
+        float c = 1.0f + (float)coef[i / block] / 128.0f;
+        out[i] = bf16_round(bf16_value(w[i]) * c);
+    }
+}
+
+/* ------------------------------------------------------------------ */
 /* Symbol statistics (Sec. 2.2) and Eq. (1)                            */
 /* ------------------------------------------------------------------ */
 void nzo_histogram(const uint16_t *w, uint64_t n, uint64_t cnt[256])
@@ -341,7 +409,7 @@ uint64_t nzo_compress_bound(uint64_t n, int k)
 {
     uint64_t nc = chunks_of(n);
     return NZO_HEADER_BYTES + 512 + pad16((nc + 1) * 4) + nc * NZO_K * 4 + nc * NZO_K +
-           pad16(nc * NZO_K * NZO_RUN_CAP * 2) + pad16(nzo_signmant_bytes(n, k));
+           pad16(nc * NZO_K * NZO_RUN_CAP * 2) + pad16(nzo_signmant_bytes(n, k)) + pad16(nzo_block_count(n, 32));
 }
 
 typedef struct {
@@ -375,8 +443,40 @@ static void *enc_worker(void *arg)
     return NULL;
 }
 
+static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, const uint8_t *coef,
+                         uint8_t *blob, uint64_t cap, uint64_t *written, int threads);
+
 int nzo_compress(const uint16_t *w, uint64_t n, int k, uint8_t *blob, uint64_t cap,
                  uint64_t *written, int threads)
+{
+    return compress_impl(w, n, k, 0, NULL, blob, cap, written, threads);
+}
+
+/* Lossy variant with block-wise normalisation: the coefficients are taken from the original
+ * weights, the weights are normalised, and the normalised tensor goes through the same path. */
+int nzo_compress_blockwise(const uint16_t *w, uint64_t n, int k, uint32_t block, uint8_t *blob,
+                           uint64_t cap, uint64_t *written, int threads)
+{
+    if (!valid_block(block) || k == 7 || !valid_k(k))
+        return NZO_EINVAL;
+    uint64_t nb = nzo_block_count(n, block);
+    uint8_t *coef = (uint8_t *)malloc((size_t)nb + 1);
+    uint16_t *normal = (uint16_t *)malloc((size_t)(n + 1) * sizeof(uint16_t));
+    if (!coef || !normal) {
+        free(coef);
+        free(normal);
+        return NZO_ENOSPACE;
+    }
+    nzo_block_coefficients(w, n, block, coef);
+    nzo_normalise(w, n, block, coef, normal);
+    int rc = compress_impl(normal, n, k, block, coef, blob, cap, written, threads);
+    free(coef);
+    free(normal);
+    return rc;
+}
+
+static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, const uint8_t *coef,
+                         uint8_t *blob, uint64_t cap, uint64_t *written, int threads)
 {
     if (!valid_k(k) || n >= ((uint64_t)1 << 32))
         return NZO_EINVAL;
@@ -440,7 +540,8 @@ int nzo_compress(const uint16_t *w, uint64_t n, int k, uint8_t *blob, uint64_t c
     uint64_t off_lens = off_states + nc * NZO_K * 4;
     uint64_t off_words = off_lens + nc * NZO_K;
     uint64_t off_sm = off_words + pad16(total_words * 2);
-    uint64_t size = off_sm + pad16(sm_bytes);
+    uint64_t off_coef = off_sm + pad16(sm_bytes);
+    uint64_t size = off_coef + pad16(nzo_block_count(n, block));
     if (written)
         *written = size;
     if (rc == NZO_OK && (size > cap || total_words >= ((uint64_t)1 << 32)))
@@ -463,6 +564,7 @@ int nzo_compress(const uint16_t *w, uint64_t n, int k, uint8_t *blob, uint64_t c
     put32(blob + 32, NZO_G);
     put32(blob + 36, (uint32_t)nc);
     put64(blob + 40, total_words);
+    put32(blob + 48, block); /* 0: no block-wise normalisation, no coefficient section */
     for (int s = 0; s < 256; s++)
         put16(blob + off_freq + 2 * s, freq[s]);
 
@@ -480,6 +582,8 @@ int nzo_compress(const uint16_t *w, uint64_t n, int k, uint8_t *blob, uint64_t c
     }
     put32(blob + off_offsets + 4 * nc, (uint32_t)run);
     nzo_pack_signmant(w, n, k, blob + off_sm);
+    if (block)
+        memcpy(blob + off_coef, coef, nzo_block_count(n, block));
 
     free(states);
     free(lens);
@@ -490,7 +594,8 @@ int nzo_compress(const uint16_t *w, uint64_t n, int k, uint8_t *blob, uint64_t c
 typedef struct {
     uint64_t n, nc, total_words;
     int k;
-    const uint8_t *freq, *offsets, *states, *lens, *words, *sm;
+    uint32_t block;
+    const uint8_t *freq, *offsets, *states, *lens, *words, *sm, *coef;
 } blob_view;
 
 static int open_blob(const uint8_t *blob, uint64_t len, blob_view *v)
@@ -506,7 +611,10 @@ static int open_blob(const uint8_t *blob, uint64_t len, blob_view *v)
         return NZO_ECORRUPT;
     v->nc = get32(blob + 36);
     v->total_words = get64(blob + 40);
+    v->block = get32(blob + 48);
     if (v->nc != chunks_of(v->n))
+        return NZO_ECORRUPT;
+    if (v->block != 0 && (!valid_block(v->block) || v->k == 7))
         return NZO_ECORRUPT;
     uint64_t off_freq = NZO_HEADER_BYTES;
     uint64_t off_offsets = off_freq + 512;
@@ -514,7 +622,8 @@ static int open_blob(const uint8_t *blob, uint64_t len, blob_view *v)
     uint64_t off_lens = off_states + v->nc * NZO_K * 4;
     uint64_t off_words = off_lens + v->nc * NZO_K;
     uint64_t off_sm = off_words + pad16(v->total_words * 2);
-    uint64_t size = off_sm + pad16(nzo_signmant_bytes(v->n, v->k));
+    uint64_t off_coef = off_sm + pad16(nzo_signmant_bytes(v->n, v->k));
+    uint64_t size = off_coef + pad16(nzo_block_count(v->n, v->block));
     if (size != len)
         return NZO_ECORRUPT;
     v->freq = blob + off_freq;
@@ -523,6 +632,7 @@ static int open_blob(const uint8_t *blob, uint64_t len, blob_view *v)
     v->lens = blob + off_lens;
     v->words = blob + off_words;
     v->sm = blob + off_sm;
+    v->coef = blob + off_coef;
     return NZO_OK;
 }
 
@@ -649,5 +759,7 @@ int nzo_decompress(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n,
             rc = jobs[t].rc;
     free(jobs);
     free(tid);
+    if (rc == NZO_OK && v.block)
+        nzo_denormalise(out, n, v.block, v.coef, out);
     return rc;
 }

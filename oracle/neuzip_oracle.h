@@ -38,6 +38,7 @@
  *   container := header(64 B) | freq[256] u16 | offsets[n_chunks+1] u32
  *              | states[n_chunks*K] u32 | lens[n_chunks*K] u8
  *              | words[total_words] u16 | signmant[ceil(n*(k+1)/8)] u8
+ *              | coef[ceil(n/block)] u8   (only when header word 48, block, is not 0)
  *   every section is zero-padded to a multiple of 16 bytes.
  *   offsets[c] = number of words that belong to chunks before c.
  *   Inside chunk c the K private runs follow each other, state 0 first;
@@ -76,6 +77,15 @@ void nzo_truncate(const uint16_t *w, uint64_t n, int k, uint16_t *out);
 uint64_t nzo_signmant_bytes(uint64_t n, int k);
 int nzo_pack_signmant(const uint16_t *w, uint64_t n, int k, uint8_t *out);
 
+/* Sec. 2.3, block-wise normalisation (reading stated in the .c file): one
+ * coefficient byte per block of 32..512 consecutive weights = mantissa of the
+ * largest-magnitude weight; stored weight = bf16(w / c), decoded weight =
+ * bf16(stored * c) with c = 1 + coef/128. */
+uint64_t nzo_block_count(uint64_t n, uint32_t block);
+int nzo_block_coefficients(const uint16_t *w, uint64_t n, uint32_t block, uint8_t *coef);
+void nzo_normalise(const uint16_t *w, uint64_t n, uint32_t block, const uint8_t *coef, uint16_t *out);
+void nzo_denormalise(const uint16_t *w, uint64_t n, uint32_t block, const uint8_t *coef, uint16_t *out);
+
 /* Sec. 2.2: symbol statistics over the 256 exponent values. */
 void nzo_histogram(const uint16_t *w, uint64_t n, uint64_t cnt[256]);
 /* Eq. (1) on the empirical distribution, bits per symbol. */
@@ -103,6 +113,10 @@ int nzo_decode_chunk(uint8_t *sym, uint32_t m, const uint16_t freq[256], int K, 
 uint64_t nzo_compress_bound(uint64_t n, int k);
 int nzo_compress(const uint16_t *w, uint64_t n, int k, uint8_t *blob, uint64_t cap,
                  uint64_t *written, int threads);
+/* Lossy container with block-wise normalisation (k in {3,1,0}); header word 48 holds the
+ * block size and a section coef[ceil(n/block)] u8 follows the sign|mantissa stream. */
+int nzo_compress_blockwise(const uint16_t *w, uint64_t n, int k, uint32_t block, uint8_t *blob,
+                           uint64_t cap, uint64_t *written, int threads);
 int nzo_decompress(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n, int threads);
 /* Reads n, k and the stored frequencies out of a container. */
 int nzo_blob_info(const uint8_t *blob, uint64_t len, uint64_t *n, int *k, uint64_t *total_words,

@@ -68,6 +68,16 @@ def lib():
         L.nzo_encode_chunk.restype = i32
         L.nzo_decode_chunk.argtypes = [u8p, u32, u16p, i32, i32, u32p, u16p, u16p, u32]
         L.nzo_decode_chunk.restype = i32
+        L.nzo_block_count.argtypes = [u64, u32]
+        L.nzo_block_count.restype = u64
+        L.nzo_block_coefficients.argtypes = [u16p, u64, u32, u8p]
+        L.nzo_block_coefficients.restype = i32
+        L.nzo_normalise.argtypes = [u16p, u64, u32, u8p, u16p]
+        L.nzo_normalise.restype = None
+        L.nzo_denormalise.argtypes = [u16p, u64, u32, u8p, u16p]
+        L.nzo_denormalise.restype = None
+        L.nzo_compress_blockwise.argtypes = [u16p, u64, i32, u32, u8p, u64, u64p, i32]
+        L.nzo_compress_blockwise.restype = i32
         L.nzo_compress_bound.argtypes = [u64, i32]
         L.nzo_compress_bound.restype = u64
         L.nzo_compress.argtypes = [u16p, u64, i32, u8p, u64, u64p, i32]
@@ -204,14 +214,49 @@ def decode_chunk(m, freq, states, runs, k_states=K, g=G):
     return sym
 
 
-def compress(w, k=7, threads=1):
+def block_coefficients(w, block):
+    w = _u16(w)
+    coef = np.zeros(int(lib().nzo_block_count(w.size, block)), np.uint8)
+    rc = lib().nzo_block_coefficients(_p(w, ctypes.c_uint16), w.size, block, _p(coef, ctypes.c_uint8))
+    if rc != OK:
+        raise OracleError(rc, "block_coefficients")
+    return coef
+
+
+def normalise(w, block, coef):
+    w = _u16(w)
+    coef = np.ascontiguousarray(coef, dtype=np.uint8)
+    out = np.empty_like(w)
+    lib().nzo_normalise(_p(w, ctypes.c_uint16), w.size, block, _p(coef, ctypes.c_uint8), _p(out, ctypes.c_uint16))
+    return out
+
+
+def denormalise(w, block, coef):
+    w = _u16(w)
+    coef = np.ascontiguousarray(coef, dtype=np.uint8)
+    out = np.empty_like(w)
+    lib().nzo_denormalise(_p(w, ctypes.c_uint16), w.size, block, _p(coef, ctypes.c_uint8), _p(out, ctypes.c_uint16))
+    return out
+
+
+def lossy_blockwise(w, k, block):
+    """What decompress(compress_blockwise(w)) must return, from the three steps alone."""
+    coef = block_coefficients(w, block)
+    return denormalise(truncate(normalise(w, block, coef), k), block, coef)
+
+
+def compress(w, k=7, threads=1, block=0):
     """bf16 words (uint16 array) -> container bytes (uint8 array)."""
     w = _u16(w)
     cap = int(lib().nzo_compress_bound(w.size, k if k in (7, 3, 1, 0) else 7))
     blob = np.empty(cap, np.uint8)
     written = ctypes.c_uint64(0)
-    rc = lib().nzo_compress(_p(w, ctypes.c_uint16), w.size, k, _p(blob, ctypes.c_uint8), cap,
-                            ctypes.byref(written), threads)
+    if block:
+        rc = lib().nzo_compress_blockwise(_p(w, ctypes.c_uint16), w.size, k, block, _p(blob, ctypes.c_uint8), cap,
+                                          ctypes.byref(written), threads)
+    else:
+        rc = lib().nzo_compress(_p(w, ctypes.c_uint16), w.size, k, _p(blob, ctypes.c_uint8), cap,
+                                ctypes.byref(written), threads)
     if rc != OK:
         raise OracleError(rc, "compress")
     return blob[: written.value].copy()
@@ -241,12 +286,14 @@ def sections(blob):
     """Byte ranges of the container's sections, for tests that compare them one by one."""
     info = blob_info(blob)
     n, k, tw = info["n"], info["k"], info["total_words"]
+    block = int(np.ascontiguousarray(blob[48:52]).view("<u4")[0])
     nc = (n + CHUNK - 1) // CHUNK
     pad = lambda v: (v + 15) & ~15
     out, pos = {}, 0
     for name, size in (("header", HEADER_BYTES), ("freq", 512), ("offsets", pad((nc + 1) * 4)),
                        ("states", nc * K * 4), ("lens", nc * K), ("words", pad(tw * 2)),
-                       ("signmant", pad(signmant_bytes(n, k)))):
+                       ("signmant", pad(signmant_bytes(n, k))),
+                       ("coef", pad((n + block - 1) // block) if block else 0)):
         out[name] = (pos, pos + size)
         pos += size
     return out

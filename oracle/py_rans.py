@@ -103,8 +103,56 @@ def _pad(b):
     return b + bytes((-len(b)) % 16)
 
 
-def compress(words16, k=7):
+def _f32(bits):
+    return struct.unpack("<f", struct.pack("<I", bits & 0xFFFFFFFF))[0]
+
+
+def _bits(value):
+    """IEEE binary32 bit pattern of a Python float (rounds to nearest even, as struct does)."""
+    try:
+        return struct.unpack("<I", struct.pack("<f", value))[0]
+    except OverflowError:
+        return 0x7F800000 if value > 0 else 0xFF800000
+
+
+def bf16_round(bits32):
+    if (bits32 & 0x7FFFFFFF) > 0x7F800000:
+        return (bits32 >> 16) | 0x40
+    return ((bits32 + 0x7FFF + ((bits32 >> 16) & 1)) >> 16) & 0xFFFF
+
+
+def block_coefficients(words16, block):
+    """Sec. 2.3: per block, the mantissa of the weight of largest magnitude (first on ties)."""
+    out = []
+    for b in range(0, len(words16), block):
+        blk = words16[b:b + block]
+        best = max(range(len(blk)), key=lambda i: (blk[i] & 0x7FFF, -i))
+        out.append(blk[best] & 0x7F)
+    return out
+
+
+def scale(words16, block, coef, divide):
+    """bf16(w / c) or bf16(w * c), c = 1 + coef/128, in binary32 (Python doubles hold the exact
+    product, and a quotient of two bf16 values is never close enough to a binary32 tie for the
+    extra rounding through double to matter)."""
+    out = []
+    for i, u in enumerate(words16):
+        c = 1.0 + coef[i // block] / 128.0
+        v = _f32(u << 16)
+        if v != v:
+            out.append(u | 0x40)
+            continue
+        r = v / c if divide else v * c
+        out.append(bf16_round(_bits(r)))
+    return out
+
+
+def compress(words16, k=7, block=0):
     """List of bf16 words -> container bytes."""
+    coef = []
+    if block:
+        coef = block_coefficients(words16, block)
+        words16 = scale(words16, block, coef, divide=True)
     n = len(words16)
     expo = [exponent(u) for u in words16]
     cnt = [0] * 256
@@ -123,7 +171,7 @@ def compress(words16, k=7):
             lens.append(len(run))
             payload.extend(run)
     offsets.append(len(payload))
-    header = struct.pack("<IIQIIIIIIQ", 0x315A554E, 1, n, k, PROB_BITS, CHUNK, K, G, nc, len(payload))
+    header = struct.pack("<IIQIIIIIIQI", 0x315A554E, 1, n, k, PROB_BITS, CHUNK, K, G, nc, len(payload), block)
     header += bytes(64 - len(header))
     out = header
     out += struct.pack("<256H", *freq)
@@ -132,12 +180,14 @@ def compress(words16, k=7):
     out += bytes(lens)
     out += _pad(struct.pack(f"<{len(payload)}H", *payload))
     out += _pad(pack_signmant(words16, k))
+    if block:
+        out += _pad(bytes(coef))
     return out
 
 
 def decompress(blob):
     """Container bytes -> list of bf16 words."""
-    magic, ver, n, k, pb, chunk, ks, g, nc, tw = struct.unpack_from("<IIQIIIIIIQ", blob, 0)
+    magic, ver, n, k, pb, chunk, ks, g, nc, tw, block = struct.unpack_from("<IIQIIIIIIQI", blob, 0)
     assert (magic, ver, pb, chunk, ks, g) == (0x315A554E, 1, PROB_BITS, CHUNK, K, G)
     pos = 64
     freq = list(struct.unpack_from("<256H", blob, pos)); pos += 512
@@ -146,6 +196,7 @@ def decompress(blob):
     lens = blob[pos:pos + nc * K]; pos += nc * K
     payload = struct.unpack_from(f"<{tw}H", blob, pos); pos += (tw * 2 + 15) // 16 * 16
     sm = blob[pos:]
+    coef = list(blob[pos + ((n * (k + 1) + 7) // 8 + 15) // 16 * 16:]) if block else []
     width, per = k + 1, 8 // (k + 1)
     out = [0] * n
     for c in range(nc):
@@ -160,4 +211,6 @@ def decompress(blob):
                 field = (sm[gi // per] >> ((gi % per) * width)) & ((1 << width) - 1)
                 out[gi] = ((field >> k) << 15) | (e << 7) | ((field & ((1 << k) - 1)) << (7 - k))
         assert at == offsets[c + 1]
+    if block:
+        out = scale(out, block, coef, divide=False)
     return out

@@ -400,3 +400,90 @@ def test_corruption_is_detected():
         O.decompress(blob, w.size + 1)
     with pytest.raises(O.OracleError):
         O.compress(w, 5)
+
+
+# ---------------------------------------------------------------- block-wise normalisation (Sec. 2.3)
+
+def torch_bf16(words):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(words).view(np.int16).copy()).view(torch.bfloat16)
+
+
+def test_block_coefficient_is_the_mantissa_of_the_largest_weight():
+    w = inputs.bits(inputs.student_t4_bf16(10_000 + 37, seed=21))
+    v = np.abs(as_float(w))
+    for block in (32, 64, 128, 256, 512):
+        coef = O.block_coefficients(w, block)
+        assert coef.size == math.ceil(w.size / block)
+        for b in range(coef.size):
+            seg = slice(b * block, min((b + 1) * block, w.size))
+            first_max = int(np.argmax(v[seg]))                 # numpy returns the first maximum
+            frac, _ = np.frexp(v[seg][first_max])
+            assert coef[b] == int((frac * 2 - 1) * 128)        # 1.mantissa of that weight
+    with pytest.raises(O.OracleError):
+        O.block_coefficients(w, 48)
+
+
+def test_normalisation_arithmetic_matches_torch_bf16():
+    # every non-NaN bf16 pattern divided / multiplied by every coefficient class, against PyTorch's
+    # IEEE float32 division / product and its round-to-nearest-even bf16 conversion
+    import torch
+    words = ALL[~np.isnan(as_float(ALL))]
+    t = torch_bf16(words)
+    for coef in (0, 1, 37, 64, 100, 127):
+        c = 1.0 + coef / 128.0
+        co = np.full(math.ceil(words.size / 32), coef, np.uint8)
+        ours = O.normalise(words, 32, co)
+        ref = (t.float() / c).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(ours, ref), coef
+        ours = O.denormalise(words, 32, co)
+        ref = (t.float() * c).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        keep = ~np.isnan(as_float(ref))
+        assert np.array_equal(ours[keep], ref[keep]), coef
+
+
+@pytest.mark.parametrize("k", [3, 1, 0])
+def test_largest_weight_of_every_block_survives_lossy_compression(k):
+    w = inputs.bits(inputs.student_t4_bf16(50_000, seed=22))
+    v = as_float(w)
+    plain_err = np.abs(as_float(O.truncate(w, k)) - v).mean()
+    previous = None
+    for block in (512, 128, 32):
+        blob = O.compress(w, k, threads=3, block=block)
+        out = O.decompress(blob, w.size, threads=2)
+        assert np.array_equal(out, O.lossy_blockwise(w, k, block))
+        for b in range(math.ceil(w.size / block)):
+            seg = slice(b * block, min((b + 1) * block, w.size))
+            i = int(np.argmax(np.abs(v[seg])))
+            assert out[seg][i] == w[seg][i]                     # "invariant to rounding and truncation"
+        # sign kept, relative change bounded by the truncation step plus the two bf16 roundings
+        vo = as_float(out)
+        assert np.array_equal(np.signbit(vo), np.signbit(v))
+        assert (np.abs(vo - v) / np.abs(v)).max() < 2.0 ** -k + 2.0 ** -7
+        # smaller blocks reproduce the weights better (block-size study) and cost 8 bits per block
+        err = np.abs(vo - v).mean()
+        assert err < plain_err and (previous is None or err < previous)
+        previous = err
+        sec = O.sections(blob)
+        assert sec["coef"][1] - sec["coef"][0] == (math.ceil(w.size / block) + 15) // 16 * 16
+        assert sec["coef"][1] == blob.size
+
+
+@pytest.mark.parametrize("k,block,n", [(3, 512, 4096 + 77), (1, 32, 1000), (0, 128, 5000), (3, 64, 0), (0, 512, 1)])
+def test_blockwise_containers_of_both_codecs_agree(k, block, n):
+    w = inputs.bits(inputs.gaussian_bf16(n, seed=300 + n)) if n else np.zeros(0, np.uint16)
+    blob = O.compress(w, k, block=block)
+    mine = P.compress([int(u) for u in w], k, block)
+    assert blob.tobytes() == mine
+    assert P.decompress(mine) == [int(u) for u in O.lossy_blockwise(w, k, block)]
+    assert np.array_equal(O.decompress(blob, n), O.lossy_blockwise(w, k, block))
+
+
+def test_blockwise_rejects_lossless_and_odd_blocks():
+    w = inputs.bits(inputs.gaussian_bf16(1000, seed=1))
+    with pytest.raises(O.OracleError):
+        O.compress(w, 7, block=512)
+    with pytest.raises(O.OracleError):
+        O.compress(w, 3, block=100)
+    every = O.compress(ALL, 3, block=64)
+    assert np.array_equal(O.decompress(every, 65536), O.lossy_blockwise(ALL, 3, 64))
