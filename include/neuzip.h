@@ -82,6 +82,23 @@ int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa
                     void *hip_stream, neuzip_blob **blob);
 
 /*
+ * neuzip_compress_blockwise -- the lossy variant with block-wise normalisation (Sec. 2.3, last
+ * paragraph; block sizes as in the block-size study of Sec. 3).
+ *
+ *   block_size     0 (same as neuzip_compress) or 32, 64, 128, 256, 512 consecutive weights.
+ *   mantissa_bits  3, 1 or 0 when block_size != 0 (7 -> EINVAL: normalisation is lossy).
+ *
+ * Reading of the paper taken here: the coefficient of a block is the 7-bit mantissa of its
+ * largest-magnitude weight (first one on ties), stored in one byte per block; with
+ * c = 1 + coef/128 every weight is stored as bf16(w / c) before truncation and is returned as
+ * bf16(stored * c), both rounded to nearest even in IEEE binary32.  The largest weight of each
+ * block is reproduced exactly.  Everything else is as for neuzip_compress; neuzip_decompress
+ * and the other entry points recognise such blobs by themselves.
+ */
+int neuzip_compress_blockwise(const void *d_src, uint64_t n_elems, int dtype, int mantissa_bits,
+                              uint32_t block_size, void *hip_stream, neuzip_blob **blob);
+
+/*
  * neuzip_decompress -- Sec. 2.2 Eq. (3), Alg. 1 "decompression" + "merge":
  * decodes the exponents and reassembles bf16 words into the caller's
  * temporary space in one fused kernel.
@@ -138,8 +155,9 @@ uint64_t neuzip_compressed_bytes(const neuzip_blob *blob);
  * alignment padding and the derived cumulative and slot tables). */
 uint64_t neuzip_device_bytes(const neuzip_blob *blob);
 
-/* Element count and mantissa bits the blob was made with. */
+/* Element count, mantissa bits and normalisation block size (0 = none) the blob was made with. */
 uint64_t neuzip_elems(const neuzip_blob *blob);
+uint32_t neuzip_block_size(const neuzip_blob *blob);
 int neuzip_mantissa_bits(const neuzip_blob *blob);
 
 /*

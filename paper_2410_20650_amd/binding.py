@@ -33,6 +33,10 @@ def _load():
     vpp = ctypes.POINTER(vp)
     lib.neuzip_compress.argtypes = [vp, u64, i32, i32, vp, vpp]
     lib.neuzip_compress.restype = i32
+    lib.neuzip_compress_blockwise.argtypes = [vp, u64, i32, i32, u32, vp, vpp]
+    lib.neuzip_compress_blockwise.restype = i32
+    lib.neuzip_block_size.argtypes = [vp]
+    lib.neuzip_block_size.restype = u32
     lib.neuzip_decompress.argtypes = [vp, vp, u64, i32, vp]
     lib.neuzip_decompress.restype = i32
     lib.neuzip_decompress_sequence.argtypes = [vpp, u32, vp, u64, vp]
@@ -71,7 +75,7 @@ def _load():
 _lib = None
 _lib = _load()
 
-EXPORTED = ["neuzip_compress", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
+EXPORTED = ["neuzip_compress", "neuzip_compress_blockwise", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
             "neuzip_free",
             "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits",
             "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check",
@@ -126,12 +130,21 @@ class Blob:
     def mantissa_bits(self):
         return int(_lib.neuzip_mantissa_bits(self.handle))
 
+    @property
+    def block_size(self):
+        return int(_lib.neuzip_block_size(self.handle))
+
 
 def neuzip_compress(src: torch.Tensor, mantissa_bits: int = 7, stream=None, blob: Blob = None) -> Blob:
+    return neuzip_compress_blockwise(src, mantissa_bits, 0, stream, blob)
+
+
+def neuzip_compress_blockwise(src: torch.Tensor, mantissa_bits: int, block_size: int, stream=None,
+                              blob: Blob = None) -> Blob:
     _check_tensor(src)
     handle = ctypes.c_void_p(blob.handle.value if blob is not None else None)
-    rc = _lib.neuzip_compress(ctypes.c_void_p(src.data_ptr()), src.numel(), BF16, mantissa_bits,
-                              _stream_handle(stream), ctypes.byref(handle))
+    rc = _lib.neuzip_compress_blockwise(ctypes.c_void_p(src.data_ptr()), src.numel(), BF16, mantissa_bits,
+                                        block_size, _stream_handle(stream), ctypes.byref(handle))
     if rc != OK:
         raise NeuzipError(rc, "neuzip_compress")
     if blob is not None:

@@ -138,6 +138,37 @@ __device__ inline void store_fields(uint8_t *sm, uint64_t vec, uint64_t packed)
 }
 
 // ------------------------------------------------------------------------------------------
+// Block-wise normalisation of the lossy variant (Sec. 2.3): a block of 32..512 consecutive
+// weights shares one coefficient byte, the mantissa of its largest-magnitude weight; with
+// c = 1 + coef/128 a weight is stored as bf16(w / c) and comes back as bf16(stored * c), so the
+// largest weight is a power of two while stored and is not touched by the mantissa truncation.
+// IEEE binary32 arithmetic, results rounded to the nearest-even bf16; NaNs are passed through
+// with the quiet bit set, without going through the FP unit.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t bf16_round_bits(uint32_t bits32)
+{
+    return (bits32 + 0x7FFFu + ((bits32 >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ bool bf16_is_nan(uint32_t u) { return (u & 0x7FFFu) > 0x7F80u; }
+
+__device__ __forceinline__ uint32_t normalise_word(uint32_t u, float c)
+{
+    if (bf16_is_nan(u))
+        return u | 0x40u;
+    return bf16_round_bits(__float_as_uint(__uint_as_float(u << 16) / c)) & 0xFFFFu;
+}
+
+__device__ __forceinline__ uint32_t denormalise_word(uint32_t u, float c)
+{
+    if (bf16_is_nan(u))
+        return u | 0x40u;
+    return bf16_round_bits(__float_as_uint(__fmul_rn(__uint_as_float(u << 16), c))) & 0xFFFFu;
+}
+
+__device__ __forceinline__ float coefficient(uint32_t coef) { return 1.0f + static_cast<float>(coef) * 0.0078125f; }
+
+// ------------------------------------------------------------------------------------------
 // Kernel 1: exponent histogram fused with the sign|mantissa split (Alg. 1 "split").
 // One pass over the bf16 words: 2 B/elem read, (k+1)/8 B/elem written.  Counts go to 32
 // bank-private copies of the 256 bins in LDS (copy = lane mod 32, so the 64 lanes of a wave
@@ -207,6 +238,92 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const uint16_t
     }
     __syncthreads();
     // thread b sums the 32 copies of bin b, starting at a rotated copy to spread the banks
+    {
+        const uint32_t b = threadIdx.x;
+        uint32_t sum = 0;
+#pragma unroll 8
+        for (uint32_t i = 0; i < kHistCopies; ++i)
+            sum += bins[b * kHistCopies + ((i + b) & (kHistCopies - 1))];
+        if (sum)
+            atomicAdd(&counts[b], sum);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Kernel 1b: the same pass for block-wise normalised lossy compression.  A block of B weights
+// is B/8 neighbouring lanes (each lane holds 8 weights), so the largest magnitude of a block is
+// a shuffle reduction over 4..64 lanes; its mantissa is the block's coefficient.  The lane then
+// normalises its weights and proceeds as kernel 1 on the normalised words.
+// ------------------------------------------------------------------------------------------
+template <int KB>
+__global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const uint16_t *__restrict__ src, uint64_t n,
+                                                                      uint32_t block, uint8_t *__restrict__ coef_out,
+                                                                      uint8_t *__restrict__ sm,
+                                                                      uint32_t *__restrict__ counts)
+{
+    __shared__ uint32_t bins[256 * kHistCopies];
+    for (uint32_t i = threadIdx.x; i < 256 * kHistCopies; i += kHistThreads)
+        bins[i] = 0;
+    __syncthreads();
+
+    const uint32_t copy = threadIdx.x & (kHistCopies - 1);
+    const uint32_t lanes_per_block = block / 8;                 // 4 .. 64, a power of two
+    const uint64_t n_vec = (n + 7) / 8;                         // the last vector may be partial
+    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kHistThreads;
+    constexpr uint32_t per_byte = 8 / (KB + 1);
+    // the trip count is the same for all lanes of a wave, so every lane takes part in the shuffles
+    const uint64_t wave_first = static_cast<uint64_t>(blockIdx.x) * kHistThreads + (threadIdx.x & ~63u);
+    for (uint64_t base = wave_first; base < n_vec; base += stride) {
+        const uint64_t v = base + (threadIdx.x & 63u);
+        const uint64_t first = v * 8;
+        const uint32_t valid = first >= n ? 0u : (n - first < 8 ? static_cast<uint32_t>(n - first) : 8u);
+        uint32_t w[8];
+        if (valid == 8) {
+            const uint4 d = reinterpret_cast<const uint4 *>(src)[v];
+            const uint32_t q[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                w[2 * p] = q[p] & 0xFFFFu;
+                w[2 * p + 1] = q[p] >> 16;
+            }
+        } else {
+#pragma unroll
+            for (uint32_t t = 0; t < 8; ++t)
+                w[t] = t < valid ? src[first + t] : 0u;
+        }
+        // key = magnitude | earliest position wins ties | mantissa of that weight
+        uint32_t key = 0;
+        const uint32_t pos0 = static_cast<uint32_t>(first % block);
+#pragma unroll
+        for (uint32_t t = 0; t < 8; ++t) {
+            const uint32_t cand = ((w[t] & 0x7FFFu) << 16) | ((511u - (pos0 + t)) << 7) | (w[t] & 0x7Fu);
+            key = (t < valid && cand > key) ? cand : key;
+        }
+        for (uint32_t d = 1; d < lanes_per_block; d <<= 1) {
+            const uint32_t o = __shfl_xor(key, d, 64);
+            key = o > key ? o : key;
+        }
+        const uint32_t coef = key & 0x7Fu;
+        if (valid && pos0 == 0)
+            coef_out[first / block] = static_cast<uint8_t>(coef);
+        const float c = coefficient(coef);
+        uint64_t packed = 0;
+#pragma unroll
+        for (uint32_t t = 0; t < 8; ++t) {
+            if (t < valid) {
+                const uint32_t u = normalise_word(w[t], c);
+                atomicAdd(&bins[exponent_of(u) * kHistCopies + copy], 1u);
+                packed |= static_cast<uint64_t>(signmant_field<KB>(u)) << (t * (KB + 1));
+            }
+        }
+        if (valid == 8) {
+            store_fields<KB>(sm, v, packed);
+        } else {
+            for (uint32_t t = 0; t < valid; t += per_byte)  // whole bytes; a last partial byte has zero high bits
+                sm[(first + t) / per_byte] = static_cast<uint8_t>(packed >> (t * (KB + 1)));
+        }
+    }
+    __syncthreads();
     {
         const uint32_t b = threadIdx.x;
         uint32_t sum = 0;
@@ -422,7 +539,9 @@ __device__ __forceinline__ void ring_flush(uint32_t wp_before, uint32_t wp_after
     }
 }
 
+template <bool NORM>
 __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__restrict__ src, uint64_t n,
+                                                            const uint8_t *__restrict__ coef, uint32_t block,
                                                             uint32_t n_chunks, const EncSym *__restrict__ enc_g,
                                                             const TableBlock *__restrict__ tb,
                                                             uint32_t *__restrict__ states,
@@ -460,10 +579,16 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__r
             const uint4 d_next = src4[(q > 0 ? q - 1 : 0) * kStates];
             const uint32_t w[4] = {d.x, d.y, d.z, d.w};
             const uint32_t wp_before = st.wp;
+            // with block-wise normalisation the exponents coded are those of bf16(w / c)
+            float c = 1.0f;
+            if constexpr (NORM)
+                c = coefficient(coef[(base + static_cast<uint32_t>(q) * kTurn + j * kRun) / block]);
 #pragma unroll
             for (int p = 3; p >= 0; --p) {
-                rans_put(st, enc[exponent_of(w[p] >> 16)], ring);
-                rans_put(st, enc[exponent_of(w[p] & 0xFFFFu)], ring);
+                const uint32_t hi = NORM ? normalise_word(w[p] >> 16, c) : (w[p] >> 16);
+                const uint32_t lo = NORM ? normalise_word(w[p] & 0xFFFFu, c) : (w[p] & 0xFFFFu);
+                rans_put(st, enc[exponent_of(hi)], ring);
+                rans_put(st, enc[exponent_of(lo)], ring);
             }
             ring_flush(wp_before, st.wp, ring, slot);
             d = d_next;
@@ -473,8 +598,12 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__r
             const uint32_t wp_before = st.wp;
             for (int t = static_cast<int>(kRun) - 1; t >= 0; --t) {
                 const uint32_t i = static_cast<uint32_t>(q) * kTurn + j * kRun + static_cast<uint32_t>(t);
-                if (i < m)
-                    rans_put(st, enc[exponent_of(src[base + i])], ring);
+                if (i < m) {
+                    uint32_t u = src[base + i];
+                    if constexpr (NORM)
+                        u = normalise_word(u, coefficient(coef[(base + i) / block]));
+                    rans_put(st, enc[exponent_of(u)], ring);
+                }
             }
             ring_flush(wp_before, st.wp, ring, slot);
         }
@@ -715,9 +844,28 @@ __device__ __forceinline__ uint32_t rans_get(const uint32_t *__restrict__ lut, u
 // Walks one state over its part of chunk [base, base + m) and writes the merged bf16 words.
 // LONE: the tensor has a single exponent value (f = 4096): the state never moves and there are
 // no words.  Returns through x / wp what the well-formedness check needs.
-template <int KB, bool LONE, class WordSrc>
+// Field bits of 8 neighbouring elements; with block-wise normalisation (KB < 7, so the fields
+// take at most 32 bits) the block's coefficient byte rides in bits 32..39.
+template <int KB, bool NORM>
+__device__ __forceinline__ uint64_t load_turn(const uint8_t *__restrict__ sm, const uint8_t *__restrict__ coef,
+                                              uint32_t block, uint64_t first_elem)
+{
+    uint64_t f = load_fields<KB>(sm, first_elem);
+    if constexpr (NORM)
+        f |= static_cast<uint64_t>(coef[first_elem / block]) << 32;
+    return f;
+}
+
+// bf16(stored * c) on the two halves of a merged dword
+__device__ __forceinline__ uint32_t denormalise_pair(uint32_t d, float c)
+{
+    return denormalise_word(d & 0xFFFFu, c) | (denormalise_word(d >> 16, c) << 16);
+}
+
+template <int KB, bool LONE, bool NORM, class WordSrc>
 __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
                                            uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
+                                           const uint8_t *__restrict__ coef, uint32_t block,
                                            uint64_t (&fields)[kTurnGroup], uint16_t *__restrict__ out,
                                            uint64_t base, uint32_t m, uint32_t j)
 {
@@ -736,7 +884,7 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
             const uint32_t qn = q0 + kTurnGroup < kTurns ? q0 + kTurnGroup : q0;
 #pragma unroll
             for (uint32_t r = 0; r < kTurnGroup; ++r)
-                fields_next[r] = load_fields<KB>(sm, first + (qn + r) * kTurn);
+                fields_next[r] = load_turn<KB, NORM>(sm, coef, block, first + (qn + r) * kTurn);
             uint4 o[kTurnGroup];
 #pragma unroll
             for (uint32_t r = 0; r < kTurnGroup; ++r) {
@@ -748,6 +896,13 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
                 o[r].y = merge_pair<KB>(fields[r], 1, e[2], e[3]);
                 o[r].z = merge_pair<KB>(fields[r], 2, e[4], e[5]);
                 o[r].w = merge_pair<KB>(fields[r], 3, e[6], e[7]);
+                if constexpr (NORM) {
+                    const float c = coefficient(static_cast<uint32_t>(fields[r] >> 32) & 0x7Fu);
+                    o[r].x = denormalise_pair(o[r].x, c);
+                    o[r].y = denormalise_pair(o[r].y, c);
+                    o[r].z = denormalise_pair(o[r].z, c);
+                    o[r].w = denormalise_pair(o[r].w, c);
+                }
             }
 #pragma unroll
             for (uint32_t r = 0; r < kTurnGroup; ++r) {
@@ -766,8 +921,10 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
                 const uint32_t sym = (LONE ? lone : rans_get(lut, x, wp, next, src)) & 0xFFu;
                 const uint64_t g = base + i;
                 const uint32_t field = (sm[g / per_byte] >> ((g % per_byte) * width)) & ((1u << width) - 1u);
-                out[g] = static_cast<uint16_t>(((field >> KB) << 15) | (sym << 7) |
-                                               ((field & ((1u << KB) - 1u)) << (7 - KB)));
+                uint32_t u = ((field >> KB) << 15) | (sym << 7) | ((field & ((1u << KB) - 1u)) << (7 - KB));
+                if constexpr (NORM)
+                    u = denormalise_word(u, coefficient(coef[g / block]));
+                out[g] = static_cast<uint16_t>(u);
             }
         }
     }
@@ -781,21 +938,25 @@ struct DecodeArgs {
     const uint8_t *lens;
     const uint16_t *words;
     const uint8_t *sm;
+    const uint8_t *coef;  // block coefficients (block-wise normalised blobs only)
     uint16_t *out;
     uint32_t *status;
     uint64_t n;
     uint32_t n_chunks;
-    uint32_t wg_end;  // batches: first workgroup index after this tensor's
+    uint32_t block;       // 0: no block-wise normalisation
+    uint32_t wg_end;      // batches: first workgroup index after this tensor's
 };
 
 // Decodes the chunks of workgroup `wg` of one tensor.
-template <int KB>
+template <int KB, bool NORM>
 __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ tb,
                                                  const uint32_t *__restrict__ offsets,
                                                  const uint32_t *__restrict__ states,
                                                  const uint8_t *__restrict__ lens,
                                                  const uint16_t *__restrict__ words,
-                                                 const uint8_t *__restrict__ sm, uint16_t *__restrict__ out,
+                                                 const uint8_t *__restrict__ sm,
+                                                 const uint8_t *__restrict__ coef, uint32_t block,
+                                                 uint16_t *__restrict__ out,
                                                  uint64_t n, uint32_t n_chunks, uint32_t *__restrict__ status,
                                                  uint32_t wg, uint32_t *__restrict__ lut, uint8_t *__restrict__ stage)
 {
@@ -821,7 +982,7 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
     uint64_t fields0[kTurnGroup];
 #pragma unroll
     for (uint32_t r = 0; r < kTurnGroup; ++r)
-        fields0[r] = m == kChunk ? load_fields<KB>(sm, base + r * kTurn + j * kRun) : 0;
+        fields0[r] = m == kChunk ? load_turn<KB, NORM>(sm, coef, block, base + r * kTurn + j * kRun) : 0;
     const uint4 *lut_g = reinterpret_cast<const uint4 *>(tb->lut);
     uint4 lut_piece[2];  // 16 KB table / 16 B = 1024 pieces; 2 per thread at 512 threads
 #pragma unroll
@@ -869,28 +1030,28 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
 
     uint32_t wp = 0, wp_begin = 0;
     if (lone < 256) {
-        walk_state<KB, true>(lut, NoWords{}, lone, x, wp, sm, fields0, out, base, m, j);
+        walk_state<KB, true, NORM>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j);
     } else if (staged) {
         wp = wp_begin = static_cast<uint32_t>(run_byte - aligned0);
-        walk_state<KB, false>(lut, LdsWords{stage}, 0u, x, wp, sm, fields0, out, base, m, j);
+        walk_state<KB, false, NORM>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m, j);
     } else {
         // the runs of this workgroup's chunks did not fit the LDS window (more than ~4 bits per
         // symbol): read the words straight from the blob
-        walk_state<KB, false>(lut, GlobalWords{reinterpret_cast<const uint8_t *>(words) + run_byte}, 0u, x, wp, sm,
-                              fields0, out, base, m, j);
+        walk_state<KB, false, NORM>(lut, GlobalWords{reinterpret_cast<const uint8_t *>(words) + run_byte}, 0u, x, wp,
+                                    sm, coef, block, fields0, out, base, m, j);
     }
     // a well-formed run is consumed exactly and leaves the state where the encoder started
     if (x != kRansL || wp - wp_begin != 2 * len)
         atomicOr(status, 1u);
 }
 
-template <int KB>
+template <int KB, bool NORM>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(const DecodeArgs a)
 {
     __shared__ __align__(16) uint32_t lut[kM];
     __shared__ __align__(16) uint8_t stage[kStageBytes];
-    decode_workgroup<KB>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.out, a.n, a.n_chunks, a.status,
-                         blockIdx.x, lut, stage);
+    decode_workgroup<KB, NORM>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.out, a.n,
+                               a.n_chunks, a.status, blockIdx.x, lut, stage);
 }
 
 // Several tensors in one launch (a layer's weights): workgroups [t[i-1].wg_end, t[i].wg_end)
@@ -901,7 +1062,7 @@ struct BatchArgs {
     uint32_t count;
 };
 
-template <int KB>
+template <int KB, bool NORM>
 __global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchArgs b)
 {
     __shared__ __align__(16) uint32_t lut[kM];
@@ -912,18 +1073,21 @@ __global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchAr
         ++i;
     }
     const DecodeArgs &a = b.t[i];
-    decode_workgroup<KB>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.out, a.n, a.n_chunks, a.status,
-                         blockIdx.x - first, lut, stage);
+    decode_workgroup<KB, NORM>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.out, a.n,
+                               a.n_chunks, a.status, blockIdx.x - first, lut, stage);
 }
 
 // ------------------------------------------------------------------------------------------
 // Host side
 // ------------------------------------------------------------------------------------------
+inline bool valid_block(uint32_t b) { return b == 32 || b == 64 || b == 128 || b == 256 || b == 512; }
+inline uint64_t block_count(uint64_t n, uint32_t block) { return block ? (n + block - 1) / block : 0; }
+
 struct Layout {
-    uint64_t offsets, states, lens, sm, total;  // byte positions inside the fixed allocation
+    uint64_t offsets, states, lens, sm, coef, total;  // byte positions inside the fixed allocation
 };
 
-Layout fixed_layout(uint64_t n, int k)
+Layout fixed_layout(uint64_t n, int k, uint32_t block)
 {
     const uint64_t nc = chunks_of(n);
     Layout l;
@@ -931,15 +1095,16 @@ Layout fixed_layout(uint64_t n, int k)
     l.states = l.offsets + pad_to((nc + 2) * 4, 256);
     l.lens = l.states + pad_to(nc * kStates * 4, 256);
     l.sm = l.lens + pad_to(nc * kStates, 256);
-    l.total = l.sm + pad_to(signmant_bytes(n, k), 256) + 256;
+    l.coef = l.sm + pad_to(signmant_bytes(n, k), 256) + 256;
+    l.total = l.coef + pad_to(block_count(n, block), 256);
     return l;
 }
 
 struct Container {
-    uint64_t freq, offsets, states, lens, words, sm, total;  // byte positions in the flat container
+    uint64_t freq, offsets, states, lens, words, sm, coef, total;  // byte positions in the flat container
 };
 
-Container container_layout(uint64_t n, int k, uint64_t total_words)
+Container container_layout(uint64_t n, int k, uint64_t total_words, uint32_t block)
 {
     const uint64_t nc = chunks_of(n);
     Container c;
@@ -949,7 +1114,8 @@ Container container_layout(uint64_t n, int k, uint64_t total_words)
     c.lens = c.states + nc * kStates * 4;
     c.words = c.lens + nc * kStates;
     c.sm = c.words + pad_to(total_words * 2, 16);
-    c.total = c.sm + pad_to(signmant_bytes(n, k), 16);
+    c.coef = c.sm + pad_to(signmant_bytes(n, k), 16);
+    c.total = c.coef + pad_to(block_count(n, block), 16);
     return c;
 }
 
@@ -960,6 +1126,7 @@ struct neuzip_blob {
     int device;
     uint64_t n;
     int k;
+    uint32_t block;  // block size of the block-wise normalisation, 0 = none
     uint32_t n_chunks;
     uint64_t total_words;
     uint8_t *fixed;
@@ -981,6 +1148,7 @@ inline uint32_t *offsets_of(const neuzip_blob *b) { return reinterpret_cast<uint
 inline uint32_t *states_of(const neuzip_blob *b) { return reinterpret_cast<uint32_t *>(b->fixed + b->at.states); }
 inline uint8_t *lens_of(const neuzip_blob *b) { return b->fixed + b->at.lens; }
 inline uint8_t *sm_of(const neuzip_blob *b) { return b->fixed + b->at.sm; }
+inline uint8_t *coef_of(const neuzip_blob *b) { return b->fixed + b->at.coef; }
 inline bool is_blob(const neuzip_blob *b) { return b && b->magic == kBlobMagic; }
 
 // Per-process compress workspace (encoder constants, run slots, pinned staging for the size read).
@@ -1111,7 +1279,7 @@ int ensure_workspace(int device, uint32_t n_chunks, hipStream_t stream)
     return NEUZIP_OK;
 }
 
-int alloc_blob(uint64_t n, int k, neuzip_blob **out)
+int alloc_blob(uint64_t n, int k, uint32_t block, neuzip_blob **out)
 {
     neuzip_blob *b = new (std::nothrow) neuzip_blob();
     if (!b)
@@ -1120,8 +1288,9 @@ int alloc_blob(uint64_t n, int k, neuzip_blob **out)
     b->magic = kBlobMagic;
     b->n = n;
     b->k = k;
+    b->block = block;
     b->n_chunks = chunks_of(n);
-    b->at = fixed_layout(n, k);
+    b->at = fixed_layout(n, k, block);
     if (!hip_ok(hipGetDevice(&b->device))) {
         delete b;
         return NEUZIP_EHIP;
@@ -1159,7 +1328,7 @@ int reserve_words(neuzip_blob *b, uint64_t total_words)
 template <int KB>
 int launch_hist(const void *d_src, uint64_t n, neuzip_blob *b, hipStream_t stream)
 {
-    const uint64_t n_vec = n / 8;
+    const uint64_t n_vec = (n + 7) / 8;
     // every workgroup pays for clearing and merging its 32 KB of bins: give it at least 8 vectors
     // (64 elements) per thread, and launch no more workgroups than fit the chip at once
     uint64_t groups = (n_vec + kHistThreads * 8 - 1) / (kHistThreads * 8);
@@ -1167,8 +1336,13 @@ int launch_hist(const void *d_src, uint64_t n, neuzip_blob *b, hipStream_t strea
         groups = 1;
     if (groups > 1280)
         groups = 1280;
-    hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(static_cast<uint32_t>(groups)), dim3(kHistThreads), 0, stream,
-                       static_cast<const uint16_t *>(d_src), n, sm_of(b), g_ws.counts);
+    if (b->block)
+        hipLaunchKernelGGL(hist_split_norm_kernel<KB>, dim3(static_cast<uint32_t>(groups)), dim3(kHistThreads), 0,
+                           stream, static_cast<const uint16_t *>(d_src), n, b->block, coef_of(b), sm_of(b),
+                           g_ws.counts);
+    else
+        hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(static_cast<uint32_t>(groups)), dim3(kHistThreads), 0, stream,
+                           static_cast<const uint16_t *>(d_src), n, sm_of(b), g_ws.counts);
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
 
@@ -1195,6 +1369,8 @@ DecodeArgs decode_args(const neuzip_blob *b, void *d_dst)
     a.lens = lens_of(b);
     a.words = reinterpret_cast<const uint16_t *>(b->words);
     a.sm = sm_of(b);
+    a.coef = coef_of(b);
+    a.block = b->block;
     a.out = static_cast<uint16_t *>(d_dst);
     a.status = table_of(b)->status;
     a.n = b->n;
@@ -1203,12 +1379,13 @@ DecodeArgs decode_args(const neuzip_blob *b, void *d_dst)
     return a;
 }
 
-template <int KB>
+template <int KB, bool NORM>
 int launch_decode(const neuzip_blob *b, void *d_dst, hipStream_t stream)
 {
     const uint32_t per = decode_chunks_per_wg();
     const uint32_t groups = (b->n_chunks + per - 1) / per;
-    hipLaunchKernelGGL(decode_kernel<KB>, dim3(groups), dim3(per * kStates), 0, stream, decode_args(b, d_dst));
+    hipLaunchKernelGGL((decode_kernel<KB, NORM>), dim3(groups), dim3(per * kStates), 0, stream,
+                       decode_args(b, d_dst));
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
 
@@ -1216,22 +1393,35 @@ int decode_dispatch(const neuzip_blob *b, void *d_dst, hipStream_t stream)
 {
     if (b->n == 0)
         return NEUZIP_OK;
+    if (b->block) {
+        switch (b->k) {
+        case 3: return launch_decode<3, true>(b, d_dst, stream);
+        case 1: return launch_decode<1, true>(b, d_dst, stream);
+        default: return launch_decode<0, true>(b, d_dst, stream);
+        }
+    }
     switch (b->k) {
-    case 7: return launch_decode<7>(b, d_dst, stream);
-    case 3: return launch_decode<3>(b, d_dst, stream);
-    case 1: return launch_decode<1>(b, d_dst, stream);
-    default: return launch_decode<0>(b, d_dst, stream);
+    case 7: return launch_decode<7, false>(b, d_dst, stream);
+    case 3: return launch_decode<3, false>(b, d_dst, stream);
+    case 1: return launch_decode<1, false>(b, d_dst, stream);
+    default: return launch_decode<0, false>(b, d_dst, stream);
     }
 }
 
-int launch_batch(const BatchArgs &args, int k, uint32_t groups, hipStream_t stream)
+// variant = mantissa_bits, + 8 for block-wise normalised blobs
+inline int decode_variant(const neuzip_blob *b) { return b->k + (b->block ? 8 : 0); }
+
+int launch_batch(const BatchArgs &args, int variant, uint32_t groups, hipStream_t stream)
 {
     const dim3 grid(groups), block(kDecThreads);
-    switch (k) {
-    case 7: hipLaunchKernelGGL(decode_batch_kernel<7>, grid, block, 0, stream, args); break;
-    case 3: hipLaunchKernelGGL(decode_batch_kernel<3>, grid, block, 0, stream, args); break;
-    case 1: hipLaunchKernelGGL(decode_batch_kernel<1>, grid, block, 0, stream, args); break;
-    default: hipLaunchKernelGGL(decode_batch_kernel<0>, grid, block, 0, stream, args); break;
+    switch (variant) {
+    case 7: hipLaunchKernelGGL((decode_batch_kernel<7, false>), grid, block, 0, stream, args); break;
+    case 3: hipLaunchKernelGGL((decode_batch_kernel<3, false>), grid, block, 0, stream, args); break;
+    case 1: hipLaunchKernelGGL((decode_batch_kernel<1, false>), grid, block, 0, stream, args); break;
+    case 0: hipLaunchKernelGGL((decode_batch_kernel<0, false>), grid, block, 0, stream, args); break;
+    case 11: hipLaunchKernelGGL((decode_batch_kernel<3, true>), grid, block, 0, stream, args); break;
+    case 9: hipLaunchKernelGGL((decode_batch_kernel<1, true>), grid, block, 0, stream, args); break;
+    default: hipLaunchKernelGGL((decode_batch_kernel<0, true>), grid, block, 0, stream, args); break;
     }
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
@@ -1246,7 +1436,15 @@ extern "C" {
 int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa_bits, void *hip_stream,
                     neuzip_blob **blob)
 {
+    return neuzip_compress_blockwise(d_src, n_elems, dtype, mantissa_bits, 0, hip_stream, blob);
+}
+
+int neuzip_compress_blockwise(const void *d_src, uint64_t n_elems, int dtype, int mantissa_bits,
+                              uint32_t block_size, void *hip_stream, neuzip_blob **blob)
+{
     if (!blob || dtype != NEUZIP_BF16 || !valid_k(mantissa_bits))
+        return NEUZIP_EINVAL;
+    if (block_size != 0 && (!valid_block(block_size) || mantissa_bits == 7))
         return NEUZIP_EINVAL;
     if (n_elems > 0 && (!d_src || (reinterpret_cast<uintptr_t>(d_src) & 15u)))
         return NEUZIP_EINVAL;
@@ -1256,10 +1454,10 @@ int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa
 
     neuzip_blob *b = *blob;
     const bool fresh = (b == nullptr);
-    if (!fresh && (!is_blob(b) || b->n != n_elems || b->k != mantissa_bits))
+    if (!fresh && (!is_blob(b) || b->n != n_elems || b->k != mantissa_bits || b->block != block_size))
         return NEUZIP_EINVAL;
     if (fresh) {
-        const int rc = alloc_blob(n_elems, mantissa_bits, &b);
+        const int rc = alloc_blob(n_elems, mantissa_bits, block_size, &b);
         if (rc != NEUZIP_OK)
             return rc;
     }
@@ -1311,9 +1509,15 @@ int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa
     if (hip_ok(hipGetLastError()))
         bins_dirty = false;
     const uint32_t n_groups = (nc + kChunksPerGroup - 1) / kChunksPerGroup;
-    hipLaunchKernelGGL(encode_kernel, dim3(n_groups), dim3(kEncThreads), 0, stream,
-                       static_cast<const uint16_t *>(d_src), n_elems, nc, g_ws.enc, table_of(b), states_of(b),
-                       lens_of(b), g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned);
+    if (b->block)
+        hipLaunchKernelGGL(encode_kernel<true>, dim3(n_groups), dim3(kEncThreads), 0, stream,
+                           static_cast<const uint16_t *>(d_src), n_elems, coef_of(b), b->block, nc, g_ws.enc,
+                           table_of(b), states_of(b), lens_of(b), g_ws.chunk_words, g_ws.group_words, g_ws.slots,
+                           g_ws.pinned);
+    else
+        hipLaunchKernelGGL(encode_kernel<false>, dim3(n_groups), dim3(kEncThreads), 0, stream,
+                           static_cast<const uint16_t *>(d_src), n_elems, coef_of(b), 1u, nc, g_ws.enc, table_of(b),
+                           states_of(b), lens_of(b), g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned);
     const uint32_t seq = ++g_ws.seq;
     hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kScanThreads), 0, stream, g_ws.group_words, n_groups,
                        g_ws.group_prefix, offsets_of(b) + nc, g_ws.pinned, seq);
@@ -1383,9 +1587,10 @@ int neuzip_decompress_batch(const neuzip_blob *const *blobs, void *const *d_dsts
             return NEUZIP_EINVAL;
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    // tensors of equal mantissa_bits share launches of up to kBatchMax tensors, in the given order
-    static const int ks[4] = {7, 3, 1, 0};
-    for (int k : ks) {
+    // tensors of the same kind (mantissa_bits, normalised or not) share launches of up to
+    // kBatchMax tensors, in the given order
+    static const int kinds[7] = {7, 3, 1, 0, 11, 9, 8};
+    for (int k : kinds) {
         BatchArgs args;
         args.count = 0;
         uint32_t groups = 0;
@@ -1401,7 +1606,7 @@ int neuzip_decompress_batch(const neuzip_blob *const *blobs, void *const *d_dsts
             if (i == count)
                 break;
             const neuzip_blob *b = blobs[i];
-            if (b->k != k || b->n == 0)
+            if (decode_variant(b) != k || b->n == 0)
                 continue;
             DecodeArgs a = decode_args(b, d_dsts[i]);
             groups += (b->n_chunks + kDecChunksPerWg - 1) / kDecChunksPerWg;
@@ -1434,7 +1639,7 @@ uint64_t neuzip_compressed_bytes(const neuzip_blob *blob)
 {
     if (!is_blob(blob))
         return 0;
-    return container_layout(blob->n, blob->k, blob->total_words).total;
+    return container_layout(blob->n, blob->k, blob->total_words, blob->block).total;
 }
 
 uint64_t neuzip_device_bytes(const neuzip_blob *blob)
@@ -1445,13 +1650,14 @@ uint64_t neuzip_device_bytes(const neuzip_blob *blob)
 }
 
 uint64_t neuzip_elems(const neuzip_blob *blob) { return is_blob(blob) ? blob->n : 0; }
+uint32_t neuzip_block_size(const neuzip_blob *blob) { return is_blob(blob) ? blob->block : 0; }
 int neuzip_mantissa_bits(const neuzip_blob *blob) { return is_blob(blob) ? blob->k : -1; }
 
 int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *written, void *hip_stream)
 {
     if (!is_blob(blob))
         return NEUZIP_EINVAL;
-    const Container lay = container_layout(blob->n, blob->k, blob->total_words);
+    const Container lay = container_layout(blob->n, blob->k, blob->total_words, blob->block);
     if (written)
         *written = lay.total;
     if (!h_buf)
@@ -1473,6 +1679,7 @@ int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *
     put32(32, kRun);
     put32(36, blob->n_chunks);
     put64(40, blob->total_words);
+    put32(48, blob->block);
     const uint64_t nc = blob->n_chunks;
     NZ_HIP(hipMemcpyAsync(p + lay.freq, table_of(blob)->freq, 512, hipMemcpyDeviceToHost, stream));
     NZ_HIP(hipMemcpyAsync(p + lay.offsets, offsets_of(blob), (nc + 1) * 4, hipMemcpyDeviceToHost, stream));
@@ -1484,6 +1691,9 @@ int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *
         NZ_HIP(hipMemcpyAsync(p + lay.words, blob->words, blob->total_words * 2, hipMemcpyDeviceToHost, stream));
     if (blob->n)
         NZ_HIP(hipMemcpyAsync(p + lay.sm, sm_of(blob), signmant_bytes(blob->n, blob->k), hipMemcpyDeviceToHost,
+                              stream));
+    if (blob->n && blob->block)
+        NZ_HIP(hipMemcpyAsync(p + lay.coef, coef_of(blob), block_count(blob->n, blob->block), hipMemcpyDeviceToHost,
                               stream));
     NZ_HIP(hipStreamSynchronize(stream));
     return NEUZIP_OK;
@@ -1504,12 +1714,15 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
     const uint64_t n = get64(8);
     const int k = static_cast<int>(get32(16));
     const uint64_t total_words = get64(40);
+    const uint32_t block = get32(48);
     if (!valid_k(k) || n >= (1ull << 32) || total_words >= (1ull << 32))
+        return NEUZIP_ECORRUPT;
+    if (block != 0 && (!valid_block(block) || k == 7))
         return NEUZIP_ECORRUPT;
     const uint32_t nc = chunks_of(n);
     if (get32(36) != nc)
         return NEUZIP_ECORRUPT;
-    const Container lay = container_layout(n, k, total_words);
+    const Container lay = container_layout(n, k, total_words, block);
     if (lay.total != len)
         return NEUZIP_ECORRUPT;
 
@@ -1542,7 +1755,7 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
         return NEUZIP_ECORRUPT;
 
     neuzip_blob *b = nullptr;
-    int rc = alloc_blob(n, k, &b);
+    int rc = alloc_blob(n, k, block, &b);
     if (rc != NEUZIP_OK)
         return rc;
     auto fail = [&](int code) {
@@ -1580,6 +1793,13 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
         return fail(NEUZIP_EHIP);
     if (n && !hip_ok(hipMemcpyAsync(sm_of(b), p + lay.sm, signmant_bytes(n, k), hipMemcpyHostToDevice, stream)))
         return fail(NEUZIP_EHIP);
+    if (n && block) {
+        for (uint64_t i = 0; i < block_count(n, block); ++i)
+            if (p[lay.coef + i] > 127)
+                return fail(NEUZIP_ECORRUPT);
+        if (!hip_ok(hipMemcpyAsync(coef_of(b), p + lay.coef, block_count(n, block), hipMemcpyHostToDevice, stream)))
+            return fail(NEUZIP_EHIP);
+    }
     if (!hip_ok(hipStreamSynchronize(stream)))  // tb and zeros must outlive the copies
         return fail(NEUZIP_EHIP);
     *blob = b;

@@ -22,13 +22,14 @@ def nz():
     return binding
 
 
-def roundtrip_and_compare(nz, w: torch.Tensor, k: int, threads: int = 16):
+def roundtrip_and_compare(nz, w: torch.Tensor, k: int, threads: int = 16, block: int = 0):
     """Compress on the GPU, compare container and decoded words with the oracle's."""
     words = inputs.bits(w)
     n = words.size
-    blob = nz.neuzip_compress(w, k)
+    blob = nz.neuzip_compress_blockwise(w, k, block)
+    assert blob.block_size == block and blob.mantissa_bits == k and blob.elems == n
     got = nz.neuzip_export(blob)
-    want = O.compress(words, k, threads=threads)
+    want = O.compress(words, k, threads=threads, block=block)
     assert got.size == want.size == blob.compressed_bytes
     if not np.array_equal(got, want):
         sec = O.sections(want)
@@ -37,8 +38,8 @@ def roundtrip_and_compare(nz, w: torch.Tensor, k: int, threads: int = 16):
     out = torch.full_like(w, float("nan"))
     nz.neuzip_decompress(blob, out)
     nz.neuzip_check(blob)
-    expect = O.truncate(words, k)
-    assert np.array_equal(inputs.bits(out), expect), f"decoded words differ (n={n}, k={k})"
+    expect = O.lossy_blockwise(words, k, block) if block else O.truncate(words, k)
+    assert np.array_equal(inputs.bits(out), expect), f"decoded words differ (n={n}, k={k}, block={block})"
     # the oracle reads the GPU's container, the GPU reads the oracle's
     assert np.array_equal(O.decompress(got, n, threads=threads), expect)
     theirs = nz.neuzip_import(want)
@@ -116,6 +117,46 @@ def test_rare_symbols_and_long_runs(nz):
     w = (u - 65536 * (u >= 32768)).to(torch.int16).view(torch.bfloat16)
     roundtrip_and_compare(nz, w, 7)
     roundtrip_and_compare(nz, w, 1)
+
+
+@pytest.mark.parametrize("k", [3, 1, 0])
+@pytest.mark.parametrize("block", [32, 64, 128, 256, 512])
+def test_blockwise_normalisation(nz, k, block):
+    # Sec. 2.3: lossy variant with one 8-bit coefficient per block
+    for n in (1, 33, 4096, 4097 + block // 2, 300_007):
+        w = inputs.student_t4_bf16(n, 9000 + n + block, device=DEV)
+        roundtrip_and_compare(nz, w, k, block=block)
+
+
+@pytest.mark.parametrize("k", [3, 0])
+def test_blockwise_normalisation_on_every_pattern(nz, k):
+    # subnormals, zeros, infinities and NaNs go through the same arithmetic as on the CPU
+    w = inputs.all_patterns_bf16(device=DEV)
+    roundtrip_and_compare(nz, w, k, block=64)
+    perm = torch.randperm(65536, generator=torch.Generator().manual_seed(7 + k)).to(DEV)
+    roundtrip_and_compare(nz, w[perm].contiguous(), k, block=512)
+
+
+def test_blockwise_keeps_the_largest_weight_of_each_block(nz):
+    n, block = 1 << 20, 512
+    w = inputs.student_t4_bf16(n, 9100, device=DEV)
+    blob = nz.neuzip_compress_blockwise(w, 0, block)
+    out = torch.empty_like(w)
+    nz.neuzip_decompress(blob, out)
+    a = w.float().view(-1, block)
+    idx = a.abs().argmax(dim=1, keepdim=True)
+    assert torch.equal(torch.gather(out.float().view(-1, block), 1, idx), torch.gather(a, 1, idx))
+    # 8 bits per block; the exponent stream changes a little because normalised weights are coded
+    plain = nz.neuzip_compress(w, 0)
+    sec = O.sections(nz.neuzip_export(blob))
+    assert sec["coef"][1] - sec["coef"][0] == n // block
+    assert abs(blob.compressed_bytes - plain.compressed_bytes - n // block) < 0.02 * plain.compressed_bytes
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_compress_blockwise(w, 7, block)
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_compress_blockwise(w, 3, 48)
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_compress(w, 0, blob=blob)                      # a normalised blob is not reused as a plain one
 
 
 def test_empty_tensor(nz):

@@ -37,7 +37,7 @@ def test_library_exports_every_declared_symbol(nz):
 def test_binding_mirrors_the_header(nz):
     for name in declared_functions():
         if name in ("neuzip_strerror", "neuzip_last_hip_error", "neuzip_elems", "neuzip_mantissa_bits",
-                    "neuzip_device_bytes"):
+                    "neuzip_device_bytes", "neuzip_block_size"):
             continue  # surfaced as Blob properties / NeuzipError fields
         assert hasattr(nz, name), f"binding lacks {name}"
 
@@ -66,6 +66,10 @@ def test_argument_validation_happens_before_device_work(nz):
     assert lib.neuzip_compress(ctypes.c_void_p(0x1002), 16, 0, 7, None, ctypes.byref(handle)) == nz.EINVAL
     assert lib.neuzip_compress(None, 16, 0, 7, None, ctypes.byref(handle)) == nz.EINVAL
     assert lib.neuzip_compress(fake, 1 << 32, 0, 7, None, ctypes.byref(handle)) == nz.EUNSUPPORTED
+    # block-wise normalisation: only the lossy widths, only the listed block sizes
+    assert lib.neuzip_compress_blockwise(fake, 16, 0, 7, 512, None, ctypes.byref(handle)) == nz.EINVAL
+    assert lib.neuzip_compress_blockwise(fake, 16, 0, 3, 100, None, ctypes.byref(handle)) == nz.EINVAL
+    assert lib.neuzip_compress_blockwise(fake, 16, 0, 3, 16, None, ctypes.byref(handle)) == nz.EINVAL
     assert handle.value is None
     # calls on something that is not a blob
     junk = (ctypes.c_uint8 * 256)()
