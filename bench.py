@@ -202,7 +202,27 @@ def main():
                                     "hbm_frac": round((b4.compressed_bytes + 2.0 * n4) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                                     "bits_per_weight": round(8.0 * b4.compressed_bytes / n4, 4)}
             nz.neuzip_free(b4)
-        del t4, buf
+        # the same weight with block-wise normalisation (Sec. 2.3; block 512 is the paper's default)
+        ref = t4.reshape(-1).float()
+        for k, blk in ((3, 512), (0, 512), (0, 32)):
+            plain = nz.neuzip_compress(t4, k)
+            nz.neuzip_decompress(plain, buf)
+            err_plain = ((buf.float() - ref).abs().mean() / ref.abs().mean()).item()
+            nz.neuzip_free(plain)
+            b4 = nz.neuzip_compress_blockwise(t4, k, blk)
+            for _ in range(5):
+                nz.neuzip_decompress(b4, buf)
+            _, ms = timed_region(torch, stream, lambda: nz.neuzip_decompress(b4, buf), 50)
+            ms /= 50
+            err = ((buf.float() - ref).abs().mean() / ref.abs().mean()).item()
+            ext[f"config4_k{k}_block{blk}"] = {
+                "decompress_GBps_output": round(2.0 * n4 / (ms * 1e-3) / 1e9, 1),
+                "hbm_frac": round((b4.compressed_bytes + 2.0 * n4) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "bits_per_weight": round(8.0 * b4.compressed_bytes / n4, 4),
+                "mean_abs_error_over_mean_abs_weight": round(err, 5),
+                "same_without_normalisation": round(err_plain, 5)}
+            nz.neuzip_free(b4)
+        del t4, buf, ref
         torch.cuda.empty_cache()
 
         # config 3: every weight of a Llama-3-8B-shaped model, forward order, one reusable scratch

@@ -70,6 +70,22 @@ def test_config4_lossy_70b_mlp_weight(nz, k):
     assert blob.compressed_bytes == O.compress(inputs.bits(w), k, threads=THREADS).size
 
 
+@pytest.mark.parametrize("k,block", [(3, 512), (0, 512), (1, 32)])
+def test_config4_with_blockwise_normalisation(nz, k, block):
+    w = inputs.student_t4_bf16(inputs.MLP_70B, inputs.seed_for(4), device=DEV)
+    blob = nz.neuzip_compress_blockwise(w, k, block)
+    out = torch.empty(w.numel(), dtype=torch.bfloat16, device=DEV)
+    nz.neuzip_decompress(blob, out)
+    nz.neuzip_check(blob)
+    words = inputs.bits(w)
+    assert np.array_equal(nz.neuzip_export(blob), O.compress(words, k, threads=THREADS, block=block))
+    sample = slice(0, 8_000_000)                       # the three-step definition on a prefix of whole blocks
+    assert np.array_equal(inputs.bits(out)[sample], O.lossy_blockwise(words[sample], k, block))
+    a = w.reshape(-1).float().view(-1, block)
+    idx = a.abs().argmax(dim=1, keepdim=True)
+    assert torch.equal(torch.gather(out.float().view(-1, block), 1, idx), torch.gather(a, 1, idx))
+
+
 def test_config3_forward_schedule_llama3_8b_shapes(nz):
     names = inputs.llama3_8b_tensors()
     assert len(names) == 225
