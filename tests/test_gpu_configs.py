@@ -140,3 +140,30 @@ def test_config5_training_step_loop(nz):
             del new
         for blob in blobs:
             nz.neuzip_check(blob)
+
+
+def test_tensor_of_more_than_2_to_31_elements(nz):
+    # 64-bit indexing: 2^31 + 4099 elements (4.3 GB of bf16), ragged tail included
+    n = (1 << 31) + 4099
+    w = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    piece = 1 << 28
+    for i, at in enumerate(range(0, n, piece)):                 # filled in pieces to bound temporaries
+        m = min(piece, n - at)
+        w[at: at + m] = inputs.gaussian_bf16(m, inputs.seed_for(7, i), device=DEV)
+    blob = nz.neuzip_compress(w, 7)
+    out = torch.zeros_like(w)
+    nz.neuzip_decompress(blob, out)
+    nz.neuzip_check(blob)
+    assert torch.equal(out.view(torch.int16), w.view(torch.int16))
+    assert 8 * blob.compressed_bytes / n < 10.76
+    # the last chunks, which sit behind the 2^32-byte mark, against the oracle
+    tail = 3 * 4096 + 4099
+    words = inputs.bits(w[n - tail:])
+    container = nz.neuzip_export(blob)
+    assert container.size == blob.compressed_bytes
+    info = O.blob_info(container)
+    assert info["n"] == n and info["k"] == 7
+    cnt = nz.neuzip_histogram(blob)
+    assert int(cnt.astype(np.uint64).sum()) == n
+    assert np.array_equal(nz.neuzip_frequencies(blob), O.quantise(cnt.astype(np.uint64)))
+    assert np.array_equal(inputs.bits(out[n - tail:]), words)
