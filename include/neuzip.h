@@ -99,6 +99,23 @@ int neuzip_compress_blockwise(const void *d_src, uint64_t n_elems, int dtype, in
                               uint32_t block_size, void *hip_stream, neuzip_blob **blob);
 
 /*
+ * neuzip_compress_batch -- the same compression (Alg. 1 backward loop: "split", "compression",
+ * "store" for every weight of a layer after its update) for several tensors at once: each
+ * kernel of the pipeline runs once per group of up to 8 tensors and the host waits once per
+ * group, so small tensors overlap with the others.
+ *
+ *   d_srcs, n_elems  host arrays of count entries: device pointer (16-byte aligned) and element
+ *                    count of each tensor.
+ *   mantissa_bits, block_size   shared by all tensors; meaning as above.
+ *   blobs            host array of count handles, in/out with the rules of neuzip_compress
+ *                    (NULL entries are created; other entries must match and be distinct).
+ * On error, blobs created for the failing group are released and its entries of blobs are
+ * not changed; groups completed before keep their results.
+ */
+int neuzip_compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int dtype,
+                          int mantissa_bits, uint32_t block_size, void *hip_stream, neuzip_blob **blobs);
+
+/*
  * neuzip_decompress -- Sec. 2.2 Eq. (3), Alg. 1 "decompression" + "merge":
  * decodes the exponents and reassembles bf16 words into the caller's
  * temporary space in one fused kernel.

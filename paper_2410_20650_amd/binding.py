@@ -35,6 +35,8 @@ def _load():
     lib.neuzip_compress.restype = i32
     lib.neuzip_compress_blockwise.argtypes = [vp, u64, i32, i32, u32, vp, vpp]
     lib.neuzip_compress_blockwise.restype = i32
+    lib.neuzip_compress_batch.argtypes = [vpp, ctypes.POINTER(u64), u32, i32, i32, u32, vp, vpp]
+    lib.neuzip_compress_batch.restype = i32
     lib.neuzip_block_size.argtypes = [vp]
     lib.neuzip_block_size.restype = u32
     lib.neuzip_decompress.argtypes = [vp, vp, u64, i32, vp]
@@ -75,7 +77,7 @@ def _load():
 _lib = None
 _lib = _load()
 
-EXPORTED = ["neuzip_compress", "neuzip_compress_blockwise", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
+EXPORTED = ["neuzip_compress", "neuzip_compress_blockwise", "neuzip_compress_batch", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
             "neuzip_free",
             "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits",
             "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check",
@@ -151,6 +153,31 @@ def neuzip_compress_blockwise(src: torch.Tensor, mantissa_bits: int, block_size:
         blob.handle = handle
         return blob
     return Blob(handle.value)
+
+
+def neuzip_compress_batch(srcs, mantissa_bits: int = 7, block_size: int = 0, stream=None, blobs=None):
+    """Compresses several tensors with one pass of the pipeline; returns one Blob per tensor."""
+    for t in srcs:
+        _check_tensor(t)
+    if blobs is not None and len(blobs) != len(srcs):
+        raise ValueError("one blob per tensor")
+    count = len(srcs)
+    ptrs = (ctypes.c_void_p * count)(*[t.data_ptr() for t in srcs])
+    sizes = (ctypes.c_uint64 * count)(*[t.numel() for t in srcs])
+    handles = (ctypes.c_void_p * count)(*[(b.handle.value if b is not None else None)
+                                          for b in (blobs if blobs is not None else [None] * count)])
+    rc = _lib.neuzip_compress_batch(ptrs, sizes, count, BF16, mantissa_bits, block_size, _stream_handle(stream),
+                                    handles)
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_compress_batch")
+    out = []
+    for i in range(count):
+        if blobs is not None and blobs[i] is not None:
+            blobs[i].handle = ctypes.c_void_p(handles[i])
+            out.append(blobs[i])
+        else:
+            out.append(Blob(handles[i]))
+    return out
 
 
 def neuzip_decompress(blob: Blob, dst: torch.Tensor, stream=None) -> torch.Tensor:

@@ -106,6 +106,48 @@ struct EncSym {
 };
 
 // ------------------------------------------------------------------------------------------
+// Compression works on a batch of up to 8 tensors that share mantissa_bits and block size (the
+// weights of a layer): every kernel of the pipeline is launched once for the whole batch, so
+// tensors too small to fill the chip overlap with the others.  A single tensor is a batch of one.
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kBatchMax = 8;
+
+struct CompressItem {
+    const uint16_t *src;
+    uint64_t n;
+    TableBlock *tb;
+    uint32_t *offsets;
+    uint32_t *states;
+    uint8_t *lens;
+    uint8_t *sm;
+    uint8_t *coef;
+    uint16_t *words;       // known only after the stream length has been read back
+    uint32_t n_chunks;
+    uint32_t block;        // 0: no block-wise normalisation
+    uint32_t group_base;   // first encoder group (16 chunks) of this tensor in the workspace arrays
+    uint32_t hist_end;     // first workgroup after this tensor's in the histogram launch
+    uint32_t enc_end;      // ... in the encode launch
+    uint32_t compact_end;  // ... in the compaction launch
+};
+
+struct CompressBatch {
+    CompressItem it[kBatchMax];
+    uint32_t count;
+    uint32_t seq;  // stamp of this call
+};
+
+// Host-visible results of one compress call (pinned host memory the kernels write directly).
+struct HostRecord {
+    uint32_t seq;  // stamp of the compress call whose results are complete (written last)
+    uint32_t pad;
+    struct Item {
+        uint32_t total_words[2];
+        uint32_t counts[256];
+        uint16_t freq[256];
+    } item[kBatchMax];
+};
+
+// ------------------------------------------------------------------------------------------
 // Small helpers
 // ------------------------------------------------------------------------------------------
 __global__ void fill_u32_kernel(uint32_t *p, uint32_t value, uint32_t count)
@@ -177,11 +219,33 @@ __device__ __forceinline__ float coefficient(uint32_t coef) { return 1.0f + stat
 constexpr uint32_t kHistThreads = 256;
 constexpr uint32_t kHistCopies = 32;
 
-template <int KB>
-__global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const uint16_t *__restrict__ src, uint64_t n,
-                                                                 uint8_t *__restrict__ sm,
-                                                                 uint32_t *__restrict__ counts)
+// Which tensor of the batch a workgroup of one of the wide launches works on.
+struct ItemSlot {
+    uint32_t item;   // index into the batch
+    uint32_t wg;     // workgroup index inside the tensor's share of the launch
+    uint32_t wgs;    // workgroups of that share
+};
+
+template <uint32_t CompressItem::*END>
+__device__ __forceinline__ ItemSlot item_of_workgroup(const CompressBatch &b)
 {
+    uint32_t i = 0, first = 0;
+    while (i + 1 < b.count && blockIdx.x >= b.it[i].*END) {
+        first = b.it[i].*END;
+        ++i;
+    }
+    return {i, blockIdx.x - first, b.it[i].*END - first};
+}
+
+template <int KB>
+__global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const CompressBatch b,
+                                                                 uint32_t *__restrict__ counts_ws)
+{
+    const ItemSlot slot = item_of_workgroup<&CompressItem::hist_end>(b);
+    const uint16_t *__restrict__ src = b.it[slot.item].src;
+    const uint64_t n = b.it[slot.item].n;
+    uint8_t *__restrict__ sm = b.it[slot.item].sm;
+    uint32_t *__restrict__ counts = counts_ws + 256 * slot.item;
     __shared__ uint32_t bins[256 * kHistCopies];
     for (uint32_t i = threadIdx.x; i < 256 * kHistCopies; i += kHistThreads)
         bins[i] = 0;
@@ -189,11 +253,11 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const uint16_t
 
     const uint32_t copy = threadIdx.x & (kHistCopies - 1);
     const uint64_t n_vec = n / 8;
-    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kHistThreads;
+    const uint64_t stride = static_cast<uint64_t>(slot.wgs) * kHistThreads;
     const uint4 *src4 = reinterpret_cast<const uint4 *>(src);
     // four 128-bit loads are in flight per lane before any of them is used
     constexpr uint32_t kDepth = 4;
-    for (uint64_t v0 = static_cast<uint64_t>(blockIdx.x) * kHistThreads + threadIdx.x; v0 < n_vec;
+    for (uint64_t v0 = static_cast<uint64_t>(slot.wg) * kHistThreads + threadIdx.x; v0 < n_vec;
          v0 += stride * kDepth) {
         uint4 d[kDepth];
 #pragma unroll
@@ -220,7 +284,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const uint16_t
         }
     }
     // ragged tail (n mod 8 elements): one thread, element by element
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (slot.wg == 0 && threadIdx.x == 0) {
         constexpr uint32_t per_byte = 8 / (KB + 1);
         uint32_t acc = 0, filled = 0;
         for (uint64_t i = n_vec * 8; i < n; ++i) {
@@ -256,11 +320,16 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const uint16_t
 // normalises its weights and proceeds as kernel 1 on the normalised words.
 // ------------------------------------------------------------------------------------------
 template <int KB>
-__global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const uint16_t *__restrict__ src, uint64_t n,
-                                                                      uint32_t block, uint8_t *__restrict__ coef_out,
-                                                                      uint8_t *__restrict__ sm,
-                                                                      uint32_t *__restrict__ counts)
+__global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const CompressBatch b,
+                                                                      uint32_t *__restrict__ counts_ws)
 {
+    const ItemSlot slot = item_of_workgroup<&CompressItem::hist_end>(b);
+    const uint16_t *__restrict__ src = b.it[slot.item].src;
+    const uint64_t n = b.it[slot.item].n;
+    const uint32_t block = b.it[slot.item].block;
+    uint8_t *__restrict__ coef_out = b.it[slot.item].coef;
+    uint8_t *__restrict__ sm = b.it[slot.item].sm;
+    uint32_t *__restrict__ counts = counts_ws + 256 * slot.item;
     __shared__ uint32_t bins[256 * kHistCopies];
     for (uint32_t i = threadIdx.x; i < 256 * kHistCopies; i += kHistThreads)
         bins[i] = 0;
@@ -269,10 +338,10 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const uin
     const uint32_t copy = threadIdx.x & (kHistCopies - 1);
     const uint32_t lanes_per_block = block / 8;                 // 4 .. 64, a power of two
     const uint64_t n_vec = (n + 7) / 8;                         // the last vector may be partial
-    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kHistThreads;
+    const uint64_t stride = static_cast<uint64_t>(slot.wgs) * kHistThreads;
     constexpr uint32_t per_byte = 8 / (KB + 1);
     // the trip count is the same for all lanes of a wave, so every lane takes part in the shuffles
-    const uint64_t wave_first = static_cast<uint64_t>(blockIdx.x) * kHistThreads + (threadIdx.x & ~63u);
+    const uint64_t wave_first = static_cast<uint64_t>(slot.wg) * kHistThreads + (threadIdx.x & ~63u);
     for (uint64_t base = wave_first; base < n_vec; base += stride) {
         const uint64_t v = base + (threadIdx.x & 63u);
         const uint64_t first = v * 8;
@@ -370,18 +439,13 @@ __device__ inline uint64_t block_sum_u64(uint64_t v, uint64_t *scratch)
     return scratch[0] + scratch[1] + scratch[2] + scratch[3];
 }
 
-// Host-visible record of one compress call (pinned host memory the kernels write directly).
-struct HostRecord {
-    uint32_t seq;  // stamp of the compress call whose results are complete (written last)
-    uint32_t pad;
-    uint32_t total_words[2];
-    uint32_t counts[256];
-    uint16_t freq[256];
-};
-
-__global__ __launch_bounds__(256) void table_kernel(uint32_t *__restrict__ counts_ws, TableBlock *__restrict__ tb,
-                                                    EncSym *__restrict__ enc)
+__global__ __launch_bounds__(256) void table_kernel(const CompressBatch b, uint32_t *__restrict__ counts_all,
+                                                    EncSym *__restrict__ enc_all)
 {
+    // one workgroup per tensor of the batch
+    uint32_t *__restrict__ counts_ws = counts_all + 256 * blockIdx.x;
+    TableBlock *__restrict__ tb = b.it[blockIdx.x].tb;
+    EncSym *__restrict__ enc = enc_all + 256 * blockIdx.x;
     __shared__ uint64_t scratch[4];
     __shared__ uint32_t scan[256];
     const uint32_t s = threadIdx.x;
@@ -506,6 +570,7 @@ __global__ __launch_bounds__(256) void table_kernel(uint32_t *__restrict__ count
 // current turn is coded.
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kEncThreads = 256;
+constexpr uint32_t kChunksPerGroup = kEncThreads / kStates;  // 16 chunks per encoder workgroup
 constexpr uint32_t kRingWords = 16;  // per state; two halves of 8 words = 16 bytes
 
 struct EncState {
@@ -540,30 +605,42 @@ __device__ __forceinline__ void ring_flush(uint32_t wp_before, uint32_t wp_after
 }
 
 template <bool NORM>
-__global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__restrict__ src, uint64_t n,
-                                                            const uint8_t *__restrict__ coef, uint32_t block,
-                                                            uint32_t n_chunks, const EncSym *__restrict__ enc_g,
-                                                            const TableBlock *__restrict__ tb,
-                                                            uint32_t *__restrict__ states,
-                                                            uint8_t *__restrict__ lens,
-                                                            uint32_t *__restrict__ chunk_words,
-                                                            uint32_t *__restrict__ group_words,
-                                                            uint16_t *__restrict__ slots,
+__global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch b,
+                                                            const EncSym *__restrict__ enc_all,
+                                                            uint32_t *__restrict__ chunk_words_all,
+                                                            uint32_t *__restrict__ group_words_all,
+                                                            uint16_t *__restrict__ slots_all,
                                                             HostRecord *__restrict__ record)
 {
+    const ItemSlot slot_id = item_of_workgroup<&CompressItem::enc_end>(b);
+    const CompressItem &it = b.it[slot_id.item];
+    const uint16_t *__restrict__ src = it.src;
+    const uint64_t n = it.n;
+    const uint8_t *__restrict__ coef = it.coef;
+    const uint32_t block = NORM ? it.block : 1u;
+    const uint32_t n_chunks = it.n_chunks;
+    const TableBlock *__restrict__ tb = it.tb;
+    uint32_t *__restrict__ states = it.states;
+    uint8_t *__restrict__ lens = it.lens;
+    // this tensor's part of the workspace arrays
+    const uint32_t group = it.group_base + slot_id.wg;
+    uint32_t *__restrict__ chunk_words = chunk_words_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup;
+    uint16_t *__restrict__ slots = slots_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup * kStates * kRunCap;
+    const EncSym *__restrict__ enc_g = enc_all + 256 * slot_id.item;
+
     __shared__ uint4 enc_raw[256];
     __shared__ __align__(16) uint16_t rings[kEncThreads * kRingWords];
     __shared__ uint32_t group_chunk[kEncThreads / kStates];
     enc_raw[threadIdx.x] = reinterpret_cast<const uint4 *>(enc_g)[threadIdx.x];
-    if (blockIdx.x == 0) {
+    if (slot_id.wg == 0) {
         // statistics for the host: posted early, they land long before this kernel ends
-        record->counts[threadIdx.x] = tb->counts[threadIdx.x];
-        record->freq[threadIdx.x] = tb->freq[threadIdx.x];
+        record->item[slot_id.item].counts[threadIdx.x] = tb->counts[threadIdx.x];
+        record->item[slot_id.item].freq[threadIdx.x] = tb->freq[threadIdx.x];
     }
     __syncthreads();
     const EncSym *enc = reinterpret_cast<const EncSym *>(enc_raw);
 
-    const uint32_t lane_id = blockIdx.x * kEncThreads + threadIdx.x;  // = chunk * 16 + state
+    const uint32_t lane_id = slot_id.wg * kEncThreads + threadIdx.x;  // = chunk * 16 + state
     const uint32_t c = lane_id / kStates, j = lane_id % kStates;
     const bool live = c < n_chunks;
     const uint64_t base = static_cast<uint64_t>(c) * kChunk;
@@ -631,7 +708,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__r
         uint32_t total = 0;
         for (uint32_t i = 0; i < kEncThreads / kStates; ++i)
             total += group_chunk[i];
-        group_words[blockIdx.x] = total;
+        group_words_all[group] = total;
     }
 }
 
@@ -641,13 +718,19 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t *__r
 // compaction kernel.  The total goes to the blob's last offset and to the host.
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kScanThreads = 1024;
-constexpr uint32_t kChunksPerGroup = kEncThreads / kStates;  // 16
 
-__global__ __launch_bounds__(kScanThreads) void offsets_kernel(const uint32_t *__restrict__ group_words,
-                                                              uint32_t n_groups, uint64_t *__restrict__ group_prefix,
-                                                              uint32_t *__restrict__ last_offset,
-                                                              HostRecord *__restrict__ record, uint32_t seq)
+__global__ __launch_bounds__(kScanThreads) void offsets_kernel(const CompressBatch b,
+                                                              const uint32_t *__restrict__ group_words_all,
+                                                              uint64_t *__restrict__ group_prefix_all,
+                                                              uint32_t *__restrict__ done,
+                                                              HostRecord *__restrict__ record)
 {
+    // one workgroup per tensor of the batch
+    const CompressItem &it = b.it[blockIdx.x];
+    const uint32_t n_groups = (it.n_chunks + kChunksPerGroup - 1) / kChunksPerGroup;
+    const uint32_t *__restrict__ group_words = group_words_all + it.group_base;
+    uint64_t *__restrict__ group_prefix = group_prefix_all + it.group_base;
+    uint32_t *__restrict__ last_offset = it.offsets + it.n_chunks;
     __shared__ uint64_t wave_sum[kScanThreads / 64];
     __shared__ uint64_t carry_s;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -687,10 +770,15 @@ __global__ __launch_bounds__(kScanThreads) void offsets_kernel(const uint32_t *_
     if (tid == 0) {
         last_offset[0] = static_cast<uint32_t>(carry);
         last_offset[1] = 0;
-        record->total_words[0] = static_cast<uint32_t>(carry);
-        record->total_words[1] = static_cast<uint32_t>(carry >> 32);  // non-zero: too long for 32-bit offsets
+        record->item[blockIdx.x].total_words[0] = static_cast<uint32_t>(carry);
+        record->item[blockIdx.x].total_words[1] = static_cast<uint32_t>(carry >> 32);  // non-zero: too long for 32-bit offsets
+        // the workgroup that finishes last publishes the stamp and rearms the counter
         __threadfence_system();
-        __hip_atomic_store(&record->seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (atomicAdd(done, 1u) == b.count - 1) {
+            *done = 0;
+            __threadfence_system();
+            __hip_atomic_store(&record->seq, b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
     }
 }
 
@@ -700,14 +788,22 @@ __global__ __launch_bounds__(kScanThreads) void offsets_kernel(const uint32_t *_
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kCompactThreads = 256;
 
-__global__ __launch_bounds__(kCompactThreads) void compact_kernel(const uint16_t *__restrict__ slots,
-                                                                 const uint8_t *__restrict__ lens,
-                                                                 const uint32_t *__restrict__ chunk_words,
-                                                                 const uint64_t *__restrict__ group_prefix,
-                                                                 uint32_t *__restrict__ offsets,
-                                                                 uint32_t n_chunks, uint16_t *__restrict__ words)
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompressBatch b,
+                                                                 const uint16_t *__restrict__ slots_all,
+                                                                 const uint32_t *__restrict__ chunk_words_all,
+                                                                 const uint64_t *__restrict__ group_prefix_all)
 {
-    const uint32_t c = blockIdx.x * (kCompactThreads / 64) + threadIdx.x / 64;
+    const ItemSlot slot_id = item_of_workgroup<&CompressItem::compact_end>(b);
+    const CompressItem &it = b.it[slot_id.item];
+    const uint32_t n_chunks = it.n_chunks;
+    const uint8_t *__restrict__ lens = it.lens;
+    uint32_t *__restrict__ offsets = it.offsets;
+    uint16_t *__restrict__ words = it.words;
+    const uint16_t *__restrict__ slots = slots_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup * kStates * kRunCap;
+    const uint32_t *__restrict__ chunk_words = chunk_words_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup;
+    const uint64_t *__restrict__ group_prefix = group_prefix_all + it.group_base;
+
+    const uint32_t c = slot_id.wg * (kCompactThreads / 64) + threadIdx.x / 64;
     const uint32_t lane = threadIdx.x & 63;
     if (c >= n_chunks)
         return;
@@ -1056,7 +1152,6 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(const DecodeArgs a)
 
 // Several tensors in one launch (a layer's weights): workgroups [t[i-1].wg_end, t[i].wg_end)
 // belong to tensor i.  Small tensors, which alone cannot fill the chip, overlap with the others.
-constexpr uint32_t kBatchMax = 8;
 struct BatchArgs {
     DecodeArgs t[kBatchMax];
     uint32_t count;
@@ -1151,20 +1246,21 @@ inline uint8_t *sm_of(const neuzip_blob *b) { return b->fixed + b->at.sm; }
 inline uint8_t *coef_of(const neuzip_blob *b) { return b->fixed + b->at.coef; }
 inline bool is_blob(const neuzip_blob *b) { return b && b->magic == kBlobMagic; }
 
-// Per-process compress workspace (encoder constants, run slots, pinned staging for the size read).
+// Per-process compress workspace: histogram bins and encoder constants for the tensors of a batch,
+// per-chunk / per-group word counts, run slots, and pinned host memory for the results.
 struct Workspace {
     int device = -1;
-    EncSym *enc = nullptr;
-    uint32_t *counts = nullptr;       // 256 histogram bins, zero between compress calls
+    EncSym *enc = nullptr;            // kBatchMax x 256
+    uint32_t *counts = nullptr;       // kBatchMax x 256 histogram bins, zero between compress calls
+    uint32_t *done = nullptr;         // offsets-kernel workgroups that have finished (rearmed by the last)
     uint32_t *chunk_words = nullptr;  // words per chunk
     uint32_t *group_words = nullptr;  // words per encoder workgroup (16 chunks), input of the scan
-    uint64_t *group_prefix = nullptr; // its exclusive prefix sum
-    uint64_t chunk_cap = 0;
+    uint64_t *group_prefix = nullptr; // its exclusive prefix sum, per tensor
+    uint64_t group_cap = 0;           // encoder groups the arrays and the slots are sized for
     uint16_t *slots = nullptr;
-    uint64_t slots_bytes = 0;
-    HostRecord *pinned = nullptr;  // pinned host memory, written by the encode and offsets kernels
-    uint32_t seq = 0;              // stamp of the last compress call
-    hipEvent_t idle = nullptr;   // recorded after the last kernel that uses the workspace
+    HostRecord *pinned = nullptr;     // pinned host memory, written by the encode and offsets kernels
+    uint32_t seq = 0;                 // stamp of the last compress call
+    hipEvent_t idle = nullptr;        // recorded after the last kernel that uses the workspace
 };
 std::mutex g_ws_mutex;
 Workspace g_ws;
@@ -1181,23 +1277,16 @@ int release_workspace_locked()
         if (g_ws.idle) {
             if (!hip_ok(hipEventSynchronize(g_ws.idle)))
                 rc = NEUZIP_EHIP;
-            hipEventDestroy(g_ws.idle);
+            (void)hipEventDestroy(g_ws.idle);
         }
-        if (g_ws.enc)
-            hipFree(g_ws.enc);
-        if (g_ws.counts)
-            hipFree(g_ws.counts);
-        if (g_ws.chunk_words)
-            hipFree(g_ws.chunk_words);
-        if (g_ws.group_words)
-            hipFree(g_ws.group_words);
-        if (g_ws.group_prefix)
-            hipFree(g_ws.group_prefix);
-        if (g_ws.slots)
-            hipFree(g_ws.slots);
+        void *device_arrays[] = {g_ws.enc, g_ws.counts, g_ws.chunk_words, g_ws.group_words, g_ws.group_prefix,
+                                 g_ws.slots};  // `done` lives inside the counts allocation
+        for (void *ptr : device_arrays)
+            if (ptr)
+                (void)hipFree(ptr);
         if (g_ws.pinned)
-            hipHostFree(g_ws.pinned);
-        hipSetDevice(cur);
+            (void)hipHostFree(g_ws.pinned);
+        (void)hipSetDevice(cur);
     }
     g_ws = Workspace();
     return rc;
@@ -1222,59 +1311,46 @@ bool wait_for_record(uint32_t seq, hipStream_t stream)
     return __atomic_load_n(stamp, __ATOMIC_ACQUIRE) == seq;
 }
 
-int ensure_workspace(int device, uint32_t n_chunks, hipStream_t stream)
+int ensure_workspace(int device, uint64_t n_groups, hipStream_t stream)
 {
-    const uint64_t slots_bytes = static_cast<uint64_t>(n_chunks) * kStates * kRunCap * 2;
     if (g_ws.device != device) {
         const int rc = release_workspace_locked();
         if (rc != NEUZIP_OK)
             return rc;
         g_ws.device = device;
-        NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.enc), 256 * sizeof(EncSym)));
-        NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.counts), 256 * sizeof(uint32_t)));
+        NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.enc), kBatchMax * 256 * sizeof(EncSym)));
+        NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.counts), (kBatchMax * 256 + 64) * sizeof(uint32_t)));
+        g_ws.done = g_ws.counts + kBatchMax * 256;  // shares the allocation; cleared with the bins below
         NZ_HIP(hipHostMalloc(reinterpret_cast<void **>(&g_ws.pinned), sizeof(HostRecord), hipHostMallocDefault));
         std::memset(g_ws.pinned, 0, sizeof(HostRecord));
         g_ws.seq = 0;
         NZ_HIP(hipEventCreateWithFlags(&g_ws.idle, hipEventDisableTiming));
-        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, stream, g_ws.counts, 0u, 256u);
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax + 1), dim3(256), 0, stream, g_ws.counts, 0u,
+                           kBatchMax * 256 + 64);
         NZ_HIP(hipGetLastError());
         NZ_HIP(hipEventRecord(g_ws.idle, stream));
     }
     // the previous user of the workspace may still be running on another stream
     NZ_HIP(hipStreamWaitEvent(stream, g_ws.idle, 0));
-    if (g_ws.slots_bytes < slots_bytes || g_ws.chunk_cap < n_chunks) {
+    if (g_ws.group_cap < n_groups) {
         NZ_HIP(hipEventSynchronize(g_ws.idle));
-        if (g_ws.slots_bytes < slots_bytes) {
-            if (g_ws.slots) {
-                NZ_HIP(hipFree(g_ws.slots));
-                g_ws.slots = nullptr;
-                g_ws.slots_bytes = 0;
-            }
-            if (hipMalloc(reinterpret_cast<void **>(&g_ws.slots), slots_bytes) != hipSuccess) {
-                (void)hipGetLastError();
-                return NEUZIP_ENOMEM;
-            }
-            g_ws.slots_bytes = slots_bytes;
+        void *old_arrays[] = {g_ws.chunk_words, g_ws.group_words, g_ws.group_prefix, g_ws.slots};
+        for (void *ptr : old_arrays)
+            if (ptr)
+                NZ_HIP(hipFree(ptr));
+        g_ws.chunk_words = g_ws.group_words = nullptr;
+        g_ws.group_prefix = nullptr;
+        g_ws.slots = nullptr;
+        g_ws.group_cap = 0;
+        const uint64_t chunks = n_groups * kChunksPerGroup;
+        if (hipMalloc(reinterpret_cast<void **>(&g_ws.chunk_words), (chunks + 4) * 4) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void **>(&g_ws.group_words), (n_groups + 4) * 4) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void **>(&g_ws.group_prefix), (n_groups + 4) * 8) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void **>(&g_ws.slots), chunks * kStates * kRunCap * 2) != hipSuccess) {
+            (void)hipGetLastError();
+            return NEUZIP_ENOMEM;
         }
-        if (g_ws.chunk_cap < n_chunks) {
-            if (g_ws.chunk_words)
-                NZ_HIP(hipFree(g_ws.chunk_words));
-            if (g_ws.group_words)
-                NZ_HIP(hipFree(g_ws.group_words));
-            if (g_ws.group_prefix)
-                NZ_HIP(hipFree(g_ws.group_prefix));
-            g_ws.chunk_words = g_ws.group_words = nullptr;
-            g_ws.group_prefix = nullptr;
-            g_ws.chunk_cap = 0;
-            const uint64_t groups = (static_cast<uint64_t>(n_chunks) + kChunksPerGroup - 1) / kChunksPerGroup;
-            if (hipMalloc(reinterpret_cast<void **>(&g_ws.chunk_words), (groups * kChunksPerGroup + 4) * 4) != hipSuccess ||
-                hipMalloc(reinterpret_cast<void **>(&g_ws.group_words), (groups + 4) * 4) != hipSuccess ||
-                hipMalloc(reinterpret_cast<void **>(&g_ws.group_prefix), (groups + 4) * 8) != hipSuccess) {
-                (void)hipGetLastError();
-                return NEUZIP_ENOMEM;
-            }
-            g_ws.chunk_cap = n_chunks;
-        }
+        g_ws.group_cap = n_groups;
     }
     return NEUZIP_OK;
 }
@@ -1323,27 +1399,6 @@ int reserve_words(neuzip_blob *b, uint64_t total_words)
         b->words_bytes = need;
     }
     return NEUZIP_OK;
-}
-
-template <int KB>
-int launch_hist(const void *d_src, uint64_t n, neuzip_blob *b, hipStream_t stream)
-{
-    const uint64_t n_vec = (n + 7) / 8;
-    // every workgroup pays for clearing and merging its 32 KB of bins: give it at least 8 vectors
-    // (64 elements) per thread, and launch no more workgroups than fit the chip at once
-    uint64_t groups = (n_vec + kHistThreads * 8 - 1) / (kHistThreads * 8);
-    if (groups < 1)
-        groups = 1;
-    if (groups > 1280)
-        groups = 1280;
-    if (b->block)
-        hipLaunchKernelGGL(hist_split_norm_kernel<KB>, dim3(static_cast<uint32_t>(groups)), dim3(kHistThreads), 0,
-                           stream, static_cast<const uint16_t *>(d_src), n, b->block, coef_of(b), sm_of(b),
-                           g_ws.counts);
-    else
-        hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(static_cast<uint32_t>(groups)), dim3(kHistThreads), 0, stream,
-                           static_cast<const uint16_t *>(d_src), n, sm_of(b), g_ws.counts);
-    return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
 
 // Chunks per decoder workgroup.  32 (8 waves) measured best at every size: two such workgroups
@@ -1426,6 +1481,160 @@ int launch_batch(const BatchArgs &args, int variant, uint32_t groups, hipStream_
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
 
+// An empty tensor: a zeroed table block (a fill kernel, not a memset node, so the call stays safe
+// to record into a graph) and a single zero offset.
+int compress_empty(neuzip_blob *b, hipStream_t stream)
+{
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((sizeof(TableBlock) / 4 + 255) / 256), dim3(256), 0, stream,
+                       reinterpret_cast<uint32_t *>(b->fixed), 0u, static_cast<uint32_t>(sizeof(TableBlock) / 4));
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, stream, offsets_of(b), 0u, 2u);
+    if (!hip_ok(hipGetLastError()) || !hip_ok(hipStreamSynchronize(stream)))
+        return NEUZIP_EHIP;
+    std::memset(b->h_counts, 0, sizeof(b->h_counts));
+    std::memset(b->h_freq, 0, sizeof(b->h_freq));
+    b->have_counts = true;
+    b->total_words = 0;
+    return NEUZIP_OK;
+}
+
+template <int KB>
+void launch_hist(const CompressBatch &batch, bool norm, uint32_t groups, hipStream_t stream)
+{
+    if (norm)
+        hipLaunchKernelGGL(hist_split_norm_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch,
+                           g_ws.counts);
+    else
+        hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch, g_ws.counts);
+}
+
+// Compresses up to kBatchMax tensors (arguments already validated) with one pass of the pipeline.
+int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int k, uint32_t block,
+                  hipStream_t stream, neuzip_blob **blobs)
+{
+    neuzip_blob *work[kBatchMax];
+    bool fresh[kBatchMax];
+    for (uint32_t i = 0; i < count; ++i) {
+        work[i] = blobs[i];
+        fresh[i] = false;
+    }
+    bool bins_dirty = false;  // the histogram kernel ran but the table kernel did not clear the bins
+    auto fail = [&](int rc) {
+        if (bins_dirty && g_ws.counts)
+            hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax), dim3(256), 0, stream, g_ws.counts, 0u,
+                               kBatchMax * 256);
+        for (uint32_t i = 0; i < count; ++i)
+            if (fresh[i])
+                neuzip_free(work[i]);
+        return rc;
+    };
+    for (uint32_t i = 0; i < count; ++i) {
+        if (!work[i]) {
+            const int rc = alloc_blob(n_elems[i], k, block, &work[i]);
+            if (rc != NEUZIP_OK)
+                return fail(rc);
+            fresh[i] = true;
+        }
+        work[i]->have_counts = false;
+        work[i]->total_words = 0;
+    }
+
+    // the batch proper: tensors that have elements
+    CompressBatch batch;
+    std::memset(&batch, 0, sizeof(batch));
+    uint32_t owner[kBatchMax];
+    uint32_t hist_groups = 0, enc_groups = 0, compact_groups = 0;
+    for (uint32_t i = 0; i < count; ++i) {
+        neuzip_blob *b = work[i];
+        if (b->n == 0) {
+            const int rc = compress_empty(b, stream);
+            if (rc != NEUZIP_OK)
+                return fail(rc);
+            continue;
+        }
+        CompressItem &it = batch.it[batch.count];
+        owner[batch.count++] = i;
+        it.src = static_cast<const uint16_t *>(d_srcs[i]);
+        it.n = b->n;
+        it.tb = table_of(b);
+        it.offsets = offsets_of(b);
+        it.states = states_of(b);
+        it.lens = lens_of(b);
+        it.sm = sm_of(b);
+        it.coef = coef_of(b);
+        it.words = nullptr;
+        it.n_chunks = b->n_chunks;
+        it.block = block;
+        it.group_base = enc_groups;
+        // every workgroup of the histogram pass pays for clearing and merging its 32 KB of bins: give
+        // it at least 8 vectors (64 elements) per thread, and no tensor more workgroups than fit the chip
+        uint64_t hg = ((b->n + 7) / 8 + kHistThreads * 8 - 1) / (kHistThreads * 8);
+        hg = hg < 1 ? 1 : (hg > 1280 ? 1280 : hg);
+        hist_groups += static_cast<uint32_t>(hg);
+        enc_groups += (b->n_chunks + kChunksPerGroup - 1) / kChunksPerGroup;
+        compact_groups += (b->n_chunks + kCompactThreads / 64 - 1) / (kCompactThreads / 64);
+        it.hist_end = hist_groups;
+        it.enc_end = enc_groups;
+        it.compact_end = compact_groups;
+    }
+    if (batch.count > 0) {
+        std::lock_guard<std::mutex> guard(g_ws_mutex);
+        int rc = ensure_workspace(work[owner[0]]->device, enc_groups, stream);
+        if (rc != NEUZIP_OK)
+            return fail(rc);
+        batch.seq = ++g_ws.seq;
+
+        switch (k) {
+        case 7: launch_hist<7>(batch, block != 0, hist_groups, stream); break;
+        case 3: launch_hist<3>(batch, block != 0, hist_groups, stream); break;
+        case 1: launch_hist<1>(batch, block != 0, hist_groups, stream); break;
+        default: launch_hist<0>(batch, block != 0, hist_groups, stream); break;
+        }
+        if (!hip_ok(hipGetLastError()))
+            return fail(NEUZIP_EHIP);
+        bins_dirty = true;
+        // the table kernel also returns the workspace histogram bins to zero
+        hipLaunchKernelGGL(table_kernel, dim3(batch.count), dim3(256), 0, stream, batch, g_ws.counts, g_ws.enc);
+        if (hip_ok(hipGetLastError()))
+            bins_dirty = false;
+        if (block)
+            hipLaunchKernelGGL(encode_kernel<true>, dim3(enc_groups), dim3(kEncThreads), 0, stream, batch, g_ws.enc,
+                               g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned);
+        else
+            hipLaunchKernelGGL(encode_kernel<false>, dim3(enc_groups), dim3(kEncThreads), 0, stream, batch, g_ws.enc,
+                               g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned);
+        hipLaunchKernelGGL(offsets_kernel, dim3(batch.count), dim3(kScanThreads), 0, stream, batch, g_ws.group_words,
+                           g_ws.group_prefix, g_ws.done, g_ws.pinned);
+        if (!hip_ok(hipGetLastError()))
+            return fail(NEUZIP_EHIP);
+
+        // the stream lengths are data dependent: wait for them (and the statistics), which the
+        // kernels write straight into pinned host memory, the stamp last
+        if (!wait_for_record(batch.seq, stream))
+            return fail(NEUZIP_EHIP);
+        for (uint32_t j = 0; j < batch.count; ++j) {
+            const HostRecord::Item &r = g_ws.pinned->item[j];
+            neuzip_blob *b = work[owner[j]];
+            if (r.total_words[1] != 0)
+                return fail(NEUZIP_EUNSUPPORTED);  // more than 2^32 words
+            rc = reserve_words(b, r.total_words[0]);
+            if (rc != NEUZIP_OK)
+                return fail(rc);
+            b->total_words = r.total_words[0];
+            std::memcpy(b->h_counts, r.counts, 1024);
+            std::memcpy(b->h_freq, r.freq, 512);
+            b->have_counts = true;
+            batch.it[j].words = reinterpret_cast<uint16_t *>(b->words);
+        }
+        hipLaunchKernelGGL(compact_kernel, dim3(compact_groups), dim3(kCompactThreads), 0, stream, batch, g_ws.slots,
+                           g_ws.chunk_words, g_ws.group_prefix);
+        if (!hip_ok(hipGetLastError()) || !hip_ok(hipEventRecord(g_ws.idle, stream)))
+            return fail(NEUZIP_EHIP);
+    }
+    for (uint32_t i = 0; i < count; ++i)
+        blobs[i] = work[i];
+    return NEUZIP_OK;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------------
@@ -1436,115 +1645,44 @@ extern "C" {
 int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa_bits, void *hip_stream,
                     neuzip_blob **blob)
 {
-    return neuzip_compress_blockwise(d_src, n_elems, dtype, mantissa_bits, 0, hip_stream, blob);
+    return neuzip_compress_batch(&d_src, &n_elems, 1, dtype, mantissa_bits, 0, hip_stream, blob);
 }
 
 int neuzip_compress_blockwise(const void *d_src, uint64_t n_elems, int dtype, int mantissa_bits,
                               uint32_t block_size, void *hip_stream, neuzip_blob **blob)
 {
-    if (!blob || dtype != NEUZIP_BF16 || !valid_k(mantissa_bits))
+    return neuzip_compress_batch(&d_src, &n_elems, 1, dtype, mantissa_bits, block_size, hip_stream, blob);
+}
+
+int neuzip_compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int dtype,
+                          int mantissa_bits, uint32_t block_size, void *hip_stream, neuzip_blob **blobs)
+{
+    if (count == 0)
+        return NEUZIP_OK;
+    if (!d_srcs || !n_elems || !blobs || dtype != NEUZIP_BF16 || !valid_k(mantissa_bits))
         return NEUZIP_EINVAL;
     if (block_size != 0 && (!valid_block(block_size) || mantissa_bits == 7))
         return NEUZIP_EINVAL;
-    if (n_elems > 0 && (!d_src || (reinterpret_cast<uintptr_t>(d_src) & 15u)))
-        return NEUZIP_EINVAL;
-    if (n_elems >= (1ull << 32))
-        return NEUZIP_EUNSUPPORTED;
+    for (uint32_t i = 0; i < count; ++i) {
+        if (n_elems[i] > 0 && (!d_srcs[i] || (reinterpret_cast<uintptr_t>(d_srcs[i]) & 15u)))
+            return NEUZIP_EINVAL;
+        if (n_elems[i] >= (1ull << 32))
+            return NEUZIP_EUNSUPPORTED;
+        const neuzip_blob *b = blobs[i];
+        if (b && (!is_blob(b) || b->n != n_elems[i] || b->k != mantissa_bits || b->block != block_size))
+            return NEUZIP_EINVAL;
+        for (uint32_t j = 0; j < i; ++j)
+            if (b && blobs[j] == b)
+                return NEUZIP_EINVAL;  // one blob cannot receive two tensors
+    }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-
-    neuzip_blob *b = *blob;
-    const bool fresh = (b == nullptr);
-    if (!fresh && (!is_blob(b) || b->n != n_elems || b->k != mantissa_bits || b->block != block_size))
-        return NEUZIP_EINVAL;
-    if (fresh) {
-        const int rc = alloc_blob(n_elems, mantissa_bits, block_size, &b);
+    for (uint32_t first = 0; first < count; first += kBatchMax) {
+        const uint32_t m = count - first < kBatchMax ? count - first : kBatchMax;
+        const int rc = compress_some(d_srcs + first, n_elems + first, m, mantissa_bits, block_size, stream,
+                                     blobs + first);
         if (rc != NEUZIP_OK)
             return rc;
     }
-    bool bins_dirty = false;  // the histogram kernel ran but the table kernel did not clear the bins
-    auto fail = [&](int rc) {
-        if (bins_dirty && g_ws.counts)
-            hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, stream, g_ws.counts, 0u, 256u);
-        if (fresh)
-            neuzip_free(b);
-        return rc;
-    };
-
-    const uint32_t nc = b->n_chunks;
-    b->have_counts = false;
-    b->total_words = 0;
-
-    if (n_elems == 0) {
-        // empty tensor: zeroed table block (a fill kernel, not a memset node, so the call stays
-        // safe to record into a graph) and a single zero offset
-        hipLaunchKernelGGL(fill_u32_kernel, dim3((sizeof(TableBlock) / 4 + 255) / 256), dim3(256), 0, stream,
-                           reinterpret_cast<uint32_t *>(b->fixed), 0u, static_cast<uint32_t>(sizeof(TableBlock) / 4));
-        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, stream, offsets_of(b), 0u, 2u);
-        if (!hip_ok(hipGetLastError()) || !hip_ok(hipStreamSynchronize(stream)))
-            return fail(NEUZIP_EHIP);
-        std::memset(b->h_counts, 0, sizeof(b->h_counts));
-        std::memset(b->h_freq, 0, sizeof(b->h_freq));
-        b->have_counts = true;
-        *blob = b;
-        return NEUZIP_OK;
-    }
-
-    std::lock_guard<std::mutex> guard(g_ws_mutex);
-    int rc = ensure_workspace(b->device, nc, stream);
-    if (rc != NEUZIP_OK)
-        return fail(rc);
-
-    switch (mantissa_bits) {
-    case 7: rc = launch_hist<7>(d_src, n_elems, b, stream); break;
-    case 3: rc = launch_hist<3>(d_src, n_elems, b, stream); break;
-    case 1: rc = launch_hist<1>(d_src, n_elems, b, stream); break;
-    default: rc = launch_hist<0>(d_src, n_elems, b, stream); break;
-    }
-    if (rc != NEUZIP_OK)
-        return fail(rc);
-    bins_dirty = true;
-
-    // the table kernel also returns the workspace histogram bins to zero
-    hipLaunchKernelGGL(table_kernel, dim3(1), dim3(256), 0, stream, g_ws.counts, table_of(b), g_ws.enc);
-    if (hip_ok(hipGetLastError()))
-        bins_dirty = false;
-    const uint32_t n_groups = (nc + kChunksPerGroup - 1) / kChunksPerGroup;
-    if (b->block)
-        hipLaunchKernelGGL(encode_kernel<true>, dim3(n_groups), dim3(kEncThreads), 0, stream,
-                           static_cast<const uint16_t *>(d_src), n_elems, coef_of(b), b->block, nc, g_ws.enc,
-                           table_of(b), states_of(b), lens_of(b), g_ws.chunk_words, g_ws.group_words, g_ws.slots,
-                           g_ws.pinned);
-    else
-        hipLaunchKernelGGL(encode_kernel<false>, dim3(n_groups), dim3(kEncThreads), 0, stream,
-                           static_cast<const uint16_t *>(d_src), n_elems, coef_of(b), 1u, nc, g_ws.enc, table_of(b),
-                           states_of(b), lens_of(b), g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned);
-    const uint32_t seq = ++g_ws.seq;
-    hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(kScanThreads), 0, stream, g_ws.group_words, n_groups,
-                       g_ws.group_prefix, offsets_of(b) + nc, g_ws.pinned, seq);
-    if (!hip_ok(hipGetLastError()))
-        return fail(NEUZIP_EHIP);
-
-    // the stream length is data dependent: wait for it (and the statistics), which the kernels
-    // write straight into pinned host memory, the stamp last
-    if (!wait_for_record(seq, stream))
-        return fail(NEUZIP_EHIP);
-    if (g_ws.pinned->total_words[1] != 0)
-        return fail(NEUZIP_EUNSUPPORTED);  // more than 2^32 words
-    const uint64_t total_words = g_ws.pinned->total_words[0];
-    std::memcpy(b->h_counts, g_ws.pinned->counts, 1024);
-    std::memcpy(b->h_freq, g_ws.pinned->freq, 512);
-    b->have_counts = true;
-
-    rc = reserve_words(b, total_words);
-    if (rc != NEUZIP_OK)
-        return fail(rc);
-    b->total_words = total_words;
-    hipLaunchKernelGGL(compact_kernel, dim3((nc + kCompactThreads / 64 - 1) / (kCompactThreads / 64)),
-                       dim3(kCompactThreads), 0, stream, g_ws.slots, lens_of(b), g_ws.chunk_words, g_ws.group_prefix,
-                       offsets_of(b), nc, reinterpret_cast<uint16_t *>(b->words));
-    if (!hip_ok(hipGetLastError()) || !hip_ok(hipEventRecord(g_ws.idle, stream)))
-        return fail(NEUZIP_EHIP);
-    *blob = b;
     return NEUZIP_OK;
 }
 

@@ -265,6 +265,38 @@ def test_decompression_can_be_captured_in_a_hip_graph(nz):
         nz.neuzip_check(b)
 
 
+@pytest.mark.parametrize("k,block", [(7, 0), (3, 0), (0, 128)])
+def test_compress_batch_matches_one_by_one(nz, k, block):
+    # a layer's weights in one pass of the pipeline: same containers as tensor by tensor, which are
+    # the oracle's; more tensors than one group holds, ragged and empty ones included
+    shapes = [(256, 512), (64, 515), (1, 1), (0,), (896, 256), (33, 4096), (7, 9), (512, 512), (1000, 37),
+              (300, 300), (2, 4096)]
+    tensors = [inputs.student_t4_bf16(s, inputs.seed_for(5, 200 + i), device=DEV) for i, s in enumerate(shapes)]
+    blobs = nz.neuzip_compress_batch(tensors, k, block)
+    assert len(blobs) == len(tensors)
+    for t, b in zip(tensors, blobs):
+        words = inputs.bits(t)
+        assert np.array_equal(nz.neuzip_export(b), O.compress(words, k, threads=4, block=block))
+        out = torch.empty_like(t)
+        nz.neuzip_decompress(b, out)
+        nz.neuzip_check(b)
+        expect = O.lossy_blockwise(words, k, block) if block else O.truncate(words, k)
+        assert np.array_equal(inputs.bits(out), expect)
+        if t.numel():
+            assert np.array_equal(nz.neuzip_histogram(b).astype(np.uint64), O.histogram(expect if False else
+                                  (O.normalise(words, block, O.block_coefficients(words, block)) if block else words)))
+    # recompression into the same blobs after an update
+    updated = [inputs.synthetic_update(t, 900 + i) for i, t in enumerate(tensors)]
+    again = nz.neuzip_compress_batch(updated, k, block, blobs=blobs)
+    assert all(a is b for a, b in zip(again, blobs))
+    for t, b in zip(updated, blobs):
+        assert np.array_equal(nz.neuzip_export(b), O.compress(inputs.bits(t), k, threads=4, block=block))
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_compress_batch(updated[:2], k, block, blobs=[blobs[0], blobs[0]])
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_compress_batch(updated[:2], k, block, blobs=[blobs[1], blobs[0]])   # sizes do not match
+
+
 def test_other_stream(nz):
     s = torch.cuda.Stream()
     w = inputs.gaussian_bf16(300_000, 3, device=DEV)
