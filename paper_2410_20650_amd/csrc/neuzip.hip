@@ -1002,7 +1002,12 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
             }
 #pragma unroll
             for (uint32_t r = 0; r < kTurnGroup; ++r) {
-                out4[(q0 + r) * kStates] = o[r];
+                // streamed out once: non-temporal, so the words do not displace the tables in cache
+                uint4 *dst = &out4[(q0 + r) * kStates];
+                __builtin_nontemporal_store(o[r].x, &dst->x);
+                __builtin_nontemporal_store(o[r].y, &dst->y);
+                __builtin_nontemporal_store(o[r].z, &dst->z);
+                __builtin_nontemporal_store(o[r].w, &dst->w);
                 fields[r] = fields_next[r];
             }
         }
