@@ -6,7 +6,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libneuzip.so")
 SOURCES = [os.path.join(HERE, "csrc", "neuzip.hip")]
-HEADERS = [os.path.join(ROOT, "include", "neuzip.h")]
+HEADERS = [os.path.join(ROOT, "include", "neuzip.h")] + [
+    os.path.join(HERE, "csrc", name)
+    for name in ("neuzip_format.h", "neuzip_compress_kernels.h", "neuzip_decode_kernels.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -1,0 +1,339 @@
+// Fused rANS decode + merge kernels of the NeuZip codec for gfx950 (single tensor and batch).
+#pragma once
+
+#include "neuzip_format.h"
+#include "neuzip_compress_kernels.h"
+
+namespace nz {
+
+// ------------------------------------------------------------------------------------------
+// Kernel 6: fused decoder (Alg. 1 "decompression" + "merge"; Sec. 2.2 Eq. (3)).
+//
+// A workgroup owns blockDim.x / 16 neighbouring chunks (at most 32).  It copies the 4096-entry
+// slot table (symbol | f << 8 | (slot - cum) << 20, prepared once per tensor) and the chunks'
+// word runs -- one contiguous piece of the blob -- into LDS with 128-bit loads behind a single
+// barrier, and then every lane walks one
+// state: 32 turns of 8 symbols; per symbol one table read, one multiply-add, one compare, and
+// a lane-private refill that touches LDS only when a word is consumed.  The 8 decoded
+// exponents are merged with the 8 sign|mantissa fields and leave as one 128-bit store; the
+// fields of the next turn are requested before the current turn is decoded.
+// ------------------------------------------------------------------------------------------
+template <int KB>
+__device__ __forceinline__ uint64_t load_fields(const uint8_t *__restrict__ sm, uint64_t first_elem)
+{
+    // the (KB+1)*8 field bits of 8 neighbouring elements
+    if constexpr (KB == 7) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(sm + first_elem);
+        return static_cast<uint64_t>(v.x) | (static_cast<uint64_t>(v.y) << 32);
+    } else if constexpr (KB == 3) {
+        return *reinterpret_cast<const uint32_t *>(sm + first_elem / 2);
+    } else if constexpr (KB == 1) {
+        return *reinterpret_cast<const uint16_t *>(sm + first_elem / 4);
+    } else {
+        return sm[first_elem / 8];
+    }
+}
+
+// Two bf16 words (sign << 15 | exponent << 7 | kept mantissa bits << (7 - KB)) from the field
+// bits of a pair of neighbouring elements and the two slot-table entries that decoded them
+// (exponent in the low byte of an entry).
+template <int KB>
+__device__ __forceinline__ uint32_t merge_pair(uint64_t fields, int pair, uint32_t entry_lo, uint32_t entry_hi)
+{
+    // [0, exponent_hi, 0, exponent_lo]
+    const uint32_t expo = __builtin_amdgcn_perm(entry_hi, entry_lo, 0x0c040c00u);
+    if constexpr (KB == 7) {
+        // lossless: a field is the byte sign << 7 | mantissa.  Spread the two bytes over the two
+        // halfwords ([b1, b1, b0, b0]) and keep bit 15 and bits 6..0 of each.
+        const uint32_t half = static_cast<uint32_t>(fields >> (32 * (pair >> 1)));
+        const uint32_t twice = __builtin_amdgcn_perm(half, half, (pair & 1) ? 0x03030202u : 0x01010000u);
+        return (expo << 7) | (twice & 0x807F807Fu);
+    } else if constexpr (KB == 3) {
+        // byte `pair` of the 32 field bits holds two nibbles s m2 m1 m0 (low nibble = first element).
+        // Nibbles into halfwords, then one multiply by 2^4 + 2^12 puts m at bits 6..4 and s at bit 15.
+        const uint32_t v = static_cast<uint32_t>(fields);
+        const uint32_t even = v & 0x0F0F0F0Fu, odd = (v >> 4) & 0x0F0F0F0Fu;
+        const uint32_t nib = __builtin_amdgcn_perm(odd, even, 0x0c000c00u | ((4u + pair) << 16) | pair);
+        return (expo << 7) | (__umul24(nib, 0x1010u) & 0x80708070u);
+    } else if constexpr (KB == 1) {
+        // nibble `pair` of the 16 field bits is s1 m1 s0 m0: m0 -> bit 6, s0 -> 15, m1 -> 22, s1 -> 31
+        const uint32_t f2 = (static_cast<uint32_t>(fields) >> (4 * pair)) & 0xFu;
+        const uint32_t spread = __umul24(f2 << 16, 0x1010u) + __umul24(f2, 0x4040u);
+        return (expo << 7) | (spread & 0x80408040u);
+    } else {
+        // bits 2*pair and 2*pair + 1 of the 8 field bits are the two signs
+        const uint32_t v = static_cast<uint32_t>(fields);
+        return (expo << 7) | ((v << (15 - 2 * pair)) & 0x8000u) | ((v << (30 - 2 * pair)) & 0x80000000u);
+    }
+}
+
+struct LdsWords {
+    const uint8_t *base;  // LDS copy of the workgroup's runs
+    __device__ __forceinline__ uint32_t peek(uint32_t at) const { return *reinterpret_cast<const uint16_t *>(base + at); }
+};
+struct GlobalWords {
+    const uint8_t *base;  // the lane's run inside the blob
+    __device__ __forceinline__ uint32_t peek(uint32_t at) const { return *reinterpret_cast<const uint16_t *>(base + at); }
+};
+struct NoWords {
+    __device__ __forceinline__ uint32_t peek(uint32_t) const { return 0; }
+};
+
+// One rANS decoding step of a lane's state; returns the slot-table entry (symbol in its low
+// byte).  `next` always holds the word at byte position wp of the lane's word source, so a
+// refill is a shift-or; the following word is fetched only then.
+template <class WordSrc>
+__device__ __forceinline__ uint32_t rans_get(const uint32_t *__restrict__ lut, uint32_t &x, uint32_t &wp,
+                                             uint32_t &next, const WordSrc &src)
+{
+    const uint32_t e = lut[x & (kM - 1)];
+    x = __umul24((e >> 8) & 0xFFFu, x >> kProbBits) + (e >> 20);
+    if (x < kRansL) {
+        x = (x << 16) | next;
+        wp += 2;
+        next = src.peek(wp);
+    }
+    return e;
+}
+
+// Walks one state over its part of chunk [base, base + m) and writes the merged bf16 words.
+// LONE: the tensor has a single exponent value (f = 4096): the state never moves and there are
+// no words.  Returns through x / wp what the well-formedness check needs.
+// Field bits of 8 neighbouring elements; with block-wise normalisation (KB < 7, so the fields
+// take at most 32 bits) the block's coefficient byte rides in bits 32..39.
+template <int KB, bool NORM>
+__device__ __forceinline__ uint64_t load_turn(const uint8_t *__restrict__ sm, const uint8_t *__restrict__ coef,
+                                              uint32_t block, uint64_t first_elem)
+{
+    uint64_t f = load_fields<KB>(sm, first_elem);
+    if constexpr (NORM)
+        f |= static_cast<uint64_t>(coef[first_elem / block]) << 32;
+    return f;
+}
+
+// bf16(stored * c) on the two halves of a merged dword
+__device__ __forceinline__ uint32_t denormalise_pair(uint32_t d, float c)
+{
+    return denormalise_word(d & 0xFFFFu, c) | (denormalise_word(d >> 16, c) << 16);
+}
+
+template <int KB, bool LONE, bool NORM, class WordSrc>
+__device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
+                                           uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
+                                           const uint8_t *__restrict__ coef, uint32_t block,
+                                           uint64_t (&fields)[kTurnGroup], uint16_t *__restrict__ out,
+                                           uint64_t base, uint32_t m, uint32_t j)
+{
+    // `fields` arrives holding the field bits of the state's first kTurnGroup turns (full chunks only)
+    uint32_t next = LONE ? 0u : src.peek(wp);
+    if (m == kChunk) {
+        uint4 *out4 = reinterpret_cast<uint4 *>(out + base) + j;
+        const uint64_t first = base + j * kRun;
+        // Turns are taken in groups: the field loads of the next group are issued together before
+        // the current group is decoded, and the group's 128-bit stores leave back to back, so
+        // each state keeps several memory requests in flight and a chunk is written in bursts of
+        // kTurnGroup * 256 contiguous bytes.
+        for (uint32_t q0 = 0; q0 < kTurns; q0 += kTurnGroup) {
+            uint64_t fields_next[kTurnGroup];
+            // the last group re-reads its own fields (stays in bounds)
+            const uint32_t qn = q0 + kTurnGroup < kTurns ? q0 + kTurnGroup : q0;
+#pragma unroll
+            for (uint32_t r = 0; r < kTurnGroup; ++r)
+                fields_next[r] = load_turn<KB, NORM>(sm, coef, block, first + (qn + r) * kTurn);
+            uint4 o[kTurnGroup];
+#pragma unroll
+            for (uint32_t r = 0; r < kTurnGroup; ++r) {
+                uint32_t e[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    e[t] = LONE ? lone : rans_get(lut, x, wp, next, src);
+                o[r].x = merge_pair<KB>(fields[r], 0, e[0], e[1]);
+                o[r].y = merge_pair<KB>(fields[r], 1, e[2], e[3]);
+                o[r].z = merge_pair<KB>(fields[r], 2, e[4], e[5]);
+                o[r].w = merge_pair<KB>(fields[r], 3, e[6], e[7]);
+                if constexpr (NORM) {
+                    const float c = coefficient(static_cast<uint32_t>(fields[r] >> 32) & 0x7Fu);
+                    o[r].x = denormalise_pair(o[r].x, c);
+                    o[r].y = denormalise_pair(o[r].y, c);
+                    o[r].z = denormalise_pair(o[r].z, c);
+                    o[r].w = denormalise_pair(o[r].w, c);
+                }
+            }
+#pragma unroll
+            for (uint32_t r = 0; r < kTurnGroup; ++r) {
+                // streamed out once: non-temporal, so the words do not displace the tables in cache
+                uint4 *dst = &out4[(q0 + r) * kStates];
+                __builtin_nontemporal_store(o[r].x, &dst->x);
+                __builtin_nontemporal_store(o[r].y, &dst->y);
+                __builtin_nontemporal_store(o[r].z, &dst->z);
+                __builtin_nontemporal_store(o[r].w, &dst->w);
+                fields[r] = fields_next[r];
+            }
+        }
+    } else {
+        // ragged last chunk: element by element
+        constexpr uint32_t width = KB + 1, per_byte = 8 / width;
+        for (uint32_t q = 0; q < kTurns; ++q) {
+            for (uint32_t t = 0; t < kRun; ++t) {
+                const uint32_t i = q * kTurn + j * kRun + t;
+                if (i >= m)
+                    continue;
+                const uint32_t sym = (LONE ? lone : rans_get(lut, x, wp, next, src)) & 0xFFu;
+                const uint64_t g = base + i;
+                const uint32_t field = (sm[g / per_byte] >> ((g % per_byte) * width)) & ((1u << width) - 1u);
+                uint32_t u = ((field >> KB) << 15) | (sym << 7) | ((field & ((1u << KB) - 1u)) << (7 - KB));
+                if constexpr (NORM)
+                    u = denormalise_word(u, coefficient(coef[g / block]));
+                out[g] = static_cast<uint16_t>(u);
+            }
+        }
+    }
+}
+
+// What the decoder needs to know about one tensor (all device pointers).
+struct DecodeArgs {
+    const TableBlock *tb;
+    const uint32_t *offsets;
+    const uint32_t *states;
+    const uint8_t *lens;
+    const uint16_t *words;
+    const uint8_t *sm;
+    const uint8_t *coef;  // block coefficients (block-wise normalised blobs only)
+    uint16_t *out;
+    uint32_t *status;
+    uint64_t n;
+    uint32_t n_chunks;
+    uint32_t block;       // 0: no block-wise normalisation
+    uint32_t wg_end;      // batches: first workgroup index after this tensor's
+};
+
+// Decodes the chunks of workgroup `wg` of one tensor.
+template <int KB, bool NORM>
+__device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ tb,
+                                                 const uint32_t *__restrict__ offsets,
+                                                 const uint32_t *__restrict__ states,
+                                                 const uint8_t *__restrict__ lens,
+                                                 const uint16_t *__restrict__ words,
+                                                 const uint8_t *__restrict__ sm,
+                                                 const uint8_t *__restrict__ coef, uint32_t block,
+                                                 uint16_t *__restrict__ out,
+                                                 uint64_t n, uint32_t n_chunks, uint32_t *__restrict__ status,
+                                                 uint32_t wg, uint32_t *__restrict__ lut, uint8_t *__restrict__ stage)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint32_t threads = blockDim.x;            // a multiple of 64, at most kDecThreads
+    const uint32_t chunks_per_wg = threads / kStates;
+    const uint32_t c0 = wg * chunks_per_wg;
+    const uint32_t c1 = c0 + chunks_per_wg < n_chunks ? c0 + chunks_per_wg : n_chunks;
+    const uint32_t c = c0 + tid / kStates;
+    const uint32_t j = tid % kStates;
+    const bool live = c < n_chunks;
+    const uint32_t id = c * kStates + j;
+    const uint64_t base = static_cast<uint64_t>(c) * kChunk;
+    const uint32_t m = !live ? 0u : ((n - base) < kChunk ? static_cast<uint32_t>(n - base) : kChunk);
+
+    // ---- every load that depends on nothing is issued first, so their latencies overlap
+    const uint32_t off0 = offsets[c0];
+    const uint32_t off1 = offsets[c1];
+    const uint32_t off_c = live ? offsets[c] : 0u;
+    uint32_t x = live ? states[id] : kRansL;
+    const uint32_t len = live ? lens[id] : 0u;
+    const uint32_t lone = tb->lone;
+    uint64_t fields0[kTurnGroup];
+#pragma unroll
+    for (uint32_t r = 0; r < kTurnGroup; ++r)
+        fields0[r] = m == kChunk ? load_turn<KB, NORM>(sm, coef, block, base + r * kTurn + j * kRun) : 0;
+    const uint4 *lut_g = reinterpret_cast<const uint4 *>(tb->lut);
+    uint4 lut_piece[2];  // 16 KB table / 16 B = 1024 pieces; 2 per thread at 512 threads
+#pragma unroll
+    for (uint32_t r = 0; r < 2; ++r) {
+        const uint32_t i = tid + r * threads;
+        lut_piece[r] = i < kM / 4 ? lut_g[i] : make_uint4(0, 0, 0, 0);
+    }
+
+    // ---- stage the word runs of chunks [c0, c1): one contiguous piece of the blob
+    const uint64_t byte0 = static_cast<uint64_t>(off0) * 2;
+    const uint64_t byte1 = static_cast<uint64_t>(off1) * 2;
+    const uint64_t aligned0 = byte0 & ~static_cast<uint64_t>(15);
+    const uint64_t stage_len = byte1 - aligned0;
+    const bool staged = stage_len + 16 <= kStageBytes;  // room for the one-word look-ahead
+    if (staged) {
+        const uint4 *from = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(words) + aligned0);
+        uint4 *to = reinterpret_cast<uint4 *>(stage);
+        for (uint32_t i = tid; i * 16 < stage_len; i += threads)
+            to[i] = from[i];
+    }
+    // ---- slot table into LDS (small workgroups loop over the remaining pieces)
+#pragma unroll
+    for (uint32_t r = 0; r < 2; ++r) {
+        const uint32_t i = tid + r * threads;
+        if (i < kM / 4)
+            reinterpret_cast<uint4 *>(lut)[i] = lut_piece[r];
+    }
+    for (uint32_t i = tid + 2 * threads; i < kM / 4; i += threads)
+        reinterpret_cast<uint4 *>(lut)[i] = lut_g[i];
+    __syncthreads();
+
+    // ---- one lane, one state
+    if (!live)
+        return;
+    // start of this state's run: chunk offset + lengths of the states before it (16-lane prefix)
+    uint32_t before = len;
+#pragma unroll
+    for (uint32_t d = 1; d < kStates; d <<= 1) {
+        const uint32_t o = __shfl_up(before, d, kStates);
+        if (j >= d)
+            before += o;
+    }
+    before -= len;
+    const uint64_t run_byte = (static_cast<uint64_t>(off_c) + before) * 2;
+
+    uint32_t wp = 0, wp_begin = 0;
+    if (lone < 256) {
+        walk_state<KB, true, NORM>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j);
+    } else if (staged) {
+        wp = wp_begin = static_cast<uint32_t>(run_byte - aligned0);
+        walk_state<KB, false, NORM>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m, j);
+    } else {
+        // the runs of this workgroup's chunks did not fit the LDS window (more than ~4 bits per
+        // symbol): read the words straight from the blob
+        walk_state<KB, false, NORM>(lut, GlobalWords{reinterpret_cast<const uint8_t *>(words) + run_byte}, 0u, x, wp,
+                                    sm, coef, block, fields0, out, base, m, j);
+    }
+    // a well-formed run is consumed exactly and leaves the state where the encoder started
+    if (x != kRansL || wp - wp_begin != 2 * len)
+        atomicOr(status, 1u);
+}
+
+template <int KB, bool NORM>
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(const DecodeArgs a)
+{
+    __shared__ __align__(16) uint32_t lut[kM];
+    __shared__ __align__(16) uint8_t stage[kStageBytes];
+    decode_workgroup<KB, NORM>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.out, a.n,
+                               a.n_chunks, a.status, blockIdx.x, lut, stage);
+}
+
+// Several tensors in one launch (a layer's weights): workgroups [t[i-1].wg_end, t[i].wg_end)
+// belong to tensor i.  Small tensors, which alone cannot fill the chip, overlap with the others.
+struct BatchArgs {
+    DecodeArgs t[kBatchMax];
+    uint32_t count;
+};
+
+template <int KB, bool NORM>
+__global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchArgs b)
+{
+    __shared__ __align__(16) uint32_t lut[kM];
+    __shared__ __align__(16) uint8_t stage[kStageBytes];
+    uint32_t i = 0, first = 0;
+    while (i + 1 < b.count && blockIdx.x >= b.t[i].wg_end) {
+        first = b.t[i].wg_end;
+        ++i;
+    }
+    const DecodeArgs &a = b.t[i];
+    decode_workgroup<KB, NORM>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.out, a.n,
+                               a.n_chunks, a.status, blockIdx.x - first, lut, stage);
+}
+
+}  // namespace nz

@@ -1,0 +1,109 @@
+// Format constants and the device-side structures shared by the compression and decompression
+// kernels of the NeuZip codec (see neuzip.hip for the stream format).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include "neuzip.h"
+
+namespace nz {
+
+constexpr uint32_t kProbBits = NEUZIP_PROB_BITS;
+constexpr uint32_t kM = 1u << kProbBits;
+constexpr uint32_t kChunk = NEUZIP_CHUNK;
+constexpr uint32_t kStates = NEUZIP_STATES_PER_CHUNK;
+constexpr uint32_t kRun = NEUZIP_RUN;
+constexpr uint32_t kTurn = kStates * kRun;          // symbols per turn of all states (128)
+constexpr uint32_t kTurns = kChunk / kTurn;         // turns per full chunk (32)
+constexpr uint32_t kRansL = 1u << 16;
+// Words one state can emit for its 256 symbols.  Every step grows log2(x + 1) by at most 12 bits and
+// every emitted word shrinks it by at least 16 - log2(17/16) bits, which bounds a run by 193 words.
+constexpr uint32_t kRunCap = 200;
+constexpr uint32_t kMagic = 0x315A554Eu;            // "NUZ1"
+constexpr uint32_t kHeaderBytes = 64;
+
+// Decoder launch shape: at most 512 threads = 8 waves, each wave walks 4 chunks (4 x 16 states).
+constexpr uint32_t kDecThreads = 512;
+constexpr uint32_t kDecChunksPerWg = kDecThreads / kStates;   // 32
+// LDS: 16 KB slot table + staged word runs.  Two workgroups share a CU's 160 KB.
+constexpr uint32_t kStageBytes = 62 * 1024;
+// Turns (of 8 symbols per state) whose loads and stores are issued together.
+#ifndef NEUZIP_TURN_GROUP
+#define NEUZIP_TURN_GROUP 2
+#endif
+constexpr uint32_t kTurnGroup = NEUZIP_TURN_GROUP;
+static_assert(kTurns % kTurnGroup == 0, "a chunk is a whole number of turn groups");
+
+
+// ------------------------------------------------------------------------------------------
+// Device-side table block that sits at the start of every blob's fixed allocation.
+// ------------------------------------------------------------------------------------------
+struct TableBlock {
+    uint16_t freq[256];    // quantised frequencies (stored in the container)
+    uint16_t cum[264];     // exclusive cumulative frequencies, cum[256] = 4096 (derived)
+    uint32_t counts[256];  // exponent histogram of the source tensor
+    uint32_t status[4];    // [0] != 0: a decode found a malformed stream
+    uint32_t lone;         // the only exponent value of the tensor (its f is 4096), else 256
+    uint32_t pad[55];
+    // decoder slot table (derived): lut[slot] = symbol | f << 8 | (slot - cum[symbol]) << 20
+    uint32_t lut[4096];
+};
+static_assert(sizeof(TableBlock) % 256 == 0, "table block keeps later sections aligned");
+
+// Per-symbol encoder constants (16 bytes, one ds_read_b128).
+//   The step is x <- (x / f) * M + (x mod f) + cum = q * (M - f) + x + cum with q = floor(x / f).
+//   limit: the state is renormalised before the step when x >= limit = f << 20, so q < 2^20.
+//   rcp: a float slightly below 1/f, (1/f)(1 - 2^-21).  float(x) * rcp, truncated, is q or q - 1
+//   (three roundings of 2^-24 cannot overcome the 2^-21 bias, and q * 1.5 * 2^-21 < 1); one
+//   compare of the remainder against f settles it.  All of this runs at full VALU rate, unlike a
+//   32-bit multiply-high.
+struct EncSym {
+    float rcp;
+    uint32_t limit;
+    uint32_t cmpl_cum;  // (M - f) | cum << 16
+    uint32_t f;
+};
+
+// ------------------------------------------------------------------------------------------
+// Compression works on a batch of up to 8 tensors that share mantissa_bits and block size (the
+// weights of a layer): every kernel of the pipeline is launched once for the whole batch, so
+// tensors too small to fill the chip overlap with the others.  A single tensor is a batch of one.
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kBatchMax = 8;
+
+struct CompressItem {
+    const uint16_t *src;
+    uint64_t n;
+    TableBlock *tb;
+    uint32_t *offsets;
+    uint32_t *states;
+    uint8_t *lens;
+    uint8_t *sm;
+    uint8_t *coef;
+    uint16_t *words;       // known only after the stream length has been read back
+    uint32_t n_chunks;
+    uint32_t block;        // 0: no block-wise normalisation
+    uint32_t group_base;   // first encoder group (16 chunks) of this tensor in the workspace arrays
+    uint32_t hist_end;     // first workgroup after this tensor's in the histogram launch
+    uint32_t enc_end;      // ... in the encode launch
+    uint32_t compact_end;  // ... in the compaction launch
+};
+
+struct CompressBatch {
+    CompressItem it[kBatchMax];
+    uint32_t count;
+    uint32_t seq;  // stamp of this call
+};
+
+// Host-visible results of one compress call (pinned host memory the kernels write directly).
+struct HostRecord {
+    uint32_t seq;  // stamp of the compress call whose results are complete (written last)
+    uint32_t pad;
+    struct Item {
+        uint32_t total_words[2];
+        uint32_t counts[256];
+        uint16_t freq[256];
+    } item[kBatchMax];
+};
+
+}  // namespace nz
