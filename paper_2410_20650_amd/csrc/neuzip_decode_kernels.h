@@ -117,7 +117,7 @@ __device__ __forceinline__ uint32_t denormalise_pair(uint32_t d, float c)
     return denormalise_word(d & 0xFFFFu, c) | (denormalise_word(d >> 16, c) << 16);
 }
 
-template <int KB, bool LONE, bool NORM, class WordSrc>
+template <int KB, bool LONE, bool NORM, bool STREAM, class WordSrc>
 __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
                                            uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
                                            const uint8_t *__restrict__ coef, uint32_t block,
@@ -161,12 +161,16 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
             }
 #pragma unroll
             for (uint32_t r = 0; r < kTurnGroup; ++r) {
-                // streamed out once: non-temporal, so the words do not displace the tables in cache
                 uint4 *dst = &out4[(q0 + r) * kStates];
-                __builtin_nontemporal_store(o[r].x, &dst->x);
-                __builtin_nontemporal_store(o[r].y, &dst->y);
-                __builtin_nontemporal_store(o[r].z, &dst->z);
-                __builtin_nontemporal_store(o[r].w, &dst->w);
+                if constexpr (STREAM) {
+                    // a tensor larger than the last-level cache: non-temporal stores
+                    __builtin_nontemporal_store(o[r].x, &dst->x);
+                    __builtin_nontemporal_store(o[r].y, &dst->y);
+                    __builtin_nontemporal_store(o[r].z, &dst->z);
+                    __builtin_nontemporal_store(o[r].w, &dst->w);
+                } else {
+                    *dst = o[r];
+                }
                 fields[r] = fields_next[r];
             }
         }
@@ -204,6 +208,7 @@ struct DecodeArgs {
     uint64_t n;
     uint32_t n_chunks;
     uint32_t block;       // 0: no block-wise normalisation
+    uint32_t stream_out;  // non-zero: the output does not fit the last-level cache, store non-temporally
     uint32_t wg_end;      // batches: first workgroup index after this tensor's
 };
 
@@ -216,7 +221,7 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
                                                  const uint16_t *__restrict__ words,
                                                  const uint8_t *__restrict__ sm,
                                                  const uint8_t *__restrict__ coef, uint32_t block,
-                                                 uint16_t *__restrict__ out,
+                                                 uint16_t *__restrict__ out, bool stream_out,
                                                  uint64_t n, uint32_t n_chunks, uint32_t *__restrict__ status,
                                                  uint32_t wg, uint32_t *__restrict__ lut, uint8_t *__restrict__ stage)
 {
@@ -288,17 +293,30 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
     before -= len;
     const uint64_t run_byte = (static_cast<uint64_t>(off_c) + before) * 2;
 
+    // (the streaming and the cached store variants are separate instantiations: merged into one
+    // loop the compiler drops the non-temporal hint)
     uint32_t wp = 0, wp_begin = 0;
     if (lone < 256) {
-        walk_state<KB, true, NORM>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j);
+        if (stream_out)
+            walk_state<KB, true, NORM, true>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j);
+        else
+            walk_state<KB, true, NORM, false>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j);
     } else if (staged) {
         wp = wp_begin = static_cast<uint32_t>(run_byte - aligned0);
-        walk_state<KB, false, NORM>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m, j);
+        if (stream_out)
+            walk_state<KB, false, NORM, true>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
+                                              j);
+        else
+            walk_state<KB, false, NORM, false>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
+                                               j);
     } else {
         // the runs of this workgroup's chunks did not fit the LDS window (more than ~4 bits per
         // symbol): read the words straight from the blob
-        walk_state<KB, false, NORM>(lut, GlobalWords{reinterpret_cast<const uint8_t *>(words) + run_byte}, 0u, x, wp,
-                                    sm, coef, block, fields0, out, base, m, j);
+        const GlobalWords direct{reinterpret_cast<const uint8_t *>(words) + run_byte};
+        if (stream_out)
+            walk_state<KB, false, NORM, true>(lut, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j);
+        else
+            walk_state<KB, false, NORM, false>(lut, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j);
     }
     // a well-formed run is consumed exactly and leaves the state where the encoder started
     if (x != kRansL || wp - wp_begin != 2 * len)
@@ -310,7 +328,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(const DecodeArgs a)
 {
     __shared__ __align__(16) uint32_t lut[kM];
     __shared__ __align__(16) uint8_t stage[kStageBytes];
-    decode_workgroup<KB, NORM>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.out, a.n,
+    decode_workgroup<KB, NORM>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.out, a.stream_out != 0, a.n,
                                a.n_chunks, a.status, blockIdx.x, lut, stage);
 }
 
@@ -332,7 +350,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchAr
         ++i;
     }
     const DecodeArgs &a = b.t[i];
-    decode_workgroup<KB, NORM>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.out, a.n,
+    decode_workgroup<KB, NORM>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.out, a.stream_out != 0, a.n,
                                a.n_chunks, a.status, blockIdx.x - first, lut, stage);
 }
 
