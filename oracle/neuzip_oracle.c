@@ -185,13 +185,35 @@ double nzo_cross_entropy(const uint64_t cnt[256], const uint16_t freq[256])
  *   at that moment (lowest value on a tie). */
 int nzo_quantise(const uint64_t cnt[256], uint16_t freq[256])
 {
+    return nzo_quantise_guarded(cnt, 0, freq);
+}
+
+/* The same with a guard band for tables that outlive the tensor they were counted on (Alg. 1
+ * compresses every weight again after each update; a table kept from the step before must be
+ * able to code exponents the update newly produces).  With guard > 0 the symbols "that occur"
+ * are taken to be every exponent from (smallest occurring - guard) to (largest occurring +
+ * guard), clipped to 0..255: the ones with count 0 get f = 1 by the same max(1, .) rule.
+ * guard = 0 is the plain rule.  Not in the paper. */
+int nzo_quantise_guarded(const uint64_t cnt[256], uint32_t guard, uint16_t freq[256])
+{
     uint64_t total = 0;
-    for (int s = 0; s < 256; s++)
+    int lo = 256, hi = -1;
+    for (int s = 0; s < 256; s++) {
         total += cnt[s];
+        if (cnt[s] > 0) {
+            if (lo == 256)
+                lo = s;
+            hi = s;
+        }
+    }
     uint32_t f[256];
     int64_t sum = 0;
     for (int s = 0; s < 256; s++) {
-        if (cnt[s] == 0 || total == 0) {
+        int member = cnt[s] > 0;
+        if (guard > 0 && total > 0 && (int64_t)s >= (int64_t)lo - (int64_t)guard &&
+            (int64_t)s <= (int64_t)hi + (int64_t)guard)
+            member = 1;
+        if (!member || total == 0) {
             f[s] = 0;
             continue;
         }
@@ -444,12 +466,43 @@ static void *enc_worker(void *arg)
 }
 
 static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, const uint8_t *coef,
-                         uint8_t *blob, uint64_t cap, uint64_t *written, int threads);
+                         const uint16_t *given_freq, uint32_t guard, uint8_t *blob, uint64_t cap,
+                         uint64_t *written, int threads);
 
 int nzo_compress(const uint16_t *w, uint64_t n, int k, uint8_t *blob, uint64_t cap,
                  uint64_t *written, int threads)
 {
-    return compress_impl(w, n, k, 0, NULL, blob, cap, written, threads);
+    return compress_impl(w, n, k, 0, NULL, NULL, 0, blob, cap, written, threads);
+}
+
+/* The table keeps a guard band (nzo_quantise_guarded); header word 52 records the guard. */
+int nzo_compress_guarded(const uint16_t *w, uint64_t n, int k, uint32_t guard, uint8_t *blob,
+                         uint64_t cap, uint64_t *written, int threads)
+{
+    if (guard > 255)
+        return NZO_EINVAL;
+    return compress_impl(w, n, k, 0, NULL, NULL, guard, blob, cap, written, threads);
+}
+
+/* Compression with a table that was made earlier (from the weights before an update): no
+ * statistics are taken from w.  NZO_ESTALE if w holds an exponent the table gives no room. */
+int nzo_compress_with_table(const uint16_t *w, uint64_t n, int k, const uint16_t freq[256],
+                            uint32_t guard, uint8_t *blob, uint64_t cap, uint64_t *written,
+                            int threads)
+{
+    if (!freq || guard > 255)
+        return NZO_EINVAL;
+    uint32_t sum = 0;
+    for (int s = 0; s < 256; s++)
+        sum += freq[s];
+    if (sum != NZO_M && !(n == 0 && sum == 0))
+        return NZO_EINVAL;
+    uint64_t cnt[256];
+    nzo_histogram(w, n, cnt);
+    for (int s = 0; s < 256; s++)
+        if (cnt[s] > 0 && freq[s] == 0)
+            return NZO_ESTALE;
+    return compress_impl(w, n, k, 0, NULL, freq, guard, blob, cap, written, threads);
 }
 
 /* Lossy variant with block-wise normalisation: the coefficients are taken from the original
@@ -469,14 +522,15 @@ int nzo_compress_blockwise(const uint16_t *w, uint64_t n, int k, uint32_t block,
     }
     nzo_block_coefficients(w, n, block, coef);
     nzo_normalise(w, n, block, coef, normal);
-    int rc = compress_impl(normal, n, k, block, coef, blob, cap, written, threads);
+    int rc = compress_impl(normal, n, k, block, coef, NULL, 0, blob, cap, written, threads);
     free(coef);
     free(normal);
     return rc;
 }
 
 static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, const uint8_t *coef,
-                         uint8_t *blob, uint64_t cap, uint64_t *written, int threads)
+                         const uint16_t *given_freq, uint32_t guard, uint8_t *blob, uint64_t cap,
+                         uint64_t *written, int threads)
 {
     if (!valid_k(k) || n >= ((uint64_t)1 << 32))
         return NZO_EINVAL;
@@ -486,8 +540,12 @@ static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, c
 
     uint64_t cnt[256];
     uint16_t freq[256];
-    nzo_histogram(w, n, cnt);
-    nzo_quantise(cnt, freq);
+    if (given_freq) {
+        memcpy(freq, given_freq, sizeof(freq));
+    } else {
+        nzo_histogram(w, n, cnt);
+        nzo_quantise_guarded(cnt, guard, freq);
+    }
 
     uint32_t *states = (uint32_t *)malloc((size_t)(nc * NZO_K + 1) * sizeof(uint32_t));
     uint16_t *lens = (uint16_t *)malloc((size_t)(nc * NZO_K + 1) * sizeof(uint16_t));
@@ -565,6 +623,7 @@ static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, c
     put32(blob + 36, (uint32_t)nc);
     put64(blob + 40, total_words);
     put32(blob + 48, block); /* 0: no block-wise normalisation, no coefficient section */
+    put32(blob + 52, guard); /* guard band the table was made with (0: none) */
     for (int s = 0; s < 256; s++)
         put16(blob + off_freq + 2 * s, freq[s]);
 

@@ -39,6 +39,8 @@
  *              | states[n_chunks*K] u32 | lens[n_chunks*K] u8
  *              | words[total_words] u16 | signmant[ceil(n*(k+1)/8)] u8
  *              | coef[ceil(n/block)] u8   (only when header word 48, block, is not 0)
+ *   header: magic u32 @0, version u32 @4, n u64 @8, k @16, PROB_BITS @20, CHUNK @24, K @28,
+ *   G @32, n_chunks @36, total_words u64 @40, block @48, guard @52 (u32 unless noted), rest 0.
  *   every section is zero-padded to a multiple of 16 bytes.
  *   offsets[c] = number of words that belong to chunks before c.
  *   Inside chunk c the K private runs follow each other, state 0 first;
@@ -64,7 +66,7 @@ enum {
 #define NZO_L 65536u
 #define NZO_MAGIC 0x315A554Eu /* "NUZ1" */
 
-enum { NZO_OK = 0, NZO_EINVAL = -1, NZO_ENOSPACE = -2, NZO_ECORRUPT = -4 };
+enum { NZO_OK = 0, NZO_EINVAL = -1, NZO_ENOSPACE = -2, NZO_ECORRUPT = -4, NZO_ESTALE = -6 };
 
 /* Alg. 1 "split": bf16 word -> sign bit, 8-bit exponent, 7-bit mantissa. */
 void nzo_split(const uint16_t *w, uint64_t n, uint8_t *sign, uint8_t *expo, uint8_t *mant);
@@ -94,6 +96,9 @@ double nzo_entropy(const uint64_t cnt[256]);
 double nzo_cross_entropy(const uint64_t cnt[256], const uint16_t freq[256]);
 /* Integer quantisation of the counts to frequencies that sum to M. */
 int nzo_quantise(const uint64_t cnt[256], uint16_t freq[256]);
+/* The same, but every exponent within `guard` of the occupied range counts as occurring (f >= 1),
+ * so that the table can still code the tensor after a small update.  guard = 0: plain rule. */
+int nzo_quantise_guarded(const uint64_t cnt[256], uint32_t guard, uint16_t freq[256]);
 
 /* One coding step for a symbol with frequency f and cumulative start c.
  * Encoding moves the low 16 bits of x out first when needed (*emitted = 1,
@@ -113,6 +118,14 @@ int nzo_decode_chunk(uint8_t *sym, uint32_t m, const uint16_t freq[256], int K, 
 uint64_t nzo_compress_bound(uint64_t n, int k);
 int nzo_compress(const uint16_t *w, uint64_t n, int k, uint8_t *blob, uint64_t cap,
                  uint64_t *written, int threads);
+/* Table with a guard band; header word 52 holds the guard. */
+int nzo_compress_guarded(const uint16_t *w, uint64_t n, int k, uint32_t guard, uint8_t *blob,
+                         uint64_t cap, uint64_t *written, int threads);
+/* Compression with an earlier table instead of fresh statistics (Alg. 1 recompresses after every
+ * update); NZO_ESTALE when an exponent of w has frequency 0 in that table. */
+int nzo_compress_with_table(const uint16_t *w, uint64_t n, int k, const uint16_t freq[256],
+                            uint32_t guard, uint8_t *blob, uint64_t cap, uint64_t *written,
+                            int threads);
 /* Lossy container with block-wise normalisation (k in {3,1,0}); header word 48 holds the
  * block size and a section coef[ceil(n/block)] u8 follows the sign|mantissa stream. */
 int nzo_compress_blockwise(const uint16_t *w, uint64_t n, int k, uint32_t block, uint8_t *blob,

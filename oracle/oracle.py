@@ -22,7 +22,7 @@ G = 8
 RANS_L = 1 << 16
 HEADER_BYTES = 64
 
-OK, EINVAL, ENOSPACE, ECORRUPT = 0, -1, -2, -4
+OK, EINVAL, ENOSPACE, ECORRUPT, ESTALE = 0, -1, -2, -4, -6
 
 
 class OracleError(RuntimeError):
@@ -60,6 +60,12 @@ def lib():
         L.nzo_cross_entropy.restype = ctypes.c_double
         L.nzo_quantise.argtypes = [u64p, u16p]
         L.nzo_quantise.restype = i32
+        L.nzo_quantise_guarded.argtypes = [u64p, u32, u16p]
+        L.nzo_quantise_guarded.restype = i32
+        L.nzo_compress_guarded.argtypes = [u16p, u64, i32, u32, u8p, u64, u64p, i32]
+        L.nzo_compress_guarded.restype = i32
+        L.nzo_compress_with_table.argtypes = [u16p, u64, i32, u16p, u32, u8p, u64, u64p, i32]
+        L.nzo_compress_with_table.restype = i32
         L.nzo_rans_encode_step.argtypes = [u32, u32, u32, u16p, ctypes.POINTER(i32)]
         L.nzo_rans_encode_step.restype = u32
         L.nzo_rans_decode_step.argtypes = [u32, u32, u32, ctypes.c_uint16, ctypes.POINTER(i32)]
@@ -156,10 +162,13 @@ def cross_entropy(cnt, freq):
     return float(lib().nzo_cross_entropy(_p(cnt, ctypes.c_uint64), _p(freq, ctypes.c_uint16)))
 
 
-def quantise(cnt):
+def quantise(cnt, guard=0):
     cnt = np.ascontiguousarray(cnt, dtype=np.uint64)
     freq = np.zeros(256, np.uint16)
-    rc = lib().nzo_quantise(_p(cnt, ctypes.c_uint64), _p(freq, ctypes.c_uint16))
+    if guard:
+        rc = lib().nzo_quantise_guarded(_p(cnt, ctypes.c_uint64), guard, _p(freq, ctypes.c_uint16))
+    else:
+        rc = lib().nzo_quantise(_p(cnt, ctypes.c_uint64), _p(freq, ctypes.c_uint16))
     if rc != OK:
         raise OracleError(rc, "quantise")
     return freq
@@ -245,13 +254,27 @@ def lossy_blockwise(w, k, block):
     return denormalise(truncate(normalise(w, block, coef), k), block, coef)
 
 
-def compress(w, k=7, threads=1, block=0):
-    """bf16 words (uint16 array) -> container bytes (uint8 array)."""
+def compress(w, k=7, threads=1, block=0, guard=0, freq=None):
+    """bf16 words (uint16 array) -> container bytes (uint8 array).
+
+    guard: the table keeps f >= 1 that far beyond the occupied exponents; freq: code with this
+    earlier table instead of fresh statistics (OracleError with code ESTALE if it cannot)."""
     w = _u16(w)
     cap = int(lib().nzo_compress_bound(w.size, k if k in (7, 3, 1, 0) else 7))
     blob = np.empty(cap, np.uint8)
     written = ctypes.c_uint64(0)
-    if block:
+    if freq is not None:
+        if block:
+            raise ValueError("an earlier table cannot be combined with block-wise normalisation")
+        freq = np.ascontiguousarray(freq, dtype=np.uint16)
+        rc = lib().nzo_compress_with_table(_p(w, ctypes.c_uint16), w.size, k, _p(freq, ctypes.c_uint16), guard,
+                                           _p(blob, ctypes.c_uint8), cap, ctypes.byref(written), threads)
+    elif guard:
+        if block:
+            raise ValueError("a guard band cannot be combined with block-wise normalisation")
+        rc = lib().nzo_compress_guarded(_p(w, ctypes.c_uint16), w.size, k, guard, _p(blob, ctypes.c_uint8), cap,
+                                        ctypes.byref(written), threads)
+    elif block:
         rc = lib().nzo_compress_blockwise(_p(w, ctypes.c_uint16), w.size, k, block, _p(blob, ctypes.c_uint8), cap,
                                           ctypes.byref(written), threads)
     else:

@@ -23,12 +23,17 @@ def exponent(u):
     return (u >> 7) & 0xFF
 
 
-def quantise(cnt):
-    """Counts -> integer frequencies summing to M (0 for absent symbols)."""
+def quantise(cnt, guard=0):
+    """Counts -> integer frequencies summing to M (0 for absent symbols).  With guard > 0 the
+    exponents up to that far outside the occupied range are kept codable (f = 1)."""
     total = sum(cnt)
     if total == 0:
         return [0] * 256
-    f = [max(1, c * M // total) if c else 0 for c in cnt]
+    present = [s for s in range(256) if cnt[s]]
+    kept = set(present)
+    if guard:
+        kept |= set(range(max(0, present[0] - guard), min(255, present[-1] + guard) + 1))
+    f = [max(1, cnt[s] * M // total) if s in kept else 0 for s in range(256)]
     rest = M - sum(f)
     if rest > 0:
         top = max(range(256), key=lambda s: (cnt[s], -s))
@@ -147,8 +152,8 @@ def scale(words16, block, coef, divide):
     return out
 
 
-def compress(words16, k=7, block=0):
-    """List of bf16 words -> container bytes."""
+def compress(words16, k=7, block=0, guard=0, freq=None):
+    """List of bf16 words -> container bytes.  freq: an earlier table to code with."""
     coef = []
     if block:
         coef = block_coefficients(words16, block)
@@ -158,7 +163,9 @@ def compress(words16, k=7, block=0):
     cnt = [0] * 256
     for e in expo:
         cnt[e] += 1
-    freq = quantise(cnt)
+    if freq is None:
+        freq = quantise(cnt, guard)
+    freq = [int(v) for v in freq]
     nc = (n + CHUNK - 1) // CHUNK
     offsets, states, lens, payload = [], [], [], []
     for c in range(nc):
@@ -171,7 +178,8 @@ def compress(words16, k=7, block=0):
             lens.append(len(run))
             payload.extend(run)
     offsets.append(len(payload))
-    header = struct.pack("<IIQIIIIIIQI", 0x315A554E, 1, n, k, PROB_BITS, CHUNK, K, G, nc, len(payload), block)
+    header = struct.pack("<IIQIIIIIIQII", 0x315A554E, 1, n, k, PROB_BITS, CHUNK, K, G, nc, len(payload), block,
+                         guard)
     header += bytes(64 - len(header))
     out = header
     out += struct.pack("<256H", *freq)

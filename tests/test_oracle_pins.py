@@ -487,3 +487,122 @@ def test_blockwise_rejects_lossless_and_odd_blocks():
         O.compress(w, 3, block=100)
     every = O.compress(ALL, 3, block=64)
     assert np.array_equal(O.decompress(every, 65536), O.lossy_blockwise(ALL, 3, 64))
+
+
+# ---------------------------------------------------------------- tables kept across weight updates (Alg. 1 recompresses every step)
+
+def test_guarded_quantise_closed_cases():
+    # one exponent, guard 2: five codable symbols; floors give 4096 + 4 ones, the excess of 4
+    # comes off the only large entry
+    c = np.zeros(256, np.uint64)
+    c[120] = 77
+    f = O.quantise(c, guard=2)
+    assert {s: int(f[s]) for s in np.nonzero(f)[0]} == {118: 1, 119: 1, 120: 4092, 121: 1, 122: 1}
+    # the band is clipped at both ends of the byte range
+    c = np.zeros(256, np.uint64)
+    c[0] = 5
+    f = O.quantise(c, guard=3)
+    assert list(f[:5]) == [4093, 1, 1, 1, 0] and f.sum() == 4096
+    c = np.zeros(256, np.uint64)
+    c[255] = 5
+    f = O.quantise(c, guard=1)
+    assert list(f[253:]) == [0, 1, 4095]
+    # two equal halves with a hole between them, guard 1: symbols 99..105 are codable, the five
+    # empty ones get 1, and the excess of 5 is taken alternately from the two large entries,
+    # the lower symbol first: 100 gives three units, 104 two
+    c = np.zeros(256, np.uint64)
+    c[[100, 104]] = 1000
+    f = O.quantise(c, guard=1)
+    assert {s: int(f[s]) for s in np.nonzero(f)[0]} == {99: 1, 100: 2045, 101: 1, 102: 1, 103: 1, 104: 2046, 105: 1}
+    # nothing to add when every exponent already occurs
+    assert np.all(O.quantise(np.full(256, 9, np.uint64), guard=5) == 16)
+    assert O.quantise(np.zeros(256, np.uint64), guard=4).sum() == 0
+
+
+def test_guarded_quantise_properties_and_second_implementation():
+    rng = np.random.default_rng(11)
+    for trial in range(150):
+        k = int(rng.integers(1, 40))
+        lo = int(rng.integers(0, 256 - k))
+        c = np.zeros(256, np.uint64)
+        idx = lo + rng.choice(k, max(1, k // 2), replace=False)
+        c[idx] = (rng.pareto(0.7, idx.size) * 10 + 1).astype(np.uint64)
+        guard = int(rng.integers(0, 6))
+        f = O.quantise(c, guard=guard)
+        assert f.sum() == 4096
+        present = np.nonzero(c)[0]
+        want = np.zeros(256, bool)
+        if guard:
+            want[max(0, present[0] - guard): min(255, present[-1] + guard) + 1] = True
+        else:
+            want[present] = True
+        assert np.array_equal(f > 0, want)
+        assert list(f) == P.quantise([int(x) for x in c], guard)
+        if guard == 0:
+            assert np.array_equal(f, O.quantise(c))
+        # the band costs at most its share of the probability mass
+        assert O.cross_entropy(c, f) <= O.cross_entropy(c, O.quantise(c)) + math.log2(4096 / (4096 - 2 * guard - k)) + 1e-9
+
+
+@pytest.mark.parametrize("k", [7, 3, 0])
+@pytest.mark.parametrize("n", [1, 130, 4097, 20_000])
+def test_compression_with_an_earlier_table(n, k):
+    old = inputs.bits(inputs.gaussian_bf16(n, seed=300 + n))
+    new = inputs.bits(inputs.synthetic_update(inputs.gaussian_bf16(n, seed=300 + n), seed=7))
+    guard = 8
+    first = O.compress(old, k, guard=guard)
+    table = O.blob_info(first)["freq"]
+    assert np.array_equal(table, O.quantise(O.histogram(old), guard=guard))
+    assert int(first[52:56].view("<u4")[0]) == guard
+    assert np.all(table[O.split(new)[1]] > 0)                   # seeds chosen so that the update stays inside the band
+    blob = O.compress(new, k, guard=guard, freq=table)
+    # decoding needs nothing but the container: the values are the new ones
+    assert np.array_equal(O.decompress(blob, n), O.truncate(new, k))
+    assert np.array_equal(O.blob_info(blob)["freq"], table)
+    # second statement of the format, given the same table
+    assert blob.tobytes() == P.compress([int(u) for u in new], k, guard=guard, freq=[int(v) for v in table])
+    assert P.decompress(blob.tobytes()) == [int(u) for u in O.truncate(new, k)]
+
+
+def test_own_table_reproduces_plain_compression():
+    w = inputs.bits(inputs.student_t4_bf16(30_000, seed=21))
+    plain = O.compress(w, 7)
+    again = O.compress(w, 7, freq=O.blob_info(plain)["freq"])
+    assert np.array_equal(plain, again)
+    guarded = O.compress(w, 7, guard=3)
+    again = O.compress(w, 7, guard=3, freq=O.blob_info(guarded)["freq"])
+    assert np.array_equal(guarded, again)
+    assert not np.array_equal(O.blob_info(plain)["freq"], O.blob_info(guarded)["freq"])
+
+
+def test_stale_table_is_refused_when_an_exponent_has_no_room():
+    w = inputs.bits(inputs.gaussian_bf16(5000, seed=2))
+    table = O.quantise(O.histogram(w), guard=1)
+    top = int(np.nonzero(table)[0][-1])
+    bad = w.copy()
+    bad[1234] = np.uint16((top + 1) << 7)                      # one weight two binades above the band's end
+    with pytest.raises(O.OracleError) as err:
+        O.compress(bad, 7, guard=1, freq=table)
+    assert err.value.code == O.ESTALE
+    ok = w.copy()
+    ok[1234] = np.uint16(top << 7)                             # the band's last exponent is still codable
+    assert np.array_equal(O.decompress(O.compress(ok, 7, guard=1, freq=table), ok.size), ok)
+    with pytest.raises(O.OracleError):                          # a table that does not sum to 4096
+        O.compress(w, 7, freq=np.ones(256, np.uint16))
+
+
+def test_size_under_a_stale_table_is_the_cross_entropy():
+    # coded bits = information content of the NEW exponents under the OLD table + flush
+    n = 64 * 4096
+    base = inputs.gaussian_bf16(n, seed=9)
+    old, new = inputs.bits(base), inputs.bits(inputs.synthetic_update(base, seed=10))
+    table = O.quantise(O.histogram(old), guard=8)
+    blob = O.compress(new, 7, guard=8, freq=table, threads=4)
+    info = O.blob_info(blob)
+    CE = O.cross_entropy(O.histogram(new), table)
+    n_states = (n // 4096) * 16
+    coded_bits = 16 * info["total_words"] + 32 * n_states
+    assert n * CE + 16 * n_states - 0.002 * n <= coded_bits <= n * CE + 32 * n_states + 0.002 * n
+    # a small update barely moves the exponent distribution: under 0.01 bit per weight lost
+    fresh = O.compress(new, 7, threads=4)
+    assert 0 <= 8 * (blob.size - fresh.size) / n < 0.01
