@@ -116,6 +116,33 @@ int neuzip_compress_batch(const void *const *d_srcs, const uint64_t *n_elems, ui
                           int mantissa_bits, uint32_t block_size, void *hip_stream, neuzip_blob **blobs);
 
 /*
+ * neuzip_compress_guarded / neuzip_recompress -- Alg. 1 backward loop: every weight is compressed
+ * again right after its update ("compression", "store"), i.e. once per tensor per training step.
+ * The exponent statistics hardly move from one step to the next, so the table of the step before
+ * can code the updated tensor, and the pass that counts exponents (one of the two reads of the
+ * tensor) can be left out.  Not described in the paper; the reading taken here:
+ *
+ *   neuzip_compress_guarded   as neuzip_compress_batch without normalisation, but the table gives
+ *       f = 1 to every exponent up to `guard` (0..255) below the smallest and above the largest
+ *       one that occurs, so that values an update newly produces still have a code.  guard = 0 is
+ *       the plain table.  The guard is kept in the blob and in header word 52 of the container.
+ *   neuzip_recompress         blobs[i] (which must hold a compressed tensor) receives d_srcs[i],
+ *       a tensor of neuzip_elems(blobs[i]) words, coded with the table the blob already holds:
+ *       one pass over the source that splits, packs and encodes.  If a tensor holds an exponent
+ *       its table has no room for, that tensor is compressed afresh (statistics, new table with
+ *       the blob's guard) and rebuilt[i] is set to 1, else 0 (rebuilt may be NULL).  Block-wise
+ *       normalised blobs always take the second route.  After a table has been reused
+ *       neuzip_histogram reports EINVAL for the blob (no counts were taken).
+ *   Both work on host arrays of count entries like neuzip_compress_batch and synchronise the
+ *   stream once per group of up to 8 tensors.  A caller that wants a fresh table every N steps
+ *   calls neuzip_compress_guarded then.
+ */
+int neuzip_compress_guarded(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int dtype,
+                            int mantissa_bits, uint32_t guard, void *hip_stream, neuzip_blob **blobs);
+int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_stream, neuzip_blob *const *blobs,
+                      uint32_t *rebuilt);
+
+/*
  * neuzip_decompress -- Sec. 2.2 Eq. (3), Alg. 1 "decompression" + "merge":
  * decodes the exponents and reassembles bf16 words into the caller's
  * temporary space in one fused kernel.
@@ -172,9 +199,11 @@ uint64_t neuzip_compressed_bytes(const neuzip_blob *blob);
  * alignment padding and the derived cumulative and slot tables). */
 uint64_t neuzip_device_bytes(const neuzip_blob *blob);
 
-/* Element count, mantissa bits and normalisation block size (0 = none) the blob was made with. */
+/* Element count, mantissa bits, normalisation block size (0 = none) and guard band of the table
+ * (0 = none) the blob was made with. */
 uint64_t neuzip_elems(const neuzip_blob *blob);
 uint32_t neuzip_block_size(const neuzip_blob *blob);
+uint32_t neuzip_guard(const neuzip_blob *blob);
 int neuzip_mantissa_bits(const neuzip_blob *blob);
 
 /*

@@ -37,8 +37,14 @@ def _load():
     lib.neuzip_compress_blockwise.restype = i32
     lib.neuzip_compress_batch.argtypes = [vpp, ctypes.POINTER(u64), u32, i32, i32, u32, vp, vpp]
     lib.neuzip_compress_batch.restype = i32
+    lib.neuzip_compress_guarded.argtypes = [vpp, ctypes.POINTER(u64), u32, i32, i32, u32, vp, vpp]
+    lib.neuzip_compress_guarded.restype = i32
+    lib.neuzip_recompress.argtypes = [vpp, u32, vp, vpp, ctypes.POINTER(u32)]
+    lib.neuzip_recompress.restype = i32
     lib.neuzip_block_size.argtypes = [vp]
     lib.neuzip_block_size.restype = u32
+    lib.neuzip_guard.argtypes = [vp]
+    lib.neuzip_guard.restype = u32
     lib.neuzip_decompress.argtypes = [vp, vp, u64, i32, vp]
     lib.neuzip_decompress.restype = i32
     lib.neuzip_decompress_sequence.argtypes = [vpp, u32, vp, u64, vp]
@@ -77,7 +83,8 @@ def _load():
 _lib = None
 _lib = _load()
 
-EXPORTED = ["neuzip_compress", "neuzip_compress_blockwise", "neuzip_compress_batch", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
+EXPORTED = ["neuzip_compress", "neuzip_compress_blockwise", "neuzip_compress_batch", "neuzip_compress_guarded",
+            "neuzip_recompress", "neuzip_guard", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
             "neuzip_free",
             "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits",
             "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check",
@@ -136,6 +143,10 @@ class Blob:
     def block_size(self):
         return int(_lib.neuzip_block_size(self.handle))
 
+    @property
+    def guard(self):
+        return int(_lib.neuzip_guard(self.handle))
+
 
 def neuzip_compress(src: torch.Tensor, mantissa_bits: int = 7, stream=None, blob: Blob = None) -> Blob:
     return neuzip_compress_blockwise(src, mantissa_bits, 0, stream, blob)
@@ -155,7 +166,28 @@ def neuzip_compress_blockwise(src: torch.Tensor, mantissa_bits: int, block_size:
     return Blob(handle.value)
 
 
-def neuzip_compress_batch(srcs, mantissa_bits: int = 7, block_size: int = 0, stream=None, blobs=None):
+def neuzip_compress_guarded(srcs, mantissa_bits: int = 7, guard: int = 0, stream=None, blobs=None):
+    """neuzip_compress_batch with a guard band in the table (for blobs that will be recompressed)."""
+    return neuzip_compress_batch(srcs, mantissa_bits, 0, stream, blobs, guard=guard)
+
+
+def neuzip_recompress(srcs, blobs, stream=None):
+    """Codes srcs[i] into blobs[i] with the table the blob holds; returns the list of rebuilt flags."""
+    for t in srcs:
+        _check_tensor(t)
+    if len(blobs) != len(srcs) or any(b.elems != t.numel() for b, t in zip(blobs, srcs)):
+        raise ValueError("one blob of matching size per tensor")
+    count = len(srcs)
+    ptrs = (ctypes.c_void_p * count)(*[t.data_ptr() for t in srcs])
+    handles = (ctypes.c_void_p * count)(*[b.handle.value for b in blobs])
+    rebuilt = (ctypes.c_uint32 * count)()
+    rc = _lib.neuzip_recompress(ptrs, count, _stream_handle(stream), handles, rebuilt)
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_recompress")
+    return [int(v) for v in rebuilt]
+
+
+def neuzip_compress_batch(srcs, mantissa_bits: int = 7, block_size: int = 0, stream=None, blobs=None, guard=None):
     """Compresses several tensors with one pass of the pipeline; returns one Blob per tensor."""
     for t in srcs:
         _check_tensor(t)
@@ -166,8 +198,12 @@ def neuzip_compress_batch(srcs, mantissa_bits: int = 7, block_size: int = 0, str
     sizes = (ctypes.c_uint64 * count)(*[t.numel() for t in srcs])
     handles = (ctypes.c_void_p * count)(*[(b.handle.value if b is not None else None)
                                           for b in (blobs if blobs is not None else [None] * count)])
-    rc = _lib.neuzip_compress_batch(ptrs, sizes, count, BF16, mantissa_bits, block_size, _stream_handle(stream),
-                                    handles)
+    if guard is None:
+        rc = _lib.neuzip_compress_batch(ptrs, sizes, count, BF16, mantissa_bits, block_size, _stream_handle(stream),
+                                        handles)
+    else:
+        rc = _lib.neuzip_compress_guarded(ptrs, sizes, count, BF16, mantissa_bits, guard, _stream_handle(stream),
+                                          handles)
     if rc != OK:
         raise NeuzipError(rc, "neuzip_compress_batch")
     out = []

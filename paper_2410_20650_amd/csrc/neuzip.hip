@@ -108,6 +108,8 @@ struct neuzip_blob {
     uint64_t n;
     int k;
     uint32_t block;  // block size of the block-wise normalisation, 0 = none
+    uint32_t guard;  // guard band of the frequency table, 0 = none
+    bool has_table;  // holds a compressed tensor (and so a table that recompression can reuse)
     uint32_t n_chunks;
     uint64_t total_words;
     uint8_t *fixed;
@@ -139,6 +141,7 @@ struct Workspace {
     EncSym *enc = nullptr;            // kBatchMax x 256
     uint32_t *counts = nullptr;       // kBatchMax x 256 histogram bins, zero between compress calls
     uint32_t *done = nullptr;         // offsets-kernel workgroups that have finished (rearmed by the last)
+    uint32_t *stale = nullptr;        // per tensor of the batch: recompression met an exponent without room
     uint32_t *chunk_words = nullptr;  // words per chunk
     uint32_t *group_words = nullptr;  // words per encoder workgroup (16 chunks), input of the scan
     uint64_t *group_prefix = nullptr; // its exclusive prefix sum, per tensor
@@ -207,6 +210,7 @@ int ensure_workspace(int device, uint64_t n_groups, hipStream_t stream)
         NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.enc), kBatchMax * 256 * sizeof(EncSym)));
         NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.counts), (kBatchMax * 256 + 64) * sizeof(uint32_t)));
         g_ws.done = g_ws.counts + kBatchMax * 256;  // shares the allocation; cleared with the bins below
+        g_ws.stale = g_ws.done + 8;
         NZ_HIP(hipHostMalloc(reinterpret_cast<void **>(&g_ws.pinned), sizeof(HostRecord), hipHostMallocDefault));
         std::memset(g_ws.pinned, 0, sizeof(HostRecord));
         g_ws.seq = 0;
@@ -273,16 +277,22 @@ int reserve_words(neuzip_blob *b, uint64_t total_words)
     // and a state fed a damaged stream may walk up to 256 words past the start of its run
     const uint64_t need = pad_to(total_words * 2, 256) + 1024;
     if (b->words_bytes < need) {
+        // A blob that receives a new version of its tensor after every update grows and shrinks
+        // by a little each time: once an allocation has had to be replaced, the new one gets
+        // 1/64 of headroom, so that this does not mean a new allocation per call.  The first
+        // allocation of a blob is exact.
+        const bool regrown = b->words != nullptr;
         if (b->words) {
             NZ_HIP(hipFree(b->words));
             b->words = nullptr;
             b->words_bytes = 0;
         }
-        if (hipMalloc(reinterpret_cast<void **>(&b->words), need) != hipSuccess) {
+        const uint64_t roomy = regrown ? pad_to(need + need / 64, 256) : need;
+        if (hipMalloc(reinterpret_cast<void **>(&b->words), roomy) != hipSuccess) {
             (void)hipGetLastError();
             return NEUZIP_ENOMEM;
         }
-        b->words_bytes = need;
+        b->words_bytes = roomy;
     }
     return NEUZIP_OK;
 }
@@ -383,6 +393,7 @@ int compress_empty(neuzip_blob *b, hipStream_t stream)
     std::memset(b->h_freq, 0, sizeof(b->h_freq));
     b->have_counts = true;
     b->total_words = 0;
+    b->has_table = true;
     return NEUZIP_OK;
 }
 
@@ -396,9 +407,22 @@ void launch_hist(const CompressBatch &batch, bool norm, uint32_t groups, hipStre
         hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch, g_ws.counts);
 }
 
+constexpr uint32_t kKeepGuard = 0xFFFFFFFFu;  // compress_some: every blob keeps the guard band it has
+
+template <int KB>
+void launch_encode_reuse(const CompressBatch &batch, uint32_t groups, hipStream_t stream)
+{
+    hipLaunchKernelGGL((encode_kernel<false, KB>), dim3(groups), dim3(kEncThreads), 0, stream, batch, g_ws.enc,
+                       g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned, g_ws.stale);
+}
+
 // Compresses up to kBatchMax tensors (arguments already validated) with one pass of the pipeline.
+// reuse = false: statistics are taken from the tensors and new tables are built (with the given
+// guard band).  reuse = true: every blob holds a table already and the tensors are coded with
+// those, in one pass over the source; rebuilt[i] is set for the tensors whose table turned out
+// not to cover them, which are then compressed the first way.
 int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int k, uint32_t block,
-                  hipStream_t stream, neuzip_blob **blobs)
+                  uint32_t guard, bool reuse, uint32_t *rebuilt, hipStream_t stream, neuzip_blob **blobs)
 {
     neuzip_blob *work[kBatchMax];
     bool fresh[kBatchMax];
@@ -424,20 +448,31 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             fresh[i] = true;
         }
         work[i]->have_counts = false;
-        work[i]->total_words = 0;
+        if (!reuse) {
+            work[i]->total_words = 0;
+            work[i]->has_table = false;
+            if (guard != kKeepGuard)
+                work[i]->guard = guard;
+        }
     }
 
     // the batch proper: tensors that have elements
     CompressBatch batch;
     std::memset(&batch, 0, sizeof(batch));
     uint32_t owner[kBatchMax];
+    const void *stale_src[kBatchMax];
+    uint64_t stale_n[kBatchMax];
+    neuzip_blob *stale_blob[kBatchMax];
+    uint32_t stale_owner[kBatchMax];
+    uint32_t stale_count = 0;
     uint32_t hist_groups = 0, enc_groups = 0, compact_groups = 0;
     for (uint32_t i = 0; i < count; ++i) {
         neuzip_blob *b = work[i];
         if (b->n == 0) {
-            const int rc = compress_empty(b, stream);
+            const int rc = reuse ? NEUZIP_OK : compress_empty(b, stream);
             if (rc != NEUZIP_OK)
                 return fail(rc);
+            b->have_counts = true;
             continue;
         }
         CompressItem &it = batch.it[batch.count];
@@ -453,6 +488,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         it.words = nullptr;
         it.n_chunks = b->n_chunks;
         it.block = block;
+        it.guard = b->guard;
         it.group_base = enc_groups;
         // every workgroup of the histogram pass pays for clearing and merging its 32 KB of bins: give
         // it at least 8 vectors (64 elements) per thread, and no tensor more workgroups than fit the chip
@@ -466,33 +502,48 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         it.compact_end = compact_groups;
     }
     if (batch.count > 0) {
-        std::lock_guard<std::mutex> guard(g_ws_mutex);
+        std::lock_guard<std::mutex> lock(g_ws_mutex);
         int rc = ensure_workspace(work[owner[0]]->device, enc_groups, stream);
         if (rc != NEUZIP_OK)
             return fail(rc);
         batch.seq = ++g_ws.seq;
 
-        switch (k) {
-        case 7: launch_hist<7>(batch, block != 0, hist_groups, stream); break;
-        case 3: launch_hist<3>(batch, block != 0, hist_groups, stream); break;
-        case 1: launch_hist<1>(batch, block != 0, hist_groups, stream); break;
-        default: launch_hist<0>(batch, block != 0, hist_groups, stream); break;
+        if (reuse) {
+            // one pass: encoder constants from the stored tables, then split + encode together
+            hipLaunchKernelGGL(table_reuse_kernel, dim3(batch.count), dim3(256), 0, stream, batch, g_ws.enc,
+                               g_ws.stale);
+            switch (k) {
+            case 7: launch_encode_reuse<7>(batch, enc_groups, stream); break;
+            case 3: launch_encode_reuse<3>(batch, enc_groups, stream); break;
+            case 1: launch_encode_reuse<1>(batch, enc_groups, stream); break;
+            default: launch_encode_reuse<0>(batch, enc_groups, stream); break;
+            }
+        } else {
+            switch (k) {
+            case 7: launch_hist<7>(batch, block != 0, hist_groups, stream); break;
+            case 3: launch_hist<3>(batch, block != 0, hist_groups, stream); break;
+            case 1: launch_hist<1>(batch, block != 0, hist_groups, stream); break;
+            default: launch_hist<0>(batch, block != 0, hist_groups, stream); break;
+            }
+            if (!hip_ok(hipGetLastError()))
+                return fail(NEUZIP_EHIP);
+            bins_dirty = true;
+            // the table kernel also returns the workspace histogram bins to zero
+            hipLaunchKernelGGL(table_kernel, dim3(batch.count), dim3(256), 0, stream, batch, g_ws.counts, g_ws.enc);
+            if (hip_ok(hipGetLastError()))
+                bins_dirty = false;
+            if (block)
+                hipLaunchKernelGGL((encode_kernel<true, -1>), dim3(enc_groups), dim3(kEncThreads), 0, stream, batch,
+                                   g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned,
+                                   static_cast<uint32_t *>(nullptr));
+            else
+                hipLaunchKernelGGL((encode_kernel<false, -1>), dim3(enc_groups), dim3(kEncThreads), 0, stream, batch,
+                                   g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned,
+                                   static_cast<uint32_t *>(nullptr));
         }
-        if (!hip_ok(hipGetLastError()))
-            return fail(NEUZIP_EHIP);
-        bins_dirty = true;
-        // the table kernel also returns the workspace histogram bins to zero
-        hipLaunchKernelGGL(table_kernel, dim3(batch.count), dim3(256), 0, stream, batch, g_ws.counts, g_ws.enc);
-        if (hip_ok(hipGetLastError()))
-            bins_dirty = false;
-        if (block)
-            hipLaunchKernelGGL(encode_kernel<true>, dim3(enc_groups), dim3(kEncThreads), 0, stream, batch, g_ws.enc,
-                               g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned);
-        else
-            hipLaunchKernelGGL(encode_kernel<false>, dim3(enc_groups), dim3(kEncThreads), 0, stream, batch, g_ws.enc,
-                               g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned);
         hipLaunchKernelGGL(offsets_kernel, dim3(batch.count), dim3(kScanThreads), 0, stream, batch, g_ws.group_words,
-                           g_ws.group_prefix, g_ws.done, g_ws.pinned);
+                           g_ws.group_prefix, g_ws.done, g_ws.pinned,
+                           reuse ? static_cast<const uint32_t *>(g_ws.stale) : static_cast<const uint32_t *>(nullptr));
         if (!hip_ok(hipGetLastError()))
             return fail(NEUZIP_EHIP);
 
@@ -500,29 +551,58 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         // kernels write straight into pinned host memory, the stamp last
         if (!wait_for_record(batch.seq, stream))
             return fail(NEUZIP_EHIP);
+        uint32_t n_stale = 0;
         for (uint32_t j = 0; j < batch.count; ++j) {
             const HostRecord::Item &r = g_ws.pinned->item[j];
             neuzip_blob *b = work[owner[j]];
+            if (reuse && r.stale) {
+                // its table does not cover the new values: nothing of this pass is kept (the
+                // compaction skips a tensor without chunks); it is compressed afresh below
+                stale_src[n_stale] = d_srcs[owner[j]];
+                stale_n[n_stale] = n_elems[owner[j]];
+                stale_blob[n_stale] = b;
+                stale_owner[n_stale++] = owner[j];
+                b->has_table = false;
+                batch.it[j].n_chunks = 0;
+                continue;
+            }
             if (r.total_words[1] != 0)
                 return fail(NEUZIP_EUNSUPPORTED);  // more than 2^32 words
             rc = reserve_words(b, r.total_words[0]);
             if (rc != NEUZIP_OK)
                 return fail(rc);
             b->total_words = r.total_words[0];
-            std::memcpy(b->h_counts, r.counts, 1024);
-            std::memcpy(b->h_freq, r.freq, 512);
-            b->have_counts = true;
+            if (!reuse) {
+                std::memcpy(b->h_counts, r.counts, 1024);
+                std::memcpy(b->h_freq, r.freq, 512);
+                b->have_counts = true;
+            }
+            b->has_table = true;
             batch.it[j].words = reinterpret_cast<uint16_t *>(b->words);
         }
         hipLaunchKernelGGL(compact_kernel, dim3(compact_groups), dim3(kCompactThreads), 0, stream, batch, g_ws.slots,
                            g_ws.chunk_words, g_ws.group_prefix);
         if (!hip_ok(hipGetLastError()) || !hip_ok(hipEventRecord(g_ws.idle, stream)))
             return fail(NEUZIP_EHIP);
+        stale_count = n_stale;
+    }
+    if (stale_count > 0) {
+        // same stream, so the pass above has finished with the workspace before this one starts
+        const int rc = compress_some(stale_src, stale_n, stale_count, k, block, kKeepGuard, false, nullptr, stream,
+                                     stale_blob);
+        if (rc != NEUZIP_OK)
+            return rc;
+        for (uint32_t j = 0; j < stale_count; ++j)
+            if (rebuilt)
+                rebuilt[stale_owner[j]] = 1;
     }
     for (uint32_t i = 0; i < count; ++i)
         blobs[i] = work[i];
     return NEUZIP_OK;
 }
+
+int compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int dtype, int mantissa_bits,
+                   uint32_t block_size, uint32_t guard, void *hip_stream, neuzip_blob **blobs);
 
 }  // namespace
 
@@ -546,6 +626,75 @@ int neuzip_compress_blockwise(const void *d_src, uint64_t n_elems, int dtype, in
 int neuzip_compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int dtype,
                           int mantissa_bits, uint32_t block_size, void *hip_stream, neuzip_blob **blobs)
 {
+    return compress_batch(d_srcs, n_elems, count, dtype, mantissa_bits, block_size, 0, hip_stream, blobs);
+}
+
+int neuzip_compress_guarded(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int dtype,
+                            int mantissa_bits, uint32_t guard, void *hip_stream, neuzip_blob **blobs)
+{
+    if (guard > 255)
+        return NEUZIP_EINVAL;
+    return compress_batch(d_srcs, n_elems, count, dtype, mantissa_bits, 0, guard, hip_stream, blobs);
+}
+
+int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_stream, neuzip_blob *const *blobs,
+                      uint32_t *rebuilt)
+{
+    if (count == 0)
+        return NEUZIP_OK;
+    if (!d_srcs || !blobs)
+        return NEUZIP_EINVAL;
+    for (uint32_t i = 0; i < count; ++i) {
+        const neuzip_blob *b = blobs[i];
+        if (!is_blob(b) || !b->has_table)
+            return NEUZIP_EINVAL;
+        if (b->n > 0 && (!d_srcs[i] || (reinterpret_cast<uintptr_t>(d_srcs[i]) & 15u)))
+            return NEUZIP_EINVAL;
+        for (uint32_t j = 0; j < i; ++j)
+            if (blobs[j] == b)
+                return NEUZIP_EINVAL;
+    }
+    if (rebuilt)
+        for (uint32_t i = 0; i < count; ++i)
+            rebuilt[i] = 0;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // neighbouring tensors of the same kind share a pass, up to kBatchMax at a time; block-wise
+    // normalised blobs need the block maxima first and always take the two-pass route
+    uint32_t first = 0;
+    while (first < count) {
+        const neuzip_blob *lead = blobs[first];
+        uint32_t m = 1;
+        while (first + m < count && m < kBatchMax && blobs[first + m]->k == lead->k &&
+               blobs[first + m]->block == lead->block)
+            ++m;
+        uint64_t n_elems[kBatchMax];
+        neuzip_blob *group[kBatchMax];
+        for (uint32_t j = 0; j < m; ++j) {
+            n_elems[j] = blobs[first + j]->n;
+            group[j] = blobs[first + j];
+        }
+        const bool reuse = lead->block == 0;
+        const int rc = compress_some(d_srcs + first, n_elems, m, lead->k, lead->block, kKeepGuard, reuse,
+                                     rebuilt ? rebuilt + first : nullptr, stream, group);
+        if (rc != NEUZIP_OK)
+            return rc;
+        if (!reuse && rebuilt)
+            for (uint32_t j = 0; j < m; ++j)
+                rebuilt[first + j] = 1;
+        first += m;
+    }
+    return NEUZIP_OK;
+}
+
+uint32_t neuzip_guard(const neuzip_blob *blob) { return is_blob(blob) ? blob->guard : 0; }
+
+}  // extern "C"
+
+namespace {
+
+int compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int dtype, int mantissa_bits,
+                   uint32_t block_size, uint32_t guard, void *hip_stream, neuzip_blob **blobs)
+{
     if (count == 0)
         return NEUZIP_OK;
     if (!d_srcs || !n_elems || !blobs || dtype != NEUZIP_BF16 || !valid_k(mantissa_bits))
@@ -567,13 +716,17 @@ int neuzip_compress_batch(const void *const *d_srcs, const uint64_t *n_elems, ui
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     for (uint32_t first = 0; first < count; first += kBatchMax) {
         const uint32_t m = count - first < kBatchMax ? count - first : kBatchMax;
-        const int rc = compress_some(d_srcs + first, n_elems + first, m, mantissa_bits, block_size, stream,
-                                     blobs + first);
+        const int rc = compress_some(d_srcs + first, n_elems + first, m, mantissa_bits, block_size, guard, false,
+                                     nullptr, stream, blobs + first);
         if (rc != NEUZIP_OK)
             return rc;
     }
     return NEUZIP_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 int neuzip_decompress(const neuzip_blob *blob, void *d_dst, uint64_t n_elems, int dtype, void *hip_stream)
 {
@@ -656,13 +809,13 @@ void neuzip_free(neuzip_blob *blob)
     int cur = 0;
     const bool have_cur = hipGetDevice(&cur) == hipSuccess;
     if (have_cur && cur != blob->device)
-        hipSetDevice(blob->device);
+        (void)hipSetDevice(blob->device);
     if (blob->fixed)
-        hipFree(blob->fixed);
+        (void)hipFree(blob->fixed);
     if (blob->words)
-        hipFree(blob->words);
+        (void)hipFree(blob->words);
     if (have_cur && cur != blob->device)
-        hipSetDevice(cur);
+        (void)hipSetDevice(cur);
     blob->magic = 0;
     delete blob;
 }
@@ -712,6 +865,7 @@ int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *
     put32(36, blob->n_chunks);
     put64(40, blob->total_words);
     put32(48, blob->block);
+    put32(52, blob->guard);
     const uint64_t nc = blob->n_chunks;
     NZ_HIP(hipMemcpyAsync(p + lay.freq, table_of(blob)->freq, 512, hipMemcpyDeviceToHost, stream));
     NZ_HIP(hipMemcpyAsync(p + lay.offsets, offsets_of(blob), (nc + 1) * 4, hipMemcpyDeviceToHost, stream));
@@ -750,6 +904,9 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
     if (!valid_k(k) || n >= (1ull << 32) || total_words >= (1ull << 32))
         return NEUZIP_ECORRUPT;
     if (block != 0 && (!valid_block(block) || k == 7))
+        return NEUZIP_ECORRUPT;
+    const uint32_t guard = get32(52);
+    if (guard > 255 || (guard != 0 && block != 0))
         return NEUZIP_ECORRUPT;
     const uint32_t nc = chunks_of(n);
     if (get32(36) != nc)
@@ -798,6 +955,7 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
     if (rc != NEUZIP_OK)
         return fail(rc);
     b->total_words = total_words;
+    b->guard = guard;
     std::memcpy(b->h_freq, freq, 512);
     b->have_counts = false;
 
@@ -834,6 +992,7 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
     }
     if (!hip_ok(hipStreamSynchronize(stream)))  // tb and zeros must outlive the copies
         return fail(NEUZIP_EHIP);
+    b->has_table = true;
     *blob = b;
     return NEUZIP_OK;
 }

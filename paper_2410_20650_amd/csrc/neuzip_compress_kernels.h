@@ -26,6 +26,32 @@ __device__ inline uint32_t signmant_field(uint32_t u)
     return ((u >> 15) << KB) | ((u & 0x7Fu) >> (7 - KB));
 }
 
+// The fields of 8 neighbouring bf16 words (four dwords), packed low element first.  For the
+// lossless width a field is the word's low byte with its top bit replaced by the sign: two byte
+// permutes gather the low and the high bytes of four words, one bit-select joins them.
+template <int KB>
+__device__ __forceinline__ uint64_t pack_fields(const uint32_t (&w)[4])
+{
+    if constexpr (KB == 7) {
+        uint32_t out[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t low = __builtin_amdgcn_perm(w[2 * h + 1], w[2 * h], 0x06040200u);
+            const uint32_t high = __builtin_amdgcn_perm(w[2 * h + 1], w[2 * h], 0x07050301u);
+            out[h] = (low & 0x7F7F7F7Fu) | (high & 0x80808080u);
+        }
+        return static_cast<uint64_t>(out[0]) | (static_cast<uint64_t>(out[1]) << 32);
+    } else {
+        uint64_t packed = 0;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            packed |= static_cast<uint64_t>(signmant_field<KB>(w[p] & 0xFFFFu)) << ((2 * p) * (KB + 1));
+            packed |= static_cast<uint64_t>(signmant_field<KB>(w[p] >> 16)) << ((2 * p + 1) * (KB + 1));
+        }
+        return packed;
+    }
+}
+
 template <int KB>
 __device__ inline void store_fields(uint8_t *sm, uint64_t vec, uint64_t packed)
 {
@@ -131,16 +157,13 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const Compress
             if (v >= n_vec)
                 break;
             const uint32_t w[4] = {d[r].x, d[r].y, d[r].z, d[r].w};
-            uint64_t packed = 0;
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const uint32_t lo = w[p] & 0xFFFFu, hi = w[p] >> 16;
                 atomicAdd(&bins[exponent_of(lo) * kHistCopies + copy], 1u);
                 atomicAdd(&bins[exponent_of(hi) * kHistCopies + copy], 1u);
-                packed |= static_cast<uint64_t>(signmant_field<KB>(lo)) << ((2 * p) * (KB + 1));
-                packed |= static_cast<uint64_t>(signmant_field<KB>(hi)) << ((2 * p + 1) * (KB + 1));
             }
-            store_fields<KB>(sm, v, packed);
+            store_fields<KB>(sm, v, pack_fields<KB>(w));
         }
     }
     // ragged tail (n mod 8 elements): one thread, element by element
@@ -299,6 +322,20 @@ __device__ inline uint64_t block_sum_u64(uint64_t v, uint64_t *scratch)
     return scratch[0] + scratch[1] + scratch[2] + scratch[3];
 }
 
+// Encoder constants of a symbol.  A symbol without room in the table (f = 0) gets constants that
+// leave the state as it is and a zero reciprocal, by which the encoder recognises it.
+__device__ inline EncSym encoder_constants(uint32_t f, uint32_t cum)
+{
+    EncSym e = {0.0f, 0xFFFFFFFFu, 0u, 1u};
+    if (f > 0) {
+        e.rcp = __fmul_rn(__fdiv_rn(1.0f, static_cast<float>(f)), 1.0f - 0x1p-21f);
+        e.limit = f >= kM ? 0xFFFFFFFFu : (f << 20);  // f = 4096 only for a one-symbol tensor: never renormalises
+        e.cmpl_cum = (kM - f) | (cum << 16);
+        e.f = f;
+    }
+    return e;
+}
+
 __global__ __launch_bounds__(256) void table_kernel(const CompressBatch b, uint32_t *__restrict__ counts_all,
                                                     EncSym *__restrict__ enc_all)
 {
@@ -319,7 +356,17 @@ __global__ __launch_bounds__(256) void table_kernel(const CompressBatch b, uint3
     const uint64_t total = block_sum_u64(cnt, scratch);
     uint32_t f = 0;
     if (total > 0) {
-        if (cnt > 0) {
+        // With a guard band every exponent from (lowest occurring - guard) to (highest occurring +
+        // guard) is treated as occurring: it gets f = 1 and can be coded after a weight update
+        // without a new table.
+        bool member = cnt > 0;
+        const uint32_t guard = b.it[blockIdx.x].guard;
+        if (guard > 0) {
+            const uint32_t hi = static_cast<uint32_t>(block_max_u64(cnt > 0 ? s + 1 : 0, scratch)) - 1;
+            const uint32_t lo = 256 - static_cast<uint32_t>(block_max_u64(cnt > 0 ? 256 - s : 0, scratch));
+            member = s + guard >= lo && s <= hi + guard;
+        }
+        if (member) {
             const uint64_t scaled = cnt * kM / total;
             f = scaled < 1 ? 1u : static_cast<uint32_t>(scaled);
         }
@@ -382,14 +429,7 @@ __global__ __launch_bounds__(256) void table_kernel(const CompressBatch b, uint3
         tb->lone = s;
 
     // encoder constants first: the encode kernel waits for them, the decoder table is not urgent
-    EncSym e = {0.0f, 0xFFFFFFFFu, 0u, 1u};
-    if (f > 0) {
-        e.rcp = __fmul_rn(__fdiv_rn(1.0f, static_cast<float>(f)), 1.0f - 0x1p-21f);
-        e.limit = f >= kM ? 0xFFFFFFFFu : (f << 20);  // f = 4096 only for a one-symbol tensor: never renormalises
-        e.cmpl_cum = (kM - f) | (cum << 16);
-        e.f = f;
-    }
-    enc[s] = e;
+    enc[s] = encoder_constants(f, cum);
 
     // decoder slot table: thread s fills slots s, s + 256, ...; scan[t] = cum[t + 1].  The 16
     // binary searches of a thread are independent, so their LDS reads overlap.
@@ -421,13 +461,27 @@ __global__ __launch_bounds__(256) void table_kernel(const CompressBatch b, uint3
 }
 
 // ------------------------------------------------------------------------------------------
+// Kernel 2b: recompression with the table a blob already holds (Alg. 1 compresses every weight
+// again after its update; the exponent statistics barely move from one step to the next).  Only
+// the encoder constants are rebuilt, from the stored frequencies; the stale flags are cleared.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void table_reuse_kernel(const CompressBatch b, EncSym *__restrict__ enc_all,
+                                                          uint32_t *__restrict__ stale)
+{
+    const TableBlock *__restrict__ tb = b.it[blockIdx.x].tb;
+    const uint32_t s = threadIdx.x;
+    enc_all[256 * blockIdx.x + s] = encoder_constants(tb->freq[s], tb->cum[s]);
+    if (s == 0)
+        stale[blockIdx.x] = 0;
+}
+
+// ------------------------------------------------------------------------------------------
 // Kernel 3: chunked rANS encoder (Sec. 2.2 "Compression algorithm").  One lane per state.
 // A state visits its symbols back to front; the words it pushes out are collected, back to
 // front, in a 16-word LDS ring and leave for the state's own 200-word slot of the workspace in
 // 16-byte pieces, so that the tail of the slot read forwards is the decoder's order.  Final
 // states and run lengths go straight to their place in the blob; the chunk's word count goes to
-// the workspace for the offsets scan.  The next turn's 8 bf16 words are requested before the
-// current turn is coded.
+// the workspace for the offsets scan.  A turn's 8 bf16 words are requested two turns ahead.
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kEncThreads = 256;
 constexpr uint32_t kChunksPerGroup = kEncThreads / kStates;  // 16 chunks per encoder workgroup
@@ -464,14 +518,22 @@ __device__ __forceinline__ void ring_flush(uint32_t wp_before, uint32_t wp_after
     }
 }
 
-template <bool NORM>
+// SPLIT >= 0: the one-pass variant used for recompression with an existing table.  There is no
+// histogram pass to produce the sign|mantissa stream, so this kernel packs and stores the fields
+// (SPLIT = mantissa bits) of the words it codes, and it reports, through stale[item], any exponent
+// that the table has no room for (such symbols leave the state unchanged; the host then falls
+// back to a compression with fresh statistics).
+template <bool NORM, int SPLIT>
 __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch b,
                                                             const EncSym *__restrict__ enc_all,
                                                             uint32_t *__restrict__ chunk_words_all,
                                                             uint32_t *__restrict__ group_words_all,
                                                             uint16_t *__restrict__ slots_all,
-                                                            HostRecord *__restrict__ record)
+                                                            HostRecord *__restrict__ record,
+                                                            uint32_t *__restrict__ stale)
 {
+    static_assert(!(NORM && SPLIT >= 0), "the one-pass variant has no block maxima to normalise with");
+    constexpr int KB = SPLIT >= 0 ? SPLIT : 7;
     const ItemSlot slot_id = item_of_workgroup<&CompressItem::enc_end>(b);
     const CompressItem &it = b.it[slot_id.item];
     const uint16_t *__restrict__ src = it.src;
@@ -492,7 +554,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     __shared__ __align__(16) uint16_t rings[kEncThreads * kRingWords];
     __shared__ uint32_t group_chunk[kEncThreads / kStates];
     enc_raw[threadIdx.x] = reinterpret_cast<const uint4 *>(enc_g)[threadIdx.x];
-    if (slot_id.wg == 0) {
+    if (SPLIT < 0 && slot_id.wg == 0) {
         // statistics for the host: posted early, they land long before this kernel ends
         record->item[slot_id.item].counts[threadIdx.x] = tb->counts[threadIdx.x];
         record->item[slot_id.item].freq[threadIdx.x] = tb->freq[threadIdx.x];
@@ -508,14 +570,21 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     uint16_t *slot = slots + static_cast<uint64_t>(lane_id) * kRunCap;
     uint16_t *ring = rings + threadIdx.x * kRingWords;
     EncState st = {kRansL, kRunCap};
+    float least_rcp = 1.0f;  // 0 once a symbol without room in the table has been met
+    uint8_t *__restrict__ sm = it.sm;
 
     if (m == kChunk) {
         const uint4 *src4 = reinterpret_cast<const uint4 *>(src + base) + j;
+        // the source words are requested two turns ahead: the wait for a turn's words then leaves
+        // the stores of the turn before (ring flush, fields) in flight instead of waiting for them
         uint4 d = src4[(kTurns - 1) * kStates];
+        uint4 d_next = src4[(kTurns - 2) * kStates];
         for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
-            const uint4 d_next = src4[(q > 0 ? q - 1 : 0) * kStates];
+            const uint4 d_after = src4[(q > 1 ? q - 2 : 0) * kStates];
             const uint32_t w[4] = {d.x, d.y, d.z, d.w};
             const uint32_t wp_before = st.wp;
+            if constexpr (SPLIT >= 0)
+                store_fields<KB>(sm, base / 8 + static_cast<uint32_t>(q) * kStates + j, pack_fields<KB>(w));
             // with block-wise normalisation the exponents coded are those of bf16(w / c)
             float c = 1.0f;
             if constexpr (NORM)
@@ -524,26 +593,48 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
             for (int p = 3; p >= 0; --p) {
                 const uint32_t hi = NORM ? normalise_word(w[p] >> 16, c) : (w[p] >> 16);
                 const uint32_t lo = NORM ? normalise_word(w[p] & 0xFFFFu, c) : (w[p] & 0xFFFFu);
-                rans_put(st, enc[exponent_of(hi)], ring);
-                rans_put(st, enc[exponent_of(lo)], ring);
+                const EncSym e_hi = enc[exponent_of(hi)], e_lo = enc[exponent_of(lo)];
+                if constexpr (SPLIT >= 0)
+                    least_rcp = fminf(least_rcp, fminf(e_hi.rcp, e_lo.rcp));
+                rans_put(st, e_hi, ring);
+                rans_put(st, e_lo, ring);
             }
             ring_flush(wp_before, st.wp, ring, slot);
             d = d_next;
+            d_next = d_after;
         }
     } else if (m > 0) {
         for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
             const uint32_t wp_before = st.wp;
+            uint64_t packed = 0;
             for (int t = static_cast<int>(kRun) - 1; t >= 0; --t) {
                 const uint32_t i = static_cast<uint32_t>(q) * kTurn + j * kRun + static_cast<uint32_t>(t);
                 if (i < m) {
                     uint32_t u = src[base + i];
                     if constexpr (NORM)
                         u = normalise_word(u, coefficient(coef[(base + i) / block]));
-                    rans_put(st, enc[exponent_of(u)], ring);
+                    const EncSym e = enc[exponent_of(u)];
+                    if constexpr (SPLIT >= 0) {
+                        least_rcp = fminf(least_rcp, e.rcp);
+                        packed |= static_cast<uint64_t>(signmant_field<KB>(u)) << (static_cast<uint32_t>(t) * (KB + 1));
+                    }
+                    rans_put(st, e, ring);
                 }
+            }
+            if constexpr (SPLIT >= 0) {
+                // the fields of this lane's run: whole bytes; a last partial byte has zero high bits
+                constexpr uint32_t per_byte = 8 / (KB + 1);
+                const uint32_t first = static_cast<uint32_t>(q) * kTurn + j * kRun;
+                const uint32_t valid = first >= m ? 0u : (m - first < kRun ? m - first : kRun);
+                for (uint32_t t = 0; t < valid; t += per_byte)
+                    sm[(base + first + t) / per_byte] = static_cast<uint8_t>(packed >> (t * (KB + 1)));
             }
             ring_flush(wp_before, st.wp, ring, slot);
         }
+    }
+    if constexpr (SPLIT >= 0) {
+        if (least_rcp == 0.0f)
+            atomicOr(&stale[slot_id.item], 1u);
     }
     const uint32_t len = kRunCap - st.wp;
     if (live) {
@@ -583,7 +674,8 @@ __global__ __launch_bounds__(kScanThreads) void offsets_kernel(const CompressBat
                                                               const uint32_t *__restrict__ group_words_all,
                                                               uint64_t *__restrict__ group_prefix_all,
                                                               uint32_t *__restrict__ done,
-                                                              HostRecord *__restrict__ record)
+                                                              HostRecord *__restrict__ record,
+                                                              const uint32_t *__restrict__ stale)
 {
     // one workgroup per tensor of the batch
     const CompressItem &it = b.it[blockIdx.x];
@@ -632,6 +724,7 @@ __global__ __launch_bounds__(kScanThreads) void offsets_kernel(const CompressBat
         last_offset[1] = 0;
         record->item[blockIdx.x].total_words[0] = static_cast<uint32_t>(carry);
         record->item[blockIdx.x].total_words[1] = static_cast<uint32_t>(carry >> 32);  // non-zero: too long for 32-bit offsets
+        record->item[blockIdx.x].stale = stale ? stale[blockIdx.x] : 0u;
         // the workgroup that finishes last publishes the stamp and rearms the counter
         __threadfence_system();
         if (atomicAdd(done, 1u) == b.count - 1) {

@@ -83,6 +83,7 @@ struct CompressItem {
     uint16_t *words;       // known only after the stream length has been read back
     uint32_t n_chunks;
     uint32_t block;        // 0: no block-wise normalisation
+    uint32_t guard;        // exponents this far outside the occupied range keep f = 1 in the table
     uint32_t group_base;   // first encoder group (16 chunks) of this tensor in the workspace arrays
     uint32_t hist_end;     // first workgroup after this tensor's in the histogram launch
     uint32_t enc_end;      // ... in the encode launch
@@ -101,6 +102,8 @@ struct HostRecord {
     uint32_t pad;
     struct Item {
         uint32_t total_words[2];
+        uint32_t stale;    // recompression only: an exponent had no room in the blob's table
+        uint32_t pad;
         uint32_t counts[256];
         uint16_t freq[256];
     } item[kBatchMax];

@@ -37,7 +37,7 @@ def test_library_exports_every_declared_symbol(nz):
 def test_binding_mirrors_the_header(nz):
     for name in declared_functions():
         if name in ("neuzip_strerror", "neuzip_last_hip_error", "neuzip_elems", "neuzip_mantissa_bits",
-                    "neuzip_device_bytes", "neuzip_block_size"):
+                    "neuzip_device_bytes", "neuzip_block_size", "neuzip_guard"):
             continue  # surfaced as Blob properties / NeuzipError fields
         assert hasattr(nz, name), f"binding lacks {name}"
 
@@ -81,6 +81,16 @@ def test_argument_validation_happens_before_device_work(nz):
     assert lib.neuzip_decompress_batch(None, None, 2, None) == nz.EINVAL
     assert lib.neuzip_compress_batch(None, None, 2, 0, 7, 0, None, None) == nz.EINVAL
     assert lib.neuzip_compress_batch(None, None, 0, 0, 7, 0, None, None) == nz.OK
+    # guard band and recompression
+    assert lib.neuzip_compress_guarded(None, None, 2, 0, 7, 4, None, None) == nz.EINVAL
+    srcs = (ctypes.c_void_p * 1)(0x1000)
+    sizes = (ctypes.c_uint64 * 1)(16)
+    handles = (ctypes.c_void_p * 1)(None)
+    assert lib.neuzip_compress_guarded(srcs, sizes, 1, 0, 7, 256, None, handles) == nz.EINVAL
+    assert lib.neuzip_recompress(None, 0, None, None, None) == nz.OK
+    assert lib.neuzip_recompress(None, 1, None, None, None) == nz.EINVAL
+    assert lib.neuzip_recompress(srcs, 1, None, handles, None) == nz.EINVAL      # not a blob
+    assert lib.neuzip_guard(None) == 0
 
 
 def test_import_validates_containers_on_the_host(nz):
@@ -102,6 +112,10 @@ def test_import_validates_containers_on_the_host(nz):
         bad = good.copy()
         bad[sec[name][0] + delta] ^= flip
         assert try_import(bad) == nz.ECORRUPT, (name, delta)
+    # a guard band beyond the byte range
+    bad = good.copy()
+    bad[sec["header"][0] + 53] = 1
+    assert try_import(bad) == nz.ECORRUPT
     # a run longer than any state can produce
     bad = good.copy()
     bad[sec["lens"][0]] = 255
