@@ -142,6 +142,39 @@ def test_config5_training_step_loop(nz):
             nz.neuzip_check(blob)
 
 
+def test_config5_loop_with_kept_tables(nz):
+    # the same loop, a layer per call, the table of the step before kept (guard band 8): the
+    # container must be the oracle's for that table, or the oracle's fresh one where the GPU
+    # reports that it rebuilt a table
+    names = inputs.llama3_8b_tensors()[:8]                   # embedding + layer 0, full shapes
+    tensors = [inputs.gaussian_bf16(s, inputs.seed_for(5, 50 + i), device=DEV).reshape(-1)
+               for i, (_, s) in enumerate(names)]
+    groups = [[0], list(range(1, 8))]
+    blobs = nz.neuzip_compress_guarded(tensors, 7, 8)
+    tables = [nz.neuzip_frequencies(b).copy() for b in blobs]
+    outs = [torch.empty_like(t) for t in tensors]
+    for step in range(4):
+        for g in groups:
+            nz.neuzip_decompress_batch([blobs[i] for i in g], [outs[i] for i in g])
+            for i in g:
+                assert same_bits(outs[i], tensors[i]), (step, names[i][0])
+                tensors[i] = inputs.synthetic_update(outs[i], inputs.seed_for(5, 2000 * (step + 1) + i))
+            rebuilt = nz.neuzip_recompress([tensors[i] for i in g], [blobs[i] for i in g])
+            for i, r in zip(g, rebuilt):
+                if r:
+                    tables[i] = nz.neuzip_frequencies(blobs[i]).copy()
+                if i in (2, 5) or (i == 0 and step == 3):   # k_proj, gate_proj every step; the embedding once
+                    words = inputs.bits(tensors[i])
+                    want = (O.compress(words, 7, threads=THREADS, guard=8) if r
+                            else O.compress(words, 7, threads=THREADS, guard=8, freq=tables[i]))
+                    got = nz.neuzip_export(blobs[i])
+                    assert got.size == want.size and np.array_equal(got, want), (step, names[i][0], r)
+    for i, b in enumerate(blobs):
+        nz.neuzip_decompress(b, outs[i])
+        nz.neuzip_check(b)
+        assert same_bits(outs[i], tensors[i])
+
+
 def test_tensor_of_more_than_2_to_31_elements(nz):
     # 64-bit indexing: 2^31 + 4099 elements (4.3 GB of bf16), ragged tail included
     n = (1 << 31) + 4099
