@@ -606,3 +606,63 @@ def test_size_under_a_stale_table_is_the_cross_entropy():
     # a small update barely moves the exponent distribution: under 0.01 bit per weight lost
     fresh = O.compress(new, 7, threads=4)
     assert 0 <= 8 * (blob.size - fresh.size) / n < 0.01
+
+
+# ---------------------------------------------------------------- linear layer on a compressed weight (Sec. 2.2, compressed forward pass)
+
+def test_linear_oracle_one_hot_activations_pick_weight_columns():
+    from oracle import linear as L
+    out_f, in_f = 24, 256                                       # not square: a transposed operand cannot pass
+    w = inputs.bits(inputs.gaussian_bf16(out_f * in_f, seed=41))
+    blob = O.compress(w, 7)
+    picks = [0, 1, 17, 255, 128]
+    x = np.zeros((len(picks), in_f), np.uint16)
+    for t, k in enumerate(picks):
+        x[t, k] = 0x3F80                                        # bf16 1.0
+    y = L.linear(blob, out_f, in_f, x)
+    assert y.shape == (len(picks), out_f)
+    wf = as_float(w).reshape(out_f, in_f)
+    for t, k in enumerate(picks):
+        assert np.array_equal(y[t], wf[:, k])
+    # the bias is added once to every token
+    b = np.arange(out_f, dtype=np.float64) * 0.5 - 3
+    assert np.array_equal(L.linear(blob, out_f, in_f, x, bias=b), y + b)
+
+
+@pytest.mark.parametrize("k", [7, 3, 0])
+def test_linear_oracle_against_exact_rational_arithmetic(k):
+    # bf16 values are dyadic rationals: Fractions give the exact sum, whatever the order
+    from fractions import Fraction
+    from oracle import linear as L
+    out_f, in_f, tokens = 5, 128, 3
+    w = inputs.bits(inputs.student_t4_bf16(out_f * in_f, seed=42))
+    x = inputs.bits(inputs.gaussian_bf16(tokens * in_f, seed=43, std=1.0)).reshape(tokens, in_f)
+    blob = O.compress(w, k)
+    y = L.linear(blob, out_f, in_f, x)
+    mag = L.magnitude(blob, out_f, in_f, x)
+    w_hat = [Fraction(float(v)) for v in as_float(O.truncate(w, k))]   # the lossy variant multiplies the truncated weights
+    xs = [[Fraction(float(v)) for v in as_float(row)] for row in x]
+    for t in range(tokens):
+        for o in range(out_f):
+            exact = sum(w_hat[o * in_f + i] * xs[t][i] for i in range(in_f))
+            assert abs(Fraction(float(y[t, o])) - exact) <= Fraction(float(mag[t, o])) * Fraction(in_f, 2 ** 52)
+            assert float(mag[t, o]) >= abs(float(exact))
+
+
+def test_linear_oracle_row_sums_and_linearity():
+    from oracle import linear as L
+    out_f, in_f = 16, 512
+    w = inputs.bits(inputs.gaussian_bf16(out_f * in_f, seed=44))
+    blob = O.compress(w, 7)
+    ones = np.full((1, in_f), 0x3F80, np.uint16)
+    y = L.linear(blob, out_f, in_f, ones)
+    rows = as_float(w).reshape(out_f, in_f)
+    for o in range(out_f):
+        assert y[0, o] == pytest.approx(math.fsum(rows[o]), rel=1e-12, abs=1e-15)
+    # tokens are independent of each other: stacking activations stacks outputs
+    x = inputs.bits(inputs.gaussian_bf16(4 * in_f, seed=45, std=1.0)).reshape(4, in_f)
+    whole = L.linear(blob, out_f, in_f, x)
+    for t in range(4):
+        assert np.array_equal(whole[t], L.linear(blob, out_f, in_f, x[t:t + 1])[0])
+    # negating the activations (flip the bf16 sign bit) negates the output exactly
+    assert np.array_equal(L.linear(blob, out_f, in_f, x ^ 0x8000), -whole)
