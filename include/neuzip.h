@@ -186,6 +186,26 @@ int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, 
 int neuzip_decompress_batch(const neuzip_blob *const *blobs, void *const *d_dsts, uint32_t count,
                             void *hip_stream);
 
+/*
+ * neuzip_linear -- the compressed forward pass of a linear layer, Sec. 2.2:
+ *     W_hat <- decompress(c_l);   x_l <- W_hat x_{l-1} + b_l
+ * as one fused kernel: the decoded weights go from the decoder's registers straight into the
+ * matrix cores and W_hat is never written to memory.
+ *
+ *   weight        blob of a row-major out_features x in_features bf16 matrix (any mantissa_bits;
+ *                 block-wise normalised blobs -> EUNSUPPORTED).  in_features must be a multiple
+ *                 of 128 and out_features * in_features must equal neuzip_elems(weight).
+ *   d_x           tokens x in_features bf16 activations, row-major, 16-byte aligned.
+ *   tokens        1 .. 64 (larger batches: decompress once and use a dense GEMM).
+ *   d_bias        out_features floats on the device, or NULL.
+ *   d_y           tokens x out_features floats, row-major; overwritten.
+ * Products are exact, sums are accumulated in float32 by the matrix cores and, across the pieces
+ * of a row, by float atomics, so the last bits can differ from run to run.  Never allocates,
+ * never synchronises; a malformed stream is reported by neuzip_check as for neuzip_decompress.
+ */
+int neuzip_linear(const neuzip_blob *weight, uint64_t out_features, uint64_t in_features, const void *d_x,
+                  uint32_t tokens, const float *d_bias, float *d_y, void *hip_stream);
+
 /* Releases the blob and its device memory.  NULL is a no-op. */
 void neuzip_free(neuzip_blob *blob);
 

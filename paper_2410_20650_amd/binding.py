@@ -41,6 +41,8 @@ def _load():
     lib.neuzip_compress_guarded.restype = i32
     lib.neuzip_recompress.argtypes = [vpp, u32, vp, vpp, ctypes.POINTER(u32)]
     lib.neuzip_recompress.restype = i32
+    lib.neuzip_linear.argtypes = [vp, u64, u64, vp, u32, vp, vp, vp]
+    lib.neuzip_linear.restype = i32
     lib.neuzip_block_size.argtypes = [vp]
     lib.neuzip_block_size.restype = u32
     lib.neuzip_guard.argtypes = [vp]
@@ -84,7 +86,7 @@ _lib = None
 _lib = _load()
 
 EXPORTED = ["neuzip_compress", "neuzip_compress_blockwise", "neuzip_compress_batch", "neuzip_compress_guarded",
-            "neuzip_recompress", "neuzip_guard", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
+            "neuzip_recompress", "neuzip_guard", "neuzip_linear", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
             "neuzip_free",
             "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits",
             "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check",
@@ -244,6 +246,28 @@ def neuzip_decompress_batch(blobs, dsts, stream=None) -> None:
     rc = _lib.neuzip_decompress_batch(arr, ptrs, len(blobs), _stream_handle(stream))
     if rc != OK:
         raise NeuzipError(rc, "neuzip_decompress_batch")
+
+
+def neuzip_linear(weight: Blob, out_features: int, in_features: int, x: torch.Tensor, bias: torch.Tensor = None,
+                  y: torch.Tensor = None, stream=None) -> torch.Tensor:
+    """y = x W_hat^T + bias with the weight taken straight from its compressed form (float32 result)."""
+    _check_tensor(x)
+    tokens = x.numel() // in_features if in_features else 0
+    if x.numel() != tokens * in_features:
+        raise ValueError("activations must be tokens x in_features")
+    if y is None:
+        y = torch.empty((tokens, out_features), dtype=torch.float32, device=x.device)
+    if not (y.is_cuda and y.dtype == torch.float32 and y.is_contiguous() and y.numel() == tokens * out_features):
+        raise TypeError("expected a contiguous float32 CUDA tensor of tokens x out_features")
+    if bias is not None and not (bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous()
+                                 and bias.numel() == out_features):
+        raise TypeError("expected a contiguous float32 CUDA bias of out_features")
+    rc = _lib.neuzip_linear(weight.handle, out_features, in_features, ctypes.c_void_p(x.data_ptr()), tokens,
+                            ctypes.c_void_p(bias.data_ptr() if bias is not None else None),
+                            ctypes.c_void_p(y.data_ptr()), _stream_handle(stream))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_linear")
+    return y
 
 
 def neuzip_free(blob: Blob) -> None:

@@ -8,7 +8,8 @@ LIB = os.path.join(HERE, "libneuzip.so")
 SOURCES = [os.path.join(HERE, "csrc", "neuzip.hip")]
 HEADERS = [os.path.join(ROOT, "include", "neuzip.h")] + [
     os.path.join(HERE, "csrc", name)
-    for name in ("neuzip_format.h", "neuzip_compress_kernels.h", "neuzip_decode_kernels.h")]
+    for name in ("neuzip_format.h", "neuzip_compress_kernels.h", "neuzip_decode_kernels.h",
+                 "neuzip_linear_kernels.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

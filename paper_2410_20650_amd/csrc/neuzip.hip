@@ -32,6 +32,7 @@
 #include "neuzip_format.h"
 #include "neuzip_compress_kernels.h"
 #include "neuzip_decode_kernels.h"
+#include "neuzip_linear_kernels.h"
 
 using namespace nz;
 
@@ -380,6 +381,19 @@ int launch_batch(const BatchArgs &args, int variant, uint32_t groups, hipStream_
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
 
+template <int KB>
+void launch_linear(const LinearArgs &args, uint32_t wgs, hipStream_t stream)
+{
+    const dim3 grid(wgs), block(kLinThreads);
+    const uint32_t tiles = (args.tokens + 15) / 16;
+    switch (tiles) {
+    case 1: hipLaunchKernelGGL((linear_kernel<KB, 1>), grid, block, 0, stream, args); break;
+    case 2: hipLaunchKernelGGL((linear_kernel<KB, 2>), grid, block, 0, stream, args); break;
+    case 3: hipLaunchKernelGGL((linear_kernel<KB, 3>), grid, block, 0, stream, args); break;
+    default: hipLaunchKernelGGL((linear_kernel<KB, 4>), grid, block, 0, stream, args); break;
+    }
+}
+
 // An empty tensor: a zeroed table block (a fill kernel, not a memset node, so the call stays safe
 // to record into a graph) and a single zero offset.
 int compress_empty(neuzip_blob *b, hipStream_t stream)
@@ -687,6 +701,60 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
 }
 
 uint32_t neuzip_guard(const neuzip_blob *blob) { return is_blob(blob) ? blob->guard : 0; }
+
+int neuzip_linear(const neuzip_blob *weight, uint64_t out_features, uint64_t in_features, const void *d_x,
+                  uint32_t tokens, const float *d_bias, float *d_y, void *hip_stream)
+{
+    if (!is_blob(weight) || !weight->has_table || !d_x || !d_y)
+        return NEUZIP_EINVAL;
+    if (out_features == 0 || in_features == 0 || in_features % kTurn != 0 || in_features >= (1ull << 31) ||
+        out_features >= (1ull << 31) || out_features * in_features != weight->n)
+        return NEUZIP_EINVAL;
+    if (tokens == 0 || tokens > kLinMaxTokens)
+        return NEUZIP_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(d_x) & 15u) || (reinterpret_cast<uintptr_t>(d_y) & 3u) ||
+        (reinterpret_cast<uintptr_t>(d_bias) & 3u))
+        return NEUZIP_EINVAL;
+    if (weight->block != 0)
+        return NEUZIP_EUNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    uint64_t gcd = in_features, r = kChunk;
+    while (r) {
+        const uint64_t t = gcd % r;
+        gcd = r;
+        r = t;
+    }
+    LinearArgs a;
+    a.tb = table_of(weight);
+    a.offsets = offsets_of(weight);
+    a.states = states_of(weight);
+    a.lens = lens_of(weight);
+    a.words = reinterpret_cast<const uint16_t *>(weight->words);
+    a.sm = sm_of(weight);
+    a.x = static_cast<const uint16_t *>(d_x);
+    a.y = d_y;
+    a.status = table_of(weight)->status;
+    a.n = weight->n;
+    a.n_chunks = weight->n_chunks;
+    a.in_features = static_cast<uint32_t>(in_features);
+    a.out_features = static_cast<uint32_t>(out_features);
+    a.tokens = tokens;
+    a.stride = static_cast<uint32_t>(in_features / gcd);
+    a.rstep = static_cast<uint32_t>(kChunk / gcd);
+    const uint64_t per_block = static_cast<uint64_t>(kLinGroupChunks) * a.stride;
+    a.n_groups = static_cast<uint32_t>((weight->n_chunks + per_block - 1) / per_block * a.stride);
+    const uint64_t cells = static_cast<uint64_t>(tokens) * out_features;
+    hipLaunchKernelGGL(linear_init_kernel, dim3(static_cast<uint32_t>((cells + 255) / 256)), dim3(256), 0, stream, d_y,
+                       d_bias, tokens, a.out_features);
+    const uint32_t wgs = (a.n_groups + 1) / 2;
+    switch (weight->k) {
+    case 7: launch_linear<7>(a, wgs, stream); break;
+    case 3: launch_linear<3>(a, wgs, stream); break;
+    case 1: launch_linear<1>(a, wgs, stream); break;
+    default: launch_linear<0>(a, wgs, stream); break;
+    }
+    return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
+}
 
 }  // extern "C"
 

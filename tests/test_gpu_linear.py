@@ -1,0 +1,130 @@
+"""GPU parity of the fused decode + matrix-core linear layer (-m gpu).
+
+Sec. 2.2, compressed forward pass: W_hat <- decompress(c_l); x_l <- W_hat x_{l-1} + b_l.  The
+oracle evaluates that definition in float64 (oracle/linear.py).  The kernel multiplies bf16 values
+exactly and sums in float32, in an order of its own (matrix-core accumulation over 32 input
+features at a time, then float atomics across the pieces of a row), so the bar is the classical
+bound for a float32 sum of N terms in any order: |error| <= N * 2^-24 * sum |w_k x_k|, with N =
+in_features + the number of partial sums; the tests allow twice that.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import linear as L
+from oracle import oracle as O
+from paper_2410_20650_amd import inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def nz():
+    from paper_2410_20650_amd import binding
+    return binding
+
+
+def check_linear(nz, w, out_f, in_f, tokens, k=7, bias=False, seed=1):
+    """Compress w (flat bf16, out_f * in_f) on the GPU, run the fused layer, compare with the oracle."""
+    x = inputs.gaussian_bf16((tokens, in_f), seed, std=1.0, device=DEV)
+    b = (torch.arange(out_f, dtype=torch.float32, device=DEV) * 0.37 - 2.0) if bias else None
+    blob = nz.neuzip_compress(w, k)
+    y = torch.full((tokens, out_f), float("nan"), dtype=torch.float32, device=DEV)
+    nz.neuzip_linear(blob, out_f, in_f, x, b, y)
+    nz.neuzip_check(blob)
+    container = O.compress(inputs.bits(w), k, threads=8)      # the oracle's own container of the same weight
+    xw = inputs.bits(x).reshape(tokens, in_f)
+    want = L.linear(container, out_f, in_f, xw, bias=None if b is None else b.cpu().numpy().astype(np.float64))
+    mag = L.magnitude(container, out_f, in_f, xw)
+    if b is not None:
+        mag = mag + np.abs(b.cpu().numpy().astype(np.float64))
+    got = y.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    bound = 2.0 * (in_f + 64) * 2.0 ** -24 * mag + 1e-30
+    worst = np.max(np.abs(got - want) / bound)
+    assert worst <= 1.0, f"error {worst:.3f} x the float32 bound (out={out_f}, in={in_f}, tokens={tokens}, k={k})"
+    return blob, x, y
+
+
+@pytest.mark.parametrize("tokens", [1, 5, 16, 17, 33, 64])
+@pytest.mark.parametrize("out_f,in_f", [(16, 128), (40, 256), (64, 4096), (37, 4096), (48, 14336), (33, 11008),
+                                        (8, 8192)])
+def test_linear_matches_the_oracle(nz, out_f, in_f, tokens):
+    w = inputs.gaussian_bf16(out_f * in_f, 9000 + out_f + in_f, device=DEV)
+    check_linear(nz, w, out_f, in_f, tokens, seed=9100 + tokens)
+
+
+@pytest.mark.parametrize("k", [3, 1, 0])
+def test_linear_on_lossy_weights_uses_the_truncated_values(nz, k):
+    out_f, in_f = 96, 1024
+    w = inputs.student_t4_bf16(out_f * in_f, 9200 + k, device=DEV)
+    check_linear(nz, w, out_f, in_f, 9, k=k, bias=True, seed=9201)
+
+
+def test_linear_with_bias_and_one_hot_activations(nz):
+    # one-hot activations select weight columns: the result is exact, whatever the summation order
+    out_f, in_f = 50, 512
+    w = inputs.gaussian_bf16(out_f * in_f, 9300, device=DEV)
+    blob = nz.neuzip_compress(w, 7)
+    picks = [0, 7, 8, 127, 128, 300, 511]
+    x = torch.zeros((len(picks), in_f), dtype=torch.bfloat16, device=DEV)
+    for t, kcol in enumerate(picks):
+        x[t, kcol] = 1.0
+    bias = torch.linspace(-1, 1, out_f, dtype=torch.float32, device=DEV)
+    y = nz.neuzip_linear(blob, out_f, in_f, x, bias)
+    wf = w.float().reshape(out_f, in_f)
+    for t, kcol in enumerate(picks):
+        assert torch.equal(y[t], wf[:, kcol] + bias)
+
+
+def test_linear_single_exponent_and_wide_exponent_weights(nz):
+    # one exponent value: the decoder's path without words
+    out_f, in_f = 24, 512
+    sign = torch.where(torch.arange(out_f * in_f, device=DEV) % 3 == 0, -1.0, 1.0)
+    w = (sign * 0.75).to(torch.bfloat16)
+    check_linear(nz, w, out_f, in_f, 4, seed=9400)
+    # exponents spread over 40 values (over 5 bits per symbol): the word runs do not fit the LDS
+    # window and are read from the blob
+    g = torch.Generator(device=DEV).manual_seed(9401)
+    n = 64 * 2048
+    expo = torch.randint(100, 140, (n,), generator=g, device=DEV, dtype=torch.int32)
+    rest = torch.randint(0, 256, (n,), generator=g, device=DEV, dtype=torch.int32)
+    words = ((rest & 0x80) << 8) | (expo << 7) | (rest & 0x7F)
+    w = (words - 65536 * (words >= 32768)).to(torch.int16).view(torch.bfloat16)
+    check_linear(nz, w, 64, 2048, 20, seed=9402)
+
+
+def test_linear_full_projection_shape(nz):
+    # a q/o projection of Llama-3 8B at full size, a decoding batch of 8 tokens
+    out_f = in_f = 4096
+    w = inputs.gaussian_bf16(out_f * in_f, inputs.seed_for(3, 1), device=DEV)
+    blob, x, y = check_linear(nz, w, out_f, in_f, 8, seed=9500)
+    # against the dense product of the decompressed weight on the GPU (bf16 inputs, float32 sums)
+    dense = torch.empty(out_f * in_f, dtype=torch.bfloat16, device=DEV)
+    nz.neuzip_decompress(blob, dense)
+    ref = x.float() @ dense.float().reshape(out_f, in_f).T
+    assert torch.allclose(y, ref, rtol=0, atol=2e-3 * ref.abs().max().item())
+
+
+def test_linear_argument_errors(nz):
+    w = inputs.gaussian_bf16(32 * 256, 9600, device=DEV)
+    blob = nz.neuzip_compress(w, 7)
+    x = inputs.gaussian_bf16((4, 256), 9601, device=DEV)
+    lib = nz.library()
+    import ctypes
+    y = torch.zeros((4, 64), dtype=torch.float32, device=DEV)
+    args = lambda out_f, in_f, tokens: (blob.handle, out_f, in_f, ctypes.c_void_p(x.data_ptr()), tokens, None,
+                                        ctypes.c_void_p(y.data_ptr()), None)
+    assert lib.neuzip_linear(*args(32, 256, 4)) == nz.OK
+    assert lib.neuzip_linear(*args(16, 256, 4)) == nz.EINVAL       # shape does not match the blob
+    assert lib.neuzip_linear(*args(64, 128, 4)) == nz.OK           # same elements, another valid shape
+    assert lib.neuzip_linear(*args(128, 64, 4)) == nz.EINVAL       # in_features not a multiple of 128
+    assert lib.neuzip_linear(*args(32, 256, 0)) == nz.EINVAL
+    assert lib.neuzip_linear(*args(32, 256, 65)) == nz.EINVAL
+    assert lib.neuzip_linear(None, 32, 256, ctypes.c_void_p(x.data_ptr()), 4, None, ctypes.c_void_p(y.data_ptr()),
+                             None) == nz.EINVAL
+    lossy = nz.neuzip_compress_blockwise(w, 3, 64)
+    assert lib.neuzip_linear(lossy.handle, 32, 256, ctypes.c_void_p(x.data_ptr()), 4, None,
+                             ctypes.c_void_p(y.data_ptr()), None) == nz.EUNSUPPORTED
+    torch.cuda.synchronize()
