@@ -225,6 +225,43 @@ def main():
         del t4, buf, ref
         torch.cuda.empty_cache()
 
+        # the compressed forward pass of a linear layer (Sec. 2.2): the fused decode + matrix-core
+        # kernel against decompress-into-scratch followed by a dense bf16 product (torch / hipBLASLt),
+        # on the projection shapes of a Llama-3-8B layer, decoding batches of 1..16 tokens
+        lin = {}
+        for label, (out_f, in_f) in (("q_4096x4096", (4096, 4096)), ("up_14336x4096", (14336, 4096)),
+                                     ("down_4096x14336", (4096, 14336))):
+            wl = inputs.gaussian_bf16((out_f, in_f), inputs.seed_for(8, out_f % 97), device=dev)
+            bl_ = nz.neuzip_compress(wl, 7)
+            dense = torch.empty_like(wl)
+            for tokens in (1, 16):
+                xl = inputs.gaussian_bf16((tokens, in_f), inputs.seed_for(8, 500 + tokens), std=1.0, device=dev)
+                yl = torch.empty((tokens, out_f), dtype=torch.float32, device=dev)
+
+                def fused():
+                    nz.neuzip_linear(bl_, out_f, in_f, xl, None, yl)
+
+                def separate():
+                    nz.neuzip_decompress(bl_, dense.view(-1))
+                    torch.matmul(xl, dense.t())
+
+                times = {}
+                for name, fn in (("fused", fused), ("separate", separate)):
+                    for _ in range(5):
+                        fn()
+                    _, ms = timed_region(torch, stream, fn, 50)
+                    times[name] = ms / 50
+                ref = xl.float() @ dense.float().t()
+                lin[f"{label}_tokens{tokens}"] = {
+                    "fused_us": round(times["fused"] * 1e3, 1),
+                    "decompress_then_dense_product_us": round(times["separate"] * 1e3, 1),
+                    "weights_GBps": round(2.0 * out_f * in_f / (times["fused"] * 1e-3) / 1e9, 1),
+                    "max_abs_diff_vs_dense_over_max_abs": round(((yl - ref).abs().max() / ref.abs().max()).item(), 7)}
+            nz.neuzip_free(bl_)
+            del wl, dense
+        ext["linear_forward"] = lin
+        torch.cuda.empty_cache()
+
         # config 3: every weight of a Llama-3-8B-shaped model, forward order, one reusable scratch
         names = inputs.llama3_8b_tensors()
         if args.layers < 32:
