@@ -381,16 +381,29 @@ int launch_batch(const BatchArgs &args, int variant, uint32_t groups, hipStream_
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
 
+// Which form of the kernel: 16 columns (tiles of 16 tokens) or 32 columns (tiles of 32 tokens).
+// The wide form halves the activation traffic per token but doubles the waves that add partial
+// sums to one output, so it pays for more than 16 tokens on shapes whose chunks never straddle
+// rows of the weight (stride 1: no row ends inside a chunk); measured on 14336 x 4096 and
+// 4096 x 14336.
+inline uint32_t linear_columns(uint32_t tokens, uint32_t stride) { return tokens > 16 && stride == 1 ? 32u : 16u; }
+
 template <int KB>
-void launch_linear(const LinearArgs &args, uint32_t wgs, hipStream_t stream)
+void launch_linear(const LinearArgs &args, uint32_t cols, uint32_t wgs, hipStream_t stream)
 {
     const dim3 grid(wgs), block(kLinThreads);
-    const uint32_t tiles = (args.tokens + 15) / 16;
-    switch (tiles) {
-    case 1: hipLaunchKernelGGL((linear_kernel<KB, 1>), grid, block, 0, stream, args); break;
-    case 2: hipLaunchKernelGGL((linear_kernel<KB, 2>), grid, block, 0, stream, args); break;
-    case 3: hipLaunchKernelGGL((linear_kernel<KB, 3>), grid, block, 0, stream, args); break;
-    default: hipLaunchKernelGGL((linear_kernel<KB, 4>), grid, block, 0, stream, args); break;
+    if (cols == 32) {
+        if (args.tokens <= 32)
+            hipLaunchKernelGGL((linear_kernel<KB, 32, 1>), grid, block, 0, stream, args);
+        else
+            hipLaunchKernelGGL((linear_kernel<KB, 32, 2>), grid, block, 0, stream, args);
+        return;
+    }
+    switch ((args.tokens + 15) / 16) {
+    case 1: hipLaunchKernelGGL((linear_kernel<KB, 16, 1>), grid, block, 0, stream, args); break;
+    case 2: hipLaunchKernelGGL((linear_kernel<KB, 16, 2>), grid, block, 0, stream, args); break;
+    case 3: hipLaunchKernelGGL((linear_kernel<KB, 16, 3>), grid, block, 0, stream, args); break;
+    default: hipLaunchKernelGGL((linear_kernel<KB, 16, 4>), grid, block, 0, stream, args); break;
     }
 }
 
@@ -741,17 +754,19 @@ int neuzip_linear(const neuzip_blob *weight, uint64_t out_features, uint64_t in_
     a.tokens = tokens;
     a.stride = static_cast<uint32_t>(in_features / gcd);
     a.rstep = static_cast<uint32_t>(kChunk / gcd);
-    const uint64_t per_block = static_cast<uint64_t>(kLinGroupChunks) * a.stride;
+    const uint32_t cols = linear_columns(tokens, a.stride);  // chunks per group = columns of the matrix instruction
+    const uint64_t per_block = static_cast<uint64_t>(cols) * a.stride;
     a.n_groups = static_cast<uint32_t>((weight->n_chunks + per_block - 1) / per_block * a.stride);
     const uint64_t cells = static_cast<uint64_t>(tokens) * out_features;
     hipLaunchKernelGGL(linear_init_kernel, dim3(static_cast<uint32_t>((cells + 255) / 256)), dim3(256), 0, stream, d_y,
                        d_bias, tokens, a.out_features);
-    const uint32_t wgs = (a.n_groups + 1) / 2;
+    const uint32_t groups_per_wg = kDecChunksPerWg / cols;
+    const uint32_t wgs = (a.n_groups + groups_per_wg - 1) / groups_per_wg;
     switch (weight->k) {
-    case 7: launch_linear<7>(a, wgs, stream); break;
-    case 3: launch_linear<3>(a, wgs, stream); break;
-    case 1: launch_linear<1>(a, wgs, stream); break;
-    default: launch_linear<0>(a, wgs, stream); break;
+    case 7: launch_linear<7>(a, cols, wgs, stream); break;
+    case 3: launch_linear<3>(a, cols, wgs, stream); break;
+    case 1: launch_linear<1>(a, cols, wgs, stream); break;
+    default: launch_linear<0>(a, cols, wgs, stream); break;
     }
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }

@@ -17,8 +17,15 @@
 // exactly a B operand, provided the 16 chunks sit at the same input-feature offset.  Chunks that
 // are `stride` = in_features / gcd(in_features, 4096) apart do (stride * 4096 is a whole number of
 // rows), so a group is chunks first + stride * (0..15); its columns are rows `rstep` apart.
-// Every wave accumulates its own quarter of the input features of a row piece and adds the
+// Every wave accumulates its own share of the input features of a row piece and adds the
 // partial sums to y with float atomics when the row ends (y starts as the bias, or zero).
+//
+// Two forms, template parameter COLS.  COLS = 16 is the above.  COLS = 32 uses
+// v_mfma_f32_32x32x16_bf16 (A 32 x 16, B 16 x 32, lane l: row / column l % 32, k = 8 * (l / 32)
+// .. + 7; D: lane l holds column l % 32 and rows (r / 4) * 8 + (l / 32) * 4 + r % 4, r = 0..15):
+// the workgroup's 32 chunks form one group, wave w and lane l own state 2 w + l / 32 of chunk
+// l % 32.  The weights held per wave and turn are the same 512, but one 128-bit activation load
+// per lane now serves 32 tokens instead of 16, which is what limits larger batches.
 #pragma once
 
 #include "neuzip_format.h"
@@ -28,10 +35,37 @@ namespace nz {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+// Accumulator tile and matrix instruction of the two forms
+template <int COLS>
+struct LinearTile;
+template <>
+struct LinearTile<16> {
+    typedef f32x4_t acc_t;
+    static constexpr int kRegs = 4;
+    static __device__ __forceinline__ acc_t mma(bf16x8_t a, bf16x8_t b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+    // token (row of D) held in register r of lane `lane`
+    static __device__ __forceinline__ uint32_t row(uint32_t lane, int r) { return (lane >> 4) * 4 + r; }
+};
+template <>
+struct LinearTile<32> {
+    typedef f32x16_t acc_t;
+    static constexpr int kRegs = 16;
+    static __device__ __forceinline__ acc_t mma(bf16x8_t a, bf16x8_t b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint32_t row(uint32_t lane, int r)
+    {
+        return (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+    }
+};
 
 constexpr uint32_t kLinThreads = 512;
-constexpr uint32_t kLinGroupChunks = 16;                 // columns of the B operand
-constexpr uint32_t kLinGroupBytes = kStageBytes / 2;     // LDS window of one group's word runs
 constexpr uint32_t kLinMaxTokens = 64;
 
 struct LinearArgs {
@@ -70,16 +104,18 @@ __device__ __forceinline__ void atomic_add_f32(float *p, float v)
     unsafeAtomicAdd(p, v);
 }
 
-template <int KB, int MT, bool LONE, class WordSrc>
+template <int KB, int COLS, int MT, bool LONE, class WordSrc>
 __device__ __forceinline__ void linear_walk(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
                                             uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
                                             const LinearArgs &a, uint64_t base, uint32_t kk, uint32_t turns,
                                             uint32_t j, uint32_t lane)
 {
     const uint32_t in = a.in_features;
-    const uint32_t col = lane & 15u;                 // column of B and of D: this lane's chunk
-    const uint32_t kq = (j & 3u) * 8u;               // this lane's 8 input features inside the wave's 32
-    const uint32_t ksq = (j >> 2) * 32u;             // the wave's 32 inside the turn's 128
+    typedef LinearTile<COLS> Tile;
+    constexpr uint32_t kPerWave = 64 / COLS;         // states of a chunk held by one wave (4 or 2)
+    const uint32_t col = lane & (COLS - 1);          // column of B and of D: this lane's chunk
+    const uint32_t kq = (j % kPerWave) * 8u;         // this lane's 8 input features inside the wave's 32 or 16
+    const uint32_t ksq = (j / kPerWave) * kPerWave * 8u;  // the wave's features inside the turn's 128
     // Position in the matrix: the row is the lane's own (its chunk's); the input-feature offset kk
     // is that of the group's first chunk, which all 16 chunks share -- lanes without a chunk use
     // it too, because every lane supplies activations to A.
@@ -88,14 +124,16 @@ __device__ __forceinline__ void linear_walk(const uint32_t *__restrict__ lut, co
     const uint16_t *xrow[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        uint32_t t = mt * 16 + col;
+        uint32_t t = mt * COLS + col;
         t = t < a.tokens ? t : a.tokens - 1;
         xrow[mt] = a.x + static_cast<uint64_t>(t) * in + ksq + kq;
     }
-    f32x4_t acc[MT];
+    typename Tile::acc_t acc[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
-        acc[mt] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int r = 0; r < Tile::kRegs; ++r)
+            acc[mt][r] = 0.0f;
 
     uint32_t next = LONE ? 0u : src.peek(wp);
     const uint64_t first = base + j * kRun;
@@ -141,20 +179,22 @@ __device__ __forceinline__ void linear_walk(const uint32_t *__restrict__ lut, co
                 bf16x8_t v;
             } av;
             av.q4 = xa[mt];
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.v, b.v, acc[mt], 0, 0, 0);
+            acc[mt] = Tile::mma(av.v, b.v, acc[mt]);
         }
-        // end of a row of the weight (or of the chunk): the partial sums leave for y
+        // end of a row of the weight (or of the chunk): this wave's partial sums leave for y.
+        // (Summing the waves of a group in LDS first was tried: the barriers and the extra
+        // registers cost more than the atomics they save.)
         if (kk_next == 0 || q + 1 == kTurns) {
             const bool col_live = mine && row < a.out_features;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const uint32_t t = mt * 16 + (lane >> 4) * 4 + r;
+                for (int r = 0; r < Tile::kRegs; ++r) {
+                    const uint32_t t = mt * COLS + Tile::row(lane, r);
                     if (col_live && t < a.tokens)
                         atomic_add_f32(a.y + static_cast<uint64_t>(t) * a.out_features + row, acc[mt][r]);
+                    acc[mt][r] = 0.0f;
                 }
-                acc[mt] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
             }
             row += kk_next == 0 ? 1u : 0u;
         }
@@ -166,19 +206,25 @@ __device__ __forceinline__ void linear_walk(const uint32_t *__restrict__ lut, co
     }
 }
 
-template <int KB, int MT>
+template <int KB, int COLS, int MT>
 __global__ __launch_bounds__(kLinThreads) void linear_kernel(const LinearArgs a)
 {
+    constexpr uint32_t kLinGroupChunks = COLS;                       // columns of the B operand
+    constexpr uint32_t kGroupsPerWg = kDecChunksPerWg / COLS;        // 2 or 1
+    constexpr uint32_t kWavesPerGroup = kLinThreads / 64 / kGroupsPerWg;  // 4 or 8
+    constexpr uint32_t kPerWave = 64 / COLS;                         // states of a chunk per wave: 4 or 2
+    constexpr uint32_t kLinGroupBytes = kStageBytes / kGroupsPerWg;  // LDS window of one group's word runs
+    constexpr uint32_t kColsPerWave = COLS / kWavesPerGroup;         // columns a wave copies: 4
     __shared__ __align__(16) uint32_t lut[kM];
     __shared__ __align__(16) uint8_t stage[kStageBytes];
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = tid >> 6, lane = tid & 63u;
-    const uint32_t g = wave >> 2, sq = wave & 3u;
-    const uint32_t col = lane & 15u;
-    const uint32_t j = sq * 4 + (lane >> 4);
-    const uint32_t group = blockIdx.x * 2 + g;
+    const uint32_t g = wave / kWavesPerGroup, sq = wave % kWavesPerGroup;
+    const uint32_t col = lane & (COLS - 1);
+    const uint32_t j = sq * kPerWave + lane / COLS;
+    const uint32_t group = blockIdx.x * kGroupsPerWg + g;
     const bool group_live = group < a.n_groups;
-    // group -> its 16 chunks: `stride` groups interleave inside a block of 16 * stride chunks
+    // group -> its COLS chunks: `stride` groups interleave inside a block of COLS * stride chunks
     const uint32_t block_id = group / a.stride, first_in_block = group % a.stride;
     const uint64_t c64 = static_cast<uint64_t>(block_id) * kLinGroupChunks * a.stride + first_in_block +
                          static_cast<uint64_t>(a.stride) * col;
@@ -204,26 +250,26 @@ __global__ __launch_bounds__(kLinThreads) void linear_kernel(const LinearArgs a)
     for (uint32_t r = 0; r < 2; ++r)
         lut_piece[r] = lut_g[tid + r * kLinThreads];
 
-    // ---- stage the word runs of the group's 16 chunks: each chunk's piece of the blob, from the
+    // ---- stage the word runs of the group's chunks: each chunk's piece of the blob, from the
     // 16-byte boundary below its first word, one after the other in the group's window
     const uint64_t byte0 = static_cast<uint64_t>(off_c) * 2, byte1 = static_cast<uint64_t>(off_c1) * 2;
     const uint64_t aligned0 = byte0 & ~static_cast<uint64_t>(15);
     const uint32_t piece = live ? static_cast<uint32_t>((byte1 - aligned0 + 15) & ~static_cast<uint64_t>(15)) : 0u;
-    uint32_t place = piece;  // exclusive prefix over the 16 columns (lanes with equal lane / 16 agree)
+    uint32_t place = piece;  // exclusive prefix over the columns (lanes with equal lane / COLS agree)
 #pragma unroll
-    for (uint32_t d = 1; d < 16; d <<= 1) {
-        const uint32_t o = __shfl_up(place, d, 16);
+    for (uint32_t d = 1; d < COLS; d <<= 1) {
+        const uint32_t o = __shfl_up(place, d, COLS);
         if (col >= d)
             place += o;
     }
-    const uint32_t group_bytes = __shfl(place, 15, 16);
+    const uint32_t group_bytes = __shfl(place, COLS - 1, COLS);
     place -= piece;
     const bool staged = group_bytes + 16 <= kLinGroupBytes;
     uint8_t *window = stage + g * kLinGroupBytes;
     if (staged && group_live) {
 #pragma unroll
-        for (uint32_t r = 0; r < 4; ++r) {
-            const uint32_t from_col = sq * 4 + r;  // wave sq copies columns 4 sq .. 4 sq + 3
+        for (uint32_t r = 0; r < kColsPerWave; ++r) {
+            const uint32_t from_col = sq * kColsPerWave + r;  // wave sq copies 4 columns
             const uint32_t lo = __shfl(static_cast<uint32_t>(aligned0), from_col, 64);
             const uint32_t hi = __shfl(static_cast<uint32_t>(aligned0 >> 32), from_col, 64);
             const uint32_t len = __shfl(piece, from_col, 64);
@@ -255,13 +301,13 @@ __global__ __launch_bounds__(kLinThreads) void linear_kernel(const LinearArgs a)
 
     uint32_t wp = 0, wp_begin = 0;
     if (lone < 256) {
-        linear_walk<KB, MT, true>(lut, NoWords{}, lone, x, wp, a.sm, a, base, kk0, turns, j, lane);
+        linear_walk<KB, COLS, MT, true>(lut, NoWords{}, lone, x, wp, a.sm, a, base, kk0, turns, j, lane);
     } else if (staged) {
         wp = wp_begin = g * kLinGroupBytes + place + static_cast<uint32_t>(run_byte - aligned0);
-        linear_walk<KB, MT, false>(lut, LdsWords{stage}, 0u, x, wp, a.sm, a, base, kk0, turns, j, lane);
+        linear_walk<KB, COLS, MT, false>(lut, LdsWords{stage}, 0u, x, wp, a.sm, a, base, kk0, turns, j, lane);
     } else {
         const GlobalWords direct{reinterpret_cast<const uint8_t *>(a.words) + run_byte};
-        linear_walk<KB, MT, false>(lut, direct, 0u, x, wp, a.sm, a, base, kk0, turns, j, lane);
+        linear_walk<KB, COLS, MT, false>(lut, direct, 0u, x, wp, a.sm, a, base, kk0, turns, j, lane);
     }
     if (live && (x != kRansL || wp - wp_begin != 2 * len))
         atomicOr(a.status, 1u);
