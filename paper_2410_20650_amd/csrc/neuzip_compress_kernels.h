@@ -749,7 +749,10 @@ __global__ __launch_bounds__(kScanThreads) void offsets_kernel(const CompressBat
 
 // ------------------------------------------------------------------------------------------
 // Kernel 5: gather the runs from the workspace slots into the blob's word section and write the
-// chunk offsets.  One wave per chunk; the 16 runs are read with all loads in flight, then written.
+// chunk offsets.  One wave per chunk.  The chunk's slot pieces are read with 128-bit loads and
+// laid out in LDS as the 16 runs one after the other, shifted so that LDS and destination agree
+// modulo 16 bytes; the chunk then leaves with 128-bit stores (2-byte stores only for the few
+// words before the first and after the last 16-byte boundary, which neighbouring chunks share).
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kCompactThreads = 256;
 
@@ -768,46 +771,74 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const Compress
     const uint32_t *__restrict__ chunk_words = chunk_words_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup;
     const uint64_t *__restrict__ group_prefix = group_prefix_all + it.group_base;
 
-    const uint32_t c = slot_id.wg * (kCompactThreads / 64) + threadIdx.x / 64;
-    const uint32_t lane = threadIdx.x & 63;
-    if (c >= n_chunks)
+    __shared__ __align__(16) uint16_t gathered[kCompactThreads / 64][kStates * kRunCap + 8];
+    const uint32_t wave = threadIdx.x / 64, lane = threadIdx.x & 63;
+    const uint32_t c = slot_id.wg * (kCompactThreads / 64) + wave;
+    const bool live = c < n_chunks;   // (no early return: the workgroup meets at a barrier)
+    const uint32_t j = lane & 15;     // the lane's state: lanes 64 apart in the piece loop keep it
+    uint16_t *__restrict__ mine = gathered[wave];
+    uint32_t total = 0, shift = 0;
+    uint64_t at0 = 0;
+    if (live) {
+        const uint16_t *__restrict__ chunk_slots = slots + static_cast<uint64_t>(c) * kStates * kRunCap;
+        // run length of state j and its start inside the chunk (16-lane exclusive prefix)
+        const uint32_t my_len = lens[c * kStates + j];
+        uint32_t start = my_len;
+#pragma unroll
+        for (uint32_t d = 1; d < kStates; d <<= 1) {
+            const uint32_t o = __shfl_up(start, d, kStates);
+            if (j >= d)
+                start += o;
+        }
+        total = __shfl(start, kStates - 1, kStates);
+        start -= my_len;
+        // words before this chunk: those before its encoder group plus the earlier chunks of the group
+        const uint32_t g = c / kChunksPerGroup, in_group = c % kChunksPerGroup;
+        uint32_t earlier = lane < in_group ? chunk_words[g * kChunksPerGroup + lane] : 0u;
+#pragma unroll
+        for (uint32_t d = 1; d < kChunksPerGroup; d <<= 1)
+            earlier += __shfl_xor(earlier, d, kChunksPerGroup);
+        at0 = group_prefix[g] + __shfl(earlier, 0, 64);
+        if (lane == 0)
+            offsets[c] = static_cast<uint32_t>(at0);
+        shift = static_cast<uint32_t>(at0 & 7u);
+
+        // slot pieces (8 words of one state) from the lowest piece any state reached up to the top
+        const uint32_t first_pos = kRunCap - my_len;   // position of the run's first word in its slot
+        uint32_t low_piece = first_pos >> 3;
+#pragma unroll
+        for (uint32_t d = 1; d < kStates; d <<= 1) {
+            const uint32_t o = __shfl_xor(low_piece, d, kStates);
+            low_piece = o < low_piece ? o : low_piece;
+        }
+        const uint32_t n_pieces = (kRunCap / 8 - low_piece) * kStates;
+        for (uint32_t p = lane; p < n_pieces; p += 64) {
+            const uint32_t piece = low_piece + p / kStates;
+            if (piece * 8 + 7 < first_pos)
+                continue;  // wholly before this state's run
+            const uint4 v = *reinterpret_cast<const uint4 *>(chunk_slots + slot_word(j, piece * 8));
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (uint32_t t = 0; t < 8; ++t) {
+                const uint32_t pos = piece * 8 + t;
+                if (pos >= first_pos)
+                    mine[shift + start + (pos - first_pos)] = static_cast<uint16_t>(w[t >> 1] >> (16 * (t & 1)));
+            }
+        }
+    }
+    __syncthreads();
+    if (!live)
         return;
-    const uint16_t *__restrict__ chunk_slots = slots + static_cast<uint64_t>(c) * kStates * kRunCap;
-    // run length of state (lane mod 16) and its start inside the chunk (16-lane exclusive prefix)
-    const uint32_t my_len = lens[c * kStates + (lane & 15)];
-    uint32_t start = my_len;
-#pragma unroll
-    for (uint32_t d = 1; d < kStates; d <<= 1) {
-        const uint32_t o = __shfl_up(start, d, kStates);
-        if ((lane & 15) >= d)
-            start += o;
-    }
-    start -= my_len;
-    uint16_t v[kStates];
-    uint32_t len_j[kStates], start_j[kStates];
-#pragma unroll
-    for (uint32_t j = 0; j < kStates; ++j) {
-        len_j[j] = __shfl(my_len, j, 64);
-        start_j[j] = __shfl(start, j, 64);
-        v[j] = lane < len_j[j] ? chunk_slots[slot_word(j, kRunCap - len_j[j] + lane)] : static_cast<uint16_t>(0);
-    }
-    // words before this chunk: those before its encoder group plus the earlier chunks of the group
-    const uint32_t g = c / kChunksPerGroup, in_group = c % kChunksPerGroup;
-    uint32_t earlier = lane < in_group ? chunk_words[g * kChunksPerGroup + lane] : 0u;
-#pragma unroll
-    for (uint32_t d = 1; d < kChunksPerGroup; d <<= 1)
-        earlier += __shfl_xor(earlier, d, kChunksPerGroup);
-    const uint64_t at0 = group_prefix[g] + __shfl(earlier, 0, 64);
-    if (lane == 0)
-        offsets[c] = static_cast<uint32_t>(at0);
-#pragma unroll
-    for (uint32_t j = 0; j < kStates; ++j)
-        if (lane < len_j[j])
-            words[at0 + start_j[j] + lane] = v[j];
-    // runs longer than a wave (more than 4 bits per symbol): the rest, run by run
-    for (uint32_t j = 0; j < kStates; ++j)
-        for (uint32_t i = lane + 64; i < len_j[j]; i += 64)
-            words[at0 + start_j[j] + i] = chunk_slots[slot_word(j, kRunCap - len_j[j] + i)];
+    uint16_t *__restrict__ out = words + at0;
+    const uint32_t head = total < ((8 - shift) & 7u) ? total : ((8 - shift) & 7u);  // words up to the 16-byte boundary
+    if (lane < head)
+        out[lane] = mine[shift + lane];
+    const uint32_t n_body = (total - head) / 8;
+    for (uint32_t p = lane; p < n_body; p += 64)
+        *reinterpret_cast<uint4 *>(out + head + 8 * p) = *reinterpret_cast<const uint4 *>(mine + shift + head + 8 * p);
+    const uint32_t tail = total - head - 8 * n_body;
+    if (lane < tail)
+        out[head + 8 * n_body + lane] = mine[shift + head + 8 * n_body + lane];
 }
 
 }  // namespace nz
