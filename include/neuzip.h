@@ -22,6 +22,9 @@
  *   - Errors are reported through the return code only (no exceptions, no
  *     aborts, nothing is printed).  On error no output argument is modified
  *     unless stated otherwise.
+ *   - A blob belongs to the device that was current when it was created; every
+ *     call that launches work on it must be made with that device current
+ *     (NEUZIP_EINVAL otherwise).  neuzip_free may be called from any device.
  *   - Calls that touch different blobs may run concurrently from different
  *     host threads; compress calls are serialised inside the library because
  *     they share one per-device workspace.

@@ -135,6 +135,14 @@ inline uint8_t *sm_of(const neuzip_blob *b) { return b->fixed + b->at.sm; }
 inline uint8_t *coef_of(const neuzip_blob *b) { return b->fixed + b->at.coef; }
 inline bool is_blob(const neuzip_blob *b) { return b && b->magic == kBlobMagic; }
 
+// A blob lives on the device that was current when it was made; kernels are launched on the
+// current device, so the two must agree.
+inline bool on_current_device(const neuzip_blob *b)
+{
+    int cur = -1;
+    return hipGetDevice(&cur) == hipSuccess && cur == b->device;
+}
+
 // Per-process compress workspace: histogram bins and encoder constants for the tensors of a batch,
 // per-chunk / per-group word counts, run slots, and pinned host memory for the results.
 struct Workspace {
@@ -673,7 +681,7 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
         return NEUZIP_EINVAL;
     for (uint32_t i = 0; i < count; ++i) {
         const neuzip_blob *b = blobs[i];
-        if (!is_blob(b) || !b->has_table)
+        if (!is_blob(b) || !b->has_table || !on_current_device(b))
             return NEUZIP_EINVAL;
         if (b->n > 0 && (!d_srcs[i] || (reinterpret_cast<uintptr_t>(d_srcs[i]) & 15u)))
             return NEUZIP_EINVAL;
@@ -718,7 +726,7 @@ uint32_t neuzip_guard(const neuzip_blob *blob) { return is_blob(blob) ? blob->gu
 int neuzip_linear(const neuzip_blob *weight, uint64_t out_features, uint64_t in_features, const void *d_x,
                   uint32_t tokens, const float *d_bias, float *d_y, void *hip_stream)
 {
-    if (!is_blob(weight) || !weight->has_table || !d_x || !d_y)
+    if (!is_blob(weight) || !weight->has_table || !on_current_device(weight) || !d_x || !d_y)
         return NEUZIP_EINVAL;
     if (out_features == 0 || in_features == 0 || in_features % kTurn != 0 || in_features >= (1ull << 31) ||
         out_features >= (1ull << 31) || out_features * in_features != weight->n)
@@ -790,7 +798,8 @@ int compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t 
         if (n_elems[i] >= (1ull << 32))
             return NEUZIP_EUNSUPPORTED;
         const neuzip_blob *b = blobs[i];
-        if (b && (!is_blob(b) || b->n != n_elems[i] || b->k != mantissa_bits || b->block != block_size))
+        if (b && (!is_blob(b) || b->n != n_elems[i] || b->k != mantissa_bits || b->block != block_size ||
+                  !on_current_device(b)))
             return NEUZIP_EINVAL;
         for (uint32_t j = 0; j < i; ++j)
             if (b && blobs[j] == b)
@@ -813,7 +822,7 @@ extern "C" {
 
 int neuzip_decompress(const neuzip_blob *blob, void *d_dst, uint64_t n_elems, int dtype, void *hip_stream)
 {
-    if (!is_blob(blob) || dtype != NEUZIP_BF16 || blob->n != n_elems)
+    if (!is_blob(blob) || dtype != NEUZIP_BF16 || blob->n != n_elems || !on_current_device(blob))
         return NEUZIP_EINVAL;
     if (n_elems > 0 && (!d_dst || (reinterpret_cast<uintptr_t>(d_dst) & 15u)))
         return NEUZIP_EINVAL;
@@ -828,7 +837,8 @@ int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, 
     if (reinterpret_cast<uintptr_t>(d_scratch) & 15u)
         return NEUZIP_EINVAL;
     for (uint32_t i = 0; i < count; ++i) {
-        if (!is_blob(blobs[i]) || blobs[i]->n > scratch_elems || (blobs[i]->n > 0 && !d_scratch))
+        if (!is_blob(blobs[i]) || blobs[i]->n > scratch_elems || (blobs[i]->n > 0 && !d_scratch) ||
+            !on_current_device(blobs[i]))
             return NEUZIP_EINVAL;
     }
     for (uint32_t i = 0; i < count; ++i) {
@@ -844,7 +854,7 @@ int neuzip_decompress_batch(const neuzip_blob *const *blobs, void *const *d_dsts
     if (count > 0 && (!blobs || !d_dsts))
         return NEUZIP_EINVAL;
     for (uint32_t i = 0; i < count; ++i) {
-        if (!is_blob(blobs[i]))
+        if (!is_blob(blobs[i]) || !on_current_device(blobs[i]))
             return NEUZIP_EINVAL;
         if (blobs[i]->n > 0 && (!d_dsts[i] || (reinterpret_cast<uintptr_t>(d_dsts[i]) & 15u)))
             return NEUZIP_EINVAL;
@@ -923,7 +933,7 @@ int neuzip_mantissa_bits(const neuzip_blob *blob) { return is_blob(blob) ? blob-
 
 int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *written, void *hip_stream)
 {
-    if (!is_blob(blob))
+    if (!is_blob(blob) || (h_buf && !on_current_device(blob)))
         return NEUZIP_EINVAL;
     const Container lay = container_layout(blob->n, blob->k, blob->total_words, blob->block);
     if (written)
@@ -1098,7 +1108,7 @@ int neuzip_frequencies(const neuzip_blob *blob, uint16_t h_freq[256])
 
 int neuzip_check(const neuzip_blob *blob, void *hip_stream)
 {
-    if (!is_blob(blob))
+    if (!is_blob(blob) || !on_current_device(blob))
         return NEUZIP_EINVAL;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     uint32_t flag = 0;

@@ -354,3 +354,40 @@ def test_damaged_words_are_reported_by_check(nz):
         nz.neuzip_check(blob)
     assert e.value.code == nz.ECORRUPT
     nz.neuzip_check(blob)  # flag is cleared by the report
+
+
+def test_host_threads_on_their_own_streams(nz):
+    # calls that touch different blobs may come from different host threads: four threads, each
+    # with its own stream and tensors, compress (serialised inside the library: one workspace),
+    # recompress and decompress at the same time; every result is checked against the oracle's
+    import threading
+    errors = []
+
+    def worker(idx):
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for rep in range(6):
+                    n = 50_000 + 4099 * idx + 17 * rep
+                    w = inputs.gaussian_bf16(n, 7700 + 10 * idx + rep, device=DEV)
+                    stream.synchronize()
+                    blob = nz.neuzip_compress(w, 7 if rep % 2 == 0 else 3, stream)
+                    out = torch.empty_like(w)
+                    nz.neuzip_decompress(blob, out, stream)
+                    nz.neuzip_check(blob, stream)
+                    k = blob.mantissa_bits
+                    if not np.array_equal(inputs.bits(out), O.truncate(inputs.bits(w), k)):
+                        errors.append((idx, rep, "values"))
+                    if not np.array_equal(nz.neuzip_export(blob, stream), O.compress(inputs.bits(w), k)):
+                        errors.append((idx, rep, "container"))
+                    nz.neuzip_free(blob)
+        except Exception as exc:                                # surfaced in the main thread
+            errors.append((idx, repr(exc)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads)
+    assert errors == []
