@@ -128,3 +128,31 @@ def test_linear_argument_errors(nz):
     assert lib.neuzip_linear(lossy.handle, 32, 256, ctypes.c_void_p(x.data_ptr()), 4, None,
                              ctypes.c_void_p(y.data_ptr()), None) == nz.EUNSUPPORTED
     torch.cuda.synchronize()
+
+
+def test_linear_can_be_captured_in_a_hip_graph(nz):
+    # the fused layer allocates nothing and clears y with a kernel, not a memset node: a decoding
+    # step can be captured once and replayed; every replay is checked against the eager result
+    out_f, in_f, tokens = 256, 4096, 4
+    w = inputs.gaussian_bf16(out_f * in_f, 9700, device=DEV)
+    blob = nz.neuzip_compress(w, 7)
+    x = inputs.gaussian_bf16((tokens, in_f), 9701, std=1.0, device=DEV)
+    bias = torch.linspace(-1, 1, out_f, dtype=torch.float32, device=DEV)
+    y = torch.zeros((tokens, out_f), dtype=torch.float32, device=DEV)
+    eager = nz.neuzip_linear(blob, out_f, in_f, x, bias).clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        nz.neuzip_linear(blob, out_f, in_f, x, bias, y, stream=side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            nz.neuzip_linear(blob, out_f, in_f, x, bias, y, stream=side)
+    for replay in range(4):
+        y.fill_(float("nan"))                                       # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        # the order of the float atomics may differ from run to run: a few ulps of the sums
+        assert torch.allclose(y, eager, rtol=0, atol=1e-5 * eager.abs().max().item()), replay
+    nz.neuzip_check(blob)
