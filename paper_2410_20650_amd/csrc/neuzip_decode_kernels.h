@@ -121,10 +121,12 @@ template <int KB, bool LONE, bool NORM, bool STREAM, class WordSrc>
 __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
                                            uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
                                            const uint8_t *__restrict__ coef, uint32_t block,
-                                           uint64_t (&fields)[kTurnGroup], uint16_t *__restrict__ out,
+                                           uint64_t (&fields)[KB == 7 ? kTurnGroupStream : kTurnGroup],
+                                           uint16_t *__restrict__ out,
                                            uint64_t base, uint32_t m, uint32_t j)
 {
-    // `fields` arrives holding the field bits of the state's first kTurnGroup turns (full chunks only)
+    // `fields` arrives holding the field bits of the state's first turns (full chunks only)
+    constexpr uint32_t kGroup = (STREAM && KB == 7) ? kTurnGroupStream : kTurnGroup;
     uint32_t next = LONE ? 0u : src.peek(wp);
     if (m == kChunk) {
         uint4 *out4 = reinterpret_cast<uint4 *>(out + base) + j;
@@ -132,17 +134,17 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
         // Turns are taken in groups: the field loads of the next group are issued together before
         // the current group is decoded, and the group's 128-bit stores leave back to back, so
         // each state keeps several memory requests in flight and a chunk is written in bursts of
-        // kTurnGroup * 256 contiguous bytes.
-        for (uint32_t q0 = 0; q0 < kTurns; q0 += kTurnGroup) {
-            uint64_t fields_next[kTurnGroup];
+        // kGroup * 256 contiguous bytes.
+        for (uint32_t q0 = 0; q0 < kTurns; q0 += kGroup) {
+            uint64_t fields_next[kGroup];
             // the last group re-reads its own fields (stays in bounds)
-            const uint32_t qn = q0 + kTurnGroup < kTurns ? q0 + kTurnGroup : q0;
+            const uint32_t qn = q0 + kGroup < kTurns ? q0 + kGroup : q0;
 #pragma unroll
-            for (uint32_t r = 0; r < kTurnGroup; ++r)
+            for (uint32_t r = 0; r < kGroup; ++r)
                 fields_next[r] = load_turn<KB, NORM>(sm, coef, block, first + (qn + r) * kTurn);
-            uint4 o[kTurnGroup];
+            uint4 o[kGroup];
 #pragma unroll
-            for (uint32_t r = 0; r < kTurnGroup; ++r) {
+            for (uint32_t r = 0; r < kGroup; ++r) {
                 uint32_t e[8];
 #pragma unroll
                 for (int t = 0; t < 8; ++t)
@@ -160,7 +162,7 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
                 }
             }
 #pragma unroll
-            for (uint32_t r = 0; r < kTurnGroup; ++r) {
+            for (uint32_t r = 0; r < kGroup; ++r) {
                 uint4 *dst = &out4[(q0 + r) * kStates];
                 if constexpr (STREAM) {
                     // a tensor larger than the last-level cache: non-temporal stores
@@ -244,9 +246,10 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
     uint32_t x = live ? states[id] : kRansL;
     const uint32_t len = live ? lens[id] : 0u;
     const uint32_t lone = tb->lone;
-    uint64_t fields0[kTurnGroup];
+    constexpr uint32_t kPreload = KB == 7 ? kTurnGroupStream : kTurnGroup;  // the largest group a variant uses
+    uint64_t fields0[kPreload];
 #pragma unroll
-    for (uint32_t r = 0; r < kTurnGroup; ++r)
+    for (uint32_t r = 0; r < kPreload; ++r)
         fields0[r] = m == kChunk ? load_turn<KB, NORM>(sm, coef, block, base + r * kTurn + j * kRun) : 0;
     const uint4 *lut_g = reinterpret_cast<const uint4 *>(tb->lut);
     uint4 lut_piece[2];  // 16 KB table / 16 B = 1024 pieces; 2 per thread at 512 threads

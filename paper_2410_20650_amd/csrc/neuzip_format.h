@@ -27,12 +27,13 @@ constexpr uint32_t kDecThreads = 512;
 constexpr uint32_t kDecChunksPerWg = kDecThreads / kStates;   // 32
 // LDS: 16 KB slot table + staged word runs.  Two workgroups share a CU's 160 KB.
 constexpr uint32_t kStageBytes = 62 * 1024;
-// Turns (of 8 symbols per state) whose loads and stores are issued together.
-#ifndef NEUZIP_TURN_GROUP
-#define NEUZIP_TURN_GROUP 2
-#endif
-constexpr uint32_t kTurnGroup = NEUZIP_TURN_GROUP;
-static_assert(kTurns % kTurnGroup == 0, "a chunk is a whole number of turn groups");
+// Turns (of 8 symbols per state) whose loads and stores are issued together: 2 for tensors that
+// live in the last-level cache and for the lossy widths, 4 for lossless tensors that stream
+// through HBM (more bytes in flight; measured +2-3 % there, -6 % on cache-resident sizes and
+// -7 % on the lossy widths).
+constexpr uint32_t kTurnGroup = 2;
+constexpr uint32_t kTurnGroupStream = 4;
+static_assert(kTurns % kTurnGroup == 0 && kTurns % kTurnGroupStream == 0, "a chunk is a whole number of turn groups");
 
 
 // ------------------------------------------------------------------------------------------
