@@ -73,9 +73,10 @@ __device__ inline void store_fields(uint8_t *sm, uint64_t vec, uint64_t packed)
 // IEEE binary32 arithmetic, results rounded to the nearest-even bf16; NaNs are passed through
 // with the quiet bit set, without going through the FP unit.
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t bf16_round_bits(uint32_t bits32)
+// binary32 -> bf16, round to nearest even: the conversion instruction of gfx950
+__device__ __forceinline__ uint32_t bf16_of(float v)
 {
-    return (bits32 + 0x7FFFu + ((bits32 >> 16) & 1u)) >> 16;
+    return __builtin_bit_cast(uint16_t, static_cast<__bf16>(v));
 }
 
 __device__ __forceinline__ bool bf16_is_nan(uint32_t u) { return (u & 0x7FFFu) > 0x7F80u; }
@@ -84,14 +85,14 @@ __device__ __forceinline__ uint32_t normalise_word(uint32_t u, float c)
 {
     if (bf16_is_nan(u))
         return u | 0x40u;
-    return bf16_round_bits(__float_as_uint(__uint_as_float(u << 16) / c)) & 0xFFFFu;
+    return bf16_of(__uint_as_float(u << 16) / c);
 }
 
 __device__ __forceinline__ uint32_t denormalise_word(uint32_t u, float c)
 {
     if (bf16_is_nan(u))
         return u | 0x40u;
-    return bf16_round_bits(__float_as_uint(__fmul_rn(__uint_as_float(u << 16), c))) & 0xFFFFu;
+    return bf16_of(__fmul_rn(__uint_as_float(u << 16), c));
 }
 
 __device__ __forceinline__ float coefficient(uint32_t coef) { return 1.0f + static_cast<float>(coef) * 0.0078125f; }
@@ -220,6 +221,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const Com
 
     const uint32_t copy = threadIdx.x & (kHistCopies - 1);
     const uint32_t lanes_per_block = block / 8;                 // 4 .. 64, a power of two
+    const uint32_t block_shift = 31u - static_cast<uint32_t>(__clz(static_cast<int>(block)));
     const uint64_t n_vec = (n + 7) / 8;                         // the last vector may be partial
     const uint64_t stride = static_cast<uint64_t>(slot.wgs) * kHistThreads;
     constexpr uint32_t per_byte = 8 / (KB + 1);
@@ -245,7 +247,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const Com
         }
         // key = magnitude | earliest position wins ties | mantissa of that weight
         uint32_t key = 0;
-        const uint32_t pos0 = static_cast<uint32_t>(first % block);
+        const uint32_t pos0 = static_cast<uint32_t>(first & (block - 1));  // block sizes are powers of two
 #pragma unroll
         for (uint32_t t = 0; t < 8; ++t) {
             const uint32_t cand = ((w[t] & 0x7FFFu) << 16) | ((511u - (pos0 + t)) << 7) | (w[t] & 0x7Fu);
@@ -257,7 +259,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const Com
         }
         const uint32_t coef = key & 0x7Fu;
         if (valid && pos0 == 0)
-            coef_out[first / block] = static_cast<uint8_t>(coef);
+            coef_out[first >> block_shift] = static_cast<uint8_t>(coef);
         const float c = coefficient(coef);
         uint64_t packed = 0;
 #pragma unroll
@@ -551,7 +553,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     const uint16_t *__restrict__ src = it.src;
     const uint64_t n = it.n;
     const uint8_t *__restrict__ coef = it.coef;
-    const uint32_t block = NORM ? it.block : 1u;
+    const uint32_t block_shift = NORM ? 31u - static_cast<uint32_t>(__clz(static_cast<int>(it.block | 1u))) : 0u;
     const uint32_t n_chunks = it.n_chunks;
     const TableBlock *__restrict__ tb = it.tb;
     uint32_t *__restrict__ states = it.states;
@@ -600,7 +602,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
             // with block-wise normalisation the exponents coded are those of bf16(w / c)
             float c = 1.0f;
             if constexpr (NORM)
-                c = coefficient(coef[(base + static_cast<uint32_t>(q) * kTurn + j * kRun) / block]);
+                c = coefficient(coef[(base + static_cast<uint32_t>(q) * kTurn + j * kRun) >> block_shift]);
 #pragma unroll
             for (int p = 3; p >= 0; --p) {
                 const uint32_t hi = NORM ? normalise_word(w[p] >> 16, c) : (w[p] >> 16);
@@ -624,7 +626,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
                 if (i < m) {
                     uint32_t u = src[base + i];
                     if constexpr (NORM)
-                        u = normalise_word(u, coefficient(coef[(base + i) / block]));
+                        u = normalise_word(u, coefficient(coef[(base + i) >> block_shift]));
                     const EncSym e = enc[exponent_of(u)];
                     if constexpr (SPLIT >= 0) {
                         least_rcp = fminf(least_rcp, e.rcp);

@@ -103,18 +103,27 @@ __device__ __forceinline__ uint32_t rans_get(const uint32_t *__restrict__ lut, u
 // take at most 32 bits) the block's coefficient byte rides in bits 32..39.
 template <int KB, bool NORM>
 __device__ __forceinline__ uint64_t load_turn(const uint8_t *__restrict__ sm, const uint8_t *__restrict__ coef,
-                                              uint32_t block, uint64_t first_elem)
+                                              uint32_t block, uint64_t first_elem)  // block: log2 of the block size
 {
     uint64_t f = load_fields<KB>(sm, first_elem);
     if constexpr (NORM)
-        f |= static_cast<uint64_t>(coef[first_elem / block]) << 32;
+        f |= static_cast<uint64_t>(coef[first_elem >> block]) << 32;  // `block` is log2 of the block size here
     return f;
 }
 
-// bf16(stored * c) on the two halves of a merged dword
+// bf16(stored * c) on the two halves of a merged dword: two multiplies, one packed conversion;
+// a NaN keeps its bits and gets the quiet bit, as in denormalise_word
 __device__ __forceinline__ uint32_t denormalise_pair(uint32_t d, float c)
 {
-    return denormalise_word(d & 0xFFFFu, c) | (denormalise_word(d >> 16, c) << 16);
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
+    const f32x2_t prod = {__fmul_rn(__uint_as_float(d << 16), c), __fmul_rn(__uint_as_float(d & 0xFFFF0000u), c)};
+    uint32_t r = __builtin_bit_cast(uint32_t, __builtin_convertvector(prod, bf16x2_t));
+    if (bf16_is_nan(d & 0xFFFFu))
+        r = (r & 0xFFFF0000u) | (d & 0xFFFFu) | 0x40u;
+    if (bf16_is_nan(d >> 16))
+        r = (r & 0x0000FFFFu) | (d & 0xFFFF0000u) | 0x400000u;
+    return r;
 }
 
 template <int KB, bool LONE, bool NORM, bool STREAM, class WordSrc>
@@ -189,7 +198,7 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
                 const uint32_t field = (sm[g / per_byte] >> ((g % per_byte) * width)) & ((1u << width) - 1u);
                 uint32_t u = ((field >> KB) << 15) | (sym << 7) | ((field & ((1u << KB) - 1u)) << (7 - KB));
                 if constexpr (NORM)
-                    u = denormalise_word(u, coefficient(coef[g / block]));
+                    u = denormalise_word(u, coefficient(coef[g >> block]));
                 out[g] = static_cast<uint16_t>(u);
             }
         }
@@ -227,6 +236,7 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
                                                  uint64_t n, uint32_t n_chunks, uint32_t *__restrict__ status,
                                                  uint32_t wg, uint32_t *__restrict__ lut, uint8_t *__restrict__ stage)
 {
+    block = 31u - static_cast<uint32_t>(__clz(static_cast<int>(block | 1u)));  // a power of two: from here on its log2
     const uint32_t tid = threadIdx.x;
     const uint32_t threads = blockDim.x;            // a multiple of 64, at most kDecThreads
     const uint32_t chunks_per_wg = threads / kStates;
