@@ -431,7 +431,7 @@ uint64_t nzo_compress_bound(uint64_t n, int k)
 {
     uint64_t nc = chunks_of(n);
     return NZO_HEADER_BYTES + 512 + pad16((nc + 1) * 4) + nc * NZO_K * 4 + nc * NZO_K +
-           pad16(nc * NZO_K * NZO_RUN_CAP * 2) + pad16(nzo_signmant_bytes(n, k)) + pad16(nzo_block_count(n, 32));
+           pad16(nc * NZO_K * NZO_RUN_CAP * 2) + pad16(nzo_signmant_bytes(n, k)) + pad16(nzo_block_count(n, 32)) + pad16(n * 2);
 }
 
 typedef struct {
@@ -466,13 +466,13 @@ static void *enc_worker(void *arg)
 }
 
 static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, const uint8_t *coef,
-                         const uint16_t *given_freq, uint32_t guard, uint8_t *blob, uint64_t cap,
+                         const uint16_t *given_freq, uint32_t guard, const uint16_t *low, uint8_t *blob, uint64_t cap,
                          uint64_t *written, int threads);
 
 int nzo_compress(const uint16_t *w, uint64_t n, int k, uint8_t *blob, uint64_t cap,
                  uint64_t *written, int threads)
 {
-    return compress_impl(w, n, k, 0, NULL, NULL, 0, blob, cap, written, threads);
+    return compress_impl(w, n, k, 0, NULL, NULL, 0, NULL, blob, cap, written, threads);
 }
 
 /* The table keeps a guard band (nzo_quantise_guarded); header word 52 records the guard. */
@@ -481,7 +481,7 @@ int nzo_compress_guarded(const uint16_t *w, uint64_t n, int k, uint32_t guard, u
 {
     if (guard > 255)
         return NZO_EINVAL;
-    return compress_impl(w, n, k, 0, NULL, NULL, guard, blob, cap, written, threads);
+    return compress_impl(w, n, k, 0, NULL, NULL, guard, NULL, blob, cap, written, threads);
 }
 
 /* Compression with a table that was made earlier (from the weights before an update): no
@@ -502,7 +502,7 @@ int nzo_compress_with_table(const uint16_t *w, uint64_t n, int k, const uint16_t
     for (int s = 0; s < 256; s++)
         if (cnt[s] > 0 && freq[s] == 0)
             return NZO_ESTALE;
-    return compress_impl(w, n, k, 0, NULL, freq, guard, blob, cap, written, threads);
+    return compress_impl(w, n, k, 0, NULL, freq, guard, NULL, blob, cap, written, threads);
 }
 
 /* Lossy variant with block-wise normalisation: the coefficients are taken from the original
@@ -522,14 +522,14 @@ int nzo_compress_blockwise(const uint16_t *w, uint64_t n, int k, uint32_t block,
     }
     nzo_block_coefficients(w, n, block, coef);
     nzo_normalise(w, n, block, coef, normal);
-    int rc = compress_impl(normal, n, k, block, coef, NULL, 0, blob, cap, written, threads);
+    int rc = compress_impl(normal, n, k, block, coef, NULL, 0, NULL, blob, cap, written, threads);
     free(coef);
     free(normal);
     return rc;
 }
 
 static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, const uint8_t *coef,
-                         const uint16_t *given_freq, uint32_t guard, uint8_t *blob, uint64_t cap,
+                         const uint16_t *given_freq, uint32_t guard, const uint16_t *low, uint8_t *blob, uint64_t cap,
                          uint64_t *written, int threads)
 {
     if (!valid_k(k) || n >= ((uint64_t)1 << 32))
@@ -598,7 +598,8 @@ static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, c
     uint64_t off_lens = off_states + nc * NZO_K * 4;
     uint64_t off_words = off_lens + nc * NZO_K;
     uint64_t off_sm = off_words + pad16(total_words * 2);
-    uint64_t off_coef = off_sm + pad16(sm_bytes);
+    uint64_t off_low = off_sm + pad16(sm_bytes);
+    uint64_t off_coef = off_low + (low ? pad16(n * 2) : 0);
     uint64_t size = off_coef + pad16(nzo_block_count(n, block));
     if (written)
         *written = size;
@@ -640,7 +641,11 @@ static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, c
         }
     }
     put32(blob + off_offsets + 4 * nc, (uint32_t)run);
+    put32(blob + 56, low ? 1u : 0u); /* element type: 0 bf16, 1 binary32 (with a plane of low halves) */
     nzo_pack_signmant(w, n, k, blob + off_sm);
+    if (low)
+        for (uint64_t i = 0; i < n; i++)
+            put16(blob + off_low + 2 * i, low[i]);
     if (block)
         memcpy(blob + off_coef, coef, nzo_block_count(n, block));
 
@@ -654,6 +659,8 @@ typedef struct {
     uint64_t n, nc, total_words;
     int k;
     uint32_t block;
+    uint32_t f32; /* element type is binary32: a plane of low halves follows the sign|mantissa stream */
+    const uint8_t *low;
     const uint8_t *freq, *offsets, *states, *lens, *words, *sm, *coef;
 } blob_view;
 
@@ -681,7 +688,11 @@ static int open_blob(const uint8_t *blob, uint64_t len, blob_view *v)
     uint64_t off_lens = off_states + v->nc * NZO_K * 4;
     uint64_t off_words = off_lens + v->nc * NZO_K;
     uint64_t off_sm = off_words + pad16(v->total_words * 2);
-    uint64_t off_coef = off_sm + pad16(nzo_signmant_bytes(v->n, v->k));
+    v->f32 = get32(blob + 56);
+    if (v->f32 > 1 || (v->f32 && (v->k != 7 || v->block != 0)))
+        return NZO_ECORRUPT;
+    uint64_t off_low = off_sm + pad16(nzo_signmant_bytes(v->n, v->k));
+    uint64_t off_coef = off_low + (v->f32 ? pad16(v->n * 2) : 0);
     uint64_t size = off_coef + pad16(nzo_block_count(v->n, v->block));
     if (size != len)
         return NZO_ECORRUPT;
@@ -691,6 +702,7 @@ static int open_blob(const uint8_t *blob, uint64_t len, blob_view *v)
     v->lens = blob + off_lens;
     v->words = blob + off_words;
     v->sm = blob + off_sm;
+    v->low = blob + off_low;
     v->coef = blob + off_coef;
     return NZO_OK;
 }
@@ -778,13 +790,13 @@ static void *dec_worker(void *arg)
     return NULL;
 }
 
-int nzo_decompress(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n, int threads)
+static int decompress_halves(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n, int threads, uint32_t want_f32)
 {
     blob_view v;
     int rc = open_blob(blob, len, &v);
     if (rc != NZO_OK)
         return rc;
-    if (v.n != n)
+    if (v.n != n || v.f32 != want_f32)
         return NZO_EINVAL;
     if (get32(v.offsets) != 0 || get32(v.offsets + 4 * v.nc) != v.total_words)
         return NZO_ECORRUPT;
@@ -820,5 +832,53 @@ int nzo_decompress(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n,
     free(tid);
     if (rc == NZO_OK && v.block)
         nzo_denormalise(out, n, v.block, v.coef, out);
+    return rc;
+}
+
+int nzo_decompress(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n, int threads)
+{
+    return decompress_halves(blob, len, out, n, threads, 0);
+}
+
+/* ------------------------------------------------------------------ */
+/* binary32 tensors (the paper works on BFloat16 only, Sec. 2.1).       */
+/* The upper half of a binary32 word is a bf16 word: sign, the same 8   */
+/* exponent bits, the 7 leading mantissa bits.  It goes through the     */
+/* path above unchanged (lossless only); the lower halves, 16 further   */
+/* mantissa bits that do not compress, are stored as they are in a      */
+/* plane of their own after the sign|mantissa stream.                   */
+/* ------------------------------------------------------------------ */
+int nzo_compress_f32(const uint32_t *w, uint64_t n, uint8_t *blob, uint64_t cap, uint64_t *written, int threads)
+{
+    uint16_t *high = (uint16_t *)malloc((size_t)(n + 1) * sizeof(uint16_t));
+    uint16_t *low = (uint16_t *)malloc((size_t)(n + 1) * sizeof(uint16_t));
+    if (!high || !low) {
+        free(high);
+        free(low);
+        return NZO_ENOSPACE;
+    }
+    for (uint64_t i = 0; i < n; i++) {
+        high[i] = (uint16_t)(w[i] >> 16);
+        low[i] = (uint16_t)(w[i] & 0xFFFF);
+    }
+    int rc = compress_impl(high, n, 7, 0, NULL, NULL, 0, low, blob, cap, written, threads);
+    free(high);
+    free(low);
+    return rc;
+}
+
+int nzo_decompress_f32(const uint8_t *blob, uint64_t len, uint32_t *out, uint64_t n, int threads)
+{
+    uint16_t *high = (uint16_t *)malloc((size_t)(n + 1) * sizeof(uint16_t));
+    if (!high)
+        return NZO_ENOSPACE;
+    int rc = decompress_halves(blob, len, high, n, threads, 1);
+    if (rc == NZO_OK) {
+        blob_view v;
+        open_blob(blob, len, &v);
+        for (uint64_t i = 0; i < n; i++)
+            out[i] = ((uint32_t)high[i] << 16) | get16(v.low + 2 * i);
+    }
+    free(high);
     return rc;
 }

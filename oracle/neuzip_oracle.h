@@ -38,9 +38,11 @@
  *   container := header(64 B) | freq[256] u16 | offsets[n_chunks+1] u32
  *              | states[n_chunks*K] u32 | lens[n_chunks*K] u8
  *              | words[total_words] u16 | signmant[ceil(n*(k+1)/8)] u8
+ *              | low[n] u16               (only when header word 56, element type, is 1 = binary32)
  *              | coef[ceil(n/block)] u8   (only when header word 48, block, is not 0)
  *   header: magic u32 @0, version u32 @4, n u64 @8, k @16, PROB_BITS @20, CHUNK @24, K @28,
- *   G @32, n_chunks @36, total_words u64 @40, block @48, guard @52 (u32 unless noted), rest 0.
+ *   G @32, n_chunks @36, total_words u64 @40, block @48, guard @52, element type @56 (u32 unless
+ *   noted), rest 0.
  *   every section is zero-padded to a multiple of 16 bytes.
  *   offsets[c] = number of words that belong to chunks before c.
  *   Inside chunk c the K private runs follow each other, state 0 first;
@@ -131,6 +133,11 @@ int nzo_compress_with_table(const uint16_t *w, uint64_t n, int k, const uint16_t
 int nzo_compress_blockwise(const uint16_t *w, uint64_t n, int k, uint32_t block, uint8_t *blob,
                            uint64_t cap, uint64_t *written, int threads);
 int nzo_decompress(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n, int threads);
+/* binary32 tensors (not in the paper, which uses BFloat16 only): the upper halves go through the
+ * lossless path as bf16 words, the lower halves are stored raw in a plane after the
+ * sign|mantissa stream; header word 56 is 1. */
+int nzo_compress_f32(const uint32_t *w, uint64_t n, uint8_t *blob, uint64_t cap, uint64_t *written, int threads);
+int nzo_decompress_f32(const uint8_t *blob, uint64_t len, uint32_t *out, uint64_t n, int threads);
 /* Reads n, k and the stored frequencies out of a container. */
 int nzo_blob_info(const uint8_t *blob, uint64_t len, uint64_t *n, int *k, uint64_t *total_words,
                   uint16_t freq[256]);

@@ -90,6 +90,10 @@ def lib():
         L.nzo_compress.restype = i32
         L.nzo_decompress.argtypes = [u8p, u64, u16p, u64, i32]
         L.nzo_decompress.restype = i32
+        L.nzo_compress_f32.argtypes = [u32p, u64, u8p, u64, u64p, i32]
+        L.nzo_compress_f32.restype = i32
+        L.nzo_decompress_f32.argtypes = [u8p, u64, u32p, u64, i32]
+        L.nzo_decompress_f32.restype = i32
         L.nzo_blob_info.argtypes = [u8p, u64, u64p, ctypes.POINTER(i32), u64p, u16p]
         L.nzo_blob_info.restype = i32
         _lib = L
@@ -294,6 +298,32 @@ def decompress(blob, n, threads=1):
     return out
 
 
+def compress_f32(w, threads=1):
+    """binary32 words (uint32 array) -> container bytes: upper halves through the lossless bf16 path,
+    lower halves as a raw plane."""
+    w = np.ascontiguousarray(w)
+    if w.dtype != np.uint32:
+        raise TypeError("binary32 words must be passed as uint32")
+    w = w.reshape(-1)
+    cap = int(lib().nzo_compress_bound(w.size, 7))
+    blob = np.empty(cap, np.uint8)
+    written = ctypes.c_uint64(0)
+    rc = lib().nzo_compress_f32(_p(w, ctypes.c_uint32), w.size, _p(blob, ctypes.c_uint8), cap, ctypes.byref(written),
+                                threads)
+    if rc != OK:
+        raise OracleError(rc, "compress_f32")
+    return blob[: written.value].copy()
+
+
+def decompress_f32(blob, n, threads=1):
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    out = np.empty(n, np.uint32)
+    rc = lib().nzo_decompress_f32(_p(blob, ctypes.c_uint8), blob.size, _p(out, ctypes.c_uint32), n, threads)
+    if rc != OK:
+        raise OracleError(rc, "decompress_f32")
+    return out
+
+
 def blob_info(blob):
     blob = np.ascontiguousarray(blob, dtype=np.uint8)
     n, k, tw = ctypes.c_uint64(0), ctypes.c_int(0), ctypes.c_uint64(0)
@@ -310,12 +340,13 @@ def sections(blob):
     info = blob_info(blob)
     n, k, tw = info["n"], info["k"], info["total_words"]
     block = int(np.ascontiguousarray(blob[48:52]).view("<u4")[0])
+    f32 = int(np.ascontiguousarray(blob[56:60]).view("<u4")[0])
     nc = (n + CHUNK - 1) // CHUNK
     pad = lambda v: (v + 15) & ~15
     out, pos = {}, 0
     for name, size in (("header", HEADER_BYTES), ("freq", 512), ("offsets", pad((nc + 1) * 4)),
                        ("states", nc * K * 4), ("lens", nc * K), ("words", pad(tw * 2)),
-                       ("signmant", pad(signmant_bytes(n, k))),
+                       ("signmant", pad(signmant_bytes(n, k))), ("low", pad(2 * n) if f32 else 0),
                        ("coef", pad((n + block - 1) // block) if block else 0)):
         out[name] = (pos, pos + size)
         pos += size

@@ -152,8 +152,9 @@ def scale(words16, block, coef, divide):
     return out
 
 
-def compress(words16, k=7, block=0, guard=0, freq=None):
-    """List of bf16 words -> container bytes.  freq: an earlier table to code with."""
+def compress(words16, k=7, block=0, guard=0, freq=None, low=None):
+    """List of bf16 words -> container bytes.  freq: an earlier table to code with.  low: the lower
+    halves of binary32 words whose upper halves are words16 (stored as a raw plane)."""
     coef = []
     if block:
         coef = block_coefficients(words16, block)
@@ -178,8 +179,8 @@ def compress(words16, k=7, block=0, guard=0, freq=None):
             lens.append(len(run))
             payload.extend(run)
     offsets.append(len(payload))
-    header = struct.pack("<IIQIIIIIIQII", 0x315A554E, 1, n, k, PROB_BITS, CHUNK, K, G, nc, len(payload), block,
-                         guard)
+    header = struct.pack("<IIQIIIIIIQIII", 0x315A554E, 1, n, k, PROB_BITS, CHUNK, K, G, nc, len(payload), block,
+                         guard, 0 if low is None else 1)
     header += bytes(64 - len(header))
     out = header
     out += struct.pack("<256H", *freq)
@@ -188,6 +189,8 @@ def compress(words16, k=7, block=0, guard=0, freq=None):
     out += bytes(lens)
     out += _pad(struct.pack(f"<{len(payload)}H", *payload))
     out += _pad(pack_signmant(words16, k))
+    if low is not None:
+        out += _pad(struct.pack(f"<{n}H", *low))
     if block:
         out += _pad(bytes(coef))
     return out
@@ -195,7 +198,7 @@ def compress(words16, k=7, block=0, guard=0, freq=None):
 
 def decompress(blob):
     """Container bytes -> list of bf16 words."""
-    magic, ver, n, k, pb, chunk, ks, g, nc, tw, block = struct.unpack_from("<IIQIIIIIIQI", blob, 0)
+    magic, ver, n, k, pb, chunk, ks, g, nc, tw, block, _guard, f32 = struct.unpack_from("<IIQIIIIIIQIII", blob, 0)
     assert (magic, ver, pb, chunk, ks, g) == (0x315A554E, 1, PROB_BITS, CHUNK, K, G)
     pos = 64
     freq = list(struct.unpack_from("<256H", blob, pos)); pos += 512
@@ -204,7 +207,9 @@ def decompress(blob):
     lens = blob[pos:pos + nc * K]; pos += nc * K
     payload = struct.unpack_from(f"<{tw}H", blob, pos); pos += (tw * 2 + 15) // 16 * 16
     sm = blob[pos:]
-    coef = list(blob[pos + ((n * (k + 1) + 7) // 8 + 15) // 16 * 16:]) if block else []
+    after_sm = pos + ((n * (k + 1) + 7) // 8 + 15) // 16 * 16
+    low = struct.unpack_from(f"<{n}H", blob, after_sm) if f32 else None
+    coef = list(blob[after_sm:]) if block else []
     width, per = k + 1, 8 // (k + 1)
     out = [0] * n
     for c in range(nc):
@@ -221,4 +226,6 @@ def decompress(blob):
         assert at == offsets[c + 1]
     if block:
         out = scale(out, block, coef, divide=False)
+    if f32:
+        out = [(hi << 16) | lo for hi, lo in zip(out, low)]
     return out

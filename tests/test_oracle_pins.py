@@ -666,3 +666,44 @@ def test_linear_oracle_row_sums_and_linearity():
         assert np.array_equal(whole[t], L.linear(blob, out_f, in_f, x[t:t + 1])[0])
     # negating the activations (flip the bf16 sign bit) negates the output exactly
     assert np.array_equal(L.linear(blob, out_f, in_f, x ^ 0x8000), -whole)
+
+
+# ---------------------------------------------------------------- binary32 tensors (beyond the paper, which uses BFloat16 only)
+
+def test_f32_round_trip_and_layout():
+    rng = np.random.default_rng(77)
+    for n in (0, 1, 9, 4097, 30_000):
+        w = (rng.standard_normal(n) * 0.02).astype(np.float32).view(np.uint32)
+        blob = O.compress_f32(w, threads=3)
+        assert np.array_equal(O.decompress_f32(blob, n, threads=2), w)
+        # the upper halves are a bf16 tensor compressed as usual; the container differs from that
+        # one only by the element-type word and the plane of lower halves, which is stored raw
+        high, low = (w >> 16).astype(np.uint16), (w & 0xFFFF).astype(np.uint16)
+        plain = O.compress(high, 7, threads=3)
+        sec, sec16 = O.sections(blob), O.sections(plain)
+        for name in ("freq", "offsets", "states", "lens", "words", "signmant"):
+            assert np.array_equal(blob[slice(*sec[name])], plain[slice(*sec16[name])]), name
+        lo, hi = sec["low"]
+        assert np.array_equal(blob[lo: lo + 2 * n].view("<u2"), low)
+        assert blob.size == plain.size + (hi - lo)
+        # second statement of the format
+        assert blob.tobytes() == P.compress([int(u) for u in high], 7, low=[int(u) for u in low])
+        assert P.decompress(blob.tobytes()) == [int(u) for u in w]
+        # the two element types do not decode each other's containers
+        with pytest.raises(O.OracleError):
+            O.decompress(blob, n)
+        with pytest.raises(O.OracleError):
+            O.decompress_f32(plain, n)
+
+
+def test_f32_special_values_and_size():
+    # every upper half combined with a few lower halves: zeros, subnormals, Inf, NaN payloads
+    high = np.arange(65536, dtype=np.uint32)
+    for low in (0, 1, 0x8000, 0xFFFF, 0x1234):
+        w = (high << 16) | np.uint32(low)
+        assert np.array_equal(O.decompress_f32(O.compress_f32(w), w.size), w)
+    # Gaussian weights: 8 exponent bits shrink to their entropy, the other 24 bits stay
+    w = (np.random.default_rng(3).standard_normal(1 << 20) * 0.02).astype(np.float32).view(np.uint32)
+    blob = O.compress_f32(w, threads=8)
+    H = O.entropy(O.histogram((w >> 16).astype(np.uint16)))
+    assert H + 24 < 8 * blob.size / w.size < 1.01 * (H + 24)
