@@ -486,9 +486,9 @@ int nzo_compress_guarded(const uint16_t *w, uint64_t n, int k, uint32_t guard, u
 
 /* Compression with a table that was made earlier (from the weights before an update): no
  * statistics are taken from w.  NZO_ESTALE if w holds an exponent the table gives no room. */
-int nzo_compress_with_table(const uint16_t *w, uint64_t n, int k, const uint16_t freq[256],
-                            uint32_t guard, uint8_t *blob, uint64_t cap, uint64_t *written,
-                            int threads)
+/* A kept table must sum to M (all zero for an empty tensor) and give every exponent that
+ * occurs a non-zero frequency. */
+static int kept_table_serves(const uint16_t *w, uint64_t n, const uint16_t freq[256], uint32_t guard)
 {
     if (!freq || guard > 255)
         return NZO_EINVAL;
@@ -502,6 +502,16 @@ int nzo_compress_with_table(const uint16_t *w, uint64_t n, int k, const uint16_t
     for (int s = 0; s < 256; s++)
         if (cnt[s] > 0 && freq[s] == 0)
             return NZO_ESTALE;
+    return NZO_OK;
+}
+
+int nzo_compress_with_table(const uint16_t *w, uint64_t n, int k, const uint16_t freq[256],
+                            uint32_t guard, uint8_t *blob, uint64_t cap, uint64_t *written,
+                            int threads)
+{
+    int rc = kept_table_serves(w, n, freq, guard);
+    if (rc != NZO_OK)
+        return rc;
     return compress_impl(w, n, k, 0, NULL, freq, guard, NULL, blob, cap, written, threads);
 }
 
@@ -850,6 +860,14 @@ int nzo_decompress(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n,
 /* ------------------------------------------------------------------ */
 int nzo_compress_f32(const uint32_t *w, uint64_t n, uint8_t *blob, uint64_t cap, uint64_t *written, int threads)
 {
+    return nzo_compress_f32_with_table(w, n, NULL, 0, blob, cap, written, threads);
+}
+
+/* The same with a guard band, and with a table kept from an earlier compression when freq is
+ * not NULL (the rules of nzo_compress_with_table, applied to the upper halves). */
+int nzo_compress_f32_with_table(const uint32_t *w, uint64_t n, const uint16_t *freq, uint32_t guard, uint8_t *blob,
+                                uint64_t cap, uint64_t *written, int threads)
+{
     uint16_t *high = (uint16_t *)malloc((size_t)(n + 1) * sizeof(uint16_t));
     uint16_t *low = (uint16_t *)malloc((size_t)(n + 1) * sizeof(uint16_t));
     if (!high || !low) {
@@ -861,7 +879,9 @@ int nzo_compress_f32(const uint32_t *w, uint64_t n, uint8_t *blob, uint64_t cap,
         high[i] = (uint16_t)(w[i] >> 16);
         low[i] = (uint16_t)(w[i] & 0xFFFF);
     }
-    int rc = compress_impl(high, n, 7, 0, NULL, NULL, 0, low, blob, cap, written, threads);
+    int rc = guard > 255 ? NZO_EINVAL : (freq ? kept_table_serves(high, n, freq, guard) : NZO_OK);
+    if (rc == NZO_OK)
+        rc = compress_impl(high, n, 7, 0, NULL, freq, guard, low, blob, cap, written, threads);
     free(high);
     free(low);
     return rc;

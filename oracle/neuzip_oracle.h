@@ -137,6 +137,8 @@ int nzo_decompress(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n,
  * lossless path as bf16 words, the lower halves are stored raw in a plane after the
  * sign|mantissa stream; header word 56 is 1. */
 int nzo_compress_f32(const uint32_t *w, uint64_t n, uint8_t *blob, uint64_t cap, uint64_t *written, int threads);
+int nzo_compress_f32_with_table(const uint32_t *w, uint64_t n, const uint16_t *freq, uint32_t guard, uint8_t *blob,
+                                uint64_t cap, uint64_t *written, int threads);
 int nzo_decompress_f32(const uint8_t *blob, uint64_t len, uint32_t *out, uint64_t n, int threads);
 /* Reads n, k and the stored frequencies out of a container. */
 int nzo_blob_info(const uint8_t *blob, uint64_t len, uint64_t *n, int *k, uint64_t *total_words,

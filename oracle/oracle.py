@@ -92,6 +92,8 @@ def lib():
         L.nzo_decompress.restype = i32
         L.nzo_compress_f32.argtypes = [u32p, u64, u8p, u64, u64p, i32]
         L.nzo_compress_f32.restype = i32
+        L.nzo_compress_f32_with_table.argtypes = [u32p, u64, u16p, u32, u8p, u64, u64p, i32]
+        L.nzo_compress_f32_with_table.restype = i32
         L.nzo_decompress_f32.argtypes = [u8p, u64, u32p, u64, i32]
         L.nzo_decompress_f32.restype = i32
         L.nzo_blob_info.argtypes = [u8p, u64, u64p, ctypes.POINTER(i32), u64p, u16p]
@@ -298,9 +300,9 @@ def decompress(blob, n, threads=1):
     return out
 
 
-def compress_f32(w, threads=1):
+def compress_f32(w, threads=1, guard=0, freq=None):
     """binary32 words (uint32 array) -> container bytes: upper halves through the lossless bf16 path,
-    lower halves as a raw plane."""
+    lower halves as a raw plane.  guard / freq as in compress()."""
     w = np.ascontiguousarray(w)
     if w.dtype != np.uint32:
         raise TypeError("binary32 words must be passed as uint32")
@@ -308,8 +310,14 @@ def compress_f32(w, threads=1):
     cap = int(lib().nzo_compress_bound(w.size, 7))
     blob = np.empty(cap, np.uint8)
     written = ctypes.c_uint64(0)
-    rc = lib().nzo_compress_f32(_p(w, ctypes.c_uint32), w.size, _p(blob, ctypes.c_uint8), cap, ctypes.byref(written),
-                                threads)
+    table = None
+    if freq is not None:
+        table = np.ascontiguousarray(freq, dtype=np.uint16)
+        if table.size != 256:
+            raise ValueError("a frequency table has 256 entries")
+    rc = lib().nzo_compress_f32_with_table(_p(w, ctypes.c_uint32), w.size,
+                                           None if table is None else _p(table, ctypes.c_uint16), guard,
+                                           _p(blob, ctypes.c_uint8), cap, ctypes.byref(written), threads)
     if rc != OK:
         raise OracleError(rc, "compress_f32")
     return blob[: written.value].copy()

@@ -707,3 +707,31 @@ def test_f32_special_values_and_size():
     blob = O.compress_f32(w, threads=8)
     H = O.entropy(O.histogram((w >> 16).astype(np.uint16)))
     assert H + 24 < 8 * blob.size / w.size < 1.01 * (H + 24)
+
+
+def test_f32_guard_band_and_kept_table():
+    rng = np.random.default_rng(78)
+    n = 20_000
+    w0 = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    w1 = (w0 - 1e-4 * rng.standard_normal(n).astype(np.float32)).view(np.uint32)
+    w0 = w0.view(np.uint32)
+    first = O.compress_f32(w0, guard=8)
+    table = O.blob_info(first)["freq"]
+    high0 = (w0 >> 16).astype(np.uint16)
+    assert np.array_equal(table, O.quantise(O.histogram(high0), guard=8))
+    kept = O.compress_f32(w1, threads=2, guard=8, freq=table)
+    assert np.array_equal(O.decompress_f32(kept, n), w1)
+    # the same bytes as the bf16 container of the upper halves under the same table, plus the plane
+    high1, low1 = (w1 >> 16).astype(np.uint16), (w1 & 0xFFFF).astype(np.uint16)
+    plain = O.compress(high1, 7, guard=8, freq=table)
+    sec, sec16 = O.sections(kept), O.sections(plain)
+    for name in ("freq", "offsets", "states", "lens", "words", "signmant"):
+        assert np.array_equal(kept[slice(*sec[name])], plain[slice(*sec16[name])]), name
+    assert kept.tobytes() == P.compress([int(u) for u in high1], 7, guard=8, freq=[int(f) for f in table],
+                                        low=[int(u) for u in low1])
+    # an exponent outside the table: refused, as for bf16
+    w2 = w1.copy()
+    w2[5] = np.uint32((int(np.nonzero(table)[0][-1]) + 1) << 23)
+    with pytest.raises(O.OracleError) as err:
+        O.compress_f32(w2, guard=8, freq=table)
+    assert err.value.code == O.ESTALE
