@@ -16,9 +16,10 @@
  *     stream work has completed.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *     All kernels and copies of a call are enqueued on it.
- *   - Tensors are flat, contiguous arrays of n_elems 16-bit words; the shape
- *     of the matrix is irrelevant to the codec.  d_src / d_dst must be aligned
- *     to 16 bytes.  n_elems must be below 2^32.
+ *   - Tensors are flat, contiguous arrays of n_elems 16-bit words (32-bit
+ *     words for NEUZIP_F32); the shape of the matrix is irrelevant to the
+ *     codec.  d_src / d_dst must be aligned to 16 bytes.  n_elems must be
+ *     below 2^32.
  *   - Errors are reported through the return code only (no exceptions, no
  *     aborts, nothing is printed).  On error no output argument is modified
  *     unless stated otherwise.
@@ -42,8 +43,15 @@ extern "C" {
  * behind it until neuzip_free. */
 typedef struct neuzip_blob neuzip_blob;
 
-/* Element types.  The paper works on BFloat16 only (Sec. 2.1, footnote). */
-enum { NEUZIP_BF16 = 0 };
+/* Element types.  The paper works on BFloat16 only (Sec. 2.1, footnote).
+ * NEUZIP_F32 goes beyond it: the upper half of an IEEE binary32 word is a bf16 word (sign, the
+ * same 8 exponent bits, 7 mantissa bits) and is compressed exactly as one; the lower half, 16
+ * mantissa bits without structure, is kept as a raw plane after the sign|mantissa stream
+ * (header word 56 of the container = 1).  Lossless only: mantissa_bits must be 7 and there is no
+ * block-wise normalisation (EUNSUPPORTED / EINVAL otherwise).  neuzip_compress, _batch, _guarded,
+ * neuzip_recompress, the three decompress calls, export and import take such tensors;
+ * neuzip_linear does not (EUNSUPPORTED). */
+enum { NEUZIP_BF16 = 0, NEUZIP_F32 = 1 };
 
 enum {
     NEUZIP_OK = 0,
@@ -67,7 +75,7 @@ enum {
  * weight update ("split", "compression", "store"); Sec. 2.3 for k < 7.
  *
  *   d_src          n_elems bf16 words on the device (read only).
- *   dtype          NEUZIP_BF16.
+ *   dtype          NEUZIP_BF16, or NEUZIP_F32 (n_elems binary32 words; see the element types).
  *   mantissa_bits  7 = lossless; 3, 1 or 0 = keep that many leading mantissa
  *                  bits, truncating toward zero.
  *   blob           in/out.  *blob == NULL: a new blob is created.  Otherwise
@@ -150,7 +158,7 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
  * decodes the exponents and reassembles bf16 words into the caller's
  * temporary space in one fused kernel.
  *
- *   d_dst    room for n_elems bf16 words on the device, 16-byte aligned.
+ *   d_dst    room for n_elems bf16 (binary32 for such a blob) words on the device, 16-byte aligned.
  *   n_elems, dtype must equal what the blob was made from (else EINVAL).
  *
  * Never allocates, never synchronises.  For mantissa_bits < 7 the dropped
@@ -167,8 +175,9 @@ int neuzip_decompress(const neuzip_blob *blob, void *d_dst, uint64_t n_elems, in
  * is never held uncompressed.
  *
  *   blobs          host array of count blob handles.
- *   d_scratch      device buffer of scratch_elems bf16 words, 16-byte aligned;
- *                  must hold the largest tensor (else EINVAL, nothing is run).
+ *   d_scratch      device buffer of scratch_elems bf16 words (2 * scratch_elems bytes), 16-byte
+ *                  aligned; must hold the largest tensor, a binary32 blob counting two words
+ *                  per element (else EINVAL, nothing is run).
  * Never allocates, never synchronises.
  */
 int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, void *d_scratch,
@@ -181,7 +190,7 @@ int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, 
  * to fill the GPU on their own overlap with the others.
  *
  *   blobs, d_dsts  host arrays of count entries; d_dsts[i] is a device buffer of
- *                  neuzip_elems(blobs[i]) bf16 words, 16-byte aligned, not overlapping any
+ *                  neuzip_elems(blobs[i]) words of the blob's element type, 16-byte aligned, not overlapping any
  *                  other destination.
  * Tensors are grouped by mantissa_bits (one launch per group of up to 8).  Never allocates,
  * never synchronises.  On EINVAL nothing has been launched.
@@ -222,12 +231,13 @@ uint64_t neuzip_compressed_bytes(const neuzip_blob *blob);
  * alignment padding and the derived cumulative and slot tables). */
 uint64_t neuzip_device_bytes(const neuzip_blob *blob);
 
-/* Element count, mantissa bits, normalisation block size (0 = none) and guard band of the table
- * (0 = none) the blob was made with. */
+/* Element count, mantissa bits, normalisation block size (0 = none), guard band of the table
+ * (0 = none) and element type the blob was made with (-1 for something that is not a blob). */
 uint64_t neuzip_elems(const neuzip_blob *blob);
 uint32_t neuzip_block_size(const neuzip_blob *blob);
 uint32_t neuzip_guard(const neuzip_blob *blob);
 int neuzip_mantissa_bits(const neuzip_blob *blob);
+int neuzip_dtype(const neuzip_blob *blob);
 
 /*
  * neuzip_export / neuzip_import -- the container as one flat host byte buffer

@@ -13,7 +13,7 @@ import torch
 
 from . import build as _build
 
-BF16 = 0
+BF16, F32 = 0, 1
 OK, EINVAL, ENOMEM, EHIP, ECORRUPT, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 
 
@@ -63,6 +63,8 @@ def _load():
     lib.neuzip_elems.restype = u64
     lib.neuzip_mantissa_bits.argtypes = [vp]
     lib.neuzip_mantissa_bits.restype = i32
+    lib.neuzip_dtype.argtypes = [vp]
+    lib.neuzip_dtype.restype = i32
     lib.neuzip_export.argtypes = [vp, vp, u64, ctypes.POINTER(u64), vp]
     lib.neuzip_export.restype = i32
     lib.neuzip_import.argtypes = [vp, u64, vp, vpp]
@@ -88,7 +90,7 @@ _lib = _load()
 EXPORTED = ["neuzip_compress", "neuzip_compress_blockwise", "neuzip_compress_batch", "neuzip_compress_guarded",
             "neuzip_recompress", "neuzip_guard", "neuzip_linear", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
             "neuzip_free",
-            "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits",
+            "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits", "neuzip_dtype",
             "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check",
             "neuzip_release_workspace", "neuzip_strerror", "neuzip_last_hip_error"]
 
@@ -103,9 +105,21 @@ def _stream_handle(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
-def _check_tensor(t):
-    if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
-        raise TypeError("expected a contiguous bf16 CUDA tensor")
+def _check_tensor(t, wide_ok=False):
+    """Returns the library's element type of a contiguous CUDA tensor (bf16; float32 where allowed)."""
+    if t.is_cuda and t.is_contiguous():
+        if t.dtype == torch.bfloat16:
+            return BF16
+        if wide_ok and t.dtype == torch.float32:
+            return F32
+    raise TypeError("expected a contiguous bf16%s CUDA tensor" % (" or float32" if wide_ok else ""))
+
+
+def _shared_dtype(tensors):
+    kinds = {_check_tensor(t, wide_ok=True) for t in tensors}
+    if len(kinds) > 1:
+        raise TypeError("the tensors of one call share one element type")
+    return kinds.pop() if kinds else BF16
 
 
 class Blob:
@@ -149,6 +163,10 @@ class Blob:
     def guard(self):
         return int(_lib.neuzip_guard(self.handle))
 
+    @property
+    def dtype(self):
+        return int(_lib.neuzip_dtype(self.handle))
+
 
 def neuzip_compress(src: torch.Tensor, mantissa_bits: int = 7, stream=None, blob: Blob = None) -> Blob:
     return neuzip_compress_blockwise(src, mantissa_bits, 0, stream, blob)
@@ -156,9 +174,9 @@ def neuzip_compress(src: torch.Tensor, mantissa_bits: int = 7, stream=None, blob
 
 def neuzip_compress_blockwise(src: torch.Tensor, mantissa_bits: int, block_size: int, stream=None,
                               blob: Blob = None) -> Blob:
-    _check_tensor(src)
+    dtype = _check_tensor(src, wide_ok=True)
     handle = ctypes.c_void_p(blob.handle.value if blob is not None else None)
-    rc = _lib.neuzip_compress_blockwise(ctypes.c_void_p(src.data_ptr()), src.numel(), BF16, mantissa_bits,
+    rc = _lib.neuzip_compress_blockwise(ctypes.c_void_p(src.data_ptr()), src.numel(), dtype, mantissa_bits,
                                         block_size, _stream_handle(stream), ctypes.byref(handle))
     if rc != OK:
         raise NeuzipError(rc, "neuzip_compress")
@@ -175,10 +193,9 @@ def neuzip_compress_guarded(srcs, mantissa_bits: int = 7, guard: int = 0, stream
 
 def neuzip_recompress(srcs, blobs, stream=None):
     """Codes srcs[i] into blobs[i] with the table the blob holds; returns the list of rebuilt flags."""
-    for t in srcs:
-        _check_tensor(t)
-    if len(blobs) != len(srcs) or any(b.elems != t.numel() for b, t in zip(blobs, srcs)):
-        raise ValueError("one blob of matching size per tensor")
+    if len(blobs) != len(srcs) or any(b.elems != t.numel() or b.dtype != _check_tensor(t, wide_ok=True)
+                                      for b, t in zip(blobs, srcs)):
+        raise ValueError("one blob of matching size and element type per tensor")
     count = len(srcs)
     ptrs = (ctypes.c_void_p * count)(*[t.data_ptr() for t in srcs])
     handles = (ctypes.c_void_p * count)(*[b.handle.value for b in blobs])
@@ -191,8 +208,7 @@ def neuzip_recompress(srcs, blobs, stream=None):
 
 def neuzip_compress_batch(srcs, mantissa_bits: int = 7, block_size: int = 0, stream=None, blobs=None, guard=None):
     """Compresses several tensors with one pass of the pipeline; returns one Blob per tensor."""
-    for t in srcs:
-        _check_tensor(t)
+    dtype = _shared_dtype(srcs)
     if blobs is not None and len(blobs) != len(srcs):
         raise ValueError("one blob per tensor")
     count = len(srcs)
@@ -201,10 +217,10 @@ def neuzip_compress_batch(srcs, mantissa_bits: int = 7, block_size: int = 0, str
     handles = (ctypes.c_void_p * count)(*[(b.handle.value if b is not None else None)
                                           for b in (blobs if blobs is not None else [None] * count)])
     if guard is None:
-        rc = _lib.neuzip_compress_batch(ptrs, sizes, count, BF16, mantissa_bits, block_size, _stream_handle(stream),
+        rc = _lib.neuzip_compress_batch(ptrs, sizes, count, dtype, mantissa_bits, block_size, _stream_handle(stream),
                                         handles)
     else:
-        rc = _lib.neuzip_compress_guarded(ptrs, sizes, count, BF16, mantissa_bits, guard, _stream_handle(stream),
+        rc = _lib.neuzip_compress_guarded(ptrs, sizes, count, dtype, mantissa_bits, guard, _stream_handle(stream),
                                           handles)
     if rc != OK:
         raise NeuzipError(rc, "neuzip_compress_batch")
@@ -219,8 +235,8 @@ def neuzip_compress_batch(srcs, mantissa_bits: int = 7, block_size: int = 0, str
 
 
 def neuzip_decompress(blob: Blob, dst: torch.Tensor, stream=None) -> torch.Tensor:
-    _check_tensor(dst)
-    rc = _lib.neuzip_decompress(blob.handle, ctypes.c_void_p(dst.data_ptr()), dst.numel(), BF16,
+    dtype = _check_tensor(dst, wide_ok=True)
+    rc = _lib.neuzip_decompress(blob.handle, ctypes.c_void_p(dst.data_ptr()), dst.numel(), dtype,
                                 _stream_handle(stream))
     if rc != OK:
         raise NeuzipError(rc, "neuzip_decompress")
@@ -228,19 +244,19 @@ def neuzip_decompress(blob: Blob, dst: torch.Tensor, stream=None) -> torch.Tenso
 
 
 def neuzip_decompress_sequence(blobs, scratch: torch.Tensor, stream=None) -> None:
-    _check_tensor(scratch)
+    dtype = _check_tensor(scratch, wide_ok=True)
     arr = (ctypes.c_void_p * len(blobs))(*[b.handle.value for b in blobs])
+    # the library counts the scratch in 16-bit words
     rc = _lib.neuzip_decompress_sequence(arr, len(blobs), ctypes.c_void_p(scratch.data_ptr()),
-                                         scratch.numel(), _stream_handle(stream))
+                                         scratch.numel() * (2 if dtype == F32 else 1), _stream_handle(stream))
     if rc != OK:
         raise NeuzipError(rc, "neuzip_decompress_sequence")
 
 
 def neuzip_decompress_batch(blobs, dsts, stream=None) -> None:
-    for d in dsts:
-        _check_tensor(d)
-    if len(blobs) != len(dsts) or any(b.elems != d.numel() for b, d in zip(blobs, dsts)):
-        raise ValueError("one destination of matching size per blob")
+    if len(blobs) != len(dsts) or any(b.elems != d.numel() or b.dtype != _check_tensor(d, wide_ok=True)
+                                      for b, d in zip(blobs, dsts)):
+        raise ValueError("one destination of matching size and element type per blob")
     arr = (ctypes.c_void_p * len(blobs))(*[b.handle.value for b in blobs])
     ptrs = (ctypes.c_void_p * len(dsts))(*[d.data_ptr() for d in dsts])
     rc = _lib.neuzip_decompress_batch(arr, ptrs, len(blobs), _stream_handle(stream))

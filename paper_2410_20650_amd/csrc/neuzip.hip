@@ -66,10 +66,11 @@ inline bool valid_block(uint32_t b) { return b == 32 || b == 64 || b == 128 || b
 inline uint64_t block_count(uint64_t n, uint32_t block) { return block ? (n + block - 1) / block : 0; }
 
 struct Layout {
-    uint64_t offsets, states, lens, sm, coef, total;  // byte positions inside the fixed allocation
+    uint64_t offsets, states, lens, sm, low, coef, total;  // byte positions inside the fixed allocation
 };
 
-Layout fixed_layout(uint64_t n, int k, uint32_t block)
+// f32: the tensor's elements are binary32; the plane of their lower halves follows the sign|mantissa stream
+Layout fixed_layout(uint64_t n, int k, uint32_t block, bool f32)
 {
     const uint64_t nc = chunks_of(n);
     Layout l;
@@ -77,16 +78,17 @@ Layout fixed_layout(uint64_t n, int k, uint32_t block)
     l.states = l.offsets + pad_to((nc + 2) * 4, 256);
     l.lens = l.states + pad_to(nc * kStates * 4, 256);
     l.sm = l.lens + pad_to(nc * kStates, 256);
-    l.coef = l.sm + pad_to(signmant_bytes(n, k), 256) + 256;
+    l.low = l.sm + pad_to(signmant_bytes(n, k), 256) + 256;
+    l.coef = l.low + (f32 ? pad_to(n * 2, 256) + 256 : 0);
     l.total = l.coef + pad_to(block_count(n, block), 256);
     return l;
 }
 
 struct Container {
-    uint64_t freq, offsets, states, lens, words, sm, coef, total;  // byte positions in the flat container
+    uint64_t freq, offsets, states, lens, words, sm, low, coef, total;  // byte positions in the flat container
 };
 
-Container container_layout(uint64_t n, int k, uint64_t total_words, uint32_t block)
+Container container_layout(uint64_t n, int k, uint64_t total_words, uint32_t block, bool f32)
 {
     const uint64_t nc = chunks_of(n);
     Container c;
@@ -96,7 +98,8 @@ Container container_layout(uint64_t n, int k, uint64_t total_words, uint32_t blo
     c.lens = c.states + nc * kStates * 4;
     c.words = c.lens + nc * kStates;
     c.sm = c.words + pad_to(total_words * 2, 16);
-    c.coef = c.sm + pad_to(signmant_bytes(n, k), 16);
+    c.low = c.sm + pad_to(signmant_bytes(n, k), 16);
+    c.coef = c.low + (f32 ? pad_to(n * 2, 16) : 0);
     c.total = c.coef + pad_to(block_count(n, block), 16);
     return c;
 }
@@ -110,6 +113,7 @@ struct neuzip_blob {
     int k;
     uint32_t block;  // block size of the block-wise normalisation, 0 = none
     uint32_t guard;  // guard band of the frequency table, 0 = none
+    bool f32;        // elements are binary32 (lossless only): a plane of lower halves rides along
     bool has_table;  // holds a compressed tensor (and so a table that recompression can reuse)
     uint32_t n_chunks;
     uint64_t total_words;
@@ -133,6 +137,7 @@ inline uint32_t *states_of(const neuzip_blob *b) { return reinterpret_cast<uint3
 inline uint8_t *lens_of(const neuzip_blob *b) { return b->fixed + b->at.lens; }
 inline uint8_t *sm_of(const neuzip_blob *b) { return b->fixed + b->at.sm; }
 inline uint8_t *coef_of(const neuzip_blob *b) { return b->fixed + b->at.coef; }
+inline uint16_t *low_of(const neuzip_blob *b) { return reinterpret_cast<uint16_t *>(b->fixed + b->at.low); }
 inline bool is_blob(const neuzip_blob *b) { return b && b->magic == kBlobMagic; }
 
 // A blob lives on the device that was current when it was made; kernels are launched on the
@@ -254,7 +259,7 @@ int ensure_workspace(int device, uint64_t n_groups, hipStream_t stream)
     return NEUZIP_OK;
 }
 
-int alloc_blob(uint64_t n, int k, uint32_t block, neuzip_blob **out)
+int alloc_blob(uint64_t n, int k, uint32_t block, bool f32, neuzip_blob **out)
 {
     neuzip_blob *b = new (std::nothrow) neuzip_blob();
     if (!b)
@@ -264,8 +269,9 @@ int alloc_blob(uint64_t n, int k, uint32_t block, neuzip_blob **out)
     b->n = n;
     b->k = k;
     b->block = block;
+    b->f32 = f32;
     b->n_chunks = chunks_of(n);
-    b->at = fixed_layout(n, k, block);
+    b->at = fixed_layout(n, k, block, f32);
     if (!hip_ok(hipGetDevice(&b->device))) {
         delete b;
         return NEUZIP_EHIP;
@@ -330,11 +336,13 @@ DecodeArgs decode_args(const neuzip_blob *b, void *d_dst)
     a.words = reinterpret_cast<const uint16_t *>(b->words);
     a.sm = sm_of(b);
     a.coef = coef_of(b);
+    a.low = low_of(b);
     a.block = b->block;
     // 2 bytes out + ~1.3 in per element against 256 MB of Infinity Cache: beyond ~64 M elements
-    // the tensor streams through HBM and non-temporal stores measured 5 % faster; below they cost 3 %
-    a.stream_out = b->n >= (64ull << 20) ? 1u : 0u;
-    a.out = static_cast<uint16_t *>(d_dst);
+    // (half as many of binary32) the tensor streams through HBM and non-temporal stores measured
+    // 5 % faster; below they cost 3 %
+    a.stream_out = (b->f32 ? 2 * b->n : b->n) >= (64ull << 20) ? 1u : 0u;
+    a.out = d_dst;
     a.status = table_of(b)->status;
     a.n = b->n;
     a.n_chunks = b->n_chunks;
@@ -342,12 +350,12 @@ DecodeArgs decode_args(const neuzip_blob *b, void *d_dst)
     return a;
 }
 
-template <int KB, bool NORM>
+template <int KB, bool NORM, bool WIDE = false>
 int launch_decode(const neuzip_blob *b, void *d_dst, hipStream_t stream)
 {
     const uint32_t per = decode_chunks_per_wg();
     const uint32_t groups = (b->n_chunks + per - 1) / per;
-    hipLaunchKernelGGL((decode_kernel<KB, NORM>), dim3(groups), dim3(per * kStates), 0, stream,
+    hipLaunchKernelGGL((decode_kernel<KB, NORM, WIDE>), dim3(groups), dim3(per * kStates), 0, stream,
                        decode_args(b, d_dst));
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
@@ -356,6 +364,8 @@ int decode_dispatch(const neuzip_blob *b, void *d_dst, hipStream_t stream)
 {
     if (b->n == 0)
         return NEUZIP_OK;
+    if (b->f32)
+        return launch_decode<7, false, true>(b, d_dst, stream);
     if (b->block) {
         switch (b->k) {
         case 3: return launch_decode<3, true>(b, d_dst, stream);
@@ -371,8 +381,8 @@ int decode_dispatch(const neuzip_blob *b, void *d_dst, hipStream_t stream)
     }
 }
 
-// variant = mantissa_bits, + 8 for block-wise normalised blobs
-inline int decode_variant(const neuzip_blob *b) { return b->k + (b->block ? 8 : 0); }
+// variant = mantissa_bits, + 8 for block-wise normalised blobs, + 16 for binary32 blobs
+inline int decode_variant(const neuzip_blob *b) { return b->k + (b->block ? 8 : 0) + (b->f32 ? 16 : 0); }
 
 int launch_batch(const BatchArgs &args, int variant, uint32_t groups, hipStream_t stream)
 {
@@ -384,6 +394,7 @@ int launch_batch(const BatchArgs &args, int variant, uint32_t groups, hipStream_
     case 0: hipLaunchKernelGGL((decode_batch_kernel<0, false>), grid, block, 0, stream, args); break;
     case 11: hipLaunchKernelGGL((decode_batch_kernel<3, true>), grid, block, 0, stream, args); break;
     case 9: hipLaunchKernelGGL((decode_batch_kernel<1, true>), grid, block, 0, stream, args); break;
+    case 23: hipLaunchKernelGGL((decode_batch_kernel<7, false, true>), grid, block, 0, stream, args); break;
     default: hipLaunchKernelGGL((decode_batch_kernel<0, true>), grid, block, 0, stream, args); break;
     }
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
@@ -456,7 +467,7 @@ void launch_encode_reuse(const CompressBatch &batch, uint32_t groups, hipStream_
 // guard band).  reuse = true: every blob holds a table already and the tensors are coded with
 // those, in one pass over the source; rebuilt[i] is set for the tensors whose table turned out
 // not to cover them, which are then compressed the first way.
-int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int k, uint32_t block,
+int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int k, uint32_t block, bool f32,
                   uint32_t guard, bool reuse, uint32_t *rebuilt, hipStream_t stream, neuzip_blob **blobs)
 {
     neuzip_blob *work[kBatchMax];
@@ -477,7 +488,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
     };
     for (uint32_t i = 0; i < count; ++i) {
         if (!work[i]) {
-            const int rc = alloc_blob(n_elems[i], k, block, &work[i]);
+            const int rc = alloc_blob(n_elems[i], k, block, f32, &work[i]);
             if (rc != NEUZIP_OK)
                 return fail(rc);
             fresh[i] = true;
@@ -512,7 +523,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         }
         CompressItem &it = batch.it[batch.count];
         owner[batch.count++] = i;
-        it.src = static_cast<const uint16_t *>(d_srcs[i]);
+        it.src = d_srcs[i];
         it.n = b->n;
         it.tb = table_of(b);
         it.offsets = offsets_of(b);
@@ -520,6 +531,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         it.lens = lens_of(b);
         it.sm = sm_of(b);
         it.coef = coef_of(b);
+        it.low = low_of(b);
         it.words = nullptr;
         it.n_chunks = b->n_chunks;
         it.block = block;
@@ -547,14 +559,22 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             // one pass: encoder constants from the stored tables, then split + encode together
             hipLaunchKernelGGL(table_reuse_kernel, dim3(batch.count), dim3(256), 0, stream, batch, g_ws.enc,
                                g_ws.stale);
-            switch (k) {
+            switch (f32 ? 23 : k) {
+            case 23:
+                hipLaunchKernelGGL((encode_kernel<false, 7, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream, batch,
+                                   g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned, g_ws.stale);
+                break;
             case 7: launch_encode_reuse<7>(batch, enc_groups, stream); break;
             case 3: launch_encode_reuse<3>(batch, enc_groups, stream); break;
             case 1: launch_encode_reuse<1>(batch, enc_groups, stream); break;
             default: launch_encode_reuse<0>(batch, enc_groups, stream); break;
             }
         } else {
-            switch (k) {
+            switch (f32 ? 23 : k) {
+            case 23:
+                hipLaunchKernelGGL((hist_split_kernel<7, true>), dim3(hist_groups), dim3(kHistThreads), 0, stream, batch,
+                                   g_ws.counts);
+                break;
             case 7: launch_hist<7>(batch, block != 0, hist_groups, stream); break;
             case 3: launch_hist<3>(batch, block != 0, hist_groups, stream); break;
             case 1: launch_hist<1>(batch, block != 0, hist_groups, stream); break;
@@ -567,7 +587,11 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             hipLaunchKernelGGL(table_kernel, dim3(batch.count), dim3(256), 0, stream, batch, g_ws.counts, g_ws.enc);
             if (hip_ok(hipGetLastError()))
                 bins_dirty = false;
-            if (block)
+            if (f32)
+                hipLaunchKernelGGL((encode_kernel<false, -1, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream,
+                                   batch, g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned,
+                                   static_cast<uint32_t *>(nullptr));
+            else if (block)
                 hipLaunchKernelGGL((encode_kernel<true, -1>), dim3(enc_groups), dim3(kEncThreads), 0, stream, batch,
                                    g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned,
                                    static_cast<uint32_t *>(nullptr));
@@ -623,7 +647,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
     }
     if (stale_count > 0) {
         // same stream, so the pass above has finished with the workspace before this one starts
-        const int rc = compress_some(stale_src, stale_n, stale_count, k, block, kKeepGuard, false, nullptr, stream,
+        const int rc = compress_some(stale_src, stale_n, stale_count, k, block, f32, kKeepGuard, false, nullptr, stream,
                                      stale_blob);
         if (rc != NEUZIP_OK)
             return rc;
@@ -700,7 +724,7 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
         const neuzip_blob *lead = blobs[first];
         uint32_t m = 1;
         while (first + m < count && m < kBatchMax && blobs[first + m]->k == lead->k &&
-               blobs[first + m]->block == lead->block)
+               blobs[first + m]->block == lead->block && blobs[first + m]->f32 == lead->f32)
             ++m;
         uint64_t n_elems[kBatchMax];
         neuzip_blob *group[kBatchMax];
@@ -709,7 +733,7 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
             group[j] = blobs[first + j];
         }
         const bool reuse = lead->block == 0;
-        const int rc = compress_some(d_srcs + first, n_elems, m, lead->k, lead->block, kKeepGuard, reuse,
+        const int rc = compress_some(d_srcs + first, n_elems, m, lead->k, lead->block, lead->f32, kKeepGuard, reuse,
                                      rebuilt ? rebuilt + first : nullptr, stream, group);
         if (rc != NEUZIP_OK)
             return rc;
@@ -736,7 +760,7 @@ int neuzip_linear(const neuzip_blob *weight, uint64_t out_features, uint64_t in_
     if ((reinterpret_cast<uintptr_t>(d_x) & 15u) || (reinterpret_cast<uintptr_t>(d_y) & 3u) ||
         (reinterpret_cast<uintptr_t>(d_bias) & 3u))
         return NEUZIP_EINVAL;
-    if (weight->block != 0)
+    if (weight->block != 0 || weight->f32)
         return NEUZIP_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     uint64_t gcd = in_features, r = kChunk;
@@ -788,10 +812,13 @@ int compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t 
 {
     if (count == 0)
         return NEUZIP_OK;
-    if (!d_srcs || !n_elems || !blobs || dtype != NEUZIP_BF16 || !valid_k(mantissa_bits))
+    if (!d_srcs || !n_elems || !blobs || (dtype != NEUZIP_BF16 && dtype != NEUZIP_F32) || !valid_k(mantissa_bits))
         return NEUZIP_EINVAL;
     if (block_size != 0 && (!valid_block(block_size) || mantissa_bits == 7))
         return NEUZIP_EINVAL;
+    const bool f32 = dtype == NEUZIP_F32;
+    if (f32 && mantissa_bits != 7)
+        return NEUZIP_EUNSUPPORTED;  // binary32 tensors are compressed without loss only
     for (uint32_t i = 0; i < count; ++i) {
         if (n_elems[i] > 0 && (!d_srcs[i] || (reinterpret_cast<uintptr_t>(d_srcs[i]) & 15u)))
             return NEUZIP_EINVAL;
@@ -799,7 +826,7 @@ int compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t 
             return NEUZIP_EUNSUPPORTED;
         const neuzip_blob *b = blobs[i];
         if (b && (!is_blob(b) || b->n != n_elems[i] || b->k != mantissa_bits || b->block != block_size ||
-                  !on_current_device(b)))
+                  b->f32 != f32 || !on_current_device(b)))
             return NEUZIP_EINVAL;
         for (uint32_t j = 0; j < i; ++j)
             if (b && blobs[j] == b)
@@ -808,7 +835,7 @@ int compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     for (uint32_t first = 0; first < count; first += kBatchMax) {
         const uint32_t m = count - first < kBatchMax ? count - first : kBatchMax;
-        const int rc = compress_some(d_srcs + first, n_elems + first, m, mantissa_bits, block_size, guard, false,
+        const int rc = compress_some(d_srcs + first, n_elems + first, m, mantissa_bits, block_size, f32, guard, false,
                                      nullptr, stream, blobs + first);
         if (rc != NEUZIP_OK)
             return rc;
@@ -822,7 +849,8 @@ extern "C" {
 
 int neuzip_decompress(const neuzip_blob *blob, void *d_dst, uint64_t n_elems, int dtype, void *hip_stream)
 {
-    if (!is_blob(blob) || dtype != NEUZIP_BF16 || blob->n != n_elems || !on_current_device(blob))
+    if (!is_blob(blob) || dtype != (blob->f32 ? NEUZIP_F32 : NEUZIP_BF16) || blob->n != n_elems ||
+        !on_current_device(blob))
         return NEUZIP_EINVAL;
     if (n_elems > 0 && (!d_dst || (reinterpret_cast<uintptr_t>(d_dst) & 15u)))
         return NEUZIP_EINVAL;
@@ -837,8 +865,8 @@ int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, 
     if (reinterpret_cast<uintptr_t>(d_scratch) & 15u)
         return NEUZIP_EINVAL;
     for (uint32_t i = 0; i < count; ++i) {
-        if (!is_blob(blobs[i]) || blobs[i]->n > scratch_elems || (blobs[i]->n > 0 && !d_scratch) ||
-            !on_current_device(blobs[i]))
+        if (!is_blob(blobs[i]) || (blobs[i]->f32 ? 2 * blobs[i]->n : blobs[i]->n) > scratch_elems ||
+            (blobs[i]->n > 0 && !d_scratch) || !on_current_device(blobs[i]))
             return NEUZIP_EINVAL;
     }
     for (uint32_t i = 0; i < count; ++i) {
@@ -862,11 +890,11 @@ int neuzip_decompress_batch(const neuzip_blob *const *blobs, void *const *d_dsts
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     uint64_t batch_elems = 0;
     for (uint32_t i = 0; i < count; ++i)
-        batch_elems += blobs[i]->n;
+        batch_elems += blobs[i]->f32 ? 2 * blobs[i]->n : blobs[i]->n;
     const bool stream_out = batch_elems >= (64ull << 20);  // the batch as a whole exceeds the cache
     // tensors of the same kind (mantissa_bits, normalised or not) share launches of up to
     // kBatchMax tensors, in the given order
-    static const int kinds[7] = {7, 3, 1, 0, 11, 9, 8};
+    static const int kinds[8] = {7, 3, 1, 0, 11, 9, 8, 23};
     for (int k : kinds) {
         BatchArgs args;
         args.count = 0;
@@ -917,7 +945,7 @@ uint64_t neuzip_compressed_bytes(const neuzip_blob *blob)
 {
     if (!is_blob(blob))
         return 0;
-    return container_layout(blob->n, blob->k, blob->total_words, blob->block).total;
+    return container_layout(blob->n, blob->k, blob->total_words, blob->block, blob->f32).total;
 }
 
 uint64_t neuzip_device_bytes(const neuzip_blob *blob)
@@ -931,11 +959,13 @@ uint64_t neuzip_elems(const neuzip_blob *blob) { return is_blob(blob) ? blob->n 
 uint32_t neuzip_block_size(const neuzip_blob *blob) { return is_blob(blob) ? blob->block : 0; }
 int neuzip_mantissa_bits(const neuzip_blob *blob) { return is_blob(blob) ? blob->k : -1; }
 
+int neuzip_dtype(const neuzip_blob *blob) { return !is_blob(blob) ? -1 : (blob->f32 ? NEUZIP_F32 : NEUZIP_BF16); }
+
 int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *written, void *hip_stream)
 {
     if (!is_blob(blob) || (h_buf && !on_current_device(blob)))
         return NEUZIP_EINVAL;
-    const Container lay = container_layout(blob->n, blob->k, blob->total_words, blob->block);
+    const Container lay = container_layout(blob->n, blob->k, blob->total_words, blob->block, blob->f32);
     if (written)
         *written = lay.total;
     if (!h_buf)
@@ -959,6 +989,7 @@ int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *
     put64(40, blob->total_words);
     put32(48, blob->block);
     put32(52, blob->guard);
+    put32(56, blob->f32 ? 1u : 0u);  // element type
     const uint64_t nc = blob->n_chunks;
     NZ_HIP(hipMemcpyAsync(p + lay.freq, table_of(blob)->freq, 512, hipMemcpyDeviceToHost, stream));
     NZ_HIP(hipMemcpyAsync(p + lay.offsets, offsets_of(blob), (nc + 1) * 4, hipMemcpyDeviceToHost, stream));
@@ -971,6 +1002,8 @@ int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *
     if (blob->n)
         NZ_HIP(hipMemcpyAsync(p + lay.sm, sm_of(blob), signmant_bytes(blob->n, blob->k), hipMemcpyDeviceToHost,
                               stream));
+    if (blob->n && blob->f32)
+        NZ_HIP(hipMemcpyAsync(p + lay.low, low_of(blob), blob->n * 2, hipMemcpyDeviceToHost, stream));
     if (blob->n && blob->block)
         NZ_HIP(hipMemcpyAsync(p + lay.coef, coef_of(blob), block_count(blob->n, blob->block), hipMemcpyDeviceToHost,
                               stream));
@@ -1001,10 +1034,14 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
     const uint32_t guard = get32(52);
     if (guard > 255 || (guard != 0 && block != 0))
         return NEUZIP_ECORRUPT;
+    const uint32_t elem = get32(56);
+    if (elem > 1 || (elem == 1 && (k != 7 || block != 0)))
+        return NEUZIP_ECORRUPT;
+    const bool f32 = elem == 1;
     const uint32_t nc = chunks_of(n);
     if (get32(36) != nc)
         return NEUZIP_ECORRUPT;
-    const Container lay = container_layout(n, k, total_words, block);
+    const Container lay = container_layout(n, k, total_words, block, f32);
     if (lay.total != len)
         return NEUZIP_ECORRUPT;
 
@@ -1037,7 +1074,7 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
         return NEUZIP_ECORRUPT;
 
     neuzip_blob *b = nullptr;
-    int rc = alloc_blob(n, k, block, &b);
+    int rc = alloc_blob(n, k, block, f32, &b);
     if (rc != NEUZIP_OK)
         return rc;
     auto fail = [&](int code) {
@@ -1075,6 +1112,8 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
     if (total_words && !hip_ok(hipMemcpyAsync(b->words, p + lay.words, total_words * 2, hipMemcpyHostToDevice, stream)))
         return fail(NEUZIP_EHIP);
     if (n && !hip_ok(hipMemcpyAsync(sm_of(b), p + lay.sm, signmant_bytes(n, k), hipMemcpyHostToDevice, stream)))
+        return fail(NEUZIP_EHIP);
+    if (n && f32 && !hip_ok(hipMemcpyAsync(low_of(b), p + lay.low, n * 2, hipMemcpyHostToDevice, stream)))
         return fail(NEUZIP_EHIP);
     if (n && block) {
         for (uint64_t i = 0; i < block_count(n, block); ++i)

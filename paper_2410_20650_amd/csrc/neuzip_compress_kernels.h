@@ -98,6 +98,64 @@ __device__ __forceinline__ uint32_t denormalise_word(uint32_t u, float c)
 __device__ __forceinline__ float coefficient(uint32_t coef) { return 1.0f + static_cast<float>(coef) * 0.0078125f; }
 
 // ------------------------------------------------------------------------------------------
+// Element types.  The method is stated for BFloat16 (Sec. 2.1).  A binary32 word carries the same
+// sign and exponent bits in its upper half, which is a bf16 word; that half goes through the
+// lossless path unchanged and the lower half, 16 mantissa bits without structure, is kept as a
+// raw plane.  SourceVec holds 8 neighbouring elements of either type as the kernels read them:
+// one 128-bit load (bf16) or two (binary32, WIDE), and hands out the four dwords of bf16 words.
+// ------------------------------------------------------------------------------------------
+template <bool WIDE>
+struct SourceVec {
+    uint4 a, b;  // b: elements 4..7 of a binary32 vector
+    // p: the tensor as 128-bit pieces; v: index of the 8-element vector
+    __device__ __forceinline__ void load(const uint4 *__restrict__ p, uint64_t v)
+    {
+        if constexpr (WIDE) {
+            a = p[2 * v];
+            b = p[2 * v + 1];
+        } else {
+            a = p[v];
+        }
+    }
+    __device__ __forceinline__ void clear() { a = b = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ void words(uint32_t (&w)[4]) const
+    {
+        if constexpr (WIDE) {
+            // upper halves of two neighbours into one dword, first element low
+            w[0] = __builtin_amdgcn_perm(a.y, a.x, 0x07060302u);
+            w[1] = __builtin_amdgcn_perm(a.w, a.z, 0x07060302u);
+            w[2] = __builtin_amdgcn_perm(b.y, b.x, 0x07060302u);
+            w[3] = __builtin_amdgcn_perm(b.w, b.z, 0x07060302u);
+        } else {
+            w[0] = a.x;
+            w[1] = a.y;
+            w[2] = a.z;
+            w[3] = a.w;
+        }
+    }
+    // the lower halves of a binary32 vector, in element order
+    __device__ __forceinline__ uint4 lows() const
+    {
+        return make_uint4(__builtin_amdgcn_perm(a.y, a.x, 0x05040100u), __builtin_amdgcn_perm(a.w, a.z, 0x05040100u),
+                          __builtin_amdgcn_perm(b.y, b.x, 0x05040100u), __builtin_amdgcn_perm(b.w, b.z, 0x05040100u));
+    }
+};
+
+// Element i of a tensor of either type as a bf16 word; for binary32 the lower half goes to the plane.
+template <bool WIDE, bool KEEP_LOW>
+__device__ __forceinline__ uint32_t source_word(const void *__restrict__ src, uint16_t *__restrict__ low, uint64_t i)
+{
+    if constexpr (WIDE) {
+        const uint32_t u = static_cast<const uint32_t *>(src)[i];
+        if constexpr (KEEP_LOW)
+            low[i] = static_cast<uint16_t>(u);
+        return u >> 16;
+    } else {
+        return static_cast<const uint16_t *>(src)[i];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Kernel 1: exponent histogram fused with the sign|mantissa split (Alg. 1 "split").
 // One pass over the bf16 words: 2 B/elem read, (k+1)/8 B/elem written.  Counts go to 32
 // bank-private copies of the 256 bins in LDS (copy = lane mod 32, so the 64 lanes of a wave
@@ -124,14 +182,15 @@ __device__ __forceinline__ ItemSlot item_of_workgroup(const CompressBatch &b)
     return {i, blockIdx.x - first, b.it[i].*END - first};
 }
 
-template <int KB>
+template <int KB, bool WIDE = false>
 __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const CompressBatch b,
                                                                  uint32_t *__restrict__ counts_ws)
 {
     const ItemSlot slot = item_of_workgroup<&CompressItem::hist_end>(b);
-    const uint16_t *__restrict__ src = b.it[slot.item].src;
+    const void *__restrict__ src = b.it[slot.item].src;
     const uint64_t n = b.it[slot.item].n;
     uint8_t *__restrict__ sm = b.it[slot.item].sm;
+    uint16_t *__restrict__ low = b.it[slot.item].low;
     uint32_t *__restrict__ counts = counts_ws + 256 * slot.item;
     __shared__ uint32_t bins[256 * kHistCopies];
     for (uint32_t i = threadIdx.x; i < 256 * kHistCopies; i += kHistThreads)
@@ -141,23 +200,29 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const Compress
     const uint32_t copy = threadIdx.x & (kHistCopies - 1);
     const uint64_t n_vec = n / 8;
     const uint64_t stride = static_cast<uint64_t>(slot.wgs) * kHistThreads;
-    const uint4 *src4 = reinterpret_cast<const uint4 *>(src);
-    // four 128-bit loads are in flight per lane before any of them is used
+    const uint4 *src4 = static_cast<const uint4 *>(src);
+    // four 128-bit loads (binary32: eight) are in flight per lane before any of them is used
     constexpr uint32_t kDepth = 4;
     for (uint64_t v0 = static_cast<uint64_t>(slot.wg) * kHistThreads + threadIdx.x; v0 < n_vec;
          v0 += stride * kDepth) {
-        uint4 d[kDepth];
+        SourceVec<WIDE> d[kDepth];
 #pragma unroll
         for (uint32_t r = 0; r < kDepth; ++r) {
             const uint64_t v = v0 + r * stride;
-            d[r] = v < n_vec ? src4[v] : make_uint4(0, 0, 0, 0);
+            if (v < n_vec)
+                d[r].load(src4, v);
+            else
+                d[r].clear();
         }
 #pragma unroll
         for (uint32_t r = 0; r < kDepth; ++r) {
             const uint64_t v = v0 + r * stride;
             if (v >= n_vec)
                 break;
-            const uint32_t w[4] = {d[r].x, d[r].y, d[r].z, d[r].w};
+            uint32_t w[4];
+            d[r].words(w);
+            if constexpr (WIDE)
+                reinterpret_cast<uint4 *>(low)[v] = d[r].lows();
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const uint32_t lo = w[p] & 0xFFFFu, hi = w[p] >> 16;
@@ -172,7 +237,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const Compress
         constexpr uint32_t per_byte = 8 / (KB + 1);
         uint32_t acc = 0, filled = 0;
         for (uint64_t i = n_vec * 8; i < n; ++i) {
-            const uint32_t u = src[i];
+            const uint32_t u = source_word<WIDE, true>(src, low, i);
             atomicAdd(&bins[exponent_of(u) * kHistCopies + copy], 1u);
             acc |= signmant_field<KB>(u) << (filled * (KB + 1));
             if (++filled == per_byte) {
@@ -208,7 +273,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const Com
                                                                       uint32_t *__restrict__ counts_ws)
 {
     const ItemSlot slot = item_of_workgroup<&CompressItem::hist_end>(b);
-    const uint16_t *__restrict__ src = b.it[slot.item].src;
+    const uint16_t *__restrict__ src = static_cast<const uint16_t *>(b.it[slot.item].src);
     const uint64_t n = b.it[slot.item].n;
     const uint32_t block = b.it[slot.item].block;
     uint8_t *__restrict__ coef_out = b.it[slot.item].coef;
@@ -537,7 +602,7 @@ __device__ __forceinline__ void ring_flush(uint32_t wp_before, uint32_t wp_after
 // (SPLIT = mantissa bits) of the words it codes, and it reports, through stale[item], any exponent
 // that the table has no room for (such symbols leave the state unchanged; the host then falls
 // back to a compression with fresh statistics).
-template <bool NORM, int SPLIT>
+template <bool NORM, int SPLIT, bool WIDE = false>
 __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch b,
                                                             const EncSym *__restrict__ enc_all,
                                                             uint32_t *__restrict__ chunk_words_all,
@@ -547,10 +612,12 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
                                                             uint32_t *__restrict__ stale)
 {
     static_assert(!(NORM && SPLIT >= 0), "the one-pass variant has no block maxima to normalise with");
+    static_assert(!WIDE || (!NORM && (SPLIT < 0 || SPLIT == 7)), "binary32 tensors are lossless only");
     constexpr int KB = SPLIT >= 0 ? SPLIT : 7;
     const ItemSlot slot_id = item_of_workgroup<&CompressItem::enc_end>(b);
     const CompressItem &it = b.it[slot_id.item];
-    const uint16_t *__restrict__ src = it.src;
+    const void *__restrict__ src = it.src;
+    uint16_t *__restrict__ low = it.low;
     const uint64_t n = it.n;
     const uint8_t *__restrict__ coef = it.coef;
     const uint32_t block_shift = NORM ? 31u - static_cast<uint32_t>(__clz(static_cast<int>(it.block | 1u))) : 0u;
@@ -588,17 +655,24 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     uint8_t *__restrict__ sm = it.sm;
 
     if (m == kChunk) {
-        const uint4 *src4 = reinterpret_cast<const uint4 *>(src + base) + j;
+        // this state's first 8-element vector of the chunk; a turn later is kStates vectors on
+        const uint4 *src4 = static_cast<const uint4 *>(src) + (base / 8 + j) * (WIDE ? 2 : 1);
         // the source words are requested two turns ahead: the wait for a turn's words then leaves
         // the stores of the turn before (ring flush, fields) in flight instead of waiting for them
-        uint4 d = src4[(kTurns - 1) * kStates];
-        uint4 d_next = src4[(kTurns - 2) * kStates];
+        SourceVec<WIDE> d, d_next;
+        d.load(src4, (kTurns - 1) * kStates);
+        d_next.load(src4, (kTurns - 2) * kStates);
         for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
-            const uint4 d_after = src4[(q > 1 ? q - 2 : 0) * kStates];
-            const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+            SourceVec<WIDE> d_after;
+            d_after.load(src4, (q > 1 ? q - 2 : 0) * kStates);
+            uint32_t w[4];
+            d.words(w);
             const uint32_t wp_before = st.wp;
-            if constexpr (SPLIT >= 0)
+            if constexpr (SPLIT >= 0) {
                 store_fields<KB>(sm, base / 8 + static_cast<uint32_t>(q) * kStates + j, pack_fields<KB>(w));
+                if constexpr (WIDE)
+                    reinterpret_cast<uint4 *>(low)[base / 8 + static_cast<uint32_t>(q) * kStates + j] = d.lows();
+            }
             // with block-wise normalisation the exponents coded are those of bf16(w / c)
             float c = 1.0f;
             if constexpr (NORM)
@@ -624,7 +698,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
             for (int t = static_cast<int>(kRun) - 1; t >= 0; --t) {
                 const uint32_t i = static_cast<uint32_t>(q) * kTurn + j * kRun + static_cast<uint32_t>(t);
                 if (i < m) {
-                    uint32_t u = src[base + i];
+                    uint32_t u = source_word<WIDE, (SPLIT >= 0)>(src, low, base + i);
                     if constexpr (NORM)
                         u = normalise_word(u, coefficient(coef[(base + i) >> block_shift]));
                     const EncSym e = enc[exponent_of(u)];

@@ -205,6 +205,92 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
     }
 }
 
+// The same walk for a binary32 tensor (lossless only): the decoded bf16 word is the upper half
+// of the element and the lower half comes from the raw plane, so a turn reads 16 B of lower
+// halves next to its 8 B of fields and writes two 128-bit pieces.
+template <bool LONE, bool STREAM, class WordSrc>
+__device__ __forceinline__ void walk_state_wide(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
+                                                uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
+                                                const uint16_t *__restrict__ low, uint32_t *__restrict__ out,
+                                                uint64_t base, uint32_t m, uint32_t j)
+{
+    constexpr uint32_t kGroup = kTurnGroup;
+    uint32_t next = LONE ? 0u : src.peek(wp);
+    if (m == kChunk) {
+        uint4 *out4 = reinterpret_cast<uint4 *>(out + base) + 2 * j;
+        const uint4 *low4 = reinterpret_cast<const uint4 *>(low + base) + j;
+        const uint64_t first = base + j * kRun;
+        uint64_t fields[kGroup];
+        uint4 lows[kGroup];
+#pragma unroll
+        for (uint32_t r = 0; r < kGroup; ++r) {
+            fields[r] = load_fields<7>(sm, first + r * kTurn);
+            lows[r] = low4[r * kStates];
+        }
+        for (uint32_t q0 = 0; q0 < kTurns; q0 += kGroup) {
+            uint64_t fields_next[kGroup];
+            uint4 lows_next[kGroup];
+            const uint32_t qn = q0 + kGroup < kTurns ? q0 + kGroup : q0;  // the last group re-reads its own
+#pragma unroll
+            for (uint32_t r = 0; r < kGroup; ++r) {
+                fields_next[r] = load_fields<7>(sm, first + (qn + r) * kTurn);
+                lows_next[r] = low4[(qn + r) * kStates];
+            }
+            uint4 o[2 * kGroup];
+#pragma unroll
+            for (uint32_t r = 0; r < kGroup; ++r) {
+                uint32_t e[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    e[t] = LONE ? lone : rans_get(lut, x, wp, next, src);
+                const uint32_t h[4] = {merge_pair<7>(fields[r], 0, e[0], e[1]), merge_pair<7>(fields[r], 1, e[2], e[3]),
+                                       merge_pair<7>(fields[r], 2, e[4], e[5]), merge_pair<7>(fields[r], 3, e[6], e[7])};
+                const uint32_t l[4] = {lows[r].x, lows[r].y, lows[r].z, lows[r].w};
+                // element = upper half << 16 | lower half, for the two elements of each dword pair
+                o[2 * r].x = __builtin_amdgcn_perm(h[0], l[0], 0x05040100u);
+                o[2 * r].y = __builtin_amdgcn_perm(h[0], l[0], 0x07060302u);
+                o[2 * r].z = __builtin_amdgcn_perm(h[1], l[1], 0x05040100u);
+                o[2 * r].w = __builtin_amdgcn_perm(h[1], l[1], 0x07060302u);
+                o[2 * r + 1].x = __builtin_amdgcn_perm(h[2], l[2], 0x05040100u);
+                o[2 * r + 1].y = __builtin_amdgcn_perm(h[2], l[2], 0x07060302u);
+                o[2 * r + 1].z = __builtin_amdgcn_perm(h[3], l[3], 0x05040100u);
+                o[2 * r + 1].w = __builtin_amdgcn_perm(h[3], l[3], 0x07060302u);
+            }
+#pragma unroll
+            for (uint32_t r = 0; r < kGroup; ++r) {
+#pragma unroll
+                for (uint32_t half = 0; half < 2; ++half) {
+                    uint4 *dst = &out4[(q0 + r) * kStates * 2 + half];
+                    const uint4 v = o[2 * r + half];
+                    if constexpr (STREAM) {
+                        __builtin_nontemporal_store(v.x, &dst->x);
+                        __builtin_nontemporal_store(v.y, &dst->y);
+                        __builtin_nontemporal_store(v.z, &dst->z);
+                        __builtin_nontemporal_store(v.w, &dst->w);
+                    } else {
+                        *dst = v;
+                    }
+                }
+                fields[r] = fields_next[r];
+                lows[r] = lows_next[r];
+            }
+        }
+    } else {
+        // ragged last chunk: element by element
+        for (uint32_t q = 0; q < kTurns; ++q) {
+            for (uint32_t t = 0; t < kRun; ++t) {
+                const uint32_t i = q * kTurn + j * kRun + t;
+                if (i >= m)
+                    continue;
+                const uint32_t sym = (LONE ? lone : rans_get(lut, x, wp, next, src)) & 0xFFu;
+                const uint64_t g = base + i;
+                const uint32_t field = sm[g];
+                out[g] = ((field >> 7) << 31) | (sym << 23) | ((field & 0x7Fu) << 16) | low[g];
+            }
+        }
+    }
+}
+
 // What the decoder needs to know about one tensor (all device pointers).
 struct DecodeArgs {
     const TableBlock *tb;
@@ -214,7 +300,8 @@ struct DecodeArgs {
     const uint16_t *words;
     const uint8_t *sm;
     const uint8_t *coef;  // block coefficients (block-wise normalised blobs only)
-    uint16_t *out;
+    const uint16_t *low;  // lower halves (binary32 blobs only)
+    void *out;            // bf16 words, or binary32 words for a binary32 blob
     uint32_t *status;
     uint64_t n;
     uint32_t n_chunks;
@@ -224,7 +311,7 @@ struct DecodeArgs {
 };
 
 // Decodes the chunks of workgroup `wg` of one tensor.
-template <int KB, bool NORM>
+template <int KB, bool NORM, bool WIDE>
 __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ tb,
                                                  const uint32_t *__restrict__ offsets,
                                                  const uint32_t *__restrict__ states,
@@ -232,11 +319,14 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
                                                  const uint16_t *__restrict__ words,
                                                  const uint8_t *__restrict__ sm,
                                                  const uint8_t *__restrict__ coef, uint32_t block,
-                                                 uint16_t *__restrict__ out, bool stream_out,
+                                                 const uint16_t *__restrict__ low, void *__restrict__ out_any,
+                                                 bool stream_out,
                                                  uint64_t n, uint32_t n_chunks, uint32_t *__restrict__ status,
                                                  uint32_t wg, uint32_t *__restrict__ lut, uint8_t *__restrict__ stage)
 {
+    static_assert(!WIDE || (KB == 7 && !NORM), "binary32 blobs are lossless only");
     block = 31u - static_cast<uint32_t>(__clz(static_cast<int>(block | 1u)));  // a power of two: from here on its log2
+    uint16_t *__restrict__ out = static_cast<uint16_t *>(out_any);
     const uint32_t tid = threadIdx.x;
     const uint32_t threads = blockDim.x;            // a multiple of 64, at most kDecThreads
     const uint32_t chunks_per_wg = threads / kStates;
@@ -260,7 +350,7 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
     uint64_t fields0[kPreload];
 #pragma unroll
     for (uint32_t r = 0; r < kPreload; ++r)
-        fields0[r] = m == kChunk ? load_turn<KB, NORM>(sm, coef, block, base + r * kTurn + j * kRun) : 0;
+        fields0[r] = !WIDE && m == kChunk ? load_turn<KB, NORM>(sm, coef, block, base + r * kTurn + j * kRun) : 0;
     const uint4 *lut_g = reinterpret_cast<const uint4 *>(tb->lut);
     uint4 lut_piece[2];  // 16 KB table / 16 B = 1024 pieces; 2 per thread at 512 threads
 #pragma unroll
@@ -309,7 +399,27 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
     // (the streaming and the cached store variants are separate instantiations: merged into one
     // loop the compiler drops the non-temporal hint)
     uint32_t wp = 0, wp_begin = 0;
-    if (lone < 256) {
+    if constexpr (WIDE) {
+        uint32_t *out32 = static_cast<uint32_t *>(out_any);
+        if (lone < 256) {
+            if (stream_out)
+                walk_state_wide<true, true>(lut, NoWords{}, lone, x, wp, sm, low, out32, base, m, j);
+            else
+                walk_state_wide<true, false>(lut, NoWords{}, lone, x, wp, sm, low, out32, base, m, j);
+        } else if (staged) {
+            wp = wp_begin = static_cast<uint32_t>(run_byte - aligned0);
+            if (stream_out)
+                walk_state_wide<false, true>(lut, LdsWords{stage}, 0u, x, wp, sm, low, out32, base, m, j);
+            else
+                walk_state_wide<false, false>(lut, LdsWords{stage}, 0u, x, wp, sm, low, out32, base, m, j);
+        } else {
+            const GlobalWords direct{reinterpret_cast<const uint8_t *>(words) + run_byte};
+            if (stream_out)
+                walk_state_wide<false, true>(lut, direct, 0u, x, wp, sm, low, out32, base, m, j);
+            else
+                walk_state_wide<false, false>(lut, direct, 0u, x, wp, sm, low, out32, base, m, j);
+        }
+    } else if (lone < 256) {
         if (stream_out)
             walk_state<KB, true, NORM, true>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j);
         else
@@ -336,13 +446,13 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
         atomicOr(status, 1u);
 }
 
-template <int KB, bool NORM>
+template <int KB, bool NORM, bool WIDE = false>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(const DecodeArgs a)
 {
     __shared__ __align__(16) uint32_t lut[kM];
     __shared__ __align__(16) uint8_t stage[kStageBytes];
-    decode_workgroup<KB, NORM>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.out, a.stream_out != 0, a.n,
-                               a.n_chunks, a.status, blockIdx.x, lut, stage);
+    decode_workgroup<KB, NORM, WIDE>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.low, a.out,
+                                     a.stream_out != 0, a.n, a.n_chunks, a.status, blockIdx.x, lut, stage);
 }
 
 // Several tensors in one launch (a layer's weights): workgroups [t[i-1].wg_end, t[i].wg_end)
@@ -352,7 +462,7 @@ struct BatchArgs {
     uint32_t count;
 };
 
-template <int KB, bool NORM>
+template <int KB, bool NORM, bool WIDE = false>
 __global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchArgs b)
 {
     __shared__ __align__(16) uint32_t lut[kM];
@@ -363,8 +473,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchAr
         ++i;
     }
     const DecodeArgs &a = b.t[i];
-    decode_workgroup<KB, NORM>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.out, a.stream_out != 0, a.n,
-                               a.n_chunks, a.status, blockIdx.x - first, lut, stage);
+    decode_workgroup<KB, NORM, WIDE>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.low, a.out,
+                                     a.stream_out != 0, a.n, a.n_chunks, a.status, blockIdx.x - first, lut, stage);
 }
 
 }  // namespace nz

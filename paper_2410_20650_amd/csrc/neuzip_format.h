@@ -73,7 +73,7 @@ struct EncSym {
 constexpr uint32_t kBatchMax = 8;
 
 struct CompressItem {
-    const uint16_t *src;
+    const void *src;       // bf16 words, or binary32 words when the batch is of that type
     uint64_t n;
     TableBlock *tb;
     uint32_t *offsets;
@@ -81,6 +81,7 @@ struct CompressItem {
     uint8_t *lens;
     uint8_t *sm;
     uint8_t *coef;
+    uint16_t *low;         // binary32 tensors: the plane of lower halves
     uint16_t *words;       // known only after the stream length has been read back
     uint32_t n_chunks;
     uint32_t block;        // 0: no block-wise normalisation

@@ -62,10 +62,34 @@ def constant_bf16(n: int, value: float, device="cpu") -> torch.Tensor:
 
 
 def synthetic_update(w: torch.Tensor, seed: int, std: float = 1e-4) -> torch.Tensor:
-    """Stand-in for an optimiser step: w + N(0, std^2) in fp32, rounded back to bf16."""
+    """Stand-in for an optimiser step: w + N(0, std^2) in fp32, rounded back to the type of w."""
     g = _generator(seed, w.device)
     noise = torch.randn(w.shape, generator=g, device=w.device, dtype=torch.float32) * std
-    return (w.float() + noise).to(torch.bfloat16)
+    return (w.float() + noise).to(w.dtype)
+
+
+def gaussian_f32(n_or_shape, seed: int, std: float = 0.02, device="cpu") -> torch.Tensor:
+    """i.i.d. N(0, std^2) in binary32: master weights or optimiser-side copies of the same layers."""
+    shape = (n_or_shape,) if isinstance(n_or_shape, int) else tuple(n_or_shape)
+    g = _generator(seed, device)
+    return torch.randn(shape, generator=g, device=device, dtype=torch.float32) * std
+
+
+def all_upper_halves_f32(low: int, device="cpu") -> torch.Tensor:
+    """The 65,536 binary32 words whose upper half runs over every pattern, all with the given lower half."""
+    v = (torch.arange(65536, dtype=torch.int64, device=device) << 16) | int(low)
+    return (v - (v >= 2 ** 31) * 2 ** 32).to(torch.int32).view(torch.float32)
+
+
+def bits32(t: torch.Tensor) -> np.ndarray:
+    """Raw 32-bit words of a float32 tensor as a flat uint32 numpy array (host copy)."""
+    assert t.dtype == torch.float32
+    return t.detach().contiguous().view(torch.int32).cpu().numpy().view(np.uint32).reshape(-1)
+
+
+def from_bits32(words: np.ndarray, device="cpu") -> torch.Tensor:
+    w = np.ascontiguousarray(words, dtype=np.uint32).view(np.int32)
+    return torch.from_numpy(w.copy()).to(device).view(torch.float32)
 
 
 def bits(t: torch.Tensor) -> np.ndarray:

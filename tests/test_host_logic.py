@@ -37,7 +37,7 @@ def test_library_exports_every_declared_symbol(nz):
 def test_binding_mirrors_the_header(nz):
     for name in declared_functions():
         if name in ("neuzip_strerror", "neuzip_last_hip_error", "neuzip_elems", "neuzip_mantissa_bits",
-                    "neuzip_device_bytes", "neuzip_block_size", "neuzip_guard"):
+                    "neuzip_device_bytes", "neuzip_block_size", "neuzip_guard", "neuzip_dtype"):
             continue  # surfaced as Blob properties / NeuzipError fields
         assert hasattr(nz, name), f"binding lacks {name}"
 
@@ -60,7 +60,9 @@ def test_argument_validation_happens_before_device_work(nz):
     fake = ctypes.c_void_p(0x1000)
     # null out-pointer, bad dtype, bad mantissa_bits, misaligned source, oversize
     assert lib.neuzip_compress(fake, 16, 0, 7, None, None) == nz.EINVAL
-    assert lib.neuzip_compress(fake, 16, 1, 7, None, ctypes.byref(handle)) == nz.EINVAL
+    assert lib.neuzip_compress(fake, 16, 2, 7, None, ctypes.byref(handle)) == nz.EINVAL
+    assert lib.neuzip_compress(fake, 16, nz.F32, 3, None, ctypes.byref(handle)) == nz.EUNSUPPORTED   # lossless only
+    assert lib.neuzip_compress_blockwise(fake, 16, nz.F32, 3, 64, None, ctypes.byref(handle)) == nz.EUNSUPPORTED
     for k in (-1, 2, 4, 5, 6, 8):
         assert lib.neuzip_compress(fake, 16, 0, k, None, ctypes.byref(handle)) == nz.EINVAL
     assert lib.neuzip_compress(ctypes.c_void_p(0x1002), 16, 0, 7, None, ctypes.byref(handle)) == nz.EINVAL
