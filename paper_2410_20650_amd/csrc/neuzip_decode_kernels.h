@@ -217,7 +217,12 @@ __device__ __forceinline__ void walk_state_wide(const uint32_t *__restrict__ lut
     constexpr uint32_t kGroup = kTurnGroup;
     uint32_t next = LONE ? 0u : src.peek(wp);
     if (m == kChunk) {
-        uint4 *out4 = reinterpret_cast<uint4 *>(out + base) + 2 * j;
+        // where this lane stores: its own pieces 2j and 2j + 1 of a turn's 32, or, after the exchange
+        // described below, pieces (j / 8) * 16 + j % 8 and 8 further
+        uint4 *out4 = reinterpret_cast<uint4 *>(out + base) + (STREAM ? (j >> 3) * 16 + (j & 7) : 2 * j);
+        const uint32_t lane = threadIdx.x & 63u;
+        const uint32_t pull[2] = {((lane & ~7u) + ((lane & 7u) >> 1)) * 4u, ((lane & ~7u) + 4u + ((lane & 7u) >> 1)) * 4u};
+        const bool odd = lane & 1u;
         const uint4 *low4 = reinterpret_cast<const uint4 *>(low + base) + j;
         const uint64_t first = base + j * kRun;
         uint64_t fields[kGroup];
@@ -246,21 +251,44 @@ __device__ __forceinline__ void walk_state_wide(const uint32_t *__restrict__ lut
                 const uint32_t h[4] = {merge_pair<7>(fields[r], 0, e[0], e[1]), merge_pair<7>(fields[r], 1, e[2], e[3]),
                                        merge_pair<7>(fields[r], 2, e[4], e[5]), merge_pair<7>(fields[r], 3, e[6], e[7])};
                 const uint32_t l[4] = {lows[r].x, lows[r].y, lows[r].z, lows[r].w};
-                // element = upper half << 16 | lower half, for the two elements of each dword pair
-                o[2 * r].x = __builtin_amdgcn_perm(h[0], l[0], 0x05040100u);
-                o[2 * r].y = __builtin_amdgcn_perm(h[0], l[0], 0x07060302u);
-                o[2 * r].z = __builtin_amdgcn_perm(h[1], l[1], 0x05040100u);
-                o[2 * r].w = __builtin_amdgcn_perm(h[1], l[1], 0x07060302u);
-                o[2 * r + 1].x = __builtin_amdgcn_perm(h[2], l[2], 0x05040100u);
-                o[2 * r + 1].y = __builtin_amdgcn_perm(h[2], l[2], 0x07060302u);
-                o[2 * r + 1].z = __builtin_amdgcn_perm(h[3], l[3], 0x05040100u);
-                o[2 * r + 1].w = __builtin_amdgcn_perm(h[3], l[3], 0x07060302u);
+                // element = upper half << 16 | lower half: this lane's 8 elements as 16-byte pieces 2j, 2j + 1
+                // of the turn's 32
+                uint32_t mine[2][4];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    mine[d >> 1][2 * (d & 1)] = __builtin_amdgcn_perm(h[d], l[d], 0x05040100u);
+                    mine[d >> 1][2 * (d & 1) + 1] = __builtin_amdgcn_perm(h[d], l[d], 0x07060302u);
+                }
+                // A 128-bit store of piece 2j by every lane leaves every other 16 bytes of a cache line
+                // to a second instruction.  In the cache that is harmless, but once the tensor streams
+                // to HBM such half-written lines cost a third of the store rate.  There the 8 lanes of
+                // an octet trade pieces: store `half` of lane t writes piece 8 * half + t of the
+                // octet's 16, which lane 4 * half + t / 2 holds (its first piece for even t), and each
+                // store instruction covers whole 128-byte lines.  (The 16 lane exchanges per turn cost
+                // 20 % of the rate of a cache-resident tensor, which therefore keeps the plain stores.)
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    uint32_t got[4];
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        if constexpr (STREAM) {
+                            const uint32_t first = __builtin_amdgcn_ds_bpermute(static_cast<int>(pull[half]),
+                                                                                static_cast<int>(mine[0][d]));
+                            const uint32_t second = __builtin_amdgcn_ds_bpermute(static_cast<int>(pull[half]),
+                                                                                 static_cast<int>(mine[1][d]));
+                            got[d] = odd ? second : first;
+                        } else {
+                            got[d] = mine[half][d];
+                        }
+                    }
+                    o[2 * r + half] = make_uint4(got[0], got[1], got[2], got[3]);
+                }
             }
 #pragma unroll
             for (uint32_t r = 0; r < kGroup; ++r) {
 #pragma unroll
                 for (uint32_t half = 0; half < 2; ++half) {
-                    uint4 *dst = &out4[(q0 + r) * kStates * 2 + half];
+                    uint4 *dst = &out4[(q0 + r) * kStates * 2 + half * (STREAM ? 8 : 1)];
                     const uint4 v = o[2 * r + half];
                     if constexpr (STREAM) {
                         __builtin_nontemporal_store(v.x, &dst->x);

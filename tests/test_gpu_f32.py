@@ -177,3 +177,28 @@ def test_f32_argument_errors(nz):
     with pytest.raises(nz.NeuzipError):
         nz.neuzip_import(c)
     assert np.array_equal(decoded(nz, blob, w), inputs.bits32(w))   # untouched by the failed calls
+
+
+def test_f32_tensor_that_streams_to_hbm(nz):
+    # from 2^25 elements on the decoder stores non-temporally and the lanes of an octet trade
+    # 16-byte pieces so that every store instruction covers whole cache lines
+    n = (32 << 20) + 4096 + 1234
+    w = inputs.gaussian_f32(n, 9860, device=DEV)
+    words = inputs.bits32(w)
+    blob = nz.neuzip_compress(w, 7)
+    out = torch.zeros_like(w)
+    nz.neuzip_decompress(blob, out)
+    nz.neuzip_check(blob)
+    assert np.array_equal(inputs.bits32(out), words)
+    same_container(nz.neuzip_export(blob), O.compress_f32(words, threads=8), "streaming size")
+    # the same decoder inside a batch, next to a small tensor and a bf16 one
+    small = inputs.gaussian_f32(70_000, 9861, device=DEV)
+    half = inputs.gaussian_bf16(90_000, 9862, device=DEV)
+    blobs = [blob, nz.neuzip_compress(small, 7), nz.neuzip_compress(half, 7)]
+    outs = [torch.zeros_like(w), torch.zeros_like(small), torch.zeros_like(half)]
+    nz.neuzip_decompress_batch(blobs, outs)
+    for b in blobs:
+        nz.neuzip_check(b)
+    assert np.array_equal(inputs.bits32(outs[0]), words)
+    assert np.array_equal(inputs.bits32(outs[1]), inputs.bits32(small))
+    assert np.array_equal(inputs.bits(outs[2]), inputs.bits(half))
