@@ -262,6 +262,33 @@ def main():
         ext["linear_forward"] = lin
         torch.cuda.empty_cache()
 
+        # binary32 tensors (beyond the paper's BFloat16): the 8B-shaped MLP weight as float32 --
+        # the upper halves take the lossless path, the lower halves ride along as a raw plane
+        w32 = inputs.gaussian_f32(inputs.MLP_8B, inputs.seed_for(9), device=dev)
+        n32 = w32.numel()
+        o32 = torch.empty_like(w32)
+        (b32,) = nz.neuzip_compress_guarded([w32], 7, 8)
+        u32 = inputs.synthetic_update(w32, inputs.seed_for(9, 1))
+        f32 = {"elements": n32, "bits_per_weight": round(8.0 * b32.compressed_bytes / n32, 4)}
+        for name, fn, nbytes in (("decompress", lambda: nz.neuzip_decompress(b32, o32), b32.compressed_bytes + 4.0 * n32),
+                                 ("compress", lambda: nz.neuzip_compress_guarded([w32], 7, 8, blobs=[b32]),
+                                  4.0 * n32 * 2 + b32.compressed_bytes),
+                                 ("recompress_kept_table", lambda: nz.neuzip_recompress([u32], [b32]),
+                                  4.0 * n32 + b32.compressed_bytes)):
+            for _ in range(3):
+                fn()
+            _, ms = timed_region(torch, stream, fn, 20)
+            ms /= 20
+            f32[name] = {"us": round(ms * 1e3, 1), "GBps_tensor": round(4.0 * n32 / (ms * 1e-3) / 1e9, 1),
+                         "hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        nz.neuzip_decompress(b32, o32)
+        assert torch.equal(o32.view(torch.int32), u32.view(torch.int32)), "binary32 round trip"
+        f32["bitwise_round_trip"] = "verified"
+        ext["binary32_mlp_8b"] = f32
+        nz.neuzip_free(b32)
+        del w32, o32, u32
+        torch.cuda.empty_cache()
+
         # config 3: every weight of a Llama-3-8B-shaped model, forward order, one reusable scratch
         names = inputs.llama3_8b_tensors()
         if args.layers < 32:

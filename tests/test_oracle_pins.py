@@ -735,3 +735,93 @@ def test_f32_guard_band_and_kept_table():
     with pytest.raises(O.OracleError) as err:
         O.compress_f32(w2, guard=8, freq=table)
     assert err.value.code == O.ESTALE
+
+
+# ---------------------------------------------------------------- the weight update of the backward loop (Alg. 1)
+
+def _round_nearest_even(value, bits):
+    """The real `value` (a Fraction) rounded to `bits` significant binary digits, ties to even
+    (normal range only): rounding written out on the rationals."""
+    from fractions import Fraction
+    if value == 0:
+        return Fraction(0)
+    sign = -1 if value < 0 else 1
+    mag = abs(value)
+    e = mag.numerator.bit_length() - mag.denominator.bit_length()
+    if Fraction(2) ** e > mag:
+        e -= 1
+    assert Fraction(2) ** e <= mag < Fraction(2) ** (e + 1)
+    scaled = mag / Fraction(2) ** (e - bits + 1)               # in [2^(bits-1), 2^bits)
+    whole, rest = divmod(scaled, 1)
+    if rest > Fraction(1, 2) or (rest == Fraction(1, 2) and whole % 2 == 1):
+        whole += 1
+    return sign * whole * Fraction(2) ** (e - bits + 1)
+
+
+def test_update_closed_cases_from_golden_file():
+    from oracle import update as U
+    rows = [line.split() for line in open(os.path.join(os.path.dirname(__file__), "golden", "sgd_update.txt"))
+            if line.strip() and not line.startswith("#")]
+    assert len(rows) >= 10
+    for w, g, lr, want in rows:
+        got = U.sgd_update(np.array([int(w, 16)], np.uint16), np.array([int(g, 16)], np.uint16), float.fromhex(lr))
+        assert int(got[0]) == int(want, 16), (w, g, lr, want, hex(int(got[0])))
+
+
+def test_update_matches_exact_rational_arithmetic():
+    from fractions import Fraction
+    from oracle import update as U
+    rng = np.random.default_rng(101)
+    w = inputs.bits(inputs.gaussian_bf16(400, seed=102))
+    g = inputs.bits(inputs.gaussian_bf16(400, seed=103, std=1.0))
+    as_real = lambda u: Fraction(float((np.uint32(u) << 16).view(np.float32)))
+    for lr in (1e-3, 0.37, 2.0 ** -6):
+        lr32 = Fraction(float(np.float32(lr)))
+        got = U.sgd_update(w, g, lr)
+        for i in range(w.size):
+            step = _round_nearest_even(lr32 * as_real(g[i]), 24)            # the product, rounded to binary32
+            new = _round_nearest_even(as_real(w[i]) - step, 24)             # the difference, rounded to binary32
+            want = _round_nearest_even(new, 8)                              # to bf16
+            assert as_real(got[i]) == want, (i, lr)
+    assert rng is not None
+
+
+def test_update_against_torch_and_invariants():
+    import torch
+    from oracle import update as U
+    w = inputs.all_patterns_bf16()
+    wb = inputs.bits(w)
+    for seed, lr in ((1, 1e-2), (2, 3.0), (3, 1e-30)):
+        g = inputs.random_bits_bf16(65536, seed=110 + seed)
+        got = U.sgd_update(wb, inputs.bits(g), lr)
+        ref32 = w.float() - torch.tensor(lr, dtype=torch.float32) * g.float()   # library float32 arithmetic
+        ref = inputs.bits(ref32.to(torch.bfloat16))                             # library rounding to bf16
+        nan = torch.isnan(ref32).numpy()
+        assert np.array_equal(got[~nan], ref[~nan])
+        assert np.all(got[nan] == 0x7FC0)
+    # a zero gradient changes nothing (NaNs become the canonical one)
+    zero = np.zeros(65536, np.uint16)
+    same = U.sgd_update(wb, zero, 0.5)
+    is_nan = (wb & 0x7FFF) > 0x7F80
+    assert np.array_equal(same[~is_nan], wb[~is_nan]) and np.all(same[is_nan] == 0x7FC0)
+    # flipping the sign of the gradient and of the rate together changes nothing
+    g = inputs.bits(inputs.gaussian_bf16(65536, seed=120, std=1.0))
+    assert np.array_equal(U.sgd_update(wb, g, 0.01), U.sgd_update(wb, g ^ 0x8000, -0.01))
+
+
+def test_training_step_container_follows_the_kept_table_rules():
+    from oracle import update as U
+    n = 30_000
+    w0 = inputs.bits(inputs.gaussian_bf16(n, seed=130))
+    g = inputs.bits(inputs.gaussian_bf16(n, seed=131, std=1.0))
+    first = O.compress(w0, 7, guard=8)
+    new_container, rebuilt, new = U.training_step(first, g, 1e-4)
+    assert rebuilt == 0
+    assert np.array_equal(new, U.sgd_update(w0, g, 1e-4))
+    assert np.array_equal(O.decompress(new_container, n), new)
+    assert np.array_equal(O.blob_info(new_container)["freq"], O.blob_info(first)["freq"])   # the table was kept
+    # a step large enough to leave the guard band: fresh statistics
+    big, rebuilt, new = U.training_step(first, g, 1e6)
+    assert rebuilt == 1
+    assert np.array_equal(O.decompress(big, n), U.sgd_update(w0, g, 1e6))
+    assert np.array_equal(big, O.compress(new, 7, guard=8))
