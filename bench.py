@@ -289,6 +289,37 @@ def main():
         del w32, o32, u32
         torch.cuda.empty_cache()
 
+        # the weight update of the backward loop (Alg. 1): W <- W - lr * grad on the compressed 8B-shaped
+        # MLP weight, as one library call (the decoder applies the step, then the kept-table encoder)
+        # against decompress, torch's in-place bf16 step, recompress
+        wu = inputs.gaussian_bf16(inputs.MLP_8B, inputs.seed_for(10), device=dev)
+        gu = inputs.gaussian_bf16(inputs.MLP_8B, inputs.seed_for(10, 1), std=0.05, device=dev)
+        su = torch.empty_like(wu)
+        (bu,) = nz.neuzip_compress_guarded([wu], 7, 8)
+        flags = []
+
+        def update_fused():
+            flags.extend(nz.neuzip_update([bu], [gu], [su], 1e-3))
+
+        def update_separate():
+            nz.neuzip_decompress(bu, su.view(-1))
+            su.add_(gu, alpha=-1e-3)
+            flags.extend(nz.neuzip_recompress([su], [bu]))
+
+        upd = {"elements": wu.numel(), "lr": 1e-3}
+        for name, fn in (("one_call", update_fused), ("decompress_torch_step_recompress", update_separate)):
+            for _ in range(3):
+                fn()
+            del flags[:]
+            _, ms = timed_region(torch, stream, fn, 20)
+            ms /= 20
+            upd[name] = {"us": round(ms * 1e3, 1), "GBps_weights": round(2.0 * wu.numel() / (ms * 1e-3) / 1e9, 1),
+                         "tensors_rebuilt": sum(flags)}
+        ext["sgd_update_mlp_8b"] = upd
+        nz.neuzip_free(bu)
+        del wu, gu, su
+        torch.cuda.empty_cache()
+
         # config 3: every weight of a Llama-3-8B-shaped model, forward order, one reusable scratch
         names = inputs.llama3_8b_tensors()
         if args.layers < 32:

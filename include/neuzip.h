@@ -154,6 +154,34 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
                       uint32_t *rebuilt);
 
 /*
+ * neuzip_update -- the backward loop of Alg. 1 for the weights of a layer: each weight is
+ * decompressed into temporary space, the optimiser step is applied, and the weight is compressed
+ * again ("decompression", "merge", the update, "split", "compression", "store"); Sec. 2.2 applies
+ * vanilla SGD layer by layer during the backward pass, so that neither the full set of gradients
+ * nor an uncompressed model ever exists:
+ *     W_hat <- decompress(c);   W_hat <- W_hat - lr * grad;   c <- compress(W_hat)
+ *
+ *   blobs       host array of count blobs holding lossless bf16 weights (mantissa_bits 7, no
+ *               normalisation; anything else -> EUNSUPPORTED), distinct; they receive the new weights.
+ *   d_grads     host array of count device pointers: the gradient of each weight, bf16 words,
+ *               neuzip_elems(blobs[i]) of them, 16-byte aligned (read only).
+ *   d_weights   host array of count device pointers, 16-byte aligned: temporary space of
+ *               neuzip_elems(blobs[i]) bf16 words each, not overlapping; on return it holds the new
+ *               weights uncompressed (the caller may use or discard them).
+ *   lr          learning rate.
+ *   rebuilt     as for neuzip_recompress; may be NULL.
+ * Reading taken for the arithmetic, which the paper leaves open: per element, in IEEE binary32,
+ * the product lr * g and then the difference w - (lr * g) are each rounded to nearest (no fused
+ * multiply-add), and the result is rounded to the nearest bf16, ties to even; a NaN result is
+ * stored as 0x7FC0.  Two passes: the decoder applies the step on its way out (the old weight is
+ * never written), then the new weight is coded with the table the blob holds, exactly as
+ * neuzip_recompress does -- including its fallback to fresh statistics.  Synchronises the stream
+ * once per group of up to 8 weights.
+ */
+int neuzip_update(neuzip_blob *const *blobs, const void *const *d_grads, void *const *d_weights, uint32_t count,
+                  float lr, void *hip_stream, uint32_t *rebuilt);
+
+/*
  * neuzip_decompress -- Sec. 2.2 Eq. (3), Alg. 1 "decompression" + "merge":
  * decodes the exponents and reassembles bf16 words into the caller's
  * temporary space in one fused kernel.

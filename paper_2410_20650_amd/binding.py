@@ -41,6 +41,8 @@ def _load():
     lib.neuzip_compress_guarded.restype = i32
     lib.neuzip_recompress.argtypes = [vpp, u32, vp, vpp, ctypes.POINTER(u32)]
     lib.neuzip_recompress.restype = i32
+    lib.neuzip_update.argtypes = [vpp, vpp, vpp, u32, ctypes.c_float, vp, ctypes.POINTER(u32)]
+    lib.neuzip_update.restype = i32
     lib.neuzip_linear.argtypes = [vp, u64, u64, vp, u32, vp, vp, vp]
     lib.neuzip_linear.restype = i32
     lib.neuzip_block_size.argtypes = [vp]
@@ -88,7 +90,7 @@ _lib = None
 _lib = _load()
 
 EXPORTED = ["neuzip_compress", "neuzip_compress_blockwise", "neuzip_compress_batch", "neuzip_compress_guarded",
-            "neuzip_recompress", "neuzip_guard", "neuzip_linear", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
+            "neuzip_recompress", "neuzip_update", "neuzip_guard", "neuzip_linear", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
             "neuzip_free",
             "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits", "neuzip_dtype",
             "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check",
@@ -203,6 +205,25 @@ def neuzip_recompress(srcs, blobs, stream=None):
     rc = _lib.neuzip_recompress(ptrs, count, _stream_handle(stream), handles, rebuilt)
     if rc != OK:
         raise NeuzipError(rc, "neuzip_recompress")
+    return [int(v) for v in rebuilt]
+
+
+def neuzip_update(blobs, grads, weights, lr: float, stream=None):
+    """blobs[i] <- compress(decompress(blobs[i]) - lr * grads[i]); weights[i] receives the new weight.
+    Returns the list of rebuilt flags."""
+    for t in list(grads) + list(weights):
+        _check_tensor(t)
+    if not (len(blobs) == len(grads) == len(weights)) or any(
+            b.elems != g.numel() or b.elems != w.numel() for b, g, w in zip(blobs, grads, weights)):
+        raise ValueError("one gradient and one temporary tensor of matching size per blob")
+    count = len(blobs)
+    handles = (ctypes.c_void_p * count)(*[b.handle.value for b in blobs])
+    gptrs = (ctypes.c_void_p * count)(*[g.data_ptr() for g in grads])
+    wptrs = (ctypes.c_void_p * count)(*[w.data_ptr() for w in weights])
+    rebuilt = (ctypes.c_uint32 * count)()
+    rc = _lib.neuzip_update(handles, gptrs, wptrs, count, lr, _stream_handle(stream), rebuilt)
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_update")
     return [int(v) for v in rebuilt]
 
 

@@ -337,6 +337,8 @@ DecodeArgs decode_args(const neuzip_blob *b, void *d_dst)
     a.sm = sm_of(b);
     a.coef = coef_of(b);
     a.low = low_of(b);
+    a.grad = nullptr;
+    a.lr = 0.0f;
     a.block = b->block;
     // 2 bytes out + ~1.3 in per element against 256 MB of Infinity Cache: beyond ~64 M elements
     // (half as many of binary32) the tensor streams through HBM and non-temporal stores measured
@@ -350,12 +352,12 @@ DecodeArgs decode_args(const neuzip_blob *b, void *d_dst)
     return a;
 }
 
-template <int KB, bool NORM, bool WIDE = false>
+template <int KB, bool NORM, int MODE = kPlain>
 int launch_decode(const neuzip_blob *b, void *d_dst, hipStream_t stream)
 {
     const uint32_t per = decode_chunks_per_wg();
     const uint32_t groups = (b->n_chunks + per - 1) / per;
-    hipLaunchKernelGGL((decode_kernel<KB, NORM, WIDE>), dim3(groups), dim3(per * kStates), 0, stream,
+    hipLaunchKernelGGL((decode_kernel<KB, NORM, MODE>), dim3(groups), dim3(per * kStates), 0, stream,
                        decode_args(b, d_dst));
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
@@ -365,7 +367,7 @@ int decode_dispatch(const neuzip_blob *b, void *d_dst, hipStream_t stream)
     if (b->n == 0)
         return NEUZIP_OK;
     if (b->f32)
-        return launch_decode<7, false, true>(b, d_dst, stream);
+        return launch_decode<7, false, kWide>(b, d_dst, stream);
     if (b->block) {
         switch (b->k) {
         case 3: return launch_decode<3, true>(b, d_dst, stream);
@@ -394,7 +396,8 @@ int launch_batch(const BatchArgs &args, int variant, uint32_t groups, hipStream_
     case 0: hipLaunchKernelGGL((decode_batch_kernel<0, false>), grid, block, 0, stream, args); break;
     case 11: hipLaunchKernelGGL((decode_batch_kernel<3, true>), grid, block, 0, stream, args); break;
     case 9: hipLaunchKernelGGL((decode_batch_kernel<1, true>), grid, block, 0, stream, args); break;
-    case 23: hipLaunchKernelGGL((decode_batch_kernel<7, false, true>), grid, block, 0, stream, args); break;
+    case 23: hipLaunchKernelGGL((decode_batch_kernel<7, false, kWide>), grid, block, 0, stream, args); break;
+    case 39: hipLaunchKernelGGL((decode_batch_kernel<7, false, kUpdate>), grid, block, 0, stream, args); break;
     default: hipLaunchKernelGGL((decode_batch_kernel<0, true>), grid, block, 0, stream, args); break;
     }
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
@@ -743,6 +746,61 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
         first += m;
     }
     return NEUZIP_OK;
+}
+
+int neuzip_update(neuzip_blob *const *blobs, const void *const *d_grads, void *const *d_weights, uint32_t count, float lr,
+                  void *hip_stream, uint32_t *rebuilt)
+{
+    if (count == 0)
+        return NEUZIP_OK;
+    if (!blobs || !d_grads || !d_weights)
+        return NEUZIP_EINVAL;
+    for (uint32_t i = 0; i < count; ++i) {
+        const neuzip_blob *b = blobs[i];
+        if (!is_blob(b) || !b->has_table || !on_current_device(b))
+            return NEUZIP_EINVAL;
+        if (b->k != 7 || b->block != 0 || b->f32)
+            return NEUZIP_EUNSUPPORTED;  // training keeps bf16 weights without loss
+        if (b->n > 0 && (!d_grads[i] || !d_weights[i] || (reinterpret_cast<uintptr_t>(d_grads[i]) & 15u) ||
+                         (reinterpret_cast<uintptr_t>(d_weights[i]) & 15u)))
+            return NEUZIP_EINVAL;
+        for (uint32_t j = 0; j < i; ++j)
+            if (blobs[j] == b)
+                return NEUZIP_EINVAL;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // 1. decode each weight and apply the step on the way out: d_weights[i] receives the new weight
+    uint64_t batch_elems = 0;
+    for (uint32_t i = 0; i < count; ++i)
+        batch_elems += blobs[i]->n;
+    const bool stream_out = batch_elems >= (64ull << 20);
+    BatchArgs args;
+    args.count = 0;
+    uint32_t groups = 0;
+    for (uint32_t i = 0; i <= count; ++i) {
+        const bool flush = (i == count) || (args.count == kBatchMax);
+        if (flush && args.count > 0) {
+            const int rc = launch_batch(args, 39, groups, stream);
+            if (rc != NEUZIP_OK)
+                return rc;
+            args.count = 0;
+            groups = 0;
+        }
+        if (i == count)
+            break;
+        const neuzip_blob *b = blobs[i];
+        if (b->n == 0)
+            continue;
+        DecodeArgs a = decode_args(b, d_weights[i]);
+        a.grad = static_cast<const uint16_t *>(d_grads[i]);
+        a.lr = lr;
+        a.stream_out = stream_out ? 1u : 0u;
+        groups += (b->n_chunks + kDecChunksPerWg - 1) / kDecChunksPerWg;
+        a.wg_end = groups;
+        args.t[args.count++] = a;
+    }
+    // 2. code the new weights with the tables the blobs hold (fresh tables where those do not serve)
+    return neuzip_recompress(d_weights, count, hip_stream, blobs, rebuilt);
 }
 
 uint32_t neuzip_guard(const neuzip_blob *blob) { return is_blob(blob) ? blob->guard : 0; }

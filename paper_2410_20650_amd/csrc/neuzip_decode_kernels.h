@@ -126,20 +126,62 @@ __device__ __forceinline__ uint32_t denormalise_pair(uint32_t d, float c)
     return r;
 }
 
-template <int KB, bool LONE, bool NORM, bool STREAM, class WordSrc>
+// The weight update of the backward loop (Alg. 1: W_hat <- W_hat - lr * grad) on the two halves of
+// a merged dword: product and difference each rounded to binary32 (no fused multiply-add), the
+// result rounded to the nearest-even bf16, a NaN result stored as 0x7FC0.
+__device__ __forceinline__ float sgd_step(float w, float g, float lr)
+{
+#pragma clang fp contract(off)
+    const float step = lr * g;
+    return w - step;
+}
+
+__device__ __forceinline__ uint32_t update_pair(uint32_t w, uint32_t g, float lr)
+{
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
+    const f32x2_t v = {sgd_step(__uint_as_float(w << 16), __uint_as_float(g << 16), lr),
+                       sgd_step(__uint_as_float(w & 0xFFFF0000u), __uint_as_float(g & 0xFFFF0000u), lr)};
+    uint32_t r = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+    if (v[0] != v[0])
+        r = (r & 0xFFFF0000u) | 0x7FC0u;
+    if (v[1] != v[1])
+        r = (r & 0x0000FFFFu) | 0x7FC00000u;
+    return r;
+}
+
+__device__ __forceinline__ uint32_t update_word(uint32_t w, uint32_t g, float lr)
+{
+    const float v = sgd_step(__uint_as_float(w << 16), __uint_as_float(g << 16), lr);
+    return v != v ? 0x7FC0u : bf16_of(v);
+}
+
+// UPD: the words written are the decoded weights after the update with the gradient `grad` (bf16
+// words, same indexing as the output) and the rate lr.
+template <int KB, bool LONE, bool NORM, bool STREAM, bool UPD, class WordSrc>
 __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
                                            uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
                                            const uint8_t *__restrict__ coef, uint32_t block,
                                            uint64_t (&fields)[KB == 7 ? kTurnGroupStream : kTurnGroup],
                                            uint16_t *__restrict__ out,
-                                           uint64_t base, uint32_t m, uint32_t j)
+                                           uint64_t base, uint32_t m, uint32_t j,
+                                           const uint16_t *__restrict__ grad = nullptr, float lr = 0.0f)
 {
+    static_assert(!UPD || (KB == 7 && !NORM), "only lossless weights are trained");
     // `fields` arrives holding the field bits of the state's first turns (full chunks only)
-    constexpr uint32_t kGroup = (STREAM && KB == 7) ? kTurnGroupStream : kTurnGroup;
+    constexpr uint32_t kGroup = (STREAM && KB == 7 && !UPD) ? kTurnGroupStream : kTurnGroup;
     uint32_t next = LONE ? 0u : src.peek(wp);
     if (m == kChunk) {
         uint4 *out4 = reinterpret_cast<uint4 *>(out + base) + j;
         const uint64_t first = base + j * kRun;
+        // the gradients of a turn: the 128 bits the lane's output words come from
+        const uint4 *grad4 = UPD ? reinterpret_cast<const uint4 *>(grad + base) + j : nullptr;
+        uint4 grads[kGroup];
+        if constexpr (UPD) {
+#pragma unroll
+            for (uint32_t r = 0; r < kGroup; ++r)
+                grads[r] = grad4[r * kStates];
+        }
         // Turns are taken in groups: the field loads of the next group are issued together before
         // the current group is decoded, and the group's 128-bit stores leave back to back, so
         // each state keeps several memory requests in flight and a chunk is written in bursts of
@@ -151,6 +193,12 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
 #pragma unroll
             for (uint32_t r = 0; r < kGroup; ++r)
                 fields_next[r] = load_turn<KB, NORM>(sm, coef, block, first + (qn + r) * kTurn);
+            uint4 grads_next[kGroup];
+            if constexpr (UPD) {
+#pragma unroll
+                for (uint32_t r = 0; r < kGroup; ++r)
+                    grads_next[r] = grad4[(qn + r) * kStates];
+            }
             uint4 o[kGroup];
 #pragma unroll
             for (uint32_t r = 0; r < kGroup; ++r) {
@@ -169,6 +217,12 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
                     o[r].z = denormalise_pair(o[r].z, c);
                     o[r].w = denormalise_pair(o[r].w, c);
                 }
+                if constexpr (UPD) {
+                    o[r].x = update_pair(o[r].x, grads[r].x, lr);
+                    o[r].y = update_pair(o[r].y, grads[r].y, lr);
+                    o[r].z = update_pair(o[r].z, grads[r].z, lr);
+                    o[r].w = update_pair(o[r].w, grads[r].w, lr);
+                }
             }
 #pragma unroll
             for (uint32_t r = 0; r < kGroup; ++r) {
@@ -183,6 +237,8 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
                     *dst = o[r];
                 }
                 fields[r] = fields_next[r];
+                if constexpr (UPD)
+                    grads[r] = grads_next[r];
             }
         }
     } else {
@@ -199,6 +255,8 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
                 uint32_t u = ((field >> KB) << 15) | (sym << 7) | ((field & ((1u << KB) - 1u)) << (7 - KB));
                 if constexpr (NORM)
                     u = denormalise_word(u, coefficient(coef[g >> block]));
+                if constexpr (UPD)
+                    u = update_word(u, grad[g], lr);
                 out[g] = static_cast<uint16_t>(u);
             }
         }
@@ -329,6 +387,8 @@ struct DecodeArgs {
     const uint8_t *sm;
     const uint8_t *coef;  // block coefficients (block-wise normalised blobs only)
     const uint16_t *low;  // lower halves (binary32 blobs only)
+    const uint16_t *grad; // gradient of the weight, bf16 words (update variant only)
+    float lr;             // learning rate (update variant only)
     void *out;            // bf16 words, or binary32 words for a binary32 blob
     uint32_t *status;
     uint64_t n;
@@ -339,7 +399,11 @@ struct DecodeArgs {
 };
 
 // Decodes the chunks of workgroup `wg` of one tensor.
-template <int KB, bool NORM, bool WIDE>
+// MODE: what is written -- the decoded bf16 words (kPlain), binary32 words joined with their
+// lower halves (kWide), or the decoded weights after the update of the backward loop (kUpdate).
+enum DecodeMode { kPlain = 0, kWide = 1, kUpdate = 2 };
+
+template <int KB, bool NORM, int MODE>
 __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ tb,
                                                  const uint32_t *__restrict__ offsets,
                                                  const uint32_t *__restrict__ states,
@@ -348,11 +412,12 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
                                                  const uint8_t *__restrict__ sm,
                                                  const uint8_t *__restrict__ coef, uint32_t block,
                                                  const uint16_t *__restrict__ low, void *__restrict__ out_any,
-                                                 bool stream_out,
+                                                 const uint16_t *__restrict__ grad, float lr, bool stream_out,
                                                  uint64_t n, uint32_t n_chunks, uint32_t *__restrict__ status,
                                                  uint32_t wg, uint32_t *__restrict__ lut, uint8_t *__restrict__ stage)
 {
-    static_assert(!WIDE || (KB == 7 && !NORM), "binary32 blobs are lossless only");
+    constexpr bool WIDE = MODE == kWide, UPD = MODE == kUpdate;
+    static_assert(MODE == kPlain || (KB == 7 && !NORM), "binary32 blobs and trained weights are lossless only");
     block = 31u - static_cast<uint32_t>(__clz(static_cast<int>(block | 1u)));  // a power of two: from here on its log2
     uint16_t *__restrict__ out = static_cast<uint16_t *>(out_any);
     const uint32_t tid = threadIdx.x;
@@ -449,38 +514,38 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
         }
     } else if (lone < 256) {
         if (stream_out)
-            walk_state<KB, true, NORM, true>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j);
+            walk_state<KB, true, NORM, true, UPD>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
         else
-            walk_state<KB, true, NORM, false>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j);
+            walk_state<KB, true, NORM, false, UPD>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
     } else if (staged) {
         wp = wp_begin = static_cast<uint32_t>(run_byte - aligned0);
         if (stream_out)
-            walk_state<KB, false, NORM, true>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
-                                              j);
+            walk_state<KB, false, NORM, true, UPD>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
+                                              j, grad, lr);
         else
-            walk_state<KB, false, NORM, false>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
-                                               j);
+            walk_state<KB, false, NORM, false, UPD>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
+                                               j, grad, lr);
     } else {
         // the runs of this workgroup's chunks did not fit the LDS window (more than ~4 bits per
         // symbol): read the words straight from the blob
         const GlobalWords direct{reinterpret_cast<const uint8_t *>(words) + run_byte};
         if (stream_out)
-            walk_state<KB, false, NORM, true>(lut, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j);
+            walk_state<KB, false, NORM, true, UPD>(lut, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
         else
-            walk_state<KB, false, NORM, false>(lut, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j);
+            walk_state<KB, false, NORM, false, UPD>(lut, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
     }
     // a well-formed run is consumed exactly and leaves the state where the encoder started
     if (x != kRansL || wp - wp_begin != 2 * len)
         atomicOr(status, 1u);
 }
 
-template <int KB, bool NORM, bool WIDE = false>
+template <int KB, bool NORM, int MODE = kPlain>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(const DecodeArgs a)
 {
     __shared__ __align__(16) uint32_t lut[kM];
     __shared__ __align__(16) uint8_t stage[kStageBytes];
-    decode_workgroup<KB, NORM, WIDE>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.low, a.out,
-                                     a.stream_out != 0, a.n, a.n_chunks, a.status, blockIdx.x, lut, stage);
+    decode_workgroup<KB, NORM, MODE>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.low, a.out,
+                                     a.grad, a.lr, a.stream_out != 0, a.n, a.n_chunks, a.status, blockIdx.x, lut, stage);
 }
 
 // Several tensors in one launch (a layer's weights): workgroups [t[i-1].wg_end, t[i].wg_end)
@@ -490,7 +555,7 @@ struct BatchArgs {
     uint32_t count;
 };
 
-template <int KB, bool NORM, bool WIDE = false>
+template <int KB, bool NORM, int MODE = kPlain>
 __global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchArgs b)
 {
     __shared__ __align__(16) uint32_t lut[kM];
@@ -501,8 +566,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchAr
         ++i;
     }
     const DecodeArgs &a = b.t[i];
-    decode_workgroup<KB, NORM, WIDE>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.low, a.out,
-                                     a.stream_out != 0, a.n, a.n_chunks, a.status, blockIdx.x - first, lut, stage);
+    decode_workgroup<KB, NORM, MODE>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.low, a.out,
+                                     a.grad, a.lr, a.stream_out != 0, a.n, a.n_chunks, a.status, blockIdx.x - first, lut,
+                                     stage);
 }
 
 }  // namespace nz
