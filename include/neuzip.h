@@ -166,8 +166,9 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
  *   d_grads     host array of count device pointers: the gradient of each weight, bf16 words,
  *               neuzip_elems(blobs[i]) of them, 16-byte aligned (read only).
  *   d_weights   host array of count device pointers, 16-byte aligned: temporary space of
- *               neuzip_elems(blobs[i]) bf16 words each, not overlapping; on return it holds the new
- *               weights uncompressed (the caller may use or discard them).
+ *               neuzip_elems(blobs[i]) bf16 words each, not overlapping one another; on return it
+ *               holds the new weights uncompressed (the caller may use or discard them).
+ *               d_weights[i] may be d_grads[i] itself: the gradient is then overwritten in place.
  *   lr          learning rate.
  *   rebuilt     as for neuzip_recompress; may be NULL.
  * Reading taken for the arithmetic, which the paper leaves open: per element, in IEEE binary32,
