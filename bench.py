@@ -116,7 +116,7 @@ def main():
     achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic_note(),
-                "kernel": "decode_kernel<7, false>", "avg_launch_us": round(kernel_ms * 1e3, 2),
+                "kernel": "decode_kernel<7, false, 0>", "avg_launch_us": round(kernel_ms * 1e3, 2),
                 "algorithmic_bytes_per_elem": round(algo_bytes / n, 4)}
 
     # context: a plain device copy of the same output size

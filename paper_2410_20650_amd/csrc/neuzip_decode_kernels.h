@@ -143,10 +143,12 @@ __device__ __forceinline__ uint32_t update_pair(uint32_t w, uint32_t g, float lr
     const f32x2_t v = {sgd_step(__uint_as_float(w << 16), __uint_as_float(g << 16), lr),
                        sgd_step(__uint_as_float(w & 0xFFFF0000u), __uint_as_float(g & 0xFFFF0000u), lr)};
     uint32_t r = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-    if (v[0] != v[0])
-        r = (r & 0xFFFF0000u) | 0x7FC0u;
-    if (v[1] != v[1])
-        r = (r & 0x0000FFFFu) | 0x7FC00000u;
+    if (__builtin_expect(__builtin_isunordered(v[0], v[1]), 0)) {  // one compare finds a NaN in either half
+        if (v[0] != v[0])
+            r = (r & 0xFFFF0000u) | 0x7FC0u;
+        if (v[1] != v[1])
+            r = (r & 0x0000FFFFu) | 0x7FC00000u;
+    }
     return r;
 }
 
