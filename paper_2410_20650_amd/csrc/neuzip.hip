@@ -312,10 +312,12 @@ int reserve_words(neuzip_blob *b, uint64_t total_words)
     return NEUZIP_OK;
 }
 
-// Chunks per decoder workgroup.  32 (8 waves) measured best at every size: two such workgroups
-// fill a CU's LDS with 16 waves, and smaller workgroups lower that occupancy.
+// Chunks per decoder workgroup.  32 (8 waves) measured best from ~16 M elements up: two such
+// workgroups fill a CU's LDS with 16 waves, and smaller workgroups lower that occupancy.  A small
+// tensor cannot fill the chip either way and is a chain of 256 dependent steps per lane; there
+// workgroups of 16 chunks spread the waves over twice as many CUs (4-7 % faster up to 16 M elements).
 // NEUZIP_DECODE_CHUNKS_PER_WG (4..32, multiple of 4) overrides the choice for tuning runs.
-uint32_t decode_chunks_per_wg()
+uint32_t decode_chunks_per_wg(uint32_t n_chunks)
 {
     static int forced = -1;
     if (forced < 0) {
@@ -323,7 +325,9 @@ uint32_t decode_chunks_per_wg()
         const int v = env ? std::atoi(env) : 0;
         forced = (v >= 4 && v <= static_cast<int>(kDecChunksPerWg) && v % 4 == 0) ? v : 0;
     }
-    return forced > 0 ? static_cast<uint32_t>(forced) : kDecChunksPerWg;
+    if (forced > 0)
+        return static_cast<uint32_t>(forced);
+    return n_chunks <= 4096 ? 16u : kDecChunksPerWg;
 }
 
 DecodeArgs decode_args(const neuzip_blob *b, void *d_dst)
@@ -355,7 +359,7 @@ DecodeArgs decode_args(const neuzip_blob *b, void *d_dst)
 template <int KB, bool NORM, int MODE = kPlain>
 int launch_decode(const neuzip_blob *b, void *d_dst, hipStream_t stream)
 {
-    const uint32_t per = decode_chunks_per_wg();
+    const uint32_t per = decode_chunks_per_wg(b->n_chunks);
     const uint32_t groups = (b->n_chunks + per - 1) / per;
     hipLaunchKernelGGL((decode_kernel<KB, NORM, MODE>), dim3(groups), dim3(per * kStates), 0, stream,
                        decode_args(b, d_dst));
