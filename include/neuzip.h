@@ -23,6 +23,10 @@
  *   - Errors are reported through the return code only (no exceptions, no
  *     aborts, nothing is printed).  On error no output argument is modified
  *     unless stated otherwise.
+ *   - If a call that compresses into an existing blob fails after its kernels
+ *     have started (out of memory while growing the stream, a HIP error), that
+ *     blob holds no tensor any more: decompress, linear, update, recompress and
+ *     export return NEUZIP_EINVAL for it until a compress call has succeeded.
  *   - A blob belongs to the device that was current when it was created; every
  *     call that launches work on it must be made with that device current
  *     (NEUZIP_EINVAL otherwise).  neuzip_free may be called from any device.

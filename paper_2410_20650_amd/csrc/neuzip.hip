@@ -214,25 +214,38 @@ bool wait_for_record(uint32_t seq, hipStream_t stream)
     return __atomic_load_n(stamp, __ATOMIC_ACQUIRE) == seq;
 }
 
+// First use on a device: the arrays whose size does not depend on the tensors.
+int create_workspace(int device, hipStream_t stream)
+{
+    g_ws.device = device;
+    NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.enc), kBatchMax * 256 * sizeof(EncSym)));
+    NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.counts), (kBatchMax * 256 + 64) * sizeof(uint32_t)));
+    g_ws.done = g_ws.counts + kBatchMax * 256;  // shares the allocation; cleared with the bins below
+    g_ws.stale = g_ws.done + 8;
+    NZ_HIP(hipHostMalloc(reinterpret_cast<void **>(&g_ws.pinned), sizeof(HostRecord), hipHostMallocDefault));
+    std::memset(g_ws.pinned, 0, sizeof(HostRecord));
+    g_ws.seq = 0;
+    NZ_HIP(hipEventCreateWithFlags(&g_ws.idle, hipEventDisableTiming));
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax + 1), dim3(256), 0, stream, g_ws.counts, 0u,
+                       kBatchMax * 256 + 64);
+    NZ_HIP(hipGetLastError());
+    NZ_HIP(hipEventRecord(g_ws.idle, stream));
+    return NEUZIP_OK;
+}
+
 int ensure_workspace(int device, uint64_t n_groups, hipStream_t stream)
 {
     if (g_ws.device != device) {
-        const int rc = release_workspace_locked();
+        int rc = release_workspace_locked();
         if (rc != NEUZIP_OK)
             return rc;
-        g_ws.device = device;
-        NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.enc), kBatchMax * 256 * sizeof(EncSym)));
-        NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.counts), (kBatchMax * 256 + 64) * sizeof(uint32_t)));
-        g_ws.done = g_ws.counts + kBatchMax * 256;  // shares the allocation; cleared with the bins below
-        g_ws.stale = g_ws.done + 8;
-        NZ_HIP(hipHostMalloc(reinterpret_cast<void **>(&g_ws.pinned), sizeof(HostRecord), hipHostMallocDefault));
-        std::memset(g_ws.pinned, 0, sizeof(HostRecord));
-        g_ws.seq = 0;
-        NZ_HIP(hipEventCreateWithFlags(&g_ws.idle, hipEventDisableTiming));
-        hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax + 1), dim3(256), 0, stream, g_ws.counts, 0u,
-                           kBatchMax * 256 + 64);
-        NZ_HIP(hipGetLastError());
-        NZ_HIP(hipEventRecord(g_ws.idle, stream));
+        rc = create_workspace(device, stream);
+        if (rc != NEUZIP_OK) {
+            // a half-built workspace must not be taken for a complete one by the next call
+            (void)hipGetLastError();
+            (void)release_workspace_locked();
+            return rc;
+        }
     }
     // the previous user of the workspace may still be running on another stream
     NZ_HIP(hipStreamWaitEvent(stream, g_ws.idle, 0));
@@ -484,13 +497,17 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         fresh[i] = false;
     }
     bool bins_dirty = false;  // the histogram kernel ran but the table kernel did not clear the bins
+    bool touched = false;     // kernels that write into the blobs have been launched
     auto fail = [&](int rc) {
         if (bins_dirty && g_ws.counts)
             hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax), dim3(256), 0, stream, g_ws.counts, 0u,
                                kBatchMax * 256);
-        for (uint32_t i = 0; i < count; ++i)
+        for (uint32_t i = 0; i < count; ++i) {
             if (fresh[i])
                 neuzip_free(work[i]);
+            else if (touched)
+                work[i]->has_table = false;  // partly overwritten: holds no tensor until compressed again
+        }
         return rc;
     };
     for (uint32_t i = 0; i < count; ++i) {
@@ -561,6 +578,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         if (rc != NEUZIP_OK)
             return fail(rc);
         batch.seq = ++g_ws.seq;
+        touched = true;
 
         if (reuse) {
             // one pass: encoder constants from the stored tables, then split + encode together
@@ -911,8 +929,8 @@ extern "C" {
 
 int neuzip_decompress(const neuzip_blob *blob, void *d_dst, uint64_t n_elems, int dtype, void *hip_stream)
 {
-    if (!is_blob(blob) || dtype != (blob->f32 ? NEUZIP_F32 : NEUZIP_BF16) || blob->n != n_elems ||
-        !on_current_device(blob))
+    if (!is_blob(blob) || !blob->has_table || dtype != (blob->f32 ? NEUZIP_F32 : NEUZIP_BF16) ||
+        blob->n != n_elems || !on_current_device(blob))
         return NEUZIP_EINVAL;
     if (n_elems > 0 && (!d_dst || (reinterpret_cast<uintptr_t>(d_dst) & 15u)))
         return NEUZIP_EINVAL;
@@ -927,7 +945,8 @@ int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, 
     if (reinterpret_cast<uintptr_t>(d_scratch) & 15u)
         return NEUZIP_EINVAL;
     for (uint32_t i = 0; i < count; ++i) {
-        if (!is_blob(blobs[i]) || (blobs[i]->f32 ? 2 * blobs[i]->n : blobs[i]->n) > scratch_elems ||
+        if (!is_blob(blobs[i]) || !blobs[i]->has_table ||
+            (blobs[i]->f32 ? 2 * blobs[i]->n : blobs[i]->n) > scratch_elems ||
             (blobs[i]->n > 0 && !d_scratch) || !on_current_device(blobs[i]))
             return NEUZIP_EINVAL;
     }
@@ -944,7 +963,7 @@ int neuzip_decompress_batch(const neuzip_blob *const *blobs, void *const *d_dsts
     if (count > 0 && (!blobs || !d_dsts))
         return NEUZIP_EINVAL;
     for (uint32_t i = 0; i < count; ++i) {
-        if (!is_blob(blobs[i]) || !on_current_device(blobs[i]))
+        if (!is_blob(blobs[i]) || !blobs[i]->has_table || !on_current_device(blobs[i]))
             return NEUZIP_EINVAL;
         if (blobs[i]->n > 0 && (!d_dsts[i] || (reinterpret_cast<uintptr_t>(d_dsts[i]) & 15u)))
             return NEUZIP_EINVAL;
@@ -1025,7 +1044,7 @@ int neuzip_dtype(const neuzip_blob *blob) { return !is_blob(blob) ? -1 : (blob->
 
 int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *written, void *hip_stream)
 {
-    if (!is_blob(blob) || (h_buf && !on_current_device(blob)))
+    if (!is_blob(blob) || !blob->has_table || (h_buf && !on_current_device(blob)))
         return NEUZIP_EINVAL;
     const Container lay = container_layout(blob->n, blob->k, blob->total_words, blob->block, blob->f32);
     if (written)
