@@ -115,6 +115,32 @@ def test_config3_forward_schedule_llama3_8b_shapes(nz):
     assert int(scratch[:last].view(torch.int16).to(torch.int64).sum().item()) == sums[-1]
 
 
+def test_device_memory_held_matches_the_accounting(nz):
+    # Sec. 2.2 / Alg. 1: the model is held compressed and only one layer's weights exist uncompressed
+    # at a time.  What the driver reports as taken from the device while two layers of the config-3
+    # shapes are compressed must be what the library accounts for, and about 2/3 of the raw size.
+    nz.neuzip_release_workspace()
+    torch.cuda.synchronize()
+    names = inputs.llama3_8b_tensors()[1:15]
+    ws = [inputs.gaussian_bf16(shape, inputs.seed_for(3, 1 + i), device=DEV) for i, (_, shape) in enumerate(names)]
+    raw = sum(2 * w.numel() for w in ws)
+    torch.cuda.synchronize()
+    free_before, _ = torch.cuda.mem_get_info()
+    blobs = [nz.neuzip_compress(w, 7) for w in ws]
+    nz.neuzip_release_workspace()                                # the compress workspace is not part of the model
+    torch.cuda.synchronize()
+    free_after, _ = torch.cuda.mem_get_info()
+    held = free_before - free_after
+    accounted = sum(b.device_bytes for b in blobs)
+    containers = sum(b.compressed_bytes for b in blobs)
+    # the driver hands out memory in pages: allow 2 MiB per allocation (two per blob)
+    assert accounted <= held + (1 << 20) and held <= accounted + len(blobs) * 2 * (2 << 20), (held, accounted)
+    assert containers <= accounted <= 1.01 * containers
+    assert 0.66 < containers / raw < 0.675                       # 10.68 of 16 bits
+    for b in blobs:
+        b.free()
+
+
 def test_config5_training_step_loop(nz):
     # 10 steps of decompress -> synthetic update -> recompress (histogram rebuilt) -> verify,
     # on a two-layer slice of the config-3 shapes plus the embedding; oracle cross-check on a sample
