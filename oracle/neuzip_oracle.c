@@ -466,13 +466,13 @@ static void *enc_worker(void *arg)
 }
 
 static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, const uint8_t *coef,
-                         const uint16_t *given_freq, uint32_t guard, const uint16_t *low, uint8_t *blob, uint64_t cap,
+                         const uint16_t *given_freq, uint32_t guard, const uint16_t *low, uint32_t elem, uint8_t *blob, uint64_t cap,
                          uint64_t *written, int threads);
 
 int nzo_compress(const uint16_t *w, uint64_t n, int k, uint8_t *blob, uint64_t cap,
                  uint64_t *written, int threads)
 {
-    return compress_impl(w, n, k, 0, NULL, NULL, 0, NULL, blob, cap, written, threads);
+    return compress_impl(w, n, k, 0, NULL, NULL, 0, NULL, NZO_ELEM_BF16, blob, cap, written, threads);
 }
 
 /* The table keeps a guard band (nzo_quantise_guarded); header word 52 records the guard. */
@@ -481,7 +481,7 @@ int nzo_compress_guarded(const uint16_t *w, uint64_t n, int k, uint32_t guard, u
 {
     if (guard > 255)
         return NZO_EINVAL;
-    return compress_impl(w, n, k, 0, NULL, NULL, guard, NULL, blob, cap, written, threads);
+    return compress_impl(w, n, k, 0, NULL, NULL, guard, NULL, NZO_ELEM_BF16, blob, cap, written, threads);
 }
 
 /* Compression with a table that was made earlier (from the weights before an update): no
@@ -512,7 +512,7 @@ int nzo_compress_with_table(const uint16_t *w, uint64_t n, int k, const uint16_t
     int rc = kept_table_serves(w, n, freq, guard);
     if (rc != NZO_OK)
         return rc;
-    return compress_impl(w, n, k, 0, NULL, freq, guard, NULL, blob, cap, written, threads);
+    return compress_impl(w, n, k, 0, NULL, freq, guard, NULL, NZO_ELEM_BF16, blob, cap, written, threads);
 }
 
 /* Lossy variant with block-wise normalisation: the coefficients are taken from the original
@@ -532,14 +532,14 @@ int nzo_compress_blockwise(const uint16_t *w, uint64_t n, int k, uint32_t block,
     }
     nzo_block_coefficients(w, n, block, coef);
     nzo_normalise(w, n, block, coef, normal);
-    int rc = compress_impl(normal, n, k, block, coef, NULL, 0, NULL, blob, cap, written, threads);
+    int rc = compress_impl(normal, n, k, block, coef, NULL, 0, NULL, NZO_ELEM_BF16, blob, cap, written, threads);
     free(coef);
     free(normal);
     return rc;
 }
 
 static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, const uint8_t *coef,
-                         const uint16_t *given_freq, uint32_t guard, const uint16_t *low, uint8_t *blob, uint64_t cap,
+                         const uint16_t *given_freq, uint32_t guard, const uint16_t *low, uint32_t elem, uint8_t *blob, uint64_t cap,
                          uint64_t *written, int threads)
 {
     if (!valid_k(k) || n >= ((uint64_t)1 << 32))
@@ -651,7 +651,7 @@ static int compress_impl(const uint16_t *w, uint64_t n, int k, uint32_t block, c
         }
     }
     put32(blob + off_offsets + 4 * nc, (uint32_t)run);
-    put32(blob + 56, low ? 1u : 0u); /* element type: 0 bf16, 1 binary32 (with a plane of low halves) */
+    put32(blob + 56, elem); /* element type: 0 bf16, 1 binary32 (with a plane of low halves), 2 binary16 */
     nzo_pack_signmant(w, n, k, blob + off_sm);
     if (low)
         for (uint64_t i = 0; i < n; i++)
@@ -669,7 +669,7 @@ typedef struct {
     uint64_t n, nc, total_words;
     int k;
     uint32_t block;
-    uint32_t f32; /* element type is binary32: a plane of low halves follows the sign|mantissa stream */
+    uint32_t elem; /* element type; binary32: a plane of low halves follows the sign|mantissa stream */
     const uint8_t *low;
     const uint8_t *freq, *offsets, *states, *lens, *words, *sm, *coef;
 } blob_view;
@@ -698,11 +698,11 @@ static int open_blob(const uint8_t *blob, uint64_t len, blob_view *v)
     uint64_t off_lens = off_states + v->nc * NZO_K * 4;
     uint64_t off_words = off_lens + v->nc * NZO_K;
     uint64_t off_sm = off_words + pad16(v->total_words * 2);
-    v->f32 = get32(blob + 56);
-    if (v->f32 > 1 || (v->f32 && (v->k != 7 || v->block != 0)))
+    v->elem = get32(blob + 56);
+    if (v->elem > NZO_ELEM_F16 || (v->elem != NZO_ELEM_BF16 && (v->k != 7 || v->block != 0)))
         return NZO_ECORRUPT;
     uint64_t off_low = off_sm + pad16(nzo_signmant_bytes(v->n, v->k));
-    uint64_t off_coef = off_low + (v->f32 ? pad16(v->n * 2) : 0);
+    uint64_t off_coef = off_low + (v->elem == NZO_ELEM_F32 ? pad16(v->n * 2) : 0);
     uint64_t size = off_coef + pad16(nzo_block_count(v->n, v->block));
     if (size != len)
         return NZO_ECORRUPT;
@@ -800,13 +800,13 @@ static void *dec_worker(void *arg)
     return NULL;
 }
 
-static int decompress_halves(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n, int threads, uint32_t want_f32)
+static int decompress_halves(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n, int threads, uint32_t want_elem)
 {
     blob_view v;
     int rc = open_blob(blob, len, &v);
     if (rc != NZO_OK)
         return rc;
-    if (v.n != n || v.f32 != want_f32)
+    if (v.n != n || v.elem != want_elem)
         return NZO_EINVAL;
     if (get32(v.offsets) != 0 || get32(v.offsets + 4 * v.nc) != v.total_words)
         return NZO_ECORRUPT;
@@ -847,7 +847,7 @@ static int decompress_halves(const uint8_t *blob, uint64_t len, uint16_t *out, u
 
 int nzo_decompress(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n, int threads)
 {
-    return decompress_halves(blob, len, out, n, threads, 0);
+    return decompress_halves(blob, len, out, n, threads, NZO_ELEM_BF16);
 }
 
 /* ------------------------------------------------------------------ */
@@ -881,7 +881,7 @@ int nzo_compress_f32_with_table(const uint32_t *w, uint64_t n, const uint16_t *f
     }
     int rc = guard > 255 ? NZO_EINVAL : (freq ? kept_table_serves(high, n, freq, guard) : NZO_OK);
     if (rc == NZO_OK)
-        rc = compress_impl(high, n, 7, 0, NULL, freq, guard, low, blob, cap, written, threads);
+        rc = compress_impl(high, n, 7, 0, NULL, freq, guard, low, NZO_ELEM_F32, blob, cap, written, threads);
     free(high);
     free(low);
     return rc;
@@ -892,7 +892,7 @@ int nzo_decompress_f32(const uint8_t *blob, uint64_t len, uint32_t *out, uint64_
     uint16_t *high = (uint16_t *)malloc((size_t)(n + 1) * sizeof(uint16_t));
     if (!high)
         return NZO_ENOSPACE;
-    int rc = decompress_halves(blob, len, high, n, threads, 1);
+    int rc = decompress_halves(blob, len, high, n, threads, NZO_ELEM_F32);
     if (rc == NZO_OK) {
         blob_view v;
         open_blob(blob, len, &v);
@@ -900,5 +900,43 @@ int nzo_decompress_f32(const uint8_t *blob, uint64_t len, uint32_t *out, uint64_
             out[i] = ((uint32_t)high[i] << 16) | get16(v.low + 2 * i);
     }
     free(high);
+    return rc;
+}
+
+/* ------------------------------------------------------------------ */
+/* binary16 tensors (beyond the paper, which works on BFloat16).        */
+/* sign 1 | exponent 5 | mantissa 10.  The upper byte of a word (sign,  */
+/* exponent, two mantissa bits) takes the place of the bf16 exponent    */
+/* byte as the entropy-coded symbol and the lower byte (eight mantissa  */
+/* bits) the place of the sign|mantissa byte.  That is the lossless     */
+/* bf16 path applied to the word with its bits rearranged:              */
+/*   bits 15..8 -> 14..7,  bit 7 -> 15,  bits 6..0 stay,                */
+/* so the container is the bf16 container of the rearranged words with  */
+/* element type 2 in its header.                                        */
+/* ------------------------------------------------------------------ */
+static uint16_t f16_to_fields(uint16_t u) { return (uint16_t)(((u & 0x80u) << 8) | ((u >> 8) << 7) | (u & 0x7Fu)); }
+static uint16_t f16_from_fields(uint16_t v) { return (uint16_t)((((v >> 7) & 0xFFu) << 8) | ((v >> 8) & 0x80u) | (v & 0x7Fu)); }
+
+int nzo_compress_f16(const uint16_t *w, uint64_t n, const uint16_t *freq, uint32_t guard, uint8_t *blob, uint64_t cap,
+                     uint64_t *written, int threads)
+{
+    uint16_t *fields = (uint16_t *)malloc((size_t)(n + 1) * sizeof(uint16_t));
+    if (!fields)
+        return NZO_ENOSPACE;
+    for (uint64_t i = 0; i < n; i++)
+        fields[i] = f16_to_fields(w[i]);
+    int rc = guard > 255 ? NZO_EINVAL : (freq ? kept_table_serves(fields, n, freq, guard) : NZO_OK);
+    if (rc == NZO_OK)
+        rc = compress_impl(fields, n, 7, 0, NULL, freq, guard, NULL, NZO_ELEM_F16, blob, cap, written, threads);
+    free(fields);
+    return rc;
+}
+
+int nzo_decompress_f16(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n, int threads)
+{
+    int rc = decompress_halves(blob, len, out, n, threads, NZO_ELEM_F16);
+    if (rc == NZO_OK)
+        for (uint64_t i = 0; i < n; i++)
+            out[i] = f16_from_fields(out[i]);
     return rc;
 }

@@ -136,10 +136,21 @@ int nzo_decompress(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n,
 /* binary32 tensors (not in the paper, which uses BFloat16 only): the upper halves go through the
  * lossless path as bf16 words, the lower halves are stored raw in a plane after the
  * sign|mantissa stream; header word 56 is 1. */
+/* element types recorded in header word 56 */
+#define NZO_ELEM_BF16 0u
+#define NZO_ELEM_F32 1u
+#define NZO_ELEM_F16 2u
+
 int nzo_compress_f32(const uint32_t *w, uint64_t n, uint8_t *blob, uint64_t cap, uint64_t *written, int threads);
 int nzo_compress_f32_with_table(const uint32_t *w, uint64_t n, const uint16_t *freq, uint32_t guard, uint8_t *blob,
                                 uint64_t cap, uint64_t *written, int threads);
 int nzo_decompress_f32(const uint8_t *blob, uint64_t len, uint32_t *out, uint64_t n, int threads);
+
+/* binary16 words: upper byte entropy-coded in place of the exponent, lower byte raw; freq / guard as
+ * for nzo_compress_with_table (freq may be NULL for fresh statistics). */
+int nzo_compress_f16(const uint16_t *w, uint64_t n, const uint16_t *freq, uint32_t guard, uint8_t *blob, uint64_t cap,
+                     uint64_t *written, int threads);
+int nzo_decompress_f16(const uint8_t *blob, uint64_t len, uint16_t *out, uint64_t n, int threads);
 /* Reads n, k and the stored frequencies out of a container. */
 int nzo_blob_info(const uint8_t *blob, uint64_t len, uint64_t *n, int *k, uint64_t *total_words,
                   uint16_t freq[256]);

@@ -94,6 +94,10 @@ def lib():
         L.nzo_compress_f32.restype = i32
         L.nzo_compress_f32_with_table.argtypes = [u32p, u64, u16p, u32, u8p, u64, u64p, i32]
         L.nzo_compress_f32_with_table.restype = i32
+        L.nzo_compress_f16.argtypes = [u16p, u64, u16p, u32, u8p, u64, u64p, i32]
+        L.nzo_compress_f16.restype = i32
+        L.nzo_decompress_f16.argtypes = [u8p, u64, u16p, u64, i32]
+        L.nzo_decompress_f16.restype = i32
         L.nzo_decompress_f32.argtypes = [u8p, u64, u32p, u64, i32]
         L.nzo_decompress_f32.restype = i32
         L.nzo_blob_info.argtypes = [u8p, u64, u64p, ctypes.POINTER(i32), u64p, u16p]
@@ -332,6 +336,37 @@ def decompress_f32(blob, n, threads=1):
     return out
 
 
+def compress_f16(w, threads=1, guard=0, freq=None):
+    """binary16 words (uint16 array) -> container bytes: the upper byte of a word is the coded symbol,
+    the lower byte is stored raw.  guard / freq as in compress()."""
+    w = np.ascontiguousarray(w)
+    if w.dtype != np.uint16:
+        raise TypeError("binary16 words must be passed as uint16")
+    w = w.reshape(-1)
+    cap = int(lib().nzo_compress_bound(w.size, 7))
+    blob = np.empty(cap, np.uint8)
+    written = ctypes.c_uint64(0)
+    table = None
+    if freq is not None:
+        table = np.ascontiguousarray(freq, dtype=np.uint16)
+        if table.size != 256:
+            raise ValueError("a frequency table has 256 entries")
+    rc = lib().nzo_compress_f16(_p(w, ctypes.c_uint16), w.size, None if table is None else _p(table, ctypes.c_uint16),
+                                guard, _p(blob, ctypes.c_uint8), cap, ctypes.byref(written), threads)
+    if rc != OK:
+        raise OracleError(rc, "compress_f16")
+    return blob[: written.value].copy()
+
+
+def decompress_f16(blob, n, threads=1):
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    out = np.empty(n, np.uint16)
+    rc = lib().nzo_decompress_f16(_p(blob, ctypes.c_uint8), blob.size, _p(out, ctypes.c_uint16), n, threads)
+    if rc != OK:
+        raise OracleError(rc, "decompress_f16")
+    return out
+
+
 def blob_info(blob):
     blob = np.ascontiguousarray(blob, dtype=np.uint8)
     n, k, tw = ctypes.c_uint64(0), ctypes.c_int(0), ctypes.c_uint64(0)
@@ -348,7 +383,7 @@ def sections(blob):
     info = blob_info(blob)
     n, k, tw = info["n"], info["k"], info["total_words"]
     block = int(np.ascontiguousarray(blob[48:52]).view("<u4")[0])
-    f32 = int(np.ascontiguousarray(blob[56:60]).view("<u4")[0])
+    f32 = int(np.ascontiguousarray(blob[56:60]).view("<u4")[0]) == 1
     nc = (n + CHUNK - 1) // CHUNK
     pad = lambda v: (v + 15) & ~15
     out, pos = {}, 0

@@ -152,15 +152,18 @@ def scale(words16, block, coef, divide):
     return out
 
 
-def compress(words16, k=7, block=0, guard=0, freq=None, low=None):
+def compress(words16, k=7, block=0, guard=0, freq=None, low=None, half=False):
     """List of bf16 words -> container bytes.  freq: an earlier table to code with.  low: the lower
-    halves of binary32 words whose upper halves are words16 (stored as a raw plane)."""
+    halves of binary32 words whose upper halves are words16 (stored as a raw plane).  half: the
+    words are binary16 -- the symbol is a word's upper byte, its lower byte is stored raw."""
+    if half and (k != 7 or block or low is not None):
+        raise ValueError("binary16 is lossless only")
     coef = []
     if block:
         coef = block_coefficients(words16, block)
         words16 = scale(words16, block, coef, divide=True)
     n = len(words16)
-    expo = [exponent(u) for u in words16]
+    expo = [u >> 8 for u in words16] if half else [exponent(u) for u in words16]
     cnt = [0] * 256
     for e in expo:
         cnt[e] += 1
@@ -180,7 +183,7 @@ def compress(words16, k=7, block=0, guard=0, freq=None, low=None):
             payload.extend(run)
     offsets.append(len(payload))
     header = struct.pack("<IIQIIIIIIQIII", 0x315A554E, 1, n, k, PROB_BITS, CHUNK, K, G, nc, len(payload), block,
-                         guard, 0 if low is None else 1)
+                         guard, 2 if half else (0 if low is None else 1))
     header += bytes(64 - len(header))
     out = header
     out += struct.pack("<256H", *freq)
@@ -188,7 +191,7 @@ def compress(words16, k=7, block=0, guard=0, freq=None, low=None):
     out += struct.pack(f"<{nc * K}I", *states)
     out += bytes(lens)
     out += _pad(struct.pack(f"<{len(payload)}H", *payload))
-    out += _pad(pack_signmant(words16, k))
+    out += _pad(bytes(u & 0xFF for u in words16) if half else pack_signmant(words16, k))
     if low is not None:
         out += _pad(struct.pack(f"<{n}H", *low))
     if block:
@@ -198,7 +201,8 @@ def compress(words16, k=7, block=0, guard=0, freq=None, low=None):
 
 def decompress(blob):
     """Container bytes -> list of bf16 words."""
-    magic, ver, n, k, pb, chunk, ks, g, nc, tw, block, _guard, f32 = struct.unpack_from("<IIQIIIIIIQIII", blob, 0)
+    magic, ver, n, k, pb, chunk, ks, g, nc, tw, block, _guard, elem = struct.unpack_from("<IIQIIIIIIQIII", blob, 0)
+    f32, half = elem == 1, elem == 2
     assert (magic, ver, pb, chunk, ks, g) == (0x315A554E, 1, PROB_BITS, CHUNK, K, G)
     pos = 64
     freq = list(struct.unpack_from("<256H", blob, pos)); pos += 512
@@ -222,7 +226,10 @@ def decompress(blob):
             for i, e in zip(idx, decode_state(len(idx), freq, states[c * K + j], run)):
                 gi = c * CHUNK + i
                 field = (sm[gi // per] >> ((gi % per) * width)) & ((1 << width) - 1)
-                out[gi] = ((field >> k) << 15) | (e << 7) | ((field & ((1 << k) - 1)) << (7 - k))
+                if half:
+                    out[gi] = (e << 8) | field           # symbol = upper byte, raw lower byte
+                else:
+                    out[gi] = ((field >> k) << 15) | (e << 7) | ((field & ((1 << k) - 1)) << (7 - k))
         assert at == offsets[c + 1]
     if block:
         out = scale(out, block, coef, divide=False)

@@ -825,3 +825,61 @@ def test_training_step_container_follows_the_kept_table_rules():
     assert rebuilt == 1
     assert np.array_equal(O.decompress(big, n), U.sgd_update(w0, g, 1e6))
     assert np.array_equal(big, O.compress(new, 7, guard=8))
+
+
+# ---------------------------------------------------------------- binary16 tensors (beyond the paper)
+
+def test_f16_round_trip_layout_and_size():
+    rng = np.random.default_rng(91)
+    for n in (0, 1, 9, 4097, 30_000):
+        w = (rng.standard_normal(n) * 0.02).astype(np.float16).view(np.uint16)
+        blob = O.compress_f16(w, threads=3)
+        assert np.array_equal(O.decompress_f16(blob, n, threads=2), w)
+        sec = O.sections(blob)
+        # the raw plane is the words' lower bytes, the table is over their upper bytes
+        lo, _ = sec["signmant"]
+        assert np.array_equal(blob[lo: lo + n], (w & 0xFF).astype(np.uint8))
+        if n:
+            counts = np.bincount(w >> 8, minlength=256).astype(np.uint64)
+            assert np.array_equal(O.blob_info(blob)["freq"], O.quantise(counts))
+        # second statement of the format (upper byte / lower byte, written out directly)
+        assert blob.tobytes() == P.compress([int(u) for u in w], 7, half=True)
+        assert P.decompress(blob.tobytes()) == [int(u) for u in w]
+        # element types do not decode each other's containers
+        with pytest.raises(O.OracleError):
+            O.decompress(blob, n)
+        with pytest.raises(O.OracleError):
+            O.decompress_f16(O.compress(w, 7), n)
+    # every 16-bit pattern: zeros, subnormals, infinities, NaN payloads
+    every = np.arange(65536, dtype=np.uint16)
+    assert np.array_equal(O.decompress_f16(O.compress_f16(every), 65536), every)
+    # Gaussian weights: the upper byte (sign, 5 exponent bits, 2 mantissa bits) shrinks to its entropy
+    w = (np.random.default_rng(4).standard_normal(1 << 20) * 0.02).astype(np.float16).view(np.uint16)
+    blob = O.compress_f16(w, threads=8)
+    counts = np.bincount(w >> 8, minlength=256).astype(np.uint64)
+    H = O.entropy(counts)
+    assert 5.3 < H < 5.8                                     # 1 sign + ~2.55 exponent + ~2 mantissa bits
+    assert H + 8 < 8 * blob.size / w.size < 1.02 * (H + 8)
+
+
+def test_f16_guard_band_and_kept_table():
+    rng = np.random.default_rng(92)
+    n = 20_000
+    w0 = (rng.standard_normal(n) * 0.02).astype(np.float16)
+    w1 = (w0.astype(np.float32) - 1e-4 * rng.standard_normal(n).astype(np.float32)).astype(np.float16).view(np.uint16)
+    w0 = w0.view(np.uint16)
+    first = O.compress_f16(w0, guard=4)
+    table = O.blob_info(first)["freq"]
+    assert np.array_equal(table, O.quantise(np.bincount(w0 >> 8, minlength=256).astype(np.uint64), guard=4))
+    kept = O.compress_f16(w1, threads=2, guard=4, freq=table)
+    assert np.array_equal(O.decompress_f16(kept, n), w1)
+    assert np.array_equal(O.blob_info(kept)["freq"], table)
+    assert kept.tobytes() == P.compress([int(u) for u in w1], 7, guard=4, freq=[int(f) for f in table], half=True)
+    w2 = w1.copy()
+    # the band runs from the smallest occupied upper byte (small positive values) to the largest
+    # (the most negative values) plus the guard; the largest-magnitude negative number lies beyond it
+    w2[7] = np.uint16(0xFBFF)
+    assert table[0xFB] == 0 and table[0x7B] == 1
+    with pytest.raises(O.OracleError) as err:
+        O.compress_f16(w2, guard=4, freq=table)
+    assert err.value.code == O.ESTALE
