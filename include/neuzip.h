@@ -47,15 +47,18 @@ extern "C" {
  * behind it until neuzip_free. */
 typedef struct neuzip_blob neuzip_blob;
 
-/* Element types.  The paper works on BFloat16 only (Sec. 2.1, footnote).
- * NEUZIP_F32 goes beyond it: the upper half of an IEEE binary32 word is a bf16 word (sign, the
- * same 8 exponent bits, 7 mantissa bits) and is compressed exactly as one; the lower half, 16
- * mantissa bits without structure, is kept as a raw plane after the sign|mantissa stream
- * (header word 56 of the container = 1).  Lossless only: mantissa_bits must be 7 and there is no
- * block-wise normalisation (EUNSUPPORTED / EINVAL otherwise).  neuzip_compress, _batch, _guarded,
- * neuzip_recompress, the three decompress calls, export and import take such tensors;
- * neuzip_linear does not (EUNSUPPORTED). */
-enum { NEUZIP_BF16 = 0, NEUZIP_F32 = 1 };
+/* Element types.  The paper works on BFloat16 only (Sec. 2.1, footnote); the other two go beyond it.
+ * NEUZIP_F32: the upper half of an IEEE binary32 word is a bf16 word (sign, the same 8 exponent
+ * bits, 7 mantissa bits) and is compressed exactly as one; the lower half, 16 mantissa bits without
+ * structure, is kept as a raw plane after the sign|mantissa stream.
+ * NEUZIP_F16: IEEE binary16 (sign, 5 exponent bits, 10 mantissa bits); the upper byte of a word
+ * (sign, exponent, two mantissa bits) is the entropy-coded symbol in place of the bf16 exponent
+ * byte, the lower byte is stored in place of the sign|mantissa byte.
+ * Both are lossless only: mantissa_bits must be 7 and there is no block-wise normalisation
+ * (EUNSUPPORTED / EINVAL otherwise).  Header word 56 of the container holds the element type.
+ * neuzip_compress, _batch, _guarded, neuzip_recompress, the three decompress calls, export and
+ * import take such tensors; neuzip_linear and neuzip_update do not (EUNSUPPORTED). */
+enum { NEUZIP_BF16 = 0, NEUZIP_F32 = 1, NEUZIP_F16 = 2 };
 
 enum {
     NEUZIP_OK = 0,
@@ -79,7 +82,7 @@ enum {
  * weight update ("split", "compression", "store"); Sec. 2.3 for k < 7.
  *
  *   d_src          n_elems bf16 words on the device (read only).
- *   dtype          NEUZIP_BF16, or NEUZIP_F32 (n_elems binary32 words; see the element types).
+ *   dtype          NEUZIP_BF16, or NEUZIP_F32 / NEUZIP_F16 (n_elems words of that type; see the element types).
  *   mantissa_bits  7 = lossless; 3, 1 or 0 = keep that many leading mantissa
  *                  bits, truncating toward zero.
  *   blob           in/out.  *blob == NULL: a new blob is created.  Otherwise

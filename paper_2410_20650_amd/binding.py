@@ -13,7 +13,7 @@ import torch
 
 from . import build as _build
 
-BF16, F32 = 0, 1
+BF16, F32, F16 = 0, 1, 2
 OK, EINVAL, ENOMEM, EHIP, ECORRUPT, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 
 
@@ -108,13 +108,15 @@ def _stream_handle(stream):
 
 
 def _check_tensor(t, wide_ok=False):
-    """Returns the library's element type of a contiguous CUDA tensor (bf16; float32 where allowed)."""
+    """Returns the library's element type of a contiguous CUDA tensor (bf16; float32 and float16 where allowed)."""
     if t.is_cuda and t.is_contiguous():
         if t.dtype == torch.bfloat16:
             return BF16
         if wide_ok and t.dtype == torch.float32:
             return F32
-    raise TypeError("expected a contiguous bf16%s CUDA tensor" % (" or float32" if wide_ok else ""))
+        if wide_ok and t.dtype == torch.float16:
+            return F16
+    raise TypeError("expected a contiguous bf16%s CUDA tensor" % (", float32 or float16" if wide_ok else ""))
 
 
 def _shared_dtype(tensors):

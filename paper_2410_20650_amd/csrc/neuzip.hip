@@ -113,7 +113,7 @@ struct neuzip_blob {
     int k;
     uint32_t block;  // block size of the block-wise normalisation, 0 = none
     uint32_t guard;  // guard band of the frequency table, 0 = none
-    bool f32;        // elements are binary32 (lossless only): a plane of lower halves rides along
+    int elem;        // NEUZIP_BF16; NEUZIP_F32 (lossless only: a plane of lower halves rides along); NEUZIP_F16 (lossless only)
     bool has_table;  // holds a compressed tensor (and so a table that recompression can reuse)
     uint32_t n_chunks;
     uint64_t total_words;
@@ -272,7 +272,7 @@ int ensure_workspace(int device, uint64_t n_groups, hipStream_t stream)
     return NEUZIP_OK;
 }
 
-int alloc_blob(uint64_t n, int k, uint32_t block, bool f32, neuzip_blob **out)
+int alloc_blob(uint64_t n, int k, uint32_t block, int elem, neuzip_blob **out)
 {
     neuzip_blob *b = new (std::nothrow) neuzip_blob();
     if (!b)
@@ -282,9 +282,9 @@ int alloc_blob(uint64_t n, int k, uint32_t block, bool f32, neuzip_blob **out)
     b->n = n;
     b->k = k;
     b->block = block;
-    b->f32 = f32;
+    b->elem = elem;
     b->n_chunks = chunks_of(n);
-    b->at = fixed_layout(n, k, block, f32);
+    b->at = fixed_layout(n, k, block, elem == NEUZIP_F32);
     if (!hip_ok(hipGetDevice(&b->device))) {
         delete b;
         return NEUZIP_EHIP;
@@ -330,8 +330,12 @@ int reserve_words(neuzip_blob *b, uint64_t total_words)
 // tensor cannot fill the chip either way and is a chain of 256 dependent steps per lane; there
 // workgroups of 16 chunks spread the waves over twice as many CUs (4-7 % faster up to 16 M elements).
 // NEUZIP_DECODE_CHUNKS_PER_WG (4..32, multiple of 4) overrides the choice for tuning runs.
-uint32_t decode_chunks_per_wg(uint32_t n_chunks)
+// binary16 symbols carry 5-6 bits each (sign and two mantissa bits ride in the symbol), so only
+// 16 chunks' words fit the LDS window: such blobs always take workgroups of 16 chunks.
+uint32_t decode_chunks_per_wg(uint32_t n_chunks, bool f16 = false)
 {
+    if (f16)
+        return 16u;
     static int forced = -1;
     if (forced < 0) {
         const char *env = std::getenv("NEUZIP_DECODE_CHUNKS_PER_WG");
@@ -360,7 +364,7 @@ DecodeArgs decode_args(const neuzip_blob *b, void *d_dst)
     // 2 bytes out + ~1.3 in per element against 256 MB of Infinity Cache: beyond ~64 M elements
     // (half as many of binary32) the tensor streams through HBM and non-temporal stores measured
     // 5 % faster; below they cost 3 %
-    a.stream_out = (b->f32 ? 2 * b->n : b->n) >= (64ull << 20) ? 1u : 0u;
+    a.stream_out = ((b->elem == NEUZIP_F32) ? 2 * b->n : b->n) >= (64ull << 20) ? 1u : 0u;
     a.out = d_dst;
     a.status = table_of(b)->status;
     a.n = b->n;
@@ -372,7 +376,7 @@ DecodeArgs decode_args(const neuzip_blob *b, void *d_dst)
 template <int KB, bool NORM, int MODE = kPlain>
 int launch_decode(const neuzip_blob *b, void *d_dst, hipStream_t stream)
 {
-    const uint32_t per = decode_chunks_per_wg(b->n_chunks);
+    const uint32_t per = decode_chunks_per_wg(b->n_chunks, b->elem == NEUZIP_F16);
     const uint32_t groups = (b->n_chunks + per - 1) / per;
     hipLaunchKernelGGL((decode_kernel<KB, NORM, MODE>), dim3(groups), dim3(per * kStates), 0, stream,
                        decode_args(b, d_dst));
@@ -383,8 +387,10 @@ int decode_dispatch(const neuzip_blob *b, void *d_dst, hipStream_t stream)
 {
     if (b->n == 0)
         return NEUZIP_OK;
-    if (b->f32)
+    if (b->elem == NEUZIP_F32)
         return launch_decode<7, false, kWide>(b, d_dst, stream);
+    if (b->elem == NEUZIP_F16)
+        return launch_decode<7, false, kHalf>(b, d_dst, stream);
     if (b->block) {
         switch (b->k) {
         case 3: return launch_decode<3, true>(b, d_dst, stream);
@@ -400,12 +406,20 @@ int decode_dispatch(const neuzip_blob *b, void *d_dst, hipStream_t stream)
     }
 }
 
-// variant = mantissa_bits, + 8 for block-wise normalised blobs, + 16 for binary32 blobs
-inline int decode_variant(const neuzip_blob *b) { return b->k + (b->block ? 8 : 0) + (b->f32 ? 16 : 0); }
+// variant = mantissa_bits, + 8 for block-wise normalised blobs, + 16 for binary32, + 32 for binary16
+// blobs; kUpdateVariant is the lossless bf16 decoder that applies the weight step
+constexpr int kUpdateVariant = 100;
+inline int decode_variant(const neuzip_blob *b)
+{
+    return b->k + (b->block ? 8 : 0) + (b->elem == NEUZIP_F32 ? 16 : 0) + (b->elem == NEUZIP_F16 ? 32 : 0);
+}
+
+// chunks per workgroup of a batch launch of the given variant
+inline uint32_t batch_chunks_per_wg(int variant) { return variant == 39 ? 16u : kDecChunksPerWg; }
 
 int launch_batch(const BatchArgs &args, int variant, uint32_t groups, hipStream_t stream)
 {
-    const dim3 grid(groups), block(kDecThreads);
+    const dim3 grid(groups), block(batch_chunks_per_wg(variant) * kStates);
     switch (variant) {
     case 7: hipLaunchKernelGGL((decode_batch_kernel<7, false>), grid, block, 0, stream, args); break;
     case 3: hipLaunchKernelGGL((decode_batch_kernel<3, false>), grid, block, 0, stream, args); break;
@@ -414,7 +428,8 @@ int launch_batch(const BatchArgs &args, int variant, uint32_t groups, hipStream_
     case 11: hipLaunchKernelGGL((decode_batch_kernel<3, true>), grid, block, 0, stream, args); break;
     case 9: hipLaunchKernelGGL((decode_batch_kernel<1, true>), grid, block, 0, stream, args); break;
     case 23: hipLaunchKernelGGL((decode_batch_kernel<7, false, kWide>), grid, block, 0, stream, args); break;
-    case 39: hipLaunchKernelGGL((decode_batch_kernel<7, false, kUpdate>), grid, block, 0, stream, args); break;
+    case 39: hipLaunchKernelGGL((decode_batch_kernel<7, false, kHalf>), grid, block, 0, stream, args); break;
+    case kUpdateVariant: hipLaunchKernelGGL((decode_batch_kernel<7, false, kUpdate>), grid, block, 0, stream, args); break;
     default: hipLaunchKernelGGL((decode_batch_kernel<0, true>), grid, block, 0, stream, args); break;
     }
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
@@ -487,7 +502,7 @@ void launch_encode_reuse(const CompressBatch &batch, uint32_t groups, hipStream_
 // guard band).  reuse = true: every blob holds a table already and the tensors are coded with
 // those, in one pass over the source; rebuilt[i] is set for the tensors whose table turned out
 // not to cover them, which are then compressed the first way.
-int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int k, uint32_t block, bool f32,
+int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int k, uint32_t block, int elem,
                   uint32_t guard, bool reuse, uint32_t *rebuilt, hipStream_t stream, neuzip_blob **blobs)
 {
     neuzip_blob *work[kBatchMax];
@@ -512,7 +527,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
     };
     for (uint32_t i = 0; i < count; ++i) {
         if (!work[i]) {
-            const int rc = alloc_blob(n_elems[i], k, block, f32, &work[i]);
+            const int rc = alloc_blob(n_elems[i], k, block, elem, &work[i]);
             if (rc != NEUZIP_OK)
                 return fail(rc);
             fresh[i] = true;
@@ -584,7 +599,11 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             // one pass: encoder constants from the stored tables, then split + encode together
             hipLaunchKernelGGL(table_reuse_kernel, dim3(batch.count), dim3(256), 0, stream, batch, g_ws.enc,
                                g_ws.stale);
-            switch (f32 ? 23 : k) {
+            switch (elem == NEUZIP_F32 ? 23 : (elem == NEUZIP_F16 ? 39 : k)) {
+            case 39:
+                hipLaunchKernelGGL((encode_kernel<false, 7, false, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream,
+                                   batch, g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned, g_ws.stale);
+                break;
             case 23:
                 hipLaunchKernelGGL((encode_kernel<false, 7, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream, batch,
                                    g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned, g_ws.stale);
@@ -595,7 +614,11 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             default: launch_encode_reuse<0>(batch, enc_groups, stream); break;
             }
         } else {
-            switch (f32 ? 23 : k) {
+            switch (elem == NEUZIP_F32 ? 23 : (elem == NEUZIP_F16 ? 39 : k)) {
+            case 39:
+                hipLaunchKernelGGL((hist_split_kernel<7, false, true>), dim3(hist_groups), dim3(kHistThreads), 0, stream,
+                                   batch, g_ws.counts);
+                break;
             case 23:
                 hipLaunchKernelGGL((hist_split_kernel<7, true>), dim3(hist_groups), dim3(kHistThreads), 0, stream, batch,
                                    g_ws.counts);
@@ -612,7 +635,11 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             hipLaunchKernelGGL(table_kernel, dim3(batch.count), dim3(256), 0, stream, batch, g_ws.counts, g_ws.enc);
             if (hip_ok(hipGetLastError()))
                 bins_dirty = false;
-            if (f32)
+            if (elem == NEUZIP_F16)
+                hipLaunchKernelGGL((encode_kernel<false, -1, false, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream,
+                                   batch, g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned,
+                                   static_cast<uint32_t *>(nullptr));
+            else if (elem == NEUZIP_F32)
                 hipLaunchKernelGGL((encode_kernel<false, -1, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream,
                                    batch, g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned,
                                    static_cast<uint32_t *>(nullptr));
@@ -672,7 +699,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
     }
     if (stale_count > 0) {
         // same stream, so the pass above has finished with the workspace before this one starts
-        const int rc = compress_some(stale_src, stale_n, stale_count, k, block, f32, kKeepGuard, false, nullptr, stream,
+        const int rc = compress_some(stale_src, stale_n, stale_count, k, block, elem, kKeepGuard, false, nullptr, stream,
                                      stale_blob);
         if (rc != NEUZIP_OK)
             return rc;
@@ -749,7 +776,7 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
         const neuzip_blob *lead = blobs[first];
         uint32_t m = 1;
         while (first + m < count && m < kBatchMax && blobs[first + m]->k == lead->k &&
-               blobs[first + m]->block == lead->block && blobs[first + m]->f32 == lead->f32)
+               blobs[first + m]->block == lead->block && blobs[first + m]->elem == lead->elem)
             ++m;
         uint64_t n_elems[kBatchMax];
         neuzip_blob *group[kBatchMax];
@@ -758,7 +785,7 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
             group[j] = blobs[first + j];
         }
         const bool reuse = lead->block == 0;
-        const int rc = compress_some(d_srcs + first, n_elems, m, lead->k, lead->block, lead->f32, kKeepGuard, reuse,
+        const int rc = compress_some(d_srcs + first, n_elems, m, lead->k, lead->block, lead->elem, kKeepGuard, reuse,
                                      rebuilt ? rebuilt + first : nullptr, stream, group);
         if (rc != NEUZIP_OK)
             return rc;
@@ -781,7 +808,7 @@ int neuzip_update(neuzip_blob *const *blobs, const void *const *d_grads, void *c
         const neuzip_blob *b = blobs[i];
         if (!is_blob(b) || !b->has_table || !on_current_device(b))
             return NEUZIP_EINVAL;
-        if (b->k != 7 || b->block != 0 || b->f32)
+        if (b->k != 7 || b->block != 0 || b->elem != NEUZIP_BF16)
             return NEUZIP_EUNSUPPORTED;  // training keeps bf16 weights without loss
         if (b->n > 0 && (!d_grads[i] || !d_weights[i] || (reinterpret_cast<uintptr_t>(d_grads[i]) & 15u) ||
                          (reinterpret_cast<uintptr_t>(d_weights[i]) & 15u)))
@@ -802,7 +829,7 @@ int neuzip_update(neuzip_blob *const *blobs, const void *const *d_grads, void *c
     for (uint32_t i = 0; i <= count; ++i) {
         const bool flush = (i == count) || (args.count == kBatchMax);
         if (flush && args.count > 0) {
-            const int rc = launch_batch(args, 39, groups, stream);
+            const int rc = launch_batch(args, kUpdateVariant, groups, stream);
             if (rc != NEUZIP_OK)
                 return rc;
             args.count = 0;
@@ -840,7 +867,7 @@ int neuzip_linear(const neuzip_blob *weight, uint64_t out_features, uint64_t in_
     if ((reinterpret_cast<uintptr_t>(d_x) & 15u) || (reinterpret_cast<uintptr_t>(d_y) & 3u) ||
         (reinterpret_cast<uintptr_t>(d_bias) & 3u))
         return NEUZIP_EINVAL;
-    if (weight->block != 0 || weight->f32)
+    if (weight->block != 0 || weight->elem != NEUZIP_BF16)
         return NEUZIP_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     uint64_t gcd = in_features, r = kChunk;
@@ -892,13 +919,13 @@ int compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t 
 {
     if (count == 0)
         return NEUZIP_OK;
-    if (!d_srcs || !n_elems || !blobs || (dtype != NEUZIP_BF16 && dtype != NEUZIP_F32) || !valid_k(mantissa_bits))
+    if (!d_srcs || !n_elems || !blobs || (dtype != NEUZIP_BF16 && dtype != NEUZIP_F32 && dtype != NEUZIP_F16) ||
+        !valid_k(mantissa_bits))
         return NEUZIP_EINVAL;
     if (block_size != 0 && (!valid_block(block_size) || mantissa_bits == 7))
         return NEUZIP_EINVAL;
-    const bool f32 = dtype == NEUZIP_F32;
-    if (f32 && mantissa_bits != 7)
-        return NEUZIP_EUNSUPPORTED;  // binary32 tensors are compressed without loss only
+    if (dtype != NEUZIP_BF16 && mantissa_bits != 7)
+        return NEUZIP_EUNSUPPORTED;  // binary32 and binary16 tensors are compressed without loss only
     for (uint32_t i = 0; i < count; ++i) {
         if (n_elems[i] > 0 && (!d_srcs[i] || (reinterpret_cast<uintptr_t>(d_srcs[i]) & 15u)))
             return NEUZIP_EINVAL;
@@ -906,7 +933,7 @@ int compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t 
             return NEUZIP_EUNSUPPORTED;
         const neuzip_blob *b = blobs[i];
         if (b && (!is_blob(b) || b->n != n_elems[i] || b->k != mantissa_bits || b->block != block_size ||
-                  b->f32 != f32 || !on_current_device(b)))
+                  b->elem != dtype || !on_current_device(b)))
             return NEUZIP_EINVAL;
         for (uint32_t j = 0; j < i; ++j)
             if (b && blobs[j] == b)
@@ -915,7 +942,7 @@ int compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     for (uint32_t first = 0; first < count; first += kBatchMax) {
         const uint32_t m = count - first < kBatchMax ? count - first : kBatchMax;
-        const int rc = compress_some(d_srcs + first, n_elems + first, m, mantissa_bits, block_size, f32, guard, false,
+        const int rc = compress_some(d_srcs + first, n_elems + first, m, mantissa_bits, block_size, dtype, guard, false,
                                      nullptr, stream, blobs + first);
         if (rc != NEUZIP_OK)
             return rc;
@@ -929,7 +956,7 @@ extern "C" {
 
 int neuzip_decompress(const neuzip_blob *blob, void *d_dst, uint64_t n_elems, int dtype, void *hip_stream)
 {
-    if (!is_blob(blob) || !blob->has_table || dtype != (blob->f32 ? NEUZIP_F32 : NEUZIP_BF16) ||
+    if (!is_blob(blob) || !blob->has_table || dtype != blob->elem ||
         blob->n != n_elems || !on_current_device(blob))
         return NEUZIP_EINVAL;
     if (n_elems > 0 && (!d_dst || (reinterpret_cast<uintptr_t>(d_dst) & 15u)))
@@ -946,7 +973,7 @@ int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, 
         return NEUZIP_EINVAL;
     for (uint32_t i = 0; i < count; ++i) {
         if (!is_blob(blobs[i]) || !blobs[i]->has_table ||
-            (blobs[i]->f32 ? 2 * blobs[i]->n : blobs[i]->n) > scratch_elems ||
+            ((blobs[i]->elem == NEUZIP_F32) ? 2 * blobs[i]->n : blobs[i]->n) > scratch_elems ||
             (blobs[i]->n > 0 && !d_scratch) || !on_current_device(blobs[i]))
             return NEUZIP_EINVAL;
     }
@@ -971,11 +998,11 @@ int neuzip_decompress_batch(const neuzip_blob *const *blobs, void *const *d_dsts
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     uint64_t batch_elems = 0;
     for (uint32_t i = 0; i < count; ++i)
-        batch_elems += blobs[i]->f32 ? 2 * blobs[i]->n : blobs[i]->n;
+        batch_elems += (blobs[i]->elem == NEUZIP_F32) ? 2 * blobs[i]->n : blobs[i]->n;
     const bool stream_out = batch_elems >= (64ull << 20);  // the batch as a whole exceeds the cache
     // tensors of the same kind (mantissa_bits, normalised or not) share launches of up to
     // kBatchMax tensors, in the given order
-    static const int kinds[8] = {7, 3, 1, 0, 11, 9, 8, 23};
+    static const int kinds[9] = {7, 3, 1, 0, 11, 9, 8, 23, 39};
     for (int k : kinds) {
         BatchArgs args;
         args.count = 0;
@@ -996,7 +1023,7 @@ int neuzip_decompress_batch(const neuzip_blob *const *blobs, void *const *d_dsts
                 continue;
             DecodeArgs a = decode_args(b, d_dsts[i]);
             a.stream_out = stream_out ? 1u : 0u;
-            groups += (b->n_chunks + kDecChunksPerWg - 1) / kDecChunksPerWg;
+            groups += (b->n_chunks + batch_chunks_per_wg(k) - 1) / batch_chunks_per_wg(k);
             a.wg_end = groups;
             args.t[args.count++] = a;
         }
@@ -1026,7 +1053,7 @@ uint64_t neuzip_compressed_bytes(const neuzip_blob *blob)
 {
     if (!is_blob(blob))
         return 0;
-    return container_layout(blob->n, blob->k, blob->total_words, blob->block, blob->f32).total;
+    return container_layout(blob->n, blob->k, blob->total_words, blob->block, (blob->elem == NEUZIP_F32)).total;
 }
 
 uint64_t neuzip_device_bytes(const neuzip_blob *blob)
@@ -1040,13 +1067,13 @@ uint64_t neuzip_elems(const neuzip_blob *blob) { return is_blob(blob) ? blob->n 
 uint32_t neuzip_block_size(const neuzip_blob *blob) { return is_blob(blob) ? blob->block : 0; }
 int neuzip_mantissa_bits(const neuzip_blob *blob) { return is_blob(blob) ? blob->k : -1; }
 
-int neuzip_dtype(const neuzip_blob *blob) { return !is_blob(blob) ? -1 : (blob->f32 ? NEUZIP_F32 : NEUZIP_BF16); }
+int neuzip_dtype(const neuzip_blob *blob) { return is_blob(blob) ? blob->elem : -1; }
 
 int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *written, void *hip_stream)
 {
     if (!is_blob(blob) || !blob->has_table || (h_buf && !on_current_device(blob)))
         return NEUZIP_EINVAL;
-    const Container lay = container_layout(blob->n, blob->k, blob->total_words, blob->block, blob->f32);
+    const Container lay = container_layout(blob->n, blob->k, blob->total_words, blob->block, (blob->elem == NEUZIP_F32));
     if (written)
         *written = lay.total;
     if (!h_buf)
@@ -1070,7 +1097,7 @@ int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *
     put64(40, blob->total_words);
     put32(48, blob->block);
     put32(52, blob->guard);
-    put32(56, blob->f32 ? 1u : 0u);  // element type
+    put32(56, static_cast<uint32_t>(blob->elem));  // element type
     const uint64_t nc = blob->n_chunks;
     NZ_HIP(hipMemcpyAsync(p + lay.freq, table_of(blob)->freq, 512, hipMemcpyDeviceToHost, stream));
     NZ_HIP(hipMemcpyAsync(p + lay.offsets, offsets_of(blob), (nc + 1) * 4, hipMemcpyDeviceToHost, stream));
@@ -1083,7 +1110,7 @@ int neuzip_export(const neuzip_blob *blob, void *h_buf, uint64_t cap, uint64_t *
     if (blob->n)
         NZ_HIP(hipMemcpyAsync(p + lay.sm, sm_of(blob), signmant_bytes(blob->n, blob->k), hipMemcpyDeviceToHost,
                               stream));
-    if (blob->n && blob->f32)
+    if (blob->n && (blob->elem == NEUZIP_F32))
         NZ_HIP(hipMemcpyAsync(p + lay.low, low_of(blob), blob->n * 2, hipMemcpyDeviceToHost, stream));
     if (blob->n && blob->block)
         NZ_HIP(hipMemcpyAsync(p + lay.coef, coef_of(blob), block_count(blob->n, blob->block), hipMemcpyDeviceToHost,
@@ -1116,9 +1143,9 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
     if (guard > 255 || (guard != 0 && block != 0))
         return NEUZIP_ECORRUPT;
     const uint32_t elem = get32(56);
-    if (elem > 1 || (elem == 1 && (k != 7 || block != 0)))
+    if (elem > NEUZIP_F16 || (elem != NEUZIP_BF16 && (k != 7 || block != 0)))
         return NEUZIP_ECORRUPT;
-    const bool f32 = elem == 1;
+    const bool f32 = elem == NEUZIP_F32;
     const uint32_t nc = chunks_of(n);
     if (get32(36) != nc)
         return NEUZIP_ECORRUPT;
@@ -1155,7 +1182,7 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
         return NEUZIP_ECORRUPT;
 
     neuzip_blob *b = nullptr;
-    int rc = alloc_blob(n, k, block, f32, &b);
+    int rc = alloc_blob(n, k, block, static_cast<int>(elem), &b);
     if (rc != NEUZIP_OK)
         return rc;
     auto fail = [&](int code) {

@@ -65,6 +65,36 @@ __device__ inline void store_fields(uint8_t *sm, uint64_t vec, uint64_t packed)
         sm[vec] = static_cast<uint8_t>(packed);
 }
 
+// binary16 words (HALF; beyond the paper's BFloat16): the coded symbol is a word's upper byte
+// (sign, 5 exponent bits, 2 mantissa bits), the stored field its lower byte (8 mantissa bits).
+template <bool HALF>
+__device__ __forceinline__ uint32_t symbol_of(uint32_t u)
+{
+    return HALF ? (u >> 8) & 0xFFu : exponent_of(u);
+}
+
+template <int KB, bool HALF>
+__device__ __forceinline__ uint32_t field_of(uint32_t u)
+{
+    if constexpr (HALF)
+        return u & 0xFFu;
+    else
+        return signmant_field<KB>(u);
+}
+
+template <int KB, bool HALF>
+__device__ __forceinline__ uint64_t fields_of(const uint32_t (&w)[4])
+{
+    if constexpr (HALF) {
+        // the lower bytes of 8 neighbouring words, first element lowest
+        static_assert(KB == 7, "binary16 tensors are lossless only");
+        return static_cast<uint64_t>(__builtin_amdgcn_perm(w[1], w[0], 0x06040200u)) |
+               (static_cast<uint64_t>(__builtin_amdgcn_perm(w[3], w[2], 0x06040200u)) << 32);
+    } else {
+        return pack_fields<KB>(w);
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // Block-wise normalisation of the lossy variant (Sec. 2.3): a block of 32..512 consecutive
 // weights shares one coefficient byte, the mantissa of its largest-magnitude weight; with
@@ -182,7 +212,7 @@ __device__ __forceinline__ ItemSlot item_of_workgroup(const CompressBatch &b)
     return {i, blockIdx.x - first, b.it[i].*END - first};
 }
 
-template <int KB, bool WIDE = false>
+template <int KB, bool WIDE = false, bool HALF = false>
 __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const CompressBatch b,
                                                                  uint32_t *__restrict__ counts_ws)
 {
@@ -226,10 +256,10 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const Compress
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const uint32_t lo = w[p] & 0xFFFFu, hi = w[p] >> 16;
-                atomicAdd(&bins[exponent_of(lo) * kHistCopies + copy], 1u);
-                atomicAdd(&bins[exponent_of(hi) * kHistCopies + copy], 1u);
+                atomicAdd(&bins[symbol_of<HALF>(lo) * kHistCopies + copy], 1u);
+                atomicAdd(&bins[symbol_of<HALF>(hi) * kHistCopies + copy], 1u);
             }
-            store_fields<KB>(sm, v, pack_fields<KB>(w));
+            store_fields<KB>(sm, v, fields_of<KB, HALF>(w));
         }
     }
     // ragged tail (n mod 8 elements): one thread, element by element
@@ -238,8 +268,8 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const Compress
         uint32_t acc = 0, filled = 0;
         for (uint64_t i = n_vec * 8; i < n; ++i) {
             const uint32_t u = source_word<WIDE, true>(src, low, i);
-            atomicAdd(&bins[exponent_of(u) * kHistCopies + copy], 1u);
-            acc |= signmant_field<KB>(u) << (filled * (KB + 1));
+            atomicAdd(&bins[symbol_of<HALF>(u) * kHistCopies + copy], 1u);
+            acc |= field_of<KB, HALF>(u) << (filled * (KB + 1));
             if (++filled == per_byte) {
                 sm[i / per_byte] = static_cast<uint8_t>(acc);
                 acc = 0;
@@ -602,7 +632,7 @@ __device__ __forceinline__ void ring_flush(uint32_t wp_before, uint32_t wp_after
 // (SPLIT = mantissa bits) of the words it codes, and it reports, through stale[item], any exponent
 // that the table has no room for (such symbols leave the state unchanged; the host then falls
 // back to a compression with fresh statistics).
-template <bool NORM, int SPLIT, bool WIDE = false>
+template <bool NORM, int SPLIT, bool WIDE = false, bool HALF = false>
 __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch b,
                                                             const EncSym *__restrict__ enc_all,
                                                             uint32_t *__restrict__ chunk_words_all,
@@ -612,7 +642,8 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
                                                             uint32_t *__restrict__ stale)
 {
     static_assert(!(NORM && SPLIT >= 0), "the one-pass variant has no block maxima to normalise with");
-    static_assert(!WIDE || (!NORM && (SPLIT < 0 || SPLIT == 7)), "binary32 tensors are lossless only");
+    static_assert(!(WIDE || HALF) || (!NORM && (SPLIT < 0 || SPLIT == 7)), "binary32 and binary16 tensors are lossless only");
+    static_assert(!(WIDE && HALF), "one element type");
     constexpr int KB = SPLIT >= 0 ? SPLIT : 7;
     const ItemSlot slot_id = item_of_workgroup<&CompressItem::enc_end>(b);
     const CompressItem &it = b.it[slot_id.item];
@@ -669,7 +700,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
             d.words(w);
             const uint32_t wp_before = st.wp;
             if constexpr (SPLIT >= 0) {
-                store_fields<KB>(sm, base / 8 + static_cast<uint32_t>(q) * kStates + j, pack_fields<KB>(w));
+                store_fields<KB>(sm, base / 8 + static_cast<uint32_t>(q) * kStates + j, fields_of<KB, HALF>(w));
                 if constexpr (WIDE)
                     reinterpret_cast<uint4 *>(low)[base / 8 + static_cast<uint32_t>(q) * kStates + j] = d.lows();
             }
@@ -681,7 +712,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
             for (int p = 3; p >= 0; --p) {
                 const uint32_t hi = NORM ? normalise_word(w[p] >> 16, c) : (w[p] >> 16);
                 const uint32_t lo = NORM ? normalise_word(w[p] & 0xFFFFu, c) : (w[p] & 0xFFFFu);
-                const EncSym e_hi = enc[exponent_of(hi)], e_lo = enc[exponent_of(lo)];
+                const EncSym e_hi = enc[symbol_of<HALF>(hi)], e_lo = enc[symbol_of<HALF>(lo)];
                 if constexpr (SPLIT >= 0)
                     least_rcp = fminf(least_rcp, fminf(e_hi.rcp, e_lo.rcp));
                 rans_put(st, e_hi, ring);
@@ -701,10 +732,10 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
                     uint32_t u = source_word<WIDE, (SPLIT >= 0)>(src, low, base + i);
                     if constexpr (NORM)
                         u = normalise_word(u, coefficient(coef[(base + i) >> block_shift]));
-                    const EncSym e = enc[exponent_of(u)];
+                    const EncSym e = enc[symbol_of<HALF>(u)];
                     if constexpr (SPLIT >= 0) {
                         least_rcp = fminf(least_rcp, e.rcp);
-                        packed |= static_cast<uint64_t>(signmant_field<KB>(u)) << (static_cast<uint32_t>(t) * (KB + 1));
+                        packed |= static_cast<uint64_t>(field_of<KB, HALF>(u)) << (static_cast<uint32_t>(t) * (KB + 1));
                     }
                     rans_put(st, e, ring);
                 }

@@ -67,6 +67,15 @@ __device__ __forceinline__ uint32_t merge_pair(uint64_t fields, int pair, uint32
     }
 }
 
+// binary16 words: the decoded symbol is the word's upper byte, the field its lower byte.
+__device__ __forceinline__ uint32_t merge_pair_half(uint64_t fields, int pair, uint32_t entry_lo, uint32_t entry_hi)
+{
+    const uint32_t sym = __builtin_amdgcn_perm(entry_hi, entry_lo, 0x0c040c00u);  // [0, symbol_hi, 0, symbol_lo]
+    const uint32_t half = static_cast<uint32_t>(fields >> (32 * (pair >> 1)));
+    // [symbol_hi, field_hi, symbol_lo, field_lo]
+    return __builtin_amdgcn_perm(sym, half, (pair & 1) ? 0x06030402u : 0x06010400u);
+}
+
 struct LdsWords {
     const uint8_t *base;  // LDS copy of the workgroup's runs
     __device__ __forceinline__ uint32_t peek(uint32_t at) const { return *reinterpret_cast<const uint16_t *>(base + at); }
@@ -159,8 +168,8 @@ __device__ __forceinline__ uint32_t update_word(uint32_t w, uint32_t g, float lr
 }
 
 // UPD: the words written are the decoded weights after the update with the gradient `grad` (bf16
-// words, same indexing as the output) and the rate lr.
-template <int KB, bool LONE, bool NORM, bool STREAM, bool UPD, class WordSrc>
+// words, same indexing as the output) and the rate lr.  HALF: the tensor is binary16.
+template <int KB, bool LONE, bool NORM, bool STREAM, bool UPD, bool HALF, class WordSrc>
 __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
                                            uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
                                            const uint8_t *__restrict__ coef, uint32_t block,
@@ -169,7 +178,8 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
                                            uint64_t base, uint32_t m, uint32_t j,
                                            const uint16_t *__restrict__ grad = nullptr, float lr = 0.0f)
 {
-    static_assert(!UPD || (KB == 7 && !NORM), "only lossless weights are trained");
+    static_assert(!(UPD || HALF) || (KB == 7 && !NORM), "trained weights and binary16 tensors are lossless only");
+    static_assert(!(UPD && HALF), "only bf16 weights are trained");
     // `fields` arrives holding the field bits of the state's first turns (full chunks only)
     constexpr uint32_t kGroup = (STREAM && KB == 7 && !UPD) ? kTurnGroupStream : kTurnGroup;
     uint32_t next = LONE ? 0u : src.peek(wp);
@@ -208,10 +218,17 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
 #pragma unroll
                 for (int t = 0; t < 8; ++t)
                     e[t] = LONE ? lone : rans_get(lut, x, wp, next, src);
-                o[r].x = merge_pair<KB>(fields[r], 0, e[0], e[1]);
-                o[r].y = merge_pair<KB>(fields[r], 1, e[2], e[3]);
-                o[r].z = merge_pair<KB>(fields[r], 2, e[4], e[5]);
-                o[r].w = merge_pair<KB>(fields[r], 3, e[6], e[7]);
+                if constexpr (HALF) {
+                    o[r].x = merge_pair_half(fields[r], 0, e[0], e[1]);
+                    o[r].y = merge_pair_half(fields[r], 1, e[2], e[3]);
+                    o[r].z = merge_pair_half(fields[r], 2, e[4], e[5]);
+                    o[r].w = merge_pair_half(fields[r], 3, e[6], e[7]);
+                } else {
+                    o[r].x = merge_pair<KB>(fields[r], 0, e[0], e[1]);
+                    o[r].y = merge_pair<KB>(fields[r], 1, e[2], e[3]);
+                    o[r].z = merge_pair<KB>(fields[r], 2, e[4], e[5]);
+                    o[r].w = merge_pair<KB>(fields[r], 3, e[6], e[7]);
+                }
                 if constexpr (NORM) {
                     const float c = coefficient(static_cast<uint32_t>(fields[r] >> 32) & 0x7Fu);
                     o[r].x = denormalise_pair(o[r].x, c);
@@ -254,7 +271,8 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
                 const uint32_t sym = (LONE ? lone : rans_get(lut, x, wp, next, src)) & 0xFFu;
                 const uint64_t g = base + i;
                 const uint32_t field = (sm[g / per_byte] >> ((g % per_byte) * width)) & ((1u << width) - 1u);
-                uint32_t u = ((field >> KB) << 15) | (sym << 7) | ((field & ((1u << KB) - 1u)) << (7 - KB));
+                uint32_t u = HALF ? (sym << 8) | field
+                                  : ((field >> KB) << 15) | (sym << 7) | ((field & ((1u << KB) - 1u)) << (7 - KB));
                 if constexpr (NORM)
                     u = denormalise_word(u, coefficient(coef[g >> block]));
                 if constexpr (UPD)
@@ -402,8 +420,9 @@ struct DecodeArgs {
 
 // Decodes the chunks of workgroup `wg` of one tensor.
 // MODE: what is written -- the decoded bf16 words (kPlain), binary32 words joined with their
-// lower halves (kWide), or the decoded weights after the update of the backward loop (kUpdate).
-enum DecodeMode { kPlain = 0, kWide = 1, kUpdate = 2 };
+// lower halves (kWide), the decoded weights after the update of the backward loop (kUpdate), or
+// binary16 words (kHalf).
+enum DecodeMode { kPlain = 0, kWide = 1, kUpdate = 2, kHalf = 3 };
 
 template <int KB, bool NORM, int MODE>
 __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ tb,
@@ -418,7 +437,7 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
                                                  uint64_t n, uint32_t n_chunks, uint32_t *__restrict__ status,
                                                  uint32_t wg, uint32_t *__restrict__ lut, uint8_t *__restrict__ stage)
 {
-    constexpr bool WIDE = MODE == kWide, UPD = MODE == kUpdate;
+    constexpr bool WIDE = MODE == kWide, UPD = MODE == kUpdate, HALF = MODE == kHalf;
     static_assert(MODE == kPlain || (KB == 7 && !NORM), "binary32 blobs and trained weights are lossless only");
     block = 31u - static_cast<uint32_t>(__clz(static_cast<int>(block | 1u)));  // a power of two: from here on its log2
     uint16_t *__restrict__ out = static_cast<uint16_t *>(out_any);
@@ -516,25 +535,25 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
         }
     } else if (lone < 256) {
         if (stream_out)
-            walk_state<KB, true, NORM, true, UPD>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
+            walk_state<KB, true, NORM, true, UPD, HALF>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
         else
-            walk_state<KB, true, NORM, false, UPD>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
+            walk_state<KB, true, NORM, false, UPD, HALF>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
     } else if (staged) {
         wp = wp_begin = static_cast<uint32_t>(run_byte - aligned0);
         if (stream_out)
-            walk_state<KB, false, NORM, true, UPD>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
+            walk_state<KB, false, NORM, true, UPD, HALF>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
                                               j, grad, lr);
         else
-            walk_state<KB, false, NORM, false, UPD>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
+            walk_state<KB, false, NORM, false, UPD, HALF>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
                                                j, grad, lr);
     } else {
         // the runs of this workgroup's chunks did not fit the LDS window (more than ~4 bits per
         // symbol): read the words straight from the blob
         const GlobalWords direct{reinterpret_cast<const uint8_t *>(words) + run_byte};
         if (stream_out)
-            walk_state<KB, false, NORM, true, UPD>(lut, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
+            walk_state<KB, false, NORM, true, UPD, HALF>(lut, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
         else
-            walk_state<KB, false, NORM, false, UPD>(lut, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
+            walk_state<KB, false, NORM, false, UPD, HALF>(lut, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
     }
     // a well-formed run is consumed exactly and leaves the state where the encoder started
     if (x != kRansL || wp - wp_begin != 2 * len)

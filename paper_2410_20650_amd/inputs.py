@@ -81,6 +81,30 @@ def all_upper_halves_f32(low: int, device="cpu") -> torch.Tensor:
     return (v - (v >= 2 ** 31) * 2 ** 32).to(torch.int32).view(torch.float32)
 
 
+def gaussian_f16(n_or_shape, seed: int, std: float = 0.02, device="cpu") -> torch.Tensor:
+    """i.i.d. N(0, std^2) drawn in fp32 and rounded to binary16."""
+    shape = (n_or_shape,) if isinstance(n_or_shape, int) else tuple(n_or_shape)
+    g = _generator(seed, device)
+    return (torch.randn(shape, generator=g, device=device, dtype=torch.float32) * std).to(torch.float16)
+
+
+def all_patterns_f16(device="cpu") -> torch.Tensor:
+    """All 65,536 binary16 bit patterns in ascending order."""
+    v = torch.arange(65536, dtype=torch.int32, device=device)
+    return (v - 65536 * (v >= 32768)).to(torch.int16).view(torch.float16)
+
+
+def bits16(t: torch.Tensor) -> np.ndarray:
+    """Raw 16-bit words of a float16 tensor as a flat uint16 numpy array (host copy)."""
+    assert t.dtype == torch.float16
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16).reshape(-1)
+
+
+def from_bits16(words: np.ndarray, device="cpu") -> torch.Tensor:
+    w = np.ascontiguousarray(words, dtype=np.uint16).view(np.int16)
+    return torch.from_numpy(w.copy()).to(device).view(torch.float16)
+
+
 def bits32(t: torch.Tensor) -> np.ndarray:
     """Raw 32-bit words of a float32 tensor as a flat uint32 numpy array (host copy)."""
     assert t.dtype == torch.float32

@@ -155,7 +155,7 @@ def test_f32_argument_errors(nz):
         assert lib.neuzip_compress(ctypes.c_void_p(w.data_ptr()), w.numel(), nz.F32, k, none,
                                    ctypes.byref(handle)) == nz.EUNSUPPORTED
     handle = ctypes.c_void_p(None)
-    assert lib.neuzip_compress(ctypes.c_void_p(w.data_ptr()), w.numel(), 2, 7, none, ctypes.byref(handle)) == nz.EINVAL
+    assert lib.neuzip_compress(ctypes.c_void_p(w.data_ptr()), w.numel(), 3, 7, none, ctypes.byref(handle)) == nz.EINVAL
     # element types do not mix: a binary32 blob takes no bf16 tensor and decodes into no bf16 buffer
     handle = ctypes.c_void_p(blob.handle.value)
     assert lib.neuzip_compress(ctypes.c_void_p(h.data_ptr()), h.numel(), nz.BF16, 7, none,

@@ -320,7 +320,7 @@ def test_argument_errors(nz):
     with pytest.raises(nz.NeuzipError):
         nz.neuzip_decompress(blob, torch.empty(10_008, dtype=torch.bfloat16, device=DEV)[1:10_001])  # misaligned
     with pytest.raises(TypeError):
-        nz.neuzip_compress(w.to(torch.float16), 7)
+        nz.neuzip_compress(w.to(torch.float64), 7)
     with pytest.raises(TypeError):
         nz.neuzip_compress_batch([w, w.float()], 7)                # one element type per call
 

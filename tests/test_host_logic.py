@@ -60,7 +60,8 @@ def test_argument_validation_happens_before_device_work(nz):
     fake = ctypes.c_void_p(0x1000)
     # null out-pointer, bad dtype, bad mantissa_bits, misaligned source, oversize
     assert lib.neuzip_compress(fake, 16, 0, 7, None, None) == nz.EINVAL
-    assert lib.neuzip_compress(fake, 16, 2, 7, None, ctypes.byref(handle)) == nz.EINVAL
+    assert lib.neuzip_compress(fake, 16, 3, 7, None, ctypes.byref(handle)) == nz.EINVAL
+    assert lib.neuzip_compress(fake, 16, nz.F16, 0, None, ctypes.byref(handle)) == nz.EUNSUPPORTED
     assert lib.neuzip_compress(fake, 16, nz.F32, 3, None, ctypes.byref(handle)) == nz.EUNSUPPORTED   # lossless only
     assert lib.neuzip_compress_blockwise(fake, 16, nz.F32, 3, 64, None, ctypes.byref(handle)) == nz.EUNSUPPORTED
     for k in (-1, 2, 4, 5, 6, 8):
