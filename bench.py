@@ -289,6 +289,27 @@ def main():
         del w32, o32, u32
         torch.cuda.empty_cache()
 
+        # binary16: the same weight as float16 -- the upper byte of a word is the coded symbol
+        w16 = inputs.gaussian_f16(inputs.MLP_8B, inputs.seed_for(11), device=dev)
+        o16 = torch.empty_like(w16)
+        b16 = nz.neuzip_compress(w16, 7)
+        f16 = {"elements": w16.numel(), "bits_per_weight": round(8.0 * b16.compressed_bytes / w16.numel(), 4)}
+        for name, fn, nbytes in (("decompress", lambda: nz.neuzip_decompress(b16, o16), b16.compressed_bytes + 2.0 * w16.numel()),
+                                 ("compress", lambda: nz.neuzip_compress(w16, 7, blob=b16),
+                                  4.0 * w16.numel() + b16.compressed_bytes)):
+            for _ in range(3):
+                fn()
+            _, ms = timed_region(torch, stream, fn, 20)
+            ms /= 20
+            f16[name] = {"us": round(ms * 1e3, 1), "GBps_tensor": round(2.0 * w16.numel() / (ms * 1e-3) / 1e9, 1),
+                         "hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        assert torch.equal(o16.view(torch.int16), w16.view(torch.int16)), "binary16 round trip"
+        f16["bitwise_round_trip"] = "verified"
+        ext["binary16_mlp_8b"] = f16
+        nz.neuzip_free(b16)
+        del w16, o16
+        torch.cuda.empty_cache()
+
         # the weight update of the backward loop (Alg. 1): W <- W - lr * grad on the compressed 8B-shaped
         # MLP weight, as one library call (the decoder applies the step, then the kept-table encoder)
         # against decompress, torch's in-place bf16 step, recompress
