@@ -128,10 +128,13 @@ __device__ __forceinline__ uint32_t denormalise_pair(uint32_t d, float c)
     typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
     const f32x2_t prod = {__fmul_rn(__uint_as_float(d << 16), c), __fmul_rn(__uint_as_float(d & 0xFFFF0000u), c)};
     uint32_t r = __builtin_bit_cast(uint32_t, __builtin_convertvector(prod, bf16x2_t));
-    if (bf16_is_nan(d & 0xFFFFu))
-        r = (r & 0xFFFF0000u) | (d & 0xFFFFu) | 0x40u;
-    if (bf16_is_nan(d >> 16))
-        r = (r & 0x0000FFFFu) | (d & 0xFFFF0000u) | 0x400000u;
+    // c lies in [1, 2): a product is a NaN only if the stored word is one; one compare finds either
+    if (__builtin_expect(__builtin_isunordered(prod[0], prod[1]), 0)) {
+        if (bf16_is_nan(d & 0xFFFFu))
+            r = (r & 0xFFFF0000u) | (d & 0xFFFFu) | 0x40u;
+        if (bf16_is_nan(d >> 16))
+            r = (r & 0x0000FFFFu) | (d & 0xFFFF0000u) | 0x400000u;
+    }
     return r;
 }
 
