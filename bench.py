@@ -322,13 +322,20 @@ def main():
         def update_fused():
             flags.extend(nz.neuzip_update([bu], [gu], [su], 1e-3))
 
+        def update_ready():
+            # the backward pass has decompressed the weight anyway (for the input gradient): the
+            # library then needs one pass of its encoder over weight and gradient
+            nz.neuzip_decompress(bu, su.view(-1))
+            flags.extend(nz.neuzip_update([bu], [gu], [su], 1e-3, weights_ready=True))
+
         def update_separate():
             nz.neuzip_decompress(bu, su.view(-1))
             su.add_(gu, alpha=-1e-3)
             flags.extend(nz.neuzip_recompress([su], [bu]))
 
         upd = {"elements": wu.numel(), "lr": 1e-3}
-        for name, fn in (("one_call", update_fused), ("decompress_torch_step_recompress", update_separate)):
+        for name, fn in (("one_call", update_fused), ("decompress_then_one_call_with_weights_ready", update_ready),
+                         ("decompress_torch_step_recompress", update_separate)):
             for _ in range(3):
                 fn()
             del flags[:]

@@ -173,21 +173,25 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
  *   d_grads     host array of count device pointers: the gradient of each weight, bf16 words,
  *               neuzip_elems(blobs[i]) of them, 16-byte aligned (read only).
  *   d_weights   host array of count device pointers, 16-byte aligned: temporary space of
- *               neuzip_elems(blobs[i]) bf16 words each, not overlapping one another; on return it
- *               holds the new weights uncompressed (the caller may use or discard them).
- *               d_weights[i] may be d_grads[i] itself: the gradient is then overwritten in place.
+ *               neuzip_elems(blobs[i]) bf16 words each, overlapping neither one another nor the
+ *               gradients; on return it holds the new weights uncompressed (the caller may use
+ *               or discard them).
  *   lr          learning rate.
+ *   weights_ready  0: the library decompresses blobs[i] into d_weights[i] first.  Non-zero:
+ *               d_weights[i] already holds exactly decompress(blobs[i]) -- the backward pass has
+ *               just decompressed the weight for the input gradient -- and that pass is skipped.
  *   rebuilt     as for neuzip_recompress; may be NULL.
  * Reading taken for the arithmetic, which the paper leaves open: per element, in IEEE binary32,
  * the product lr * g and then the difference w - (lr * g) are each rounded to nearest (no fused
  * multiply-add), and the result is rounded to the nearest bf16, ties to even; a NaN result is
- * stored as 0x7FC0.  Two passes: the decoder applies the step on its way out (the old weight is
- * never written), then the new weight is coded with the table the blob holds, exactly as
- * neuzip_recompress does -- including its fallback to fresh statistics.  Synchronises the stream
- * once per group of up to 8 weights.
+ * stored as 0x7FC0.  With weights_ready = 0 the decoder applies the step on its way out (the old
+ * weight is never written) and the new weight is then coded as by neuzip_recompress; otherwise the
+ * one-pass encoder of neuzip_recompress reads weight and gradient, forms the new weight, writes it
+ * back to d_weights and codes it.  Either way the table the blob holds is used, with the fallback
+ * to fresh statistics.  Synchronises the stream once per group of up to 8 weights.
  */
 int neuzip_update(neuzip_blob *const *blobs, const void *const *d_grads, void *const *d_weights, uint32_t count,
-                  float lr, void *hip_stream, uint32_t *rebuilt);
+                  float lr, int weights_ready, void *hip_stream, uint32_t *rebuilt);
 
 /*
  * neuzip_decompress -- Sec. 2.2 Eq. (3), Alg. 1 "decompression" + "merge":

@@ -41,7 +41,7 @@ def _load():
     lib.neuzip_compress_guarded.restype = i32
     lib.neuzip_recompress.argtypes = [vpp, u32, vp, vpp, ctypes.POINTER(u32)]
     lib.neuzip_recompress.restype = i32
-    lib.neuzip_update.argtypes = [vpp, vpp, vpp, u32, ctypes.c_float, vp, ctypes.POINTER(u32)]
+    lib.neuzip_update.argtypes = [vpp, vpp, vpp, u32, ctypes.c_float, i32, vp, ctypes.POINTER(u32)]
     lib.neuzip_update.restype = i32
     lib.neuzip_linear.argtypes = [vp, u64, u64, vp, u32, vp, vp, vp]
     lib.neuzip_linear.restype = i32
@@ -210,9 +210,9 @@ def neuzip_recompress(srcs, blobs, stream=None):
     return [int(v) for v in rebuilt]
 
 
-def neuzip_update(blobs, grads, weights, lr: float, stream=None):
-    """blobs[i] <- compress(decompress(blobs[i]) - lr * grads[i]); weights[i] receives the new weight.
-    Returns the list of rebuilt flags."""
+def neuzip_update(blobs, grads, weights, lr: float, weights_ready: bool = False, stream=None):
+    """blobs[i] <- compress(decompress(blobs[i]) - lr * grads[i]); weights[i] receives the new weight
+    (with weights_ready it must already hold decompress(blobs[i])).  Returns the list of rebuilt flags."""
     for t in list(grads) + list(weights):
         _check_tensor(t)
     if not (len(blobs) == len(grads) == len(weights)) or any(
@@ -223,7 +223,7 @@ def neuzip_update(blobs, grads, weights, lr: float, stream=None):
     gptrs = (ctypes.c_void_p * count)(*[g.data_ptr() for g in grads])
     wptrs = (ctypes.c_void_p * count)(*[w.data_ptr() for w in weights])
     rebuilt = (ctypes.c_uint32 * count)()
-    rc = _lib.neuzip_update(handles, gptrs, wptrs, count, lr, _stream_handle(stream), rebuilt)
+    rc = _lib.neuzip_update(handles, gptrs, wptrs, count, lr, 1 if weights_ready else 0, _stream_handle(stream), rebuilt)
     if rc != OK:
         raise NeuzipError(rc, "neuzip_update")
     return [int(v) for v in rebuilt]

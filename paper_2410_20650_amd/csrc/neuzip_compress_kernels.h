@@ -572,6 +572,38 @@ __global__ __launch_bounds__(256) void table_reuse_kernel(const CompressBatch b,
         stale[blockIdx.x] = 0;
 }
 
+// The weight update of the backward loop (Alg. 1: W_hat <- W_hat - lr * grad) on the two halves of
+// a merged dword: product and difference each rounded to binary32 (no fused multiply-add), the
+// result rounded to the nearest-even bf16, a NaN result stored as 0x7FC0.
+__device__ __forceinline__ float sgd_step(float w, float g, float lr)
+{
+#pragma clang fp contract(off)
+    const float step = lr * g;
+    return w - step;
+}
+
+__device__ __forceinline__ uint32_t update_pair(uint32_t w, uint32_t g, float lr)
+{
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
+    const f32x2_t v = {sgd_step(__uint_as_float(w << 16), __uint_as_float(g << 16), lr),
+                       sgd_step(__uint_as_float(w & 0xFFFF0000u), __uint_as_float(g & 0xFFFF0000u), lr)};
+    uint32_t r = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+    if (__builtin_expect(__builtin_isunordered(v[0], v[1]), 0)) {  // one compare finds a NaN in either half
+        if (v[0] != v[0])
+            r = (r & 0xFFFF0000u) | 0x7FC0u;
+        if (v[1] != v[1])
+            r = (r & 0x0000FFFFu) | 0x7FC00000u;
+    }
+    return r;
+}
+
+__device__ __forceinline__ uint32_t update_word(uint32_t w, uint32_t g, float lr)
+{
+    const float v = sgd_step(__uint_as_float(w << 16), __uint_as_float(g << 16), lr);
+    return v != v ? 0x7FC0u : bf16_of(v);
+}
+
 // ------------------------------------------------------------------------------------------
 // Kernel 3: chunked rANS encoder (Sec. 2.2 "Compression algorithm").  One lane per state.
 // A state visits its symbols back to front; the words it pushes out are collected, back to
@@ -632,7 +664,10 @@ __device__ __forceinline__ void ring_flush(uint32_t wp_before, uint32_t wp_after
 // (SPLIT = mantissa bits) of the words it codes, and it reports, through stale[item], any exponent
 // that the table has no room for (such symbols leave the state unchanged; the host then falls
 // back to a compression with fresh statistics).
-template <bool NORM, int SPLIT, bool WIDE = false, bool HALF = false>
+// UPD (with SPLIT = 7): the backward loop's weight step fused in.  The source holds the decompressed
+// weight, `grad` its gradient; the kernel forms W - lr * grad, writes it back over the source and
+// codes it, so the new weight is read once and never re-read from memory.
+template <bool NORM, int SPLIT, bool WIDE = false, bool HALF = false, bool UPD = false>
 __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch b,
                                                             const EncSym *__restrict__ enc_all,
                                                             uint32_t *__restrict__ chunk_words_all,
@@ -644,11 +679,14 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     static_assert(!(NORM && SPLIT >= 0), "the one-pass variant has no block maxima to normalise with");
     static_assert(!(WIDE || HALF) || (!NORM && (SPLIT < 0 || SPLIT == 7)), "binary32 and binary16 tensors are lossless only");
     static_assert(!(WIDE && HALF), "one element type");
+    static_assert(!UPD || (SPLIT == 7 && !NORM && !WIDE && !HALF), "only lossless bf16 weights are trained");
     constexpr int KB = SPLIT >= 0 ? SPLIT : 7;
     const ItemSlot slot_id = item_of_workgroup<&CompressItem::enc_end>(b);
     const CompressItem &it = b.it[slot_id.item];
     const void *__restrict__ src = it.src;
     uint16_t *__restrict__ low = it.low;
+    const uint16_t *__restrict__ grad = it.grad;
+    const float lr = b.lr;
     const uint64_t n = it.n;
     const uint8_t *__restrict__ coef = it.coef;
     const uint32_t block_shift = NORM ? 31u - static_cast<uint32_t>(__clz(static_cast<int>(it.block | 1u))) : 0u;
@@ -693,11 +731,30 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
         SourceVec<WIDE> d, d_next;
         d.load(src4, (kTurns - 1) * kStates);
         d_next.load(src4, (kTurns - 2) * kStates);
+        // the gradients travel with the weights, one 128-bit piece per turn
+        const uint4 *grad4 = UPD ? reinterpret_cast<const uint4 *>(grad) + (base / 8 + j) : nullptr;
+        uint4 g = make_uint4(0, 0, 0, 0), g_next = g;
+        if constexpr (UPD) {
+            g = grad4[(kTurns - 1) * kStates];
+            g_next = grad4[(kTurns - 2) * kStates];
+        }
         for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
             SourceVec<WIDE> d_after;
             d_after.load(src4, (q > 1 ? q - 2 : 0) * kStates);
+            uint4 g_after = g;
+            if constexpr (UPD)
+                g_after = grad4[(q > 1 ? q - 2 : 0) * kStates];
             uint32_t w[4];
             d.words(w);
+            if constexpr (UPD) {
+                w[0] = update_pair(w[0], g.x, lr);
+                w[1] = update_pair(w[1], g.y, lr);
+                w[2] = update_pair(w[2], g.z, lr);
+                w[3] = update_pair(w[3], g.w, lr);
+                // the new weight replaces the old one in the caller's buffer (same lane, same place)
+                reinterpret_cast<uint4 *>(const_cast<void *>(src))[base / 8 + static_cast<uint32_t>(q) * kStates + j] =
+                    make_uint4(w[0], w[1], w[2], w[3]);
+            }
             const uint32_t wp_before = st.wp;
             if constexpr (SPLIT >= 0) {
                 store_fields<KB>(sm, base / 8 + static_cast<uint32_t>(q) * kStates + j, fields_of<KB, HALF>(w));
@@ -721,6 +778,10 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
             ring_flush(wp_before, st.wp, ring, chunk_slots, j);
             d = d_next;
             d_next = d_after;
+            if constexpr (UPD) {
+                g = g_next;
+                g_next = g_after;
+            }
         }
     } else if (m > 0) {
         for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
@@ -730,6 +791,10 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
                 const uint32_t i = static_cast<uint32_t>(q) * kTurn + j * kRun + static_cast<uint32_t>(t);
                 if (i < m) {
                     uint32_t u = source_word<WIDE, (SPLIT >= 0)>(src, low, base + i);
+                    if constexpr (UPD) {
+                        u = update_word(u, grad[base + i], lr);
+                        static_cast<uint16_t *>(const_cast<void *>(src))[base + i] = static_cast<uint16_t>(u);
+                    }
                     if constexpr (NORM)
                         u = normalise_word(u, coefficient(coef[(base + i) >> block_shift]));
                     const EncSym e = enc[symbol_of<HALF>(u)];

@@ -138,38 +138,6 @@ __device__ __forceinline__ uint32_t denormalise_pair(uint32_t d, float c)
     return r;
 }
 
-// The weight update of the backward loop (Alg. 1: W_hat <- W_hat - lr * grad) on the two halves of
-// a merged dword: product and difference each rounded to binary32 (no fused multiply-add), the
-// result rounded to the nearest-even bf16, a NaN result stored as 0x7FC0.
-__device__ __forceinline__ float sgd_step(float w, float g, float lr)
-{
-#pragma clang fp contract(off)
-    const float step = lr * g;
-    return w - step;
-}
-
-__device__ __forceinline__ uint32_t update_pair(uint32_t w, uint32_t g, float lr)
-{
-    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
-    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
-    const f32x2_t v = {sgd_step(__uint_as_float(w << 16), __uint_as_float(g << 16), lr),
-                       sgd_step(__uint_as_float(w & 0xFFFF0000u), __uint_as_float(g & 0xFFFF0000u), lr)};
-    uint32_t r = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-    if (__builtin_expect(__builtin_isunordered(v[0], v[1]), 0)) {  // one compare finds a NaN in either half
-        if (v[0] != v[0])
-            r = (r & 0xFFFF0000u) | 0x7FC0u;
-        if (v[1] != v[1])
-            r = (r & 0x0000FFFFu) | 0x7FC00000u;
-    }
-    return r;
-}
-
-__device__ __forceinline__ uint32_t update_word(uint32_t w, uint32_t g, float lr)
-{
-    const float v = sgd_step(__uint_as_float(w << 16), __uint_as_float(g << 16), lr);
-    return v != v ? 0x7FC0u : bf16_of(v);
-}
-
 // UPD: the words written are the decoded weights after the update with the gradient `grad` (bf16
 // words, same indexing as the output) and the rate lr.  HALF: the tensor is binary16.
 template <int KB, bool LONE, bool NORM, bool STREAM, bool UPD, bool HALF, class WordSrc>

@@ -82,6 +82,7 @@ struct CompressItem {
     uint8_t *sm;
     uint8_t *coef;
     uint16_t *low;         // binary32 tensors: the plane of lower halves
+    const uint16_t *grad;  // weight step fused into the encoder: the gradient (src is then written too)
     uint16_t *words;       // known only after the stream length has been read back
     uint32_t n_chunks;
     uint32_t block;        // 0: no block-wise normalisation
@@ -96,6 +97,7 @@ struct CompressBatch {
     CompressItem it[kBatchMax];
     uint32_t count;
     uint32_t seq;  // stamp of this call
+    float lr;      // learning rate of the fused weight step
 };
 
 // Host-visible results of one compress call (pinned host memory the kernels write directly).

@@ -51,7 +51,8 @@ class CompressedLinear:
         torch.matmul(grad_y.t(), x, out=grad_w)                           # out_features x in_features, bf16
         if self.bias is not None:
             self.bias -= lr * grad_y.float().sum(dim=0)
-        (rebuilt,) = nz.neuzip_update([self.blob], [grad_w.view(-1)], [space.view(-1)[:n]], lr)
+        # `space` still holds W_hat from the decompression above: the step and the coding are one pass
+        (rebuilt,) = nz.neuzip_update([self.blob], [grad_w.view(-1)], [space.view(-1)[:n]], lr, weights_ready=True)
         return grad_x, rebuilt
 
 

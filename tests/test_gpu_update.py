@@ -33,11 +33,14 @@ def same_container(got, want, what):
                              f"({got.size} vs {want.size} bytes)")
 
 
-def one_step(nz, blob, container, g, lr, what, in_place=False):
-    """Runs the step on the GPU and in the oracle; returns the oracle's new container."""
+def one_step(nz, blob, container, g, lr, what, ready=False):
+    """Runs the step on the GPU and in the oracle; returns the oracle's new container.  ready: the
+    caller decompresses the weight itself and hands it over, as the backward pass does."""
     want_container, want_rebuilt, want_words = U.training_step(container, inputs.bits(g), lr, threads=8)
-    space = g.clone() if in_place else torch.full_like(g, float("nan"))
-    (rebuilt,) = nz.neuzip_update([blob], [space if in_place else g], [space], lr)
+    space = torch.full_like(g, float("nan"))
+    if ready:
+        nz.neuzip_decompress(blob, space)
+    (rebuilt,) = nz.neuzip_update([blob], [g], [space], lr, weights_ready=ready)
     assert np.array_equal(inputs.bits(space), want_words), f"{what}: new weights"
     assert rebuilt == want_rebuilt, what
     same_container(nz.neuzip_export(blob), want_container, what)
@@ -55,7 +58,7 @@ def test_update_matches_the_oracle_over_several_steps(nz, n):
     container = O.compress(inputs.bits(w), 7, threads=8, guard=8)
     for step, lr in enumerate((1e-3, 3e-4, 1e-3)):
         g = inputs.gaussian_bf16(n, 10_100 + 7 * step + n % 13, std=0.05, device=DEV)
-        container = one_step(nz, blob, container, g, lr, f"n={n} step {step}", in_place=(step == 1))
+        container = one_step(nz, blob, container, g, lr, f"n={n} step {step}", ready=(step == 1))
 
 
 @pytest.mark.parametrize("lr", [0.0, 1e-2, -3.0, 1e-30, 3e38, float("inf")])
@@ -65,7 +68,7 @@ def test_update_on_every_weight_pattern(nz, lr):
     blob = nz.neuzip_compress(w, 7)
     container = O.compress(inputs.bits(w), 7)
     g = inputs.random_bits_bf16(65536, 10_200, device=DEV)
-    one_step(nz, blob, container, g, lr, f"lr={lr}")
+    one_step(nz, blob, container, g, lr, f"lr={lr}", ready=True)
     # and every pattern as the gradient of ordinary weights
     w2 = inputs.gaussian_bf16(65536, 10_201, device=DEV)
     (blob2,) = nz.neuzip_compress_guarded([w2], 7, 4)
@@ -132,15 +135,16 @@ def test_update_argument_errors(nz):
     wide = nz.neuzip_compress(w.float(), 7)
     lib = nz.library()
     one = lambda h: (ctypes.c_void_p * 1)(h)
-    call = lambda handle, gp, wp: lib.neuzip_update(one(handle), one(gp), one(wp), 1, 1e-3, None, None)
+    call = lambda handle, gp, wp: lib.neuzip_update(one(handle), one(gp), one(wp), 1, 1e-3, 0, None, None)
     assert call(wide.handle.value, g.data_ptr(), s.data_ptr()) == nz.EUNSUPPORTED
     assert call(blob.handle.value, g.data_ptr() + 2, s.data_ptr()) == nz.EINVAL      # misaligned gradient
     assert call(blob.handle.value, g.data_ptr(), None) == nz.EINVAL
+    assert call(blob.handle.value, g.data_ptr(), g.data_ptr()) == nz.EINVAL          # the step cannot run over its own gradient
     assert call(None, g.data_ptr(), s.data_ptr()) == nz.EINVAL
     two = (ctypes.c_void_p * 2)(blob.handle.value, blob.handle.value)
     gp = (ctypes.c_void_p * 2)(g.data_ptr(), g.data_ptr())
     wp = (ctypes.c_void_p * 2)(s.data_ptr(), s.data_ptr())
-    assert lib.neuzip_update(two, gp, wp, 2, 1e-3, None, None) == nz.EINVAL          # one blob twice
+    assert lib.neuzip_update(two, gp, wp, 2, 1e-3, 0, None, None) == nz.EINVAL          # one blob twice
     with pytest.raises(ValueError):
         nz.neuzip_update([blob], [g[:100].contiguous()], [s], 1e-3)
     assert np.array_equal(nz.neuzip_export(blob), before)                            # untouched by the failed calls
