@@ -771,7 +771,6 @@ def test_update_closed_cases_from_golden_file():
 def test_update_matches_exact_rational_arithmetic():
     from fractions import Fraction
     from oracle import update as U
-    rng = np.random.default_rng(101)
     w = inputs.bits(inputs.gaussian_bf16(400, seed=102))
     g = inputs.bits(inputs.gaussian_bf16(400, seed=103, std=1.0))
     as_real = lambda u: Fraction(float((np.uint32(u) << 16).view(np.float32)))
@@ -783,7 +782,6 @@ def test_update_matches_exact_rational_arithmetic():
             new = _round_nearest_even(as_real(w[i]) - step, 24)             # the difference, rounded to binary32
             want = _round_nearest_even(new, 8)                              # to bf16
             assert as_real(got[i]) == want, (i, lr)
-    assert rng is not None
 
 
 def test_update_against_torch_and_invariants():

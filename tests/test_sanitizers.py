@@ -6,7 +6,6 @@ ragged sizes, every mantissa width and a damaged container.
 """
 import os
 import subprocess
-import sys
 import textwrap
 
 import pytest
