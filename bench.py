@@ -159,11 +159,14 @@ def main():
         cores = min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "16") or 16))
         words = inputs.bits(w)
         container = nz.neuzip_export(blob)
-        best = float("inf")
-        for _ in range(3):
+        # about ten seconds of oracle work: repeated whole-tensor passes, the median is reported
+        times, spent = [], 0.0
+        while len(times) < 3 or (spent < 10.0 and len(times) < 200):
             t0 = time.perf_counter()
             back = O.decompress(container, n, threads=cores)
-            best = min(best, time.perf_counter() - t0)
+            times.append(time.perf_counter() - t0)
+            spent += times[-1]
+        best = sorted(times)[len(times) // 2]
         assert np.array_equal(back, words), "oracle and GPU disagree"
         t0 = time.perf_counter()
         theirs = O.compress(words, 7, threads=cores)
@@ -172,8 +175,8 @@ def main():
         result["cpu_baseline"] = {"value": round(out_bytes / best / 1e9, 3), "unit": "GB/s", "cores": cores,
                                   "kind": "oracle",
                                   "sample": "the whole config-2 tensor (58.7M elements), oracle decompress of "
-                                            "the GPU-written container, best of 3; containers compared "
-                                            "byte for byte",
+                                            "the GPU-written container, median of %d passes (%.1f s); "
+                                            "containers compared byte for byte" % (len(times), spent),
                                   "compress_GBps_input": round(out_bytes / enc_s / 1e9, 3)}
         del words, container, back, theirs
 
