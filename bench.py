@@ -331,6 +331,11 @@ def main():
             nz.neuzip_decompress(bu, su.view(-1))
             flags.extend(nz.neuzip_update([bu], [gu], [su], 1e-3, weights_ready=True))
 
+        def update_ready_discard():
+            # ... and nobody needs the new weight uncompressed: it is not written back
+            nz.neuzip_decompress(bu, su.view(-1))
+            flags.extend(nz.neuzip_update([bu], [gu], [su], 1e-3, weights_ready=2))
+
         def update_separate():
             nz.neuzip_decompress(bu, su.view(-1))
             su.add_(gu, alpha=-1e-3)
@@ -338,6 +343,7 @@ def main():
 
         upd = {"elements": wu.numel(), "lr": 1e-3}
         for name, fn in (("one_call", update_fused), ("decompress_then_one_call_with_weights_ready", update_ready),
+                         ("decompress_then_one_call_new_weights_not_kept", update_ready_discard),
                          ("decompress_torch_step_recompress", update_separate)):
             for _ in range(3):
                 fn()

@@ -175,11 +175,15 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
  *   d_weights   host array of count device pointers, 16-byte aligned: temporary space of
  *               neuzip_elems(blobs[i]) bf16 words each, overlapping neither one another nor the
  *               gradients; on return it holds the new weights uncompressed (the caller may use
- *               or discard them).
+ *               or discard them; but see weights_ready = 2).
  *   lr          learning rate.
- *   weights_ready  0: the library decompresses blobs[i] into d_weights[i] first.  Non-zero:
- *               d_weights[i] already holds exactly decompress(blobs[i]) -- the backward pass has
- *               just decompressed the weight for the input gradient -- and that pass is skipped.
+ *   weights_ready  NEUZIP_UPDATE_FROM_BLOB (0): the library decompresses blobs[i] itself.
+ *               NEUZIP_UPDATE_WEIGHTS_READY (1): d_weights[i] already holds exactly
+ *               decompress(blobs[i]) -- the backward pass has just decompressed the weight for the
+ *               input gradient -- and that pass is skipped.  NEUZIP_UPDATE_WEIGHTS_READY_DISCARD (2):
+ *               the same, and the caller has no use for the new weights uncompressed: they are
+ *               not written back (a third less memory traffic), and d_weights[i] afterwards holds
+ *               the old weight, or the new one for a tensor whose table was rebuilt.
  *   rebuilt     as for neuzip_recompress; may be NULL.
  * Reading taken for the arithmetic, which the paper leaves open: per element, in IEEE binary32,
  * the product lr * g and then the difference w - (lr * g) are each rounded to nearest (no fused
@@ -190,6 +194,7 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
  * back to d_weights and codes it.  Either way the table the blob holds is used, with the fallback
  * to fresh statistics.  Synchronises the stream once per group of up to 8 weights.
  */
+enum { NEUZIP_UPDATE_FROM_BLOB = 0, NEUZIP_UPDATE_WEIGHTS_READY = 1, NEUZIP_UPDATE_WEIGHTS_READY_DISCARD = 2 };
 int neuzip_update(neuzip_blob *const *blobs, const void *const *d_grads, void *const *d_weights, uint32_t count,
                   float lr, int weights_ready, void *hip_stream, uint32_t *rebuilt);
 

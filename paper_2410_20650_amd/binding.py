@@ -210,9 +210,11 @@ def neuzip_recompress(srcs, blobs, stream=None):
     return [int(v) for v in rebuilt]
 
 
-def neuzip_update(blobs, grads, weights, lr: float, weights_ready: bool = False, stream=None):
-    """blobs[i] <- compress(decompress(blobs[i]) - lr * grads[i]); weights[i] receives the new weight
-    (with weights_ready it must already hold decompress(blobs[i])).  Returns the list of rebuilt flags."""
+def neuzip_update(blobs, grads, weights, lr: float, weights_ready=False, stream=None):
+    """blobs[i] <- compress(decompress(blobs[i]) - lr * grads[i]); weights[i] receives the new weight.
+    weights_ready: False / 0 -- the library decompresses; True / 1 -- weights[i] already holds
+    decompress(blobs[i]); 2 -- the same, and the new weights are not written back.  Returns the list
+    of rebuilt flags."""
     for t in list(grads) + list(weights):
         _check_tensor(t)
     if not (len(blobs) == len(grads) == len(weights)) or any(
@@ -223,7 +225,7 @@ def neuzip_update(blobs, grads, weights, lr: float, weights_ready: bool = False,
     gptrs = (ctypes.c_void_p * count)(*[g.data_ptr() for g in grads])
     wptrs = (ctypes.c_void_p * count)(*[w.data_ptr() for w in weights])
     rebuilt = (ctypes.c_uint32 * count)()
-    rc = _lib.neuzip_update(handles, gptrs, wptrs, count, lr, 1 if weights_ready else 0, _stream_handle(stream), rebuilt)
+    rc = _lib.neuzip_update(handles, gptrs, wptrs, count, lr, int(weights_ready), _stream_handle(stream), rebuilt)
     if rc != OK:
         raise NeuzipError(rc, "neuzip_update")
     return [int(v) for v in rebuilt]

@@ -502,10 +502,11 @@ void launch_encode_reuse(const CompressBatch &batch, uint32_t groups, hipStream_
 // guard band).  reuse = true: every blob holds a table already and the tensors are coded with
 // those, in one pass over the source; rebuilt[i] is set for the tensors whose table turned out
 // not to cover them, which are then compressed the first way.  d_grads (with reuse, lossless bf16
-// only): the sources are weights that first take the step W - lr * grad, in place, in that same pass.
+// only): the sources are weights that first take the step W - lr * grad in that same pass; the new
+// weights replace them if keep_new is set (else only those of rebuilt tensors do).
 int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int k, uint32_t block, int elem,
                   uint32_t guard, bool reuse, uint32_t *rebuilt, hipStream_t stream, neuzip_blob **blobs,
-                  const void *const *d_grads = nullptr, float lr = 0.0f)
+                  const void *const *d_grads = nullptr, float lr = 0.0f, bool keep_new = true)
 {
     neuzip_blob *work[kBatchMax];
     bool fresh[kBatchMax];
@@ -548,6 +549,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
     std::memset(&batch, 0, sizeof(batch));
     uint32_t owner[kBatchMax];
     const void *stale_src[kBatchMax];
+    const void *stale_grad[kBatchMax];
     uint64_t stale_n[kBatchMax];
     neuzip_blob *stale_blob[kBatchMax];
     uint32_t stale_owner[kBatchMax];
@@ -597,6 +599,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             return fail(rc);
         batch.seq = ++g_ws.seq;
         batch.lr = lr;
+        batch.keep_new = keep_new ? 1u : 0u;
         touched = true;
 
         if (reuse) {
@@ -679,6 +682,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
                 // its table does not cover the new values: nothing of this pass is kept (the
                 // compaction skips a tensor without chunks); it is compressed afresh below
                 stale_src[n_stale] = d_srcs[owner[j]];
+                stale_grad[n_stale] = d_grads ? d_grads[owner[j]] : nullptr;
                 stale_n[n_stale] = n_elems[owner[j]];
                 stale_blob[n_stale] = b;
                 stale_owner[n_stale++] = owner[j];
@@ -707,6 +711,18 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         stale_count = n_stale;
     }
     if (stale_count > 0) {
+        // a fused weight step that did not write the new weights back: form them now, in place
+        if (d_grads && !keep_new) {
+            for (uint32_t j = 0; j < stale_count; ++j) {
+                const uint64_t vecs = (stale_n[j] + 7) / 8;
+                const uint32_t wgs = static_cast<uint32_t>(vecs / 256 + 1 < 4096 ? vecs / 256 + 1 : 4096);
+                hipLaunchKernelGGL(sgd_update_kernel, dim3(wgs), dim3(256), 0, stream,
+                                   static_cast<uint16_t *>(const_cast<void *>(stale_src[j])),
+                                   static_cast<const uint16_t *>(stale_grad[j]), stale_n[j], lr);
+            }
+            if (!hip_ok(hipGetLastError()))
+                return NEUZIP_EHIP;
+        }
         // same stream, so the pass above has finished with the workspace before this one starts
         const int rc = compress_some(stale_src, stale_n, stale_count, k, block, elem, kKeepGuard, false, nullptr, stream,
                                      stale_blob);
@@ -811,7 +827,7 @@ int neuzip_update(neuzip_blob *const *blobs, const void *const *d_grads, void *c
 {
     if (count == 0)
         return NEUZIP_OK;
-    if (!blobs || !d_grads || !d_weights)
+    if (!blobs || !d_grads || !d_weights || weights_ready < 0 || weights_ready > 2)
         return NEUZIP_EINVAL;
     for (uint32_t i = 0; i < count; ++i) {
         const neuzip_blob *b = blobs[i];
@@ -879,7 +895,7 @@ int neuzip_update(neuzip_blob *const *blobs, const void *const *d_grads, void *c
         }
         const int rc = compress_some(d_weights + first, n_elems, m, 7, 0, NEUZIP_BF16, kKeepGuard, true,
                                      rebuilt ? rebuilt + first : nullptr, stream, group,
-                                     weights_ready ? d_grads + first : nullptr, lr);
+                                     weights_ready ? d_grads + first : nullptr, lr, weights_ready != 2);
         if (rc != NEUZIP_OK)
             return rc;
     }

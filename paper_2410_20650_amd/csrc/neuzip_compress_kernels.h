@@ -604,6 +604,25 @@ __device__ __forceinline__ uint32_t update_word(uint32_t w, uint32_t g, float lr
     return v != v ? 0x7FC0u : bf16_of(v);
 }
 
+// The weight step alone, in place: w <- w - lr * g over n bf16 words (for the rare tensor whose
+// kept table did not serve after a fused step that was asked not to write the new weight back).
+__global__ __launch_bounds__(256) void sgd_update_kernel(uint16_t *__restrict__ w, const uint16_t *__restrict__ g,
+                                                         uint64_t n, float lr)
+{
+    const uint64_t n_vec = n / 8;
+    uint4 *w4 = reinterpret_cast<uint4 *>(w);
+    const uint4 *g4 = reinterpret_cast<const uint4 *>(g);
+    for (uint64_t v = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; v < n_vec;
+         v += static_cast<uint64_t>(gridDim.x) * blockDim.x) {
+        const uint4 a = w4[v], c = g4[v];
+        w4[v] = make_uint4(update_pair(a.x, c.x, lr), update_pair(a.y, c.y, lr), update_pair(a.z, c.z, lr),
+                           update_pair(a.w, c.w, lr));
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        for (uint64_t i = n_vec * 8; i < n; ++i)
+            w[i] = static_cast<uint16_t>(update_word(w[i], g[i], lr));
+}
+
 // ------------------------------------------------------------------------------------------
 // Kernel 3: chunked rANS encoder (Sec. 2.2 "Compression algorithm").  One lane per state.
 // A state visits its symbols back to front; the words it pushes out are collected, back to
@@ -751,9 +770,11 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
                 w[1] = update_pair(w[1], g.y, lr);
                 w[2] = update_pair(w[2], g.z, lr);
                 w[3] = update_pair(w[3], g.w, lr);
-                // the new weight replaces the old one in the caller's buffer (same lane, same place)
-                reinterpret_cast<uint4 *>(const_cast<void *>(src))[base / 8 + static_cast<uint32_t>(q) * kStates + j] =
-                    make_uint4(w[0], w[1], w[2], w[3]);
+                // if the caller wants it, the new weight replaces the old one in its buffer (same lane,
+                // same place)
+                if (b.keep_new)
+                    reinterpret_cast<uint4 *>(const_cast<void *>(src))[base / 8 + static_cast<uint32_t>(q) * kStates + j] =
+                        make_uint4(w[0], w[1], w[2], w[3]);
             }
             const uint32_t wp_before = st.wp;
             if constexpr (SPLIT >= 0) {
@@ -793,7 +814,8 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
                     uint32_t u = source_word<WIDE, (SPLIT >= 0)>(src, low, base + i);
                     if constexpr (UPD) {
                         u = update_word(u, grad[base + i], lr);
-                        static_cast<uint16_t *>(const_cast<void *>(src))[base + i] = static_cast<uint16_t>(u);
+                        if (b.keep_new)
+                            static_cast<uint16_t *>(const_cast<void *>(src))[base + i] = static_cast<uint16_t>(u);
                     }
                     if constexpr (NORM)
                         u = normalise_word(u, coefficient(coef[(base + i) >> block_shift]));

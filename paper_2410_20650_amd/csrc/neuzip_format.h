@@ -98,6 +98,7 @@ struct CompressBatch {
     uint32_t count;
     uint32_t seq;  // stamp of this call
     float lr;      // learning rate of the fused weight step
+    uint32_t keep_new;  // fused weight step: write the new weight back over the source
 };
 
 // Host-visible results of one compress call (pinned host memory the kernels write directly).

@@ -42,8 +42,8 @@ class CompressedLinear:
                             grad_space: torch.Tensor):
         """The layer's part of the backward loop.  x: the input the forward pass saw (bf16), grad_y: the
         gradient of the loss with respect to the layer's output (bf16), both tokens x features.
-        Returns (grad_x, rebuilt flag); the blob holds the updated weight afterwards, `space` its
-        uncompressed form and `grad_space` the weight gradient that was applied (bf16)."""
+        Returns (grad_x, rebuilt flag); the blob holds the updated weight afterwards and `grad_space`
+        the weight gradient that was applied (bf16); what `space` holds is unspecified."""
         w_hat = self.weight_into(space)                                   # the second decompression
         grad_x = torch.matmul(grad_y, w_hat)                              # tokens x in_features
         n = self.out_features * self.in_features
@@ -51,8 +51,9 @@ class CompressedLinear:
         torch.matmul(grad_y.t(), x, out=grad_w)                           # out_features x in_features, bf16
         if self.bias is not None:
             self.bias -= lr * grad_y.float().sum(dim=0)
-        # `space` still holds W_hat from the decompression above: the step and the coding are one pass
-        (rebuilt,) = nz.neuzip_update([self.blob], [grad_w.view(-1)], [space.view(-1)[:n]], lr, weights_ready=True)
+        # `space` still holds W_hat from the decompression above: the step and the coding are one pass,
+        # and nobody needs the new weight uncompressed
+        (rebuilt,) = nz.neuzip_update([self.blob], [grad_w.view(-1)], [space.view(-1)[:n]], lr, weights_ready=2)
         return grad_x, rebuilt
 
 

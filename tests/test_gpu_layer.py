@@ -62,7 +62,9 @@ def test_training_steps_follow_alg1(nz, tokens):
             want = as_f64(grad_y).T @ as_f64(layer_input)
             mag = np.abs(as_f64(grad_y)).T @ np.abs(as_f64(layer_input))
             assert np.all(np.abs(as_f64(grad_w) - want) <= 2.0 ** -8 * np.abs(want) + 2.0 ** -18 * mag + 1e-30), i
-            seen[i] = (inputs.bits(grad_w).copy(), nz.neuzip_export(layers[i].blob), inputs.bits(space[: grad_w.numel()]))
+            now = torch.empty(grad_w.numel(), dtype=torch.bfloat16, device=DEV)
+            nz.neuzip_decompress(layers[i].blob, now)
+            seen[i] = (inputs.bits(grad_w).copy(), nz.neuzip_export(layers[i].blob), inputs.bits(now))
 
         loss, flags = layer.training_step(layers, x, target, lr, space, grad_space, observer=observer)
         losses.append(loss)

@@ -33,16 +33,21 @@ def same_container(got, want, what):
                              f"({got.size} vs {want.size} bytes)")
 
 
-def one_step(nz, blob, container, g, lr, what, ready=False):
-    """Runs the step on the GPU and in the oracle; returns the oracle's new container.  ready: the
-    caller decompresses the weight itself and hands it over, as the backward pass does."""
+def one_step(nz, blob, container, g, lr, what, ready=0):
+    """Runs the step on the GPU and in the oracle; returns the oracle's new container.  ready = 1, 2:
+    the caller decompresses the weight itself and hands it over, as the backward pass does; with 2
+    the new weight is not written back."""
     want_container, want_rebuilt, want_words = U.training_step(container, inputs.bits(g), lr, threads=8)
+    old_words = O.decompress(container, g.numel(), threads=8)
     space = torch.full_like(g, float("nan"))
     if ready:
         nz.neuzip_decompress(blob, space)
     (rebuilt,) = nz.neuzip_update([blob], [g], [space], lr, weights_ready=ready)
-    assert np.array_equal(inputs.bits(space), want_words), f"{what}: new weights"
     assert rebuilt == want_rebuilt, what
+    if ready == 2 and not rebuilt:
+        assert np.array_equal(inputs.bits(space), old_words), f"{what}: the buffer was to be left alone"
+    else:
+        assert np.array_equal(inputs.bits(space), want_words), f"{what}: new weights"
     same_container(nz.neuzip_export(blob), want_container, what)
     out = torch.full_like(g, float("nan"))
     nz.neuzip_decompress(blob, out)
@@ -58,7 +63,7 @@ def test_update_matches_the_oracle_over_several_steps(nz, n):
     container = O.compress(inputs.bits(w), 7, threads=8, guard=8)
     for step, lr in enumerate((1e-3, 3e-4, 1e-3)):
         g = inputs.gaussian_bf16(n, 10_100 + 7 * step + n % 13, std=0.05, device=DEV)
-        container = one_step(nz, blob, container, g, lr, f"n={n} step {step}", ready=(step == 1))
+        container = one_step(nz, blob, container, g, lr, f"n={n} step {step}", ready=step)
 
 
 @pytest.mark.parametrize("lr", [0.0, 1e-2, -3.0, 1e-30, 3e38, float("inf")])
@@ -68,14 +73,16 @@ def test_update_on_every_weight_pattern(nz, lr):
     blob = nz.neuzip_compress(w, 7)
     container = O.compress(inputs.bits(w), 7)
     g = inputs.random_bits_bf16(65536, 10_200, device=DEV)
-    one_step(nz, blob, container, g, lr, f"lr={lr}", ready=True)
+    one_step(nz, blob, container, g, lr, f"lr={lr}", ready=1)
     # and every pattern as the gradient of ordinary weights
     w2 = inputs.gaussian_bf16(65536, 10_201, device=DEV)
     (blob2,) = nz.neuzip_compress_guarded([w2], 7, 4)
-    one_step(nz, blob2, O.compress(inputs.bits(w2), 7, guard=4), inputs.all_patterns_bf16(device=DEV), lr, f"grad lr={lr}")
+    one_step(nz, blob2, O.compress(inputs.bits(w2), 7, guard=4), inputs.all_patterns_bf16(device=DEV), lr, f"grad lr={lr}",
+             ready=2)
 
 
-def test_update_a_layer_in_one_call(nz):
+@pytest.mark.parametrize("ready", [0, 1, 2])
+def test_update_a_layer_in_one_call(nz, ready):
     shapes = [(512, 512), (128, 512), (128, 512), (512, 512), (512, 1792), (512, 1792), (1792, 512), (77, 13), (0,),
               (3, 4096)]
     ws = [inputs.gaussian_bf16(s, 10_300 + i, device=DEV) for i, s in enumerate(shapes)]
@@ -86,12 +93,15 @@ def test_update_a_layer_in_one_call(nz):
     gs[4] = inputs.from_bits(g4, DEV).reshape(shapes[4])
     blobs = nz.neuzip_compress_guarded(ws, 7, 8)
     containers = [O.compress(inputs.bits(w), 7, guard=8) for w in ws]
-    spaces = [torch.full_like(w, float("nan")) for w in ws]
-    rebuilt = nz.neuzip_update(blobs, gs, spaces, 1e-3)
+    spaces = [w.clone() if ready else torch.full_like(w, float("nan")) for w in ws]
+    rebuilt = nz.neuzip_update(blobs, gs, spaces, 1e-3, weights_ready=ready)
     assert rebuilt[4] == 1 and sum(rebuilt) < len(rebuilt)
     for i, (b, c, g, s) in enumerate(zip(blobs, containers, gs, spaces)):
         want_container, want_rebuilt, want_words = U.training_step(c, inputs.bits(g), 1e-3)
-        assert np.array_equal(inputs.bits(s), want_words), i
+        if ready == 2 and not rebuilt[i]:
+            assert np.array_equal(inputs.bits(s), inputs.bits(ws[i])), i
+        else:
+            assert np.array_equal(inputs.bits(s), want_words), i
         assert want_rebuilt == rebuilt[i], (i, rebuilt)
         same_container(nz.neuzip_export(b), want_container, f"tensor {i}")
 
@@ -145,6 +155,7 @@ def test_update_argument_errors(nz):
     gp = (ctypes.c_void_p * 2)(g.data_ptr(), g.data_ptr())
     wp = (ctypes.c_void_p * 2)(s.data_ptr(), s.data_ptr())
     assert lib.neuzip_update(two, gp, wp, 2, 1e-3, 0, None, None) == nz.EINVAL          # one blob twice
+    assert lib.neuzip_update(one(blob.handle.value), one(g.data_ptr()), one(s.data_ptr()), 1, 1e-3, 3, None, None) == nz.EINVAL
     with pytest.raises(ValueError):
         nz.neuzip_update([blob], [g[:100].contiguous()], [s], 1e-3)
     assert np.array_equal(nz.neuzip_export(blob), before)                            # untouched by the failed calls
