@@ -161,7 +161,7 @@ def main():
         container = nz.neuzip_export(blob)
         # about ten seconds of oracle work: repeated whole-tensor passes, the median is reported
         times, spent = [], 0.0
-        while len(times) < 3 or (spent < 10.0 and len(times) < 200):
+        while len(times) < 3 or (spent < 10.0 and len(times) < 1000):
             t0 = time.perf_counter()
             back = O.decompress(container, n, threads=cores)
             times.append(time.perf_counter() - t0)
