@@ -70,6 +70,23 @@ def test_ragged_sizes(nz, n, k):
     roundtrip_and_compare(nz, w, k)
 
 
+def test_seeded_random_sizes_and_distributions(nz):
+    # sizes anywhere between one element and a few hundred chunks, value distributions drawn per case
+    rng = np.random.default_rng(7700)
+    for case in range(24):
+        n = int(rng.integers(1, 2 ** int(rng.integers(1, 21))))
+        k = int(rng.choice(KS))
+        kind = case % 3
+        if kind == 0:
+            w = inputs.gaussian_bf16(n, 7701 + case, std=float(10.0 ** rng.uniform(-4, 1)), device=DEV)
+        elif kind == 1:
+            w = inputs.student_t4_bf16(n, 7701 + case, device=DEV)
+        else:
+            w = inputs.random_bits_bf16(n, 7701 + case, device=DEV)
+        block = int(rng.choice([0, 32, 128, 512])) if k != 7 else 0
+        roundtrip_and_compare(nz, w, k, block=block)
+
+
 @pytest.mark.parametrize("k", KS)
 def test_every_bf16_pattern(nz, k):
     w = inputs.all_patterns_bf16(device=DEV)
