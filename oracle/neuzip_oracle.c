@@ -192,8 +192,9 @@ int nzo_quantise(const uint64_t cnt[256], uint16_t freq[256])
  * compresses every weight again after each update; a table kept from the step before must be
  * able to code exponents the update newly produces).  With guard > 0 the symbols "that occur"
  * are taken to be every exponent from (smallest occurring - guard) to (largest occurring +
- * guard), clipped to 0..255: the ones with count 0 get f = 1 by the same max(1, .) rule.
- * guard = 0 is the plain rule.  Not in the paper. */
+ * guard), clipped to 0..255, and symbol 0 as well (the exponent of +-0: an update w - lr * g
+ * cancels exactly now and then, far below every other exponent that occurs): the ones with
+ * count 0 get f = 1 by the same max(1, .) rule.  guard = 0 is the plain rule.  Not in the paper. */
 int nzo_quantise_guarded(const uint64_t cnt[256], uint32_t guard, uint16_t freq[256])
 {
     uint64_t total = 0;
@@ -210,8 +211,8 @@ int nzo_quantise_guarded(const uint64_t cnt[256], uint32_t guard, uint16_t freq[
     int64_t sum = 0;
     for (int s = 0; s < 256; s++) {
         int member = cnt[s] > 0;
-        if (guard > 0 && total > 0 && (int64_t)s >= (int64_t)lo - (int64_t)guard &&
-            (int64_t)s <= (int64_t)hi + (int64_t)guard)
+        if (guard > 0 && total > 0 &&
+            (s == 0 || ((int64_t)s >= (int64_t)lo - (int64_t)guard && (int64_t)s <= (int64_t)hi + (int64_t)guard)))
             member = 1;
         if (!member || total == 0) {
             f[s] = 0;

@@ -25,14 +25,14 @@ def exponent(u):
 
 def quantise(cnt, guard=0):
     """Counts -> integer frequencies summing to M (0 for absent symbols).  With guard > 0 the
-    exponents up to that far outside the occupied range are kept codable (f = 1)."""
+    exponents up to that far outside the occupied range, and exponent 0, are kept codable (f = 1)."""
     total = sum(cnt)
     if total == 0:
         return [0] * 256
     present = [s for s in range(256) if cnt[s]]
     kept = set(present)
     if guard:
-        kept |= set(range(max(0, present[0] - guard), min(255, present[-1] + guard) + 1))
+        kept |= set(range(max(0, present[0] - guard), min(255, present[-1] + guard) + 1)) | {0}
     f = [max(1, cnt[s] * M // total) if s in kept else 0 for s in range(256)]
     rest = M - sum(f)
     if rest > 0:

@@ -492,12 +492,12 @@ def test_blockwise_rejects_lossless_and_odd_blocks():
 # ---------------------------------------------------------------- tables kept across weight updates (Alg. 1 recompresses every step)
 
 def test_guarded_quantise_closed_cases():
-    # one exponent, guard 2: five codable symbols; floors give 4096 + 4 ones, the excess of 4
-    # comes off the only large entry
+    # one exponent, guard 2: five codable symbols in the band plus exponent 0 (an update can cancel to
+    # +-0); floors give 4096 + 5 ones, the excess of 5 comes off the only large entry
     c = np.zeros(256, np.uint64)
     c[120] = 77
     f = O.quantise(c, guard=2)
-    assert {s: int(f[s]) for s in np.nonzero(f)[0]} == {118: 1, 119: 1, 120: 4092, 121: 1, 122: 1}
+    assert {s: int(f[s]) for s in np.nonzero(f)[0]} == {0: 1, 118: 1, 119: 1, 120: 4091, 121: 1, 122: 1}
     # the band is clipped at both ends of the byte range
     c = np.zeros(256, np.uint64)
     c[0] = 5
@@ -506,14 +506,15 @@ def test_guarded_quantise_closed_cases():
     c = np.zeros(256, np.uint64)
     c[255] = 5
     f = O.quantise(c, guard=1)
-    assert list(f[253:]) == [0, 1, 4095]
-    # two equal halves with a hole between them, guard 1: symbols 99..105 are codable, the five
-    # empty ones get 1, and the excess of 5 is taken alternately from the two large entries,
-    # the lower symbol first: 100 gives three units, 104 two
+    assert list(f[253:]) == [0, 1, 4094] and f[0] == 1 and f.sum() == 4096
+    # two equal halves with a hole between them, guard 1: symbols 99..105 and 0 are codable, the six
+    # empty ones get 1, and the excess of 6 is taken alternately from the two large entries,
+    # the lower symbol first: three units each
     c = np.zeros(256, np.uint64)
     c[[100, 104]] = 1000
     f = O.quantise(c, guard=1)
-    assert {s: int(f[s]) for s in np.nonzero(f)[0]} == {99: 1, 100: 2045, 101: 1, 102: 1, 103: 1, 104: 2046, 105: 1}
+    assert {s: int(f[s]) for s in np.nonzero(f)[0]} == {0: 1, 99: 1, 100: 2045, 101: 1, 102: 1, 103: 1, 104: 2045,
+                                                        105: 1}
     # nothing to add when every exponent already occurs
     assert np.all(O.quantise(np.full(256, 9, np.uint64), guard=5) == 16)
     assert O.quantise(np.zeros(256, np.uint64), guard=4).sum() == 0
@@ -534,6 +535,7 @@ def test_guarded_quantise_properties_and_second_implementation():
         want = np.zeros(256, bool)
         if guard:
             want[max(0, present[0] - guard): min(255, present[-1] + guard) + 1] = True
+            want[0] = True
         else:
             want[present] = True
         assert np.array_equal(f > 0, want)
@@ -541,7 +543,7 @@ def test_guarded_quantise_properties_and_second_implementation():
         if guard == 0:
             assert np.array_equal(f, O.quantise(c))
         # the band costs at most its share of the probability mass
-        assert O.cross_entropy(c, f) <= O.cross_entropy(c, O.quantise(c)) + math.log2(4096 / (4096 - 2 * guard - k)) + 1e-9
+        assert O.cross_entropy(c, f) <= O.cross_entropy(c, O.quantise(c)) + math.log2(4096 / (4096 - 2 * guard - k - 1)) + 1e-9
 
 
 @pytest.mark.parametrize("k", [7, 3, 0])
