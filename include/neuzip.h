@@ -142,8 +142,9 @@ int neuzip_compress_batch(const void *const *d_srcs, const uint64_t *n_elems, ui
  *
  *   neuzip_compress_guarded   as neuzip_compress_batch without normalisation, but the table gives
  *       f = 1 to every exponent up to `guard` (0..255) below the smallest and above the largest
- *       one that occurs, so that values an update newly produces still have a code.  guard = 0 is
- *       the plain table.  The guard is kept in the blob and in header word 52 of the container.
+ *       one that occurs, and to exponent 0 (an update w - lr * g cancels exactly to +-0 now and
+ *       then), so that values an update newly produces still have a code.  guard = 0 is the
+ *       plain table.  The guard is kept in the blob and in header word 52 of the container.
  *   neuzip_recompress         blobs[i] (which must hold a compressed tensor) receives d_srcs[i],
  *       a tensor of neuzip_elems(blobs[i]) words, coded with the table the blob already holds:
  *       one pass over the source that splits, packs and encodes.  If a tensor holds an exponent

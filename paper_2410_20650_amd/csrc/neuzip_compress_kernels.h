@@ -454,14 +454,14 @@ __global__ __launch_bounds__(256) void table_kernel(const CompressBatch b, uint3
     uint32_t f = 0;
     if (total > 0) {
         // With a guard band every exponent from (lowest occurring - guard) to (highest occurring +
-        // guard) is treated as occurring: it gets f = 1 and can be coded after a weight update
-        // without a new table.
+        // guard), and exponent 0 (an update cancels exactly to +-0 now and then), is treated as
+        // occurring: it gets f = 1 and can be coded after a weight update without a new table.
         bool member = cnt > 0;
         const uint32_t guard = b.it[blockIdx.x].guard;
         if (guard > 0) {
             const uint32_t hi = static_cast<uint32_t>(block_max_u64(cnt > 0 ? s + 1 : 0, scratch)) - 1;
             const uint32_t lo = 256 - static_cast<uint32_t>(block_max_u64(cnt > 0 ? 256 - s : 0, scratch));
-            member = s + guard >= lo && s <= hi + guard;
+            member = s == 0 || (s + guard >= lo && s <= hi + guard);
         }
         if (member) {
             const uint64_t scaled = cnt * kM / total;

@@ -57,10 +57,10 @@ def test_guard_band_on_every_pattern_and_on_a_single_exponent(nz):
     w = inputs.all_patterns_bf16(device=DEV)
     (blob,) = nz.neuzip_compress_guarded([w], 7, 3)
     same_container(nz.neuzip_export(blob), O.compress(inputs.bits(w), 7, guard=3), "all patterns")
-    c = inputs.constant_bf16(10_000, 0.75, device=DEV)       # one exponent: the band makes it 1 + 2*4 symbols
+    c = inputs.constant_bf16(10_000, 0.75, device=DEV)       # one exponent: the band makes it 1 + 2*4 symbols, + exponent 0
     (blob,) = nz.neuzip_compress_guarded([c], 7, 4)
     f = nz.neuzip_frequencies(blob)
-    assert np.count_nonzero(f) == 9 and f.max() == 4096 - 8
+    assert np.count_nonzero(f) == 10 and f.max() == 4096 - 9 and f[0] == 1
     same_container(nz.neuzip_export(blob), O.compress(inputs.bits(c), 7, guard=4), "single exponent")
     assert np.array_equal(decoded(nz, blob, c), inputs.bits(c))
 
