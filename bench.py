@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
 def parse_args():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=200)
-    p.add_argument("--warmup", type=int, default=20)
+    p.add_argument("--steps", type=int, default=2000)
+    p.add_argument("--warmup", type=int, default=200)
     p.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     p.add_argument("--extended", action="store_true", help="also time config 4 (lossy) and a config-3 sweep")
     p.add_argument("--sweep", action="store_true",
