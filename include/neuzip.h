@@ -185,6 +185,9 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
  *               the same, and the caller has no use for the new weights uncompressed: they are
  *               not written back (a third less memory traffic), and d_weights[i] afterwards holds
  *               the old weight, or the new one for a tensor whose table was rebuilt.
+ *               NEUZIP_UPDATE_FROM_BLOB_DISCARD (3): as 0, but d_weights is mere scratch space
+ *               whose content afterwards is as for 2 (the library decompresses into it and then
+ *               proceeds as for 2, which moves fewer bytes than 0).
  *   rebuilt     as for neuzip_recompress; may be NULL.
  * Reading taken for the arithmetic, which the paper leaves open: per element, in IEEE binary32,
  * the product lr * g and then the difference w - (lr * g) are each rounded to nearest (no fused
@@ -195,7 +198,12 @@ int neuzip_recompress(const void *const *d_srcs, uint32_t count, void *hip_strea
  * back to d_weights and codes it.  Either way the table the blob holds is used, with the fallback
  * to fresh statistics.  Synchronises the stream once per group of up to 8 weights.
  */
-enum { NEUZIP_UPDATE_FROM_BLOB = 0, NEUZIP_UPDATE_WEIGHTS_READY = 1, NEUZIP_UPDATE_WEIGHTS_READY_DISCARD = 2 };
+enum {
+    NEUZIP_UPDATE_FROM_BLOB = 0,
+    NEUZIP_UPDATE_WEIGHTS_READY = 1,
+    NEUZIP_UPDATE_WEIGHTS_READY_DISCARD = 2,
+    NEUZIP_UPDATE_FROM_BLOB_DISCARD = 3
+};
 int neuzip_update(neuzip_blob *const *blobs, const void *const *d_grads, void *const *d_weights, uint32_t count,
                   float lr, int weights_ready, void *hip_stream, uint32_t *rebuilt);
 

@@ -213,8 +213,8 @@ def neuzip_recompress(srcs, blobs, stream=None):
 def neuzip_update(blobs, grads, weights, lr: float, weights_ready=False, stream=None):
     """blobs[i] <- compress(decompress(blobs[i]) - lr * grads[i]); weights[i] receives the new weight.
     weights_ready: False / 0 -- the library decompresses; True / 1 -- weights[i] already holds
-    decompress(blobs[i]); 2 -- the same, and the new weights are not written back.  Returns the list
-    of rebuilt flags."""
+    decompress(blobs[i]); 2 -- the same, and the new weights are not written back; 3 -- the library
+    decompresses and weights[i] is mere scratch space.  Returns the list of rebuilt flags."""
     for t in list(grads) + list(weights):
         _check_tensor(t)
     if not (len(blobs) == len(grads) == len(weights)) or any(

@@ -40,11 +40,11 @@ def one_step(nz, blob, container, g, lr, what, ready=0):
     want_container, want_rebuilt, want_words = U.training_step(container, inputs.bits(g), lr, threads=8)
     old_words = O.decompress(container, g.numel(), threads=8)
     space = torch.full_like(g, float("nan"))
-    if ready:
+    if ready in (1, 2):
         nz.neuzip_decompress(blob, space)
     (rebuilt,) = nz.neuzip_update([blob], [g], [space], lr, weights_ready=ready)
     assert rebuilt == want_rebuilt, what
-    if ready == 2 and not rebuilt:
+    if ready >= 2 and not rebuilt:
         assert np.array_equal(inputs.bits(space), old_words), f"{what}: the buffer was to be left alone"
     else:
         assert np.array_equal(inputs.bits(space), want_words), f"{what}: new weights"
@@ -64,6 +64,8 @@ def test_update_matches_the_oracle_over_several_steps(nz, n):
     for step, lr in enumerate((1e-3, 3e-4, 1e-3)):
         g = inputs.gaussian_bf16(n, 10_100 + 7 * step + n % 13, std=0.05, device=DEV)
         container = one_step(nz, blob, container, g, lr, f"n={n} step {step}", ready=step)
+    g = inputs.gaussian_bf16(n, 10_190 + n % 13, std=0.05, device=DEV)
+    one_step(nz, blob, container, g, 1e-3, f"n={n} scratch only", ready=3)
 
 
 @pytest.mark.parametrize("lr", [0.0, 1e-2, -3.0, 1e-30, 3e38, float("inf")])
@@ -81,7 +83,7 @@ def test_update_on_every_weight_pattern(nz, lr):
              ready=2)
 
 
-@pytest.mark.parametrize("ready", [0, 1, 2])
+@pytest.mark.parametrize("ready", [0, 1, 2, 3])
 def test_update_a_layer_in_one_call(nz, ready):
     shapes = [(512, 512), (128, 512), (128, 512), (512, 512), (512, 1792), (512, 1792), (1792, 512), (77, 13), (0,),
               (3, 4096)]
@@ -93,12 +95,12 @@ def test_update_a_layer_in_one_call(nz, ready):
     gs[4] = inputs.from_bits(g4, DEV).reshape(shapes[4])
     blobs = nz.neuzip_compress_guarded(ws, 7, 8)
     containers = [O.compress(inputs.bits(w), 7, guard=8) for w in ws]
-    spaces = [w.clone() if ready else torch.full_like(w, float("nan")) for w in ws]
+    spaces = [w.clone() if ready in (1, 2) else torch.full_like(w, float("nan")) for w in ws]
     rebuilt = nz.neuzip_update(blobs, gs, spaces, 1e-3, weights_ready=ready)
     assert rebuilt[4] == 1 and sum(rebuilt) < len(rebuilt)
     for i, (b, c, g, s) in enumerate(zip(blobs, containers, gs, spaces)):
         want_container, want_rebuilt, want_words = U.training_step(c, inputs.bits(g), 1e-3)
-        if ready == 2 and not rebuilt[i]:
+        if ready >= 2 and not rebuilt[i]:
             assert np.array_equal(inputs.bits(s), inputs.bits(ws[i])), i
         else:
             assert np.array_equal(inputs.bits(s), want_words), i
@@ -155,7 +157,7 @@ def test_update_argument_errors(nz):
     gp = (ctypes.c_void_p * 2)(g.data_ptr(), g.data_ptr())
     wp = (ctypes.c_void_p * 2)(s.data_ptr(), s.data_ptr())
     assert lib.neuzip_update(two, gp, wp, 2, 1e-3, 0, None, None) == nz.EINVAL          # one blob twice
-    assert lib.neuzip_update(one(blob.handle.value), one(g.data_ptr()), one(s.data_ptr()), 1, 1e-3, 3, None, None) == nz.EINVAL
+    assert lib.neuzip_update(one(blob.handle.value), one(g.data_ptr()), one(s.data_ptr()), 1, 1e-3, 4, None, None) == nz.EINVAL
     with pytest.raises(ValueError):
         nz.neuzip_update([blob], [g[:100].contiguous()], [s], 1e-3)
     assert np.array_equal(nz.neuzip_export(blob), before)                            # untouched by the failed calls
