@@ -141,6 +141,36 @@ def test_device_memory_held_matches_the_accounting(nz):
         b.free()
 
 
+def test_no_device_memory_is_leaked(nz):
+    # every kind of blob made, used and freed over and over: what the driver reports as free stays put
+    w = inputs.gaussian_bf16(1_000_003, 1, device=DEV)
+    g = inputs.gaussian_bf16(1_000_003, 2, std=0.05, device=DEV)
+    s = torch.empty_like(w)
+    w32 = inputs.gaussian_f32(300_001, 3, device=DEV)
+    w16 = inputs.gaussian_f16(300_001, 4, device=DEV)
+
+    def cycle():
+        b = nz.neuzip_compress(w, 7)
+        nz.neuzip_decompress(b, s)
+        (gb,) = nz.neuzip_compress_guarded([w], 7, 8)
+        nz.neuzip_update([gb], [g], [s], 1e-3)
+        nz.neuzip_recompress([w], [gb])
+        imported = nz.neuzip_import(nz.neuzip_export(gb))
+        others = [nz.neuzip_compress_blockwise(w, 3, 64), nz.neuzip_compress(w32, 7), nz.neuzip_compress(w16, 7)]
+        for blob in [b, gb, imported] + others:
+            blob.free()
+
+    for _ in range(5):
+        cycle()
+    torch.cuda.synchronize()
+    free_before, _ = torch.cuda.mem_get_info()
+    for _ in range(60):
+        cycle()
+    torch.cuda.synchronize()
+    free_after, _ = torch.cuda.mem_get_info()
+    assert free_before - free_after <= 8 << 20, (free_before, free_after)
+
+
 def test_config5_training_step_loop(nz):
     # 10 steps of decompress -> synthetic update -> recompress (histogram rebuilt) -> verify,
     # on a two-layer slice of the config-3 shapes plus the embedding; oracle cross-check on a sample
