@@ -66,7 +66,7 @@ enum {
     NEUZIP_ENOMEM = -2,       /* device or host allocation failed, or h_buf too small */
     NEUZIP_EHIP = -3,         /* a HIP runtime call failed; see neuzip_last_hip_error() */
     NEUZIP_ECORRUPT = -4,     /* a container or a decoded stream is not well formed */
-    NEUZIP_EUNSUPPORTED = -5  /* size outside the supported range */
+    NEUZIP_EUNSUPPORTED = -5  /* a size, or a combination of element type and option, that is not supported */
 };
 
 /* Format constants of the stream (mirrored in every container header). */
@@ -212,7 +212,7 @@ int neuzip_update(neuzip_blob *const *blobs, const void *const *d_grads, void *c
  * decodes the exponents and reassembles bf16 words into the caller's
  * temporary space in one fused kernel.
  *
- *   d_dst    room for n_elems bf16 (binary32 for such a blob) words on the device, 16-byte aligned.
+ *   d_dst    room for n_elems words of the blob's element type on the device, 16-byte aligned.
  *   n_elems, dtype must equal what the blob was made from (else EINVAL).
  *
  * Never allocates, never synchronises.  For mantissa_bits < 7 the dropped
