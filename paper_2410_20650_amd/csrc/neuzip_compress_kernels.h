@@ -638,14 +638,19 @@ constexpr uint32_t kRingWords = 16;  // per state; two halves of 8 words = 16 by
 
 struct EncState {
     uint32_t x;
-    uint32_t wp;          // next free position in the slot is wp - 1 (words, counts down from kRunCap)
+    uint32_t wp;          // next free position in the slot is wp - 1 (words, counts down from kRunCap);
+                          // brought up to date once per turn (ring_advance)
+    uint32_t cur;         // byte position of the last word written in the workgroup's ring array:
+                          // lane * 32 + 2 * (wp mod 16)
 };
 
-__device__ __forceinline__ void rans_put(EncState &st, const EncSym e, uint16_t *__restrict__ ring)
+// rings: the workgroup's ring array as bytes; lane_ring: this lane's 32-byte ring in it (threadIdx.x * 32)
+__device__ __forceinline__ void rans_put(EncState &st, const EncSym e, uint8_t *__restrict__ rings, uint32_t lane_ring)
 {
     if (st.x >= e.limit) {
-        --st.wp;
-        ring[st.wp & (kRingWords - 1)] = static_cast<uint16_t>(st.x);
+        // one position down, wrapping inside the lane's 16 words: two instructions for the address
+        st.cur = lane_ring | ((st.cur - 2u) & (2u * kRingWords - 2u));
+        *reinterpret_cast<uint16_t *>(rings + st.cur) = static_cast<uint16_t>(st.x);
         st.x >>= 16;
     }
     uint32_t q = static_cast<uint32_t>(__fmul_rn(__uint2float_rn(st.x), e.rcp));  // q or q - 1
@@ -663,6 +668,12 @@ __device__ __forceinline__ void rans_put(EncState &st, const EncSym e, uint16_t 
 __device__ __forceinline__ uint32_t slot_word(uint32_t j, uint32_t p)
 {
     return (((p >> 3) * kStates + j) << 3) | (p & 7u);
+}
+
+// The words pushed since `cur_before` (at most 8 per turn, so the ring position tells) come off wp.
+__device__ __forceinline__ void ring_advance(EncState &st, uint32_t cur_before)
+{
+    st.wp -= ((cur_before - st.cur) & (2u * kRingWords - 2u)) >> 1;
 }
 
 // Moves the 8-word group completed during the last turn (at most one: a turn pushes at most 8
@@ -720,7 +731,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     const EncSym *__restrict__ enc_g = enc_all + 256 * slot_id.item;
 
     __shared__ uint4 enc_raw[256];
-    __shared__ __align__(16) uint16_t rings[kEncThreads * kRingWords];
+    __shared__ __align__(32) uint16_t rings[kEncThreads * kRingWords];
     __shared__ uint32_t group_chunk[kEncThreads / kStates];
     enc_raw[threadIdx.x] = reinterpret_cast<const uint4 *>(enc_g)[threadIdx.x];
     if (SPLIT < 0 && slot_id.wg == 0) {
@@ -738,7 +749,9 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     const uint32_t m = !live ? 0u : ((n - base) < kChunk ? static_cast<uint32_t>(n - base) : kChunk);
     uint16_t *chunk_slots = slots + static_cast<uint64_t>(c) * kStates * kRunCap;
     uint16_t *ring = rings + threadIdx.x * kRingWords;
-    EncState st = {kRansL, kRunCap};
+    uint8_t *ring_bytes = reinterpret_cast<uint8_t *>(rings);
+    const uint32_t lane_ring = threadIdx.x * (2u * kRingWords);
+    EncState st = {kRansL, kRunCap, lane_ring + 2u * (kRunCap % kRingWords)};
     float least_rcp = 1.0f;  // 0 once a symbol without room in the table has been met
     uint8_t *__restrict__ sm = it.sm;
 
@@ -776,7 +789,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
                     reinterpret_cast<uint4 *>(const_cast<void *>(src))[base / 8 + static_cast<uint32_t>(q) * kStates + j] =
                         make_uint4(w[0], w[1], w[2], w[3]);
             }
-            const uint32_t wp_before = st.wp;
+            const uint32_t wp_before = st.wp, cur_before = st.cur;
             if constexpr (SPLIT >= 0) {
                 store_fields<KB>(sm, base / 8 + static_cast<uint32_t>(q) * kStates + j, fields_of<KB, HALF>(w));
                 if constexpr (WIDE)
@@ -793,9 +806,10 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
                 const EncSym e_hi = enc[symbol_of<HALF>(hi)], e_lo = enc[symbol_of<HALF>(lo)];
                 if constexpr (SPLIT >= 0)
                     least_rcp = fminf(least_rcp, fminf(e_hi.rcp, e_lo.rcp));
-                rans_put(st, e_hi, ring);
-                rans_put(st, e_lo, ring);
+                rans_put(st, e_hi, ring_bytes, lane_ring);
+                rans_put(st, e_lo, ring_bytes, lane_ring);
             }
+            ring_advance(st, cur_before);
             ring_flush(wp_before, st.wp, ring, chunk_slots, j);
             d = d_next;
             d_next = d_after;
@@ -806,7 +820,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
         }
     } else if (m > 0) {
         for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
-            const uint32_t wp_before = st.wp;
+            const uint32_t wp_before = st.wp, cur_before = st.cur;
             uint64_t packed = 0;
             for (int t = static_cast<int>(kRun) - 1; t >= 0; --t) {
                 const uint32_t i = static_cast<uint32_t>(q) * kTurn + j * kRun + static_cast<uint32_t>(t);
@@ -824,7 +838,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
                         least_rcp = fminf(least_rcp, e.rcp);
                         packed |= static_cast<uint64_t>(field_of<KB, HALF>(u)) << (static_cast<uint32_t>(t) * (KB + 1));
                     }
-                    rans_put(st, e, ring);
+                    rans_put(st, e, ring_bytes, lane_ring);
                 }
             }
             if constexpr (SPLIT >= 0) {
@@ -835,6 +849,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
                 for (uint32_t t = 0; t < valid; t += per_byte)
                     sm[(base + first + t) / per_byte] = static_cast<uint8_t>(packed >> (t * (KB + 1)));
             }
+            ring_advance(st, cur_before);
             ring_flush(wp_before, st.wp, ring, chunk_slots, j);
         }
     }
