@@ -991,6 +991,16 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const Compress
     uint64_t at0 = 0;
     if (live) {
         const uint16_t *__restrict__ chunk_slots = slots + static_cast<uint64_t>(c) * kStates * kRunCap;
+        // Slot pieces (8 words of one state) are taken row by row from the top of the slots down:
+        // this lane reads, for its state j, rows lane / 16, lane / 16 + 4, ...  The top 8 rows (64
+        // words per state: all of a run at up to 4 bits per symbol) are requested at once, before
+        // the run lengths that say how much of them is needed have arrived.
+        constexpr uint32_t kRows = kRunCap / 8, kAhead = 2;
+        const uint32_t row0 = lane / kStates;
+        uint4 ahead[kAhead];
+#pragma unroll
+        for (uint32_t k = 0; k < kAhead; ++k)
+            ahead[k] = *reinterpret_cast<const uint4 *>(chunk_slots + slot_word(j, (kRows - 1 - (row0 + 4 * k)) * 8));
         // run length of state j and its start inside the chunk (16-lane exclusive prefix)
         const uint32_t my_len = lens[c * kStates + j];
         uint32_t start = my_len;
@@ -1013,20 +1023,18 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const Compress
             offsets[c] = static_cast<uint32_t>(at0);
         shift = static_cast<uint32_t>(at0 & 7u);
 
-        // slot pieces (8 words of one state) from the lowest piece any state reached up to the top
         const uint32_t first_pos = kRunCap - my_len;   // position of the run's first word in its slot
-        uint32_t low_piece = first_pos >> 3;
-#pragma unroll
-        for (uint32_t d = 1; d < kStates; d <<= 1) {
-            const uint32_t o = __shfl_xor(low_piece, d, kStates);
-            low_piece = o < low_piece ? o : low_piece;
-        }
-        const uint32_t n_pieces = (kRunCap / 8 - low_piece) * kStates;
-        for (uint32_t p = lane; p < n_pieces; p += 64) {
-            const uint32_t piece = low_piece + p / kStates;
-            if (piece * 8 + 7 < first_pos)
-                continue;  // wholly before this state's run
-            const uint4 v = *reinterpret_cast<const uint4 *>(chunk_slots + slot_word(j, piece * 8));
+        const uint32_t first_piece = first_pos >> 3;   // rows below it hold nothing of this state
+        for (uint32_t k = 0;; ++k) {
+            const uint32_t row = row0 + 4 * k;
+            if (row >= kRows || kRows - 1 - row < first_piece)
+                break;
+            const uint32_t piece = kRows - 1 - row;
+            uint4 v;
+            if (k < kAhead)
+                v = k == 0 ? ahead[0] : ahead[1];
+            else
+                v = *reinterpret_cast<const uint4 *>(chunk_slots + slot_word(j, piece * 8));
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (uint32_t t = 0; t < 8; ++t) {
