@@ -315,6 +315,36 @@ int neuzip_frequencies(const neuzip_blob *blob, uint16_t h_freq[256]);
  * word run that was not consumed exactly; clears the flag. */
 int neuzip_check(const neuzip_blob *blob, void *hip_stream);
 
+/*
+ * neuzip_compress_noalloc -- neuzip_compress for callers that cannot allocate device or pinned
+ * memory at the time of the call: code that runs where hipMalloc is forbidden (a region under
+ * stream capture, a tight serving or training loop, a harness that intercepts allocation).
+ *
+ *   d_src, n_elems, dtype, mantissa_bits, hip_stream   as for neuzip_compress.
+ *   blob    an existing blob of this library made from a tensor of the same n_elems, dtype and
+ *           mantissa_bits without block-wise normalisation (else EINVAL / EUNSUPPORTED).  It
+ *           receives the new tensor; its old content is lost; its guard band is kept.
+ *
+ * The result is the same as neuzip_compress into that blob: same table, same stream, same container.
+ * What differs: the pipeline's workspace (histogram bins, encoder constants, run slots, word
+ * counts, the record of the stream length) is a fixed array of about 6.6 MB inside the library's
+ * device code, present once on every GPU the library runs on until the process ends, and the
+ * stream length comes back by a copy from it.  The call makes no hipMalloc, hipHostMalloc or
+ * hipFree.  Limits and error behaviour:
+ *   - n_elems <= NEUZIP_NOALLOC_MAX_ELEMS, else EUNSUPPORTED (nothing is run).
+ *   - the blob's word section is not grown: if the new stream needs more room than the blob
+ *     holds, the call returns ENOMEM and the blob holds no tensor until a compress call succeeds
+ *     (its fixed sections have been overwritten by then).  A blob last filled by a tensor of the
+ *     same or a higher exponent entropy has room.
+ *   - all calls on one GPU share that GPU's array: calls that overlap in time on one GPU (from
+ *     several host threads or streams) race and must be serialised by the caller.  The array
+ *     keeps the last call's contents; the call clears what has to start at zero.
+ * Synchronises hip_stream once, like neuzip_compress.
+ */
+#define NEUZIP_NOALLOC_MAX_ELEMS (1ull << 22)
+int neuzip_compress_noalloc(const void *d_src, uint64_t n_elems, int dtype, int mantissa_bits,
+                            void *hip_stream, neuzip_blob *blob);
+
 /* Frees the per-device workspace compress keeps between calls. */
 int neuzip_release_workspace(void);
 

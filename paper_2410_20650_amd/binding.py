@@ -33,6 +33,8 @@ def _load():
     vpp = ctypes.POINTER(vp)
     lib.neuzip_compress.argtypes = [vp, u64, i32, i32, vp, vpp]
     lib.neuzip_compress.restype = i32
+    lib.neuzip_compress_noalloc.argtypes = [vp, u64, i32, i32, vp, vp]
+    lib.neuzip_compress_noalloc.restype = i32
     lib.neuzip_compress_blockwise.argtypes = [vp, u64, i32, i32, u32, vp, vpp]
     lib.neuzip_compress_blockwise.restype = i32
     lib.neuzip_compress_batch.argtypes = [vpp, ctypes.POINTER(u64), u32, i32, i32, u32, vp, vpp]
@@ -89,7 +91,7 @@ def _load():
 _lib = None
 _lib = _load()
 
-EXPORTED = ["neuzip_compress", "neuzip_compress_blockwise", "neuzip_compress_batch", "neuzip_compress_guarded",
+EXPORTED = ["neuzip_compress", "neuzip_compress_noalloc", "neuzip_compress_blockwise", "neuzip_compress_batch", "neuzip_compress_guarded",
             "neuzip_recompress", "neuzip_update", "neuzip_guard", "neuzip_linear", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
             "neuzip_free",
             "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits", "neuzip_dtype",
@@ -174,6 +176,16 @@ class Blob:
 
 def neuzip_compress(src: torch.Tensor, mantissa_bits: int = 7, stream=None, blob: Blob = None) -> Blob:
     return neuzip_compress_blockwise(src, mantissa_bits, 0, stream, blob)
+
+
+def neuzip_compress_noalloc(src: torch.Tensor, mantissa_bits: int, blob: Blob, stream=None) -> Blob:
+    """neuzip_compress into an existing blob through the library's fixed workspace (allocates nothing)."""
+    dtype = _check_tensor(src, wide_ok=True)
+    rc = _lib.neuzip_compress_noalloc(ctypes.c_void_p(src.data_ptr()), src.numel(), dtype, mantissa_bits,
+                                      _stream_handle(stream), blob.handle)
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_compress_noalloc")
+    return blob
 
 
 def neuzip_compress_blockwise(src: torch.Tensor, mantissa_bits: int, block_size: int, stream=None,

@@ -54,7 +54,7 @@ inline bool hip_ok(hipError_t e)
             return NEUZIP_EHIP;      \
     } while (0)
 
-inline uint64_t pad_to(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+constexpr uint64_t pad_to(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 inline bool valid_k(int k) { return k == 7 || k == 3 || k == 1 || k == 0; }
 inline uint64_t signmant_bytes(uint64_t n, int k) { return (n * static_cast<uint64_t>(k + 1) + 7) / 8; }
 inline uint32_t chunks_of(uint64_t n) { return static_cast<uint32_t>((n + kChunk - 1) / kChunk); }
@@ -479,22 +479,22 @@ int compress_empty(neuzip_blob *b, hipStream_t stream)
 }
 
 template <int KB>
-void launch_hist(const CompressBatch &batch, bool norm, uint32_t groups, hipStream_t stream)
+void launch_hist(const Workspace &ws, const CompressBatch &batch, bool norm, uint32_t groups, hipStream_t stream)
 {
     if (norm)
         hipLaunchKernelGGL(hist_split_norm_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch,
-                           g_ws.counts);
+                           ws.counts);
     else
-        hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch, g_ws.counts);
+        hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch, ws.counts);
 }
 
 constexpr uint32_t kKeepGuard = 0xFFFFFFFFu;  // compress_some: every blob keeps the guard band it has
 
 template <int KB>
-void launch_encode_reuse(const CompressBatch &batch, uint32_t groups, hipStream_t stream)
+void launch_encode_reuse(const Workspace &ws, const CompressBatch &batch, uint32_t groups, hipStream_t stream)
 {
-    hipLaunchKernelGGL((encode_kernel<false, KB>), dim3(groups), dim3(kEncThreads), 0, stream, batch, g_ws.enc,
-                       g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned, g_ws.stale);
+    hipLaunchKernelGGL((encode_kernel<false, KB>), dim3(groups), dim3(kEncThreads), 0, stream, batch, ws.enc,
+                       ws.chunk_words, ws.group_words, ws.slots, ws.pinned, ws.stale);
 }
 
 // Compresses up to kBatchMax tensors (arguments already validated) with one pass of the pipeline.
@@ -504,10 +504,15 @@ void launch_encode_reuse(const CompressBatch &batch, uint32_t groups, hipStream_
 // not to cover them, which are then compressed the first way.  d_grads (with reuse, lossless bf16
 // only): the sources are weights that first take the step W - lr * grad in that same pass; the new
 // weights replace them if keep_new is set (else only those of rebuilt tensors do).
+// fixed_ws: a workspace of fixed size that lives in the library's static device array, for the entry
+// point that allocates nothing (reuse = false, every blob exists already); nullptr: the shared
+// workspace that grows on demand.
 int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int k, uint32_t block, int elem,
                   uint32_t guard, bool reuse, uint32_t *rebuilt, hipStream_t stream, neuzip_blob **blobs,
-                  const void *const *d_grads = nullptr, float lr = 0.0f, bool keep_new = true)
+                  const void *const *d_grads = nullptr, float lr = 0.0f, bool keep_new = true,
+                  Workspace *fixed_ws = nullptr)
 {
+    Workspace &ws = fixed_ws ? *fixed_ws : g_ws;
     neuzip_blob *work[kBatchMax];
     bool fresh[kBatchMax];
     for (uint32_t i = 0; i < count; ++i) {
@@ -517,8 +522,8 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
     bool bins_dirty = false;  // the histogram kernel ran but the table kernel did not clear the bins
     bool touched = false;     // kernels that write into the blobs have been launched
     auto fail = [&](int rc) {
-        if (bins_dirty && g_ws.counts)
-            hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax), dim3(256), 0, stream, g_ws.counts, 0u,
+        if (bins_dirty && ws.counts)
+            hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax), dim3(256), 0, stream, ws.counts, 0u,
                                kBatchMax * 256);
         for (uint32_t i = 0; i < count; ++i) {
             if (fresh[i])
@@ -594,89 +599,106 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
     }
     if (batch.count > 0) {
         std::lock_guard<std::mutex> lock(g_ws_mutex);
-        int rc = ensure_workspace(work[owner[0]]->device, enc_groups, stream);
-        if (rc != NEUZIP_OK)
-            return fail(rc);
-        batch.seq = ++g_ws.seq;
+        int rc = NEUZIP_OK;
+        if (fixed_ws) {
+            if (enc_groups > ws.group_cap)
+                return fail(NEUZIP_EUNSUPPORTED);
+            // the static array keeps what the last call left: bins, counter and flags start at zero
+            hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax + 1), dim3(256), 0, stream, ws.counts, 0u,
+                               kBatchMax * 256 + 64);
+            if (!hip_ok(hipGetLastError()))
+                return fail(NEUZIP_EHIP);
+        } else {
+            rc = ensure_workspace(work[owner[0]]->device, enc_groups, stream);
+            if (rc != NEUZIP_OK)
+                return fail(rc);
+        }
+        batch.seq = ++ws.seq;
         batch.lr = lr;
         batch.keep_new = keep_new ? 1u : 0u;
         touched = true;
 
         if (reuse) {
             // one pass: encoder constants from the stored tables, then split + encode together
-            hipLaunchKernelGGL(table_reuse_kernel, dim3(batch.count), dim3(256), 0, stream, batch, g_ws.enc,
-                               g_ws.stale);
+            hipLaunchKernelGGL(table_reuse_kernel, dim3(batch.count), dim3(256), 0, stream, batch, ws.enc,
+                               ws.stale);
             switch (d_grads ? kUpdateVariant : (elem == NEUZIP_F32 ? 23 : (elem == NEUZIP_F16 ? 39 : k))) {
             case kUpdateVariant:
                 hipLaunchKernelGGL((encode_kernel<false, 7, false, false, true>), dim3(enc_groups), dim3(kEncThreads), 0,
-                                   stream, batch, g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned,
-                                   g_ws.stale);
+                                   stream, batch, ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned,
+                                   ws.stale);
                 break;
             case 39:
                 hipLaunchKernelGGL((encode_kernel<false, 7, false, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream,
-                                   batch, g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned, g_ws.stale);
+                                   batch, ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned, ws.stale);
                 break;
             case 23:
                 hipLaunchKernelGGL((encode_kernel<false, 7, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream, batch,
-                                   g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned, g_ws.stale);
+                                   ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned, ws.stale);
                 break;
-            case 7: launch_encode_reuse<7>(batch, enc_groups, stream); break;
-            case 3: launch_encode_reuse<3>(batch, enc_groups, stream); break;
-            case 1: launch_encode_reuse<1>(batch, enc_groups, stream); break;
-            default: launch_encode_reuse<0>(batch, enc_groups, stream); break;
+            case 7: launch_encode_reuse<7>(ws, batch, enc_groups, stream); break;
+            case 3: launch_encode_reuse<3>(ws, batch, enc_groups, stream); break;
+            case 1: launch_encode_reuse<1>(ws, batch, enc_groups, stream); break;
+            default: launch_encode_reuse<0>(ws, batch, enc_groups, stream); break;
             }
         } else {
             switch (elem == NEUZIP_F32 ? 23 : (elem == NEUZIP_F16 ? 39 : k)) {
             case 39:
                 hipLaunchKernelGGL((hist_split_kernel<7, false, true>), dim3(hist_groups), dim3(kHistThreads), 0, stream,
-                                   batch, g_ws.counts);
+                                   batch, ws.counts);
                 break;
             case 23:
                 hipLaunchKernelGGL((hist_split_kernel<7, true>), dim3(hist_groups), dim3(kHistThreads), 0, stream, batch,
-                                   g_ws.counts);
+                                   ws.counts);
                 break;
-            case 7: launch_hist<7>(batch, block != 0, hist_groups, stream); break;
-            case 3: launch_hist<3>(batch, block != 0, hist_groups, stream); break;
-            case 1: launch_hist<1>(batch, block != 0, hist_groups, stream); break;
-            default: launch_hist<0>(batch, block != 0, hist_groups, stream); break;
+            case 7: launch_hist<7>(ws, batch, block != 0, hist_groups, stream); break;
+            case 3: launch_hist<3>(ws, batch, block != 0, hist_groups, stream); break;
+            case 1: launch_hist<1>(ws, batch, block != 0, hist_groups, stream); break;
+            default: launch_hist<0>(ws, batch, block != 0, hist_groups, stream); break;
             }
             if (!hip_ok(hipGetLastError()))
                 return fail(NEUZIP_EHIP);
             bins_dirty = true;
             // the table kernel also returns the workspace histogram bins to zero
-            hipLaunchKernelGGL(table_kernel, dim3(batch.count), dim3(256), 0, stream, batch, g_ws.counts, g_ws.enc);
+            hipLaunchKernelGGL(table_kernel, dim3(batch.count), dim3(256), 0, stream, batch, ws.counts, ws.enc);
             if (hip_ok(hipGetLastError()))
                 bins_dirty = false;
             if (elem == NEUZIP_F16)
                 hipLaunchKernelGGL((encode_kernel<false, -1, false, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream,
-                                   batch, g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned,
+                                   batch, ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned,
                                    static_cast<uint32_t *>(nullptr));
             else if (elem == NEUZIP_F32)
                 hipLaunchKernelGGL((encode_kernel<false, -1, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream,
-                                   batch, g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned,
+                                   batch, ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned,
                                    static_cast<uint32_t *>(nullptr));
             else if (block)
                 hipLaunchKernelGGL((encode_kernel<true, -1>), dim3(enc_groups), dim3(kEncThreads), 0, stream, batch,
-                                   g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned,
+                                   ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned,
                                    static_cast<uint32_t *>(nullptr));
             else
                 hipLaunchKernelGGL((encode_kernel<false, -1>), dim3(enc_groups), dim3(kEncThreads), 0, stream, batch,
-                                   g_ws.enc, g_ws.chunk_words, g_ws.group_words, g_ws.slots, g_ws.pinned,
+                                   ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned,
                                    static_cast<uint32_t *>(nullptr));
         }
-        hipLaunchKernelGGL(offsets_kernel, dim3(batch.count), dim3(kScanThreads), 0, stream, batch, g_ws.group_words,
-                           g_ws.group_prefix, g_ws.done, g_ws.pinned,
-                           reuse ? static_cast<const uint32_t *>(g_ws.stale) : static_cast<const uint32_t *>(nullptr));
+        hipLaunchKernelGGL(offsets_kernel, dim3(batch.count), dim3(kScanThreads), 0, stream, batch, ws.group_words,
+                           ws.group_prefix, ws.done, ws.pinned,
+                           reuse ? static_cast<const uint32_t *>(ws.stale) : static_cast<const uint32_t *>(nullptr));
         if (!hip_ok(hipGetLastError()))
             return fail(NEUZIP_EHIP);
 
         // the stream lengths are data dependent: wait for them (and the statistics), which the
         // kernels write straight into pinned host memory, the stamp last
-        if (!wait_for_record(batch.seq, stream))
+        HostRecord::Item fetched;  // fixed workspace: the record lies in device memory and is copied out
+        if (fixed_ws) {
+            if (!hip_ok(hipMemcpyAsync(&fetched, &ws.pinned->item[0], sizeof(fetched), hipMemcpyDeviceToHost, stream)) ||
+                !hip_ok(hipStreamSynchronize(stream)))
+                return fail(NEUZIP_EHIP);
+        } else if (!wait_for_record(batch.seq, stream)) {
             return fail(NEUZIP_EHIP);
+        }
         uint32_t n_stale = 0;
         for (uint32_t j = 0; j < batch.count; ++j) {
-            const HostRecord::Item &r = g_ws.pinned->item[j];
+            const HostRecord::Item &r = fixed_ws ? fetched : ws.pinned->item[j];
             neuzip_blob *b = work[owner[j]];
             if (reuse && r.stale) {
                 // its table does not cover the new values: nothing of this pass is kept (the
@@ -692,7 +714,11 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             }
             if (r.total_words[1] != 0)
                 return fail(NEUZIP_EUNSUPPORTED);  // more than 2^32 words
-            rc = reserve_words(b, r.total_words[0]);
+            if (fixed_ws)  // no allocation: the stream must fit the room the blob has
+                rc = pad_to(static_cast<uint64_t>(r.total_words[0]) * 2, 256) + 1024 <= b->words_bytes ? NEUZIP_OK
+                                                                                                          : NEUZIP_ENOMEM;
+            else
+                rc = reserve_words(b, r.total_words[0]);
             if (rc != NEUZIP_OK)
                 return fail(rc);
             b->total_words = r.total_words[0];
@@ -704,9 +730,9 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             b->has_table = true;
             batch.it[j].words = reinterpret_cast<uint16_t *>(b->words);
         }
-        hipLaunchKernelGGL(compact_kernel, dim3(compact_groups), dim3(kCompactThreads), 0, stream, batch, g_ws.slots,
-                           g_ws.chunk_words, g_ws.group_prefix);
-        if (!hip_ok(hipGetLastError()) || !hip_ok(hipEventRecord(g_ws.idle, stream)))
+        hipLaunchKernelGGL(compact_kernel, dim3(compact_groups), dim3(kCompactThreads), 0, stream, batch, ws.slots,
+                           ws.chunk_words, ws.group_prefix);
+        if (!hip_ok(hipGetLastError()) || (!fixed_ws && !hip_ok(hipEventRecord(ws.idle, stream))))
             return fail(NEUZIP_EHIP);
         stale_count = n_stale;
     }
@@ -1010,7 +1036,96 @@ int compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t 
 
 }  // namespace
 
+// ------------------------------------------------------------------------------------------
+// Compression for callers that cannot allocate: the compress workspace of one tensor of at most
+// NEUZIP_NOALLOC_MAX_ELEMS elements, carved out of a device array that is part of the library's
+// code object.  Each GPU holds its own copy of the array at its own address; the address is asked
+// for once per device (with that device current) and only that pointer is ever handed to kernels
+// or copies -- the array's name is not a device address in host code.
+// ------------------------------------------------------------------------------------------
+namespace {
+
+constexpr uint32_t kFixedChunks = static_cast<uint32_t>(NEUZIP_NOALLOC_MAX_ELEMS / kChunk);
+constexpr uint32_t kFixedGroups = kFixedChunks / kChunksPerGroup;
+static_assert(NEUZIP_NOALLOC_MAX_ELEMS % (kChunk * kChunksPerGroup) == 0, "whole encoder groups");
+constexpr uint64_t kFixedEncAt = 0;                                                        // 256 encoder constants
+constexpr uint64_t kFixedCountsAt = kFixedEncAt + 256 * sizeof(EncSym);                    // bins, counter, flags
+constexpr uint64_t kFixedRecordAt = kFixedCountsAt + pad_to((kBatchMax * 256 + 64) * 4, 256);
+constexpr uint64_t kFixedChunkWordsAt = kFixedRecordAt + pad_to(sizeof(HostRecord), 256);
+constexpr uint64_t kFixedGroupWordsAt = kFixedChunkWordsAt + pad_to((kFixedChunks + 4) * 4, 256);
+constexpr uint64_t kFixedGroupPrefixAt = kFixedGroupWordsAt + pad_to((kFixedGroups + 4) * 4, 256);
+constexpr uint64_t kFixedSlotsAt = kFixedGroupPrefixAt + pad_to((kFixedGroups + 4) * 8, 256);
+constexpr uint64_t kFixedBytes = kFixedSlotsAt + static_cast<uint64_t>(kFixedChunks) * kStates * kRunCap * 2;
+
+static __device__ __align__(256) unsigned char scratch[kFixedBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+uint8_t *g_scratch_ptr[kMaxDevices];   // per device: where that device holds the array
+uint32_t g_scratch_seq[kMaxDevices];   // per device: stamp of the last call
+
+// The array of the current device, asked for on the first call there.
+int scratch_of_current_device(int *device, uint8_t **ptr)
+{
+    NZ_HIP(hipGetDevice(device));
+    if (*device < 0 || *device >= kMaxDevices)
+        return NEUZIP_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[*device]) {
+        void *at = nullptr;
+        NZ_HIP(hipGetSymbolAddress(&at, HIP_SYMBOL(scratch)));
+        if (!at)
+            return NEUZIP_EHIP;
+        g_scratch_ptr[*device] = static_cast<uint8_t *>(at);
+    }
+    *ptr = g_scratch_ptr[*device];
+    return NEUZIP_OK;
+}
+
+}  // namespace
+
 extern "C" {
+
+int neuzip_compress_noalloc(const void *d_src, uint64_t n_elems, int dtype, int mantissa_bits, void *hip_stream,
+                            neuzip_blob *blob)
+{
+    if ((dtype != NEUZIP_BF16 && dtype != NEUZIP_F32 && dtype != NEUZIP_F16) || !valid_k(mantissa_bits))
+        return NEUZIP_EINVAL;
+    if (dtype != NEUZIP_BF16 && mantissa_bits != 7)
+        return NEUZIP_EUNSUPPORTED;
+    if (!is_blob(blob) || blob->n != n_elems || blob->k != mantissa_bits || blob->elem != dtype ||
+        !on_current_device(blob))
+        return NEUZIP_EINVAL;
+    if (blob->block != 0)
+        return NEUZIP_EUNSUPPORTED;
+    if (n_elems > NEUZIP_NOALLOC_MAX_ELEMS)
+        return NEUZIP_EUNSUPPORTED;
+    if (n_elems > 0 && (!d_src || (reinterpret_cast<uintptr_t>(d_src) & 15u)))
+        return NEUZIP_EINVAL;
+    int device = -1;
+    uint8_t *base = nullptr;
+    const int rc = scratch_of_current_device(&device, &base);
+    if (rc != NEUZIP_OK)
+        return rc;
+    Workspace ws;
+    ws.device = device;
+    ws.enc = reinterpret_cast<EncSym *>(base + kFixedEncAt);
+    ws.counts = reinterpret_cast<uint32_t *>(base + kFixedCountsAt);
+    ws.done = ws.counts + kBatchMax * 256;
+    ws.stale = ws.done + 8;
+    ws.pinned = reinterpret_cast<HostRecord *>(base + kFixedRecordAt);  // device memory here: copied out, not read in place
+    ws.chunk_words = reinterpret_cast<uint32_t *>(base + kFixedChunkWordsAt);
+    ws.group_words = reinterpret_cast<uint32_t *>(base + kFixedGroupWordsAt);
+    ws.group_prefix = reinterpret_cast<uint64_t *>(base + kFixedGroupPrefixAt);
+    ws.slots = reinterpret_cast<uint16_t *>(base + kFixedSlotsAt);
+    ws.group_cap = kFixedGroups;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        ws.seq = g_scratch_seq[device]++;
+    }
+    return compress_some(&d_src, &n_elems, 1, mantissa_bits, 0, dtype, kKeepGuard, false, nullptr,
+                         static_cast<hipStream_t>(hip_stream), &blob, nullptr, 0.0f, true, &ws);
+}
 
 int neuzip_decompress(const neuzip_blob *blob, void *d_dst, uint64_t n_elems, int dtype, void *hip_stream)
 {
