@@ -425,6 +425,7 @@ static uint16_t get16(const uint8_t *p) { return (uint16_t)(p[0] | (p[1] << 8));
 /* Room for one state's words.  A step grows log2(x + 1) by at most 12 bits, an emitted word
  * shrinks it by at least 16 - log2(17/16) bits, so 256 symbols give at most 193 words. */
 #define NZO_RUN_CAP 200u
+#define NZO_RUN_MAX 193u
 
 static uint64_t chunks_of(uint64_t n) { return (n + NZO_CHUNK - 1) / NZO_CHUNK; }
 
@@ -461,6 +462,13 @@ static void *enc_worker(void *arg)
         if (rc != NZO_OK) {
             job->rc = rc;
             return NULL;
+        }
+        /* the bound derived above the capacity: no state of a 4096-symbol chunk emits more */
+        for (int j = 0; j < NZO_K; j++) {
+            if (job->lens[c * NZO_K + j] > NZO_RUN_MAX) {
+                job->rc = NZO_ENOSPACE;
+                return NULL;
+            }
         }
     }
     return NULL;

@@ -300,6 +300,51 @@ def test_long_rare_symbol_run_hits_the_word_capacity_bound():
     assert np.all(O.decode_chunk(4096, freq, states, runs) == 255)
 
 
+def test_no_state_emits_more_than_193_words_for_256_symbols():
+    # The bound the format's run lengths rest on (one byte per run, slots of 200 words), in two parts.
+    # 1) The two inequalities of the argument, checked on the oracle's own step for every frequency at the
+    #    edges of its ranges and at random states (integers only):
+    #      a step without a word:  x' + 1 <= 4096 (x + 1)                  (log2(x + 1) grows by at most 12)
+    #      a step with a word:     the state falls to y = x >> 16 >= 16 before it is advanced, so
+    #                              y + 1 <= (17/16) y <= (17/16) (x + 1) / 65536, and then the same growth
+    #    With t words among 256 steps:  16 <= log2(x_end + 1) <= log2(65537) + 256 * 12 - t (16 - log2(17/16)),
+    #    so t <= (log2(65537) - 16 + 3072) / (16 - log2(17/16)) = 193.06.
+    rng = np.random.default_rng(7)
+    for f in range(1, 4097):
+        limit = f << 20
+        cums = (0, 4096 - f)
+        quiet = [1 << 16, min(limit, 1 << 32) - 1] + [int(v) for v in rng.integers(1 << 16, min(limit, 1 << 32), 3)]
+        for x in quiet:
+            for c in cums:
+                xn, word = O.rans_encode_step(x, f, c)
+                assert word is None and (1 << 16) <= xn < (1 << 32)
+                assert xn + 1 <= 4096 * (x + 1)
+        if limit < (1 << 32):
+            loud = [limit, (1 << 32) - 1, limit | 0xFFFF] + [int(v) for v in rng.integers(limit, 1 << 32, 3)]
+            for x in loud:
+                for c in cums:
+                    xn, word = O.rans_encode_step(x, f, c)
+                    y = x >> 16
+                    assert word == (x & 0xFFFF) and y >= 16 * f
+                    assert 16 * (y + 1) <= 17 * y and 65536 * y <= x
+                    assert (1 << 16) <= xn < (1 << 32) and xn + 1 <= 4096 * (y + 1)
+    assert math.floor((math.log2(65537) - 16 + 256 * 12) / (16 - math.log2(17 / 16))) == 193
+    # 2) A search for a long run (a heuristic, the proof is part 1): per step and per number of words so
+    #    far, the largest states reached are kept and every choice of a rare symbol is tried.  It finds
+    #    192, the all-rare case of the test above, and nothing beyond the bound.
+    choices = [(f, c) for f in (1, 2, 3, 4, 8) for c in (0, 4096 - f)]
+    front = {0: {1 << 16}}
+    for _ in range(256):
+        nxt = {}
+        for words, states in front.items():
+            for x in states:
+                for f, c in choices:
+                    xn, word = O.rans_encode_step(x, f, c)
+                    nxt.setdefault(words + (word is not None), set()).add(xn)
+        front = {wd: set(sorted(st)[-6:]) for wd, st in nxt.items() if wd >= max(nxt) - 2}
+    assert 192 <= max(front) <= 193
+
+
 # ---------------------------------------------------------------- container: both statements of the format agree
 
 @pytest.mark.parametrize("k", [7, 3, 1, 0])
