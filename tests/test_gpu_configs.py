@@ -51,7 +51,7 @@ def test_config2_llama_mlp_weight(nz):
     assert 8 * blob.compressed_bytes / w.numel() <= 1.02 * (entropy + 8)
 
 
-@pytest.mark.parametrize("k", [3, 0])
+@pytest.mark.parametrize("k", [3, 1, 0])
 def test_config4_lossy_70b_mlp_weight(nz, k):
     w = inputs.student_t4_bf16(inputs.MLP_70B, inputs.seed_for(4), device=DEV)
     blob = nz.neuzip_compress(w, k)
@@ -196,6 +196,47 @@ def test_config5_training_step_loop(nz):
             del new
         for blob in blobs:
             nz.neuzip_check(blob)
+
+
+def test_config5_training_step_loop_on_the_whole_model(nz):
+    # the loop at its full size: all 225 tensors, 10 steps, a layer per call (batch calls), every tensor
+    # verified bit by bit after every step; the oracle's containers for the embedding and the first
+    # and last layer at the first and the last step
+    names = inputs.llama3_8b_tensors()
+    blobs = []
+    for i, (_, shape) in enumerate(names):
+        t = inputs.gaussian_bf16(shape, inputs.seed_for(5, i), device=DEV)
+        blobs.append(nz.neuzip_compress(t, 7))
+        del t
+    groups = [[0]] + [list(range(1 + 7 * l, 8 + 7 * l)) for l in range(32)]
+    scratch = torch.empty(128256 * 4096, dtype=torch.bfloat16, device=DEV)
+    fresh = torch.empty_like(scratch)
+
+    def pieces(buf, g):
+        at, out = 0, []
+        for i in g:
+            out.append(buf[at: at + blobs[i].elems])
+            at += (blobs[i].elems + 127) // 128 * 128
+        return out
+
+    for step in range(10):
+        for gi, g in enumerate(groups):
+            bl, olds, news = [blobs[i] for i in g], pieces(scratch, g), pieces(fresh, g)
+            nz.neuzip_decompress_batch(bl, olds)
+            for i, old, new in zip(g, olds, news):
+                new.copy_(inputs.synthetic_update(old, inputs.seed_for(5, 1000 * (step + 1) + i)))
+            nz.neuzip_compress_batch(news, 7, 0, blobs=bl)
+            nz.neuzip_decompress_batch(bl, olds)
+            for i, old, new in zip(g, olds, news):
+                assert same_bits(old, new), (step, names[i][0])
+            if step in (0, 9) and gi in (0, 1, 32):
+                for b, new in zip(bl, news):
+                    oracle_parity(nz, new, b, 7)
+    for b in blobs:
+        nz.neuzip_check(b)
+    total = sum(b.elems for b in blobs)
+    assert total == 7_504_658_432
+    assert 8 * sum(b.compressed_bytes for b in blobs) / total < 10.76
 
 
 def test_config5_loop_with_kept_tables(nz):
