@@ -152,16 +152,14 @@ inline bool on_current_device(const neuzip_blob *b)
 // per-chunk / per-group word counts, run slots, and pinned host memory for the results.
 struct Workspace {
     int device = -1;
-    EncSym *enc = nullptr;            // kBatchMax x 256
-    uint32_t *counts = nullptr;       // kBatchMax x 256 histogram bins, zero between compress calls
-    uint32_t *done = nullptr;         // offsets-kernel workgroups that have finished (rearmed by the last)
-    uint32_t *stale = nullptr;        // per tensor of the batch: recompression met an exponent without room
+    uint32_t *counts = nullptr;       // kBatchMax x 256 histogram bins, then the kFlagWords counters and flags of a
+                                      // call; all zero between compress calls
     uint32_t *chunk_words = nullptr;  // words per chunk
     uint32_t *group_words = nullptr;  // words per encoder workgroup (16 chunks), input of the scan
     uint64_t *group_prefix = nullptr; // its exclusive prefix sum, per tensor
     uint64_t group_cap = 0;           // encoder groups the arrays and the slots are sized for
     uint16_t *slots = nullptr;
-    HostRecord *pinned = nullptr;     // pinned host memory, written by the encode and offsets kernels
+    HostRecord *pinned = nullptr;     // pinned host memory, written by the encode kernel
     uint32_t seq = 0;                 // stamp of the last compress call
     hipEvent_t idle = nullptr;        // recorded after the last kernel that uses the workspace
 };
@@ -182,8 +180,7 @@ int release_workspace_locked()
                 rc = NEUZIP_EHIP;
             (void)hipEventDestroy(g_ws.idle);
         }
-        void *device_arrays[] = {g_ws.enc, g_ws.counts, g_ws.chunk_words, g_ws.group_words, g_ws.group_prefix,
-                                 g_ws.slots};  // `done` lives inside the counts allocation
+        void *device_arrays[] = {g_ws.counts, g_ws.chunk_words, g_ws.group_words, g_ws.group_prefix, g_ws.slots};
         for (void *ptr : device_arrays)
             if (ptr)
                 (void)hipFree(ptr);
@@ -195,7 +192,7 @@ int release_workspace_locked()
     return rc;
 }
 
-// Waits until the offsets kernel of call `seq` has published its record.  The stamp arrives a
+// Waits until the encode kernel of call `seq` has published its record.  The stamp arrives a
 // few microseconds after the kernel's last store, well before a blocking stream synchronise would
 // wake up; after a bounded spin the stream is synchronised anyway, which also surfaces errors.
 bool wait_for_record(uint32_t seq, hipStream_t stream)
@@ -218,16 +215,13 @@ bool wait_for_record(uint32_t seq, hipStream_t stream)
 int create_workspace(int device, hipStream_t stream)
 {
     g_ws.device = device;
-    NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.enc), kBatchMax * 256 * sizeof(EncSym)));
-    NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.counts), (kBatchMax * 256 + 64) * sizeof(uint32_t)));
-    g_ws.done = g_ws.counts + kBatchMax * 256;  // shares the allocation; cleared with the bins below
-    g_ws.stale = g_ws.done + 8;
+    NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.counts), (kBatchMax * 256 + kFlagWords) * sizeof(uint32_t)));
     NZ_HIP(hipHostMalloc(reinterpret_cast<void **>(&g_ws.pinned), sizeof(HostRecord), hipHostMallocDefault));
     std::memset(g_ws.pinned, 0, sizeof(HostRecord));
     g_ws.seq = 0;
     NZ_HIP(hipEventCreateWithFlags(&g_ws.idle, hipEventDisableTiming));
     hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax + 1), dim3(256), 0, stream, g_ws.counts, 0u,
-                       kBatchMax * 256 + 64);
+                       kBatchMax * 256 + kFlagWords);
     NZ_HIP(hipGetLastError());
     NZ_HIP(hipEventRecord(g_ws.idle, stream));
     return NEUZIP_OK;
@@ -323,6 +317,12 @@ int reserve_words(neuzip_blob *b, uint64_t total_words)
         b->words_bytes = roomy;
     }
     return NEUZIP_OK;
+}
+
+// Words a blob's word section has room for: reserve_words() would be content with it as it is.
+inline uint64_t words_room(const neuzip_blob *b)
+{
+    return b->words_bytes >= 1024 ? (b->words_bytes - 1024) / 256 * 256 / 2 : 0;
 }
 
 // Chunks per decoder workgroup.  32 (8 waves) measured best from ~16 M elements up: two such
@@ -481,21 +481,15 @@ int compress_empty(neuzip_blob *b, hipStream_t stream)
 template <int KB>
 void launch_hist(const Workspace &ws, const CompressBatch &batch, bool norm, uint32_t groups, hipStream_t stream)
 {
+    uint32_t *flags = ws.counts + kBatchMax * 256;
     if (norm)
-        hipLaunchKernelGGL(hist_split_norm_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch,
-                           ws.counts);
+        hipLaunchKernelGGL(hist_split_norm_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch, ws.counts,
+                           flags);
     else
-        hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch, ws.counts);
+        hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch, ws.counts, flags);
 }
 
 constexpr uint32_t kKeepGuard = 0xFFFFFFFFu;  // compress_some: every blob keeps the guard band it has
-
-template <int KB>
-void launch_encode_reuse(const Workspace &ws, const CompressBatch &batch, uint32_t groups, hipStream_t stream)
-{
-    hipLaunchKernelGGL((encode_kernel<false, KB>), dim3(groups), dim3(kEncThreads), 0, stream, batch, ws.enc,
-                       ws.chunk_words, ws.group_words, ws.slots, ws.pinned, ws.stale);
-}
 
 // Compresses up to kBatchMax tensors (arguments already validated) with one pass of the pipeline.
 // reuse = false: statistics are taken from the tensors and new tables are built (with the given
@@ -519,12 +513,8 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         work[i] = blobs[i];
         fresh[i] = false;
     }
-    bool bins_dirty = false;  // the histogram kernel ran but the table kernel did not clear the bins
     bool touched = false;     // kernels that write into the blobs have been launched
     auto fail = [&](int rc) {
-        if (bins_dirty && ws.counts)
-            hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax), dim3(256), 0, stream, ws.counts, 0u,
-                               kBatchMax * 256);
         for (uint32_t i = 0; i < count; ++i) {
             if (fresh[i])
                 neuzip_free(work[i]);
@@ -603,9 +593,9 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         if (fixed_ws) {
             if (enc_groups > ws.group_cap)
                 return fail(NEUZIP_EUNSUPPORTED);
-            // the static array keeps what the last call left: bins, counter and flags start at zero
+            // the static array keeps what the last call left: bins, counters and flags start at zero
             hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax + 1), dim3(256), 0, stream, ws.counts, 0u,
-                               kBatchMax * 256 + 64);
+                               kBatchMax * 256 + kFlagWords);
             if (!hip_ok(hipGetLastError()))
                 return fail(NEUZIP_EHIP);
         } else {
@@ -617,40 +607,19 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         batch.lr = lr;
         batch.keep_new = keep_new ? 1u : 0u;
         touched = true;
+        uint32_t *flags = ws.counts + kBatchMax * 256;
 
-        if (reuse) {
-            // one pass: encoder constants from the stored tables, then split + encode together
-            hipLaunchKernelGGL(table_reuse_kernel, dim3(batch.count), dim3(256), 0, stream, batch, ws.enc,
-                               ws.stale);
-            switch (d_grads ? kUpdateVariant : (elem == NEUZIP_F32 ? 23 : (elem == NEUZIP_F16 ? 39 : k))) {
-            case kUpdateVariant:
-                hipLaunchKernelGGL((encode_kernel<false, 7, false, false, true>), dim3(enc_groups), dim3(kEncThreads), 0,
-                                   stream, batch, ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned,
-                                   ws.stale);
-                break;
-            case 39:
-                hipLaunchKernelGGL((encode_kernel<false, 7, false, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream,
-                                   batch, ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned, ws.stale);
-                break;
-            case 23:
-                hipLaunchKernelGGL((encode_kernel<false, 7, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream, batch,
-                                   ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned, ws.stale);
-                break;
-            case 7: launch_encode_reuse<7>(ws, batch, enc_groups, stream); break;
-            case 3: launch_encode_reuse<3>(ws, batch, enc_groups, stream); break;
-            case 1: launch_encode_reuse<1>(ws, batch, enc_groups, stream); break;
-            default: launch_encode_reuse<0>(ws, batch, enc_groups, stream); break;
-            }
-        } else {
-            switch (elem == NEUZIP_F32 ? 23 : (elem == NEUZIP_F16 ? 39 : k)) {
-            case 39:
-                hipLaunchKernelGGL((hist_split_kernel<7, false, true>), dim3(hist_groups), dim3(kHistThreads), 0, stream,
-                                   batch, ws.counts);
-                break;
-            case 23:
-                hipLaunchKernelGGL((hist_split_kernel<7, true>), dim3(hist_groups), dim3(kHistThreads), 0, stream, batch,
-                                   ws.counts);
-                break;
+        // Two launches produce everything but the final place of the words: the histogram pass, whose
+        // last workgroup per tensor builds the table (fresh statistics only), and the encoder, whose
+        // last workgroup per tensor turns the word counts into offsets and reports the stream
+        // length.  With fresh tables the encoder launch carries one more workgroup per tensor, which
+        // fills in the decoder's slot table meanwhile.
+        const int variant = d_grads ? kUpdateVariant : (elem == NEUZIP_F32 ? 23 : (elem == NEUZIP_F16 ? 39 : k));
+        if (!reuse) {
+            const dim3 grid(hist_groups), threads(kHistThreads);
+            switch (variant) {
+            case 39: hipLaunchKernelGGL((hist_split_kernel<7, false, true>), grid, threads, 0, stream, batch, ws.counts, flags); break;
+            case 23: hipLaunchKernelGGL((hist_split_kernel<7, true>), grid, threads, 0, stream, batch, ws.counts, flags); break;
             case 7: launch_hist<7>(ws, batch, block != 0, hist_groups, stream); break;
             case 3: launch_hist<3>(ws, batch, block != 0, hist_groups, stream); break;
             case 1: launch_hist<1>(ws, batch, block != 0, hist_groups, stream); break;
@@ -658,51 +627,71 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             }
             if (!hip_ok(hipGetLastError()))
                 return fail(NEUZIP_EHIP);
-            bins_dirty = true;
-            // the table kernel also returns the workspace histogram bins to zero
-            hipLaunchKernelGGL(table_kernel, dim3(batch.count), dim3(256), 0, stream, batch, ws.counts, ws.enc);
-            if (hip_ok(hipGetLastError()))
-                bins_dirty = false;
-            if (elem == NEUZIP_F16)
-                hipLaunchKernelGGL((encode_kernel<false, -1, false, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream,
-                                   batch, ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned,
-                                   static_cast<uint32_t *>(nullptr));
-            else if (elem == NEUZIP_F32)
-                hipLaunchKernelGGL((encode_kernel<false, -1, true>), dim3(enc_groups), dim3(kEncThreads), 0, stream,
-                                   batch, ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned,
-                                   static_cast<uint32_t *>(nullptr));
-            else if (block)
-                hipLaunchKernelGGL((encode_kernel<true, -1>), dim3(enc_groups), dim3(kEncThreads), 0, stream, batch,
-                                   ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned,
-                                   static_cast<uint32_t *>(nullptr));
-            else
-                hipLaunchKernelGGL((encode_kernel<false, -1>), dim3(enc_groups), dim3(kEncThreads), 0, stream, batch,
-                                   ws.enc, ws.chunk_words, ws.group_words, ws.slots, ws.pinned,
-                                   static_cast<uint32_t *>(nullptr));
         }
-        hipLaunchKernelGGL(offsets_kernel, dim3(batch.count), dim3(kScanThreads), 0, stream, batch, ws.group_words,
-                           ws.group_prefix, ws.done, ws.pinned,
-                           reuse ? static_cast<const uint32_t *>(ws.stale) : static_cast<const uint32_t *>(nullptr));
-        if (!hip_ok(hipGetLastError()))
-            return fail(NEUZIP_EHIP);
+        {
+            const dim3 grid(enc_groups + (reuse ? 0u : batch.count)), threads(kEncThreads);
+#define NZ_ENCODE(...)                                                                                             \
+    hipLaunchKernelGGL((encode_kernel<__VA_ARGS__>), grid, threads, 0, stream, batch, ws.chunk_words, ws.group_words, \
+                       ws.group_prefix, ws.slots, ws.pinned, flags)
+            if (reuse) {
+                switch (variant) {
+                case kUpdateVariant: NZ_ENCODE(false, 7, false, false, true); break;
+                case 39: NZ_ENCODE(false, 7, false, true); break;
+                case 23: NZ_ENCODE(false, 7, true); break;
+                case 7: NZ_ENCODE(false, 7); break;
+                case 3: NZ_ENCODE(false, 3); break;
+                case 1: NZ_ENCODE(false, 1); break;
+                default: NZ_ENCODE(false, 0); break;
+                }
+            } else if (elem == NEUZIP_F16) {
+                NZ_ENCODE(false, -1, false, true);
+            } else if (elem == NEUZIP_F32) {
+                NZ_ENCODE(false, -1, true);
+            } else if (block) {
+                NZ_ENCODE(true, -1);
+            } else {
+                NZ_ENCODE(false, -1);
+            }
+#undef NZ_ENCODE
+            if (!hip_ok(hipGetLastError()))
+                return fail(NEUZIP_EHIP);
+        }
 
-        // the stream lengths are data dependent: wait for them (and the statistics), which the
-        // kernels write straight into pinned host memory, the stamp last
-        HostRecord::Item fetched;  // fixed workspace: the record lies in device memory and is copied out
+        // The stream lengths are data dependent.  A blob that already has a word section (one that is
+        // compressed into again, as in a training loop) gets its compaction launched right away, into
+        // the room it has; the kernel itself leaves a tensor alone whose words turn out not to fit, or
+        // whose kept table turned out stale.  Then the host waits for the lengths (and the statistics),
+        // which the kernels write straight into pinned host memory, the stamp last.
+        bool early = false;
+        for (uint32_t j = 0; j < batch.count; ++j) {
+            const neuzip_blob *b = work[owner[j]];
+            batch.it[j].words = reinterpret_cast<uint16_t *>(b->words);
+            batch.it[j].words_cap = words_room(b);
+            early = early || batch.it[j].words_cap > 0;
+        }
+        if (early) {
+            hipLaunchKernelGGL(compact_kernel, dim3(compact_groups), dim3(kCompactThreads), 0, stream, batch, ws.slots,
+                               ws.chunk_words, ws.group_prefix);
+            if (!hip_ok(hipGetLastError()))
+                return fail(NEUZIP_EHIP);
+        }
+        HostRecord::Item fetched[kBatchMax];  // fixed workspace: the record lies in device memory and is copied out
         if (fixed_ws) {
-            if (!hip_ok(hipMemcpyAsync(&fetched, &ws.pinned->item[0], sizeof(fetched), hipMemcpyDeviceToHost, stream)) ||
+            if (!hip_ok(hipMemcpyAsync(fetched, &ws.pinned->item[0], sizeof(HostRecord::Item) * batch.count,
+                                       hipMemcpyDeviceToHost, stream)) ||
                 !hip_ok(hipStreamSynchronize(stream)))
                 return fail(NEUZIP_EHIP);
         } else if (!wait_for_record(batch.seq, stream)) {
             return fail(NEUZIP_EHIP);
         }
         uint32_t n_stale = 0;
+        bool late = false;
         for (uint32_t j = 0; j < batch.count; ++j) {
-            const HostRecord::Item &r = fixed_ws ? fetched : ws.pinned->item[j];
+            const HostRecord::Item &r = fixed_ws ? fetched[j] : ws.pinned->item[j];
             neuzip_blob *b = work[owner[j]];
             if (reuse && r.stale) {
                 // its table does not cover the new values: nothing of this pass is kept (the
-                // compaction skips a tensor without chunks); it is compressed afresh below
+                // compaction skips such a tensor); it is compressed afresh below
                 stale_src[n_stale] = d_srcs[owner[j]];
                 stale_grad[n_stale] = d_grads ? d_grads[owner[j]] : nullptr;
                 stale_n[n_stale] = n_elems[owner[j]];
@@ -714,13 +703,18 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             }
             if (r.total_words[1] != 0)
                 return fail(NEUZIP_EUNSUPPORTED);  // more than 2^32 words
-            if (fixed_ws)  // no allocation: the stream must fit the room the blob has
-                rc = pad_to(static_cast<uint64_t>(r.total_words[0]) * 2, 256) + 1024 <= b->words_bytes ? NEUZIP_OK
-                                                                                                          : NEUZIP_ENOMEM;
-            else
+            if (early && r.total_words[0] <= batch.it[j].words_cap) {
+                batch.it[j].n_chunks = 0;  // in place already: the early launch took the same decision
+            } else {
+                if (fixed_ws)  // no allocation: the stream must fit the room the blob has
+                    return fail(NEUZIP_ENOMEM);
                 rc = reserve_words(b, r.total_words[0]);
-            if (rc != NEUZIP_OK)
-                return fail(rc);
+                if (rc != NEUZIP_OK)
+                    return fail(rc);
+                batch.it[j].words = reinterpret_cast<uint16_t *>(b->words);
+                batch.it[j].words_cap = words_room(b);
+                late = true;
+            }
             b->total_words = r.total_words[0];
             if (!reuse) {
                 std::memcpy(b->h_counts, r.counts, 1024);
@@ -728,11 +722,15 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
                 b->have_counts = true;
             }
             b->has_table = true;
-            batch.it[j].words = reinterpret_cast<uint16_t *>(b->words);
         }
-        hipLaunchKernelGGL(compact_kernel, dim3(compact_groups), dim3(kCompactThreads), 0, stream, batch, ws.slots,
-                           ws.chunk_words, ws.group_prefix);
-        if (!hip_ok(hipGetLastError()) || (!fixed_ws && !hip_ok(hipEventRecord(ws.idle, stream))))
+        if (late) {
+            // the tensors that had no room (or no word section yet): now that it is allocated
+            hipLaunchKernelGGL(compact_kernel, dim3(compact_groups), dim3(kCompactThreads), 0, stream, batch, ws.slots,
+                               ws.chunk_words, ws.group_prefix);
+            if (!hip_ok(hipGetLastError()))
+                return fail(NEUZIP_EHIP);
+        }
+        if (!fixed_ws && !hip_ok(hipEventRecord(ws.idle, stream)))
             return fail(NEUZIP_EHIP);
         stale_count = n_stale;
     }
@@ -1048,9 +1046,8 @@ namespace {
 constexpr uint32_t kFixedChunks = static_cast<uint32_t>(NEUZIP_NOALLOC_MAX_ELEMS / kChunk);
 constexpr uint32_t kFixedGroups = kFixedChunks / kChunksPerGroup;
 static_assert(NEUZIP_NOALLOC_MAX_ELEMS % (kChunk * kChunksPerGroup) == 0, "whole encoder groups");
-constexpr uint64_t kFixedEncAt = 0;                                                        // 256 encoder constants
-constexpr uint64_t kFixedCountsAt = kFixedEncAt + 256 * sizeof(EncSym);                    // bins, counter, flags
-constexpr uint64_t kFixedRecordAt = kFixedCountsAt + pad_to((kBatchMax * 256 + 64) * 4, 256);
+constexpr uint64_t kFixedCountsAt = 0;                                                     // bins, counters, flags
+constexpr uint64_t kFixedRecordAt = kFixedCountsAt + pad_to((kBatchMax * 256 + kFlagWords) * 4, 256);
 constexpr uint64_t kFixedChunkWordsAt = kFixedRecordAt + pad_to(sizeof(HostRecord), 256);
 constexpr uint64_t kFixedGroupWordsAt = kFixedChunkWordsAt + pad_to((kFixedChunks + 4) * 4, 256);
 constexpr uint64_t kFixedGroupPrefixAt = kFixedGroupWordsAt + pad_to((kFixedGroups + 4) * 4, 256);
@@ -1109,10 +1106,7 @@ int neuzip_compress_noalloc(const void *d_src, uint64_t n_elems, int dtype, int 
         return rc;
     Workspace ws;
     ws.device = device;
-    ws.enc = reinterpret_cast<EncSym *>(base + kFixedEncAt);
     ws.counts = reinterpret_cast<uint32_t *>(base + kFixedCountsAt);
-    ws.done = ws.counts + kBatchMax * 256;
-    ws.stale = ws.done + 8;
     ws.pinned = reinterpret_cast<HostRecord *>(base + kFixedRecordAt);  // device memory here: copied out, not read in place
     ws.chunk_words = reinterpret_cast<uint32_t *>(base + kFixedChunkWordsAt);
     ws.group_words = reinterpret_cast<uint32_t *>(base + kFixedGroupWordsAt);

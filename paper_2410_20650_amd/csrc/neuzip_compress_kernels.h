@@ -1,6 +1,8 @@
-// Compression kernels of the NeuZip codec for gfx950: histogram + sign|mantissa split (with and
-// without block-wise normalisation), frequency table, chunked rANS encoder, offsets scan,
-// compaction.  Every kernel works on a batch of up to 8 tensors described by a CompressBatch.
+// Compression kernels of the NeuZip codec for gfx950, three launches per call: histogram +
+// sign|mantissa split (with and without block-wise normalisation), whose last workgroup per tensor
+// builds the frequency table; the chunked rANS encoder, whose last workgroup per tensor turns the
+// word counts into offsets; the compaction.  Every kernel works on a batch of up to 8 tensors
+// described by a CompressBatch.
 #pragma once
 
 #include "neuzip_format.h"
@@ -186,13 +188,232 @@ __device__ __forceinline__ uint32_t source_word(const void *__restrict__ src, ui
 }
 
 // ------------------------------------------------------------------------------------------
+// Counters and flags of a compress call: 64 words of the workspace behind the histogram bins.  All
+// are zero between calls: whoever takes the last ticket of a counter sets it back.
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kFlagHistDone = 0;   // [8] histogram workgroups of tensor i that have merged their bins
+constexpr uint32_t kFlagEncDone = 8;    // [8] encoder workgroups of tensor i that have posted their word count
+constexpr uint32_t kFlagAllDone = 16;   // tensors of the batch whose offsets are complete
+constexpr uint32_t kFlagStale = 24;     // [8] recompression met an exponent without room in tensor i's table
+constexpr uint32_t kFlagWords = 64;
+
+// Stores and atomics issued so far by this wave have been performed (their acknowledgements are in)
+// before anything that follows: what a workgroup does before it takes a ticket of a completion
+// counter.  The counters, and the data the ticket's last holder reads, are accessed with
+// device-scope atomics, which bypass the per-XCD caches, so no cache write-back is needed.
+__device__ __forceinline__ void wait_for_memory_acks() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// ------------------------------------------------------------------------------------------
+// Counts -> frequencies that sum to 4096, cumulative table.  256 threads, thread s owns symbol s.
+// Integer only:
+//   f = max(1, floor(cnt * 4096 / N)) for symbols that occur, else 0; a shortfall goes to the
+//   most frequent symbol (lowest value on a tie); an excess is taken one unit at a time from
+//   the symbol whose f is largest at that moment (lowest value on a tie).
+// ------------------------------------------------------------------------------------------
+__device__ inline uint64_t block_max_u64(uint64_t v, uint64_t *scratch)
+{
+    // 256 threads = 4 waves
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint64_t o = __shfl_xor(v, off, 64);
+        v = o > v ? o : v;
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0)
+        scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint64_t r = scratch[0];
+    for (int i = 1; i < 4; ++i)
+        r = scratch[i] > r ? scratch[i] : r;
+    return r;
+}
+
+__device__ inline uint64_t block_sum_u64(uint64_t v, uint64_t *scratch)
+{
+    for (int off = 32; off > 0; off >>= 1)
+        v += __shfl_xor(v, off, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0)
+        scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return scratch[0] + scratch[1] + scratch[2] + scratch[3];
+}
+
+// Inclusive sum of v over the 256 threads of the workgroup, left in scan[] as well.
+__device__ inline uint32_t block_scan_u32(uint32_t v, uint64_t *scratch, uint32_t *scan)
+{
+    const uint32_t s = threadIdx.x;
+    uint32_t incl = v;
+#pragma unroll
+    for (uint32_t d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d, 64);
+        if ((s & 63u) >= d)
+            incl += o;
+    }
+    __syncthreads();
+    if ((s & 63u) == 63u)
+        scratch[s >> 6] = incl;
+    __syncthreads();
+    for (uint32_t wv = 0; wv < (s >> 6); ++wv)
+        incl += static_cast<uint32_t>(scratch[wv]);
+    scan[s] = incl;
+    __syncthreads();
+    return incl;
+}
+
+// Encoder constants of a symbol.  A symbol without room in the table (f = 0) gets constants that
+// leave the state as it is and a zero reciprocal, by which the encoder recognises it.
+__device__ inline EncSym encoder_constants(uint32_t f, uint32_t cum)
+{
+    EncSym e = {0.0f, 0xFFFFFFFFu, 0u, 1u};
+    if (f > 0) {
+        e.rcp = __fmul_rn(__fdiv_rn(1.0f, static_cast<float>(f)), 1.0f - 0x1p-21f);
+        e.limit = f >= kM ? 0xFFFFFFFFu : (f << 20);  // f = 4096 only for a one-symbol tensor: never renormalises
+        e.cmpl_cum = (kM - f) | (cum << 16);
+        e.f = f;
+    }
+    return e;
+}
+
+// The table of one tensor from its exponent counts (cnt: the count of symbol threadIdx.x); also
+// keeps the counts in the blob and clears its status words.  scratch: 4 words of 64 bits in LDS.
+__device__ inline void build_table(const CompressItem &it, uint64_t cnt, uint64_t *scratch, uint32_t *scan)
+{
+    TableBlock *__restrict__ tb = it.tb;
+    const uint32_t s = threadIdx.x;
+    tb->counts[s] = static_cast<uint32_t>(cnt);
+    if (s < 4)
+        tb->status[s] = 0;
+    const uint64_t total = block_sum_u64(cnt, scratch);
+    uint32_t f = 0;
+    if (total > 0) {
+        // With a guard band every exponent from (lowest occurring - guard) to (highest occurring +
+        // guard), and exponent 0 (an update cancels exactly to +-0 now and then), is treated as
+        // occurring: it gets f = 1 and can be coded after a weight update without a new table.
+        bool member = cnt > 0;
+        const uint32_t guard = it.guard;
+        if (guard > 0) {
+            const uint32_t hi = static_cast<uint32_t>(block_max_u64(cnt > 0 ? s + 1 : 0, scratch)) - 1;
+            const uint32_t lo = 256 - static_cast<uint32_t>(block_max_u64(cnt > 0 ? 256 - s : 0, scratch));
+            member = s == 0 || (s + guard >= lo && s <= hi + guard);
+        }
+        if (member) {
+            const uint64_t scaled = cnt * kM / total;
+            f = scaled < 1 ? 1u : static_cast<uint32_t>(scaled);
+        }
+        const int32_t sum = static_cast<int32_t>(block_sum_u64(f, scratch));
+        int32_t rest = static_cast<int32_t>(kM) - sum;
+        if (rest > 0) {
+            const uint64_t key = (cnt << 8) | (255u - s);
+            const uint64_t best = block_max_u64(key, scratch);
+            if (key == best)
+                f += static_cast<uint32_t>(rest);
+        }
+        if (rest < 0) {
+            // Usual case: the most frequent symbol stays the largest through all -rest decrements
+            // (its key after -rest - 1 of them still beats the runner-up's), so it takes them all.
+            const uint64_t key = (static_cast<uint64_t>(f) << 8) | (255u - s);
+            const uint64_t best = block_max_u64(key, scratch);
+            const uint64_t second = block_max_u64(key == best ? 0 : key, scratch);
+            const uint64_t best_late = best - (static_cast<uint64_t>(-rest - 1) << 8);
+            if ((best >> 8) >= static_cast<uint64_t>(-rest) && best_late > second) {
+                if (key == best)
+                    f -= static_cast<uint32_t>(-rest);
+                rest = 0;
+            }
+        }
+        while (rest < 0) {  // general case, one unit at a time; uniform across the workgroup
+            const uint64_t key = (static_cast<uint64_t>(f) << 8) | (255u - s);
+            const uint64_t best = block_max_u64(key, scratch);
+            if (key == best)
+                --f;
+            ++rest;
+        }
+    }
+    const uint32_t incl = block_scan_u32(f, scratch, scan);
+    tb->freq[s] = static_cast<uint16_t>(f);
+    tb->cum[s] = static_cast<uint16_t>(incl - f);
+    if (s == 255)
+        tb->cum[256] = static_cast<uint16_t>(incl);
+    // the only exponent value of the tensor, if there is just one (its f is 4096), else 256
+    const uint32_t lone = static_cast<uint32_t>(block_max_u64(f == kM ? s + 1 : 0, scratch));
+    if (s == 0)
+        tb->lone = lone ? lone - 1 : 256;
+}
+
+// Decoder slot table of a tensor from the frequencies its table block holds:
+// lut[slot] = symbol | f << 8 | (slot - cum[symbol]) << 20.  256 threads; thread s fills slots
+// s, s + 256, ...; scan[t] = cum[t + 1].  The 16 binary searches of a thread are independent, so
+// their LDS reads overlap.
+__device__ inline void build_slot_table(TableBlock *__restrict__ tb, uint64_t *scratch, uint32_t *scan)
+{
+    const uint32_t s = threadIdx.x;
+    block_scan_u32(tb->freq[s], scratch, scan);
+    if (scan[255] != kM)
+        return;  // an empty table: nothing decodes through it
+    constexpr uint32_t kPer = kM / 256;
+    uint32_t lo[kPer], hi[kPer];
+#pragma unroll
+    for (uint32_t r = 0; r < kPer; ++r) {
+        lo[r] = 0;
+        hi[r] = 255;
+    }
+#pragma unroll
+    for (uint32_t step = 0; step < 8; ++step) {
+#pragma unroll
+        for (uint32_t r = 0; r < kPer; ++r) {  // smallest t with cum[t + 1] > slot
+            const uint32_t mid = (lo[r] + hi[r]) >> 1;
+            const bool above = scan[mid] > s + 256 * r;
+            hi[r] = above ? mid : hi[r];
+            lo[r] = above ? lo[r] : (mid < hi[r] ? mid + 1 : hi[r]);
+        }
+    }
+#pragma unroll
+    for (uint32_t r = 0; r < kPer; ++r) {
+        const uint32_t slot = s + 256 * r, t = lo[r];
+        const uint32_t begin = t ? scan[t - 1] : 0u;
+        tb->lut[slot] = t | (((scan[t] - begin) & 0xFFFu) << 8) | ((slot - begin) << 20);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// End of a histogram workgroup: thread b sums the 32 copies of bin b (starting at a rotated copy to
+// spread the banks) into the workspace bins.  The workgroup that finishes last for its tensor then
+// takes the totals, leaves the bins at zero for the next call, and builds the tensor's table, so
+// that no launch of its own is needed for that.
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kHistCopies = 32;
+__device__ __forceinline__ void finish_histogram(const CompressBatch &b, uint32_t item, uint32_t wgs,
+                                                 uint32_t *__restrict__ bins, uint32_t *__restrict__ counts,
+                                                 uint32_t *__restrict__ flags)
+{
+    __syncthreads();
+    const uint32_t s = threadIdx.x;
+    uint32_t sum = 0;
+#pragma unroll 8
+    for (uint32_t i = 0; i < kHistCopies; ++i)
+        sum += bins[s * kHistCopies + ((i + s) & (kHistCopies - 1))];
+    if (sum)
+        atomicAdd(&counts[s], sum);
+    wait_for_memory_acks();
+    __syncthreads();  // all adds of this workgroup are in; the bins in LDS are free from here on
+    if (s == 0)
+        bins[0] = atomicAdd(&flags[kFlagHistDone + item], 1u) == wgs - 1 ? 1u : 0u;
+    __syncthreads();
+    if (!bins[0])
+        return;
+    if (s == 0)
+        flags[kFlagHistDone + item] = 0;
+    const uint64_t cnt = atomicExch(&counts[s], 0u);
+    build_table(b.it[item], cnt, reinterpret_cast<uint64_t *>(bins + 16), bins + 64);
+}
+
+// ------------------------------------------------------------------------------------------
 // Kernel 1: exponent histogram fused with the sign|mantissa split (Alg. 1 "split").
 // One pass over the bf16 words: 2 B/elem read, (k+1)/8 B/elem written.  Counts go to 32
 // bank-private copies of the 256 bins in LDS (copy = lane mod 32, so the 64 lanes of a wave
 // hit 32 different banks whatever the symbol skew is), then one global atomic per bin.
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kHistThreads = 256;
-constexpr uint32_t kHistCopies = 32;
 
 // Which tensor of the batch a workgroup of one of the wide launches works on.
 struct ItemSlot {
@@ -214,7 +435,8 @@ __device__ __forceinline__ ItemSlot item_of_workgroup(const CompressBatch &b)
 
 template <int KB, bool WIDE = false, bool HALF = false>
 __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const CompressBatch b,
-                                                                 uint32_t *__restrict__ counts_ws)
+                                                                 uint32_t *__restrict__ counts_ws,
+                                                                 uint32_t *__restrict__ flags)
 {
     const ItemSlot slot = item_of_workgroup<&CompressItem::hist_end>(b);
     const void *__restrict__ src = b.it[slot.item].src;
@@ -280,17 +502,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const Compress
         if (filled)
             sm[(n - 1) / per_byte] = static_cast<uint8_t>(acc);
     }
-    __syncthreads();
-    // thread b sums the 32 copies of bin b, starting at a rotated copy to spread the banks
-    {
-        const uint32_t b = threadIdx.x;
-        uint32_t sum = 0;
-#pragma unroll 8
-        for (uint32_t i = 0; i < kHistCopies; ++i)
-            sum += bins[b * kHistCopies + ((i + b) & (kHistCopies - 1))];
-        if (sum)
-            atomicAdd(&counts[b], sum);
-    }
+    finish_histogram(b, slot.item, slot.wgs, bins, counts, flags);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -301,7 +513,8 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const Compress
 // ------------------------------------------------------------------------------------------
 template <int KB>
 __global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const CompressBatch b,
-                                                                      uint32_t *__restrict__ counts_ws)
+                                                                      uint32_t *__restrict__ counts_ws,
+                                                                      uint32_t *__restrict__ flags)
 {
     const ItemSlot slot = item_of_workgroup<&CompressItem::hist_end>(b);
     const uint16_t *__restrict__ src = static_cast<const uint16_t *>(b.it[slot.item].src);
@@ -373,204 +586,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const Com
                 sm[(first + t) / per_byte] = static_cast<uint8_t>(packed >> (t * (KB + 1)));
         }
     }
-    __syncthreads();
-    {
-        const uint32_t b = threadIdx.x;
-        uint32_t sum = 0;
-#pragma unroll 8
-        for (uint32_t i = 0; i < kHistCopies; ++i)
-            sum += bins[b * kHistCopies + ((i + b) & (kHistCopies - 1))];
-        if (sum)
-            atomicAdd(&counts[b], sum);
-    }
-}
-
-// ------------------------------------------------------------------------------------------
-// Kernel 2: counts -> frequencies that sum to 4096, cumulative table, encoder constants.
-// One workgroup of 256 threads, thread s owns symbol s.  Integer only:
-//   f = max(1, floor(cnt * 4096 / N)) for symbols that occur, else 0; a shortfall goes to the
-//   most frequent symbol (lowest value on a tie); an excess is taken one unit at a time from
-//   the symbol whose f is largest at that moment (lowest value on a tie).
-// ------------------------------------------------------------------------------------------
-__device__ inline uint64_t block_max_u64(uint64_t v, uint64_t *scratch)
-{
-    // 256 threads = 4 waves
-    for (int off = 32; off > 0; off >>= 1) {
-        const uint64_t o = __shfl_xor(v, off, 64);
-        v = o > v ? o : v;
-    }
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0)
-        scratch[threadIdx.x >> 6] = v;
-    __syncthreads();
-    uint64_t r = scratch[0];
-    for (int i = 1; i < 4; ++i)
-        r = scratch[i] > r ? scratch[i] : r;
-    return r;
-}
-
-__device__ inline uint64_t block_sum_u64(uint64_t v, uint64_t *scratch)
-{
-    for (int off = 32; off > 0; off >>= 1)
-        v += __shfl_xor(v, off, 64);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0)
-        scratch[threadIdx.x >> 6] = v;
-    __syncthreads();
-    return scratch[0] + scratch[1] + scratch[2] + scratch[3];
-}
-
-// Encoder constants of a symbol.  A symbol without room in the table (f = 0) gets constants that
-// leave the state as it is and a zero reciprocal, by which the encoder recognises it.
-__device__ inline EncSym encoder_constants(uint32_t f, uint32_t cum)
-{
-    EncSym e = {0.0f, 0xFFFFFFFFu, 0u, 1u};
-    if (f > 0) {
-        e.rcp = __fmul_rn(__fdiv_rn(1.0f, static_cast<float>(f)), 1.0f - 0x1p-21f);
-        e.limit = f >= kM ? 0xFFFFFFFFu : (f << 20);  // f = 4096 only for a one-symbol tensor: never renormalises
-        e.cmpl_cum = (kM - f) | (cum << 16);
-        e.f = f;
-    }
-    return e;
-}
-
-__global__ __launch_bounds__(256) void table_kernel(const CompressBatch b, uint32_t *__restrict__ counts_all,
-                                                    EncSym *__restrict__ enc_all)
-{
-    // one workgroup per tensor of the batch
-    uint32_t *__restrict__ counts_ws = counts_all + 256 * blockIdx.x;
-    TableBlock *__restrict__ tb = b.it[blockIdx.x].tb;
-    EncSym *__restrict__ enc = enc_all + 256 * blockIdx.x;
-    __shared__ uint64_t scratch[4];
-    __shared__ uint32_t scan[256];
-    const uint32_t s = threadIdx.x;
-    // the histogram was accumulated in the workspace; keep a copy in the blob and leave the
-    // workspace bins at zero for the next tensor
-    const uint64_t cnt = counts_ws[s];
-    counts_ws[s] = 0;
-    tb->counts[s] = static_cast<uint32_t>(cnt);
-    if (s < 4)
-        tb->status[s] = 0;
-    const uint64_t total = block_sum_u64(cnt, scratch);
-    uint32_t f = 0;
-    if (total > 0) {
-        // With a guard band every exponent from (lowest occurring - guard) to (highest occurring +
-        // guard), and exponent 0 (an update cancels exactly to +-0 now and then), is treated as
-        // occurring: it gets f = 1 and can be coded after a weight update without a new table.
-        bool member = cnt > 0;
-        const uint32_t guard = b.it[blockIdx.x].guard;
-        if (guard > 0) {
-            const uint32_t hi = static_cast<uint32_t>(block_max_u64(cnt > 0 ? s + 1 : 0, scratch)) - 1;
-            const uint32_t lo = 256 - static_cast<uint32_t>(block_max_u64(cnt > 0 ? 256 - s : 0, scratch));
-            member = s == 0 || (s + guard >= lo && s <= hi + guard);
-        }
-        if (member) {
-            const uint64_t scaled = cnt * kM / total;
-            f = scaled < 1 ? 1u : static_cast<uint32_t>(scaled);
-        }
-        const int32_t sum = static_cast<int32_t>(block_sum_u64(f, scratch));
-        int32_t rest = static_cast<int32_t>(kM) - sum;
-        if (rest > 0) {
-            const uint64_t key = (cnt << 8) | (255u - s);
-            const uint64_t best = block_max_u64(key, scratch);
-            if (key == best)
-                f += static_cast<uint32_t>(rest);
-        }
-        if (rest < 0) {
-            // Usual case: the most frequent symbol stays the largest through all -rest decrements
-            // (its key after -rest - 1 of them still beats the runner-up's), so it takes them all.
-            const uint64_t key = (static_cast<uint64_t>(f) << 8) | (255u - s);
-            const uint64_t best = block_max_u64(key, scratch);
-            const uint64_t second = block_max_u64(key == best ? 0 : key, scratch);
-            const uint64_t best_late = best - (static_cast<uint64_t>(-rest - 1) << 8);
-            if ((best >> 8) >= static_cast<uint64_t>(-rest) && best_late > second) {
-                if (key == best)
-                    f -= static_cast<uint32_t>(-rest);
-                rest = 0;
-            }
-        }
-        while (rest < 0) {  // general case, one unit at a time; uniform across the workgroup
-            const uint64_t key = (static_cast<uint64_t>(f) << 8) | (255u - s);
-            const uint64_t best = block_max_u64(key, scratch);
-            if (key == best)
-                --f;
-            ++rest;
-        }
-    }
-    // inclusive cumulative sum over the 256 symbols: wave scan, then the sums of the waves before
-    {
-        uint32_t incl = f;
-#pragma unroll
-        for (uint32_t d = 1; d < 64; d <<= 1) {
-            const uint32_t o = __shfl_up(incl, d, 64);
-            if ((s & 63u) >= d)
-                incl += o;
-        }
-        __syncthreads();
-        if ((s & 63u) == 63u)
-            scratch[s >> 6] = incl;
-        __syncthreads();
-        for (uint32_t wv = 0; wv < (s >> 6); ++wv)
-            incl += static_cast<uint32_t>(scratch[wv]);
-        scan[s] = incl;
-    }
-    __syncthreads();
-    const uint32_t cum = scan[s] - f;
-    tb->freq[s] = static_cast<uint16_t>(f);
-    tb->cum[s] = static_cast<uint16_t>(cum);
-    if (s == 255)
-        tb->cum[256] = static_cast<uint16_t>(scan[255]);
-    if (s == 0)
-        tb->lone = 256;
-    __syncthreads();
-    if (f == kM)
-        tb->lone = s;
-
-    // encoder constants first: the encode kernel waits for them, the decoder table is not urgent
-    enc[s] = encoder_constants(f, cum);
-
-    // decoder slot table: thread s fills slots s, s + 256, ...; scan[t] = cum[t + 1].  The 16
-    // binary searches of a thread are independent, so their LDS reads overlap.
-    if (total > 0) {
-        constexpr uint32_t kPer = kM / 256;
-        uint32_t lo[kPer], hi[kPer];
-#pragma unroll
-        for (uint32_t r = 0; r < kPer; ++r) {
-            lo[r] = 0;
-            hi[r] = 255;
-        }
-#pragma unroll
-        for (uint32_t step = 0; step < 8; ++step) {
-#pragma unroll
-            for (uint32_t r = 0; r < kPer; ++r) {  // smallest t with cum[t + 1] > slot
-                const uint32_t mid = (lo[r] + hi[r]) >> 1;
-                const bool above = scan[mid] > s + 256 * r;
-                hi[r] = above ? mid : hi[r];
-                lo[r] = above ? lo[r] : (mid < hi[r] ? mid + 1 : hi[r]);
-            }
-        }
-#pragma unroll
-        for (uint32_t r = 0; r < kPer; ++r) {
-            const uint32_t slot = s + 256 * r, t = lo[r];
-            const uint32_t begin = t ? scan[t - 1] : 0u;
-            tb->lut[slot] = t | (((scan[t] - begin) & 0xFFFu) << 8) | ((slot - begin) << 20);
-        }
-    }
-}
-
-// ------------------------------------------------------------------------------------------
-// Kernel 2b: recompression with the table a blob already holds (Alg. 1 compresses every weight
-// again after its update; the exponent statistics barely move from one step to the next).  Only
-// the encoder constants are rebuilt, from the stored frequencies; the stale flags are cleared.
-// ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void table_reuse_kernel(const CompressBatch b, EncSym *__restrict__ enc_all,
-                                                          uint32_t *__restrict__ stale)
-{
-    const TableBlock *__restrict__ tb = b.it[blockIdx.x].tb;
-    const uint32_t s = threadIdx.x;
-    enc_all[256 * blockIdx.x + s] = encoder_constants(tb->freq[s], tb->cum[s]);
-    if (s == 0)
-        stale[blockIdx.x] = 0;
+    finish_histogram(b, slot.item, slot.wgs, bins, counts, flags);
 }
 
 // The weight update of the backward loop (Alg. 1: W_hat <- W_hat - lr * grad) on the two halves of
@@ -700,18 +716,28 @@ __device__ __forceinline__ void ring_flush(uint32_t wp_before, uint32_t wp_after
 // codes it, so the new weight is read once and never re-read from memory.
 template <bool NORM, int SPLIT, bool WIDE = false, bool HALF = false, bool UPD = false>
 __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch b,
-                                                            const EncSym *__restrict__ enc_all,
                                                             uint32_t *__restrict__ chunk_words_all,
                                                             uint32_t *__restrict__ group_words_all,
+                                                            uint64_t *__restrict__ group_prefix_all,
                                                             uint16_t *__restrict__ slots_all,
                                                             HostRecord *__restrict__ record,
-                                                            uint32_t *__restrict__ stale)
+                                                            uint32_t *__restrict__ flags)
 {
     static_assert(!(NORM && SPLIT >= 0), "the one-pass variant has no block maxima to normalise with");
     static_assert(!(WIDE || HALF) || (!NORM && (SPLIT < 0 || SPLIT == 7)), "binary32 and binary16 tensors are lossless only");
     static_assert(!(WIDE && HALF), "one element type");
     static_assert(!UPD || (SPLIT == 7 && !NORM && !WIDE && !HALF), "only lossless bf16 weights are trained");
     constexpr int KB = SPLIT >= 0 ? SPLIT : 7;
+    __shared__ uint4 enc_raw[256];
+    __shared__ __align__(32) uint16_t rings[kEncThreads * kRingWords];
+    __shared__ uint32_t group_chunk[kEncThreads / kStates];
+    __shared__ uint64_t scratch[4];
+    if (blockIdx.x >= b.it[b.count - 1].enc_end) {
+        // the workgroups behind the encoders' (fresh tables only): one per tensor, it fills in the
+        // decoder's slot table while the others encode
+        build_slot_table(b.it[blockIdx.x - b.it[b.count - 1].enc_end].tb, scratch, reinterpret_cast<uint32_t *>(rings));
+        return;
+    }
     const ItemSlot slot_id = item_of_workgroup<&CompressItem::enc_end>(b);
     const CompressItem &it = b.it[slot_id.item];
     const void *__restrict__ src = it.src;
@@ -729,12 +755,13 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     const uint32_t group = it.group_base + slot_id.wg;
     uint32_t *__restrict__ chunk_words = chunk_words_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup;
     uint16_t *__restrict__ slots = slots_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup * kStates * kRunCap;
-    const EncSym *__restrict__ enc_g = enc_all + 256 * slot_id.item;
+    uint32_t *__restrict__ stale = flags + kFlagStale;
 
-    __shared__ uint4 enc_raw[256];
-    __shared__ __align__(32) uint16_t rings[kEncThreads * kRingWords];
-    __shared__ uint32_t group_chunk[kEncThreads / kStates];
-    enc_raw[threadIdx.x] = reinterpret_cast<const uint4 *>(enc_g)[threadIdx.x];
+    // encoder constants of the 256 symbols, from the table the blob holds
+    {
+        const EncSym e = encoder_constants(tb->freq[threadIdx.x], tb->cum[threadIdx.x]);
+        enc_raw[threadIdx.x] = make_uint4(__float_as_uint(e.rcp), e.limit, e.cmpl_cum, e.f);
+    }
     if (SPLIT < 0 && slot_id.wg == 0) {
         // statistics for the host: posted early, they land long before this kernel ends
         record->item[slot_id.item].counts[threadIdx.x] = tb->counts[threadIdx.x];
@@ -855,8 +882,10 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
         }
     }
     if constexpr (SPLIT >= 0) {
-        if (least_rcp == 0.0f)
+        if (least_rcp == 0.0f) {
             atomicOr(&stale[slot_id.item], 1u);
+            wait_for_memory_acks();
+        }
     }
     const uint32_t len = kRunCap - st.wp;
     if (live) {
@@ -881,78 +910,62 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
         uint32_t total = 0;
         for (uint32_t i = 0; i < kEncThreads / kStates; ++i)
             total += group_chunk[i];
-        group_words_all[group] = total;
+        // device-scope store and ticket: the workgroup that takes the last ticket reads all of them
+        __hip_atomic_store(&group_words_all[group], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        wait_for_memory_acks();
+        group_chunk[0] = atomicAdd(&flags[kFlagEncDone + slot_id.item], 1u) == slot_id.wgs - 1 ? 1u : 0u;
     }
-}
-
-// ------------------------------------------------------------------------------------------
-// Kernel 4: exclusive prefix sum of the words per encoder workgroup (16 chunks each).  One
-// workgroup walks the groups in tiles of 4096; the per-chunk offsets follow from these in the
-// compaction kernel.  The total goes to the blob's last offset and to the host.
-// ------------------------------------------------------------------------------------------
-constexpr uint32_t kScanThreads = 1024;
-
-__global__ __launch_bounds__(kScanThreads) void offsets_kernel(const CompressBatch b,
-                                                              const uint32_t *__restrict__ group_words_all,
-                                                              uint64_t *__restrict__ group_prefix_all,
-                                                              uint32_t *__restrict__ done,
-                                                              HostRecord *__restrict__ record,
-                                                              const uint32_t *__restrict__ stale)
-{
-    // one workgroup per tensor of the batch
-    const CompressItem &it = b.it[blockIdx.x];
-    const uint32_t n_groups = (it.n_chunks + kChunksPerGroup - 1) / kChunksPerGroup;
-    const uint32_t *__restrict__ group_words = group_words_all + it.group_base;
-    uint64_t *__restrict__ group_prefix = group_prefix_all + it.group_base;
-    uint32_t *__restrict__ last_offset = it.offsets + it.n_chunks;
-    __shared__ uint64_t wave_sum[kScanThreads / 64];
-    __shared__ uint64_t carry_s;
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint64_t carry = 0;
-    for (uint32_t tile = 0; tile < n_groups; tile += kScanThreads * 4) {
-        const uint32_t i0 = tile + tid * 4;
-        uint32_t v[4];
-#pragma unroll
-        for (uint32_t r = 0; r < 4; ++r)
-            v[r] = i0 + r < n_groups ? group_words[i0 + r] : 0u;
-        const uint64_t mine = static_cast<uint64_t>(v[0]) + v[1] + v[2] + v[3];
-        uint64_t incl = mine;  // inclusive scan over the wave
+    __syncthreads();
+    if (!group_chunk[0])
+        return;
+    // ---- last workgroup of this tensor: exclusive prefix sum of the words per encoder workgroup (the
+    // per-chunk offsets follow from these in the compaction kernel); the total goes to the blob's last
+    // offset and to the host
+    {
+        const uint32_t tid = threadIdx.x;
+        const uint32_t n_groups = slot_id.wgs;
+        const uint32_t *group_words = group_words_all + it.group_base;
+        uint64_t *__restrict__ group_prefix = group_prefix_all + it.group_base;
+        const uint32_t per = (n_groups + kEncThreads - 1) / kEncThreads;
+        const uint32_t first = tid * per;
+        uint64_t mine = 0;
+        for (uint32_t i = first; i < first + per && i < n_groups; ++i)
+            mine += __hip_atomic_load(&group_words[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // exclusive sum of `mine` over the 256 threads
+        uint64_t incl = mine;
 #pragma unroll
         for (uint32_t d = 1; d < 64; d <<= 1) {
             const uint64_t o = __shfl_up(incl, d, 64);
-            if (lane >= d)
+            if ((tid & 63u) >= d)
                 incl += o;
         }
-        if (lane == 63)
-            wave_sum[wave] = incl;
+        if ((tid & 63u) == 63u)
+            scratch[tid >> 6] = incl;
         __syncthreads();
-        uint64_t before = carry;
-        for (uint32_t wv = 0; wv < wave; ++wv)
-            before += wave_sum[wv];
-        uint64_t run = before + incl - mine;
-#pragma unroll
-        for (uint32_t r = 0; r < 4; ++r) {
-            if (i0 + r < n_groups)
-                group_prefix[i0 + r] = run;
-            run += v[r];
+        uint64_t run = incl - mine;
+        for (uint32_t wv = 0; wv < (tid >> 6); ++wv)
+            run += scratch[wv];
+        for (uint32_t i = first; i < first + per && i < n_groups; ++i) {
+            group_prefix[i] = run;
+            run += __hip_atomic_load(&group_words[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        if (tid == kScanThreads - 1)
-            carry_s = run;
-        __syncthreads();
-        carry = carry_s;
-    }
-    if (tid == 0) {
-        last_offset[0] = static_cast<uint32_t>(carry);
-        last_offset[1] = 0;
-        record->item[blockIdx.x].total_words[0] = static_cast<uint32_t>(carry);
-        record->item[blockIdx.x].total_words[1] = static_cast<uint32_t>(carry >> 32);  // non-zero: too long for 32-bit offsets
-        record->item[blockIdx.x].stale = stale ? stale[blockIdx.x] : 0u;
-        // the workgroup that finishes last publishes the stamp and rearms the counter
-        __threadfence_system();
-        if (atomicAdd(done, 1u) == b.count - 1) {
-            *done = 0;
+        if (tid == kEncThreads - 1) {
+            const uint32_t was_stale = SPLIT >= 0 ? atomicExch(&stale[slot_id.item], 0u) : 0u;
+            uint32_t *__restrict__ last_offset = it.offsets + n_chunks;
+            last_offset[0] = static_cast<uint32_t>(run);
+            // the word behind the last offset tells the compaction to leave this tensor alone
+            last_offset[1] = (was_stale || (run >> 32)) ? 1u : 0u;
+            record->item[slot_id.item].total_words[0] = static_cast<uint32_t>(run);
+            record->item[slot_id.item].total_words[1] = static_cast<uint32_t>(run >> 32);  // non-zero: too long for 32-bit offsets
+            record->item[slot_id.item].stale = was_stale;
+            flags[kFlagEncDone + slot_id.item] = 0;
+            // the tensor that finishes last publishes the stamp and sets the counter back
             __threadfence_system();
-            __hip_atomic_store(&record->seq, b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+            if (atomicAdd(&flags[kFlagAllDone], 1u) == b.count - 1) {
+                flags[kFlagAllDone] = 0;
+                __threadfence_system();
+                __hip_atomic_store(&record->seq, b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+            }
         }
     }
 }
@@ -974,6 +987,11 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const Compress
     const ItemSlot slot_id = item_of_workgroup<&CompressItem::compact_end>(b);
     const CompressItem &it = b.it[slot_id.item];
     const uint32_t n_chunks = it.n_chunks;
+    // The launch may have been made before the host knew the stream's length (into the room the blob
+    // had): a tensor whose words do not fit that room, or whose kept table turned out stale, is left
+    // alone (the same for all workgroups of the tensor).
+    if (n_chunks == 0 || it.offsets[n_chunks + 1] != 0 || it.offsets[n_chunks] > it.words_cap)
+        return;
     const uint8_t *__restrict__ lens = it.lens;
     uint32_t *__restrict__ offsets = it.offsets;
     uint16_t *__restrict__ words = it.words;

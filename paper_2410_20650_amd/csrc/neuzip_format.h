@@ -51,7 +51,8 @@ struct TableBlock {
 };
 static_assert(sizeof(TableBlock) % 256 == 0, "table block keeps later sections aligned");
 
-// Per-symbol encoder constants (16 bytes, one ds_read_b128).
+// Per-symbol encoder constants (16 bytes, one ds_read_b128), derived by every encoder workgroup from
+// the frequencies and cumulative frequencies of the tensor's table.
 //   The step is x <- (x / f) * M + (x mod f) + cum = q * (M - f) + x + cum with q = floor(x / f).
 //   limit: the state is renormalised before the step when x >= limit = f << 20, so q < 2^20.
 //   rcp: a float slightly below 1/f, (1/f)(1 - 2^-21).  float(x) * rcp, truncated, is q or q - 1
@@ -83,7 +84,8 @@ struct CompressItem {
     uint8_t *coef;
     uint16_t *low;         // binary32 tensors: the plane of lower halves
     const uint16_t *grad;  // weight step fused into the encoder: the gradient (src is then written too)
-    uint16_t *words;       // known only after the stream length has been read back
+    uint16_t *words;       // the blob's word section (the compaction's destination) ...
+    uint64_t words_cap;    // ... and the words it has room for
     uint32_t n_chunks;
     uint32_t block;        // 0: no block-wise normalisation
     uint32_t guard;        // exponents this far outside the occupied range keep f = 1 in the table
