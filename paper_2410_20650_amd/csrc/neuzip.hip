@@ -152,11 +152,14 @@ inline bool on_current_device(const neuzip_blob *b)
 // per-chunk / per-group word counts, run slots, and pinned host memory for the results.
 struct Workspace {
     int device = -1;
-    uint32_t *counts = nullptr;       // kBatchMax x 256 histogram bins, then the kFlagWords counters and flags of a
-                                      // call; all zero between compress calls
+    uint32_t *counts = nullptr;       // kBatchMax x 256 histogram bins, zero between compress calls; behind them, in
+                                      // the same allocation, the two copies of the call state and a counter
+    CallState *state = nullptr;       // [2], used by alternate calls (stamp & 1)
+    uint32_t *all_done = nullptr;     // tensors of the batch that have been reported to the host
+    uint32_t *super_words = nullptr;  // [2][super_cap] words per 64 encoder groups, used by alternate calls
+    uint32_t super_cap = 0;
     uint32_t *chunk_words = nullptr;  // words per chunk
     uint32_t *group_words = nullptr;  // words per encoder workgroup (16 chunks), input of the scan
-    uint64_t *group_prefix = nullptr; // its exclusive prefix sum, per tensor
     uint64_t group_cap = 0;           // encoder groups the arrays and the slots are sized for
     uint16_t *slots = nullptr;
     HostRecord *pinned = nullptr;     // pinned host memory, written by the encode kernel
@@ -180,7 +183,7 @@ int release_workspace_locked()
                 rc = NEUZIP_EHIP;
             (void)hipEventDestroy(g_ws.idle);
         }
-        void *device_arrays[] = {g_ws.counts, g_ws.chunk_words, g_ws.group_words, g_ws.group_prefix, g_ws.slots};
+        void *device_arrays[] = {g_ws.counts, g_ws.chunk_words, g_ws.group_words, g_ws.super_words, g_ws.slots};
         for (void *ptr : device_arrays)
             if (ptr)
                 (void)hipFree(ptr);
@@ -211,17 +214,37 @@ bool wait_for_record(uint32_t seq, hipStream_t stream)
     return __atomic_load_n(stamp, __ATOMIC_ACQUIRE) == seq;
 }
 
+// Words of the small allocation: the histogram bins of a batch, two call states, a counter (padded).
+constexpr uint32_t kSmallWords = kBatchMax * 256 + 2 * sizeof(CallState) / 4 + 16;
+// Entries of one copy of the per-64-groups array for a batch of n_groups encoder groups in all: every
+// tensor of the batch may end with a partial block.
+inline uint32_t super_entries(uint64_t n_groups) { return static_cast<uint32_t>(n_groups / kSuperGroups + kBatchMax + 1); }
+
+// Returns everything a failed call may have left behind in the workspace to zero.
+void reset_workspace(const Workspace &ws, hipStream_t stream)
+{
+    if (ws.counts)
+        hipLaunchKernelGGL(fill_u32_kernel, dim3((kSmallWords + 255) / 256), dim3(256), 0, stream, ws.counts, 0u,
+                           kSmallWords);
+    if (ws.super_words)
+        hipLaunchKernelGGL(fill_u32_kernel, dim3((2 * ws.super_cap + 255) / 256), dim3(256), 0, stream, ws.super_words, 0u,
+                           2 * ws.super_cap);
+    (void)hipGetLastError();
+}
+
 // First use on a device: the arrays whose size does not depend on the tensors.
 int create_workspace(int device, hipStream_t stream)
 {
     g_ws.device = device;
-    NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.counts), (kBatchMax * 256 + kFlagWords) * sizeof(uint32_t)));
+    NZ_HIP(hipMalloc(reinterpret_cast<void **>(&g_ws.counts), kSmallWords * sizeof(uint32_t)));
+    g_ws.state = reinterpret_cast<CallState *>(g_ws.counts + kBatchMax * 256);
+    g_ws.all_done = g_ws.counts + kBatchMax * 256 + 2 * sizeof(CallState) / 4;
     NZ_HIP(hipHostMalloc(reinterpret_cast<void **>(&g_ws.pinned), sizeof(HostRecord), hipHostMallocDefault));
     std::memset(g_ws.pinned, 0, sizeof(HostRecord));
     g_ws.seq = 0;
     NZ_HIP(hipEventCreateWithFlags(&g_ws.idle, hipEventDisableTiming));
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax + 1), dim3(256), 0, stream, g_ws.counts, 0u,
-                       kBatchMax * 256 + kFlagWords);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((kSmallWords + 255) / 256), dim3(256), 0, stream, g_ws.counts, 0u,
+                       kSmallWords);
     NZ_HIP(hipGetLastError());
     NZ_HIP(hipEventRecord(g_ws.idle, stream));
     return NEUZIP_OK;
@@ -245,23 +268,29 @@ int ensure_workspace(int device, uint64_t n_groups, hipStream_t stream)
     NZ_HIP(hipStreamWaitEvent(stream, g_ws.idle, 0));
     if (g_ws.group_cap < n_groups) {
         NZ_HIP(hipEventSynchronize(g_ws.idle));
-        void *old_arrays[] = {g_ws.chunk_words, g_ws.group_words, g_ws.group_prefix, g_ws.slots};
+        void *old_arrays[] = {g_ws.chunk_words, g_ws.group_words, g_ws.super_words, g_ws.slots};
         for (void *ptr : old_arrays)
             if (ptr)
                 NZ_HIP(hipFree(ptr));
-        g_ws.chunk_words = g_ws.group_words = nullptr;
-        g_ws.group_prefix = nullptr;
+        g_ws.chunk_words = g_ws.group_words = g_ws.super_words = nullptr;
         g_ws.slots = nullptr;
         g_ws.group_cap = 0;
+        g_ws.super_cap = 0;
         const uint64_t chunks = n_groups * kChunksPerGroup;
+        const uint32_t super_cap = super_entries(n_groups);
         if (hipMalloc(reinterpret_cast<void **>(&g_ws.chunk_words), (chunks + 4) * 4) != hipSuccess ||
             hipMalloc(reinterpret_cast<void **>(&g_ws.group_words), (n_groups + 4) * 4) != hipSuccess ||
-            hipMalloc(reinterpret_cast<void **>(&g_ws.group_prefix), (n_groups + 4) * 8) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void **>(&g_ws.super_words), 2ull * super_cap * 4) != hipSuccess ||
             hipMalloc(reinterpret_cast<void **>(&g_ws.slots), chunks * kStates * kRunCap * 2) != hipSuccess) {
             (void)hipGetLastError();
             return NEUZIP_ENOMEM;
         }
         g_ws.group_cap = n_groups;
+        g_ws.super_cap = super_cap;
+        // both copies start at zero (the call state behind the bins is zero between calls anyway)
+        hipLaunchKernelGGL(fill_u32_kernel, dim3((2 * super_cap + 255) / 256), dim3(256), 0, stream, g_ws.super_words, 0u,
+                           2 * super_cap);
+        NZ_HIP(hipGetLastError());
     }
     return NEUZIP_OK;
 }
@@ -300,16 +329,14 @@ int reserve_words(neuzip_blob *b, uint64_t total_words)
     const uint64_t need = pad_to(total_words * 2, 256) + 1024;
     if (b->words_bytes < need) {
         // A blob that receives a new version of its tensor after every update grows and shrinks
-        // by a little each time: once an allocation has had to be replaced, the new one gets
-        // 1/64 of headroom, so that this does not mean a new allocation per call.  The first
-        // allocation of a blob is exact.
-        const bool regrown = b->words != nullptr;
+        // by a little each time: an allocation gets 1/64 of headroom (0.3 % of the container), so
+        // that this does not mean a new allocation per call.
         if (b->words) {
             NZ_HIP(hipFree(b->words));
             b->words = nullptr;
             b->words_bytes = 0;
         }
-        const uint64_t roomy = regrown ? pad_to(need + need / 64, 256) : need;
+        const uint64_t roomy = pad_to(need + need / 64, 256);
         if (hipMalloc(reinterpret_cast<void **>(&b->words), roomy) != hipSuccess) {
             (void)hipGetLastError();
             return NEUZIP_ENOMEM;
@@ -481,12 +508,10 @@ int compress_empty(neuzip_blob *b, hipStream_t stream)
 template <int KB>
 void launch_hist(const Workspace &ws, const CompressBatch &batch, bool norm, uint32_t groups, hipStream_t stream)
 {
-    uint32_t *flags = ws.counts + kBatchMax * 256;
     if (norm)
-        hipLaunchKernelGGL(hist_split_norm_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch, ws.counts,
-                           flags);
+        hipLaunchKernelGGL(hist_split_norm_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch, ws.counts);
     else
-        hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch, ws.counts, flags);
+        hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(groups), dim3(kHistThreads), 0, stream, batch, ws.counts);
 }
 
 constexpr uint32_t kKeepGuard = 0xFFFFFFFFu;  // compress_some: every blob keeps the guard band it has
@@ -514,7 +539,10 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         fresh[i] = false;
     }
     bool touched = false;     // kernels that write into the blobs have been launched
+    bool ws_dirty = false;    // kernels have run whose sums in the workspace no later kernel has cleared
     auto fail = [&](int rc) {
+        if (ws_dirty)
+            reset_workspace(ws, stream);
         for (uint32_t i = 0; i < count; ++i) {
             if (fresh[i])
                 neuzip_free(work[i]);
@@ -549,7 +577,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
     neuzip_blob *stale_blob[kBatchMax];
     uint32_t stale_owner[kBatchMax];
     uint32_t stale_count = 0;
-    uint32_t hist_groups = 0, enc_groups = 0, compact_groups = 0;
+    uint32_t hist_groups = 0, enc_groups = 0, compact_groups = 0, super_used = 0;
     for (uint32_t i = 0; i < count; ++i) {
         neuzip_blob *b = work[i];
         if (b->n == 0) {
@@ -576,6 +604,8 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         it.block = block;
         it.guard = b->guard;
         it.group_base = enc_groups;
+        it.super_base = super_used;
+        super_used += ((b->n_chunks + kChunksPerGroup - 1) / kChunksPerGroup + kSuperGroups - 1) / kSuperGroups;
         // every workgroup of the histogram pass pays for clearing and merging its 32 KB of bins: give
         // it at least 8 vectors (64 elements) per thread, and no tensor more workgroups than fit the chip
         uint64_t hg = ((b->n + 7) / 8 + kHistThreads * 8 - 1) / (kHistThreads * 8);
@@ -593,11 +623,8 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         if (fixed_ws) {
             if (enc_groups > ws.group_cap)
                 return fail(NEUZIP_EUNSUPPORTED);
-            // the static array keeps what the last call left: bins, counters and flags start at zero
-            hipLaunchKernelGGL(fill_u32_kernel, dim3(kBatchMax + 1), dim3(256), 0, stream, ws.counts, 0u,
-                               kBatchMax * 256 + kFlagWords);
-            if (!hip_ok(hipGetLastError()))
-                return fail(NEUZIP_EHIP);
+            // the static array keeps what the last call left: bins, call states and sums start at zero
+            reset_workspace(ws, stream);
         } else {
             rc = ensure_workspace(work[owner[0]]->device, enc_groups, stream);
             if (rc != NEUZIP_OK)
@@ -607,19 +634,23 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         batch.lr = lr;
         batch.keep_new = keep_new ? 1u : 0u;
         touched = true;
-        uint32_t *flags = ws.counts + kBatchMax * 256;
+        // the call state and the sums per 64 groups exist twice; calls alternate between the copies
+        const uint32_t copy = batch.seq & 1u;
+        CallState *state = ws.state + copy, *state_next = ws.state + (copy ^ 1u);
+        uint32_t *super_words = ws.super_words + copy * ws.super_cap;
+        uint32_t *super_next = ws.super_words + (copy ^ 1u) * ws.super_cap;
 
-        // Two launches produce everything but the final place of the words: the histogram pass, whose
-        // last workgroup per tensor builds the table (fresh statistics only), and the encoder, whose
-        // last workgroup per tensor turns the word counts into offsets and reports the stream
-        // length.  With fresh tables the encoder launch carries one more workgroup per tensor, which
-        // fills in the decoder's slot table meanwhile.
+        // Three launches.  The histogram pass (fresh statistics only).  The encoder, every workgroup of
+        // which derives the table from the counts by itself; with fresh tables its launch carries one
+        // more workgroup per tensor, which fills in the decoder's slot table meanwhile.  The compaction,
+        // which also works out the chunk offsets, tells the host the stream lengths and returns the
+        // workspace's sums to zero.
         const int variant = d_grads ? kUpdateVariant : (elem == NEUZIP_F32 ? 23 : (elem == NEUZIP_F16 ? 39 : k));
         if (!reuse) {
             const dim3 grid(hist_groups), threads(kHistThreads);
             switch (variant) {
-            case 39: hipLaunchKernelGGL((hist_split_kernel<7, false, true>), grid, threads, 0, stream, batch, ws.counts, flags); break;
-            case 23: hipLaunchKernelGGL((hist_split_kernel<7, true>), grid, threads, 0, stream, batch, ws.counts, flags); break;
+            case 39: hipLaunchKernelGGL((hist_split_kernel<7, false, true>), grid, threads, 0, stream, batch, ws.counts); break;
+            case 23: hipLaunchKernelGGL((hist_split_kernel<7, true>), grid, threads, 0, stream, batch, ws.counts); break;
             case 7: launch_hist<7>(ws, batch, block != 0, hist_groups, stream); break;
             case 3: launch_hist<3>(ws, batch, block != 0, hist_groups, stream); break;
             case 1: launch_hist<1>(ws, batch, block != 0, hist_groups, stream); break;
@@ -627,12 +658,13 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             }
             if (!hip_ok(hipGetLastError()))
                 return fail(NEUZIP_EHIP);
+            ws_dirty = true;
         }
         {
             const dim3 grid(enc_groups + (reuse ? 0u : batch.count)), threads(kEncThreads);
-#define NZ_ENCODE(...)                                                                                             \
-    hipLaunchKernelGGL((encode_kernel<__VA_ARGS__>), grid, threads, 0, stream, batch, ws.chunk_words, ws.group_words, \
-                       ws.group_prefix, ws.slots, ws.pinned, flags)
+#define NZ_ENCODE(...)                                                                                          \
+    hipLaunchKernelGGL((encode_kernel<__VA_ARGS__>), grid, threads, 0, stream, batch, ws.counts, ws.chunk_words, \
+                       ws.group_words, super_words, ws.slots, ws.pinned, state)
             if (reuse) {
                 switch (variant) {
                 case kUpdateVariant: NZ_ENCODE(false, 7, false, false, true); break;
@@ -655,26 +687,29 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
 #undef NZ_ENCODE
             if (!hip_ok(hipGetLastError()))
                 return fail(NEUZIP_EHIP);
+            ws_dirty = true;
         }
 
-        // The stream lengths are data dependent.  A blob that already has a word section (one that is
-        // compressed into again, as in a training loop) gets its compaction launched right away, into
-        // the room it has; the kernel itself leaves a tensor alone whose words turn out not to fit, or
-        // whose kept table turned out stale.  Then the host waits for the lengths (and the statistics),
-        // which the kernels write straight into pinned host memory, the stamp last.
-        bool early = false;
+        // The stream lengths are data dependent.  The compaction is launched right away all the same:
+        // a blob that already has a word section (one that is compressed into again, as in a training
+        // loop) has its words moved into the room it has, and the kernel itself leaves a tensor alone
+        // whose words turn out not to fit, or whose kept table turned out stale.  It also writes the
+        // lengths into pinned host memory, the stamp last, which is what the host then waits for.
         for (uint32_t j = 0; j < batch.count; ++j) {
             const neuzip_blob *b = work[owner[j]];
             batch.it[j].words = reinterpret_cast<uint16_t *>(b->words);
             batch.it[j].words_cap = words_room(b);
-            early = early || batch.it[j].words_cap > 0;
         }
-        if (early) {
+        auto launch_compact = [&](bool report) {
+            batch.report = report ? 1u : 0u;
             hipLaunchKernelGGL(compact_kernel, dim3(compact_groups), dim3(kCompactThreads), 0, stream, batch, ws.slots,
-                               ws.chunk_words, ws.group_prefix);
-            if (!hip_ok(hipGetLastError()))
-                return fail(NEUZIP_EHIP);
-        }
+                               ws.chunk_words, ws.group_words, super_words, state, ws.counts, state_next, super_next,
+                               ws.super_cap, ws.all_done, ws.pinned);
+            return hip_ok(hipGetLastError());
+        };
+        if (!launch_compact(true))
+            return fail(NEUZIP_EHIP);
+        ws_dirty = false;
         HostRecord::Item fetched[kBatchMax];  // fixed workspace: the record lies in device memory and is copied out
         if (fixed_ws) {
             if (!hip_ok(hipMemcpyAsync(fetched, &ws.pinned->item[0], sizeof(HostRecord::Item) * batch.count,
@@ -691,7 +726,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             neuzip_blob *b = work[owner[j]];
             if (reuse && r.stale) {
                 // its table does not cover the new values: nothing of this pass is kept (the
-                // compaction skips such a tensor); it is compressed afresh below
+                // compaction has left such a tensor alone); it is compressed afresh below
                 stale_src[n_stale] = d_srcs[owner[j]];
                 stale_grad[n_stale] = d_grads ? d_grads[owner[j]] : nullptr;
                 stale_n[n_stale] = n_elems[owner[j]];
@@ -703,8 +738,8 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             }
             if (r.total_words[1] != 0)
                 return fail(NEUZIP_EUNSUPPORTED);  // more than 2^32 words
-            if (early && r.total_words[0] <= batch.it[j].words_cap) {
-                batch.it[j].n_chunks = 0;  // in place already: the early launch took the same decision
+            if (r.total_words[0] <= batch.it[j].words_cap) {
+                batch.it[j].n_chunks = 0;  // in place already: the kernel took the same decision
             } else {
                 if (fixed_ws)  // no allocation: the stream must fit the room the blob has
                     return fail(NEUZIP_ENOMEM);
@@ -723,13 +758,9 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
             }
             b->has_table = true;
         }
-        if (late) {
-            // the tensors that had no room (or no word section yet): now that it is allocated
-            hipLaunchKernelGGL(compact_kernel, dim3(compact_groups), dim3(kCompactThreads), 0, stream, batch, ws.slots,
-                               ws.chunk_words, ws.group_prefix);
-            if (!hip_ok(hipGetLastError()))
-                return fail(NEUZIP_EHIP);
-        }
+        // the tensors that had no room (or no word section yet), now that it is allocated
+        if (late && !launch_compact(false))
+            return fail(NEUZIP_EHIP);
         if (!fixed_ws && !hip_ok(hipEventRecord(ws.idle, stream)))
             return fail(NEUZIP_EHIP);
         stale_count = n_stale;
@@ -1046,12 +1077,13 @@ namespace {
 constexpr uint32_t kFixedChunks = static_cast<uint32_t>(NEUZIP_NOALLOC_MAX_ELEMS / kChunk);
 constexpr uint32_t kFixedGroups = kFixedChunks / kChunksPerGroup;
 static_assert(NEUZIP_NOALLOC_MAX_ELEMS % (kChunk * kChunksPerGroup) == 0, "whole encoder groups");
-constexpr uint64_t kFixedCountsAt = 0;                                                     // bins, counters, flags
-constexpr uint64_t kFixedRecordAt = kFixedCountsAt + pad_to((kBatchMax * 256 + kFlagWords) * 4, 256);
+constexpr uint64_t kFixedCountsAt = 0;                                                     // bins, call states, counter
+constexpr uint64_t kFixedRecordAt = kFixedCountsAt + pad_to(kSmallWords * 4, 256);
 constexpr uint64_t kFixedChunkWordsAt = kFixedRecordAt + pad_to(sizeof(HostRecord), 256);
 constexpr uint64_t kFixedGroupWordsAt = kFixedChunkWordsAt + pad_to((kFixedChunks + 4) * 4, 256);
-constexpr uint64_t kFixedGroupPrefixAt = kFixedGroupWordsAt + pad_to((kFixedGroups + 4) * 4, 256);
-constexpr uint64_t kFixedSlotsAt = kFixedGroupPrefixAt + pad_to((kFixedGroups + 4) * 8, 256);
+constexpr uint32_t kFixedSuperCap = kFixedGroups / kSuperGroups + kBatchMax + 1;
+constexpr uint64_t kFixedSuperAt = kFixedGroupWordsAt + pad_to((kFixedGroups + 4) * 4, 256);
+constexpr uint64_t kFixedSlotsAt = kFixedSuperAt + pad_to(2 * kFixedSuperCap * 4, 256);
 constexpr uint64_t kFixedBytes = kFixedSlotsAt + static_cast<uint64_t>(kFixedChunks) * kStates * kRunCap * 2;
 
 static __device__ __align__(256) unsigned char scratch[kFixedBytes];
@@ -1107,10 +1139,13 @@ int neuzip_compress_noalloc(const void *d_src, uint64_t n_elems, int dtype, int 
     Workspace ws;
     ws.device = device;
     ws.counts = reinterpret_cast<uint32_t *>(base + kFixedCountsAt);
+    ws.state = reinterpret_cast<CallState *>(ws.counts + kBatchMax * 256);
+    ws.all_done = ws.counts + kBatchMax * 256 + 2 * sizeof(CallState) / 4;
+    ws.super_words = reinterpret_cast<uint32_t *>(base + kFixedSuperAt);
+    ws.super_cap = kFixedSuperCap;
     ws.pinned = reinterpret_cast<HostRecord *>(base + kFixedRecordAt);  // device memory here: copied out, not read in place
     ws.chunk_words = reinterpret_cast<uint32_t *>(base + kFixedChunkWordsAt);
     ws.group_words = reinterpret_cast<uint32_t *>(base + kFixedGroupWordsAt);
-    ws.group_prefix = reinterpret_cast<uint64_t *>(base + kFixedGroupPrefixAt);
     ws.slots = reinterpret_cast<uint16_t *>(base + kFixedSlotsAt);
     ws.group_cap = kFixedGroups;
     {

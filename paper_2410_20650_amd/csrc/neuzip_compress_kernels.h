@@ -187,77 +187,157 @@ __device__ __forceinline__ uint32_t source_word(const void *__restrict__ src, ui
     }
 }
 
-// ------------------------------------------------------------------------------------------
-// Counters and flags of a compress call: 64 words of the workspace behind the histogram bins.  All
-// are zero between calls: whoever takes the last ticket of a counter sets it back.
-// ------------------------------------------------------------------------------------------
-constexpr uint32_t kFlagHistDone = 0;   // [8] histogram workgroups of tensor i that have merged their bins
-constexpr uint32_t kFlagEncDone = 8;    // [8] encoder workgroups of tensor i that have posted their word count
-constexpr uint32_t kFlagAllDone = 16;   // tensors of the batch whose offsets are complete
-constexpr uint32_t kFlagStale = 24;     // [8] recompression met an exponent without room in tensor i's table
-constexpr uint32_t kFlagWords = 64;
-
 // Stores and atomics issued so far by this wave have been performed (their acknowledgements are in)
-// before anything that follows: what a workgroup does before it takes a ticket of a completion
-// counter.  The counters, and the data the ticket's last holder reads, are accessed with
-// device-scope atomics, which bypass the per-XCD caches, so no cache write-back is needed.
+// before anything that follows.
 __device__ __forceinline__ void wait_for_memory_acks() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // ------------------------------------------------------------------------------------------
-// Counts -> frequencies that sum to 4096, cumulative table.  256 threads, thread s owns symbol s.
+// Counts -> frequencies that sum to 4096, cumulative table: by ONE wave, lane l owning symbols
+// 4l .. 4l + 3, with lane shuffles only (no barrier), so that every encoder workgroup can derive
+// the table of its tensor from the 256 counts by itself and no launch is spent on it.
 // Integer only:
 //   f = max(1, floor(cnt * 4096 / N)) for symbols that occur, else 0; a shortfall goes to the
 //   most frequent symbol (lowest value on a tie); an excess is taken one unit at a time from
 //   the symbol whose f is largest at that moment (lowest value on a tie).
 // ------------------------------------------------------------------------------------------
-__device__ inline uint64_t block_max_u64(uint64_t v, uint64_t *scratch)
+// Inclusive scan of v over the 64 lanes of the wave with data-parallel-primitive moves (vector ALU
+// rate: no trip through the LDS crossbar as with a lane shuffle): inside each row of 16 lanes by
+// shifts of 1, 2, 4, 8 (a lane without a source keeps the identity), then the last lane of rows 0
+// and 2 is added into rows 1 and 3, then lane 31 into rows 2 and 3.  All 64 lanes must be active.
+template <class Op>
+__device__ __forceinline__ uint32_t wave_scan_u32(uint32_t v, uint32_t identity, Op op)
 {
-    // 256 threads = 4 waves
-    for (int off = 32; off > 0; off >>= 1) {
-        const uint64_t o = __shfl_xor(v, off, 64);
-        v = o > v ? o : v;
-    }
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0)
-        scratch[threadIdx.x >> 6] = v;
-    __syncthreads();
-    uint64_t r = scratch[0];
-    for (int i = 1; i < 4; ++i)
-        r = scratch[i] > r ? scratch[i] : r;
-    return r;
+#define NZ_DPP(ctrl, rows) \
+    static_cast<uint32_t>(__builtin_amdgcn_update_dpp(static_cast<int>(identity), static_cast<int>(v), ctrl, rows, 0xf, false))
+    v = op(v, NZ_DPP(0x111, 0xf));  // row_shr:1
+    v = op(v, NZ_DPP(0x112, 0xf));  // row_shr:2
+    v = op(v, NZ_DPP(0x114, 0xf));  // row_shr:4
+    v = op(v, NZ_DPP(0x118, 0xf));  // row_shr:8
+    v = op(v, NZ_DPP(0x142, 0xa));  // row_bcast:15 into rows 1 and 3
+    v = op(v, NZ_DPP(0x143, 0xc));  // row_bcast:31 into rows 2 and 3
+#undef NZ_DPP
+    return v;
 }
 
-__device__ inline uint64_t block_sum_u64(uint64_t v, uint64_t *scratch)
+struct OpAdd {
+    __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a + b; }
+};
+struct OpMax {
+    __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a > b ? a : b; }
+};
+
+// Sum / maximum over the wave, the same value in every lane (lane 63 of the scan, read out as a scalar).
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
 {
-    for (int off = 32; off > 0; off >>= 1)
-        v += __shfl_xor(v, off, 64);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0)
-        scratch[threadIdx.x >> 6] = v;
-    __syncthreads();
-    return scratch[0] + scratch[1] + scratch[2] + scratch[3];
+    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(wave_scan_u32(v, 0u, OpAdd{})), 63));
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(wave_scan_u32(v, 0u, OpMax{})), 63));
 }
 
-// Inclusive sum of v over the 256 threads of the workgroup, left in scan[] as well.
-__device__ inline uint32_t block_scan_u32(uint32_t v, uint64_t *scratch, uint32_t *scan)
+// The frequencies (f) and exclusive cumulative frequencies (cum) of symbols 4 * lane .. 4 * lane + 3
+// from their counts, which add up to `total`; returns the tensor's only exponent value if it has
+// just one, else 256.  Must be called by all 64 lanes of a wave.
+__device__ inline uint32_t build_table_wave(const uint32_t (&cnt)[4], uint64_t total, uint32_t guard, uint32_t (&f)[4],
+                                            uint32_t (&cum)[4])
 {
-    const uint32_t s = threadIdx.x;
-    uint32_t incl = v;
+    const uint32_t lane = threadIdx.x & 63u;
 #pragma unroll
-    for (uint32_t d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(incl, d, 64);
-        if ((s & 63u) >= d)
-            incl += o;
+    for (int i = 0; i < 4; ++i)
+        f[i] = 0;
+    if (total > 0) {
+        const float total_f = static_cast<float>(total);
+        // With a guard band every exponent from (lowest occurring - guard) to (highest occurring +
+        // guard), and exponent 0 (an update cancels exactly to +-0 now and then), is treated as
+        // occurring: it gets f = 1 and can be coded after a weight update without a new table.
+        uint32_t hi = 0, lo = 0;
+        if (guard > 0) {
+            uint32_t top = 0, bottom = 0;  // highest occupied symbol + 1; 256 - lowest occupied symbol
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t s = 4 * lane + i;
+                if (cnt[i] > 0) {
+                    top = s + 1 > top ? s + 1 : top;
+                    bottom = 256 - s > bottom ? 256 - s : bottom;
+                }
+            }
+            hi = wave_max_u32(top) - 1;
+            lo = 256 - wave_max_u32(bottom);
+        }
+        uint32_t sum = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t s = 4 * lane + i;
+            const bool member = cnt[i] > 0 || (guard > 0 && (s == 0 || (s + guard >= lo && s <= hi + guard)));
+            if (member) {
+                // floor(cnt * 4096 / total) without a 64-bit division: the float quotient is within one
+                // of it (its relative error is below 2^-22 and the quotient at most 4096), and the exact
+                // remainder tells which way
+                const uint64_t num = static_cast<uint64_t>(cnt[i]) * kM;
+                uint32_t q = static_cast<uint32_t>(__fdiv_rn(static_cast<float>(num), total_f));
+                q = q > kM ? kM : q;
+                const int64_t r = static_cast<int64_t>(num - static_cast<uint64_t>(q) * total);
+                if (r < 0)
+                    q -= 1;
+                else if (r >= static_cast<int64_t>(total))
+                    q += 1;
+                f[i] = q < 1 ? 1u : q;
+            }
+            sum += f[i];
+        }
+        int32_t rest = static_cast<int32_t>(kM) - static_cast<int32_t>(wave_sum_u32(sum));
+        if (rest > 0) {
+            // the most frequent symbol, the lowest one on a tie
+            uint32_t most = cnt[0];
+#pragma unroll
+            for (int i = 1; i < 4; ++i)
+                most = cnt[i] > most ? cnt[i] : most;
+            most = wave_max_u32(most);
+            uint32_t who = 0;  // 256 - symbol of this lane's lowest symbol with that count
+#pragma unroll
+            for (int i = 3; i >= 0; --i)
+                who = cnt[i] == most ? 256 - (4 * lane + i) : who;
+            who = 256 - wave_max_u32(who);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (4 * lane + i == who)
+                    f[i] += static_cast<uint32_t>(rest);
+        }
+        while (rest < 0) {  // uniform across the wave
+            uint32_t key = 0, runner = 0;  // the two largest (f, lowest symbol first) of this lane
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t k = (f[i] << 8) | (255u - (4 * lane + i));
+                runner = k > key ? key : (k > runner ? k : runner);
+                key = k > key ? k : key;
+            }
+            const uint32_t best = wave_max_u32(key);
+            const uint32_t second = wave_max_u32(key == best ? runner : key);
+            // Usual case: the largest symbol stays the largest through all -rest decrements (its key
+            // after -rest - 1 of them still beats the runner-up's), so it takes them all at once.
+            const uint32_t want = static_cast<uint32_t>(-rest);
+            const bool all_at_once = (best >> 8) >= want && best - ((want - 1) << 8) > second;
+            const uint32_t take = all_at_once ? want : 1u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (((f[i] << 8) | (255u - (4 * lane + i))) == best)
+                    f[i] -= take;
+            rest += static_cast<int32_t>(take);
+        }
     }
-    __syncthreads();
-    if ((s & 63u) == 63u)
-        scratch[s >> 6] = incl;
-    __syncthreads();
-    for (uint32_t wv = 0; wv < (s >> 6); ++wv)
-        incl += static_cast<uint32_t>(scratch[wv]);
-    scan[s] = incl;
-    __syncthreads();
-    return incl;
+    // exclusive cumulative sums: over the lanes before, then inside the lane
+    const uint32_t mine = f[0] + f[1] + f[2] + f[3];
+    cum[0] = wave_scan_u32(mine, 0u, OpAdd{}) - mine;
+    cum[1] = cum[0] + f[0];
+    cum[2] = cum[1] + f[1];
+    cum[3] = cum[2] + f[2];
+    uint32_t lone = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        lone = f[i] == kM ? 4 * lane + i + 1 : lone;
+    lone = wave_max_u32(lone);
+    return lone ? lone - 1 : 256u;
 }
 
 // Encoder constants of a symbol.  A symbol without room in the table (f = 0) gets constants that
@@ -274,117 +354,48 @@ __device__ inline EncSym encoder_constants(uint32_t f, uint32_t cum)
     return e;
 }
 
-// The table of one tensor from its exponent counts (cnt: the count of symbol threadIdx.x); also
-// keeps the counts in the blob and clears its status words.  scratch: 4 words of 64 bits in LDS.
-__device__ inline void build_table(const CompressItem &it, uint64_t cnt, uint64_t *scratch, uint32_t *scan)
-{
-    TableBlock *__restrict__ tb = it.tb;
-    const uint32_t s = threadIdx.x;
-    tb->counts[s] = static_cast<uint32_t>(cnt);
-    if (s < 4)
-        tb->status[s] = 0;
-    const uint64_t total = block_sum_u64(cnt, scratch);
-    uint32_t f = 0;
-    if (total > 0) {
-        // With a guard band every exponent from (lowest occurring - guard) to (highest occurring +
-        // guard), and exponent 0 (an update cancels exactly to +-0 now and then), is treated as
-        // occurring: it gets f = 1 and can be coded after a weight update without a new table.
-        bool member = cnt > 0;
-        const uint32_t guard = it.guard;
-        if (guard > 0) {
-            const uint32_t hi = static_cast<uint32_t>(block_max_u64(cnt > 0 ? s + 1 : 0, scratch)) - 1;
-            const uint32_t lo = 256 - static_cast<uint32_t>(block_max_u64(cnt > 0 ? 256 - s : 0, scratch));
-            member = s == 0 || (s + guard >= lo && s <= hi + guard);
-        }
-        if (member) {
-            const uint64_t scaled = cnt * kM / total;
-            f = scaled < 1 ? 1u : static_cast<uint32_t>(scaled);
-        }
-        const int32_t sum = static_cast<int32_t>(block_sum_u64(f, scratch));
-        int32_t rest = static_cast<int32_t>(kM) - sum;
-        if (rest > 0) {
-            const uint64_t key = (cnt << 8) | (255u - s);
-            const uint64_t best = block_max_u64(key, scratch);
-            if (key == best)
-                f += static_cast<uint32_t>(rest);
-        }
-        if (rest < 0) {
-            // Usual case: the most frequent symbol stays the largest through all -rest decrements
-            // (its key after -rest - 1 of them still beats the runner-up's), so it takes them all.
-            const uint64_t key = (static_cast<uint64_t>(f) << 8) | (255u - s);
-            const uint64_t best = block_max_u64(key, scratch);
-            const uint64_t second = block_max_u64(key == best ? 0 : key, scratch);
-            const uint64_t best_late = best - (static_cast<uint64_t>(-rest - 1) << 8);
-            if ((best >> 8) >= static_cast<uint64_t>(-rest) && best_late > second) {
-                if (key == best)
-                    f -= static_cast<uint32_t>(-rest);
-                rest = 0;
-            }
-        }
-        while (rest < 0) {  // general case, one unit at a time; uniform across the workgroup
-            const uint64_t key = (static_cast<uint64_t>(f) << 8) | (255u - s);
-            const uint64_t best = block_max_u64(key, scratch);
-            if (key == best)
-                --f;
-            ++rest;
-        }
-    }
-    const uint32_t incl = block_scan_u32(f, scratch, scan);
-    tb->freq[s] = static_cast<uint16_t>(f);
-    tb->cum[s] = static_cast<uint16_t>(incl - f);
-    if (s == 255)
-        tb->cum[256] = static_cast<uint16_t>(incl);
-    // the only exponent value of the tensor, if there is just one (its f is 4096), else 256
-    const uint32_t lone = static_cast<uint32_t>(block_max_u64(f == kM ? s + 1 : 0, scratch));
-    if (s == 0)
-        tb->lone = lone ? lone - 1 : 256;
-}
-
-// Decoder slot table of a tensor from the frequencies its table block holds:
-// lut[slot] = symbol | f << 8 | (slot - cum[symbol]) << 20.  256 threads; thread s fills slots
-// s, s + 256, ...; scan[t] = cum[t + 1].  The 16 binary searches of a thread are independent, so
-// their LDS reads overlap.
-__device__ inline void build_slot_table(TableBlock *__restrict__ tb, uint64_t *scratch, uint32_t *scan)
+// Decoder slot table of a tensor: lut[slot] = symbol | f << 8 | (slot - cum[symbol]) << 20.
+// 256 threads; scan[t] = cum[t + 1] (in LDS, complete); thread s fills slots s, s + 256, ...
+__device__ inline void build_slot_table(TableBlock *__restrict__ tb, const uint32_t *__restrict__ scan)
 {
     const uint32_t s = threadIdx.x;
-    block_scan_u32(tb->freq[s], scratch, scan);
     if (scan[255] != kM)
         return;  // an empty table: nothing decodes through it
-    constexpr uint32_t kPer = kM / 256;
-    uint32_t lo[kPer], hi[kPer];
+    // (four searches at a time: this runs beside the encoders in their kernel and must not raise its
+    // register count)
+    constexpr uint32_t kPer = kM / 256, kAtOnce = 4;
+#pragma unroll 1
+    for (uint32_t r0 = 0; r0 < kPer; r0 += kAtOnce) {
+        uint32_t lo[kAtOnce], hi[kAtOnce];
 #pragma unroll
-    for (uint32_t r = 0; r < kPer; ++r) {
-        lo[r] = 0;
-        hi[r] = 255;
-    }
-#pragma unroll
-    for (uint32_t step = 0; step < 8; ++step) {
-#pragma unroll
-        for (uint32_t r = 0; r < kPer; ++r) {  // smallest t with cum[t + 1] > slot
-            const uint32_t mid = (lo[r] + hi[r]) >> 1;
-            const bool above = scan[mid] > s + 256 * r;
-            hi[r] = above ? mid : hi[r];
-            lo[r] = above ? lo[r] : (mid < hi[r] ? mid + 1 : hi[r]);
+        for (uint32_t r = 0; r < kAtOnce; ++r) {
+            lo[r] = 0;
+            hi[r] = 255;
         }
-    }
 #pragma unroll
-    for (uint32_t r = 0; r < kPer; ++r) {
-        const uint32_t slot = s + 256 * r, t = lo[r];
-        const uint32_t begin = t ? scan[t - 1] : 0u;
-        tb->lut[slot] = t | (((scan[t] - begin) & 0xFFFu) << 8) | ((slot - begin) << 20);
+        for (uint32_t step = 0; step < 8; ++step) {
+#pragma unroll
+            for (uint32_t r = 0; r < kAtOnce; ++r) {  // smallest t with cum[t + 1] > slot
+                const uint32_t mid = (lo[r] + hi[r]) >> 1;
+                const bool above = scan[mid] > s + 256 * (r0 + r);
+                hi[r] = above ? mid : hi[r];
+                lo[r] = above ? lo[r] : (mid < hi[r] ? mid + 1 : hi[r]);
+            }
+        }
+#pragma unroll
+        for (uint32_t r = 0; r < kAtOnce; ++r) {
+            const uint32_t slot = s + 256 * (r0 + r), t = lo[r];
+            const uint32_t begin = t ? scan[t - 1] : 0u;
+            tb->lut[slot] = t | (((scan[t] - begin) & 0xFFFu) << 8) | ((slot - begin) << 20);
+        }
     }
 }
 
-// ------------------------------------------------------------------------------------------
-// End of a histogram workgroup: thread b sums the 32 copies of bin b (starting at a rotated copy to
-// spread the banks) into the workspace bins.  The workgroup that finishes last for its tensor then
-// takes the totals, leaves the bins at zero for the next call, and builds the tensor's table, so
-// that no launch of its own is needed for that.
-// ------------------------------------------------------------------------------------------
 constexpr uint32_t kHistCopies = 32;
-__device__ __forceinline__ void finish_histogram(const CompressBatch &b, uint32_t item, uint32_t wgs,
-                                                 uint32_t *__restrict__ bins, uint32_t *__restrict__ counts,
-                                                 uint32_t *__restrict__ flags)
+
+// End of a histogram workgroup: thread b sums the 32 copies of bin b (starting at a rotated copy to
+// spread the banks) and adds the sum to the workspace bin.
+__device__ __forceinline__ void merge_bins(const uint32_t *__restrict__ bins, uint32_t *__restrict__ counts)
 {
     __syncthreads();
     const uint32_t s = threadIdx.x;
@@ -394,17 +405,6 @@ __device__ __forceinline__ void finish_histogram(const CompressBatch &b, uint32_
         sum += bins[s * kHistCopies + ((i + s) & (kHistCopies - 1))];
     if (sum)
         atomicAdd(&counts[s], sum);
-    wait_for_memory_acks();
-    __syncthreads();  // all adds of this workgroup are in; the bins in LDS are free from here on
-    if (s == 0)
-        bins[0] = atomicAdd(&flags[kFlagHistDone + item], 1u) == wgs - 1 ? 1u : 0u;
-    __syncthreads();
-    if (!bins[0])
-        return;
-    if (s == 0)
-        flags[kFlagHistDone + item] = 0;
-    const uint64_t cnt = atomicExch(&counts[s], 0u);
-    build_table(b.it[item], cnt, reinterpret_cast<uint64_t *>(bins + 16), bins + 64);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -435,8 +435,7 @@ __device__ __forceinline__ ItemSlot item_of_workgroup(const CompressBatch &b)
 
 template <int KB, bool WIDE = false, bool HALF = false>
 __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const CompressBatch b,
-                                                                 uint32_t *__restrict__ counts_ws,
-                                                                 uint32_t *__restrict__ flags)
+                                                                 uint32_t *__restrict__ counts_ws)
 {
     const ItemSlot slot = item_of_workgroup<&CompressItem::hist_end>(b);
     const void *__restrict__ src = b.it[slot.item].src;
@@ -502,7 +501,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const Compress
         if (filled)
             sm[(n - 1) / per_byte] = static_cast<uint8_t>(acc);
     }
-    finish_histogram(b, slot.item, slot.wgs, bins, counts, flags);
+    merge_bins(bins, counts);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -513,8 +512,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const Compress
 // ------------------------------------------------------------------------------------------
 template <int KB>
 __global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const CompressBatch b,
-                                                                      uint32_t *__restrict__ counts_ws,
-                                                                      uint32_t *__restrict__ flags)
+                                                                      uint32_t *__restrict__ counts_ws)
 {
     const ItemSlot slot = item_of_workgroup<&CompressItem::hist_end>(b);
     const uint16_t *__restrict__ src = static_cast<const uint16_t *>(b.it[slot.item].src);
@@ -586,7 +584,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const Com
                 sm[(first + t) / per_byte] = static_cast<uint8_t>(packed >> (t * (KB + 1)));
         }
     }
-    finish_histogram(b, slot.item, slot.wgs, bins, counts, flags);
+    merge_bins(bins, counts);
 }
 
 // The weight update of the backward loop (Alg. 1: W_hat <- W_hat - lr * grad) on the two halves of
@@ -716,12 +714,13 @@ __device__ __forceinline__ void ring_flush(uint32_t wp_before, uint32_t wp_after
 // codes it, so the new weight is read once and never re-read from memory.
 template <bool NORM, int SPLIT, bool WIDE = false, bool HALF = false, bool UPD = false>
 __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch b,
+                                                            const uint32_t *__restrict__ counts_ws,
                                                             uint32_t *__restrict__ chunk_words_all,
                                                             uint32_t *__restrict__ group_words_all,
-                                                            uint64_t *__restrict__ group_prefix_all,
+                                                            uint32_t *__restrict__ super_words_all,
                                                             uint16_t *__restrict__ slots_all,
                                                             HostRecord *__restrict__ record,
-                                                            uint32_t *__restrict__ flags)
+                                                            CallState *__restrict__ state)
 {
     static_assert(!(NORM && SPLIT >= 0), "the one-pass variant has no block maxima to normalise with");
     static_assert(!(WIDE || HALF) || (!NORM && (SPLIT < 0 || SPLIT == 7)), "binary32 and binary16 tensors are lossless only");
@@ -731,14 +730,13 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     __shared__ uint4 enc_raw[256];
     __shared__ __align__(32) uint16_t rings[kEncThreads * kRingWords];
     __shared__ uint32_t group_chunk[kEncThreads / kStates];
-    __shared__ uint64_t scratch[4];
-    if (blockIdx.x >= b.it[b.count - 1].enc_end) {
-        // the workgroups behind the encoders' (fresh tables only): one per tensor, it fills in the
-        // decoder's slot table while the others encode
-        build_slot_table(b.it[blockIdx.x - b.it[b.count - 1].enc_end].tb, scratch, reinterpret_cast<uint32_t *>(rings));
-        return;
-    }
-    const ItemSlot slot_id = item_of_workgroup<&CompressItem::enc_end>(b);
+    const uint32_t all_groups = b.it[b.count - 1].enc_end;
+    const bool table_wg = blockIdx.x >= all_groups;  // behind the encoders' (fresh tables only): one per tensor
+    ItemSlot slot_id;
+    if (table_wg)
+        slot_id = {blockIdx.x - all_groups, 0u, 0u};
+    else
+        slot_id = item_of_workgroup<&CompressItem::enc_end>(b);
     const CompressItem &it = b.it[slot_id.item];
     const void *__restrict__ src = it.src;
     uint16_t *__restrict__ low = it.low;
@@ -748,26 +746,64 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     const uint8_t *__restrict__ coef = it.coef;
     const uint32_t block_shift = NORM ? 31u - static_cast<uint32_t>(__clz(static_cast<int>(it.block | 1u))) : 0u;
     const uint32_t n_chunks = it.n_chunks;
-    const TableBlock *__restrict__ tb = it.tb;
+    TableBlock *__restrict__ tb = it.tb;
     uint32_t *__restrict__ states = it.states;
     uint8_t *__restrict__ lens = it.lens;
     // this tensor's part of the workspace arrays
     const uint32_t group = it.group_base + slot_id.wg;
     uint32_t *__restrict__ chunk_words = chunk_words_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup;
     uint16_t *__restrict__ slots = slots_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup * kStates * kRunCap;
-    uint32_t *__restrict__ stale = flags + kFlagStale;
 
-    // encoder constants of the 256 symbols, from the table the blob holds
-    {
+    // ---- encoder constants of the 256 symbols
+    if constexpr (SPLIT < 0) {
+        // Fresh statistics: the histogram pass has left the 256 counts in the workspace; the first wave
+        // of every workgroup turns them into the table by itself (the same arithmetic everywhere, so
+        // the same table).  The tensor's first workgroup also puts the table into the blob and posts
+        // the statistics to the host.
+        if (threadIdx.x < 64) {
+            const uint32_t lane = threadIdx.x;
+            const uint4 c4 = reinterpret_cast<const uint4 *>(counts_ws + 256 * slot_id.item)[lane];
+            const uint32_t cnt[4] = {c4.x, c4.y, c4.z, c4.w};
+            uint32_t f[4], cum[4];
+            const uint32_t lone = build_table_wave(cnt, n, it.guard, f, cum);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const EncSym e = encoder_constants(f[i], cum[i]);
+                enc_raw[4 * lane + i] = make_uint4(__float_as_uint(e.rcp), e.limit, e.cmpl_cum, e.f);
+            }
+            if (table_wg) {
+                uint32_t *scan = reinterpret_cast<uint32_t *>(rings);  // scan[t] = cum[t + 1]
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    scan[4 * lane + i] = cum[i] + f[i];
+            } else if (slot_id.wg == 0) {
+                reinterpret_cast<uint4 *>(tb->counts)[lane] = c4;
+                reinterpret_cast<uint2 *>(tb->freq)[lane] = make_uint2(f[0] | (f[1] << 16), f[2] | (f[3] << 16));
+                reinterpret_cast<uint2 *>(tb->cum)[lane] = make_uint2(cum[0] | (cum[1] << 16), cum[2] | (cum[3] << 16));
+                if (lane == 63)
+                    tb->cum[256] = static_cast<uint16_t>(cum[3] + f[3]);
+                if (lane < 4)
+                    tb->status[lane] = 0;
+                if (lane == 0)
+                    tb->lone = lone;
+                // The statistics for the host, as whole-wave stores (1 KB and 512 B).  They are complete when
+                // this kernel ends; the stamp that tells the host to look is written by the kernel after it.
+                HostRecord::Item *mine = &record->item[slot_id.item];
+                reinterpret_cast<uint4 *>(mine->counts)[lane] = c4;
+                reinterpret_cast<uint2 *>(mine->freq)[lane] = make_uint2(f[0] | (f[1] << 16), f[2] | (f[3] << 16));
+            }
+        }
+    } else {
+        // the table the blob holds
         const EncSym e = encoder_constants(tb->freq[threadIdx.x], tb->cum[threadIdx.x]);
         enc_raw[threadIdx.x] = make_uint4(__float_as_uint(e.rcp), e.limit, e.cmpl_cum, e.f);
     }
-    if (SPLIT < 0 && slot_id.wg == 0) {
-        // statistics for the host: posted early, they land long before this kernel ends
-        record->item[slot_id.item].counts[threadIdx.x] = tb->counts[threadIdx.x];
-        record->item[slot_id.item].freq[threadIdx.x] = tb->freq[threadIdx.x];
-    }
     __syncthreads();
+    if (table_wg) {
+        // fills in the decoder's slot table while the others encode
+        build_slot_table(tb, reinterpret_cast<const uint32_t *>(rings));
+        return;
+    }
     const EncSym *enc = reinterpret_cast<const EncSym *>(enc_raw);
 
     const uint32_t lane_id = slot_id.wg * kEncThreads + threadIdx.x;  // = chunk * 16 + state
@@ -882,10 +918,8 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
         }
     }
     if constexpr (SPLIT >= 0) {
-        if (least_rcp == 0.0f) {
-            atomicOr(&stale[slot_id.item], 1u);
-            wait_for_memory_acks();
-        }
+        if (least_rcp == 0.0f)
+            atomicOr(&state->stale[slot_id.item], 1u);
     }
     const uint32_t len = kRunCap - st.wp;
     if (live) {
@@ -907,97 +941,93 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     }
     __syncthreads();
     if (threadIdx.x == 0) {
+        // words of this workgroup: for the compaction's offsets (by group, and added up per 64 groups
+        // and per tensor, so that a chunk's offset is a short sum) and for the host (the total)
         uint32_t total = 0;
         for (uint32_t i = 0; i < kEncThreads / kStates; ++i)
             total += group_chunk[i];
-        // device-scope store and ticket: the workgroup that takes the last ticket reads all of them
-        __hip_atomic_store(&group_words_all[group], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        wait_for_memory_acks();
-        group_chunk[0] = atomicAdd(&flags[kFlagEncDone + slot_id.item], 1u) == slot_id.wgs - 1 ? 1u : 0u;
-    }
-    __syncthreads();
-    if (!group_chunk[0])
-        return;
-    // ---- last workgroup of this tensor: exclusive prefix sum of the words per encoder workgroup (the
-    // per-chunk offsets follow from these in the compaction kernel); the total goes to the blob's last
-    // offset and to the host
-    {
-        const uint32_t tid = threadIdx.x;
-        const uint32_t n_groups = slot_id.wgs;
-        const uint32_t *group_words = group_words_all + it.group_base;
-        uint64_t *__restrict__ group_prefix = group_prefix_all + it.group_base;
-        const uint32_t per = (n_groups + kEncThreads - 1) / kEncThreads;
-        const uint32_t first = tid * per;
-        uint64_t mine = 0;
-        for (uint32_t i = first; i < first + per && i < n_groups; ++i)
-            mine += __hip_atomic_load(&group_words[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // exclusive sum of `mine` over the 256 threads
-        uint64_t incl = mine;
-#pragma unroll
-        for (uint32_t d = 1; d < 64; d <<= 1) {
-            const uint64_t o = __shfl_up(incl, d, 64);
-            if ((tid & 63u) >= d)
-                incl += o;
-        }
-        if ((tid & 63u) == 63u)
-            scratch[tid >> 6] = incl;
-        __syncthreads();
-        uint64_t run = incl - mine;
-        for (uint32_t wv = 0; wv < (tid >> 6); ++wv)
-            run += scratch[wv];
-        for (uint32_t i = first; i < first + per && i < n_groups; ++i) {
-            group_prefix[i] = run;
-            run += __hip_atomic_load(&group_words[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (tid == kEncThreads - 1) {
-            const uint32_t was_stale = SPLIT >= 0 ? atomicExch(&stale[slot_id.item], 0u) : 0u;
-            uint32_t *__restrict__ last_offset = it.offsets + n_chunks;
-            last_offset[0] = static_cast<uint32_t>(run);
-            // the word behind the last offset tells the compaction to leave this tensor alone
-            last_offset[1] = (was_stale || (run >> 32)) ? 1u : 0u;
-            record->item[slot_id.item].total_words[0] = static_cast<uint32_t>(run);
-            record->item[slot_id.item].total_words[1] = static_cast<uint32_t>(run >> 32);  // non-zero: too long for 32-bit offsets
-            record->item[slot_id.item].stale = was_stale;
-            flags[kFlagEncDone + slot_id.item] = 0;
-            // the tensor that finishes last publishes the stamp and sets the counter back
-            __threadfence_system();
-            if (atomicAdd(&flags[kFlagAllDone], 1u) == b.count - 1) {
-                flags[kFlagAllDone] = 0;
-                __threadfence_system();
-                __hip_atomic_store(&record->seq, b.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-            }
-        }
+        group_words_all[group] = total;
+        atomicAdd(&super_words_all[it.super_base + slot_id.wg / kSuperGroups], total);
+        atomicAdd(&state->total[slot_id.item], static_cast<unsigned long long>(total));
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// Kernel 5: gather the runs from the workspace slots into the blob's word section and write the
+// Kernel 4: gather the runs from the workspace slots into the blob's word section and write the
 // chunk offsets.  One wave per chunk.  The chunk's slot pieces are read with 128-bit loads and
 // laid out in LDS as the 16 runs one after the other, shifted so that LDS and destination agree
 // modulo 16 bytes; the chunk then leaves with 128-bit stores (2-byte stores only for the few
 // words before the first and after the last 16-byte boundary, which neighbouring chunks share).
+// A chunk's offset is the sum of the words of the groups before its own -- whole blocks of 64
+// groups from the encoder's per-block sums, the rest group by group -- and of the chunks before it
+// in its group.
+// The launch usually follows the encoder's at once, before the host knows the stream's length, into
+// the room the blob has: a tensor whose words do not fit that room, or whose kept table turned out
+// stale, is left alone, and the host launches again once it has made room.  In that first launch
+// (b.report) the first wave of each tensor also tells the host the length, and returns to zero what
+// the next call needs at zero: the histogram bins and the other copy of the call state.
 // ------------------------------------------------------------------------------------------
 constexpr uint32_t kCompactThreads = 256;
 
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const CompressBatch b,
                                                                  const uint16_t *__restrict__ slots_all,
                                                                  const uint32_t *__restrict__ chunk_words_all,
-                                                                 const uint64_t *__restrict__ group_prefix_all)
+                                                                 const uint32_t *__restrict__ group_words_all,
+                                                                 const uint32_t *__restrict__ super_words_all,
+                                                                 const CallState *__restrict__ state,
+                                                                 uint32_t *__restrict__ counts_ws,
+                                                                 CallState *__restrict__ state_next,
+                                                                 uint32_t *__restrict__ super_next, uint32_t super_cap,
+                                                                 uint32_t *__restrict__ all_done,
+                                                                 HostRecord *__restrict__ record)
 {
     const ItemSlot slot_id = item_of_workgroup<&CompressItem::compact_end>(b);
     const CompressItem &it = b.it[slot_id.item];
     const uint32_t n_chunks = it.n_chunks;
-    // The launch may have been made before the host knew the stream's length (into the room the blob
-    // had): a tensor whose words do not fit that room, or whose kept table turned out stale, is left
-    // alone (the same for all workgroups of the tensor).
-    if (n_chunks == 0 || it.offsets[n_chunks + 1] != 0 || it.offsets[n_chunks] > it.words_cap)
+    const unsigned long long all_words = state->total[slot_id.item];
+    const uint32_t was_stale = state->stale[slot_id.item];
+    if (b.report && slot_id.wg == 0 && threadIdx.x < 64) {
+        const uint32_t lane = threadIdx.x;
+        // every workgroup of the encoder launch has read the counts: the bins go back to zero
+        reinterpret_cast<uint4 *>(counts_ws + 256 * slot_id.item)[lane] = make_uint4(0, 0, 0, 0);
+        // the other copy of the call state, for the call after this one (nobody is using it now)
+        if (slot_id.item == 0) {
+            for (uint32_t i = lane; i < sizeof(CallState) / 4; i += 64)
+                reinterpret_cast<uint32_t *>(state_next)[i] = 0;
+            for (uint32_t i = lane; i < super_cap; i += 64)
+                super_next[i] = 0;
+        }
+        if (lane == 0) {
+            if (n_chunks > 0) {
+                it.offsets[n_chunks] = static_cast<uint32_t>(all_words);
+                it.offsets[n_chunks + 1] = 0;
+            }
+            // The record is host memory the host polls.  Its words are written past the caches; once
+            // they are acknowledged this tensor counts as reported, and the tensor reported last
+            // writes the stamp, which therefore cannot overtake any of them.
+            HostRecord::Item *mine = &record->item[slot_id.item];
+            __hip_atomic_store(&mine->total_words[0], static_cast<uint32_t>(all_words), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(&mine->total_words[1], static_cast<uint32_t>(all_words >> 32), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_SYSTEM);  // non-zero: too long for 32-bit offsets
+            __hip_atomic_store(&mine->stale, was_stale, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            wait_for_memory_acks();
+            if (atomicAdd(all_done, 1u) == b.count - 1) {
+                *all_done = 0;
+                __hip_atomic_store(&record->seq, b.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            }
+        }
+    }
+    // (the same decision in all workgroups of the tensor)
+    if (n_chunks == 0 || was_stale != 0 || all_words > it.words_cap || (all_words >> 32) != 0)
         return;
     const uint8_t *__restrict__ lens = it.lens;
     uint32_t *__restrict__ offsets = it.offsets;
     uint16_t *__restrict__ words = it.words;
     const uint16_t *__restrict__ slots = slots_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup * kStates * kRunCap;
     const uint32_t *__restrict__ chunk_words = chunk_words_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup;
-    const uint64_t *__restrict__ group_prefix = group_prefix_all + it.group_base;
+    const uint32_t *__restrict__ group_words = group_words_all + it.group_base;
+    const uint32_t *__restrict__ super_words = super_words_all + it.super_base;
 
     __shared__ __align__(16) uint16_t gathered[kCompactThreads / 64][kStates * kRunCap + 8];
     const uint32_t wave = threadIdx.x / 64, lane = threadIdx.x & 63;
@@ -1030,13 +1060,16 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const Compress
         }
         total = __shfl(start, kStates - 1, kStates);
         start -= my_len;
-        // words before this chunk: those before its encoder group plus the earlier chunks of the group
+        // words before this chunk: the whole blocks of 64 encoder groups before its group, the groups
+        // before it in its block, the chunks before it in its group
         const uint32_t g = c / kChunksPerGroup, in_group = c % kChunksPerGroup;
-        uint32_t earlier = lane < in_group ? chunk_words[g * kChunksPerGroup + lane] : 0u;
-#pragma unroll
-        for (uint32_t d = 1; d < kChunksPerGroup; d <<= 1)
-            earlier += __shfl_xor(earlier, d, kChunksPerGroup);
-        at0 = group_prefix[g] + __shfl(earlier, 0, 64);
+        const uint32_t blocks = g / kSuperGroups, in_block = g % kSuperGroups;
+        // (32-bit sums: the tensor's words, which fit the destination, are fewer than 2^32)
+        uint32_t before = lane < in_block ? group_words[blocks * kSuperGroups + lane] : 0u;
+        before += lane < in_group ? chunk_words[g * kChunksPerGroup + lane] : 0u;
+        for (uint32_t i = lane; i < blocks; i += 64)
+            before += super_words[i];
+        at0 = wave_sum_u32(before);
         if (lane == 0)
             offsets[c] = static_cast<uint32_t>(at0);
         shift = static_cast<uint32_t>(at0 & 7u);

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <cstddef>
 #include <cstdint>
 #include "neuzip.h"
 
@@ -90,6 +91,7 @@ struct CompressItem {
     uint32_t block;        // 0: no block-wise normalisation
     uint32_t guard;        // exponents this far outside the occupied range keep f = 1 in the table
     uint32_t group_base;   // first encoder group (16 chunks) of this tensor in the workspace arrays
+    uint32_t super_base;   // first entry of this tensor in the array of words per 64 encoder groups
     uint32_t hist_end;     // first workgroup after this tensor's in the histogram launch
     uint32_t enc_end;      // ... in the encode launch
     uint32_t compact_end;  // ... in the compaction launch
@@ -101,12 +103,23 @@ struct CompressBatch {
     uint32_t seq;  // stamp of this call
     float lr;      // learning rate of the fused weight step
     uint32_t keep_new;  // fused weight step: write the new weight back over the source
+    uint32_t report;    // compaction launch: also report the stream lengths to the host and tidy the workspace
 };
+
+// What the encoder workgroups of a call add up for the compaction and for the host, in the workspace.
+// There are two copies, used by alternate calls: while one call's compaction reads its copy, it
+// returns the other one (and the histogram bins) to zero for the call that follows.
+struct CallState {
+    unsigned long long total[kBatchMax];  // words of tensor i
+    uint32_t stale[kBatchMax];            // recompression met an exponent without room in tensor i's table
+    uint32_t pad[8];
+};
+constexpr uint32_t kSuperGroups = 64;  // encoder groups whose words are also added up in one entry
 
 // Host-visible results of one compress call (pinned host memory the kernels write directly).
 struct HostRecord {
     uint32_t seq;  // stamp of the compress call whose results are complete (written last)
-    uint32_t pad;
+    uint32_t pad[3];  // (the items, and the arrays in them, are 16-byte aligned)
     struct Item {
         uint32_t total_words[2];
         uint32_t stale;    // recompression only: an exponent had no room in the blob's table
@@ -115,5 +128,6 @@ struct HostRecord {
         uint16_t freq[256];
     } item[kBatchMax];
 };
+static_assert(sizeof(HostRecord::Item) % 16 == 0 && offsetof(HostRecord, item) % 16 == 0, "whole-wave 128-bit stores");
 
 }  // namespace nz

@@ -59,7 +59,7 @@ def test_config1_gaussian_1024x1024(nz):
     assert np.array_equal(nz.neuzip_frequencies(blob), O.quantise(cnt))
     bits_per_weight = 8 * blob.compressed_bytes / words.size
     assert bits_per_weight <= 1.02 * (O.entropy(cnt) + 8)
-    assert blob.device_bytes < 1.01 * blob.compressed_bytes + 8192
+    assert blob.device_bytes < 1.01 * blob.compressed_bytes + 16384   # tables, alignment, 1/64 of headroom for the words
 
 
 @pytest.mark.parametrize("k", KS)
