@@ -754,6 +754,28 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     uint32_t *__restrict__ chunk_words = chunk_words_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup;
     uint16_t *__restrict__ slots = slots_all + static_cast<uint64_t>(it.group_base) * kChunksPerGroup * kStates * kRunCap;
 
+    const uint32_t lane_id = slot_id.wg * kEncThreads + threadIdx.x;  // = chunk * 16 + state
+    const uint32_t c = lane_id / kStates, j = lane_id % kStates;
+    const bool live = !table_wg && c < n_chunks;
+    const uint64_t base = static_cast<uint64_t>(c) * kChunk;
+    const uint32_t m = !live ? 0u : ((n - base) < kChunk ? static_cast<uint32_t>(n - base) : kChunk);
+    // The source words of a full chunk are requested two turns ahead, in three buffers used in
+    // rotation; the first two requests go out here, so that they travel while the table is made.
+    // This state's first 8-element vector of the chunk; a turn later is kStates vectors on.
+    const uint4 *src4 = static_cast<const uint4 *>(src) + (base / 8 + j) * (WIDE ? 2 : 1);
+    // the gradients travel with the weights, one 128-bit piece per turn
+    const uint4 *grad4 = UPD ? reinterpret_cast<const uint4 *>(grad) + (base / 8 + j) : nullptr;
+    SourceVec<WIDE> d0, d1, d2;
+    uint4 g0 = make_uint4(0, 0, 0, 0), g1 = g0, g2 = g0;
+    if (m == kChunk) {
+        d0.load(src4, (kTurns - 1) * kStates);
+        d1.load(src4, (kTurns - 2) * kStates);
+        if constexpr (UPD) {
+            g0 = grad4[(kTurns - 1) * kStates];
+            g1 = grad4[(kTurns - 2) * kStates];
+        }
+    }
+
     // ---- encoder constants of the 256 symbols
     if constexpr (SPLIT < 0) {
         // Fresh statistics: the histogram pass has left the 256 counts in the workspace; the first wave
@@ -806,11 +828,6 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     }
     const EncSym *enc = reinterpret_cast<const EncSym *>(enc_raw);
 
-    const uint32_t lane_id = slot_id.wg * kEncThreads + threadIdx.x;  // = chunk * 16 + state
-    const uint32_t c = lane_id / kStates, j = lane_id % kStates;
-    const bool live = c < n_chunks;
-    const uint64_t base = static_cast<uint64_t>(c) * kChunk;
-    const uint32_t m = !live ? 0u : ((n - base) < kChunk ? static_cast<uint32_t>(n - base) : kChunk);
     uint16_t *chunk_slots = slots + static_cast<uint64_t>(c) * kStates * kRunCap;
     uint16_t *ring = rings + threadIdx.x * kRingWords;
     uint8_t *ring_bytes = reinterpret_cast<uint8_t *>(rings);
@@ -820,24 +837,11 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     uint8_t *__restrict__ sm = it.sm;
 
     if (m == kChunk) {
-        // this state's first 8-element vector of the chunk; a turn later is kStates vectors on
-        const uint4 *src4 = static_cast<const uint4 *>(src) + (base / 8 + j) * (WIDE ? 2 : 1);
-        // the source words are requested two turns ahead: the wait for a turn's words then leaves
-        // the stores of the turn before (ring flush, fields) in flight instead of waiting for them
-        SourceVec<WIDE> d, d_next;
-        d.load(src4, (kTurns - 1) * kStates);
-        d_next.load(src4, (kTurns - 2) * kStates);
-        // the gradients travel with the weights, one 128-bit piece per turn
-        const uint4 *grad4 = UPD ? reinterpret_cast<const uint4 *>(grad) + (base / 8 + j) : nullptr;
-        uint4 g = make_uint4(0, 0, 0, 0), g_next = g;
-        if constexpr (UPD) {
-            g = grad4[(kTurns - 1) * kStates];
-            g_next = grad4[(kTurns - 2) * kStates];
-        }
-        for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
-            SourceVec<WIDE> d_after;
+        // One turn: the vector of turn q - 2 is requested into the buffer that is free (the wait for a
+        // turn's words then leaves the stores of the turn before -- ring flush, fields -- in flight
+        // instead of waiting for them), then turn q is coded from its buffer.
+        auto turn = [&](const SourceVec<WIDE> &d, const uint4 &g, SourceVec<WIDE> &d_after, uint4 &g_after, int q) {
             d_after.load(src4, (q > 1 ? q - 2 : 0) * kStates);
-            uint4 g_after = g;
             if constexpr (UPD)
                 g_after = grad4[(q > 1 ? q - 2 : 0) * kStates];
             uint32_t w[4];
@@ -868,20 +872,27 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
                 const uint32_t hi = NORM ? normalise_word(w[p] >> 16, c) : (w[p] >> 16);
                 const uint32_t lo = NORM ? normalise_word(w[p] & 0xFFFFu, c) : (w[p] & 0xFFFFu);
                 const EncSym e_hi = enc[symbol_of<HALF>(hi)], e_lo = enc[symbol_of<HALF>(lo)];
-                if constexpr (SPLIT >= 0)
+                if constexpr (SPLIT >= 0) {
                     least_rcp = fminf(least_rcp, fminf(e_hi.rcp, e_lo.rcp));
+                    // (taken here and now: left to the scheduler, the minimum is put off to the end of the
+                    // loop body and every symbol's four registers stay occupied until then)
+                    asm volatile("" : "+v"(least_rcp));
+                }
                 rans_put(st, e_hi, ring_bytes, lane_ring);
                 rans_put(st, e_lo, ring_bytes, lane_ring);
             }
             ring_advance(st, cur_before);
             ring_flush(wp_before, st.wp, ring, chunk_slots, j);
-            d = d_next;
-            d_next = d_after;
-            if constexpr (UPD) {
-                g = g_next;
-                g_next = g_after;
-            }
+        };
+        // turns kTurns - 1 .. 2 in groups of three (so that no buffer has to be copied into another)
+        static_assert((kTurns - 2) % 3 == 0, "the rotation of three buffers ends with turns 1 and 0 in the first two");
+        for (int q = static_cast<int>(kTurns) - 1; q >= 2; q -= 3) {
+            turn(d0, g0, d2, g2, q);
+            turn(d1, g1, d0, g0, q - 1);
+            turn(d2, g2, d1, g1, q - 2);
         }
+        turn(d0, g0, d2, g2, 1);
+        turn(d1, g1, d0, g0, 0);
     } else if (m > 0) {
         for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
             const uint32_t wp_before = st.wp, cur_before = st.cur;
