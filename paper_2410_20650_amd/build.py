@@ -4,7 +4,9 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-LIB = os.path.join(HERE, "libneuzip.so")
+# NEUZIP_LIBRARY points the binding at another build of the library (tuning runs); build() always writes the in-tree one
+LIB = os.environ.get("NEUZIP_LIBRARY") or os.path.join(HERE, "libneuzip.so")
+BUILT_LIB = os.path.join(HERE, "libneuzip.so")
 SOURCES = [os.path.join(HERE, "csrc", "neuzip.hip")]
 HEADERS = [os.path.join(ROOT, "include", "neuzip.h")] + [
     os.path.join(HERE, "csrc", name)
@@ -20,19 +22,19 @@ HIPCC_FLAGS = [
 
 
 def is_stale() -> bool:
-    if not os.path.exists(LIB):
+    if not os.path.exists(BUILT_LIB):
         return True
-    built = os.path.getmtime(LIB)
+    built = os.path.getmtime(BUILT_LIB)
     return any(os.path.getmtime(p) > built for p in SOURCES + HEADERS)
 
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), *SOURCES, "-o", LIB]
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), *SOURCES, "-o", BUILT_LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return BUILT_LIB
 
 
 if __name__ == "__main__":

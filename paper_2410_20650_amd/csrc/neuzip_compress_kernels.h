@@ -399,6 +399,8 @@ __device__ __forceinline__ void merge_bins(const uint32_t *__restrict__ bins, ui
 {
     __syncthreads();
     const uint32_t s = threadIdx.x;
+    if (s >= 256)
+        return;
     uint32_t sum = 0;
 #pragma unroll 8
     for (uint32_t i = 0; i < kHistCopies; ++i)
@@ -413,7 +415,10 @@ __device__ __forceinline__ void merge_bins(const uint32_t *__restrict__ bins, ui
 // bank-private copies of the 256 bins in LDS (copy = lane mod 32, so the 64 lanes of a wave
 // hit 32 different banks whatever the symbol skew is), then one global atomic per bin.
 // ------------------------------------------------------------------------------------------
-constexpr uint32_t kHistThreads = 256;
+// Workgroups of 256 threads for tensors that stream through HBM, of 1024 threads (and fewer of them)
+// for a batch that fits the last-level cache: there the pass is short, and the merges of the
+// workgroups' bins into the global ones, which all arrive at its end, are what is left to shorten.
+constexpr uint32_t kHistThreadsMax = 1024;
 
 // Which tensor of the batch a workgroup of one of the wide launches works on.
 struct ItemSlot {
@@ -434,7 +439,7 @@ __device__ __forceinline__ ItemSlot item_of_workgroup(const CompressBatch &b)
 }
 
 template <int KB, bool WIDE = false, bool HALF = false>
-__global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const CompressBatch b,
+__global__ __launch_bounds__(kHistThreadsMax) void hist_split_kernel(const CompressBatch b,
                                                                  uint32_t *__restrict__ counts_ws)
 {
     const ItemSlot slot = item_of_workgroup<&CompressItem::hist_end>(b);
@@ -444,18 +449,18 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const Compress
     uint16_t *__restrict__ low = b.it[slot.item].low;
     uint32_t *__restrict__ counts = counts_ws + 256 * slot.item;
     __shared__ uint32_t bins[256 * kHistCopies];
-    for (uint32_t i = threadIdx.x; i < 256 * kHistCopies; i += kHistThreads)
+    for (uint32_t i = threadIdx.x; i < 256 * kHistCopies; i += blockDim.x)
         bins[i] = 0;
     __syncthreads();
 
     const uint32_t copy = threadIdx.x & (kHistCopies - 1);
     const uint64_t n_vec = n / 8;
-    const uint64_t stride = static_cast<uint64_t>(slot.wgs) * kHistThreads;
+    const uint64_t stride = static_cast<uint64_t>(slot.wgs) * blockDim.x;
     const uint4 *src4 = static_cast<const uint4 *>(src);
     // eight 128-bit loads are in flight per lane before any of them is used (four vectors of
     // binary32, which take two loads each); measured 5 % faster than four on a cache-resident tensor
     constexpr uint32_t kDepth = WIDE ? 4 : 8;
-    for (uint64_t v0 = static_cast<uint64_t>(slot.wg) * kHistThreads + threadIdx.x; v0 < n_vec;
+    for (uint64_t v0 = static_cast<uint64_t>(slot.wg) * blockDim.x + threadIdx.x; v0 < n_vec;
          v0 += stride * kDepth) {
         SourceVec<WIDE> d[kDepth];
 #pragma unroll
@@ -511,7 +516,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_kernel(const Compress
 // normalises its weights and proceeds as kernel 1 on the normalised words.
 // ------------------------------------------------------------------------------------------
 template <int KB>
-__global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const CompressBatch b,
+__global__ __launch_bounds__(kHistThreadsMax) void hist_split_norm_kernel(const CompressBatch b,
                                                                       uint32_t *__restrict__ counts_ws)
 {
     const ItemSlot slot = item_of_workgroup<&CompressItem::hist_end>(b);
@@ -522,7 +527,7 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const Com
     uint8_t *__restrict__ sm = b.it[slot.item].sm;
     uint32_t *__restrict__ counts = counts_ws + 256 * slot.item;
     __shared__ uint32_t bins[256 * kHistCopies];
-    for (uint32_t i = threadIdx.x; i < 256 * kHistCopies; i += kHistThreads)
+    for (uint32_t i = threadIdx.x; i < 256 * kHistCopies; i += blockDim.x)
         bins[i] = 0;
     __syncthreads();
 
@@ -530,10 +535,10 @@ __global__ __launch_bounds__(kHistThreads) void hist_split_norm_kernel(const Com
     const uint32_t lanes_per_block = block / 8;                 // 4 .. 64, a power of two
     const uint32_t block_shift = 31u - static_cast<uint32_t>(__clz(static_cast<int>(block)));
     const uint64_t n_vec = (n + 7) / 8;                         // the last vector may be partial
-    const uint64_t stride = static_cast<uint64_t>(slot.wgs) * kHistThreads;
+    const uint64_t stride = static_cast<uint64_t>(slot.wgs) * blockDim.x;
     constexpr uint32_t per_byte = 8 / (KB + 1);
     // the trip count is the same for all lanes of a wave, so every lane takes part in the shuffles
-    const uint64_t wave_first = static_cast<uint64_t>(slot.wg) * kHistThreads + (threadIdx.x & ~63u);
+    const uint64_t wave_first = static_cast<uint64_t>(slot.wg) * blockDim.x + (threadIdx.x & ~63u);
     for (uint64_t base = wave_first; base < n_vec; base += stride) {
         const uint64_t v = base + (threadIdx.x & 63u);
         const uint64_t first = v * 8;
