@@ -142,6 +142,10 @@ class Model:
         self.nz = nz
 
     def tensor_by_tensor(self):
+        for b in self.blobs:
+            self.nz.neuzip_decompress(b, self.big[: b.elems])
+
+    def sequence(self):
         self.nz.neuzip_decompress_sequence(self.blobs, self.big)
 
     def layer_by_layer(self):
@@ -393,13 +397,16 @@ def main():
         model = Model(torch, nz, inputs, dev, args.layers)
         c3 = {"tensors": len(model.blobs), "elements": model.total,
               "bits_per_weight": round(8.0 * model.comp / model.total, 4)}
-        for label, fn in (("tensor_by_tensor", model.tensor_by_tensor), ("layer_by_layer", model.layer_by_layer)):
+        for label, fn in (("tensor_by_tensor", model.tensor_by_tensor), ("sequence", model.sequence),
+                          ("layer_by_layer", model.layer_by_layer)):
             us = event_us(torch, stream, fn, 5, warm=2)
             c3[label] = {"ms": round(us / 1e3, 4), "GBps_output": round(2.0 * model.total / us / 1e3, 1),
                          "hbm_frac": hbm_frac(model.comp + 2.0 * model.total, us)}
-        c3["schedules"] = ("tensor_by_tensor: neuzip_decompress_sequence, one launch per tensor into the start of the "
-                           "scratch; layer_by_layer: neuzip_decompress_batch, the 7 weights of a layer in one launch "
-                           "into 7 pieces of the same scratch")
+        c3["schedules"] = ("all into ONE scratch of the embedding's size.  tensor_by_tensor: neuzip_decompress per tensor, "
+                           "each to the start of the scratch (the small projections cannot fill the chip); sequence: one "
+                           "neuzip_decompress_sequence call, neighbours that fit the scratch together share it and a "
+                           "launch (8 per launch); layer_by_layer: neuzip_decompress_batch, the 7 weights of a layer "
+                           "in one launch into 7 pieces of the scratch")
         result["config3"] = c3
 
         # ------------------------------------------------------------ config 5: training-step loop

@@ -225,17 +225,25 @@ int neuzip_decompress(const neuzip_blob *blob, void *d_dst, uint64_t n_elems, in
 /*
  * neuzip_decompress_sequence -- the per-layer schedule of Sec. 2.2 / Alg. 1
  * forward loop: every blob, in the given order, is decompressed into the same
- * temporary space, one after the other on hip_stream, so that the whole model
- * is never held uncompressed.
+ * temporary space on hip_stream, so that the whole model is never held
+ * uncompressed.
  *
  *   blobs          host array of count blob handles.
  *   d_scratch      device buffer of scratch_elems bf16 words (2 * scratch_elems bytes), 16-byte
  *                  aligned; must hold the largest tensor, a binary32 blob counting two words
  *                  per element (else EINVAL, nothing is run).
+ *   h_offsets      NULL, or a host array of count entries that receives where each tensor goes:
+ *                  its first 16-bit word's index in the space.
+ * Neighbouring blobs of one kind (element type, mantissa_bits, normalisation) that fit the space
+ * together -- the projections of a layer, say -- are placed one behind the other, each at a
+ * 256-byte boundary, and share one launch (at most 8 per launch), so that tensors too small to
+ * fill the GPU on their own overlap; the next group starts at the front of the space again and
+ * overwrites it.  When the call's work has run, the tensors of the last group are what the space
+ * holds.  A caller that consumes the weights between the groups issues one call per layer.
  * Never allocates, never synchronises.
  */
 int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, void *d_scratch,
-                               uint64_t scratch_elems, void *hip_stream);
+                               uint64_t scratch_elems, uint64_t *h_offsets, void *hip_stream);
 
 /*
  * neuzip_decompress_batch -- Sec. 2.2 Eq. (3) / Alg. 1 "decompression" + "merge" for the

@@ -53,7 +53,7 @@ def _load():
     lib.neuzip_guard.restype = u32
     lib.neuzip_decompress.argtypes = [vp, vp, u64, i32, vp]
     lib.neuzip_decompress.restype = i32
-    lib.neuzip_decompress_sequence.argtypes = [vpp, u32, vp, u64, vp]
+    lib.neuzip_decompress_sequence.argtypes = [vpp, u32, vp, u64, ctypes.POINTER(u64), vp]
     lib.neuzip_decompress_sequence.restype = i32
     lib.neuzip_decompress_batch.argtypes = [vpp, vpp, u32, vp]
     lib.neuzip_decompress_batch.restype = i32
@@ -280,14 +280,18 @@ def neuzip_decompress(blob: Blob, dst: torch.Tensor, stream=None) -> torch.Tenso
     return dst
 
 
-def neuzip_decompress_sequence(blobs, scratch: torch.Tensor, stream=None) -> None:
+def neuzip_decompress_sequence(blobs, scratch: torch.Tensor, stream=None):
+    """Decompresses the blobs in order into the one scratch tensor; returns, per blob, the index of its
+    first element in the scratch (neighbouring blobs that fit together share the space and a launch)."""
     dtype = _check_tensor(scratch, wide_ok=True)
     arr = (ctypes.c_void_p * len(blobs))(*[b.handle.value for b in blobs])
-    # the library counts the scratch in 16-bit words
+    offsets = (ctypes.c_uint64 * len(blobs))()
+    # the library counts the scratch, and the offsets, in 16-bit words
     rc = _lib.neuzip_decompress_sequence(arr, len(blobs), ctypes.c_void_p(scratch.data_ptr()),
-                                         scratch.numel() * (2 if dtype == F32 else 1), _stream_handle(stream))
+                                         scratch.numel() * (2 if dtype == F32 else 1), offsets, _stream_handle(stream))
     if rc != OK:
         raise NeuzipError(rc, "neuzip_decompress_sequence")
+    return [int(v) // (2 if dtype == F32 else 1) for v in offsets]
 
 
 def neuzip_decompress_batch(blobs, dsts, stream=None) -> None:

@@ -1176,22 +1176,59 @@ int neuzip_decompress(const neuzip_blob *blob, void *d_dst, uint64_t n_elems, in
 }
 
 int neuzip_decompress_sequence(const neuzip_blob *const *blobs, uint32_t count, void *d_scratch,
-                               uint64_t scratch_elems, void *hip_stream)
+                               uint64_t scratch_elems, uint64_t *h_offsets, void *hip_stream)
 {
     if (count > 0 && !blobs)
         return NEUZIP_EINVAL;
     if (reinterpret_cast<uintptr_t>(d_scratch) & 15u)
         return NEUZIP_EINVAL;
+    auto words_of = [](const neuzip_blob *b) { return b->elem == NEUZIP_F32 ? 2 * b->n : b->n; };
     for (uint32_t i = 0; i < count; ++i) {
-        if (!is_blob(blobs[i]) || !blobs[i]->has_table ||
-            ((blobs[i]->elem == NEUZIP_F32) ? 2 * blobs[i]->n : blobs[i]->n) > scratch_elems ||
+        if (!is_blob(blobs[i]) || !blobs[i]->has_table || words_of(blobs[i]) > scratch_elems ||
             (blobs[i]->n > 0 && !d_scratch) || !on_current_device(blobs[i]))
             return NEUZIP_EINVAL;
     }
-    for (uint32_t i = 0; i < count; ++i) {
-        const int rc = decode_dispatch(blobs[i], d_scratch, static_cast<hipStream_t>(hip_stream));
-        if (rc != NEUZIP_OK)
-            return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // Neighbouring blobs of one kind that fit the space together are placed one behind the other, each
+    // at a 256-byte boundary, and share a launch (up to kBatchMax of them): tensors too small to fill
+    // the chip on their own then overlap.  The next group starts at the front of the space again.
+    uint32_t first = 0;
+    while (first < count) {
+        BatchArgs args;
+        args.count = 0;
+        uint32_t groups = 0;
+        uint64_t at = 0;  // 16-bit words from the start of the space
+        const int kind = decode_variant(blobs[first]);
+        uint32_t i = first, live = first;  // live: the last blob of the group that has elements
+        for (; i < count && args.count < kBatchMax; ++i) {
+            const neuzip_blob *b = blobs[i];
+            if (decode_variant(b) != kind || at + words_of(b) > scratch_elems)
+                break;
+            if (h_offsets)
+                h_offsets[i] = at;
+            if (b->n > 0) {
+                DecodeArgs a = decode_args(b, static_cast<uint16_t *>(d_scratch) + at);
+                groups += (b->n_chunks + batch_chunks_per_wg(kind) - 1) / batch_chunks_per_wg(kind);
+                a.wg_end = groups;
+                args.t[args.count++] = a;
+                live = i;
+            }
+            at = pad_to(at + words_of(b), 128);
+        }
+        if (args.count == 1) {
+            // a tensor on its own takes the single-tensor launch (its workgroup size follows the tensor's size)
+            const int rc = decode_dispatch(blobs[live], args.t[0].out, stream);
+            if (rc != NEUZIP_OK)
+                return rc;
+        } else if (args.count > 1) {
+            const bool stream_out = at >= (64ull << 20);  // the group as a whole exceeds the cache
+            for (uint32_t t = 0; t < args.count; ++t)
+                args.t[t].stream_out = stream_out ? 1u : 0u;
+            const int rc = launch_batch(args, kind, groups, stream);
+            if (rc != NEUZIP_OK)
+                return rc;
+        }
+        first = i;
     }
     return NEUZIP_OK;
 }

@@ -108,11 +108,15 @@ def test_config3_forward_schedule_llama3_8b_shapes(nz):
     assert total == 7_504_658_432
     assert 8 * comp / total < 10.76                        # 2 % over entropy + 8 bits
     # the whole forward pass in one call; the scratch ends up holding the last layer
-    nz.neuzip_decompress_sequence(blobs, scratch)
+    at = nz.neuzip_decompress_sequence(blobs, scratch)
     for b in blobs:
         nz.neuzip_check(b)
-    last = blobs[-1].elems
-    assert int(scratch[:last].view(torch.int16).to(torch.int64).sum().item()) == sums[-1]
+    # the embedding fills the scratch; after it the projections go through in groups of 8 that share the space
+    assert at[0] == 0 and at[1] == 0 and at[9] == 0 and all(a % 128 == 0 for a in at)
+    assert at[2] == blobs[1].elems and at[8] == sum(b.elems for b in blobs[1:8])
+    for i in range(len(blobs) - 8, len(blobs)):           # 224 projections = 28 groups: the last group is whole
+        piece = scratch[at[i]: at[i] + blobs[i].elems]
+        assert int(piece.view(torch.int16).to(torch.int64).sum().item()) == sums[i], names[i][0]
 
 
 def test_device_memory_held_matches_the_accounting(nz):

@@ -134,11 +134,12 @@ def test_f32_batches_and_sequence(nz):
     assert np.array_equal(inputs.bits(outs[-1]), inputs.bits(h))
     # one scratch buffer for all, sized for the largest tensor in 16-bit words
     scratch = torch.zeros(512 * 1792, dtype=torch.float32, device=DEV)
-    nz.neuzip_decompress_sequence(blobs + [hb], scratch)
+    at = nz.neuzip_decompress_sequence(blobs + [hb], scratch)
     torch.cuda.synchronize()
+    assert at[-1] == 0                                   # another element type: a group of its own
     assert np.array_equal(inputs.bits(scratch.view(torch.bfloat16)[:50_000]), inputs.bits(h))
-    nz.neuzip_decompress_sequence(blobs, scratch)
-    assert np.array_equal(inputs.bits32(scratch[:3 * 4096]), inputs.bits32(ws[-1]))
+    at = nz.neuzip_decompress_sequence(blobs, scratch)
+    assert np.array_equal(inputs.bits32(scratch[at[-1]: at[-1] + 3 * 4096]), inputs.bits32(ws[-1]))
     small = torch.zeros(512 * 1792 - 8, dtype=torch.float32, device=DEV)
     with pytest.raises(nz.NeuzipError):
         nz.neuzip_decompress_sequence(blobs, small)

@@ -209,12 +209,31 @@ def test_forward_schedule_into_one_scratch(nz):
     blobs = [nz.neuzip_compress(t, 7) for t in tensors]
     scratch = torch.zeros(max(t.numel() for t in tensors), dtype=torch.bfloat16, device=DEV)
     # one call runs the whole sequence; what is left in the scratch is the last layer
-    nz.neuzip_decompress_sequence(blobs, scratch)
-    assert torch.equal(scratch[: tensors[-1].numel()].view(torch.int16), tensors[-1].reshape(-1).view(torch.int16))
+    at = nz.neuzip_decompress_sequence(blobs, scratch)
+    last = tensors[-1]
+    assert torch.equal(scratch[at[-1]: at[-1] + last.numel()].view(torch.int16), last.reshape(-1).view(torch.int16))
     # layer by layer with a consumer in between sees every layer intact
     for t, b in zip(tensors, blobs):
-        nz.neuzip_decompress_sequence([b], scratch)
+        assert nz.neuzip_decompress_sequence([b], scratch) == [0]
         assert torch.equal(scratch[: t.numel()].view(torch.int16), t.reshape(-1).view(torch.int16))
+    # a space that holds them all: neighbours are placed one behind the other (256-byte boundaries)
+    # and share launches of up to 8; with 10 tensors the last two start at the front again
+    more = tensors + [inputs.gaussian_bf16(s, inputs.seed_for(3, 40 + i), device=DEV) for i, s in enumerate([(3, 7), (130, 100), (64, 512)])]
+    more_blobs = blobs + [nz.neuzip_compress(t, 7) for t in more[len(tensors):]]
+    roomy = torch.zeros(sum(t.numel() + 128 for t in more), dtype=torch.bfloat16, device=DEV)
+    at = nz.neuzip_decompress_sequence(more_blobs, roomy)
+    expect, run = [], 0
+    for i, t in enumerate(more):
+        if i == 8:
+            run = 0
+        expect.append(run)
+        run = (run + t.numel() + 127) // 128 * 128
+    assert at == expect
+    for i in list(range(2, 8)) + [8, 9]:                  # what the second group did not overwrite, and that group
+        t = more[i]
+        assert torch.equal(roomy[at[i]: at[i] + t.numel()].view(torch.int16), t.reshape(-1).view(torch.int16)), i
+    for b in more_blobs:
+        nz.neuzip_check(b)
     small = torch.zeros(1000, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(nz.NeuzipError):
         nz.neuzip_decompress_sequence(blobs, small)
@@ -266,7 +285,7 @@ def test_decompression_can_be_captured_in_a_hip_graph(nz):
         side.synchronize()
         with torch.cuda.graph(graph, stream=side):
             nz.neuzip_decompress_batch(blobs, outs, stream=side)
-            nz.neuzip_decompress_sequence(blobs, scratch, stream=side)
+            at = nz.neuzip_decompress_sequence(blobs, scratch, stream=side)
     for replay in range(4):
         for o in outs:
             o.fill_(float(replay))                                    # eager work between replays
@@ -277,7 +296,7 @@ def test_decompression_can_be_captured_in_a_hip_graph(nz):
         for t, o in zip(tensors, outs):
             assert torch.equal(o.view(torch.int16), t.reshape(-1).view(torch.int16)), replay
         last = tensors[-1]
-        assert torch.equal(scratch[: last.numel()].view(torch.int16), last.reshape(-1).view(torch.int16))
+        assert torch.equal(scratch[at[-1]: at[-1] + last.numel()].view(torch.int16), last.reshape(-1).view(torch.int16))
     for b in blobs:
         nz.neuzip_check(b)
 

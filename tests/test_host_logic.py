@@ -80,7 +80,7 @@ def test_argument_validation_happens_before_device_work(nz):
     assert lib.neuzip_decompress(None, fake, 16, 0, None) == nz.EINVAL
     assert lib.neuzip_check(None, None) == nz.EINVAL
     assert lib.neuzip_export(None, None, 0, None, None) == nz.EINVAL
-    assert lib.neuzip_decompress_sequence(None, 3, fake, 16, None) == nz.EINVAL
+    assert lib.neuzip_decompress_sequence(None, 3, fake, 16, None, None) == nz.EINVAL
     assert lib.neuzip_decompress_batch(None, None, 2, None) == nz.EINVAL
     assert lib.neuzip_compress_batch(None, None, 2, 0, 7, 0, None, None) == nz.EINVAL
     assert lib.neuzip_compress_batch(None, None, 0, 0, 7, 0, None, None) == nz.OK
