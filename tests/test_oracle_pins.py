@@ -696,6 +696,28 @@ def test_linear_oracle_against_exact_rational_arithmetic(k):
             assert float(mag[t, o]) >= abs(float(exact))
 
 
+@pytest.mark.parametrize("k,block", [(3, 32), (1, 64), (0, 512)])
+def test_linear_oracle_on_blockwise_normalised_weights_against_exact_rational_arithmetic(k, block):
+    # the paper's default lossy form: the layer multiplies what the three steps of the normalisation give
+    # back (normalise, truncate, de-normalise), here taken from their own definition, not from a container
+    from fractions import Fraction
+    from oracle import linear as L
+    out_f, in_f, tokens = 6, 256, 2
+    w = inputs.bits(inputs.student_t4_bf16(out_f * in_f, seed=46))
+    x = inputs.bits(inputs.gaussian_bf16(tokens * in_f, seed=47, std=1.0)).reshape(tokens, in_f)
+    blob = O.compress(w, k, block=block)
+    y = L.linear(blob, out_f, in_f, x)
+    mag = L.magnitude(blob, out_f, in_f, x)
+    values = O.lossy_blockwise(w, k, block)
+    assert not np.array_equal(values, O.truncate(w, k))                 # the normalisation does change the values
+    w_hat = [Fraction(float(v)) for v in as_float(values)]
+    xs = [[Fraction(float(v)) for v in as_float(row)] for row in x]
+    for t in range(tokens):
+        for o in range(out_f):
+            exact = sum(w_hat[o * in_f + i] * xs[t][i] for i in range(in_f))
+            assert abs(Fraction(float(y[t, o])) - exact) <= Fraction(float(mag[t, o])) * Fraction(in_f, 2 ** 52)
+
+
 def test_linear_oracle_row_sums_and_linearity():
     from oracle import linear as L
     out_f, in_f = 16, 512
