@@ -88,11 +88,14 @@ enum {
  *   blob           in/out.  *blob == NULL: a new blob is created.  Otherwise
  *                  *blob must be a blob of this library with the same n_elems
  *                  and mantissa_bits; its device memory is reused (and grown
- *                  if the new stream is longer) and its old content is lost.
+ *                  if the new stream is longer), its old content is lost, and it
+ *                  keeps the guard band it was made with (neuzip_compress_guarded).
  *
  * Builds the exponent histogram, the 12-bit frequency table, encodes every
  * 4096-symbol chunk with 16 rANS states, and stores exponent stream and
- * sign|mantissa stream in device memory sized exactly for this tensor.
+ * sign|mantissa stream in device memory sized for this tensor (the word
+ * section with 1/64 of headroom, 0.3 % of the container, so that a blob which
+ * is compressed into again after an update seldom has to be re-allocated).
  * Synchronises hip_stream once (the stream length is data dependent).
  * n_elems == 0 yields a valid empty blob.
  */
@@ -144,7 +147,10 @@ int neuzip_compress_batch(const void *const *d_srcs, const uint64_t *n_elems, ui
  *       f = 1 to every exponent up to `guard` (0..255) below the smallest and above the largest
  *       one that occurs, and to exponent 0 (an update w - lr * g cancels exactly to +-0 now and
  *       then), so that values an update newly produces still have a code.  guard = 0 is the
- *       plain table.  The guard is kept in the blob and in header word 52 of the container.
+ *       plain table.  The guard is kept in the blob and in header word 52 of the container.  For
+ *       NEUZIP_F16 the band is taken on the coded symbol, the word's upper byte (sign, exponent, two
+ *       mantissa bits): byte values up to `guard` below the smallest and above the largest one that
+ *       occurs, and byte 0.
  *   neuzip_recompress         blobs[i] (which must hold a compressed tensor) receives d_srcs[i],
  *       a tensor of neuzip_elems(blobs[i]) words, coded with the table the blob already holds:
  *       one pass over the source that splits, packs and encodes.  If a tensor holds an exponent
@@ -266,11 +272,14 @@ int neuzip_decompress_batch(const neuzip_blob *const *blobs, void *const *d_dsts
  * as one fused kernel: the decoded weights go from the decoder's registers straight into the
  * matrix cores and W_hat is never written to memory.
  *
- *   weight        blob of a row-major out_features x in_features bf16 matrix (any mantissa_bits;
- *                 block-wise normalised blobs -> EUNSUPPORTED).  in_features must be a multiple
- *                 of 128 and out_features * in_features must equal neuzip_elems(weight).
+ *   weight        blob of a row-major out_features x in_features bf16 matrix (any mantissa_bits,
+ *                 with or without block-wise normalisation; other element types ->
+ *                 EUNSUPPORTED).  in_features must be a multiple of 128 and out_features *
+ *                 in_features must equal neuzip_elems(weight).
  *   d_x           tokens x in_features bf16 activations, row-major, 16-byte aligned.
- *   tokens        1 .. 64 (larger batches: decompress once and use a dense GEMM).
+ *   tokens        at least 1.  The kernel holds the partial sums of up to 64 tokens; a larger
+ *                 batch goes through in tiles of 64, each of which decodes the weight again (for
+ *                 more than a few tiles, decompressing once and a dense GEMM is the faster way).
  *   d_bias        out_features floats on the device, or NULL.
  *   d_y           tokens x out_features floats, row-major; overwritten.
  * Products are exact, sums are accumulated in float32 by the matrix cores and, across the pieces
@@ -352,6 +361,13 @@ int neuzip_check(const neuzip_blob *blob, void *hip_stream);
 #define NEUZIP_NOALLOC_MAX_ELEMS (1ull << 22)
 int neuzip_compress_noalloc(const void *d_src, uint64_t n_elems, int dtype, int mantissa_bits,
                             void *hip_stream, neuzip_blob *blob);
+
+/* Device bytes of the workspace that compress calls share and keep between calls: the encoder's
+ * run slots -- 16 x 200 words per 4096-element chunk of the largest batch compressed so far, 1.56
+ * bytes per element -- plus word counts and histogram bins.  It is not part of any blob; Sec. 2.2's
+ * peak-memory accounting has to count it while weights are being compressed (training), and
+ * neuzip_release_workspace returns it (inference, once the model is compressed).  0 if none is held. */
+uint64_t neuzip_workspace_bytes(void);
 
 /* Frees the per-device workspace compress keeps between calls. */
 int neuzip_release_workspace(void);

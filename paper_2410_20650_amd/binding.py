@@ -79,6 +79,8 @@ def _load():
     lib.neuzip_frequencies.restype = i32
     lib.neuzip_check.argtypes = [vp, vp]
     lib.neuzip_check.restype = i32
+    lib.neuzip_workspace_bytes.argtypes = []
+    lib.neuzip_workspace_bytes.restype = u64
     lib.neuzip_release_workspace.argtypes = []
     lib.neuzip_release_workspace.restype = i32
     lib.neuzip_strerror.argtypes = [i32]
@@ -96,7 +98,7 @@ EXPORTED = ["neuzip_compress", "neuzip_compress_noalloc", "neuzip_compress_block
             "neuzip_free",
             "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits", "neuzip_dtype",
             "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check",
-            "neuzip_release_workspace", "neuzip_strerror", "neuzip_last_hip_error"]
+            "neuzip_workspace_bytes", "neuzip_release_workspace", "neuzip_strerror", "neuzip_last_hip_error"]
 
 
 def library():
@@ -378,6 +380,10 @@ def neuzip_check(blob: Blob, stream=None) -> None:
     rc = _lib.neuzip_check(blob.handle, _stream_handle(stream))
     if rc != OK:
         raise NeuzipError(rc, "neuzip_check")
+
+
+def neuzip_workspace_bytes() -> int:
+    return int(_lib.neuzip_workspace_bytes())
 
 
 def neuzip_release_workspace() -> None:

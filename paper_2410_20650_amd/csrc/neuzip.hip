@@ -469,22 +469,22 @@ int launch_batch(const BatchArgs &args, int variant, uint32_t groups, hipStream_
 // 4096 x 14336.
 inline uint32_t linear_columns(uint32_t tokens, uint32_t stride) { return tokens > 16 && stride == 1 ? 32u : 16u; }
 
-template <int KB>
+template <int KB, bool NORM>
 void launch_linear(const LinearArgs &args, uint32_t cols, uint32_t wgs, hipStream_t stream)
 {
     const dim3 grid(wgs), block(kLinThreads);
     if (cols == 32) {
         if (args.tokens <= 32)
-            hipLaunchKernelGGL((linear_kernel<KB, 32, 1>), grid, block, 0, stream, args);
+            hipLaunchKernelGGL((linear_kernel<KB, 32, 1, NORM>), grid, block, 0, stream, args);
         else
-            hipLaunchKernelGGL((linear_kernel<KB, 32, 2>), grid, block, 0, stream, args);
+            hipLaunchKernelGGL((linear_kernel<KB, 32, 2, NORM>), grid, block, 0, stream, args);
         return;
     }
     switch ((args.tokens + 15) / 16) {
-    case 1: hipLaunchKernelGGL((linear_kernel<KB, 16, 1>), grid, block, 0, stream, args); break;
-    case 2: hipLaunchKernelGGL((linear_kernel<KB, 16, 2>), grid, block, 0, stream, args); break;
-    case 3: hipLaunchKernelGGL((linear_kernel<KB, 16, 3>), grid, block, 0, stream, args); break;
-    default: hipLaunchKernelGGL((linear_kernel<KB, 16, 4>), grid, block, 0, stream, args); break;
+    case 1: hipLaunchKernelGGL((linear_kernel<KB, 16, 1, NORM>), grid, block, 0, stream, args); break;
+    case 2: hipLaunchKernelGGL((linear_kernel<KB, 16, 2, NORM>), grid, block, 0, stream, args); break;
+    case 3: hipLaunchKernelGGL((linear_kernel<KB, 16, 3, NORM>), grid, block, 0, stream, args); break;
+    default: hipLaunchKernelGGL((linear_kernel<KB, 16, 4, NORM>), grid, block, 0, stream, args); break;
     }
 }
 
@@ -826,7 +826,8 @@ int neuzip_compress_blockwise(const void *d_src, uint64_t n_elems, int dtype, in
 int neuzip_compress_batch(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int dtype,
                           int mantissa_bits, uint32_t block_size, void *hip_stream, neuzip_blob **blobs)
 {
-    return compress_batch(d_srcs, n_elems, count, dtype, mantissa_bits, block_size, 0, hip_stream, blobs);
+    // (a blob that is compressed into again keeps the guard band it was made with)
+    return compress_batch(d_srcs, n_elems, count, dtype, mantissa_bits, block_size, kKeepGuard, hip_stream, blobs);
 }
 
 int neuzip_compress_guarded(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int dtype,
@@ -984,12 +985,12 @@ int neuzip_linear(const neuzip_blob *weight, uint64_t out_features, uint64_t in_
     if (out_features == 0 || in_features == 0 || in_features % kTurn != 0 || in_features >= (1ull << 31) ||
         out_features >= (1ull << 31) || out_features * in_features != weight->n)
         return NEUZIP_EINVAL;
-    if (tokens == 0 || tokens > kLinMaxTokens)
+    if (tokens == 0)
         return NEUZIP_EINVAL;
     if ((reinterpret_cast<uintptr_t>(d_x) & 15u) || (reinterpret_cast<uintptr_t>(d_y) & 3u) ||
         (reinterpret_cast<uintptr_t>(d_bias) & 3u))
         return NEUZIP_EINVAL;
-    if (weight->block != 0 || weight->elem != NEUZIP_BF16)
+    if (weight->elem != NEUZIP_BF16)
         return NEUZIP_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     uint64_t gcd = in_features, r = kChunk;
@@ -1012,22 +1013,42 @@ int neuzip_linear(const neuzip_blob *weight, uint64_t out_features, uint64_t in_
     a.n_chunks = weight->n_chunks;
     a.in_features = static_cast<uint32_t>(in_features);
     a.out_features = static_cast<uint32_t>(out_features);
-    a.tokens = tokens;
+    a.coef = coef_of(weight);
+    a.block_shift = 0;
+    while (weight->block && (1u << a.block_shift) < weight->block)
+        ++a.block_shift;
     a.stride = static_cast<uint32_t>(in_features / gcd);
     a.rstep = static_cast<uint32_t>(kChunk / gcd);
-    const uint32_t cols = linear_columns(tokens, a.stride);  // chunks per group = columns of the matrix instruction
-    const uint64_t per_block = static_cast<uint64_t>(cols) * a.stride;
-    a.n_groups = static_cast<uint32_t>((weight->n_chunks + per_block - 1) / per_block * a.stride);
     const uint64_t cells = static_cast<uint64_t>(tokens) * out_features;
     hipLaunchKernelGGL(linear_init_kernel, dim3(static_cast<uint32_t>((cells + 255) / 256)), dim3(256), 0, stream, d_y,
                        d_bias, tokens, a.out_features);
-    const uint32_t groups_per_wg = kDecChunksPerWg / cols;
-    const uint32_t wgs = (a.n_groups + groups_per_wg - 1) / groups_per_wg;
-    switch (weight->k) {
-    case 7: launch_linear<7>(a, cols, wgs, stream); break;
-    case 3: launch_linear<3>(a, cols, wgs, stream); break;
-    case 1: launch_linear<1>(a, cols, wgs, stream); break;
-    default: launch_linear<0>(a, cols, wgs, stream); break;
+    // the kernel holds the partial sums of at most 64 tokens: larger batches go through in tiles of 64
+    // (each tile decodes the weight again: beyond a few tiles decompressing once and a dense product win)
+    for (uint32_t t0 = 0; t0 < tokens; t0 += kLinMaxTokens) {
+        a.tokens = tokens - t0 < kLinMaxTokens ? tokens - t0 : kLinMaxTokens;
+        a.x = static_cast<const uint16_t *>(d_x) + static_cast<uint64_t>(t0) * in_features;
+        a.y = d_y + static_cast<uint64_t>(t0) * out_features;
+        const uint32_t cols = linear_columns(a.tokens, a.stride);  // chunks per group = columns of the matrix instruction
+        const uint64_t per_block = static_cast<uint64_t>(cols) * a.stride;
+        a.n_groups = static_cast<uint32_t>((weight->n_chunks + per_block - 1) / per_block * a.stride);
+        const uint32_t groups_per_wg = kDecChunksPerWg / cols;
+        const uint32_t wgs = (a.n_groups + groups_per_wg - 1) / groups_per_wg;
+        if (weight->block) {
+            switch (weight->k) {
+            case 3: launch_linear<3, true>(a, cols, wgs, stream); break;
+            case 1: launch_linear<1, true>(a, cols, wgs, stream); break;
+            default: launch_linear<0, true>(a, cols, wgs, stream); break;
+            }
+        } else {
+            switch (weight->k) {
+            case 7: launch_linear<7, false>(a, cols, wgs, stream); break;
+            case 3: launch_linear<3, false>(a, cols, wgs, stream); break;
+            case 1: launch_linear<1, false>(a, cols, wgs, stream); break;
+            default: launch_linear<0, false>(a, cols, wgs, stream); break;
+            }
+        }
+        if (!hip_ok(hipGetLastError()))
+            return NEUZIP_EHIP;
     }
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
@@ -1516,6 +1537,18 @@ int neuzip_check(const neuzip_blob *blob, void *hip_stream)
         return NEUZIP_ECORRUPT;
     }
     return NEUZIP_OK;
+}
+
+uint64_t neuzip_workspace_bytes(void)
+{
+    std::lock_guard<std::mutex> guard(g_ws_mutex);
+    if (g_ws.device < 0)
+        return 0;
+    const uint64_t chunks = g_ws.group_cap * kChunksPerGroup;
+    uint64_t bytes = kSmallWords * 4;
+    if (g_ws.group_cap)
+        bytes += (chunks + 4) * 4 + (g_ws.group_cap + 4) * 4 + 2ull * g_ws.super_cap * 4 + chunks * kStates * kRunCap * 2;
+    return bytes;
 }
 
 int neuzip_release_workspace(void)

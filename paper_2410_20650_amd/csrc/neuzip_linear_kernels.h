@@ -75,6 +75,8 @@ struct LinearArgs {
     const uint8_t *lens;
     const uint16_t *words;
     const uint8_t *sm;
+    const uint8_t *coef;   // block coefficients (block-wise normalised blobs only)
+    uint32_t block_shift;  // log2 of the block size of the normalisation
     const uint16_t *x;     // [tokens][in_features] bf16
     float *y;              // [tokens][out_features], holds the bias (or zero) on entry
     uint32_t *status;
@@ -104,7 +106,9 @@ __device__ __forceinline__ void atomic_add_f32(float *p, float v)
     unsafeAtomicAdd(p, v);
 }
 
-template <int KB, int COLS, int MT, bool LONE, class WordSrc>
+// NORM: the blob is block-wise normalised (Sec. 2.3): the merged words are multiplied by their block's
+// coefficient, as in the decoder, before they enter the matrix instruction.
+template <int KB, int COLS, int MT, bool LONE, bool NORM, class WordSrc>
 __device__ __forceinline__ void linear_walk(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
                                             uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
                                             const LinearArgs &a, uint64_t base, uint32_t kk, uint32_t turns,
@@ -137,7 +141,7 @@ __device__ __forceinline__ void linear_walk(const uint32_t *__restrict__ lut, co
 
     uint32_t next = LONE ? 0u : src.peek(wp);
     const uint64_t first = base + j * kRun;
-    uint64_t fields = turns > 0 ? load_fields<KB>(sm, first) : 0;
+    uint64_t fields = turns > 0 ? load_turn<KB, NORM>(sm, a.coef, a.block_shift, first) : 0;
     uint4 xa[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -151,7 +155,7 @@ __device__ __forceinline__ void linear_walk(const uint32_t *__restrict__ lut, co
         const uint32_t kk_next = kk + kTurn == in ? 0u : kk + kTurn;
         uint64_t fields_next = 0;
         if (q + 1 < turns)
-            fields_next = load_fields<KB>(sm, first + (q + 1) * kTurn);
+            fields_next = load_turn<KB, NORM>(sm, a.coef, a.block_shift, first + (q + 1) * kTurn);
         uint4 xa_next[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
@@ -171,6 +175,12 @@ __device__ __forceinline__ void linear_walk(const uint32_t *__restrict__ lut, co
             b.u[1] = merge_pair<KB>(fields, 1, e[2], e[3]);
             b.u[2] = merge_pair<KB>(fields, 2, e[4], e[5]);
             b.u[3] = merge_pair<KB>(fields, 3, e[6], e[7]);
+            if constexpr (NORM) {
+                const float c = coefficient(static_cast<uint32_t>(fields >> 32) & 0x7Fu);
+#pragma unroll
+                for (int d = 0; d < 4; ++d)
+                    b.u[d] = denormalise_pair(b.u[d], c);
+            }
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -206,7 +216,7 @@ __device__ __forceinline__ void linear_walk(const uint32_t *__restrict__ lut, co
     }
 }
 
-template <int KB, int COLS, int MT>
+template <int KB, int COLS, int MT, bool NORM = false>
 __global__ __launch_bounds__(kLinThreads) void linear_kernel(const LinearArgs a)
 {
     constexpr uint32_t kLinGroupChunks = COLS;                       // columns of the B operand
@@ -301,13 +311,13 @@ __global__ __launch_bounds__(kLinThreads) void linear_kernel(const LinearArgs a)
 
     uint32_t wp = 0, wp_begin = 0;
     if (lone < 256) {
-        linear_walk<KB, COLS, MT, true>(lut, NoWords{}, lone, x, wp, a.sm, a, base, kk0, turns, j, lane);
+        linear_walk<KB, COLS, MT, true, NORM>(lut, NoWords{}, lone, x, wp, a.sm, a, base, kk0, turns, j, lane);
     } else if (staged) {
         wp = wp_begin = g * kLinGroupBytes + place + static_cast<uint32_t>(run_byte - aligned0);
-        linear_walk<KB, COLS, MT, false>(lut, LdsWords{stage}, 0u, x, wp, a.sm, a, base, kk0, turns, j, lane);
+        linear_walk<KB, COLS, MT, false, NORM>(lut, LdsWords{stage}, 0u, x, wp, a.sm, a, base, kk0, turns, j, lane);
     } else {
         const GlobalWords direct{reinterpret_cast<const uint8_t *>(a.words) + run_byte};
-        linear_walk<KB, COLS, MT, false>(lut, direct, 0u, x, wp, a.sm, a, base, kk0, turns, j, lane);
+        linear_walk<KB, COLS, MT, false, NORM>(lut, direct, 0u, x, wp, a.sm, a, base, kk0, turns, j, lane);
     }
     if (live && (x != kRansL || wp - wp_begin != 2 * len))
         atomicOr(a.status, 1u);

@@ -131,9 +131,18 @@ def test_device_memory_held_matches_the_accounting(nz):
     torch.cuda.synchronize()
     free_before, _ = torch.cuda.mem_get_info()
     blobs = [nz.neuzip_compress(w, 7) for w in ws]
-    nz.neuzip_release_workspace()                                # the compress workspace is not part of the model
+    # the compress workspace is not part of the model: 1.56 bytes per element of the largest tensor so far,
+    # accounted for by the library, and gone once released
+    torch.cuda.synchronize()
+    free_with_workspace, _ = torch.cuda.mem_get_info()
+    workspace = nz.neuzip_workspace_bytes()
+    largest = max(w.numel() for w in ws)
+    assert 1.5 * largest < workspace < 1.6 * largest
+    nz.neuzip_release_workspace()
+    assert nz.neuzip_workspace_bytes() == 0
     torch.cuda.synchronize()
     free_after, _ = torch.cuda.mem_get_info()
+    assert abs((free_after - free_with_workspace) - workspace) <= 6 * (2 << 20)
     held = free_before - free_after
     accounted = sum(b.device_bytes for b in blobs)
     containers = sum(b.compressed_bytes for b in blobs)

@@ -25,15 +25,15 @@ def nz():
     return binding
 
 
-def check_linear(nz, w, out_f, in_f, tokens, k=7, bias=False, seed=1):
+def check_linear(nz, w, out_f, in_f, tokens, k=7, bias=False, seed=1, block=0):
     """Compress w (flat bf16, out_f * in_f) on the GPU, run the fused layer, compare with the oracle."""
     x = inputs.gaussian_bf16((tokens, in_f), seed, std=1.0, device=DEV)
     b = (torch.arange(out_f, dtype=torch.float32, device=DEV) * 0.37 - 2.0) if bias else None
-    blob = nz.neuzip_compress(w, k)
+    blob = nz.neuzip_compress_blockwise(w, k, block)
     y = torch.full((tokens, out_f), float("nan"), dtype=torch.float32, device=DEV)
     nz.neuzip_linear(blob, out_f, in_f, x, b, y)
     nz.neuzip_check(blob)
-    container = O.compress(inputs.bits(w), k, threads=8)      # the oracle's own container of the same weight
+    container = O.compress(inputs.bits(w), k, threads=8, block=block)   # the oracle's own container of the same weight
     xw = inputs.bits(x).reshape(tokens, in_f)
     want = L.linear(container, out_f, in_f, xw, bias=None if b is None else b.cpu().numpy().astype(np.float64))
     mag = L.magnitude(container, out_f, in_f, xw)
@@ -60,6 +60,21 @@ def test_linear_on_lossy_weights_uses_the_truncated_values(nz, k):
     out_f, in_f = 96, 1024
     w = inputs.student_t4_bf16(out_f * in_f, 9200 + k, device=DEV)
     check_linear(nz, w, out_f, in_f, 9, k=k, bias=True, seed=9201)
+
+
+@pytest.mark.parametrize("k,block", [(3, 512), (3, 32), (1, 64), (0, 512), (0, 128)])
+def test_linear_on_blockwise_normalised_weights(nz, k, block):
+    # the paper's default lossy form (block-wise normalisation): the layer multiplies bf16(stored * c)
+    for out_f, in_f, tokens in ((96, 1024, 9), (37, 4096, 17), (16, 14336, 33)):
+        w = inputs.student_t4_bf16(out_f * in_f, 9400 + k + block, device=DEV)
+        check_linear(nz, w, out_f, in_f, tokens, k=k, bias=True, seed=9401, block=block)
+
+
+@pytest.mark.parametrize("tokens", [65, 128, 200])
+def test_linear_on_more_than_64_tokens_goes_through_in_tiles(nz, tokens):
+    for out_f, in_f, k, block in ((40, 256, 7, 0), (64, 4096, 7, 0), (48, 14336, 3, 0), (33, 1024, 0, 512)):
+        w = inputs.gaussian_bf16(out_f * in_f, 9500 + out_f, device=DEV)
+        check_linear(nz, w, out_f, in_f, tokens, k=k, bias=True, seed=9501 + tokens, block=block)
 
 
 def test_linear_with_bias_and_one_hot_activations(nz):
@@ -121,12 +136,11 @@ def test_linear_argument_errors(nz):
     assert lib.neuzip_linear(*args(64, 128, 4)) == nz.OK           # same elements, another valid shape
     assert lib.neuzip_linear(*args(128, 64, 4)) == nz.EINVAL       # in_features not a multiple of 128
     assert lib.neuzip_linear(*args(32, 256, 0)) == nz.EINVAL
-    assert lib.neuzip_linear(*args(32, 256, 65)) == nz.EINVAL
     assert lib.neuzip_linear(None, 32, 256, ctypes.c_void_p(x.data_ptr()), 4, None, ctypes.c_void_p(y.data_ptr()),
                              None) == nz.EINVAL
-    lossy = nz.neuzip_compress_blockwise(w, 3, 64)
-    assert lib.neuzip_linear(lossy.handle, 32, 256, ctypes.c_void_p(x.data_ptr()), 4, None,
-                             ctypes.c_void_p(y.data_ptr()), None) == nz.EUNSUPPORTED
+    w32 = nz.neuzip_compress(inputs.gaussian_f32(32 * 256, 9602, device=DEV), 7)
+    assert lib.neuzip_linear(w32.handle, 32, 256, ctypes.c_void_p(x.data_ptr()), 4, None,
+                             ctypes.c_void_p(y.data_ptr()), None) == nz.EUNSUPPORTED   # bf16 weights only
     torch.cuda.synchronize()
 
 

@@ -53,6 +53,21 @@ def test_guard_band_table_matches_the_oracle(nz, n, guard):
     assert np.array_equal(decoded(nz, back, w), words)
 
 
+def test_a_guarded_blob_keeps_its_guard_when_compressed_into_again(nz):
+    w0 = inputs.gaussian_bf16(100_000, seed=4100, device=DEV)
+    w1 = inputs.gaussian_bf16(100_000, seed=4101, std=0.05, device=DEV)
+    (blob,) = nz.neuzip_compress_guarded([w0], 7, 8)
+    for call in (lambda: nz.neuzip_compress(w1, 7, blob=blob), lambda: nz.neuzip_compress_batch([w1], 7, 0, blobs=[blob]),
+                 lambda: nz.neuzip_compress_noalloc(w1, 7, blob)):
+        nz.neuzip_compress_guarded([w0], 7, 8, blobs=[blob])
+        call()
+        assert blob.guard == 8
+        same_container(nz.neuzip_export(blob), O.compress(inputs.bits(w1), 7, threads=8, guard=8), "guard kept")
+    nz.neuzip_compress_guarded([w1], 7, 0, blobs=[blob])             # the guarded entry point sets it anew
+    assert blob.guard == 0
+    same_container(nz.neuzip_export(blob), O.compress(inputs.bits(w1), 7, threads=8), "guard dropped")
+
+
 def test_guard_band_on_every_pattern_and_on_a_single_exponent(nz):
     w = inputs.all_patterns_bf16(device=DEV)
     (blob,) = nz.neuzip_compress_guarded([w], 7, 3)
