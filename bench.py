@@ -306,6 +306,13 @@ def main():
     src = torch.empty_like(scratch)
     us = event_us(torch, stream, lambda: scratch.copy_(src), 50, warm=5)
     result["device_copy_GBps_read_plus_write"] = round(2 * out_bytes / us / 1e3, 1)
+    # ... and a kernel that only moves the decoder's bytes (reads the container's size, writes the tensor's)
+    probe_in = torch.empty(comp_bytes // 16 * 16, dtype=torch.uint8, device=dev)
+    us = event_us(torch, stream, lambda: nz.neuzip_stream_probe(probe_in, src), 50, warm=5)
+    result["stream_probe"] = {"config2_GBps": round((probe_in.numel() + out_bytes) / us / 1e3, 1), "config2_us": round(us, 2),
+                              "what": "a kernel that only reads the container's bytes and writes the tensor's, "
+                                      "interleaved, with the decoder's access widths: the ceiling for this byte mix"}
+    del probe_in
 
     # compress rate (histogram + table + encode + offsets + compaction, incl. the one size read-back)
     us = wall_us(torch, lambda: nz.neuzip_compress(w, 7, blob=blob), 10, warm=3)
@@ -389,6 +396,10 @@ def main():
             nz.neuzip_free(b4)
         us = event_us(torch, stream, lambda: buf.copy_(t4.view(-1)), 20, warm=3)
         c4["device_copy_GBps_read_plus_write"] = round(4.0 * n4 / us / 1e3, 1)
+        probe_in = torch.empty(int(c4["k7"]["bits_per_weight"] * n4 / 8) // 16 * 16, dtype=torch.uint8, device=dev)
+        us = event_us(torch, stream, lambda: nz.neuzip_stream_probe(probe_in, buf), 20, warm=3)
+        c4["stream_probe_k7_GBps"] = round((probe_in.numel() + 2.0 * n4) / us / 1e3, 1)
+        del probe_in
         result["config4"] = c4
         del t4, buf
         torch.cuda.empty_cache()

@@ -327,6 +327,18 @@ int neuzip_import(const void *h_buf, uint64_t len, void *hip_stream, neuzip_blob
 int neuzip_histogram(const neuzip_blob *blob, uint32_t h_counts[256]);
 int neuzip_frequencies(const neuzip_blob *blob, uint16_t h_freq[256]);
 
+/*
+ * neuzip_stream_probe -- measurement aid for the throughput experiment of Sec. 3 (the throughput
+ * figure compares against plain data movement): one kernel that only moves bytes the way the fused
+ * decoder does, reading in_bytes from d_in and writing out_bytes to d_out interleaved in that
+ * proportion (128-bit accesses; non-temporal stores from 128 MB of output up).  Its rate is the
+ * ceiling for a decoder of that byte mix on the machine at hand.
+ *   d_in, d_out   device buffers, 16-byte aligned; in_bytes and out_bytes multiples of 16, out_bytes
+ *                 at least 64; d_out is overwritten with a pattern.  EINVAL otherwise.
+ * Never allocates, never synchronises.
+ */
+int neuzip_stream_probe(const void *d_in, uint64_t in_bytes, void *d_out, uint64_t out_bytes, void *hip_stream);
+
 /* Synchronises hip_stream and returns ECORRUPT if any decompression of this
  * blob so far found a state that did not return to its initial value or a
  * word run that was not consumed exactly; clears the flag. */

@@ -77,6 +77,8 @@ def _load():
     lib.neuzip_histogram.restype = i32
     lib.neuzip_frequencies.argtypes = [vp, ctypes.POINTER(ctypes.c_uint16)]
     lib.neuzip_frequencies.restype = i32
+    lib.neuzip_stream_probe.argtypes = [vp, u64, vp, u64, vp]
+    lib.neuzip_stream_probe.restype = i32
     lib.neuzip_check.argtypes = [vp, vp]
     lib.neuzip_check.restype = i32
     lib.neuzip_workspace_bytes.argtypes = []
@@ -97,7 +99,7 @@ EXPORTED = ["neuzip_compress", "neuzip_compress_noalloc", "neuzip_compress_block
             "neuzip_recompress", "neuzip_update", "neuzip_guard", "neuzip_linear", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
             "neuzip_free",
             "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits", "neuzip_dtype",
-            "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check",
+            "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check", "neuzip_stream_probe",
             "neuzip_workspace_bytes", "neuzip_release_workspace", "neuzip_strerror", "neuzip_last_hip_error"]
 
 
@@ -374,6 +376,16 @@ def neuzip_frequencies(blob: Blob) -> np.ndarray:
     if rc != OK:
         raise NeuzipError(rc, "neuzip_frequencies")
     return out
+
+
+def neuzip_stream_probe(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    """Reads all of src and overwrites all of dst the way the decoder moves its bytes (a timing aid)."""
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
+        raise TypeError("expected contiguous CUDA tensors")
+    rc = _lib.neuzip_stream_probe(ctypes.c_void_p(src.data_ptr()), src.numel() * src.element_size(),
+                                  ctypes.c_void_p(dst.data_ptr()), dst.numel() * dst.element_size(), _stream_handle(stream))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_stream_probe")
 
 
 def neuzip_check(blob: Blob, stream=None) -> None:

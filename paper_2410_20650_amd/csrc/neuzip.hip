@@ -1522,6 +1522,25 @@ int neuzip_frequencies(const neuzip_blob *blob, uint16_t h_freq[256])
     return NEUZIP_OK;
 }
 
+int neuzip_stream_probe(const void *d_in, uint64_t in_bytes, void *d_out, uint64_t out_bytes, void *hip_stream)
+{
+    if ((reinterpret_cast<uintptr_t>(d_in) & 15u) || (reinterpret_cast<uintptr_t>(d_out) & 15u) || (in_bytes & 15u) ||
+        (out_bytes & 15u) || out_bytes < 64 || !d_out || (in_bytes && !d_in))
+        return NEUZIP_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const uint64_t out_vecs = out_bytes / 16 - 1;  // the last 16 bytes of the output are the kernel's sink word
+    uint32_t *sink = reinterpret_cast<uint32_t *>(static_cast<uint8_t *>(d_out) + out_bytes - 16);
+    const uint64_t want = (out_vecs + 256 * 4 - 1) / (256 * 4);
+    const uint32_t wgs = static_cast<uint32_t>(want < 1 ? 1 : (want > 8192 ? 8192 : want));
+    if (out_bytes >= (128ull << 20))
+        hipLaunchKernelGGL(stream_probe_kernel<true>, dim3(wgs), dim3(256), 0, stream, static_cast<const uint4 *>(d_in),
+                           in_bytes / 16, static_cast<uint4 *>(d_out), out_vecs, sink);
+    else
+        hipLaunchKernelGGL(stream_probe_kernel<false>, dim3(wgs), dim3(256), 0, stream, static_cast<const uint4 *>(d_in),
+                           in_bytes / 16, static_cast<uint4 *>(d_out), out_vecs, sink);
+    return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
+}
+
 int neuzip_check(const neuzip_blob *blob, void *hip_stream)
 {
     if (!is_blob(blob) || !on_current_device(blob))

@@ -889,15 +889,18 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
             ring_advance(st, cur_before);
             ring_flush(wp_before, st.wp, ring, chunk_slots, j);
         };
-        // turns kTurns - 1 .. 2 in groups of three (so that no buffer has to be copied into another)
-        static_assert((kTurns - 2) % 3 == 0, "the rotation of three buffers ends with turns 1 and 0 in the first two");
-        for (int q = static_cast<int>(kTurns) - 1; q >= 2; q -= 3) {
+        // turns in groups of three (so that no buffer has to be copied into another); what is left over
+        // when the number of turns is no multiple of three comes last, with the rotation continued
+        int q = static_cast<int>(kTurns) - 1;
+        for (; q >= 2; q -= 3) {
             turn(d0, g0, d2, g2, q);
             turn(d1, g1, d0, g0, q - 1);
             turn(d2, g2, d1, g1, q - 2);
         }
-        turn(d0, g0, d2, g2, 1);
-        turn(d1, g1, d0, g0, 0);
+        if constexpr (kTurns % 3 >= 1)
+            turn(d0, g0, d2, g2, q);
+        if constexpr (kTurns % 3 == 2)
+            turn(d1, g1, d0, g0, q - 1);
     } else if (m > 0) {
         for (int q = static_cast<int>(kTurns) - 1; q >= 0; --q) {
             const uint32_t wp_before = st.wp, cur_before = st.cur;
@@ -1049,7 +1052,8 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const Compress
     const uint32_t wave = threadIdx.x / 64, lane = threadIdx.x & 63;
     const uint32_t c = slot_id.wg * (kCompactThreads / 64) + wave;
     const bool live = c < n_chunks;   // (no early return: the workgroup meets at a barrier)
-    const uint32_t j = lane & 15;     // the lane's state: lanes 64 apart in the piece loop keep it
+    constexpr uint32_t kRowsPerPass = 64 / kStates;  // slot rows (one piece per state) the wave reads at a time
+    const uint32_t j = lane % kStates;  // the lane's state: lanes 64 apart in the piece loop keep it
     uint16_t *__restrict__ mine = gathered[wave];
     uint32_t total = 0, shift = 0;
     uint64_t at0 = 0;
@@ -1064,7 +1068,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const Compress
         uint4 ahead[kAhead];
 #pragma unroll
         for (uint32_t k = 0; k < kAhead; ++k)
-            ahead[k] = *reinterpret_cast<const uint4 *>(chunk_slots + slot_word(j, (kRows - 1 - (row0 + 4 * k)) * 8));
+            ahead[k] = *reinterpret_cast<const uint4 *>(chunk_slots + slot_word(j, (kRows - 1 - (row0 + kRowsPerPass * k)) * 8));
         // run length of state j and its start inside the chunk (16-lane exclusive prefix)
         const uint32_t my_len = lens[c * kStates + j];
         uint32_t start = my_len;
@@ -1093,7 +1097,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const Compress
         const uint32_t first_pos = kRunCap - my_len;   // position of the run's first word in its slot
         const uint32_t first_piece = first_pos >> 3;   // rows below it hold nothing of this state
         for (uint32_t k = 0;; ++k) {
-            const uint32_t row = row0 + 4 * k;
+            const uint32_t row = row0 + kRowsPerPass * k;
             if (row >= kRows || kRows - 1 - row < first_piece)
                 break;
             const uint32_t piece = kRows - 1 - row;

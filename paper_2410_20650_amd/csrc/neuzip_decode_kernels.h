@@ -563,4 +563,48 @@ __global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchAr
                                      stage);
 }
 
+// ------------------------------------------------------------------------------------------
+// Measurement aid: a kernel that does nothing but the decoder's memory traffic -- it reads in_vecs
+// 16-byte pieces and writes out_vecs 16-byte pieces, interleaved in that proportion, with the same
+// kinds of instructions (128-bit loads; 128-bit stores, non-temporal for outputs beyond the
+// last-level cache).  What it reaches is the ceiling a decoder of that byte mix can reach on this
+// machine; the decoder's own rate is reported against it.
+// ------------------------------------------------------------------------------------------
+template <bool STREAM>
+__global__ __launch_bounds__(256) void stream_probe_kernel(const uint4 *__restrict__ in, uint64_t in_vecs,
+                                                           uint4 *__restrict__ out, uint64_t out_vecs,
+                                                           uint32_t *__restrict__ sink)
+{
+    const uint64_t threads = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+    uint32_t acc = 0;
+    constexpr uint32_t kDepth = 4;  // pieces in flight per lane, each way
+    for (uint64_t v0 = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; v0 < out_vecs; v0 += threads * kDepth) {
+        uint4 got[kDepth];
+#pragma unroll
+        for (uint32_t r = 0; r < kDepth; ++r) {
+            const uint64_t v = v0 + r * threads;
+            // neighbouring lanes share input pieces where the input is the shorter side: one request
+            got[r] = (v < out_vecs && in_vecs) ? in[v * in_vecs / out_vecs] : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (uint32_t r = 0; r < kDepth; ++r) {
+            const uint64_t v = v0 + r * threads;
+            acc ^= got[r].x ^ got[r].y ^ got[r].z ^ got[r].w;
+            if (v < out_vecs) {
+                const uint4 w = make_uint4(static_cast<uint32_t>(v), 1u, 2u, 3u);
+                if constexpr (STREAM) {
+                    __builtin_nontemporal_store(w.x, &out[v].x);
+                    __builtin_nontemporal_store(w.y, &out[v].y);
+                    __builtin_nontemporal_store(w.z, &out[v].z);
+                    __builtin_nontemporal_store(w.w, &out[v].w);
+                } else {
+                    out[v] = w;
+                }
+            }
+        }
+    }
+    if (acc == 0x9E3779B9u)  // keeps the loads alive; practically never taken
+        atomicOr(sink, 1u);
+}
+
 }  // namespace nz
