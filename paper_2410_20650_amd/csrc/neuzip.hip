@@ -165,6 +165,7 @@ struct Workspace {
     HostRecord *pinned = nullptr;     // pinned host memory, written by the encode kernel
     uint32_t seq = 0;                 // stamp of the last compress call
     hipEvent_t idle = nullptr;        // recorded after the last kernel that uses the workspace
+    hipStream_t last_stream = nullptr; // ... on this stream
 };
 std::mutex g_ws_mutex;
 Workspace g_ws;
@@ -247,6 +248,7 @@ int create_workspace(int device, hipStream_t stream)
                        kSmallWords);
     NZ_HIP(hipGetLastError());
     NZ_HIP(hipEventRecord(g_ws.idle, stream));
+    g_ws.last_stream = stream;
     return NEUZIP_OK;
 }
 
@@ -264,8 +266,11 @@ int ensure_workspace(int device, uint64_t n_groups, hipStream_t stream)
             return rc;
         }
     }
-    // the previous user of the workspace may still be running on another stream
-    NZ_HIP(hipStreamWaitEvent(stream, g_ws.idle, 0));
+    // the previous user of the workspace may still be running on another stream (on the same one, the
+    // stream's own order does)
+    if (stream != g_ws.last_stream)
+        NZ_HIP(hipStreamWaitEvent(stream, g_ws.idle, 0));
+    g_ws.last_stream = stream;
     if (g_ws.group_cap < n_groups) {
         NZ_HIP(hipEventSynchronize(g_ws.idle));
         void *old_arrays[] = {g_ws.chunk_words, g_ws.group_words, g_ws.super_words, g_ws.slots};
