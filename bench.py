@@ -60,7 +60,7 @@ def parse_args():
 
 def read_traffic_note():
     """HBM bytes per decode launch measured with rocprofv3 --pmc in a separate run (see profiles/), or None."""
-    path = os.path.join(ROOT, "profiles", "decode_config2_traffic.txt")
+    path = os.path.join(ROOT, "profiles", "decode_config2.txt")
     try:
         with open(path) as fh:
             for line in fh:
@@ -277,7 +277,7 @@ def main():
     achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic_note(),
-                "traffic_source": "profiles/decode_config2_traffic.txt (rocprofv3 --pmc, a separate run; not measured in this one)",
+                "traffic_source": "profiles/decode_config2.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, a separate run; not measured in this one)",
                 "kernel": "decode_kernel<7, false, 0>", "avg_launch_us": round(kernel_ms * 1e3, 2),
                 "algorithmic_bytes_per_elem": round(algo_bytes / n, 4),
                 "working_set": "196 MB: fits the 256 MB last-level cache, so this figure is cache assisted; "
