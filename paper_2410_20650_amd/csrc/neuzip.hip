@@ -1,10 +1,11 @@
 // NeuZip codec for MI355X (gfx950): host side of the C ABI declared in include/neuzip.h.  The
-// kernels live in neuzip_compress_kernels.h and neuzip_decode_kernels.h, the shared constants and
+// kernels live in neuzip_compress_kernels.h, neuzip_decode_kernels.h and neuzip_linear_kernels.h, the shared constants and
 // device structures in neuzip_format.h; all of it is compiled as this one translation unit.
 //
 // Stream format (little-endian):
 //   container := header(64 B) | freq[256] u16 | offsets[nc+1] u32 | states[nc*16] u32
 //              | lens[nc*16] u8 | words[total] u16 | signmant[ceil(n*(k+1)/8)] u8
+//              | low[n] u16 (binary32 blobs only: the lower halves of the elements)
 //              | coef[ceil(n/block)] u8 (block-wise normalised blobs only)
 //   every section zero-padded to 16 bytes.  A chunk is 4096 exponent symbols; local symbol i
 //   belongs to rANS state j = (i mod 128) / 8, so a state codes runs of 8 neighbouring symbols.

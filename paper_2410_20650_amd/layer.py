@@ -8,6 +8,10 @@ it is used (Sec. 2.2, Eq. (3)); here a decoding batch of up to 64 tokens goes th
 kernel instead, which never writes the weight.  Backward loop: the weight is decompressed again,
 the gradients of the layer are formed, the optimiser step is applied at once and the weight is
 compressed again, so that neither the uncompressed model nor the full set of gradients ever exists.
+
+Biases are not compressed (Sec. 2.1 and 2.2 treat weight matrices only): they are plain float32
+tensors of the caller's, and their addition and their own SGD step below are ordinary torch
+arithmetic outside the codec's path.
 """
 import torch
 
