@@ -344,12 +344,13 @@ __device__ inline uint32_t build_table_wave(const uint32_t (&cnt)[4], uint64_t t
 // leave the state as it is and a zero reciprocal, by which the encoder recognises it.
 __device__ inline EncSym encoder_constants(uint32_t f, uint32_t cum)
 {
-    EncSym e = {0.0f, 0xFFFFFFFFu, 0u, 1u};
+    EncSym e = {0.0f, 0xFFFF0000u, 1u, 0};
     if (f > 0) {
         e.rcp = __fmul_rn(__fdiv_rn(1.0f, static_cast<float>(f)), 1.0f - 0x1p-21f);
-        e.limit = f >= kM ? 0xFFFFFFFFu : (f << 20);  // f = 4096 only for a one-symbol tensor: never renormalises
-        e.cmpl_cum = (kM - f) | (cum << 16);
+        // f = 4096 only for a one-symbol tensor: the state stays at 2^16 and never renormalises
+        e.limit_cum = (f >= kM ? 0xFFFF0000u : (f << 20)) | cum;
         e.f = f;
+        e.neg_cmpl = static_cast<int32_t>(f) - static_cast<int32_t>(kM);
     }
     return e;
 }
@@ -667,16 +668,23 @@ struct EncState {
 // rings: the workgroup's ring array as bytes; lane_ring: this lane's 32-byte ring in it (threadIdx.x * 32)
 __device__ __forceinline__ void rans_put(EncState &st, const EncSym e, uint8_t *__restrict__ rings, uint32_t lane_ring)
 {
-    if (st.x >= e.limit) {
+    if ((st.x >> 16) >= (e.limit_cum >> 16)) {
         // one position down, wrapping inside the lane's 16 words: two instructions for the address
         st.cur = lane_ring | ((st.cur - 2u) & (2u * kRingWords - 2u));
         *reinterpret_cast<uint16_t *>(rings + st.cur) = static_cast<uint16_t>(st.x);
-        st.x >>= 16;
+        // (the shift as written keeps the compiler from sharing it with the test above, which reads the
+        // state's upper half through an operand select and needs no shift of its own)
+        asm volatile("v_lshrrev_b32 %0, 16, %0" : "+v"(st.x));
     }
-    uint32_t q = static_cast<uint32_t>(__fmul_rn(__uint2float_rn(st.x), e.rcp));  // q or q - 1
-    const uint32_t r = st.x - __umul24(q, e.f);
-    q += r >= e.f ? 1u : 0u;
-    st.x = __umul24(q, e.cmpl_cum & 0xFFFFu) + st.x + (e.cmpl_cum >> 16);
+    // -q or -(q - 1): the conversion truncates toward zero, as it does for the positive product
+    int32_t qn = static_cast<int32_t>(-__fmul_rn(__uint2float_rn(st.x), e.rcp));
+    const uint32_t r = static_cast<uint32_t>(__mul24(qn, static_cast<int32_t>(e.f))) + st.x;
+    qn -= r >= e.f ? 1 : 0;
+    const uint32_t grown = static_cast<uint32_t>(__mul24(qn, e.neg_cmpl)) + st.x;
+    // + cum, the lower half of limit_cum, taken by the add's operand select
+    asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0"
+        : "=v"(st.x)
+        : "v"(grown), "v"(e.limit_cum));
 }
 
 // Layout of a chunk's 16 slots in the workspace (16 x 200 words): word position p of state j sits
@@ -796,7 +804,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const EncSym e = encoder_constants(f[i], cum[i]);
-                enc_raw[4 * lane + i] = make_uint4(__float_as_uint(e.rcp), e.limit, e.cmpl_cum, e.f);
+                enc_raw[4 * lane + i] = make_uint4(__float_as_uint(e.rcp), e.limit_cum, e.f, static_cast<uint32_t>(e.neg_cmpl));
             }
             if (table_wg) {
                 uint32_t *scan = reinterpret_cast<uint32_t *>(rings);  // scan[t] = cum[t + 1]
@@ -823,7 +831,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
     } else {
         // the table the blob holds
         const EncSym e = encoder_constants(tb->freq[threadIdx.x], tb->cum[threadIdx.x]);
-        enc_raw[threadIdx.x] = make_uint4(__float_as_uint(e.rcp), e.limit, e.cmpl_cum, e.f);
+        enc_raw[threadIdx.x] = make_uint4(__float_as_uint(e.rcp), e.limit_cum, e.f, static_cast<uint32_t>(e.neg_cmpl));
     }
     __syncthreads();
     if (table_wg) {

@@ -55,16 +55,21 @@ static_assert(sizeof(TableBlock) % 256 == 0, "table block keeps later sections a
 // Per-symbol encoder constants (16 bytes, one ds_read_b128), derived by every encoder workgroup from
 // the frequencies and cumulative frequencies of the tensor's table.
 //   The step is x <- (x / f) * M + (x mod f) + cum = q * (M - f) + x + cum with q = floor(x / f).
-//   limit: the state is renormalised before the step when x >= limit = f << 20, so q < 2^20.
+//   limit_cum: the state is renormalised before the step when x >= f << 20, so q < 2^20.  f << 20
+//   has no bits in its lower half, so the test compares the upper halves only (x >> 16 against
+//   f << 4) and the lower half of the same dword carries cum (both halves are read through the
+//   sub-dword operand selects of the compare and the add, without an instruction to extract them).
 //   rcp: a float slightly below 1/f, (1/f)(1 - 2^-21).  float(x) * rcp, truncated, is q or q - 1
 //   (three roundings of 2^-24 cannot overcome the 2^-21 bias, and q * 1.5 * 2^-21 < 1); one
 //   compare of the remainder against f settles it.  All of this runs at full VALU rate, unlike a
-//   32-bit multiply-high.
+//   32-bit multiply-high.  The quotient is formed negated (the sign rides on the float multiply),
+//   so that the remainder x - q f and the new state are one 24-bit multiply-add each:
+//   r = (-q) f + x, x' = (-q)(f - M) + x (+ cum).
 struct EncSym {
     float rcp;
-    uint32_t limit;
-    uint32_t cmpl_cum;  // (M - f) | cum << 16
+    uint32_t limit_cum;  // f << 20 | cum (upper half 0xFFFF: never renormalises)
     uint32_t f;
+    int32_t neg_cmpl;    // f - M
 };
 
 // ------------------------------------------------------------------------------------------
