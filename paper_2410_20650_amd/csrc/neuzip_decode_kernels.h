@@ -76,6 +76,48 @@ __device__ __forceinline__ uint32_t merge_pair_half(uint64_t fields, int pair, u
     return __builtin_amdgcn_perm(sym, half, (pair & 1) ? 0x06030402u : 0x06010400u);
 }
 
+// Lossy tensors with one or no mantissa bit: spreading a few field bits over two bf16 words costs more
+// vector instructions than the decoding itself, so it is looked up instead.  A small LDS table, filled
+// by the workgroup, maps
+//   k = 1: a byte of field bits (four elements, s m per element) to the sign and mantissa bits of two
+//          dwords of output (256 entries of 8 bytes);
+//   k = 0: a nibble of sign bits (four elements) to the sign bits of two dwords (16 entries).
+// A turn's 8 elements take two reads; few distinct addresses are in flight at a time for k = 0.
+template <int KB>
+constexpr uint32_t kSpreadEntries = KB == 1 ? 256u : (KB == 0 ? 16u : 1u);
+template <int KB>
+constexpr uint32_t kStageBytesOf = kStageBytes - (KB == 1 ? 2048u : (KB == 0 ? 128u : 0u));  // same LDS in all
+
+template <int KB>
+__device__ __forceinline__ uint2 spread_entry(uint32_t i)
+{
+    if constexpr (KB == 1) {
+        // nibble s1 m1 s0 m0: m0 -> bit 6, s0 -> 15, m1 -> 22, s1 -> 31
+        auto one = [](uint32_t f) { return ((f & 1u) << 6) | ((f & 2u) << 14) | ((f & 4u) << 20) | ((f & 8u) << 28); };
+        return make_uint2(one(i & 0xFu), one(i >> 4));
+    } else {
+        // signs s3 s2 s1 s0: even elements -> bit 15, odd ones -> bit 31
+        return make_uint2(((i & 1u) << 15) | ((i & 2u) << 30), ((i & 4u) << 13) | ((i & 8u) << 28));
+    }
+}
+
+// The four output dwords of a turn (k = 1 or 0) from its field bits, the eight slot-table entries
+// that decoded its exponents, and the table above.
+template <int KB>
+__device__ __forceinline__ uint4 merge_turn_small(uint64_t fields, const uint32_t (&e)[8], const uint2 *__restrict__ spread)
+{
+    static_assert(KB == 1 || KB == 0, "wider fields are merged arithmetically");
+    const uint32_t v = static_cast<uint32_t>(fields);
+    const uint2 a = spread[KB == 1 ? (v & 0xFFu) : (v & 0xFu)];
+    const uint2 b = spread[KB == 1 ? ((v >> 8) & 0xFFu) : ((v >> 4) & 0xFu)];
+    uint4 o;
+    o.x = (__builtin_amdgcn_perm(e[1], e[0], 0x0c040c00u) << 7) | a.x;
+    o.y = (__builtin_amdgcn_perm(e[3], e[2], 0x0c040c00u) << 7) | a.y;
+    o.z = (__builtin_amdgcn_perm(e[5], e[4], 0x0c040c00u) << 7) | b.x;
+    o.w = (__builtin_amdgcn_perm(e[7], e[6], 0x0c040c00u) << 7) | b.y;
+    return o;
+}
+
 struct LdsWords {
     const uint8_t *base;  // LDS copy of the workgroup's runs
     __device__ __forceinline__ uint32_t peek(uint32_t at) const { return *reinterpret_cast<const uint16_t *>(base + at); }
@@ -141,7 +183,8 @@ __device__ __forceinline__ uint32_t denormalise_pair(uint32_t d, float c)
 // UPD: the words written are the decoded weights after the update with the gradient `grad` (bf16
 // words, same indexing as the output) and the rate lr.  HALF: the tensor is binary16.
 template <int KB, bool LONE, bool NORM, bool STREAM, bool UPD, bool HALF, class WordSrc>
-__device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, const WordSrc &src, uint32_t lone,
+__device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, const uint2 *__restrict__ spread,
+                                           const WordSrc &src, uint32_t lone,
                                            uint32_t &x, uint32_t &wp, const uint8_t *__restrict__ sm,
                                            const uint8_t *__restrict__ coef, uint32_t block,
                                            uint64_t (&fields)[KB == 7 ? kTurnGroupStream : kTurnGroup],
@@ -194,6 +237,8 @@ __device__ __forceinline__ void walk_state(const uint32_t *__restrict__ lut, con
                     o[r].y = merge_pair_half(fields[r], 1, e[2], e[3]);
                     o[r].z = merge_pair_half(fields[r], 2, e[4], e[5]);
                     o[r].w = merge_pair_half(fields[r], 3, e[6], e[7]);
+                } else if constexpr (KB <= 1) {
+                    o[r] = merge_turn_small<KB>(fields[r], e, spread);
                 } else {
                     o[r].x = merge_pair<KB>(fields[r], 0, e[0], e[1]);
                     o[r].y = merge_pair<KB>(fields[r], 1, e[2], e[3]);
@@ -406,7 +451,8 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
                                                  const uint16_t *__restrict__ low, void *__restrict__ out_any,
                                                  const uint16_t *__restrict__ grad, float lr, bool stream_out,
                                                  uint64_t n, uint32_t n_chunks, uint32_t *__restrict__ status,
-                                                 uint32_t wg, uint32_t *__restrict__ lut, uint8_t *__restrict__ stage)
+                                                 uint32_t wg, uint32_t *__restrict__ lut, uint8_t *__restrict__ stage,
+                                                 uint2 *__restrict__ spread)
 {
     constexpr bool WIDE = MODE == kWide, UPD = MODE == kUpdate, HALF = MODE == kHalf;
     static_assert(MODE == kPlain || (KB == 7 && !NORM), "binary32 blobs and trained weights are lossless only");
@@ -449,7 +495,7 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
     const uint64_t byte1 = static_cast<uint64_t>(off1) * 2;
     const uint64_t aligned0 = byte0 & ~static_cast<uint64_t>(15);
     const uint64_t stage_len = byte1 - aligned0;
-    const bool staged = stage_len + 16 <= kStageBytes;  // room for the one-word look-ahead
+    const bool staged = stage_len + 16 <= kStageBytesOf<KB>;  // room for the one-word look-ahead
     if (staged) {
         const uint4 *from = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(words) + aligned0);
         uint4 *to = reinterpret_cast<uint4 *>(stage);
@@ -465,6 +511,10 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
     }
     for (uint32_t i = tid + 2 * threads; i < kM / 4; i += threads)
         reinterpret_cast<uint4 *>(lut)[i] = lut_g[i];
+    if constexpr (KB <= 1) {
+        for (uint32_t i = tid; i < kSpreadEntries<KB>; i += threads)
+            spread[i] = spread_entry<KB>(i);
+    }
     __syncthreads();
 
     // ---- one lane, one state
@@ -506,25 +556,25 @@ __device__ __forceinline__ void decode_workgroup(const TableBlock *__restrict__ 
         }
     } else if (lone < 256) {
         if (stream_out)
-            walk_state<KB, true, NORM, true, UPD, HALF>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
+            walk_state<KB, true, NORM, true, UPD, HALF>(lut, spread, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
         else
-            walk_state<KB, true, NORM, false, UPD, HALF>(lut, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
+            walk_state<KB, true, NORM, false, UPD, HALF>(lut, spread, NoWords{}, lone, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
     } else if (staged) {
         wp = wp_begin = static_cast<uint32_t>(run_byte - aligned0);
         if (stream_out)
-            walk_state<KB, false, NORM, true, UPD, HALF>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
+            walk_state<KB, false, NORM, true, UPD, HALF>(lut, spread, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
                                               j, grad, lr);
         else
-            walk_state<KB, false, NORM, false, UPD, HALF>(lut, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
+            walk_state<KB, false, NORM, false, UPD, HALF>(lut, spread, LdsWords{stage}, 0u, x, wp, sm, coef, block, fields0, out, base, m,
                                                j, grad, lr);
     } else {
         // the runs of this workgroup's chunks did not fit the LDS window (more than ~4 bits per
         // symbol): read the words straight from the blob
         const GlobalWords direct{reinterpret_cast<const uint8_t *>(words) + run_byte};
         if (stream_out)
-            walk_state<KB, false, NORM, true, UPD, HALF>(lut, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
+            walk_state<KB, false, NORM, true, UPD, HALF>(lut, spread, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
         else
-            walk_state<KB, false, NORM, false, UPD, HALF>(lut, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
+            walk_state<KB, false, NORM, false, UPD, HALF>(lut, spread, direct, 0u, x, wp, sm, coef, block, fields0, out, base, m, j, grad, lr);
     }
     // a well-formed run is consumed exactly and leaves the state where the encoder started
     if (x != kRansL || wp - wp_begin != 2 * len)
@@ -535,9 +585,11 @@ template <int KB, bool NORM, int MODE = kPlain>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(const DecodeArgs a)
 {
     __shared__ __align__(16) uint32_t lut[kM];
-    __shared__ __align__(16) uint8_t stage[kStageBytes];
+    __shared__ __align__(16) uint8_t stage[kStageBytesOf<KB>];
+    __shared__ uint2 spread[kSpreadEntries<KB>];
     decode_workgroup<KB, NORM, MODE>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.low, a.out,
-                                     a.grad, a.lr, a.stream_out != 0, a.n, a.n_chunks, a.status, blockIdx.x, lut, stage);
+                                     a.grad, a.lr, a.stream_out != 0, a.n, a.n_chunks, a.status, blockIdx.x, lut, stage,
+                                     spread);
 }
 
 // Several tensors in one launch (a layer's weights): workgroups [t[i-1].wg_end, t[i].wg_end)
@@ -551,7 +603,8 @@ template <int KB, bool NORM, int MODE = kPlain>
 __global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchArgs b)
 {
     __shared__ __align__(16) uint32_t lut[kM];
-    __shared__ __align__(16) uint8_t stage[kStageBytes];
+    __shared__ __align__(16) uint8_t stage[kStageBytesOf<KB>];
+    __shared__ uint2 spread[kSpreadEntries<KB>];
     uint32_t i = 0, first = 0;
     while (i + 1 < b.count && blockIdx.x >= b.t[i].wg_end) {
         first = b.t[i].wg_end;
@@ -560,7 +613,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchAr
     const DecodeArgs &a = b.t[i];
     decode_workgroup<KB, NORM, MODE>(a.tb, a.offsets, a.states, a.lens, a.words, a.sm, a.coef, a.block, a.low, a.out,
                                      a.grad, a.lr, a.stream_out != 0, a.n, a.n_chunks, a.status, blockIdx.x - first, lut,
-                                     stage);
+                                     stage, spread);
 }
 
 // ------------------------------------------------------------------------------------------
