@@ -576,6 +576,41 @@ def extended(args, torch, nz, inputs, np, dev, stream, model):
                 "max_abs_diff_vs_dense_over_max_abs": round(((yl - want).abs().max() / want.abs().max()).item(), 7)}
         nz.neuzip_free(bl_)
         del wl, dense
+    # the q, k and v projections of a Llama-3-8B attention block on the same activations: one fused
+    # launch for the three against three fused calls and against decompressing the three (one launch)
+    # followed by three dense products
+    in_f, outs = 4096, (4096, 1024, 1024)
+    wq = [inputs.gaussian_bf16((o, in_f), inputs.seed_for(8, 700 + i), device=dev) for i, o in enumerate(outs)]
+    bq = [nz.neuzip_compress(w, 7) for w in wq]
+    dq = [torch.empty_like(w) for w in wq]
+    for tokens in (1, 16):
+        xl = inputs.gaussian_bf16((tokens, in_f), inputs.seed_for(8, 800 + tokens), std=1.0, device=dev)
+        yq = [torch.empty((tokens, o), dtype=torch.float32, device=dev) for o in outs]
+
+        def one_launch():
+            nz.neuzip_linear_batch(bq, outs, in_f, xl, None, yq)
+
+        def three_calls():
+            for b_, o_, y_ in zip(bq, outs, yq):
+                nz.neuzip_linear(b_, o_, in_f, xl, None, y_)
+
+        def separate():
+            nz.neuzip_decompress_batch(bq, [d.view(-1) for d in dq])
+            for d in dq:
+                torch.matmul(xl, d.t())
+
+        times = {name: event_us(torch, stream, fn, 50, warm=5)
+                 for name, fn in (("one", one_launch), ("three", three_calls), ("separate", separate))}
+        one_launch()
+        worst = max(((y_ - xl.float() @ d.float().t()).abs().max() / (xl.float() @ d.float().t()).abs().max()).item()
+                    for y_, d in zip(yq, dq))
+        lin[f"qkv_4096+1024+1024x4096_tokens{tokens}"] = {
+            "one_launch_us": round(times["one"], 1), "three_fused_calls_us": round(times["three"], 1),
+            "decompress_batch_then_dense_products_us": round(times["separate"], 1),
+            "max_abs_diff_vs_dense_over_max_abs": round(worst, 7)}
+    for b_ in bq:
+        nz.neuzip_free(b_)
+    del wq, dq
     ext["linear_forward"] = lin
     torch.cuda.empty_cache()
 

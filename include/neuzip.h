@@ -289,6 +289,25 @@ int neuzip_decompress_batch(const neuzip_blob *const *blobs, void *const *d_dsts
 int neuzip_linear(const neuzip_blob *weight, uint64_t out_features, uint64_t in_features, const void *d_x,
                   uint32_t tokens, const float *d_bias, float *d_y, void *hip_stream);
 
+/*
+ * neuzip_linear_batch -- the same compressed forward pass (Sec. 2.2) for several weights that are
+ * applied to the same activations, such as the q, k and v projections of an attention block or the
+ * gate and up projections of an MLP: y_i <- W_hat_i x + b_i for i < count in one launch, so that
+ * weights too small to fill the GPU on their own overlap with the others.
+ *
+ *   weights, out_features, d_y   host arrays of count entries (count at most 4, else EINVAL); weight i is
+ *                 out_features[i] x in_features, d_y[i] receives tokens x out_features[i] floats.
+ *                 All weights have the same mantissa_bits and are either all block-wise normalised
+ *                 or none is (else EINVAL).
+ *   d_bias        NULL (no biases), or a host array of count device pointers, each NULL or
+ *                 out_features[i] floats.
+ *   in_features, d_x, tokens     as for neuzip_linear; the activations are shared.
+ * Otherwise as neuzip_linear (which is this call with count = 1).  On EINVAL nothing has been launched.
+ */
+int neuzip_linear_batch(const neuzip_blob *const *weights, const uint64_t *out_features, uint32_t count,
+                        uint64_t in_features, const void *d_x, uint32_t tokens, const float *const *d_bias,
+                        float *const *d_y, void *hip_stream);
+
 /* Releases the blob and its device memory.  NULL is a no-op. */
 void neuzip_free(neuzip_blob *blob);
 

@@ -47,6 +47,8 @@ def _load():
     lib.neuzip_update.restype = i32
     lib.neuzip_linear.argtypes = [vp, u64, u64, vp, u32, vp, vp, vp]
     lib.neuzip_linear.restype = i32
+    lib.neuzip_linear_batch.argtypes = [vp, vp, u32, u64, vp, u32, vp, vp, vp]
+    lib.neuzip_linear_batch.restype = i32
     lib.neuzip_block_size.argtypes = [vp]
     lib.neuzip_block_size.restype = u32
     lib.neuzip_guard.argtypes = [vp]
@@ -96,7 +98,7 @@ _lib = None
 _lib = _load()
 
 EXPORTED = ["neuzip_compress", "neuzip_compress_noalloc", "neuzip_compress_blockwise", "neuzip_compress_batch", "neuzip_compress_guarded",
-            "neuzip_recompress", "neuzip_update", "neuzip_guard", "neuzip_linear", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
+            "neuzip_recompress", "neuzip_update", "neuzip_guard", "neuzip_linear", "neuzip_linear_batch", "neuzip_block_size", "neuzip_decompress", "neuzip_decompress_sequence", "neuzip_decompress_batch",
             "neuzip_free",
             "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits", "neuzip_dtype",
             "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check", "neuzip_stream_probe",
@@ -329,6 +331,41 @@ def neuzip_linear(weight: Blob, out_features: int, in_features: int, x: torch.Te
     if rc != OK:
         raise NeuzipError(rc, "neuzip_linear")
     return y
+
+
+def neuzip_linear_batch(weights, out_features, in_features: int, x: torch.Tensor, biases=None, ys=None,
+                        stream=None):
+    """y_i = x W_hat_i^T + bias_i for several compressed weights applied to the same activations, in one
+    launch (at most 4 weights).  Returns the list of float32 results."""
+    _check_tensor(x)
+    count = len(weights)
+    if len(out_features) != count or (biases is not None and len(biases) != count) or \
+            (ys is not None and len(ys) != count):
+        raise ValueError("weights, out_features, biases and ys must have one entry per weight")
+    tokens = x.numel() // in_features if in_features else 0
+    if x.numel() != tokens * in_features:
+        raise ValueError("activations must be tokens x in_features")
+    if ys is None:
+        ys = [torch.empty((tokens, o), dtype=torch.float32, device=x.device) for o in out_features]
+    for y, o in zip(ys, out_features):
+        if not (y.is_cuda and y.dtype == torch.float32 and y.is_contiguous() and y.numel() == tokens * o):
+            raise TypeError("expected contiguous float32 CUDA tensors of tokens x out_features")
+    if biases is not None:
+        for bias, o in zip(biases, out_features):
+            if bias is not None and not (bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous()
+                                         and bias.numel() == o):
+                raise TypeError("expected contiguous float32 CUDA biases of out_features")
+    arr = (ctypes.c_void_p * count)(*[w.handle.value for w in weights])
+    outs = (ctypes.c_uint64 * count)(*[int(o) for o in out_features])
+    yp = (ctypes.c_void_p * count)(*[y.data_ptr() for y in ys])
+    bp = None
+    if biases is not None:
+        bp = (ctypes.c_void_p * count)(*[(b.data_ptr() if b is not None else None) for b in biases])
+    rc = _lib.neuzip_linear_batch(arr, outs, count, in_features, ctypes.c_void_p(x.data_ptr()), tokens, bp, yp,
+                                  _stream_handle(stream))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_linear_batch")
+    return ys
 
 
 def neuzip_free(blob: Blob) -> None:

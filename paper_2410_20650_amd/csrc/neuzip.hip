@@ -475,23 +475,33 @@ int launch_batch(const BatchArgs &args, int variant, uint32_t groups, hipStream_
 // 4096 x 14336.
 inline uint32_t linear_columns(uint32_t tokens, uint32_t stride) { return tokens > 16 && stride == 1 ? 32u : 16u; }
 
+// One weight: the plain kernel (its arguments are the first entry); several: the batch kernel.
 template <int KB, bool NORM>
-void launch_linear(const LinearArgs &args, uint32_t cols, uint32_t wgs, hipStream_t stream)
+void launch_linear(const LinearBatchArgs &batch, uint32_t cols, uint32_t wgs, hipStream_t stream)
 {
     const dim3 grid(wgs), block(kLinThreads);
+    const uint32_t tokens = batch.t[0].tokens;
+#define NZ_LINEAR(COLS, MT)                                                                                       \
+    do {                                                                                                          \
+        if (batch.count == 1)                                                                                     \
+            hipLaunchKernelGGL((linear_kernel<KB, COLS, MT, NORM>), grid, block, 0, stream, batch.t[0]);          \
+        else                                                                                                      \
+            hipLaunchKernelGGL((linear_batch_kernel<KB, COLS, MT, NORM>), grid, block, 0, stream, batch);         \
+    } while (0)
     if (cols == 32) {
-        if (args.tokens <= 32)
-            hipLaunchKernelGGL((linear_kernel<KB, 32, 1, NORM>), grid, block, 0, stream, args);
+        if (tokens <= 32)
+            NZ_LINEAR(32, 1);
         else
-            hipLaunchKernelGGL((linear_kernel<KB, 32, 2, NORM>), grid, block, 0, stream, args);
+            NZ_LINEAR(32, 2);
         return;
     }
-    switch ((args.tokens + 15) / 16) {
-    case 1: hipLaunchKernelGGL((linear_kernel<KB, 16, 1, NORM>), grid, block, 0, stream, args); break;
-    case 2: hipLaunchKernelGGL((linear_kernel<KB, 16, 2, NORM>), grid, block, 0, stream, args); break;
-    case 3: hipLaunchKernelGGL((linear_kernel<KB, 16, 3, NORM>), grid, block, 0, stream, args); break;
-    default: hipLaunchKernelGGL((linear_kernel<KB, 16, 4, NORM>), grid, block, 0, stream, args); break;
+    switch ((tokens + 15) / 16) {
+    case 1: NZ_LINEAR(16, 1); break;
+    case 2: NZ_LINEAR(16, 2); break;
+    case 3: NZ_LINEAR(16, 3); break;
+    default: NZ_LINEAR(16, 4); break;
     }
+#undef NZ_LINEAR
 }
 
 // An empty tensor: a zeroed table block (a fill kernel, not a memset node, so the call stays safe
@@ -986,18 +996,34 @@ uint32_t neuzip_guard(const neuzip_blob *blob) { return is_blob(blob) ? blob->gu
 int neuzip_linear(const neuzip_blob *weight, uint64_t out_features, uint64_t in_features, const void *d_x,
                   uint32_t tokens, const float *d_bias, float *d_y, void *hip_stream)
 {
-    if (!is_blob(weight) || !weight->has_table || !on_current_device(weight) || !d_x || !d_y)
+    return neuzip_linear_batch(&weight, &out_features, 1, in_features, d_x, tokens, &d_bias, &d_y, hip_stream);
+}
+
+int neuzip_linear_batch(const neuzip_blob *const *weights, const uint64_t *out_features, uint32_t count,
+                        uint64_t in_features, const void *d_x, uint32_t tokens, const float *const *d_bias,
+                        float *const *d_y, void *hip_stream)
+{
+    if (count == 0)
+        return NEUZIP_OK;
+    if (!weights || !out_features || !d_y || !d_x || tokens == 0 || count > kLinBatchMax)
         return NEUZIP_EINVAL;
-    if (out_features == 0 || in_features == 0 || in_features % kTurn != 0 || in_features >= (1ull << 31) ||
-        out_features >= (1ull << 31) || out_features * in_features != weight->n)
+    if (in_features == 0 || in_features % kTurn != 0 || in_features >= (1ull << 31) ||
+        (reinterpret_cast<uintptr_t>(d_x) & 15u))
         return NEUZIP_EINVAL;
-    if (tokens == 0)
-        return NEUZIP_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(d_x) & 15u) || (reinterpret_cast<uintptr_t>(d_y) & 3u) ||
-        (reinterpret_cast<uintptr_t>(d_bias) & 3u))
-        return NEUZIP_EINVAL;
-    if (weight->elem != NEUZIP_BF16)
-        return NEUZIP_EUNSUPPORTED;
+    for (uint32_t i = 0; i < count; ++i) {
+        const neuzip_blob *w = weights[i];
+        if (!is_blob(w) || !w->has_table || !on_current_device(w) || !d_y[i])
+            return NEUZIP_EINVAL;
+        if (out_features[i] == 0 || out_features[i] >= (1ull << 31) || out_features[i] * in_features != w->n)
+            return NEUZIP_EINVAL;
+        if ((reinterpret_cast<uintptr_t>(d_y[i]) & 3u) || (d_bias && (reinterpret_cast<uintptr_t>(d_bias[i]) & 3u)))
+            return NEUZIP_EINVAL;
+        if (w->elem != NEUZIP_BF16)
+            return NEUZIP_EUNSUPPORTED;
+        // one launch serves one kind of weight
+        if (w->k != weights[0]->k || (w->block != 0) != (weights[0]->block != 0))
+            return NEUZIP_EINVAL;
+    }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     uint64_t gcd = in_features, r = kChunk;
     while (r) {
@@ -1005,52 +1031,75 @@ int neuzip_linear(const neuzip_blob *weight, uint64_t out_features, uint64_t in_
         gcd = r;
         r = t;
     }
-    LinearArgs a;
-    a.tb = table_of(weight);
-    a.offsets = offsets_of(weight);
-    a.states = states_of(weight);
-    a.lens = lens_of(weight);
-    a.words = reinterpret_cast<const uint16_t *>(weight->words);
-    a.sm = sm_of(weight);
-    a.x = static_cast<const uint16_t *>(d_x);
-    a.y = d_y;
-    a.status = table_of(weight)->status;
-    a.n = weight->n;
-    a.n_chunks = weight->n_chunks;
-    a.in_features = static_cast<uint32_t>(in_features);
-    a.out_features = static_cast<uint32_t>(out_features);
-    a.coef = coef_of(weight);
-    a.block_shift = 0;
-    while (weight->block && (1u << a.block_shift) < weight->block)
-        ++a.block_shift;
-    a.stride = static_cast<uint32_t>(in_features / gcd);
-    a.rstep = static_cast<uint32_t>(kChunk / gcd);
-    const uint64_t cells = static_cast<uint64_t>(tokens) * out_features;
-    hipLaunchKernelGGL(linear_init_kernel, dim3(static_cast<uint32_t>((cells + 255) / 256)), dim3(256), 0, stream, d_y,
-                       d_bias, tokens, a.out_features);
+    LinearBatchArgs batch;
+    LinearInitBatchArgs init;
+    std::memset(&batch, 0, sizeof(batch));
+    std::memset(&init, 0, sizeof(init));
+    batch.count = init.count = count;
+    init.tokens = tokens;
+    uint32_t init_wgs = 0;
+    for (uint32_t i = 0; i < count; ++i) {
+        const neuzip_blob *w = weights[i];
+        LinearArgs &a = batch.t[i];
+        a.tb = table_of(w);
+        a.offsets = offsets_of(w);
+        a.states = states_of(w);
+        a.lens = lens_of(w);
+        a.words = reinterpret_cast<const uint16_t *>(w->words);
+        a.sm = sm_of(w);
+        a.status = table_of(w)->status;
+        a.n = w->n;
+        a.n_chunks = w->n_chunks;
+        a.in_features = static_cast<uint32_t>(in_features);
+        a.out_features = static_cast<uint32_t>(out_features[i]);
+        a.coef = coef_of(w);
+        a.block_shift = 0;
+        while (w->block && (1u << a.block_shift) < w->block)
+            ++a.block_shift;
+        a.stride = static_cast<uint32_t>(in_features / gcd);
+        a.rstep = static_cast<uint32_t>(kChunk / gcd);
+        const uint64_t cells = static_cast<uint64_t>(tokens) * out_features[i];
+        init.y[i] = d_y[i];
+        init.bias[i] = d_bias ? d_bias[i] : nullptr;
+        init.out_features[i] = a.out_features;
+        init_wgs += static_cast<uint32_t>((cells + 255) / 256);
+        init.wg_end[i] = init_wgs;
+    }
+    if (count == 1)
+        hipLaunchKernelGGL(linear_init_kernel, dim3(init_wgs), dim3(256), 0, stream, init.y[0], init.bias[0], tokens,
+                           init.out_features[0]);
+    else
+        hipLaunchKernelGGL(linear_init_batch_kernel, dim3(init_wgs), dim3(256), 0, stream, init);
     // the kernel holds the partial sums of at most 64 tokens: larger batches go through in tiles of 64
-    // (each tile decodes the weight again: beyond a few tiles decompressing once and a dense product win)
+    // (each tile decodes the weights again: beyond a few tiles decompressing once and a dense product win)
+    const neuzip_blob *first = weights[0];
     for (uint32_t t0 = 0; t0 < tokens; t0 += kLinMaxTokens) {
-        a.tokens = tokens - t0 < kLinMaxTokens ? tokens - t0 : kLinMaxTokens;
-        a.x = static_cast<const uint16_t *>(d_x) + static_cast<uint64_t>(t0) * in_features;
-        a.y = d_y + static_cast<uint64_t>(t0) * out_features;
-        const uint32_t cols = linear_columns(a.tokens, a.stride);  // chunks per group = columns of the matrix instruction
-        const uint64_t per_block = static_cast<uint64_t>(cols) * a.stride;
-        a.n_groups = static_cast<uint32_t>((weight->n_chunks + per_block - 1) / per_block * a.stride);
+        const uint32_t tile = tokens - t0 < kLinMaxTokens ? tokens - t0 : kLinMaxTokens;
+        const uint32_t cols = linear_columns(tile, batch.t[0].stride);  // chunks per group = columns of the matrix instruction
         const uint32_t groups_per_wg = kDecChunksPerWg / cols;
-        const uint32_t wgs = (a.n_groups + groups_per_wg - 1) / groups_per_wg;
-        if (weight->block) {
-            switch (weight->k) {
-            case 3: launch_linear<3, true>(a, cols, wgs, stream); break;
-            case 1: launch_linear<1, true>(a, cols, wgs, stream); break;
-            default: launch_linear<0, true>(a, cols, wgs, stream); break;
+        uint32_t wgs = 0;
+        for (uint32_t i = 0; i < count; ++i) {
+            LinearArgs &a = batch.t[i];
+            a.tokens = tile;
+            a.x = static_cast<const uint16_t *>(d_x) + static_cast<uint64_t>(t0) * in_features;
+            a.y = d_y[i] + static_cast<uint64_t>(t0) * out_features[i];
+            const uint64_t per_block = static_cast<uint64_t>(cols) * a.stride;
+            a.n_groups = static_cast<uint32_t>((weights[i]->n_chunks + per_block - 1) / per_block * a.stride);
+            wgs += (a.n_groups + groups_per_wg - 1) / groups_per_wg;
+            batch.wg_end[i] = wgs;
+        }
+        if (first->block) {
+            switch (first->k) {
+            case 3: launch_linear<3, true>(batch, cols, wgs, stream); break;
+            case 1: launch_linear<1, true>(batch, cols, wgs, stream); break;
+            default: launch_linear<0, true>(batch, cols, wgs, stream); break;
             }
         } else {
-            switch (weight->k) {
-            case 7: launch_linear<7, false>(a, cols, wgs, stream); break;
-            case 3: launch_linear<3, false>(a, cols, wgs, stream); break;
-            case 1: launch_linear<1, false>(a, cols, wgs, stream); break;
-            default: launch_linear<0, false>(a, cols, wgs, stream); break;
+            switch (first->k) {
+            case 7: launch_linear<7, false>(batch, cols, wgs, stream); break;
+            case 3: launch_linear<3, false>(batch, cols, wgs, stream); break;
+            case 1: launch_linear<1, false>(batch, cols, wgs, stream); break;
+            default: launch_linear<0, false>(batch, cols, wgs, stream); break;
             }
         }
         if (!hip_ok(hipGetLastError()))

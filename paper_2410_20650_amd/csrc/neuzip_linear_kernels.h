@@ -90,6 +90,23 @@ struct LinearArgs {
     uint32_t n_groups;
 };
 
+// Several weights applied to the same kind of input in one launch (the q, k and v projections of an
+// attention block, say): workgroups [wg_end[i-1], wg_end[i]) belong to weight i.  Weights too small to
+// fill the chip on their own overlap with the others.
+constexpr uint32_t kLinBatchMax = 4;
+struct LinearBatchArgs {
+    LinearArgs t[kLinBatchMax];
+    uint32_t wg_end[kLinBatchMax];
+    uint32_t count;
+};
+struct LinearInitBatchArgs {
+    float *y[kLinBatchMax];
+    const float *bias[kLinBatchMax];
+    uint32_t out_features[kLinBatchMax];
+    uint32_t wg_end[kLinBatchMax];
+    uint32_t tokens, count;
+};
+
 // y[t][o] = bias[o] (or 0): the accumulation target of the kernel below
 __global__ void linear_init_kernel(float *__restrict__ y, const float *__restrict__ bias, uint32_t tokens,
                                    uint32_t out_features)
@@ -97,6 +114,18 @@ __global__ void linear_init_kernel(float *__restrict__ y, const float *__restric
     const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i < static_cast<uint64_t>(tokens) * out_features)
         y[i] = bias ? bias[i % out_features] : 0.0f;
+}
+
+__global__ void linear_init_batch_kernel(const LinearInitBatchArgs b)
+{
+    uint32_t i = 0, first = 0;
+    while (i + 1 < b.count && blockIdx.x >= b.wg_end[i]) {
+        first = b.wg_end[i];
+        ++i;
+    }
+    const uint64_t at = static_cast<uint64_t>(blockIdx.x - first) * blockDim.x + threadIdx.x;
+    if (at < static_cast<uint64_t>(b.tokens) * b.out_features[i])
+        b.y[i][at] = b.bias[i] ? b.bias[i][at % b.out_features[i]] : 0.0f;
 }
 
 __device__ __forceinline__ void atomic_add_f32(float *p, float v)
@@ -216,8 +245,9 @@ __device__ __forceinline__ void linear_walk(const uint32_t *__restrict__ lut, co
     }
 }
 
-template <int KB, int COLS, int MT, bool NORM = false>
-__global__ __launch_bounds__(kLinThreads) void linear_kernel(const LinearArgs a)
+template <int KB, int COLS, int MT, bool NORM>
+__device__ __forceinline__ void linear_workgroup(const LinearArgs &a, uint32_t wg, uint32_t *__restrict__ lut,
+                                                 uint8_t *__restrict__ stage)
 {
     constexpr uint32_t kLinGroupChunks = COLS;                       // columns of the B operand
     constexpr uint32_t kGroupsPerWg = kDecChunksPerWg / COLS;        // 2 or 1
@@ -225,14 +255,12 @@ __global__ __launch_bounds__(kLinThreads) void linear_kernel(const LinearArgs a)
     constexpr uint32_t kPerWave = 64 / COLS;                         // states of a chunk per wave: 4 or 2
     constexpr uint32_t kLinGroupBytes = kStageBytes / kGroupsPerWg;  // LDS window of one group's word runs
     constexpr uint32_t kColsPerWave = COLS / kWavesPerGroup;         // columns a wave copies: 4
-    __shared__ __align__(16) uint32_t lut[kM];
-    __shared__ __align__(16) uint8_t stage[kStageBytes];
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = tid >> 6, lane = tid & 63u;
     const uint32_t g = wave / kWavesPerGroup, sq = wave % kWavesPerGroup;
     const uint32_t col = lane & (COLS - 1);
     const uint32_t j = sq * kPerWave + lane / COLS;
-    const uint32_t group = blockIdx.x * kGroupsPerWg + g;
+    const uint32_t group = wg * kGroupsPerWg + g;
     const bool group_live = group < a.n_groups;
     // group -> its COLS chunks: `stride` groups interleave inside a block of COLS * stride chunks
     const uint32_t block_id = group / a.stride, first_in_block = group % a.stride;
@@ -321,6 +349,27 @@ __global__ __launch_bounds__(kLinThreads) void linear_kernel(const LinearArgs a)
     }
     if (live && (x != kRansL || wp - wp_begin != 2 * len))
         atomicOr(a.status, 1u);
+}
+
+template <int KB, int COLS, int MT, bool NORM = false>
+__global__ __launch_bounds__(kLinThreads) void linear_kernel(const LinearArgs a)
+{
+    __shared__ __align__(16) uint32_t lut[kM];
+    __shared__ __align__(16) uint8_t stage[kStageBytes];
+    linear_workgroup<KB, COLS, MT, NORM>(a, blockIdx.x, lut, stage);
+}
+
+template <int KB, int COLS, int MT, bool NORM = false>
+__global__ __launch_bounds__(kLinThreads) void linear_batch_kernel(const LinearBatchArgs b)
+{
+    __shared__ __align__(16) uint32_t lut[kM];
+    __shared__ __align__(16) uint8_t stage[kStageBytes];
+    uint32_t i = 0, first = 0;
+    while (i + 1 < b.count && blockIdx.x >= b.wg_end[i]) {
+        first = b.wg_end[i];
+        ++i;
+    }
+    linear_workgroup<KB, COLS, MT, NORM>(b.t[i], blockIdx.x - first, lut, stage);
 }
 
 }  // namespace nz

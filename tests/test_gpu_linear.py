@@ -77,6 +77,50 @@ def test_linear_on_more_than_64_tokens_goes_through_in_tiles(nz, tokens):
         check_linear(nz, w, out_f, in_f, tokens, k=k, bias=True, seed=9501 + tokens, block=block)
 
 
+@pytest.mark.parametrize("tokens", [1, 8, 40, 100])
+@pytest.mark.parametrize("k,block", [(7, 0), (3, 0), (0, 512)])
+def test_linear_batch_of_projections_matches_the_oracle_and_the_single_calls(nz, tokens, k, block):
+    # the q, k and v projections of an attention block on the same activations, in one launch
+    in_f, outs = 1024, (256, 64, 37)
+    ws = [inputs.gaussian_bf16(o * in_f, 9800 + o, device=DEV) for o in outs]
+    x = inputs.gaussian_bf16((tokens, in_f), 9801 + tokens, std=1.0, device=DEV)
+    biases = [torch.linspace(-1, 1, outs[0], dtype=torch.float32, device=DEV), None,
+              torch.linspace(2, 3, outs[2], dtype=torch.float32, device=DEV)]
+    blobs = [nz.neuzip_compress_blockwise(w, k, block) for w in ws]
+    ys = [torch.full((tokens, o), float("nan"), dtype=torch.float32, device=DEV) for o in outs]
+    nz.neuzip_linear_batch(blobs, outs, in_f, x, biases, ys)
+    xw = inputs.bits(x).reshape(tokens, in_f)
+    for w, blob, o, bias, y in zip(ws, blobs, outs, biases, ys):
+        nz.neuzip_check(blob)
+        container = O.compress(inputs.bits(w), k, threads=8, block=block)
+        b64 = None if bias is None else bias.cpu().numpy().astype(np.float64)
+        want = L.linear(container, o, in_f, xw, bias=b64)
+        mag = L.magnitude(container, o, in_f, xw) + (0 if b64 is None else np.abs(b64))
+        got = y.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got))
+        bound = 2.0 * (in_f + 64) * 2.0 ** -24 * mag + 1e-30
+        assert np.max(np.abs(got - want) / bound) <= 1.0, (o, tokens, k, block)
+        single = nz.neuzip_linear(blob, o, in_f, x, bias)
+        assert torch.allclose(y, single, rtol=0, atol=1e-5 * max(single.abs().max().item(), 1e-30))
+
+
+def test_linear_batch_argument_errors(nz):
+    in_f = 256
+    w7 = nz.neuzip_compress(inputs.gaussian_bf16(32 * in_f, 9810, device=DEV), 7)
+    w3 = nz.neuzip_compress(inputs.gaussian_bf16(32 * in_f, 9811, device=DEV), 3)
+    x = inputs.gaussian_bf16((4, in_f), 9812, device=DEV)
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_linear_batch([w7, w3], [32, 32], in_f, x)            # mixed mantissa widths
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_linear_batch([w7] * 5, [32] * 5, in_f, x)            # more than 4 weights
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_linear_batch([w7, w7], [32, 16], in_f, x)            # shape does not match the blob
+    assert nz.neuzip_linear_batch([], [], in_f, x) == []
+    ys = nz.neuzip_linear_batch([w7, w7], [32, 32], in_f, x)
+    assert torch.equal(ys[0], ys[1]) or torch.allclose(ys[0], ys[1], rtol=0, atol=1e-6)
+    torch.cuda.synchronize()
+
+
 def test_linear_with_bias_and_one_hot_activations(nz):
     # one-hot activations select weight columns: the result is exact, whatever the summation order
     out_f, in_f = 50, 512
