@@ -34,9 +34,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
 CPU_SHARE = 16          # host threads a one-GPU machine grants a job
 
-PROFILE_CASES = ("decode_config2", "decode_config4_k7", "decode_config4_k3", "decode_embedding", "decode_batch_layer",
+PROFILE_CASES = ("decode_config2", "decode_config4_k7", "decode_config4_k3", "decode_config4_k1", "decode_config4_k0",
+                 "decode_embedding", "decode_batch_layer",
                  "decode_small_kv", "compress_config2", "recompress_config2", "compress_embedding",
-                 "recompress_embedding", "update_config2", "linear_q")
+                 "recompress_embedding", "update_config2", "linear_q", "linear_qkv")
 
 
 def parse_args():
@@ -188,7 +189,7 @@ def profile_case(args, torch, nz, inputs, np, dev, stream):
         w = None
 
     if case.startswith("decode_") and case != "decode_batch_layer":
-        k = 3 if case.endswith("_k3") else 7
+        k = {"_k3": 3, "_k1": 1, "_k0": 0}.get(case[-3:], 7)
         blob = nz.neuzip_compress(w, k)
         out = torch.empty(w.numel(), dtype=torch.bfloat16, device=dev)
         run(lambda: nz.neuzip_decompress(blob, out), blob.compressed_bytes + 2 * w.numel(), w.numel())
@@ -214,6 +215,14 @@ def profile_case(args, torch, nz, inputs, np, dev, stream):
         nz.neuzip_decompress(blob, tmp.view(-1))
         run_wall(lambda: nz.neuzip_update([blob], [grad], [tmp], 1e-3, weights_ready=2),
                  4 * w.numel() + blob.compressed_bytes, w.numel())
+    elif case == "linear_qkv":
+        outs = (4096, 1024, 1024)
+        ws = [inputs.gaussian_bf16((o, 4096), inputs.seed_for(8, 700 + i), device=dev) for i, o in enumerate(outs)]
+        blobs = [nz.neuzip_compress(t, 7) for t in ws]
+        x = inputs.gaussian_bf16((1, 4096), inputs.seed_for(8, 501), std=1.0, device=dev)
+        ys = [torch.empty((1, o), dtype=torch.float32, device=dev) for o in outs]
+        run(lambda: nz.neuzip_linear_batch(blobs, outs, 4096, x, None, ys), sum(b.compressed_bytes for b in blobs),
+            sum(t.numel() for t in ws))
     elif case == "linear_q":
         blob = nz.neuzip_compress(w, 7)
         x = inputs.gaussian_bf16((1, 4096), inputs.seed_for(8, 501), std=1.0, device=dev)
