@@ -35,6 +35,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
 CPU_SHARE = 16          # host threads a one-GPU machine grants a job
 
 PROFILE_CASES = ("decode_config2", "decode_config4_k7", "decode_config4_k3", "decode_config4_k1", "decode_config4_k0",
+                 "decode_config4_k3_block512",
                  "decode_embedding", "decode_batch_layer",
                  "decode_small_kv", "compress_config2", "recompress_config2", "compress_embedding",
                  "recompress_embedding", "update_config2", "linear_q", "linear_qkv")
@@ -189,8 +190,11 @@ def profile_case(args, torch, nz, inputs, np, dev, stream):
         w = None
 
     if case.startswith("decode_") and case != "decode_batch_layer":
-        k = {"_k3": 3, "_k1": 1, "_k0": 0}.get(case[-3:], 7)
-        blob = nz.neuzip_compress(w, k)
+        if case.endswith("_block512"):     # the paper's default lossy form: block-wise normalisation (Sec. 2.3)
+            k, blob = 3, nz.neuzip_compress_blockwise(w, 3, 512)
+        else:
+            k = {"_k3": 3, "_k1": 1, "_k0": 0}.get(case[-3:], 7)
+            blob = nz.neuzip_compress(w, k)
         out = torch.empty(w.numel(), dtype=torch.bfloat16, device=dev)
         run(lambda: nz.neuzip_decompress(blob, out), blob.compressed_bytes + 2 * w.numel(), w.numel())
         nz.neuzip_check(blob)
