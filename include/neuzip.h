@@ -394,11 +394,20 @@ int neuzip_compress_noalloc(const void *d_src, uint64_t n_elems, int dtype, int 
                             void *hip_stream, neuzip_blob *blob);
 
 /* Device bytes of the workspace that compress calls share and keep between calls: the encoder's
- * run slots -- 16 x 200 words per 4096-element chunk of the largest batch compressed so far, 1.56
- * bytes per element -- plus word counts and histogram bins.  It is not part of any blob; Sec. 2.2's
- * peak-memory accounting has to count it while weights are being compressed (training), and
- * neuzip_release_workspace returns it (inference, once the model is compressed).  0 if none is held. */
+ * run slots -- 16 x 200 words per 4096-element chunk, 1.56 bytes per element of the largest batch
+ * compressed so far, but never more than the workspace limit below -- plus word counts and histogram
+ * bins.  It is not part of any blob; Sec. 2.2's peak-memory accounting has to count it while weights
+ * are being compressed (training), and neuzip_release_workspace returns it (inference, once the
+ * model is compressed).  0 if none is held. */
 uint64_t neuzip_workspace_bytes(void);
+
+/* Limit on the encoder's run slots, in bytes (default 384 MiB, i.e. 251 M elements; 0 restores the
+ * default; at least one group of 16 chunks, 102400 bytes, is always allowed).  A batch that would need
+ * more is compressed tensor by tensor, and a single tensor that would need more goes through the
+ * encoder in tiles of whole chunks, with one wait for the host per tile; the containers are the
+ * same.  A workspace already larger than the new limit is freed.  Applies to all compress, recompress
+ * and update calls except neuzip_compress_noalloc.  Not to be called while such a call runs. */
+int neuzip_set_workspace_limit(uint64_t slot_bytes);
 
 /* Frees the per-device workspace compress keeps between calls. */
 int neuzip_release_workspace(void);

@@ -87,6 +87,8 @@ def _load():
     lib.neuzip_workspace_bytes.restype = u64
     lib.neuzip_release_workspace.argtypes = []
     lib.neuzip_release_workspace.restype = i32
+    lib.neuzip_set_workspace_limit.argtypes = [u64]
+    lib.neuzip_set_workspace_limit.restype = i32
     lib.neuzip_strerror.argtypes = [i32]
     lib.neuzip_strerror.restype = ctypes.c_char_p
     lib.neuzip_last_hip_error.argtypes = []
@@ -102,7 +104,7 @@ EXPORTED = ["neuzip_compress", "neuzip_compress_noalloc", "neuzip_compress_block
             "neuzip_free",
             "neuzip_compressed_bytes", "neuzip_device_bytes", "neuzip_elems", "neuzip_mantissa_bits", "neuzip_dtype",
             "neuzip_export", "neuzip_import", "neuzip_histogram", "neuzip_frequencies", "neuzip_check", "neuzip_stream_probe",
-            "neuzip_workspace_bytes", "neuzip_release_workspace", "neuzip_strerror", "neuzip_last_hip_error"]
+            "neuzip_workspace_bytes", "neuzip_release_workspace", "neuzip_set_workspace_limit", "neuzip_strerror", "neuzip_last_hip_error"]
 
 
 def library():
@@ -433,6 +435,13 @@ def neuzip_check(blob: Blob, stream=None) -> None:
 
 def neuzip_workspace_bytes() -> int:
     return int(_lib.neuzip_workspace_bytes())
+
+
+def neuzip_set_workspace_limit(slot_bytes: int) -> None:
+    """Limit on the encoder's run slots in bytes (0: the default); larger tensors are compressed in tiles."""
+    rc = _lib.neuzip_set_workspace_limit(int(slot_bytes))
+    if rc != OK:
+        raise NeuzipError(rc, "neuzip_set_workspace_limit")
 
 
 def neuzip_release_workspace() -> None:

@@ -531,6 +531,107 @@ void launch_hist(const Workspace &ws, const CompressBatch &batch, bool norm, uin
         hipLaunchKernelGGL(hist_split_kernel<KB>, dim3(groups), dim3(threads), 0, stream, batch, ws.counts);
 }
 
+// Bytes of encoder slots one group of 16 chunks takes, and the limit on the slot array: a batch that
+// needs more is compressed tensor by tensor, and a tensor that alone needs more in tiles of whole groups.
+constexpr uint64_t kSlotBytesPerGroup = static_cast<uint64_t>(kChunksPerGroup) * kStates * kRunCap * 2;
+// (384 MiB: the seven weights of a Llama-3-8B layer, 218 M elements, still go through as one batch --
+// measured 8 % faster than in two parts -- and the 525 M-element embedding takes three tiles, 3 % slower
+// than in one piece with 0.82 GB of slots)
+constexpr uint64_t kDefaultSlotLimit = 384ull << 20;
+uint64_t g_slot_limit = kDefaultSlotLimit;
+inline uint64_t slot_limit_groups()
+{
+    const uint64_t g = g_slot_limit / kSlotBytesPerGroup;
+    return g < 1 ? 1 : g;
+}
+
+// Makes room for `want` words in a blob's word section while keeping the first `keep` words it holds
+// (the tiles compacted so far).
+int grow_words_keeping(neuzip_blob *b, uint64_t want, uint64_t keep, hipStream_t stream)
+{
+    const uint64_t need = pad_to(want * 2, 256) + 1024;
+    if (b->words_bytes >= need)
+        return NEUZIP_OK;
+    const uint64_t roomy = pad_to(need + need / 64, 256);
+    uint8_t *fresh = nullptr;
+    if (hipMalloc(reinterpret_cast<void **>(&fresh), roomy) != hipSuccess) {
+        (void)hipGetLastError();
+        return NEUZIP_ENOMEM;
+    }
+    if (b->words) {
+        if (keep > 0) {
+            const uint64_t bytes = pad_to(keep * 2, 16) < b->words_bytes ? pad_to(keep * 2, 16) : b->words_bytes;
+            if (!hip_ok(hipMemcpyAsync(fresh, b->words, bytes, hipMemcpyDeviceToDevice, stream)) ||
+                !hip_ok(hipStreamSynchronize(stream))) {
+                (void)hipFree(fresh);
+                return NEUZIP_EHIP;
+            }
+        }
+        if (!hip_ok(hipFree(b->words))) {
+            (void)hipFree(fresh);
+            return NEUZIP_EHIP;
+        }
+    }
+    b->words = fresh;
+    b->words_bytes = roomy;
+    return NEUZIP_OK;
+}
+
+// The encoder launch of a compress pass.  variant: kUpdateVariant, 39 (binary16), 23 (binary32) or the
+// mantissa width; reuse: the one-pass encoders that code with the table the blob holds.
+bool launch_encode(const Workspace &ws, const CompressBatch &batch, uint32_t workgroups, int variant, bool reuse, int elem,
+                   uint32_t block, uint32_t *super_words, CallState *state, hipStream_t stream)
+{
+    const dim3 grid(workgroups), threads(kEncThreads);
+#define NZ_ENCODE(...)                                                                                          \
+    hipLaunchKernelGGL((encode_kernel<__VA_ARGS__>), grid, threads, 0, stream, batch, ws.counts, ws.chunk_words, \
+                       ws.group_words, super_words, ws.slots, ws.pinned, state)
+    if (reuse) {
+        switch (variant) {
+        case kUpdateVariant: NZ_ENCODE(false, 7, false, false, true); break;
+        case 39: NZ_ENCODE(false, 7, false, true); break;
+        case 23: NZ_ENCODE(false, 7, true); break;
+        case 7: NZ_ENCODE(false, 7); break;
+        case 3: NZ_ENCODE(false, 3); break;
+        case 1: NZ_ENCODE(false, 1); break;
+        default: NZ_ENCODE(false, 0); break;
+        }
+    } else if (elem == NEUZIP_F16) {
+        NZ_ENCODE(false, -1, false, true);
+    } else if (elem == NEUZIP_F32) {
+        NZ_ENCODE(false, -1, true);
+    } else if (block) {
+        NZ_ENCODE(true, -1);
+    } else {
+        NZ_ENCODE(false, -1);
+    }
+#undef NZ_ENCODE
+    return hip_ok(hipGetLastError());
+}
+
+bool launch_compaction(const Workspace &ws, const CompressBatch &batch, uint32_t workgroups, uint32_t *super_words,
+                       CallState *state, CallState *state_next, uint32_t *super_next, hipStream_t stream)
+{
+    hipLaunchKernelGGL(compact_kernel, dim3(workgroups), dim3(kCompactThreads), 0, stream, batch, ws.slots, ws.chunk_words,
+                       ws.group_words, super_words, state, ws.counts, state_next, super_next, ws.super_cap, ws.all_done,
+                       ws.pinned);
+    return hip_ok(hipGetLastError());
+}
+
+void launch_histogram(const Workspace &ws, const CompressBatch &batch, int variant, bool norm, uint32_t groups,
+                      uint32_t threads, hipStream_t stream)
+{
+    const dim3 grid(groups), block(threads);
+    switch (variant) {
+    case 39: hipLaunchKernelGGL((hist_split_kernel<7, false, true>), grid, block, 0, stream, batch, ws.counts); break;
+    case 23: hipLaunchKernelGGL((hist_split_kernel<7, true>), grid, block, 0, stream, batch, ws.counts); break;
+    case 7: launch_hist<7>(ws, batch, norm, groups, threads, stream); break;
+    case 3: launch_hist<3>(ws, batch, norm, groups, threads, stream); break;
+    case 1: launch_hist<1>(ws, batch, norm, groups, threads, stream); break;
+    default: launch_hist<0>(ws, batch, norm, groups, threads, stream); break;
+    }
+}
+
 constexpr uint32_t kKeepGuard = 0xFFFFFFFFu;  // compress_some: every blob keeps the guard band it has
 
 // Compresses up to kBatchMax tensors (arguments already validated) with one pass of the pipeline.
@@ -543,12 +644,188 @@ constexpr uint32_t kKeepGuard = 0xFFFFFFFFu;  // compress_some: every blob keeps
 // fixed_ws: a workspace of fixed size that lives in the library's static device array, for the entry
 // point that allocates nothing (reuse = false, every blob exists already); nullptr: the shared
 // workspace that grows on demand.
+// One tensor whose encoder slots would not fit the workspace limit: the histogram pass runs over the
+// whole tensor once, then encoder and compaction take the tensor in tiles of whole encoder groups.  A
+// tile is an item of its own (pointers at the tile's first chunk, table_n and words_before tell the
+// kernels about the rest), and the host waits for each tile's length before the next tile reuses the
+// slots; the word section grows, keeping what it holds, when a tile does not fit.  *stale: a kept
+// table turned out not to cover the tensor (reuse only); nothing of the pass is kept then.
+int compress_tiled(neuzip_blob *b, const void *d_src, const void *d_grad, int k, uint32_t block, int elem, bool reuse,
+                   float lr, bool keep_new, hipStream_t stream, bool *stale)
+{
+    *stale = false;
+    Workspace &ws = g_ws;
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    const uint32_t groups_total = (b->n_chunks + kChunksPerGroup - 1) / kChunksPerGroup;
+    const uint32_t tile_groups = static_cast<uint32_t>(slot_limit_groups() < groups_total ? slot_limit_groups() : groups_total);
+    int rc = ensure_workspace(b->device, tile_groups, stream);
+    if (rc != NEUZIP_OK)
+        return rc;
+    const int variant = d_grad ? kUpdateVariant : (elem == NEUZIP_F32 ? 23 : (elem == NEUZIP_F16 ? 39 : k));
+    const uint32_t src_bytes = elem == NEUZIP_F32 ? 4u : 2u;
+    bool bins_dirty = false;
+    auto fail = [&](int code) {
+        if (bins_dirty)
+            reset_workspace(ws, stream);
+        b->has_table = false;
+        return code;
+    };
+    CompressBatch batch;
+    std::memset(&batch, 0, sizeof(batch));
+    batch.count = 1;
+    batch.lr = lr;
+    batch.keep_new = keep_new ? 1u : 0u;
+    CompressItem &it = batch.it[0];
+    it.tb = table_of(b);
+    it.table_n = b->n;
+    it.block = block;
+    it.guard = b->guard;
+    if (!reuse) {
+        // statistics of the whole tensor (and its fields, coefficients and lower halves)
+        it.src = d_src;
+        it.n = b->n;
+        it.sm = sm_of(b);
+        it.coef = coef_of(b);
+        it.low = low_of(b);
+        it.n_chunks = b->n_chunks;
+        const uint64_t bytes = b->n * src_bytes;
+        const uint32_t threads = bytes <= (128ull << 20) ? kHistThreadsMax : 256u;
+        const uint32_t cap = threads == 256u ? 1280u : 512u;
+        uint64_t hg = ((b->n + 7) / 8 + threads * 8 - 1) / (threads * 8);
+        hg = hg < 1 ? 1 : (hg > cap ? cap : hg);
+        it.hist_end = static_cast<uint32_t>(hg);
+        launch_histogram(ws, batch, variant, block != 0, it.hist_end, threads, stream);
+        if (!hip_ok(hipGetLastError()))
+            return fail(NEUZIP_EHIP);
+        bins_dirty = true;
+    }
+    uint64_t words_before = 0;
+    for (uint32_t g0 = 0; g0 < groups_total; g0 += tile_groups) {
+        const uint32_t g1 = g0 + tile_groups < groups_total ? g0 + tile_groups : groups_total;
+        const uint32_t c0 = g0 * kChunksPerGroup;
+        const uint32_t c1 = g1 * kChunksPerGroup < b->n_chunks ? g1 * kChunksPerGroup : b->n_chunks;
+        const uint64_t e0 = static_cast<uint64_t>(c0) * kChunk;
+        const uint64_t e1 = static_cast<uint64_t>(c1) * kChunk < b->n ? static_cast<uint64_t>(c1) * kChunk : b->n;
+        const bool last = g1 == groups_total;
+        it.src = static_cast<const uint8_t *>(d_src) + e0 * src_bytes;
+        it.grad = d_grad ? static_cast<const uint16_t *>(d_grad) + e0 : nullptr;
+        it.n = e1 - e0;
+        it.offsets = offsets_of(b) + c0;
+        it.states = states_of(b) + static_cast<uint64_t>(c0) * kStates;
+        it.lens = lens_of(b) + static_cast<uint64_t>(c0) * kStates;
+        it.sm = sm_of(b) + e0 * static_cast<uint64_t>(k + 1) / 8;
+        it.coef = block ? coef_of(b) + e0 / block : coef_of(b);
+        it.low = low_of(b) ? low_of(b) + e0 : nullptr;
+        it.n_chunks = c1 - c0;
+        it.group_base = 0;
+        it.super_base = 0;
+        it.enc_end = g1 - g0;
+        it.compact_end = (it.n_chunks + kCompactThreads / 64 - 1) / (kCompactThreads / 64);
+        it.words = reinterpret_cast<uint16_t *>(b->words);
+        it.words_cap = words_room(b);
+        it.words_before = words_before;
+        batch.seq = ++ws.seq;
+        batch.keep_counts = last ? 0u : 1u;
+        const uint32_t copy = batch.seq & 1u;
+        CallState *state = ws.state + copy, *state_next = ws.state + (copy ^ 1u);
+        uint32_t *super_words = ws.super_words + copy * ws.super_cap;
+        uint32_t *super_next = ws.super_words + (copy ^ 1u) * ws.super_cap;
+        // (the workgroup that fills in the decoder's slot table rides with the first tile)
+        if (!launch_encode(ws, batch, it.enc_end + ((!reuse && g0 == 0) ? 1u : 0u), variant, reuse, elem, block, super_words,
+                           state, stream))
+            return fail(NEUZIP_EHIP);
+        bins_dirty = true;  // (sums of this tile; the compaction's report clears them)
+        batch.report = 1;
+        if (!launch_compaction(ws, batch, it.compact_end, super_words, state, state_next, super_next, stream))
+            return fail(NEUZIP_EHIP);
+        if (!wait_for_record(batch.seq, stream))
+            return fail(NEUZIP_EHIP);
+        bins_dirty = !reuse && !last;  // the histogram bins stay until the last tile has been encoded
+        const HostRecord::Item &r = ws.pinned->item[0];
+        if (reuse && r.stale) {
+            // The table does not cover this tile: the tensor will be compressed afresh.  A weight step
+            // that writes the new weights back still has to reach the remaining tiles.
+            *stale = true;
+            b->has_table = false;
+            if (!(d_grad && keep_new)) {
+                (void)hipEventRecord(ws.idle, stream);
+                return NEUZIP_OK;
+            }
+        }
+        if (r.total_words[1] != 0)
+            return fail(NEUZIP_EUNSUPPORTED);
+        const uint64_t upto = words_before + r.total_words[0];
+        if (upto >= (1ull << 32))
+            return fail(NEUZIP_EUNSUPPORTED);  // more than 2^32 words
+        if (!*stale && upto > it.words_cap) {
+            // no room (or no word section yet): size it for the whole tensor at the rate seen so far
+            const uint64_t guess = last ? upto : upto / c1 * b->n_chunks + upto % c1 * b->n_chunks / c1;
+            rc = grow_words_keeping(b, last ? upto : guess + guess / 32, words_before, stream);
+            if (rc != NEUZIP_OK)
+                return fail(rc);
+            it.words = reinterpret_cast<uint16_t *>(b->words);
+            it.words_cap = words_room(b);
+            batch.report = 0;
+            if (!launch_compaction(ws, batch, it.compact_end, super_words, state, state_next, super_next, stream))
+                return fail(NEUZIP_EHIP);
+        }
+        words_before = upto;
+        if (!reuse && g0 == 0) {
+            std::memcpy(b->h_counts, r.counts, 1024);
+            std::memcpy(b->h_freq, r.freq, 512);
+            b->have_counts = true;
+        }
+    }
+    if (!*stale) {
+        b->total_words = words_before;
+        b->has_table = true;
+    }
+    if (!hip_ok(hipEventRecord(ws.idle, stream)))
+        return NEUZIP_EHIP;
+    return NEUZIP_OK;
+}
+
 int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t count, int k, uint32_t block, int elem,
                   uint32_t guard, bool reuse, uint32_t *rebuilt, hipStream_t stream, neuzip_blob **blobs,
                   const void *const *d_grads = nullptr, float lr = 0.0f, bool keep_new = true,
                   Workspace *fixed_ws = nullptr)
 {
     Workspace &ws = fixed_ws ? *fixed_ws : g_ws;
+    auto groups_of = [](uint64_t n) { return (static_cast<uint64_t>(chunks_of(n)) + kChunksPerGroup - 1) / kChunksPerGroup; };
+    if (!fixed_ws && count > 1) {
+        // a batch whose encoder slots would exceed the workspace limit goes through in parts: runs of
+        // neighbouring tensors that fit together (a tensor that alone does not fit is a part of its own)
+        uint64_t groups = 0;
+        for (uint32_t i = 0; i < count; ++i)
+            groups += groups_of(n_elems[i]);
+        if (groups > slot_limit_groups()) {
+            bool was_null[kBatchMax];
+            for (uint32_t i = 0; i < count; ++i)
+                was_null[i] = blobs[i] == nullptr;
+            for (uint32_t first = 0; first < count;) {
+                uint32_t m = 1;
+                uint64_t part = groups_of(n_elems[first]);
+                while (first + m < count && part + groups_of(n_elems[first + m]) <= slot_limit_groups()) {
+                    part += groups_of(n_elems[first + m]);
+                    ++m;
+                }
+                const int rc = compress_some(d_srcs + first, n_elems + first, m, k, block, elem, guard, reuse,
+                                             rebuilt ? rebuilt + first : nullptr, stream, blobs + first,
+                                             d_grads ? d_grads + first : nullptr, lr, keep_new, nullptr);
+                if (rc != NEUZIP_OK) {
+                    for (uint32_t j = 0; j < first; ++j) {
+                        if (was_null[j]) {
+                            neuzip_free(blobs[j]);
+                            blobs[j] = nullptr;
+                        }
+                    }
+                    return rc;
+                }
+                first += m;
+            }
+            return NEUZIP_OK;
+        }
+    }
     neuzip_blob *work[kBatchMax];
     bool fresh[kBatchMax];
     for (uint32_t i = 0; i < count; ++i) {
@@ -603,7 +880,25 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         batch_bytes += work[i]->n * (elem == NEUZIP_F32 ? 4u : 2u);
     const uint32_t hist_threads = batch_bytes <= (128ull << 20) ? kHistThreadsMax : 256u;
     const uint32_t hist_cap = hist_threads == 256u ? 1280u : 512u;
-    for (uint32_t i = 0; i < count; ++i) {
+    // a single tensor beyond the workspace limit: in tiles
+    const bool tiled = !fixed_ws && count == 1 && groups_of(work[0]->n) > slot_limit_groups();
+    if (tiled) {
+        bool stale = false;
+        touched = true;
+        const int rc = compress_tiled(work[0], d_srcs[0], d_grads ? d_grads[0] : nullptr, k, block, elem, reuse, lr, keep_new,
+                                      stream, &stale);
+        if (rc != NEUZIP_OK)
+            return fail(rc);
+        if (stale) {
+            stale_src[0] = d_srcs[0];
+            stale_grad[0] = d_grads ? d_grads[0] : nullptr;
+            stale_n[0] = n_elems[0];
+            stale_blob[0] = work[0];
+            stale_owner[0] = 0;
+            stale_count = 1;
+        }
+    }
+    for (uint32_t i = 0; i < count && !tiled; ++i) {
         neuzip_blob *b = work[i];
         if (b->n == 0) {
             const int rc = reuse ? NEUZIP_OK : compress_empty(b, stream);
@@ -616,6 +911,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         owner[batch.count++] = i;
         it.src = d_srcs[i];
         it.n = b->n;
+        it.table_n = b->n;
         it.tb = table_of(b);
         it.offsets = offsets_of(b);
         it.states = states_of(b);
@@ -672,48 +968,15 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         // workspace's sums to zero.
         const int variant = d_grads ? kUpdateVariant : (elem == NEUZIP_F32 ? 23 : (elem == NEUZIP_F16 ? 39 : k));
         if (!reuse) {
-            const dim3 grid(hist_groups), threads(hist_threads);
-            switch (variant) {
-            case 39: hipLaunchKernelGGL((hist_split_kernel<7, false, true>), grid, threads, 0, stream, batch, ws.counts); break;
-            case 23: hipLaunchKernelGGL((hist_split_kernel<7, true>), grid, threads, 0, stream, batch, ws.counts); break;
-            case 7: launch_hist<7>(ws, batch, block != 0, hist_groups, hist_threads, stream); break;
-            case 3: launch_hist<3>(ws, batch, block != 0, hist_groups, hist_threads, stream); break;
-            case 1: launch_hist<1>(ws, batch, block != 0, hist_groups, hist_threads, stream); break;
-            default: launch_hist<0>(ws, batch, block != 0, hist_groups, hist_threads, stream); break;
-            }
+            launch_histogram(ws, batch, variant, block != 0, hist_groups, hist_threads, stream);
             if (!hip_ok(hipGetLastError()))
                 return fail(NEUZIP_EHIP);
             ws_dirty = true;
         }
-        {
-            const dim3 grid(enc_groups + (reuse ? 0u : batch.count)), threads(kEncThreads);
-#define NZ_ENCODE(...)                                                                                          \
-    hipLaunchKernelGGL((encode_kernel<__VA_ARGS__>), grid, threads, 0, stream, batch, ws.counts, ws.chunk_words, \
-                       ws.group_words, super_words, ws.slots, ws.pinned, state)
-            if (reuse) {
-                switch (variant) {
-                case kUpdateVariant: NZ_ENCODE(false, 7, false, false, true); break;
-                case 39: NZ_ENCODE(false, 7, false, true); break;
-                case 23: NZ_ENCODE(false, 7, true); break;
-                case 7: NZ_ENCODE(false, 7); break;
-                case 3: NZ_ENCODE(false, 3); break;
-                case 1: NZ_ENCODE(false, 1); break;
-                default: NZ_ENCODE(false, 0); break;
-                }
-            } else if (elem == NEUZIP_F16) {
-                NZ_ENCODE(false, -1, false, true);
-            } else if (elem == NEUZIP_F32) {
-                NZ_ENCODE(false, -1, true);
-            } else if (block) {
-                NZ_ENCODE(true, -1);
-            } else {
-                NZ_ENCODE(false, -1);
-            }
-#undef NZ_ENCODE
-            if (!hip_ok(hipGetLastError()))
-                return fail(NEUZIP_EHIP);
-            ws_dirty = true;
-        }
+        if (!launch_encode(ws, batch, enc_groups + (reuse ? 0u : batch.count), variant, reuse, elem, block, super_words, state,
+                           stream))
+            return fail(NEUZIP_EHIP);
+        ws_dirty = true;
 
         // The stream lengths are data dependent.  The compaction is launched right away all the same:
         // a blob that already has a word section (one that is compressed into again, as in a training
@@ -727,10 +990,7 @@ int compress_some(const void *const *d_srcs, const uint64_t *n_elems, uint32_t c
         }
         auto launch_compact = [&](bool report) {
             batch.report = report ? 1u : 0u;
-            hipLaunchKernelGGL(compact_kernel, dim3(compact_groups), dim3(kCompactThreads), 0, stream, batch, ws.slots,
-                               ws.chunk_words, ws.group_words, super_words, state, ws.counts, state_next, super_next,
-                               ws.super_cap, ws.all_done, ws.pinned);
-            return hip_ok(hipGetLastError());
+            return launch_compaction(ws, batch, compact_groups, super_words, state, state_next, super_next, stream);
         };
         if (!launch_compact(true))
             return fail(NEUZIP_EHIP);
@@ -831,6 +1091,16 @@ int neuzip_compress(const void *d_src, uint64_t n_elems, int dtype, int mantissa
                     neuzip_blob **blob)
 {
     return neuzip_compress_batch(&d_src, &n_elems, 1, dtype, mantissa_bits, 0, hip_stream, blob);
+}
+
+int neuzip_set_workspace_limit(uint64_t slot_bytes)
+{
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    g_slot_limit = slot_bytes == 0 ? kDefaultSlotLimit : slot_bytes;
+    // a workspace that was grown beyond the new limit is given back
+    if (g_ws.device >= 0 && g_ws.group_cap > slot_limit_groups())
+        return release_workspace_locked();
+    return NEUZIP_OK;
 }
 
 int neuzip_compress_blockwise(const void *d_src, uint64_t n_elems, int dtype, int mantissa_bits,

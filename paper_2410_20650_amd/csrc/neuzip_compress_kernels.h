@@ -800,7 +800,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const CompressBatch
             const uint4 c4 = reinterpret_cast<const uint4 *>(counts_ws + 256 * slot_id.item)[lane];
             const uint32_t cnt[4] = {c4.x, c4.y, c4.z, c4.w};
             uint32_t f[4], cum[4];
-            const uint32_t lone = build_table_wave(cnt, n, it.guard, f, cum);
+            const uint32_t lone = build_table_wave(cnt, it.table_n, it.guard, f, cum);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const EncSym e = encoder_constants(f[i], cum[i]);
@@ -1011,12 +1011,14 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const Compress
     const ItemSlot slot_id = item_of_workgroup<&CompressItem::compact_end>(b);
     const CompressItem &it = b.it[slot_id.item];
     const uint32_t n_chunks = it.n_chunks;
-    const unsigned long long all_words = state->total[slot_id.item];
+    const unsigned long long own_words = state->total[slot_id.item];
+    const unsigned long long all_words = it.words_before + own_words;  // up to the end of this tile
     const uint32_t was_stale = state->stale[slot_id.item];
     if (b.report && slot_id.wg == 0 && threadIdx.x < 64) {
         const uint32_t lane = threadIdx.x;
         // every workgroup of the encoder launch has read the counts: the bins go back to zero
-        reinterpret_cast<uint4 *>(counts_ws + 256 * slot_id.item)[lane] = make_uint4(0, 0, 0, 0);
+        if (!b.keep_counts)
+            reinterpret_cast<uint4 *>(counts_ws + 256 * slot_id.item)[lane] = make_uint4(0, 0, 0, 0);
         // the other copy of the call state, for the call after this one (nobody is using it now)
         if (slot_id.item == 0) {
             for (uint32_t i = lane; i < sizeof(CallState) / 4; i += 64)
@@ -1033,9 +1035,10 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const Compress
             // they are acknowledged this tensor counts as reported, and the tensor reported last
             // writes the stamp, which therefore cannot overtake any of them.
             HostRecord::Item *mine = &record->item[slot_id.item];
-            __hip_atomic_store(&mine->total_words[0], static_cast<uint32_t>(all_words), __ATOMIC_RELAXED,
+            // (the words of this item alone: the host adds up the tiles of a tensor)
+            __hip_atomic_store(&mine->total_words[0], static_cast<uint32_t>(own_words), __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_SYSTEM);
-            __hip_atomic_store(&mine->total_words[1], static_cast<uint32_t>(all_words >> 32), __ATOMIC_RELAXED,
+            __hip_atomic_store(&mine->total_words[1], static_cast<uint32_t>(own_words >> 32), __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_SYSTEM);  // non-zero: too long for 32-bit offsets
             __hip_atomic_store(&mine->stale, was_stale, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             wait_for_memory_acks();
@@ -1097,7 +1100,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const Compress
         before += lane < in_group ? chunk_words[g * kChunksPerGroup + lane] : 0u;
         for (uint32_t i = lane; i < blocks; i += 64)
             before += super_words[i];
-        at0 = wave_sum_u32(before);
+        at0 = it.words_before + wave_sum_u32(before);
         if (lane == 0)
             offsets[c] = static_cast<uint32_t>(at0);
         shift = static_cast<uint32_t>(at0 & 7u);

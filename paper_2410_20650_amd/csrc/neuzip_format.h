@@ -82,6 +82,13 @@ constexpr uint32_t kBatchMax = 8;
 struct CompressItem {
     const void *src;       // bf16 words, or binary32 words when the batch is of that type
     uint64_t n;
+    // A tensor whose encoder slots would exceed the workspace limit goes through the encoder and the
+    // compaction in tiles of whole chunks.  A tile is an item of its own whose pointers (source, states,
+    // lens, offsets, fields, ...) start at the tile's first chunk and whose n is the tile's elements;
+    // table_n is the element count of the whole tensor (the table is the tensor's), words_before the
+    // words of the tiles before it (its chunk offsets and its place in the word section start there).
+    uint64_t table_n;
+    uint64_t words_before;
     TableBlock *tb;
     uint32_t *offsets;
     uint32_t *states;
@@ -109,6 +116,7 @@ struct CompressBatch {
     float lr;      // learning rate of the fused weight step
     uint32_t keep_new;  // fused weight step: write the new weight back over the source
     uint32_t report;    // compaction launch: also report the stream lengths to the host and tidy the workspace
+    uint32_t keep_counts;  // ... but leave the histogram bins: further tiles of the tensor need them
 };
 
 // What the encoder workgroups of a call add up for the compaction and for the host, in the workspace.
