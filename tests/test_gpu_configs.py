@@ -106,6 +106,8 @@ def test_config3_forward_schedule_llama3_8b_shapes(nz):
             oracle_parity(nz, w, blob, 7)
         del w
     assert total == 7_504_658_432
+    # the embedding (0.82 GB of encoder slots if taken whole) went through in tiles: the workspace is capped
+    assert nz.neuzip_workspace_bytes() <= (384 << 20) + (8 << 20)
     assert 8 * comp / total < 10.76                        # 2 % over entropy + 8 bits
     # the whole forward pass in one call; the scratch ends up holding the last layer
     at = nz.neuzip_decompress_sequence(blobs, scratch)
