@@ -130,6 +130,8 @@ int neuzip_compress_blockwise(const void *d_src, uint64_t n_elems, int dtype, in
  *   mantissa_bits, block_size   shared by all tensors; meaning as above.
  *   blobs            host array of count handles, in/out with the rules of neuzip_compress
  *                    (NULL entries are created; other entries must match and be distinct).
+ * A group whose encoder slots would exceed the workspace limit (neuzip_set_workspace_limit) is
+ * taken in parts, with one wait per part; the results are the same.
  * On error, blobs created for the failing group are released and its entries of blobs are
  * not changed; groups completed before keep their results.
  */
