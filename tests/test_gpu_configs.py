@@ -121,6 +121,34 @@ def test_config3_forward_schedule_llama3_8b_shapes(nz):
         assert int(piece.view(torch.int16).to(torch.int64).sum().item()) == sums[i], names[i][0]
 
 
+def test_a_tensor_of_the_largest_size_the_boundary_takes(nz):
+    # n just below 2^32 elements (8.6 GB of bf16), ragged last chunk: the tensor goes through the encoder in
+    # tiles, its chunk offsets use nearly the whole 32-bit range of words, and every index in the kernels has
+    # to be 64 bits wide.  Round trip on the device, then the container against the oracle's, byte for byte.
+    n = (1 << 32) - 4096 + 5
+    w = inputs.gaussian_bf16(n, inputs.seed_for(7), device=DEV)
+    blob = nz.neuzip_compress(w, 7)
+    assert blob.elems == n
+    assert nz.neuzip_workspace_bytes() <= (384 << 20) + (8 << 20)
+    out = torch.empty_like(w)
+    nz.neuzip_decompress(blob, out)
+    nz.neuzip_check(blob)
+    for lo in range(0, n, 1 << 30):                        # (compared in pieces: a mask of n bytes is enough)
+        assert same_bits(out[lo: lo + (1 << 30)], w[lo: lo + (1 << 30)]), lo
+    del out
+    assert 8 * blob.compressed_bytes / n < 10.76
+    words = inputs.bits(w)
+    del w
+    want = O.compress(words, 7, threads=THREADS)
+    del words
+    got = nz.neuzip_export(blob)
+    assert got.size == want.size
+    assert np.array_equal(got, want), "container differs from the oracle's"
+    nz.neuzip_free(blob)
+    nz.neuzip_release_workspace()
+    torch.cuda.empty_cache()
+
+
 def test_device_memory_held_matches_the_accounting(nz):
     # Sec. 2.2 / Alg. 1: the model is held compressed and only one layer's weights exist uncompressed
     # at a time.  What the driver reports as taken from the device while two layers of the config-3
