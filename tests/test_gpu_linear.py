@@ -166,6 +166,33 @@ def test_linear_full_projection_shape(nz):
     assert torch.allclose(y, ref, rtol=0, atol=2e-3 * ref.abs().max().item())
 
 
+def test_linear_on_the_largest_weight_of_the_model(nz):
+    # the output projection of Llama-3 8B (128256 x 4096, 525 M elements) applied to a decoding batch.
+    # Every output against the dense float32 product of the decompressed weight on the GPU; a sample of
+    # rows against the definition (Sec. 2.2: W_hat x with W_hat = decompress(c), which for a lossless
+    # blob is the weight itself) in float64, within the float32 summation bound.
+    out_f, in_f, tokens = 128256, 4096, 8
+    w = inputs.gaussian_bf16((out_f, in_f), inputs.seed_for(3, 0), device=DEV)
+    x = inputs.gaussian_bf16((tokens, in_f), 9900, std=1.0, device=DEV)
+    blob = nz.neuzip_compress(w, 7)
+    y = nz.neuzip_linear(blob, out_f, in_f, x)
+    nz.neuzip_check(blob)
+    dense = torch.empty_like(w)
+    nz.neuzip_decompress(blob, dense.view(-1))
+    assert torch.equal(dense.view(torch.int16), w.view(torch.int16))
+    ref = x.float() @ dense.float().T
+    assert torch.allclose(y, ref, rtol=0, atol=2e-3 * ref.abs().max().item())
+    rows = torch.linspace(0, out_f - 1, 257, device=DEV).long()
+    w64 = w[rows].double().cpu().numpy()
+    x64 = x.double().cpu().numpy()
+    want = x64 @ w64.T
+    mag = np.abs(x64) @ np.abs(w64).T
+    got = y[:, rows].cpu().numpy().astype(np.float64)
+    bound = 2.0 * (in_f + 64) * 2.0 ** -24 * mag + 1e-30
+    assert np.max(np.abs(got - want) / bound) <= 1.0
+    nz.neuzip_free(blob)
+
+
 def test_linear_argument_errors(nz):
     w = inputs.gaussian_bf16(32 * 256, 9600, device=DEV)
     blob = nz.neuzip_compress(w, 7)
