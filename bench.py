@@ -502,6 +502,8 @@ def training_loop(torch, nz, inputs, stream, model, steps, kept_table):
     else:
         out["compress_GBps_input_one_call_per_tensor"] = round(2.0 * total / enc_single_s / 1e9, 1)
         out["compress_calls"] = "one neuzip_compress_batch call per layer (7 tensors), fresh statistics every step"
+    # what the compress calls hold besides the blobs (encoder run slots, capped by the workspace limit)
+    out["compress_workspace_MiB"] = nz.neuzip_workspace_bytes() >> 20
     return out
 
 
