@@ -323,8 +323,10 @@ def main():
     probe_in = torch.empty(comp_bytes // 16 * 16, dtype=torch.uint8, device=dev)
     us = event_us(torch, stream, lambda: nz.neuzip_stream_probe(probe_in, src), 50, warm=5)
     result["stream_probe"] = {"config2_GBps": round((probe_in.numel() + out_bytes) / us / 1e3, 1), "config2_us": round(us, 2),
-                              "what": "a kernel that only reads the container's bytes and writes the tensor's, "
-                                      "interleaved, with the decoder's access widths: the ceiling for this byte mix"}
+                              "what": "a kernel that only reads the container's bytes and writes the tensor's, in the "
+                                      "decoder's launch shape and access pattern (512-lane workgroups owning 32 chunks, "
+                                      "the decoder's LDS, field loads and 16-byte stores four turns at a time): the "
+                                      "ceiling for a decoder of this shape"}
     del probe_in
 
     # compress rate (histogram + table + encode + offsets + compaction, incl. the one size read-back)

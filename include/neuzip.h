@@ -351,11 +351,15 @@ int neuzip_frequencies(const neuzip_blob *blob, uint16_t h_freq[256]);
 /*
  * neuzip_stream_probe -- measurement aid for the throughput experiment of Sec. 3 (the throughput
  * figure compares against plain data movement): one kernel that only moves bytes the way the fused
- * decoder does, reading in_bytes from d_in and writing out_bytes to d_out interleaved in that
- * proportion (128-bit accesses; non-temporal stores from 128 MB of output up).  Its rate is the
- * ceiling for a decoder of that byte mix on the machine at hand.
- *   d_in, d_out   device buffers, 16-byte aligned; in_bytes and out_bytes multiples of 16, out_bytes
- *                 at least 64; d_out is overwritten with a pattern.  EINVAL otherwise.
+ * decoder does, in the decoder's launch shape -- workgroups of 512 lanes that own 32 chunks of 8 KB
+ * of output and hold the decoder's LDS, a 128-bit copy of their share of the input into LDS at the
+ * start, then per lane and turn a field load of 8, 4, 2 or 1 bytes and a 16-byte store 256 bytes
+ * apart, four turns at a time, non-temporal stores from 128 MB of output up -- reading (nearly all
+ * of) in_bytes from d_in and writing out_bytes to d_out.  Its rate is the ceiling for a decoder with
+ * that access pattern and byte mix on the machine at hand.
+ *   d_in, d_out   device buffers, 16-byte aligned; in_bytes and out_bytes multiples of 16; out_bytes
+ *                 at least 8208; in_bytes between 1/16 of out_bytes (plus one workgroup's worth) and
+ *                 about 1.2 times out_bytes; d_out is overwritten with a pattern.  EINVAL otherwise.
  * Never allocates, never synchronises.
  */
 int neuzip_stream_probe(const void *d_in, uint64_t in_bytes, void *d_out, uint64_t out_bytes, void *hip_stream);

@@ -1850,19 +1850,48 @@ int neuzip_frequencies(const neuzip_blob *blob, uint16_t h_freq[256])
 int neuzip_stream_probe(const void *d_in, uint64_t in_bytes, void *d_out, uint64_t out_bytes, void *hip_stream)
 {
     if ((reinterpret_cast<uintptr_t>(d_in) & 15u) || (reinterpret_cast<uintptr_t>(d_out) & 15u) || (in_bytes & 15u) ||
-        (out_bytes & 15u) || out_bytes < 64 || !d_out || (in_bytes && !d_in))
+        (out_bytes & 15u) || !d_out || !d_in)
         return NEUZIP_EINVAL;
+    // whole chunks of 8 KB of output; the last 16 bytes of the output are the kernel's sink word
+    const uint64_t chunks64 = (out_bytes - 16) / (2 * kChunk);
+    if (out_bytes < 2 * kChunk + 16 || chunks64 >= (1ull << 31))
+        return NEUZIP_EINVAL;
+    const uint32_t n_chunks = static_cast<uint32_t>(chunks64);
+    const uint32_t wgs = (n_chunks + kDecChunksPerWg - 1) / kDecChunksPerWg;
+    // the input is split the way a container's is: per lane and turn the widest field (8, 4, 2 or 1
+    // bytes) the input affords, the rest as "words", an equal share per workgroup
+    const uint64_t per_chunk = in_bytes / n_chunks;
+    const uint32_t fw = per_chunk >= 8 * kTurns * kStates ? 8u : (per_chunk >= 4 * kTurns * kStates ? 4u
+                        : (per_chunk >= 2 * kTurns * kStates ? 2u : (per_chunk >= kTurns * kStates ? 1u : 0u)));
+    if (fw == 0)
+        return NEUZIP_EINVAL;  // less input than one byte per eight outputs: not a decoder's mix
+    const uint64_t field_bytes = static_cast<uint64_t>(wgs) * kDecChunksPerWg * kTurns * kStates * fw;
+    if (field_bytes > in_bytes)
+        return NEUZIP_EINVAL;
+    const uint64_t vecs = (in_bytes - field_bytes) / 16 / wgs;
+    const uint32_t word_vecs = static_cast<uint32_t>(vecs < kStageBytes / 16 ? vecs : kStageBytes / 16);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const uint64_t out_vecs = out_bytes / 16 - 1;  // the last 16 bytes of the output are the kernel's sink word
+    const uint8_t *fields = static_cast<const uint8_t *>(d_in);
+    const uint4 *words = reinterpret_cast<const uint4 *>(fields + field_bytes);
+    uint4 *out = static_cast<uint4 *>(d_out);
     uint32_t *sink = reinterpret_cast<uint32_t *>(static_cast<uint8_t *>(d_out) + out_bytes - 16);
-    const uint64_t want = (out_vecs + 256 * 4 - 1) / (256 * 4);
-    const uint32_t wgs = static_cast<uint32_t>(want < 1 ? 1 : (want > 8192 ? 8192 : want));
-    if (out_bytes >= (128ull << 20))
-        hipLaunchKernelGGL(stream_probe_kernel<true>, dim3(wgs), dim3(256), 0, stream, static_cast<const uint4 *>(d_in),
-                           in_bytes / 16, static_cast<uint4 *>(d_out), out_vecs, sink);
-    else
-        hipLaunchKernelGGL(stream_probe_kernel<false>, dim3(wgs), dim3(256), 0, stream, static_cast<const uint4 *>(d_in),
-                           in_bytes / 16, static_cast<uint4 *>(d_out), out_vecs, sink);
+    const bool stream_out = out_bytes >= (128ull << 20);
+#define NZ_PROBE(FW)                                                                                                 \
+    do {                                                                                                             \
+        if (stream_out)                                                                                              \
+            hipLaunchKernelGGL((stream_probe_kernel<FW, true>), dim3(wgs), dim3(kDecThreads), 0, stream, fields, words, \
+                               word_vecs, out, n_chunks, sink);                                                      \
+        else                                                                                                         \
+            hipLaunchKernelGGL((stream_probe_kernel<FW, false>), dim3(wgs), dim3(kDecThreads), 0, stream, fields, words, \
+                               word_vecs, out, n_chunks, sink);                                                      \
+    } while (0)
+    switch (fw) {
+    case 8: NZ_PROBE(8); break;
+    case 4: NZ_PROBE(4); break;
+    case 2: NZ_PROBE(2); break;
+    default: NZ_PROBE(1); break;
+    }
+#undef NZ_PROBE
     return hip_ok(hipGetLastError()) ? NEUZIP_OK : NEUZIP_EHIP;
 }
 

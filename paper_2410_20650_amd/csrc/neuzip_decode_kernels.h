@@ -1,6 +1,8 @@
 // Fused rANS decode + merge kernels of the NeuZip codec for gfx950 (single tensor and batch).
 #pragma once
 
+#include <type_traits>
+
 #include "neuzip_format.h"
 #include "neuzip_compress_kernels.h"
 
@@ -617,46 +619,71 @@ __global__ __launch_bounds__(kDecThreads) void decode_batch_kernel(const BatchAr
 }
 
 // ------------------------------------------------------------------------------------------
-// Measurement aid: a kernel that does nothing but the decoder's memory traffic -- it reads in_vecs
-// 16-byte pieces and writes out_vecs 16-byte pieces, interleaved in that proportion, with the same
-// kinds of instructions (128-bit loads; 128-bit stores, non-temporal for outputs beyond the
-// last-level cache).  What it reaches is the ceiling a decoder of that byte mix can reach on this
-// machine; the decoder's own rate is reported against it.
+// Measurement aid: the decoder's memory traffic without its arithmetic, in the decoder's own launch
+// shape.  A workgroup of 512 lanes owns 32 chunks of 8 KB of output and holds the decoder's LDS (so the
+// same 16 waves per CU are resident); it first copies its share of the "word" input into LDS with
+// 128-bit loads behind one barrier; then lane (chunk, state) reads FW bytes of "field" input and writes
+// 16 bytes per turn, 256 bytes apart, turns taken four at a time with the next four field loads in
+// flight, non-temporal stores for outputs beyond the last-level cache -- the decoder's instructions
+// with nothing between them.  What it reaches is the ceiling for a decoder with this access pattern on
+// this machine; the decoder's own rate is reported against it.
 // ------------------------------------------------------------------------------------------
-template <bool STREAM>
-__global__ __launch_bounds__(256) void stream_probe_kernel(const uint4 *__restrict__ in, uint64_t in_vecs,
-                                                           uint4 *__restrict__ out, uint64_t out_vecs,
-                                                           uint32_t *__restrict__ sink)
+template <int FW, bool STREAM>
+__global__ __launch_bounds__(kDecThreads) void stream_probe_kernel(const uint8_t *__restrict__ fields,
+                                                                   const uint4 *__restrict__ words, uint32_t word_vecs_per_wg,
+                                                                   uint4 *__restrict__ out, uint32_t n_chunks,
+                                                                   uint32_t *__restrict__ sink)
 {
-    const uint64_t threads = static_cast<uint64_t>(gridDim.x) * blockDim.x;
-    uint32_t acc = 0;
-    constexpr uint32_t kDepth = 4;  // pieces in flight per lane, each way
-    for (uint64_t v0 = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; v0 < out_vecs; v0 += threads * kDepth) {
-        uint4 got[kDepth];
+    __shared__ __align__(16) uint32_t lut[kM];
+    __shared__ __align__(16) uint8_t stage[kStageBytes];
+    const uint32_t tid = threadIdx.x, c = blockIdx.x * kDecChunksPerWg + tid / kStates, j = tid % kStates;
+    const uint4 *from = words + static_cast<uint64_t>(blockIdx.x) * word_vecs_per_wg;
+    for (uint32_t i = tid; i < word_vecs_per_wg; i += kDecThreads)
+        reinterpret_cast<uint4 *>(stage)[i % (kStageBytes / 16)] = from[i];
+    lut[tid] = tid;
+    __syncthreads();
+    uint32_t acc = lut[(tid * 7u) % kM] ^ reinterpret_cast<const uint32_t *>(stage)[tid];
+    if (c >= n_chunks)
+        return;
+    typedef typename std::conditional<FW == 8, uint2, typename std::conditional<FW == 4, uint32_t,
+            typename std::conditional<FW == 2, uint16_t, uint8_t>::type>::type>::type field_t;
+    const field_t *f = reinterpret_cast<const field_t *>(fields + static_cast<uint64_t>(c) * (kTurns * kStates * FW)) + j;
+    uint4 *o = out + static_cast<uint64_t>(c) * (kChunk / 8) + j;
+    constexpr uint32_t kBurst = kTurnGroupStream;
+    field_t now[kBurst];
 #pragma unroll
-        for (uint32_t r = 0; r < kDepth; ++r) {
-            const uint64_t v = v0 + r * threads;
-            // neighbouring lanes share input pieces where the input is the shorter side: one request
-            got[r] = (v < out_vecs && in_vecs) ? in[v * in_vecs / out_vecs] : make_uint4(0, 0, 0, 0);
-        }
+    for (uint32_t r = 0; r < kBurst; ++r)
+        now[r] = f[r * kStates];
+    for (uint32_t q = 0; q < kTurns; q += kBurst) {
+        field_t next[kBurst];
+        const uint32_t qn = q + kBurst < kTurns ? q + kBurst : q;
 #pragma unroll
-        for (uint32_t r = 0; r < kDepth; ++r) {
-            const uint64_t v = v0 + r * threads;
-            acc ^= got[r].x ^ got[r].y ^ got[r].z ^ got[r].w;
-            if (v < out_vecs) {
-                const uint4 w = make_uint4(static_cast<uint32_t>(v), 1u, 2u, 3u);
-                if constexpr (STREAM) {
-                    __builtin_nontemporal_store(w.x, &out[v].x);
-                    __builtin_nontemporal_store(w.y, &out[v].y);
-                    __builtin_nontemporal_store(w.z, &out[v].z);
-                    __builtin_nontemporal_store(w.w, &out[v].w);
-                } else {
-                    out[v] = w;
-                }
+        for (uint32_t r = 0; r < kBurst; ++r)
+            next[r] = f[(qn + r) * kStates];
+#pragma unroll
+        for (uint32_t r = 0; r < kBurst; ++r) {
+            uint32_t lo, hi;
+            if constexpr (FW == 8) {
+                lo = now[r].x;
+                hi = now[r].y;
+            } else {
+                lo = now[r];
+                hi = q;
             }
+            const uint4 w = make_uint4(lo, hi, acc, q + r);
+            uint4 *dst = &o[(q + r) * kStates];
+            if constexpr (STREAM) {
+                __builtin_nontemporal_store(w.x, &dst->x);
+                __builtin_nontemporal_store(w.y, &dst->y);
+                __builtin_nontemporal_store(w.z, &dst->z);
+                __builtin_nontemporal_store(w.w, &dst->w);
+            } else {
+                *dst = w;
+            }
+            now[r] = next[r];
         }
     }
-    if (acc == 0x9E3779B9u)  // keeps the loads alive; practically never taken
+    if (acc == 0x9E3779B9u)  // keeps the LDS reads alive; practically never taken
         atomicOr(sink, 1u);
 }
 

@@ -429,3 +429,22 @@ def test_host_threads_on_their_own_streams(nz):
         t.join(timeout=100)
     assert not any(t.is_alive() for t in threads)
     assert errors == []
+
+
+def test_stream_probe_moves_the_bytes_and_rejects_what_is_no_decoders_mix(nz):
+    # the measuring aid: writes its pattern over whole 8 KB chunks of the output, reads the input, no more
+    out = torch.zeros(64 * 8192 // 2 + 8, dtype=torch.bfloat16, device=DEV)          # 64 chunks + the sink word
+    guard = torch.full((4096,), 7, dtype=torch.uint8, device=DEV)
+    inp = torch.full((64 * 5504,), 3, dtype=torch.uint8, device=DEV)                  # a lossless container's share
+    nz.neuzip_stream_probe(inp, out)
+    torch.cuda.synchronize()
+    words = out.view(torch.int32)
+    assert int(words[0].item()) == 0x03030303                                       # the field bytes it read
+    turn = words[: 64 * 2048].reshape(-1, 4)[:, 3]                                   # the turn number, in every 16-byte piece
+    assert int(turn.sum().item()) == 64 * 16 * sum(range(32)) and int(turn.max().item()) == 31
+    assert bool((guard == 7).all()) and bool((inp == 3).all())
+    tiny = torch.zeros(16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_stream_probe(tiny, out)                                           # less than a byte per 8 outputs
+    with pytest.raises(nz.NeuzipError):
+        nz.neuzip_stream_probe(inp, tiny)                                           # no whole chunk of output
